@@ -1,0 +1,322 @@
+"""ctypes marshalling for the C++ oracle (argument conversion only; no arithmetic of the method here)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "qoda_oracle.cpp")
+_LIB = os.path.join(_HERE, "libqoda_oracle.so")
+_CXXFLAGS = ["-O2", "-std=c++17", "-ffp-contract=off", "-fno-fast-math", "-Wall", "-Wextra", "-shared", "-fPIC"]
+
+HIST_BINS = 2048
+GRID_POINTS = 257
+GRID_BASE = 760
+BLOCK = 256
+CHUNK = 16384
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with g++ (always when ``force``; otherwise only if stale or missing)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        subprocess.check_call(["g++", *_CXXFLAGS, _SRC, "-o", _LIB])
+    return _LIB
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        L = C.CDLL(_LIB)
+        u8p, u32p, u64p, i32p, i64p = (C.POINTER(t) for t in (C.c_uint8, C.c_uint32, C.c_uint64, C.c_int32, C.c_int64))
+        fp, dp = C.POINTER(C.c_float), C.POINTER(C.c_double)
+        pp = C.POINTER(C.c_void_p)
+        L.oracle_philox4x32_10.argtypes = [u32p, u32p, u32p]
+        L.oracle_philox4x32_10.restype = None
+        L.oracle_draw16.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint64]
+        L.oracle_draw16.restype = C.c_uint32
+        L.oracle_sqrt_floor.argtypes = [C.c_double]
+        L.oracle_sqrt_floor.restype = C.c_float
+        L.oracle_rcp_floor.argtypes = [C.c_float]
+        L.oracle_rcp_floor.restype = C.c_float
+        L.oracle_level_index.argtypes = [fp, C.c_int32, C.c_float]
+        L.oracle_level_index.restype = C.c_int32
+        L.oracle_index_bits.argtypes = [C.c_int32]
+        L.oracle_index_bits.restype = C.c_int32
+        L.oracle_sumsq.argtypes = [fp, C.c_int64]
+        L.oracle_sumsq.restype = C.c_double
+        L.oracle_quantize_range.argtypes = [fp, C.c_int64, C.c_int64, C.c_float, fp, C.c_int32, C.c_uint64, C.c_uint32,
+                                            C.c_uint32, C.c_uint32, u8p, u8p]
+        L.oracle_quantize_range.restype = None
+        L.oracle_quantize_with_draws.argtypes = [fp, C.c_int64, C.c_float, fp, C.c_int32, u32p, u8p, u8p]
+        L.oracle_quantize_with_draws.restype = None
+        L.oracle_decode.argtypes = [u8p, u8p, C.c_int64, C.c_float, fp, C.c_int32, fp]
+        L.oracle_decode.restype = None
+        L.oracle_message_bytes.argtypes = [C.c_int32, i64p, i32p]
+        L.oracle_message_bytes.restype = C.c_int64
+        L.oracle_header_bytes.argtypes = [C.c_int32, i64p, i32p]
+        L.oracle_header_bytes.restype = C.c_int64
+        L.oracle_layout.argtypes = [C.c_int32, i64p, i32p, i64p, i64p]
+        L.oracle_layout.restype = None
+        L.oracle_pack_layer.argtypes = [u8p, u8p, C.c_int64, C.c_int32, u8p]
+        L.oracle_pack_layer.restype = None
+        L.oracle_unpack_layer.argtypes = [u8p, C.c_int64, C.c_int32, u8p, u8p]
+        L.oracle_unpack_layer.restype = None
+        L.oracle_quantize.argtypes = [C.c_int32, i64p, i32p, pp, pp, C.c_uint64, C.c_uint32, C.c_uint32, u8p, u8p, dp, dp]
+        L.oracle_quantize.restype = C.c_int32
+        L.oracle_dequant_aggregate.argtypes = [C.c_int32, i64p, i32p, C.c_int32, pp, pp]
+        L.oracle_dequant_aggregate.restype = None
+        L.oracle_step_size.argtypes = [C.c_int32, dp, dp, fp]
+        L.oracle_step_size.restype = None
+        L.oracle_oda_update.argtypes = [C.c_int64, fp, fp, fp, fp, fp, C.c_float, C.c_float]
+        L.oracle_oda_update.restype = None
+        L.oracle_histogram.argtypes = [fp, C.c_int64, u32p]
+        L.oracle_histogram.restype = None
+        L.oracle_fit_objective.argtypes = [u64p, fp, C.c_int32]
+        L.oracle_fit_objective.restype = C.c_double
+        L.oracle_fit_dp.argtypes = [u64p, C.c_int32, fp]
+        L.oracle_fit_dp.restype = None
+        L.oracle_fit_levels.argtypes = [C.c_int32, i64p, i32p, C.c_int32, i32p, C.c_int32, pp, pp, u32p, u64p]
+        L.oracle_fit_levels.restype = C.c_int32
+        _lib = L
+    return _lib
+
+
+def _p(a: np.ndarray, t):
+    return a.ctypes.data_as(C.POINTER(t))
+
+
+def _f32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _ptr_array(arrs: Sequence[Optional[np.ndarray]]):
+    out = (C.c_void_p * len(arrs))()
+    for i, a in enumerate(arrs):
+        out[i] = None if a is None else a.ctypes.data
+    return out
+
+
+# ------------------------------------------------------------------ scalars
+def philox4x32_10(ctr: Sequence[int], key: Sequence[int]) -> np.ndarray:
+    c = np.asarray(ctr, dtype=np.uint32)
+    k = np.asarray(key, dtype=np.uint32)
+    out = np.zeros(4, dtype=np.uint32)
+    lib().oracle_philox4x32_10(_p(c, C.c_uint32), _p(k, C.c_uint32), _p(out, C.c_uint32))
+    return out
+
+
+def draw16(seed: int, round_: int, node: int, layer: int, e: int) -> int:
+    return int(lib().oracle_draw16(seed, round_, node, layer, e))
+
+
+def sqrt_floor(s: float) -> np.float32:
+    return np.float32(lib().oracle_sqrt_floor(float(s)))
+
+
+def rcp_floor(x) -> np.float32:
+    return np.float32(lib().oracle_rcp_floor(C.c_float(float(x))))
+
+
+def level_index(levels, u) -> int:
+    lev = _f32(levels)
+    return int(lib().oracle_level_index(_p(lev, C.c_float), len(lev), C.c_float(float(u))))
+
+
+def index_bits(S: int) -> int:
+    return int(lib().oracle_index_bits(S))
+
+
+def sumsq(v) -> float:
+    v = _f32(v)
+    return float(lib().oracle_sumsq(_p(v, C.c_float), v.size))
+
+
+def norm_and_inv(v):
+    n = sqrt_floor(sumsq(v))
+    return n, rcp_floor(n)
+
+
+# ------------------------------------------------------------------ one layer, unpacked
+def quantize_range(v, e0: int, e1: int, inv, levels, seed: int, round_: int, node: int, layer: int):
+    v = _f32(v)
+    lev = _f32(levels)
+    sign = np.zeros(e1 - e0, dtype=np.uint8)
+    idx = np.zeros(e1 - e0, dtype=np.uint8)
+    lib().oracle_quantize_range(_p(v, C.c_float), e0, e1, C.c_float(float(inv)), _p(lev, C.c_float), len(lev), seed,
+                                round_, node, layer, _p(sign, C.c_uint8), _p(idx, C.c_uint8))
+    return sign, idx
+
+
+def quantize_with_draws(v, inv, levels, w16):
+    v = _f32(v)
+    lev = _f32(levels)
+    w = np.ascontiguousarray(w16, dtype=np.uint32)
+    sign = np.zeros(v.size, dtype=np.uint8)
+    idx = np.zeros(v.size, dtype=np.uint8)
+    lib().oracle_quantize_with_draws(_p(v, C.c_float), v.size, C.c_float(float(inv)), _p(lev, C.c_float), len(lev),
+                                     _p(w, C.c_uint32), _p(sign, C.c_uint8), _p(idx, C.c_uint8))
+    return sign, idx
+
+
+def decode(sign, idx, norm, levels) -> np.ndarray:
+    sign = np.ascontiguousarray(sign, dtype=np.uint8)
+    idx = np.ascontiguousarray(idx, dtype=np.uint8)
+    lev = _f32(levels)
+    out = np.zeros(sign.size, dtype=np.float32)
+    lib().oracle_decode(_p(sign, C.c_uint8), _p(idx, C.c_uint8), sign.size, C.c_float(float(norm)), _p(lev, C.c_float),
+                        len(lev), _p(out, C.c_float))
+    return out
+
+
+# ------------------------------------------------------------------ layout
+def _dims(sizes, points):
+    d = np.ascontiguousarray(sizes, dtype=np.int64)
+    S = np.ascontiguousarray(points, dtype=np.int32)
+    assert d.size == S.size
+    return d, S
+
+
+def message_bytes(sizes, points) -> int:
+    d, S = _dims(sizes, points)
+    return int(lib().oracle_message_bytes(d.size, _p(d, C.c_int64), _p(S, C.c_int32)))
+
+
+def header_bytes(sizes, points) -> int:
+    d, S = _dims(sizes, points)
+    return int(lib().oracle_header_bytes(d.size, _p(d, C.c_int64), _p(S, C.c_int32)))
+
+
+def layout(sizes, points):
+    d, S = _dims(sizes, points)
+    h = np.zeros(d.size, dtype=np.int64)
+    m = np.zeros(d.size, dtype=np.int64)
+    lib().oracle_layout(d.size, _p(d, C.c_int64), _p(S, C.c_int32), _p(h, C.c_int64), _p(m, C.c_int64))
+    return h, m
+
+
+def pack_layer(sign, idx, S: int) -> np.ndarray:
+    sign = np.ascontiguousarray(sign, dtype=np.uint8)
+    idx = np.ascontiguousarray(idx, dtype=np.uint8)
+    d = sign.size
+    planes = 1 + index_bits(S)
+    region = np.zeros(((d + BLOCK - 1) // BLOCK) * 32 * planes, dtype=np.uint8)
+    lib().oracle_pack_layer(_p(sign, C.c_uint8), _p(idx, C.c_uint8), d, S, _p(region, C.c_uint8))
+    return region
+
+
+def unpack_layer(region, d: int, S: int):
+    region = np.ascontiguousarray(region, dtype=np.uint8)
+    sign = np.zeros(d, dtype=np.uint8)
+    idx = np.zeros(d, dtype=np.uint8)
+    lib().oracle_unpack_layer(_p(region, C.c_uint8), d, S, _p(sign, C.c_uint8), _p(idx, C.c_uint8))
+    return sign, idx
+
+
+# ------------------------------------------------------------------ whole messages
+def quantize(sizes, points, levels: Sequence[np.ndarray], grads: Sequence[np.ndarray], seed: int, round_: int,
+             node: int, msg_prev: Optional[np.ndarray] = None):
+    """ENCODE(Q(V_k)) for one node.  Returns (msg bytes, sumsq per layer, delta, status)."""
+    d, S = _dims(sizes, points)
+    lev = [_f32(a) for a in levels]
+    g = [_f32(a) for a in grads]
+    for l in range(d.size):
+        assert g[l].size == d[l] and lev[l].size == S[l]
+    msg = np.zeros(message_bytes(d, S), dtype=np.uint8)
+    ss = np.zeros(d.size, dtype=np.float64)
+    delta = np.zeros(1, dtype=np.float64)
+    prev = None
+    if msg_prev is not None:
+        prev = np.ascontiguousarray(msg_prev, dtype=np.uint8)
+        assert prev.size == msg.size
+    st = lib().oracle_quantize(d.size, _p(d, C.c_int64), _p(S, C.c_int32), _ptr_array(lev), _ptr_array(g), seed, round_,
+                               node, _p(msg, C.c_uint8), None if prev is None else _p(prev, C.c_uint8),
+                               _p(ss, C.c_double), _p(delta, C.c_double))
+    return msg, ss, float(delta[0]), int(st)
+
+
+def dequant_aggregate(sizes, points, msgs: Sequence[np.ndarray]) -> List[np.ndarray]:
+    d, S = _dims(sizes, points)
+    ms = [np.ascontiguousarray(m, dtype=np.uint8) for m in msgs]
+    out = [np.zeros(int(n), dtype=np.float32) for n in d]
+    lib().oracle_dequant_aggregate(d.size, _p(d, C.c_int64), _p(S, C.c_int32), len(ms), _ptr_array(ms), _ptr_array(out))
+    return out
+
+
+def step_size(delta: Sequence[float], acc: float):
+    """Returns (new acc, eta)."""
+    dl = np.ascontiguousarray(delta, dtype=np.float64)
+    a = np.array([acc], dtype=np.float64)
+    eta = np.zeros(1, dtype=np.float32)
+    lib().oracle_step_size(dl.size, _p(dl, C.c_double), _p(a, C.c_double), _p(eta, C.c_float))
+    return float(a[0]), np.float32(eta[0])
+
+
+def oda_update(mean, x1, y, eta, gamma, want_next: bool = True):
+    """In place on ``y``.  Returns (x_next or None, x_half)."""
+    mean = _f32(mean)
+    x1 = _f32(x1)
+    assert y.dtype == np.float32 and y.flags.c_contiguous
+    xn = np.zeros_like(y) if want_next else None
+    xh = np.zeros_like(y)
+    lib().oracle_oda_update(y.size, _p(mean, C.c_float), _p(x1, C.c_float), _p(y, C.c_float),
+                            None if xn is None else _p(xn, C.c_float), _p(xh, C.c_float), C.c_float(float(eta)),
+                            C.c_float(float(gamma)))
+    return xn, xh
+
+
+# ------------------------------------------------------------------ level fit
+def histogram(v) -> np.ndarray:
+    v = _f32(v)
+    h = np.zeros(HIST_BINS, dtype=np.uint32)
+    lib().oracle_histogram(_p(v, C.c_float), v.size, _p(h, C.c_uint32))
+    return h
+
+
+def fit_objective(W, levels) -> float:
+    W = np.ascontiguousarray(W, dtype=np.uint64)
+    assert W.size == GRID_POINTS
+    lev = _f32(levels)
+    return float(lib().oracle_fit_objective(_p(W, C.c_uint64), _p(lev, C.c_float), lev.size))
+
+
+def fit_dp(W, S: int) -> np.ndarray:
+    W = np.ascontiguousarray(W, dtype=np.uint64)
+    assert W.size == GRID_POINTS
+    lev = np.zeros(S, dtype=np.float32)
+    lib().oracle_fit_dp(_p(W, C.c_uint64), S, _p(lev, C.c_float))
+    return lev
+
+
+def fit_levels(sizes, layer_type, type_points, K: int, grads: Sequence[np.ndarray], levels: Sequence[np.ndarray]):
+    """grads: K*L arrays (entry k*L+l).  levels: M arrays, updated copies returned with (hist, pooled, status)."""
+    d = np.ascontiguousarray(sizes, dtype=np.int64)
+    lt = np.ascontiguousarray(layer_type, dtype=np.int32)
+    tp = np.ascontiguousarray(type_points, dtype=np.int32)
+    L, M = d.size, tp.size
+    g = [_f32(a) for a in grads]
+    assert len(g) == K * L
+    lev = [_f32(a).copy() for a in levels]
+    hist = np.zeros(K * L * HIST_BINS, dtype=np.uint32)
+    pooled = np.zeros(M * GRID_POINTS, dtype=np.uint64)
+    st = lib().oracle_fit_levels(L, _p(d, C.c_int64), _p(lt, C.c_int32), M, _p(tp, C.c_int32), K, _ptr_array(g),
+                                 _ptr_array(lev), _p(hist, C.c_uint32), _p(pooled, C.c_uint64))
+    return lev, hist.reshape(K, L, HIST_BINS), pooled.reshape(M, GRID_POINTS), int(st)
+
+
+def grid_values() -> np.ndarray:
+    """The 257 normalised grid points g_j as float32 (bit pattern (j + 760) << 20)."""
+    return ((np.arange(GRID_POINTS, dtype=np.uint32) + GRID_BASE) << 20).view(np.float32)
+
+
+def grid_mids() -> np.ndarray:
+    m = (((np.arange(GRID_POINTS, dtype=np.uint32) + GRID_BASE) << 20) | (1 << 19)).view(np.float32).astype(np.float64)
+    m[-1] = 1.0
+    return m

@@ -1,0 +1,557 @@
+// QODA CPU oracle -- TEST INFRASTRUCTURE, NOT THE PRODUCT.
+//
+// A plain, single-threaded, deliberately slow C++17 implementation of the per-round hot path of
+// Quantized Optimistic Dual Averaging with layer-wise unbiased stochastic quantization
+// (arXiv 2505.14371).  It exists so that the GPU library can be checked against something that a
+// reader can verify against the paper by eye.  It shares no code with the GPU library; only tests,
+// the smoke check and the bench's cpu_baseline leg may call it.
+//
+// What follows the paper, and where:
+//   * vector representation (norm, signs, normalised magnitudes u_i)          -- Sec. 2.2
+//   * level index tau(u), relative distance xi(u), random rounding q_l(u),
+//     Q(v_i) = ||v|| * sign(v_i) * q_l(u_i), coordinates drawn independently  -- Sec. 3.1
+//   * ENCODE / DECODE: 32-bit float norm, one sign bit, fixed-width level
+//     index per coordinate (no entropy code, as in the experiments)           -- Sec. 3.2, App. C.1
+//   * level fit: minimise sum_i int (l_{i+1}-u)(u-l_i) dF~(u), F~ the
+//     norm^2-weighted pooled CDF of the sampled dual vectors                  -- Sec. 3.2, eq. (Qada2) and
+//                                                                                 the weights lambda_z
+//   * optimistic dual averaging update and adaptive step size                -- Sec. 4, eq. (ODA),
+//                                                                                 eq. (general_stepsize), Alg. 1
+//
+// Pin status (see tests/test_oracle_*.py): every function below is pinned to something the paper or the
+// mathematics fixes EXCEPT the Philox generator's known-answer vectors: no published known-answer
+// file is available here, so philox4x32_10 is pinned only statistically (uniformity, independence,
+// unbiasedness of the rounding it drives) -- "external KAT: parity unpinned".
+// The level fit minimises the paper's objective exactly on a histogram grid; the paper delegates the
+// optimiser itself to third-party code it does not describe, so optimality relative to that code is
+// also "parity unpinned".
+//
+// Arithmetic contract (the GPU library follows the same written contract independently):
+//   fp32 operations are single IEEE operations, never fused; sums that feed integer decisions are
+//   taken in fp64 in a fixed "slot + halving tree" order; square roots and reciprocals that feed
+//   integer decisions are defined by exact comparisons (largest float whose square / product does not
+//   exceed the argument), so they do not depend on how well a sqrt or divide instruction rounds.
+//
+// Build: g++ -O2 -std=c++17 -ffp-contract=off -fno-fast-math -shared -fPIC qoda_oracle.cpp -o libqoda_oracle.so
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <limits>
+#include <vector>
+
+namespace {
+
+constexpr int64_t kBlock = 256;     // coordinates per packed block
+constexpr int64_t kChunk = 16384;   // coordinates per reduction chunk (64 blocks)
+constexpr int kSlots = 256;         // reduction slots per chunk
+constexpr int kHistBins = 2048;     // histogram bins on the top 11 magnitude bits of a float
+constexpr int kGridBase = 760;      // (127-32)<<3 : bin of 2^-32 on the normalised grid
+constexpr int kGridPoints = 257;    // normalised grid g_0=2^-32 ... g_256=1
+
+inline uint32_t f2u(float f) { uint32_t u; std::memcpy(&u, &f, 4); return u; }
+inline float u2f(uint32_t u) { float f; std::memcpy(&f, &u, 4); return f; }
+
+inline int index_bits(int S) {   // b = ceil(log2 S), at least 1
+  int b = 1;
+  while ((1 << b) < S) ++b;
+  return b;
+}
+
+// ----- Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11), written from the published construction.
+void philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+  const uint64_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+  const uint32_t W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+  uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+  uint32_t k0 = key[0], k1 = key[1];
+  for (int r = 0; r < 10; ++r) {
+    if (r > 0) { k0 += W0; k1 += W1; }
+    const uint64_t p0 = M0 * (uint64_t)c0;
+    const uint64_t p1 = M1 * (uint64_t)c2;
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+    const uint32_t n1 = (uint32_t)p1;
+    const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    const uint32_t n3 = (uint32_t)p0;
+    c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// The 16-bit uniform integer that decides coordinate e of (layer, round, node).
+// One generator call serves 8 coordinates: the same lane position (e mod 256)/4 of two consecutive
+// 256-coordinate blocks; the even block takes the low halves of the four output words, the odd block
+// the high halves; word index = e mod 4.
+uint32_t draw16(uint64_t seed, uint32_t round, uint32_t node, uint32_t layer, uint64_t e) {
+  const uint32_t ctr[4] = {(uint32_t)(((e >> 9) << 6) | ((e >> 2) & 63u)), layer, round, node};
+  const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+  uint32_t out[4];
+  philox4x32_10(ctr, key, out);
+  const uint32_t w = out[e & 3];
+  return ((e >> 8) & 1) ? (w >> 16) : (w & 0xFFFFu);
+}
+
+// ----- canonical fp64 reductions.
+// slot of coordinate e inside its chunk: block B = (e mod 16384)/256, slot = 64*(B/16) + (e mod 256)/4.
+inline int slot_of(int64_t e) {
+  const int64_t ec = e % kChunk;
+  const int64_t B = ec / kBlock;
+  return (int)(64 * (B / 16) + (ec % kBlock) / 4);
+}
+
+double halving_tree(double *p) {   // p has kSlots entries; destroys p
+  for (int h = kSlots / 2; h >= 1; h /= 2)
+    for (int i = 0; i < h; ++i) p[i] = p[i] + p[i + h];
+  return p[0];
+}
+
+// Combine per-chunk sums: slot j takes chunks j, j+256, ... in increasing order, then the tree.
+double combine_chunks(const std::vector<double> &chunk_sums) {
+  double p[kSlots];
+  for (int j = 0; j < kSlots; ++j) p[j] = 0.0;
+  for (size_t c = 0; c < chunk_sums.size(); ++c) p[c % kSlots] = p[c % kSlots] + chunk_sums[c];
+  return halving_tree(p);
+}
+
+// per-chunk sums of squares of one layer (products are exact in fp64).
+void chunk_sumsq(const float *v, int64_t d, std::vector<double> &out) {
+  const int64_t nchunks = (d + kChunk - 1) / kChunk;
+  for (int64_t c = 0; c < nchunks; ++c) {
+    double p[kSlots];
+    for (int j = 0; j < kSlots; ++j) p[j] = 0.0;
+    const int64_t e1 = std::min(d, (c + 1) * kChunk);
+    for (int64_t e = c * kChunk; e < e1; ++e) {
+      const double x = (double)v[e];
+      p[slot_of(e)] = p[slot_of(e)] + x * x;
+    }
+    out.push_back(halving_tree(p));
+  }
+}
+
+// largest float n >= 0 with n*n <= s (n*n is exact in fp64).  s must be finite and >= 0.
+float sqrt_floor(double s) {
+  if (!(s >= 0.0) || !(s <= (double)std::numeric_limits<float>::max() * (double)std::numeric_limits<float>::max()))
+    return 0.0f;   // caller flags non-finite
+  double r = std::sqrt(s);
+  float n = (r >= (double)std::numeric_limits<float>::max()) ? std::numeric_limits<float>::max() : (float)r;
+  for (int it = 0; it < 4 && (double)n * (double)n > s; ++it) n = u2f(f2u(n) - 1);
+  for (int it = 0; it < 4; ++it) {
+    if (n == std::numeric_limits<float>::max()) break;
+    const float up = u2f(f2u(n) + 1);
+    if ((double)up * (double)up <= s) n = up; else break;
+  }
+  return n;
+}
+
+// largest finite float r >= 0 with x*r <= 1 (x*r is exact in fp64); 0 for x <= 0 or non-finite x.
+float rcp_floor(float x) {
+  if (!(x > 0.0f) || std::isinf(x)) return 0.0f;
+  float r = 1.0f / x;
+  if (std::isinf(r)) r = std::numeric_limits<float>::max();
+  for (int it = 0; it < 4 && (double)x * (double)r > 1.0; ++it) r = u2f(f2u(r) - 1);
+  for (int it = 0; it < 4; ++it) {
+    if (r == std::numeric_limits<float>::max()) break;
+    const float up = u2f(f2u(r) + 1);
+    if ((double)x * (double)up <= 1.0) r = up; else break;
+  }
+  return r;
+}
+
+// tau(u) = largest j in [0, S-2] with level[j] <= u   (Sec. 3.1; at u = 1 the last interval is taken)
+int level_index(const float *lev, int S, float u) {
+  int tau = 0;
+  for (int j = 1; j <= S - 2; ++j)
+    if (lev[j] <= u) tau = j;
+  return tau;
+}
+
+struct Code { uint8_t sign; uint8_t h; };
+
+// Q of one coordinate (Sec. 2.2 + Sec. 3.1): u = min(|v| * inv, 1); tau; xi; round up iff draw < xi.
+Code quantize_coord(float v, float inv, const float *lev, int S, uint32_t w16) {
+  const float u = std::fmin(std::fabs(v) * inv, 1.0f);
+  const int tau = level_index(lev, S, u);
+  const float rgap = rcp_floor(lev[tau + 1] - lev[tau]);
+  const float xi = (u - lev[tau]) * rgap;
+  const bool up = ((float)w16 + 0.5f) < xi * 65536.0f;
+  Code c;
+  c.sign = (uint8_t)(f2u(v) >> 31);
+  c.h = (uint8_t)(tau + (up ? 1 : 0));
+  return c;
+}
+
+inline float decode_value(uint8_t sign, int h, float norm, const float *lev, int S) {
+  if (h > S - 1) h = S - 1;
+  const float t = norm * lev[h];
+  return sign ? -t : t;
+}
+
+// ----- message layout.
+struct Layout {
+  int L;
+  std::vector<int64_t> d, nblk, hdr_off, msg_off;
+  std::vector<int> S, planes;
+  int64_t header_bytes, message_bytes;
+  int64_t total_chunks;
+};
+
+inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+Layout make_layout(int L, const int64_t *d, const int32_t *S) {
+  Layout lay;
+  lay.L = L;
+  int64_t h = 0;
+  for (int l = 0; l < L; ++l) {
+    lay.d.push_back(d[l]);
+    lay.S.push_back(S[l]);
+    lay.planes.push_back(1 + index_bits(S[l]));
+    lay.nblk.push_back((d[l] + kBlock - 1) / kBlock);
+    lay.hdr_off.push_back(h);
+    h += 4 * (1 + (int64_t)S[l]);
+  }
+  lay.header_bytes = round_up(h, 256);
+  int64_t off = lay.header_bytes;
+  int64_t chunks = 0;
+  for (int l = 0; l < L; ++l) {
+    lay.msg_off.push_back(off);
+    off += lay.nblk[l] * 32 * lay.planes[l];
+    chunks += (d[l] + kChunk - 1) / kChunk;
+  }
+  lay.message_bytes = round_up(off, 256);
+  lay.total_chunks = chunks;
+  return lay;
+}
+
+// bit (plane p) of coordinate e of a layer inside a message: word p*4 + (e mod 4) of block e/256, bit (e mod 256)/4.
+inline uint64_t *word_ptr(uint8_t *layer_base, int planes, int64_t e, int p) {
+  return reinterpret_cast<uint64_t *>(layer_base + (e / kBlock) * 32 * planes) + (p * 4 + (e & 3));
+}
+inline const uint64_t *word_ptr(const uint8_t *layer_base, int planes, int64_t e, int p) {
+  return reinterpret_cast<const uint64_t *>(layer_base + (e / kBlock) * 32 * planes) + (p * 4 + (e & 3));
+}
+inline int bit_of(int64_t e) { return (int)((e % kBlock) / 4); }
+
+void put_code(uint8_t *layer_base, int planes, int64_t e, Code c) {
+  const int i = bit_of(e);
+  if (c.sign) *word_ptr(layer_base, planes, e, 0) |= (uint64_t)1 << i;
+  for (int p = 1; p < planes; ++p)
+    if ((c.h >> (p - 1)) & 1) *word_ptr(layer_base, planes, e, p) |= (uint64_t)1 << i;
+}
+
+Code get_code(const uint8_t *layer_base, int planes, int64_t e) {
+  const int i = bit_of(e);
+  Code c;
+  c.sign = (uint8_t)((*word_ptr(layer_base, planes, e, 0) >> i) & 1);
+  int h = 0;
+  for (int p = 1; p < planes; ++p) h |= (int)((*word_ptr(layer_base, planes, e, p) >> i) & 1) << (p - 1);
+  c.h = (uint8_t)h;
+  return c;
+}
+
+struct HeaderView { float norm; const float *lev; };
+inline HeaderView header_of(const uint8_t *msg, const Layout &lay, int l) {
+  HeaderView h;
+  const float *p = reinterpret_cast<const float *>(msg + lay.hdr_off[l]);
+  h.norm = p[0];
+  h.lev = p + 1;
+  return h;
+}
+
+inline float grid_value(int j) { return u2f((uint32_t)(j + kGridBase) << 20); }
+inline double grid_mid(int j) {
+  if (j == kGridPoints - 1) return 1.0;
+  return (double)u2f(((uint32_t)(j + kGridBase) << 20) | (1u << 19));
+}
+
+}  // namespace
+
+extern "C" {
+
+// ---------------------------------------------------------------- scalar building blocks (exposed for the pins)
+void oracle_philox4x32_10(const uint32_t *ctr, const uint32_t *key, uint32_t *out) { philox4x32_10(ctr, key, out); }
+uint32_t oracle_draw16(uint64_t seed, uint32_t round, uint32_t node, uint32_t layer, uint64_t e) {
+  return draw16(seed, round, node, layer, e);
+}
+float oracle_sqrt_floor(double s) { return sqrt_floor(s); }
+float oracle_rcp_floor(float x) { return rcp_floor(x); }
+int32_t oracle_level_index(const float *lev, int32_t S, float u) { return level_index(lev, S, u); }
+int32_t oracle_index_bits(int32_t S) { return index_bits(S); }
+
+// canonical sum of squares of one layer (Sec. 2.2, L2 norm before the square root).
+double oracle_sumsq(const float *v, int64_t d) {
+  std::vector<double> cs;
+  chunk_sumsq(v, d, cs);
+  return combine_chunks(cs);
+}
+
+// ---------------------------------------------------------------- one layer, unpacked (Sec. 3.1)
+// Quantize coordinates [e0, e1) of a layer of d entries; inv is the layer's reciprocal norm.
+void oracle_quantize_range(const float *v, int64_t e0, int64_t e1, float inv, const float *lev, int32_t S,
+                           uint64_t seed, uint32_t round, uint32_t node, uint32_t layer, uint8_t *sign_out,
+                           uint8_t *index_out) {
+  for (int64_t e = e0; e < e1; ++e) {
+    const Code c = quantize_coord(v[e], inv, lev, S, draw16(seed, round, node, layer, (uint64_t)e));
+    sign_out[e - e0] = c.sign;
+    index_out[e - e0] = c.h;
+  }
+}
+
+// Same, but with the 16-bit draw supplied by the caller (used to enumerate every outcome in the pins).
+void oracle_quantize_with_draws(const float *v, int64_t n, float inv, const float *lev, int32_t S,
+                                const uint32_t *w16, uint8_t *sign_out, uint8_t *index_out) {
+  for (int64_t e = 0; e < n; ++e) {
+    const Code c = quantize_coord(v[e], inv, lev, S, w16[e]);
+    sign_out[e] = c.sign;
+    index_out[e] = c.h;
+  }
+}
+
+void oracle_decode(const uint8_t *sign, const uint8_t *index, int64_t n, float norm, const float *lev, int32_t S,
+                   float *out) {
+  for (int64_t e = 0; e < n; ++e) out[e] = decode_value(sign[e], index[e], norm, lev, S);
+}
+
+// ---------------------------------------------------------------- message layout (Sec. 3.2, fixed width)
+int64_t oracle_message_bytes(int32_t L, const int64_t *d, const int32_t *S) { return make_layout(L, d, S).message_bytes; }
+int64_t oracle_header_bytes(int32_t L, const int64_t *d, const int32_t *S) { return make_layout(L, d, S).header_bytes; }
+void oracle_layout(int32_t L, const int64_t *d, const int32_t *S, int64_t *hdr_off, int64_t *msg_off) {
+  const Layout lay = make_layout(L, d, S);
+  for (int l = 0; l < L; ++l) { hdr_off[l] = lay.hdr_off[l]; msg_off[l] = lay.msg_off[l]; }
+}
+
+// pack / unpack the codes of one layer into its block region (region must hold nblk*32*planes bytes).
+void oracle_pack_layer(const uint8_t *sign, const uint8_t *index, int64_t d, int32_t S, uint8_t *region) {
+  const int planes = 1 + index_bits(S);
+  const int64_t nblk = (d + kBlock - 1) / kBlock;
+  std::memset(region, 0, (size_t)(nblk * 32 * planes));
+  for (int64_t e = 0; e < d; ++e) { Code c; c.sign = sign[e]; c.h = index[e]; put_code(region, planes, e, c); }
+}
+void oracle_unpack_layer(const uint8_t *region, int64_t d, int32_t S, uint8_t *sign, uint8_t *index) {
+  const int planes = 1 + index_bits(S);
+  for (int64_t e = 0; e < d; ++e) { const Code c = get_code(region, planes, e); sign[e] = c.sign; index[e] = c.h; }
+}
+
+// ---------------------------------------------------------------- ENCODE(Q(V_k)) for one node: Alg. 1 line 12
+// grads[l]  : layer l of the node's dual vector.      levels[l] : the S[l] levels of layer l's type.
+// msg       : message_bytes output.                    msg_prev  : previous-round message of this node or NULL.
+// sumsq_out : L canonical sums of squares (may be NULL).
+// delta_out : || Vhat_{k,t+1/2} - Vhat_{k,t-1/2} ||^2 (the step-size term of eq. (general_stepsize)); prev = 0 if NULL.
+// returns 0, or 1 if a layer's sum of squares is not finite.
+int32_t oracle_quantize(int32_t L, const int64_t *d, const int32_t *S, const float *const *levels,
+                        const float *const *grads, uint64_t seed, uint32_t round, uint32_t node, uint8_t *msg,
+                        const uint8_t *msg_prev, double *sumsq_out, double *delta_out) {
+  const Layout lay = make_layout(L, d, S);
+  std::memset(msg, 0, (size_t)lay.message_bytes);
+  int32_t status = 0;
+  std::vector<double> delta_chunks;
+  for (int l = 0; l < L; ++l) {
+    const double s = oracle_sumsq(grads[l], d[l]);
+    if (sumsq_out) sumsq_out[l] = s;
+    const bool finite = (s >= 0.0) && (s <= (double)std::numeric_limits<float>::max() * (double)std::numeric_limits<float>::max());
+    if (!finite) status = 1;
+    const float norm = finite ? sqrt_floor(s) : 0.0f;
+    const float inv = rcp_floor(norm);
+    float *hdr = reinterpret_cast<float *>(msg + lay.hdr_off[l]);
+    hdr[0] = norm;
+    for (int j = 0; j < S[l]; ++j) hdr[1 + j] = levels[l][j];
+    uint8_t *region = msg + lay.msg_off[l];
+    const int64_t nchunks = (d[l] + kChunk - 1) / kChunk;
+    for (int64_t c = 0; c < nchunks; ++c) {
+      double p[kSlots];
+      for (int j = 0; j < kSlots; ++j) p[j] = 0.0;
+      const int64_t e1 = std::min(d[l], (c + 1) * kChunk);   // padding coordinates carry code 0 and add nothing
+      for (int64_t e = c * kChunk; e < e1; ++e) {
+        const Code code =
+            quantize_coord(grads[l][e], inv, levels[l], S[l], draw16(seed, round, node, (uint32_t)l, (uint64_t)e));
+        put_code(region, lay.planes[l], e, code);
+        const float cur = decode_value(code.sign, code.h, norm, levels[l], S[l]);
+        float prev = 0.0f;
+        if (msg_prev) {
+          const HeaderView hp = header_of(msg_prev, lay, l);
+          const Code pc = get_code(msg_prev + lay.msg_off[l], lay.planes[l], e);
+          prev = decode_value(pc.sign, pc.h, hp.norm, hp.lev, S[l]);
+        }
+        const float diff = cur - prev;
+        p[slot_of(e)] = p[slot_of(e)] + (double)diff * (double)diff;
+      }
+      delta_chunks.push_back(halving_tree(p));
+    }
+  }
+  if (delta_out) *delta_out = combine_chunks(delta_chunks);
+  return status;
+}
+
+// ---------------------------------------------------------------- DECODE + mean over the K nodes: Alg. 1 lines 15-17
+// mean_out[l][e] = ((Vhat_0 + Vhat_1) + ... + Vhat_{K-1}) * (1/K), all in fp32, k increasing.
+void oracle_dequant_aggregate(int32_t L, const int64_t *d, const int32_t *S, int32_t K, const uint8_t *const *msgs,
+                              float *const *mean_out) {
+  const Layout lay = make_layout(L, d, S);
+  const float invK = 1.0f / (float)K;
+  for (int l = 0; l < L; ++l)
+    for (int64_t e = 0; e < d[l]; ++e) {
+      float sum = 0.0f;
+      for (int k = 0; k < K; ++k) {
+        const HeaderView h = header_of(msgs[k], lay, l);
+        const Code c = get_code(msgs[k] + lay.msg_off[l], lay.planes[l], e);
+        const float val = decode_value(c.sign, c.h, h.norm, h.lev, S[l]);
+        sum = (k == 0) ? val : sum + val;
+      }
+      mean_out[l][e] = sum * invK;
+    }
+}
+
+// ---------------------------------------------------------------- step size: eq. (general_stepsize)
+// acc <- acc + (delta_0 + ... + delta_{K-1}) / K^2 ;  eta = gamma = (1 + acc)^(-1/2), taken as
+// rcp_floor(sqrt_floor(1 + acc)) so that it is defined by exact comparisons.
+void oracle_step_size(int32_t K, const double *delta, double *acc, float *eta_out) {
+  double sum = 0.0;
+  for (int k = 0; k < K; ++k) sum = (k == 0) ? delta[k] : sum + delta[k];
+  const double invK2 = 1.0 / ((double)K * (double)K);
+  *acc = *acc + sum * invK2;
+  *eta_out = rcp_floor(sqrt_floor(1.0 + *acc));
+}
+
+// ---------------------------------------------------------------- eq. (ODA) + Alg. 1 lines 10, 17, 18
+// Y <- Y - mean ; X_next = X_1 + eta * Y ; X_half = X_next - gamma * mean   (next round's extrapolated point).
+void oracle_oda_update(int64_t n, const float *mean, const float *x1, float *y, float *x_next, float *x_half,
+                       float eta, float gamma) {
+  for (int64_t e = 0; e < n; ++e) {
+    const float yn = y[e] - mean[e];
+    const float ey = eta * yn;
+    const float xn = x1[e] + ey;
+    const float gm = gamma * mean[e];
+    y[e] = yn;
+    if (x_next) x_next[e] = xn;
+    x_half[e] = xn - gm;
+  }
+}
+
+// ---------------------------------------------------------------- level fit: eq. (Qada2), weights lambda_z
+// The K nodes' current vectors are the Z samples.  Every coordinate of (node k, layer l) carries weight
+// ||v_{k,l}||^2 (the factor that multiplies its normalised variance in eq. (MQV)/(Qada2)); layers of the
+// same type pool.  The distribution is estimated by a histogram:
+//   1. bin |v| on its top 11 magnitude bits (8 exponent + 3 mantissa bits): counts[k][l][2048];
+//   2. map each bin's midpoint c to u = min(c * inv_norm, 1), re-bin u the same way onto the 257-point
+//      grid g_j (g_0 = 2^-32, ..., g_256 = 1), adding weight wfix(k,l) * count, where
+//      wfix = floor(sumsq(k,l) * 2^(23 - e)) and e is the binary exponent of the largest sumsq of the type;
+//   3. minimise sum_i sum_{bins in [l_i, l_{i+1})} W_j (l_{i+1} - mid_j)(mid_j - l_i) exactly over interior
+//      levels restricted to grid points, by dynamic programming (first level 0 and last level 1 are fixed).
+// hist_out (optional): K*L*2048 uint32 counts.  pooled_out (optional): M*257 uint64 weights.
+// levels_io: M pointers to S_m floats; a type whose sampled vectors are all zero keeps its levels.
+void oracle_histogram(const float *v, int64_t d, uint32_t *counts /* 2048, accumulated into */) {
+  for (int64_t e = 0; e < d; ++e) counts[(f2u(v[e]) & 0x7FFFFFFFu) >> 20] += 1;
+}
+
+// objective of eq. (Qada2) for given levels on pooled grid weights W[257] (used by the fit and by its pins)
+double oracle_fit_objective(const uint64_t *W, const float *lev, int32_t S) {
+  double total = 0.0;
+  for (int j = 0; j < kGridPoints - 1; ++j) {
+    if (W[j] == 0) continue;
+    const double u = grid_mid(j);
+    const int tau = level_index(lev, S, (float)u);
+    total += (double)W[j] * ((double)lev[tau + 1] - u) * (u - (double)lev[tau]);
+  }
+  return total;
+}
+
+void oracle_fit_dp(const uint64_t *W, int32_t S, float *lev_out) {
+  const int J = kGridPoints;
+  std::vector<double> P0(J + 1), P1(J + 1), P2(J + 1);
+  P0[0] = P1[0] = P2[0] = 0.0;
+  for (int j = 0; j < J; ++j) {
+    const double w = (double)W[j];
+    const double m = grid_mid(j);
+    const double wm = w * m;
+    P0[j + 1] = P0[j] + w;
+    P1[j + 1] = P1[j] + wm;
+    P2[j + 1] = P2[j] + wm * m;
+  }
+  auto cost0 = [&](int b) { return (double)grid_value(b) * P1[b] - P2[b]; };
+  auto cost = [&](int a, int b) {
+    const double ga = (double)grid_value(a), gb = (double)grid_value(b);
+    return ((ga + gb) * (P1[b] - P1[a]) - (P2[b] - P2[a])) - (ga * gb) * (P0[b] - P0[a]);
+  };
+  lev_out[0] = 0.0f;
+  lev_out[S - 1] = 1.0f;
+  if (S == 2) return;
+  const int last = J - 1;   // grid index of level S-1
+  const double inf = std::numeric_limits<double>::infinity();
+  // D[s][b]: best cost of bins below g_b with level s placed at grid index b, s = 1..S-2
+  std::vector<std::vector<double>> D(S, std::vector<double>(J, inf));
+  std::vector<std::vector<int>> arg(S, std::vector<int>(J, -1));
+  for (int b = 1; b <= last - (S - 2); ++b) D[1][b] = cost0(b);
+  for (int s = 2; s <= S - 2; ++s)
+    for (int b = s; b <= last - (S - 1 - s); ++b) {
+      double best = inf; int besta = -1;
+      for (int a = s - 1; a <= b - 1; ++a) {
+        const double c = D[s - 1][a] + cost(a, b);
+        if (c < best) { best = c; besta = a; }
+      }
+      D[s][b] = best; arg[s][b] = besta;
+    }
+  double best = inf; int besta = -1;
+  for (int a = S - 2; a <= last - 1; ++a) {
+    const double c = D[S - 2][a] + cost(a, last);
+    if (c < best) { best = c; besta = a; }
+  }
+  int b = besta;
+  for (int s = S - 2; s >= 1; --s) {
+    lev_out[s] = grid_value(b);
+    b = arg[s][b];
+  }
+}
+
+int32_t oracle_fit_levels(int32_t L, const int64_t *d, const int32_t *layer_type, int32_t M, const int32_t *type_points,
+                          int32_t K, const float *const *grads /* K*L, entry k*L+l */, float *const *levels_io,
+                          uint32_t *hist_out, uint64_t *pooled_out) {
+  std::vector<double> s((size_t)K * L);
+  std::vector<uint32_t> hist((size_t)K * L * kHistBins, 0);
+  for (int k = 0; k < K; ++k)
+    for (int l = 0; l < L; ++l) {
+      s[(size_t)k * L + l] = oracle_sumsq(grads[(size_t)k * L + l], d[l]);
+      oracle_histogram(grads[(size_t)k * L + l], d[l], &hist[((size_t)k * L + l) * kHistBins]);
+    }
+  if (hist_out) std::memcpy(hist_out, hist.data(), hist.size() * sizeof(uint32_t));
+  const double smax_ok = (double)std::numeric_limits<float>::max() * (double)std::numeric_limits<float>::max();
+  int32_t status = 0;
+  for (int m = 0; m < M; ++m) {
+    std::vector<uint64_t> W(kGridPoints, 0);
+    double smax = 0.0;
+    bool finite = true;
+    for (int l = 0; l < L; ++l) {
+      if (layer_type[l] != m) continue;
+      for (int k = 0; k < K; ++k) {
+        const double v = s[(size_t)k * L + l];
+        if (!(v >= 0.0) || !(v <= smax_ok)) finite = false;
+        else if (v > smax) smax = v;
+      }
+    }
+    if (!finite) status = 1;
+    if (finite && smax > 0.0) {
+      const int ex = std::ilogb(smax);
+      for (int l = 0; l < L; ++l) {
+        if (layer_type[l] != m) continue;
+        for (int k = 0; k < K; ++k) {
+          const double sv = s[(size_t)k * L + l];
+          const uint64_t wfix = (uint64_t)std::floor(std::ldexp(sv, 23 - ex));
+          const float inv = rcp_floor(sqrt_floor(sv));
+          if (wfix == 0 || inv == 0.0f) continue;
+          const uint32_t *cnt = &hist[((size_t)k * L + l) * kHistBins];
+          for (int b = 1; b < kHistBins; ++b) {
+            if (cnt[b] == 0) continue;
+            const float c = u2f(((uint32_t)b << 20) | (1u << 19));
+            const float uc = std::fmin(c * inv, 1.0f);
+            int j = (int)(f2u(uc) >> 20) - kGridBase;
+            if (j < 0) j = 0;
+            if (j > kGridPoints - 1) j = kGridPoints - 1;
+            W[j] += wfix * (uint64_t)cnt[b];
+          }
+        }
+      }
+      oracle_fit_dp(W.data(), type_points[m], levels_io[m]);
+    }
+    if (pooled_out) std::memcpy(pooled_out + (size_t)m * kGridPoints, W.data(), kGridPoints * sizeof(uint64_t));
+  }
+  return status;
+}
+
+}  // extern "C"

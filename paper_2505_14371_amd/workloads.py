@@ -1,0 +1,174 @@
+"""Seeded synthetic inputs shaped like the paper's workloads.
+
+This module holds no arithmetic of the method (no norms, levels, rounding, packing or updates): it only
+produces layer sizes and random layer contents, for the GPU library and for the CPU checker alike.
+
+The paper trains a WGAN on CIFAR and Transformer-XL on WikiText-103 (Sec. 7); neither the data nor the
+models are used here.  Gradients are replaced by heavy-tailed synthetic vectors with one scale per tensor:
+Student-t with 3 degrees of freedom, Z0 / sqrt((Z1^2+Z2^2+Z3^2)/3), times sigma_l drawn log-uniformly.
+"""
+from __future__ import annotations
+
+import dataclasses
+from typing import List, Optional, Tuple
+
+import numpy as np
+
+
+@dataclasses.dataclass(frozen=True)
+class Workload:
+    name: str
+    sizes: Tuple[int, ...]          # elements per layer (tensor), in order
+    num_nodes: int                  # K
+    points: int                     # S: grid points of every layer's level sequence, including 0 and 1
+    rounds: int
+    seed: int
+    dist: str                       # "normal" | "student_t3"
+    scale_range: Optional[Tuple[float, float]] = None   # log-uniform per-tensor sigma; None = 1
+    bf16: bool = False              # round entries to bfloat16 (nearest even) before use
+    adaptive: bool = True           # levels fitted every round
+
+    @property
+    def total(self) -> int:
+        return int(sum(self.sizes))
+
+
+def _txl_sizes() -> Tuple[int, ...]:
+    d_model, n_head, d_head, d_inner, n_layer, vocab = 410, 10, 41, 2100, 16, 267735
+    s: List[int] = [vocab * d_model, n_head * d_head, n_head * d_head]
+    for _ in range(n_layer):
+        s += [3 * n_head * d_head * d_model, n_head * d_head * d_model, d_model * n_head * d_head, d_model, d_model,
+              d_inner * d_model, d_inner, d_model * d_inner, d_model, d_model, d_model]
+    return tuple(s)
+
+
+def _gpt_sizes() -> Tuple[int, ...]:
+    d, ffn, n_layer, vocab, ctx = 2048, 8192, 24, 50304, 2048
+    s: List[int] = [vocab * d, ctx * d]
+    for _ in range(n_layer):
+        s += [d, d, 3 * d * d, 3 * d, d * d, d, d, d, ffn * d, ffn, d * ffn, d]
+    s += [d, d]
+    return tuple(s)
+
+
+_WORKLOADS = {
+    "bilinear": Workload("bilinear", (512, 512), 4, 8, 200, 0, "normal", adaptive=False),
+    "microbench": Workload("microbench", (1 << 24,), 1, 16, 1, 1, "normal", adaptive=False),
+    "dcgan": Workload("dcgan", (819200, 2097152, 524288, 131072, 3072, 3072, 131072, 524288, 2097152, 8192), 8, 16,
+                      100, 3, "student_t3", (1e-4, 1e-1)),
+    "txl": Workload("txl", _txl_sizes(), 8, 8, 20, 4, "student_t3", (1e-5, 1e-2)),
+    "gpt1p3b": Workload("gpt1p3b", _gpt_sizes(), 16, 4, 10, 5, "student_t3", (1e-5, 1e-2), bf16=True),
+}
+
+
+def get(name: str) -> Workload:
+    return _WORKLOADS[name]
+
+
+def names() -> List[str]:
+    return list(_WORKLOADS)
+
+
+def mini(name: str, max_layer: int = 40000, max_layers: int = 12) -> Workload:
+    """A shrunken copy of a workload for element-by-element checks: the same distribution and node count,
+    the first ``max_layers`` tensors, each clipped to ``max_layer`` elements and made ragged (sizes that are
+    not multiples of 4 or 256 are kept or produced on purpose)."""
+    w = _WORKLOADS[name]
+    sizes = []
+    for i, s in enumerate(w.sizes[:max_layers]):
+        s = min(s, max_layer + 37 * i + (i % 4))
+        sizes.append(int(s))
+    return dataclasses.replace(w, name=w.name + "-mini", sizes=tuple(sizes))
+
+
+def layer_scales(w: Workload) -> np.ndarray:
+    """sigma_l per tensor: fixed for a workload (same across nodes and rounds)."""
+    if w.scale_range is None:
+        return np.ones(len(w.sizes), dtype=np.float64)
+    rng = np.random.default_rng(np.random.SeedSequence([w.seed, 0xA11CE]))
+    lo, hi = np.log(w.scale_range[0]), np.log(w.scale_range[1])
+    return np.exp(rng.uniform(lo, hi, size=len(w.sizes)))
+
+
+def _bf16_round(x: np.ndarray) -> np.ndarray:
+    u = x.astype(np.float32).view(np.uint32).astype(np.uint64)
+    r = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16) << 16
+    return r.astype(np.uint32).view(np.float32)
+
+
+def layer_numpy(w: Workload, node: int, layer: int, round_: int = 1, n: Optional[int] = None) -> np.ndarray:
+    """fp32 contents of (node, layer) at ``round_``; independent draws per node, layer and round."""
+    n = w.sizes[layer] if n is None else n
+    rng = np.random.default_rng(np.random.SeedSequence([w.seed, round_, node, layer]))
+    if w.dist == "normal":
+        x = rng.standard_normal(n)
+    elif w.dist == "student_t3":
+        z = rng.standard_normal((4, n))
+        x = z[0] / np.sqrt((z[1] ** 2 + z[2] ** 2 + z[3] ** 2) / 3.0)
+    else:
+        raise ValueError(w.dist)
+    x = (x * layer_scales(w)[layer]).astype(np.float32)
+    return _bf16_round(x) if w.bf16 else x
+
+
+def node_numpy(w: Workload, node: int, round_: int = 1) -> List[np.ndarray]:
+    return [layer_numpy(w, node, l, round_) for l in range(len(w.sizes))]
+
+
+def padded_offsets(sizes, align: int = 64) -> Tuple[np.ndarray, int]:
+    """Element offsets of the layers inside one flat buffer, each layer starting on an ``align``-element
+    boundary (256 bytes for fp32), and the buffer length."""
+    off = np.zeros(len(sizes), dtype=np.int64)
+    cur = 0
+    for i, s in enumerate(sizes):
+        off[i] = cur
+        cur += (int(s) + align - 1) // align * align
+    return off, max(cur, align)
+
+
+def node_torch(w: Workload, node: int, round_: int, device, out=None):
+    """One node's layers generated on ``device`` with torch, inside one flat fp32 buffer (layers aligned to
+    256 bytes).  Returns (flat, offsets).  Values differ from ``layer_numpy`` (different generator): a check
+    that uses these copies them to the host instead of regenerating them."""
+    import torch
+
+    off, total = padded_offsets(w.sizes)
+    flat = torch.zeros(total, dtype=torch.float32, device=device) if out is None else out
+    gen = torch.Generator(device=device)
+    gen.manual_seed((w.seed * 1000003 + round_) * 1009 + node)
+    scales = layer_scales(w)
+    piece = 1 << 26
+    for l, s in enumerate(w.sizes):
+        for p0 in range(0, s, piece):
+            n = min(piece, s - p0)
+            if w.dist == "normal":
+                x = torch.randn(n, device=device, generator=gen)
+            else:
+                z = torch.randn((4, n), device=device, generator=gen)
+                x = z[0] / torch.sqrt((z[1] * z[1] + z[2] * z[2] + z[3] * z[3]) / 3.0)
+                del z
+            x = x * float(scales[l])
+            if w.bf16:
+                x = x.to(torch.bfloat16).to(torch.float32)
+            flat[off[l] + p0: off[l] + p0 + n] = x
+            del x
+    return flat, off
+
+
+def bilinear_game(seed: int = 0, n: int = 512):
+    """The stochastic bilinear saddle game min_x max_y x^T A y: A (n x n, entries N(0, 1/n)), start (x0, y0)."""
+    rng = np.random.default_rng(np.random.SeedSequence([seed, 0xB111]))
+    A = (rng.standard_normal((n, n)) / np.sqrt(n)).astype(np.float32)
+    x0 = rng.standard_normal(n).astype(np.float32)
+    y0 = rng.standard_normal(n).astype(np.float32)
+    return A, x0, y0
+
+
+def bilinear_operator(A: np.ndarray, x: np.ndarray, y: np.ndarray, node: int, round_: int, seed: int = 0,
+                      sigma: float = 0.1):
+    """Node ``node``'s stochastic dual vector at (x, y): (A y, -A^T x) + N(0, sigma^2), computed in fp64 and
+    rounded to fp32.  This is the user's operator, outside the library and the checker."""
+    rng = np.random.default_rng(np.random.SeedSequence([seed, 0x0153, round_, node]))
+    gx = A.astype(np.float64) @ y.astype(np.float64) + sigma * rng.standard_normal(x.size)
+    gy = -(A.astype(np.float64).T @ x.astype(np.float64)) + sigma * rng.standard_normal(y.size)
+    return gx.astype(np.float32), gy.astype(np.float32)

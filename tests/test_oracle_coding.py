@@ -1,0 +1,132 @@
+"""Pins for the oracle's fixed-width ENCODE / DECODE (Sec. 3.2, App. C.1) and the K-way mean (Alg. 1 l.15-17).
+The bit layout is this build's own (the paper gives none), so its pin is the round trip plus byte accounting;
+DECODE is pinned to the definition +-||v|| * l_h and the mean to the textbook mean."""
+import numpy as np
+import pytest
+
+from paper_2505_14371_amd import workloads
+
+
+def uniform_levels(S):
+    return (np.arange(S, dtype=np.float64) / (S - 1)).astype(np.float32)
+
+
+@pytest.mark.parametrize("S", [2, 3, 4, 5, 8, 16, 17, 32, 200, 256])
+@pytest.mark.parametrize("d", [1, 5, 255, 256, 257, 1000, 16384 + 3])
+def test_pack_unpack_round_trip(oracle, S, d):
+    rng = np.random.default_rng(S * 100003 + d)
+    sign = rng.integers(0, 2, d).astype(np.uint8)
+    idx = rng.integers(0, S, d).astype(np.uint8)
+    region = oracle.pack_layer(sign, idx, S)
+    b = max(1, int(np.ceil(np.log2(S))))
+    assert oracle.index_bits(S) == b
+    assert region.size == ((d + 255) // 256) * 32 * (1 + b)          # (1 + b) bits per padded coordinate
+    s2, i2 = oracle.unpack_layer(region, d, S)
+    assert np.array_equal(s2, sign) and np.array_equal(i2, idx)
+    # population count of every plane equals the number of set bits it has to carry: nothing is lost or doubled
+    words = region.view(np.uint64).reshape(-1, 1 + b, 4)
+    assert int(np.unpackbits(words[:, 0].copy().view(np.uint8)).sum()) == int(sign.sum())
+    for p in range(b):
+        assert int(np.unpackbits(words[:, 1 + p].copy().view(np.uint8)).sum()) == int(((idx >> p) & 1).sum())
+
+
+def test_bit_position_of_a_single_coordinate(oracle):
+    # coordinate e sits in block e/256, word (plane*4 + e%4), bit (e%256)/4: the ballot of component e%4
+    S, d = 8, 1000
+    for e in [0, 1, 5, 255, 256, 700, 999]:
+        sign = np.zeros(d, np.uint8)
+        idx = np.zeros(d, np.uint8)
+        sign[e] = 1
+        idx[e] = 5                                                      # bits 0 and 2
+        words = oracle.pack_layer(sign, idx, S).view(np.uint64).reshape(-1, 4, 4)
+        want = np.zeros_like(words)
+        for plane in (0, 1, 3):
+            want[e // 256, plane, e % 4] = np.uint64(1) << np.uint64((e % 256) // 4)
+        assert np.array_equal(words, want)
+
+
+def test_message_layout_and_size(oracle):
+    sizes = [1000, 0, 256, 70000, 3]
+    points = [8, 4, 16, 4, 256]
+    hdr, off = oracle.layout(sizes, points)
+    assert hdr.tolist() == [0, 36, 56, 124, 144]                      # 4 * (1 + S) bytes per layer, in order
+    hb = oracle.header_bytes(sizes, points)
+    assert hb == 1280 and hb % 256 == 0                                # 144 + 4*257 = 1172 -> 1280
+    planes = [4, 3, 5, 3, 9]
+    nblk = [4, 0, 1, 274, 1]
+    want = hb
+    for l in range(5):
+        assert off[l] == want
+        want += nblk[l] * 32 * planes[l]
+    assert oracle.message_bytes(sizes, points) == (want + 255) // 256 * 256
+
+
+def test_message_is_header_plus_packed_codes_and_decodes_to_norm_times_level(oracle):
+    w = workloads.mini("dcgan", max_layer=3000, max_layers=4)
+    K = 3
+    points = [16, 4, 8, 5]
+    levels = [uniform_levels(S) for S in points]
+    grads = [workloads.node_numpy(w, k, 1) for k in range(K)]
+    hdr, off = oracle.layout(w.sizes, points)
+    msgs = []
+    for k in range(K):
+        msg, ss, delta, st = oracle.quantize(w.sizes, points, levels, grads[k], 9, 2, k)
+        assert st == 0
+        want_delta = 0.0
+        for l, d in enumerate(w.sizes):
+            norm, inv = oracle.norm_and_inv(grads[k][l])
+            assert ss[l] == oracle.sumsq(grads[k][l])
+            head = msg[hdr[l]: hdr[l] + 4 * (1 + points[l])].view(np.float32)
+            assert head[0] == norm and np.array_equal(head[1:], levels[l])
+            sign, idx = oracle.quantize_range(grads[k][l], 0, d, inv, levels[l], 9, 2, k, l)
+            planes = 1 + oracle.index_bits(points[l])
+            region = msg[off[l]: off[l] + ((d + 255) // 256) * 32 * planes]
+            assert np.array_equal(region, oracle.pack_layer(sign, idx, points[l]))
+            q = oracle.decode(sign, idx, norm, levels[l])
+            assert np.array_equal(q, np.where(sign == 1, -1.0, 1.0).astype(np.float32) * (norm * levels[l][idx]))
+            want_delta += float(np.sum(q.astype(np.float64) ** 2))
+        assert delta == pytest.approx(want_delta, rel=1e-12)          # no previous message: delta = ||Vhat||^2
+        msgs.append(msg)
+    # K = 1: the aggregate is the decoded vector itself
+    one = oracle.dequant_aggregate(w.sizes, points, msgs[:1])
+    for l, d in enumerate(w.sizes):
+        norm, inv = oracle.norm_and_inv(grads[0][l])
+        sign, idx = oracle.quantize_range(grads[0][l], 0, d, inv, levels[l], 9, 2, 0, l)
+        assert np.array_equal(one[l], oracle.decode(sign, idx, norm, levels[l]))
+    # K = 3: the textbook mean of the decoded vectors
+    mean = oracle.dequant_aggregate(w.sizes, points, msgs)
+    for l, d in enumerate(w.sizes):
+        dec = []
+        for k in range(K):
+            norm, inv = oracle.norm_and_inv(grads[k][l])
+            sign, idx = oracle.quantize_range(grads[k][l], 0, d, inv, levels[l], 9, 2, k, l)
+            dec.append(oracle.decode(sign, idx, norm, levels[l]).astype(np.float64))
+        ref = np.mean(dec, axis=0)
+        assert np.allclose(mean[l], ref, rtol=1e-6, atol=1e-6 * np.abs(ref).max())
+
+
+def test_delta_is_the_squared_distance_to_the_previous_decoded_message(oracle):
+    w = workloads.mini("txl", max_layer=20000, max_layers=5)
+    points = [8] * len(w.sizes)
+    lev1 = [uniform_levels(8)] * len(w.sizes)
+    lev2 = [np.array([0, 0.01, 0.03, 0.07, 0.15, 0.3, 0.6, 1.0], np.float32)] * len(w.sizes)
+    g1 = workloads.node_numpy(w, 0, 1)
+    g2 = workloads.node_numpy(w, 0, 2)
+    m1, _, d1, _ = oracle.quantize(w.sizes, points, lev1, g1, 4, 1, 0)
+    m2, _, d2, _ = oracle.quantize(w.sizes, points, lev2, g2, 4, 2, 0, msg_prev=m1)
+    v1 = oracle.dequant_aggregate(w.sizes, points, [m1])
+    v2 = oracle.dequant_aggregate(w.sizes, points, [m2])      # each message carries its own levels
+    want = sum(float(np.sum((a.astype(np.float64) - b.astype(np.float64)) ** 2)) for a, b in zip(v2, v1))
+    assert d2 == pytest.approx(want, rel=1e-6)
+    assert d1 == pytest.approx(sum(float(np.sum(a.astype(np.float64) ** 2)) for a in v1), rel=1e-12)
+
+
+def test_nonfinite_input_raises_the_status_flag(oracle):
+    sizes, points = [300], [4]
+    g = np.ones(300, np.float32)
+    g[17] = np.inf
+    _, _, _, st = oracle.quantize(sizes, points, [uniform_levels(4)], [g], 1, 1, 0)
+    assert st == 1
+    g[17] = np.nan
+    _, _, _, st = oracle.quantize(sizes, points, [uniform_levels(4)], [g], 1, 1, 0)
+    assert st == 1
