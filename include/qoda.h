@@ -1,0 +1,143 @@
+/*
+ * qoda.h -- C ABI of the MI355X (gfx950) hot path of Quantized Optimistic Dual Averaging with layer-wise
+ * unbiased stochastic quantization (arXiv 2505.14371).
+ *
+ * One context describes one model: L layers (tensors) of d_l fp32 entries, M types of level sequences, K nodes.
+ * The K nodes are K sets of buffers on one GPU; "broadcast / receive" (Alg. 1 lines 13-14) is the caller handing
+ * the K message buffers back to the library.
+ *
+ * Conventions
+ *   - Pointers named *_dev are DEVICE pointers owned by the caller; arrays of such pointers are HOST arrays
+ *     (the library copies them).  Everything else is host memory.  Every fp32 layer pointer must be 16-byte
+ *     aligned; message buffers must be 256-byte aligned and hold qoda_message_bytes() bytes.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is enqueued on it; no call
+ *     waits for the device except qoda_get_levels, qoda_read_buffer and qoda_status, which say so.
+ *   - Every call returns QODA_OK (0) or a negative error code and then qoda_last_error() describes it.  Nothing
+ *     throws across this boundary.  Bad arguments are rejected before anything is launched.
+ *   - A context is not thread-safe: use it from one host thread at a time, on one stream at a time.
+ *   - Non-finite input (a layer whose sum of squares is not a finite number or whose norm exceeds FLT_MAX) sets
+ *     a sticky device-side flag reported by qoda_status(); that layer's output is then unspecified (but in
+ *     bounds).
+ *
+ * Level sequences (Sec. 3.1): type m has S_m grid points 0 = l_0 < l_1 < ... < l_{S_m-1} = 1, i.e. the paper's
+ * alpha_m = S_m - 2 interior levels.  A coordinate's code is one sign bit plus a ceil(log2 S_m)-bit level index.
+ *
+ * Message format (ENCODE / DECODE of Sec. 3.2 and App. C.1, fixed width, no entropy code):
+ *   header   for each layer, in order: fp32 norm (the paper's C_q = 32 bits), then its S fp32 level values
+ *            (so that a stored previous-round message stays decodable after the levels change); padded to 256 B;
+ *   body     for each layer, ceil(d_l/256) blocks of 256 coordinates, each block 4*(1+b) little-endian 64-bit
+ *            words; word p*4+j holds plane p (0 = sign, p >= 1 = bit p-1 of the level index) of the coordinates
+ *            256*B + 4*i + j, i = bit position 0..63.  Padding coordinates carry code 0.
+ */
+#ifndef QODA_H_
+#define QODA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define QODA_OK 0
+#define QODA_EINVAL (-1)    /* bad argument (null, misaligned, out of range, levels not increasing, ...) */
+#define QODA_ENOMEM (-2)    /* device or host allocation failed */
+#define QODA_EHIP (-3)      /* a HIP runtime call failed; see qoda_last_error() */
+#define QODA_ENONFINITE (-4) /* returned by qoda_status() when the device flag is set */
+
+#define QODA_MAX_POINTS 256 /* S_m <= 256: level index fits 8 bits */
+
+typedef struct qoda_ctx qoda_ctx;
+
+typedef struct {
+  int32_t num_layers;         /* L >= 1 */
+  const int64_t *layer_size;  /* d_l >= 0 elements, host array [L], copied; d_l < 2^31 * 8 */
+  const int32_t *layer_type;  /* m(l) in [0, M), host array [L], copied */
+  int32_t num_types;          /* M >= 1 */
+  const int32_t *type_points; /* S_m in [2, 256], host array [M], copied */
+  int32_t num_nodes;          /* K >= 1 */
+  int32_t norm_kind;          /* 2 = L2 (the only kind built) */
+  uint64_t seed;              /* key of the counter-based generator */
+} qoda_config;
+
+/* Create / destroy.  qoda_create allocates all device scratch (a few MB plus 8 bytes per 16384 coordinates per
+ * node; the fit's histogram, 8 KB per (node, layer), is allocated on the first qoda_fit_levels).  Levels start
+ * uniform: l_j = j/(S-1).  On failure *out is NULL. */
+int qoda_create(const qoda_config *cfg, qoda_ctx **out);
+int qoda_destroy(qoda_ctx *ctx);
+
+/* Packed bytes of one node's message (header + body, multiple of 256). */
+size_t qoda_message_bytes(const qoda_ctx *ctx);
+/* Byte offsets of each layer's header entry and body inside a message (host arrays [L], either may be NULL). */
+int qoda_message_layout(const qoda_ctx *ctx, int64_t *hdr_off, int64_t *body_off);
+
+/* Set / get the S_m levels of one type (Sec. 3.1).  set: levels_host[0] == 0, levels_host[S-1] == 1, strictly
+ * increasing, else QODA_EINVAL; enqueues the upload and the rebuild of the search tables.  get: waits for `stream`. */
+int qoda_set_levels(qoda_ctx *ctx, int32_t type, const float *levels_host, void *stream);
+int qoda_get_levels(qoda_ctx *ctx, int32_t type, float *levels_host, void *stream);
+
+/* Level fit, Alg. 1 lines 2-7 / eq. (Qada2) with the weights lambda_z: the K nodes' current vectors are the Z
+ * samples; every coordinate of (node, layer) weighs ||v_{k,l}||^2; layers of one type pool.  The distribution is
+ * estimated by a histogram on the top 11 magnitude bits of each entry and the objective is minimised exactly
+ * over level positions on a 257-point grid (3 mantissa bits per octave down to 2^-32).  A type whose vectors are
+ * all zero keeps its levels.  grad_dev: host array [K*L], entry k*L+l.
+ * Side effect: the per-(node, layer) norms of these vectors stay in the context tagged with `round`; a following
+ * qoda_quantize / qoda_quantize_all with the same `round` and the same pointers reuses them instead of reading
+ * the vectors a second time.  The caller must not change the vectors in between. */
+int qoda_fit_levels(qoda_ctx *ctx, const float *const *grad_dev, uint32_t round, void *stream);
+
+/* ENCODE(Q(V_{k,t+1/2})), Alg. 1 line 12 (Sec. 2.2, 3.1, 3.2): per-layer L2 norm, u = min(|v| / ||v||, 1), level
+ * search, stochastic rounding with one 16-bit counter-based draw per coordinate (counter = coordinate, layer,
+ * round, node), sign + index bit planes.  Also leaves delta_k = ||Vhat_{k,t+1/2} - Vhat_{k,t-1/2}||^2 in the
+ * context for the step size (eq. (general_stepsize)); msg_prev_dev == NULL means Vhat_{k,t-1/2} = 0 (round 1).
+ * grad_dev: host array [L] (node k's layers).  msg_dev / msg_prev_dev must not overlap. */
+int qoda_quantize(qoda_ctx *ctx, int32_t node, const float *const *grad_dev, uint32_t round, void *msg_dev,
+                  const void *msg_prev_dev, void *stream);
+/* The same for all K nodes in one set of launches.  grad_dev: host [K*L]; msg_dev: host [K];
+ * msg_prev_dev: host [K] or NULL (all previous messages zero). */
+int qoda_quantize_all(qoda_ctx *ctx, const float *const *grad_dev, uint32_t round, void *const *msg_dev,
+                      const void *const *msg_prev_dev, void *stream);
+
+/* DECODE + mean, Alg. 1 lines 15-17 without the update: mean_out[l][e] = (Vhat_0 + ... + Vhat_{K-1}) / K with
+ * Vhat_k = +-norm_k * l_h, summed in fp32 in increasing k.  msgs_dev: host [K]; mean_out_dev: host [L]. */
+int qoda_dequant_aggregate(qoda_ctx *ctx, const void *const *msgs_dev, float *const *mean_out_dev, void *stream);
+
+/* Solver state of Alg. 1 (all caller-owned device memory): X_1 (read only), Y_t (in/out, Y_1 = 0), the next
+ * query point X_{t+3/2} (out), optionally X_{t+1} (out), the step-size accumulator (in/out, starts at 0) and
+ * optionally the two step sizes (out: eta_{t+1}, gamma_{t+1}).  Pointer arrays are host arrays [L]. */
+typedef struct {
+  const float *const *x1_dev;
+  float *const *y_dev;
+  float *const *x_half_dev;
+  float *const *x_next_dev; /* may be NULL */
+  double *acc_dev;          /* device double: sum_{s<=t} sum_k delta_{k,s} / K^2 */
+  float *eta_dev;           /* device float[2] or NULL */
+} qoda_state;
+
+/* One fused pass, Alg. 1 lines 15-18 and line 10 of the next round (eq. (ODA), eq. (general_stepsize)):
+ *   acc += (sum_k delta_k) / K^2 with the delta_k left by the K preceding quantize calls;
+ *   eta_{t+1} = gamma_{t+1} = (1 + acc)^(-1/2);
+ *   mean = (1/K) sum_k DECODE(msgs[k]);  Y <- Y - mean;  X_{t+1} = X_1 + eta_{t+1} Y;
+ *   X_{t+3/2} = X_{t+1} - gamma_{t+1} mean.
+ * msgs_dev: host [K]. */
+int qoda_step(qoda_ctx *ctx, const void *const *msgs_dev, const qoda_state *state, void *stream);
+
+/* Read an internal device buffer into host memory (waits for `stream`); for tests and diagnostics. */
+#define QODA_BUF_SUMSQ 0  /* double[K*L]  canonical per-layer sums of squares of the last norm pass        */
+#define QODA_BUF_NORM 1   /* float [K*L]  norms                                                            */
+#define QODA_BUF_INV 2    /* float [K*L]  reciprocal norms                                                 */
+#define QODA_BUF_DELTA 3  /* double[K]    delta_k of the last quantize of each node                        */
+#define QODA_BUF_HIST 4   /* uint32[K*L*2048] histogram of the last fit                                    */
+#define QODA_BUF_POOLED 5 /* uint64[M*257] pooled grid weights of the last fit                             */
+int qoda_read_buffer(qoda_ctx *ctx, int32_t which, void *dst_host, size_t bytes, void *stream);
+
+/* Waits for `stream`; returns QODA_OK, or QODA_ENONFINITE if a non-finite layer was seen since the last call
+ * (the flag is cleared). */
+int qoda_status(qoda_ctx *ctx, void *stream);
+
+const char *qoda_last_error(const qoda_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QODA_H_ */

@@ -1,0 +1,532 @@
+// Host side of libqoda: context, argument checks, device tables, and the order in which the kernels of
+// qoda_kernels.hip are enqueued for each C-ABI call declared in include/qoda.h.
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/qoda.h"
+#include "qoda_kernels.h"
+
+using namespace qoda;
+
+struct qoda_ctx {
+  int L = 0, M = 0, K = 0, G = 0;
+  uint64_t seed = 0;
+  std::vector<LayerMeta> meta;
+  std::vector<int> type_points;
+  size_t message_bytes = 0, header_bytes = 0;
+  int maxS = 0;
+  // device memory owned by the context
+  LayerMeta *d_meta = nullptr;
+  int2 *d_tiles = nullptr;
+  int *d_type_points = nullptr;
+  double *d_partial = nullptr, *d_dpartial = nullptr, *d_sumsq = nullptr, *d_delta = nullptr;
+  float *d_norm = nullptr, *d_inv = nullptr, *d_lev = nullptr, *d_rgap = nullptr, *d_eta = nullptr;
+  unsigned char *d_lut = nullptr;
+  unsigned int *d_hist = nullptr, *d_status = nullptr;
+  unsigned long long *d_pooled = nullptr;
+  int *d_type_exp = nullptr;
+  short *d_dp_arg = nullptr;
+  long long *d_dp_arg_off = nullptr;
+  // device pointer tables (uploaded when their host shadow changes)
+  struct Table {
+    void **dev = nullptr;
+    std::vector<void *> host;
+    size_t n = 0;
+    bool valid = false;
+  };
+  Table t_grad, t_msg, t_prev, t_in, t_x1, t_y, t_xh, t_xn, t_mean;
+  hipEvent_t upload_done = nullptr;
+  bool upload_pending = false;
+  // norm cache left by qoda_fit_levels
+  bool norms_valid = false;
+  uint32_t norms_round = 0;
+  std::vector<const float *> norms_grad;
+  std::vector<float> h_lev;   // host shadow of the level tables (source of asynchronous uploads)
+  std::string err;
+};
+
+namespace {
+
+int fail(qoda_ctx *c, int code, const char *fmt, ...) {
+  if (c) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    c->err = buf;
+  }
+  return code;
+}
+
+#define HIP_TRY(c, call)                                                                        \
+  do {                                                                                          \
+    hipError_t e_ = (call);                                                                     \
+    if (e_ != hipSuccess)                                                                       \
+      return fail((c), e_ == hipErrorOutOfMemory ? QODA_ENOMEM : QODA_EHIP, "%s: %s", #call,    \
+                  hipGetErrorString(e_));                                                       \
+  } while (0)
+
+int index_bits(int S) {
+  int b = 1;
+  while ((1 << b) < S) ++b;
+  return b;
+}
+
+size_t round_up(size_t x, size_t m) { return (x + m - 1) / m * m; }
+
+template <class T>
+hipError_t dev_alloc(T **p, size_t n) {
+  return hipMalloc(reinterpret_cast<void **>(p), (n ? n : 1) * sizeof(T));
+}
+
+// Upload a table of device pointers if it differs from what the device copy holds.
+int sync_table(qoda_ctx *c, qoda_ctx::Table &t, const void *const *src, size_t n, hipStream_t s) {
+  if (t.valid && t.n == n && std::memcmp(t.host.data(), src, n * sizeof(void *)) == 0) return QODA_OK;
+  if (c->upload_pending) {   // the previous asynchronous upload may still be reading a host shadow
+    HIP_TRY(c, hipEventSynchronize(c->upload_done));
+    c->upload_pending = false;
+  }
+  t.host.resize(n);
+  std::memcpy(t.host.data(), src, n * sizeof(void *));
+  t.n = n;
+  HIP_TRY(c, hipMemcpyAsync(t.dev, t.host.data(), n * sizeof(void *), hipMemcpyHostToDevice, s));
+  HIP_TRY(c, hipEventRecord(c->upload_done, s));
+  c->upload_pending = true;
+  t.valid = true;
+  return QODA_OK;
+}
+
+Dev base_args(const qoda_ctx *c) {
+  Dev a;
+  std::memset(&a, 0, sizeof a);
+  a.meta = c->d_meta;
+  a.tiles = c->d_tiles;
+  a.L = c->L; a.G = c->G; a.K = c->K; a.M = c->M;
+  a.type_points = c->d_type_points;
+  a.partial = c->d_partial; a.dpartial = c->d_dpartial; a.sumsq = c->d_sumsq;
+  a.norm = c->d_norm; a.inv = c->d_inv; a.delta = c->d_delta;
+  a.lev = c->d_lev; a.rgap = c->d_rgap; a.lut = c->d_lut;
+  a.hist = c->d_hist; a.pooled = c->d_pooled; a.type_exp = c->d_type_exp;
+  a.dp_arg = c->d_dp_arg; a.dp_arg_off = c->d_dp_arg_off;
+  a.status = c->d_status; a.eta = c->d_eta;
+  a.seed = c->seed;
+  a.node0 = 0; a.nnodes = c->K;
+  a.invK = 1.0f / (float)c->K;
+  a.invK2 = 1.0 / ((double)c->K * (double)c->K);
+  return a;
+}
+
+int check_layer_ptrs(qoda_ctx *c, const void *const *p, size_t n, const char *what, bool allow_null_for_empty) {
+  if (!p) return fail(c, QODA_EINVAL, "%s: null pointer array", what);
+  for (size_t i = 0; i < n; ++i) {
+    const bool empty = c->meta[i % c->L].d == 0;
+    if (!p[i]) {
+      if (empty && allow_null_for_empty) continue;
+      return fail(c, QODA_EINVAL, "%s[%zu] is null", what, i);
+    }
+    if (reinterpret_cast<uintptr_t>(p[i]) % 16 != 0) return fail(c, QODA_EINVAL, "%s[%zu] is not 16-byte aligned", what, i);
+  }
+  return QODA_OK;
+}
+
+int check_msg_ptrs(qoda_ctx *c, const void *const *p, size_t n, const char *what, bool allow_null) {
+  if (!p) return fail(c, QODA_EINVAL, "%s: null pointer array", what);
+  for (size_t i = 0; i < n; ++i) {
+    if (!p[i]) {
+      if (allow_null) continue;
+      return fail(c, QODA_EINVAL, "%s[%zu] is null", what, i);
+    }
+    if (reinterpret_cast<uintptr_t>(p[i]) % 256 != 0) return fail(c, QODA_EINVAL, "%s[%zu] is not 256-byte aligned", what, i);
+  }
+  return QODA_OK;
+}
+
+void free_all(qoda_ctx *c) {
+  void *ptrs[] = {c->d_meta, c->d_tiles, c->d_type_points, c->d_partial, c->d_dpartial, c->d_sumsq, c->d_delta,
+                  c->d_norm, c->d_inv, c->d_lev, c->d_rgap, c->d_eta, c->d_lut, c->d_hist, c->d_status, c->d_pooled,
+                  c->d_type_exp, c->d_dp_arg, c->d_dp_arg_off, c->t_grad.dev, c->t_msg.dev, c->t_prev.dev, c->t_in.dev,
+                  c->t_x1.dev, c->t_y.dev, c->t_xh.dev, c->t_xn.dev, c->t_mean.dev};
+  for (void *p : ptrs)
+    if (p) (void)hipFree(p);
+  if (c->upload_done) (void)hipEventDestroy(c->upload_done);
+}
+
+// norms of nodes [node0, node0+n) from the gradient table already on the device
+int run_norm_pass(qoda_ctx *c, Dev a, bool with_hist, hipStream_t s) {
+  HIP_TRY(c, launch_sumsq(a, with_hist, s));
+  HIP_TRY(c, launch_norm_finalize(a, s));
+  return QODA_OK;
+}
+
+int quantize_impl(qoda_ctx *c, int node0, int nnodes, const float *const *grad_full /* K*L shadow */, uint32_t round,
+                  hipStream_t s, bool have_prev) {
+  Dev a = base_args(c);
+  a.grad = reinterpret_cast<const float *const *>(c->t_grad.dev);
+  a.msg = reinterpret_cast<unsigned char *const *>(c->t_msg.dev);
+  a.prev = have_prev ? reinterpret_cast<const unsigned char *const *>(c->t_prev.dev) : nullptr;
+  a.round = round;
+  a.node0 = node0;
+  a.nnodes = nnodes;
+  bool cached = c->norms_valid && c->norms_round == round;
+  if (cached)
+    for (int k = node0; k < node0 + nnodes && cached; ++k)
+      for (int l = 0; l < c->L; ++l)
+        if (c->norms_grad[(size_t)k * c->L + l] != grad_full[(size_t)k * c->L + l]) { cached = false; break; }
+  if (!cached) {
+    c->norms_valid = false;   // the cached norms of these nodes are about to be overwritten
+    int rc = run_norm_pass(c, a, false, s);
+    if (rc) return rc;
+  }
+  HIP_TRY(c, launch_write_header(a, s));
+  HIP_TRY(c, launch_quantize(a, s));
+  HIP_TRY(c, launch_delta_finalize(a, s));
+  return QODA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int qoda_create(const qoda_config *cfg, qoda_ctx **out) {
+  if (!out) return QODA_EINVAL;
+  *out = nullptr;
+  if (!cfg || !cfg->layer_size || !cfg->layer_type || !cfg->type_points) return QODA_EINVAL;
+  if (cfg->num_layers < 1 || cfg->num_types < 1 || cfg->num_nodes < 1 || cfg->num_nodes > 65535) return QODA_EINVAL;
+  if (cfg->norm_kind != 2) return QODA_EINVAL;
+  qoda_ctx *c = new (std::nothrow) qoda_ctx;
+  if (!c) return QODA_ENOMEM;
+  c->L = cfg->num_layers; c->M = cfg->num_types; c->K = cfg->num_nodes; c->seed = cfg->seed;
+  for (int m = 0; m < c->M; ++m) {
+    if (cfg->type_points[m] < 2 || cfg->type_points[m] > QODA_MAX_POINTS) { delete c; return QODA_EINVAL; }
+    c->type_points.push_back(cfg->type_points[m]);
+  }
+  size_t hdr = 0;
+  long long chunks = 0;
+  c->meta.resize(c->L);
+  for (int l = 0; l < c->L; ++l) {
+    const long long d = cfg->layer_size[l];
+    const int ty = cfg->layer_type[l];
+    if (d < 0 || d >= (1ll << 34) || ty < 0 || ty >= c->M) { delete c; return QODA_EINVAL; }
+    LayerMeta &m = c->meta[l];
+    m.d = d;
+    m.type = ty;
+    m.S = c->type_points[ty];
+    m.planes = 1 + index_bits(m.S);
+    m.nblk = (d + kBlockCoords - 1) / kBlockCoords;
+    m.hdr_off = (int)hdr;
+    hdr += 4 * (size_t)(1 + m.S);
+    m.first_chunk = (int)chunks;
+    m.nchunks = (int)((d + kChunkCoords - 1) / kChunkCoords);
+    chunks += m.nchunks;
+    if (m.S > c->maxS) c->maxS = m.S;
+    if (hdr > (1u << 30) || chunks > (1ll << 30)) { delete c; return QODA_EINVAL; }
+  }
+  if ((size_t)c->K * c->maxS * sizeof(float) > 64 * 1024) { delete c; return QODA_EINVAL; }   // decode tables must fit LDS
+  c->header_bytes = round_up(hdr, 256);
+  size_t off = c->header_bytes;
+  for (int l = 0; l < c->L; ++l) {
+    c->meta[l].body_off = (long long)off;
+    off += (size_t)c->meta[l].nblk * 32 * c->meta[l].planes;
+  }
+  c->message_bytes = round_up(off, 256);
+  c->G = (int)chunks;
+  c->h_lev.assign((size_t)c->M * kMaxPoints, 0.0f);
+
+  std::vector<int2> tiles((size_t)c->G);
+  for (int l = 0; l < c->L; ++l)
+    for (int ch = 0; ch < c->meta[l].nchunks; ++ch) tiles[(size_t)c->meta[l].first_chunk + ch] = make_int2(l, ch);
+  std::vector<long long> arg_off(c->M);
+  long long arg_total = 0;
+  for (int m = 0; m < c->M; ++m) { arg_off[m] = arg_total; arg_total += (long long)c->type_points[m] * kGridPoints; }
+
+  const size_t KL = (size_t)c->K * c->L, KG = (size_t)c->K * c->G;
+  hipError_t e = hipSuccess;
+  auto A = [&](hipError_t r) { if (e == hipSuccess) e = r; };
+  A(dev_alloc(&c->d_meta, (size_t)c->L));
+  A(dev_alloc(&c->d_tiles, (size_t)c->G));
+  A(dev_alloc(&c->d_type_points, (size_t)c->M));
+  A(dev_alloc(&c->d_partial, KG));
+  A(dev_alloc(&c->d_dpartial, KG));
+  A(dev_alloc(&c->d_sumsq, KL));
+  A(dev_alloc(&c->d_delta, (size_t)c->K));
+  A(dev_alloc(&c->d_norm, KL));
+  A(dev_alloc(&c->d_inv, KL));
+  A(dev_alloc(&c->d_lev, (size_t)c->M * kMaxPoints));
+  A(dev_alloc(&c->d_rgap, (size_t)c->M * kMaxPoints));
+  A(dev_alloc(&c->d_eta, 2));
+  A(dev_alloc(&c->d_lut, (size_t)c->M * kLutSize));
+  A(dev_alloc(&c->d_status, 1));
+  A(dev_alloc(&c->d_pooled, (size_t)c->M * kGridPoints));
+  A(dev_alloc(&c->d_type_exp, (size_t)c->M));
+  A(dev_alloc(&c->d_dp_arg, (size_t)arg_total));
+  A(dev_alloc(&c->d_dp_arg_off, (size_t)c->M));
+  qoda_ctx::Table *tabs[] = {&c->t_grad, &c->t_msg, &c->t_prev, &c->t_in, &c->t_x1, &c->t_y, &c->t_xh, &c->t_xn, &c->t_mean};
+  const size_t tab_n[] = {KL, (size_t)c->K, (size_t)c->K, (size_t)c->K, (size_t)c->L, (size_t)c->L, (size_t)c->L, (size_t)c->L, (size_t)c->L};
+  for (int i = 0; i < 9; ++i) A(dev_alloc(&tabs[i]->dev, tab_n[i]));
+  A(hipEventCreateWithFlags(&c->upload_done, hipEventDisableTiming));
+  if (e == hipSuccess) A(hipMemcpy(c->d_meta, c->meta.data(), c->L * sizeof(LayerMeta), hipMemcpyHostToDevice));
+  if (e == hipSuccess && c->G) A(hipMemcpy(c->d_tiles, tiles.data(), c->G * sizeof(int2), hipMemcpyHostToDevice));
+  if (e == hipSuccess) A(hipMemcpy(c->d_type_points, c->type_points.data(), c->M * sizeof(int), hipMemcpyHostToDevice));
+  if (e == hipSuccess) A(hipMemcpy(c->d_dp_arg_off, arg_off.data(), c->M * sizeof(long long), hipMemcpyHostToDevice));
+  if (e == hipSuccess) A(hipMemset(c->d_status, 0, sizeof(unsigned int)));
+  if (e == hipSuccess) A(hipMemset(c->d_delta, 0, c->K * sizeof(double)));
+  if (e == hipSuccess) A(hipMemset(c->d_pooled, 0, (size_t)c->M * kGridPoints * sizeof(unsigned long long)));
+  if (e == hipSuccess) {
+    const float one[2] = {1.0f, 1.0f};
+    A(hipMemcpy(c->d_eta, one, sizeof one, hipMemcpyHostToDevice));
+  }
+  if (e != hipSuccess) {
+    free_all(c);
+    delete c;
+    return e == hipErrorOutOfMemory ? QODA_ENOMEM : QODA_EHIP;
+  }
+  // uniform initial levels l_j = j / (S - 1)
+  for (int m = 0; m < c->M; ++m) {
+    const int S = c->type_points[m];
+    std::vector<float> lev(S);
+    for (int j = 0; j < S; ++j) lev[j] = (float)((double)j / (double)(S - 1));
+    lev[S - 1] = 1.0f;
+    int rc = qoda_set_levels(c, m, lev.data(), nullptr);
+    if (rc != QODA_OK) { free_all(c); delete c; return rc; }
+  }
+  if (hipDeviceSynchronize() != hipSuccess) { free_all(c); delete c; return QODA_EHIP; }
+  *out = c;
+  return QODA_OK;
+}
+
+int qoda_destroy(qoda_ctx *c) {
+  if (!c) return QODA_EINVAL;
+  (void)hipDeviceSynchronize();
+  free_all(c);
+  delete c;
+  return QODA_OK;
+}
+
+size_t qoda_message_bytes(const qoda_ctx *c) { return c ? c->message_bytes : 0; }
+
+int qoda_message_layout(const qoda_ctx *c, int64_t *hdr_off, int64_t *body_off) {
+  if (!c) return QODA_EINVAL;
+  for (int l = 0; l < c->L; ++l) {
+    if (hdr_off) hdr_off[l] = c->meta[l].hdr_off;
+    if (body_off) body_off[l] = c->meta[l].body_off;
+  }
+  return QODA_OK;
+}
+
+int qoda_set_levels(qoda_ctx *c, int32_t type, const float *lev, void *stream) {
+  if (!c) return QODA_EINVAL;
+  if (type < 0 || type >= c->M || !lev) return fail(c, QODA_EINVAL, "qoda_set_levels: bad type or null levels");
+  const int S = c->type_points[type];
+  if (lev[0] != 0.0f || lev[S - 1] != 1.0f) return fail(c, QODA_EINVAL, "qoda_set_levels: levels must start at 0 and end at 1");
+  for (int j = 0; j + 1 < S; ++j)
+    if (!(lev[j] < lev[j + 1])) return fail(c, QODA_EINVAL, "qoda_set_levels: levels must be strictly increasing");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (c->upload_pending) {   // an earlier asynchronous upload may still be reading a host shadow
+    HIP_TRY(c, hipEventSynchronize(c->upload_done));
+    c->upload_pending = false;
+  }
+  float *shadow = c->h_lev.data() + (size_t)type * kMaxPoints;
+  std::memcpy(shadow, lev, S * sizeof(float));
+  HIP_TRY(c, hipMemcpyAsync(c->d_lev + (size_t)type * kMaxPoints, shadow, S * sizeof(float), hipMemcpyHostToDevice, s));
+  HIP_TRY(c, hipEventRecord(c->upload_done, s));
+  c->upload_pending = true;
+  Dev a = base_args(c);
+  HIP_TRY(c, launch_build_tables(a, type, s));
+  return QODA_OK;
+}
+
+int qoda_get_levels(qoda_ctx *c, int32_t type, float *lev, void *stream) {
+  if (!c) return QODA_EINVAL;
+  if (type < 0 || type >= c->M || !lev) return fail(c, QODA_EINVAL, "qoda_get_levels: bad type or null output");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  HIP_TRY(c, hipMemcpyAsync(lev, c->d_lev + (size_t)type * kMaxPoints, c->type_points[type] * sizeof(float),
+                            hipMemcpyDeviceToHost, s));
+  HIP_TRY(c, hipStreamSynchronize(s));
+  return QODA_OK;
+}
+
+int qoda_fit_levels(qoda_ctx *c, const float *const *grad_dev, uint32_t round, void *stream) {
+  if (!c) return QODA_EINVAL;
+  const size_t KL = (size_t)c->K * c->L;
+  int rc = check_layer_ptrs(c, reinterpret_cast<const void *const *>(grad_dev), KL, "qoda_fit_levels: grad_dev", true);
+  if (rc) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (!c->d_hist) HIP_TRY(c, dev_alloc(&c->d_hist, KL * kHistBins));
+  rc = sync_table(c, c->t_grad, reinterpret_cast<const void *const *>(grad_dev), KL, s);
+  if (rc) return rc;
+  c->norms_valid = false;
+  Dev a = base_args(c);
+  a.grad = reinterpret_cast<const float *const *>(c->t_grad.dev);
+  a.round = round;
+  HIP_TRY(c, launch_zero_u32(c->d_hist, KL * kHistBins, s));
+  HIP_TRY(c, launch_zero_u32(reinterpret_cast<unsigned int *>(c->d_pooled), (size_t)c->M * kGridPoints * 2, s));
+  rc = run_norm_pass(c, a, true, s);
+  if (rc) return rc;
+  HIP_TRY(c, launch_fit(a, s));
+  c->norms_grad.assign(grad_dev, grad_dev + KL);
+  c->norms_round = round;
+  c->norms_valid = true;
+  return QODA_OK;
+}
+
+int qoda_quantize_all(qoda_ctx *c, const float *const *grad_dev, uint32_t round, void *const *msg_dev,
+                      const void *const *msg_prev_dev, void *stream) {
+  if (!c) return QODA_EINVAL;
+  const size_t KL = (size_t)c->K * c->L;
+  int rc = check_layer_ptrs(c, reinterpret_cast<const void *const *>(grad_dev), KL, "qoda_quantize_all: grad_dev", true);
+  if (rc) return rc;
+  rc = check_msg_ptrs(c, reinterpret_cast<const void *const *>(msg_dev), c->K, "qoda_quantize_all: msg_dev", false);
+  if (rc) return rc;
+  if (msg_prev_dev) {
+    rc = check_msg_ptrs(c, msg_prev_dev, c->K, "qoda_quantize_all: msg_prev_dev", true);
+    if (rc) return rc;
+    for (int k = 0; k < c->K; ++k)
+      if (msg_prev_dev[k] == msg_dev[k]) return fail(c, QODA_EINVAL, "qoda_quantize_all: msg_prev_dev[%d] aliases msg_dev", k);
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  rc = sync_table(c, c->t_grad, reinterpret_cast<const void *const *>(grad_dev), KL, s);
+  if (rc) return rc;
+  rc = sync_table(c, c->t_msg, reinterpret_cast<const void *const *>(msg_dev), c->K, s);
+  if (rc) return rc;
+  if (msg_prev_dev) {
+    rc = sync_table(c, c->t_prev, msg_prev_dev, c->K, s);
+    if (rc) return rc;
+  }
+  return quantize_impl(c, 0, c->K, grad_dev, round, s, msg_prev_dev != nullptr);
+}
+
+int qoda_quantize(qoda_ctx *c, int32_t node, const float *const *grad_dev, uint32_t round, void *msg_dev,
+                  const void *msg_prev_dev, void *stream) {
+  if (!c) return QODA_EINVAL;
+  if (node < 0 || node >= c->K) return fail(c, QODA_EINVAL, "qoda_quantize: node %d out of range", node);
+  int rc = check_layer_ptrs(c, reinterpret_cast<const void *const *>(grad_dev), c->L, "qoda_quantize: grad_dev", true);
+  if (rc) return rc;
+  const void *mp[1] = {msg_dev};
+  rc = check_msg_ptrs(c, mp, 1, "qoda_quantize: msg_dev", false);
+  if (rc) return rc;
+  const void *pp[1] = {msg_prev_dev};
+  rc = check_msg_ptrs(c, pp, 1, "qoda_quantize: msg_prev_dev", true);
+  if (rc) return rc;
+  if (msg_prev_dev == msg_dev) return fail(c, QODA_EINVAL, "qoda_quantize: msg_prev_dev aliases msg_dev");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  // splice this node's pointers into full-size shadows of the K*L / K tables
+  const size_t KL = (size_t)c->K * c->L;
+  std::vector<void *> g(c->t_grad.valid ? c->t_grad.host : std::vector<void *>(KL, nullptr));
+  g.resize(KL, nullptr);
+  for (int l = 0; l < c->L; ++l) g[(size_t)node * c->L + l] = const_cast<float *>(grad_dev[l]);
+  std::vector<void *> m(c->t_msg.valid ? c->t_msg.host : std::vector<void *>(c->K, nullptr));
+  m.resize(c->K, nullptr);
+  m[node] = msg_dev;
+  std::vector<void *> p(c->t_prev.valid ? c->t_prev.host : std::vector<void *>(c->K, nullptr));
+  p.resize(c->K, nullptr);
+  p[node] = const_cast<void *>(msg_prev_dev);
+  rc = sync_table(c, c->t_grad, g.data(), KL, s);
+  if (rc) return rc;
+  rc = sync_table(c, c->t_msg, m.data(), c->K, s);
+  if (rc) return rc;
+  rc = sync_table(c, c->t_prev, p.data(), c->K, s);
+  if (rc) return rc;
+  return quantize_impl(c, node, 1, reinterpret_cast<const float *const *>(c->t_grad.host.data()), round, s, true);
+}
+
+static int decode_common(qoda_ctx *c, const void *const *msgs_dev, Dev &a, hipStream_t s, const char *who) {
+  int rc = check_msg_ptrs(c, msgs_dev, c->K, who, false);
+  if (rc) return rc;
+  rc = sync_table(c, c->t_in, msgs_dev, c->K, s);
+  if (rc) return rc;
+  a.msgs_in = reinterpret_cast<const unsigned char *const *>(c->t_in.dev);
+  return QODA_OK;
+}
+
+int qoda_dequant_aggregate(qoda_ctx *c, const void *const *msgs_dev, float *const *mean_out_dev, void *stream) {
+  if (!c) return QODA_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  Dev a = base_args(c);
+  int rc = decode_common(c, msgs_dev, a, s, "qoda_dequant_aggregate: msgs_dev");
+  if (rc) return rc;
+  rc = check_layer_ptrs(c, reinterpret_cast<const void *const *>(mean_out_dev), c->L, "qoda_dequant_aggregate: mean_out_dev", true);
+  if (rc) return rc;
+  rc = sync_table(c, c->t_mean, reinterpret_cast<const void *const *>(mean_out_dev), c->L, s);
+  if (rc) return rc;
+  a.mean_out = reinterpret_cast<float *const *>(c->t_mean.dev);
+  HIP_TRY(c, launch_decode(a, false, (size_t)c->K * c->maxS * sizeof(float), s));
+  return QODA_OK;
+}
+
+int qoda_step(qoda_ctx *c, const void *const *msgs_dev, const qoda_state *st, void *stream) {
+  if (!c) return QODA_EINVAL;
+  if (!st || !st->acc_dev) return fail(c, QODA_EINVAL, "qoda_step: null state or accumulator");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  Dev a = base_args(c);
+  int rc = decode_common(c, msgs_dev, a, s, "qoda_step: msgs_dev");
+  if (rc) return rc;
+  const struct { const void *const *p; qoda_ctx::Table *t; const char *name; bool optional; } tabs[] = {
+      {reinterpret_cast<const void *const *>(st->x1_dev), &c->t_x1, "qoda_step: x1_dev", false},
+      {reinterpret_cast<const void *const *>(st->y_dev), &c->t_y, "qoda_step: y_dev", false},
+      {reinterpret_cast<const void *const *>(st->x_half_dev), &c->t_xh, "qoda_step: x_half_dev", false},
+      {reinterpret_cast<const void *const *>(st->x_next_dev), &c->t_xn, "qoda_step: x_next_dev", true}};
+  for (const auto &t : tabs) {
+    if (!t.p && t.optional) continue;
+    rc = check_layer_ptrs(c, t.p, c->L, t.name, true);
+    if (rc) return rc;
+    rc = sync_table(c, *t.t, t.p, c->L, s);
+    if (rc) return rc;
+  }
+  a.x1 = reinterpret_cast<const float *const *>(c->t_x1.dev);
+  a.y = reinterpret_cast<float *const *>(c->t_y.dev);
+  a.x_half = reinterpret_cast<float *const *>(c->t_xh.dev);
+  a.x_next = st->x_next_dev ? reinterpret_cast<float *const *>(c->t_xn.dev) : nullptr;
+  a.acc = st->acc_dev;
+  a.eta_out = st->eta_dev;
+  HIP_TRY(c, launch_step_scalars(a, s));
+  HIP_TRY(c, launch_decode(a, true, (size_t)c->K * c->maxS * sizeof(float), s));
+  return QODA_OK;
+}
+
+int qoda_read_buffer(qoda_ctx *c, int32_t which, void *dst, size_t bytes, void *stream) {
+  if (!c) return QODA_EINVAL;
+  if (!dst) return fail(c, QODA_EINVAL, "qoda_read_buffer: null destination");
+  const size_t KL = (size_t)c->K * c->L;
+  const void *src = nullptr;
+  size_t have = 0;
+  switch (which) {
+    case QODA_BUF_SUMSQ: src = c->d_sumsq; have = KL * sizeof(double); break;
+    case QODA_BUF_NORM: src = c->d_norm; have = KL * sizeof(float); break;
+    case QODA_BUF_INV: src = c->d_inv; have = KL * sizeof(float); break;
+    case QODA_BUF_DELTA: src = c->d_delta; have = c->K * sizeof(double); break;
+    case QODA_BUF_HIST: src = c->d_hist; have = c->d_hist ? KL * kHistBins * sizeof(unsigned int) : 0; break;
+    case QODA_BUF_POOLED: src = c->d_pooled; have = (size_t)c->M * kGridPoints * sizeof(unsigned long long); break;
+    default: return fail(c, QODA_EINVAL, "qoda_read_buffer: unknown buffer %d", which);
+  }
+  if (!src || bytes != have) return fail(c, QODA_EINVAL, "qoda_read_buffer: buffer %d holds %zu bytes, asked for %zu", which, have, bytes);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  HIP_TRY(c, hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToHost, s));
+  HIP_TRY(c, hipStreamSynchronize(s));
+  return QODA_OK;
+}
+
+int qoda_status(qoda_ctx *c, void *stream) {
+  if (!c) return QODA_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  unsigned int flag = 0;
+  HIP_TRY(c, hipMemcpyAsync(&flag, c->d_status, sizeof flag, hipMemcpyDeviceToHost, s));
+  HIP_TRY(c, hipStreamSynchronize(s));
+  if (flag) {
+    HIP_TRY(c, launch_zero_u32(c->d_status, 1, s));
+    return fail(c, QODA_ENONFINITE, "a layer's sum of squares was not a finite number");
+  }
+  return QODA_OK;
+}
+
+const char *qoda_last_error(const qoda_ctx *c) { return c ? c->err.c_str() : "null context"; }
+
+}  // extern "C"

@@ -1,0 +1,85 @@
+// Device-side data layout and launch entry points shared by the kernels and the host API of libqoda.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace qoda {
+
+constexpr int kBlockCoords = 256;    // coordinates per packed block (one wave64 step of 128-bit loads)
+constexpr int kChunkCoords = 16384;  // coordinates per workgroup tile (64 blocks) = one reduction chunk
+constexpr int kThreads = 256;        // workgroup size everywhere: 4 waves, 256 reduction slots
+constexpr int kHistBins = 2048;      // top 11 magnitude bits of an fp32 value
+constexpr int kGridBase = 760;       // (127 - 32) << 3
+constexpr int kGridPoints = 257;     // normalised grid g_0 = 2^-32 ... g_256 = 1
+constexpr int kMaxPoints = 256;
+constexpr int kLutSize = 1024;       // level-search table indexed by bits(u) >> 20 (u in [0,1] -> 0..1016)
+constexpr int kTypeSkip = 0x7fffffff;
+
+struct LayerMeta {
+  long long d;         // elements
+  long long body_off;  // byte offset of the layer's blocks inside a message
+  long long nblk;      // ceil(d / 256)
+  int hdr_off;         // byte offset of {norm, levels[S]} inside a message
+  int S;               // grid points of the layer's type
+  int planes;          // 1 + ceil(log2 S)
+  int type;
+  int first_chunk;     // index of the layer's first tile in the per-node tile list
+  int nchunks;         // ceil(d / 16384)
+};
+
+// Everything a kernel needs; passed by value.
+struct Dev {
+  const LayerMeta *meta;
+  const int2 *tiles;  // per tile: (layer, chunk inside layer)
+  int L, G, K, M;
+  const int *type_points;          // [M]
+  const float *const *grad;        // [K*L] layer pointers
+  unsigned char *const *msg;       // [K]
+  const unsigned char *const *prev;  // [K] or nullptr
+  const unsigned char *const *msgs_in;  // [K] messages to decode
+  double *partial;    // [K*G] per-tile sums of squares
+  double *dpartial;   // [K*G] per-tile squared differences
+  double *sumsq;      // [K*L]
+  float *norm;        // [K*L]
+  float *inv;         // [K*L]
+  double *delta;      // [K]
+  float *lev;         // [M*256]
+  float *rgap;        // [M*256]
+  unsigned char *lut; // [M*1024]
+  unsigned int *hist;          // [K*L*2048]
+  unsigned long long *pooled;  // [M*257]
+  int *type_exp;               // [M]
+  short *dp_arg;               // DP back-pointers, type m at dp_arg_off[m]
+  const long long *dp_arg_off; // [M]
+  unsigned int *status;
+  float *eta;                  // [2] eta, gamma
+  // step / aggregate
+  const float *const *x1;
+  float *const *y;
+  float *const *x_half;
+  float *const *x_next;  // table pointer may be nullptr
+  float *const *mean_out;
+  double *acc;
+  float *eta_out;  // may be nullptr
+  unsigned long long seed;
+  unsigned int round;
+  int node0;    // first node handled by this launch
+  int nnodes;   // nodes handled by this launch (grid.y)
+  float invK;
+  double invK2;
+};
+
+// Launch wrappers (each checks nothing: the host API validates shapes before calling).
+hipError_t launch_zero_u32(unsigned int *p, size_t n, hipStream_t s);
+hipError_t launch_sumsq(const Dev &a, bool with_hist, hipStream_t s);
+hipError_t launch_norm_finalize(const Dev &a, hipStream_t s);
+hipError_t launch_write_header(const Dev &a, hipStream_t s);
+hipError_t launch_quantize(const Dev &a, hipStream_t s);
+hipError_t launch_delta_finalize(const Dev &a, hipStream_t s);
+hipError_t launch_step_scalars(const Dev &a, hipStream_t s);
+hipError_t launch_decode(const Dev &a, bool update, size_t lds_bytes, hipStream_t s);
+hipError_t launch_fit(const Dev &a, hipStream_t s);
+hipError_t launch_build_tables(const Dev &a, int type, hipStream_t s);
+
+}  // namespace qoda

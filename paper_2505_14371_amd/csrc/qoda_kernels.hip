@@ -1,0 +1,653 @@
+// gfx950 kernels of the QODA hot path (arXiv 2505.14371): per-layer norms, stochastic quantization + bit-plane
+// packing, fused decode + K-way mean + optimistic dual averaging update, and the histogram level fit.
+//
+// Execution shape used throughout: one workgroup = 256 threads = 4 wave64 = one tile of 16384 coordinates of
+// one (node, layer).  Wave w owns the 16 consecutive 256-coordinate blocks 16w..16w+15 of the tile; in a block,
+// lane i owns coordinates 4i..4i+3 (one 128-bit load, 1 KB contiguous per wave).  A wave-wide ballot of one
+// component j is therefore exactly one 64-bit word of the packed message, and thread t = 64w+i is reduction
+// slot t of the fixed-order fp64 sums.
+//
+// Arithmetic that feeds an integer decision (level index, rounding direction, packed bits, histogram bin) is
+// written as single IEEE operations with contraction off, so that it has one well-defined result.
+
+#include "qoda_kernels.h"
+
+namespace qoda {
+
+namespace {
+
+__device__ __forceinline__ unsigned int f2u(float f) { return __float_as_uint(f); }
+__device__ __forceinline__ float u2f(unsigned int u) { return __uint_as_float(u); }
+
+constexpr float kFltMax = 3.402823466e+38f;
+
+// largest float n >= 0 with n*n <= s (n*n is exact in fp64); 0 when s is not a finite number in range.
+__device__ float sqrt_floor(double s) {
+  const double lim = (double)kFltMax * (double)kFltMax;
+  if (!(s >= 0.0) || !(s <= lim)) return 0.0f;
+  const double r = sqrt(s);
+  float n = (r >= (double)kFltMax) ? kFltMax : (float)r;
+  for (int it = 0; it < 4 && (double)n * (double)n > s; ++it) n = u2f(f2u(n) - 1u);
+  for (int it = 0; it < 4; ++it) {
+    if (n == kFltMax) break;
+    const float up = u2f(f2u(n) + 1u);
+    if ((double)up * (double)up <= s) n = up; else break;
+  }
+  return n;
+}
+
+// largest finite float r >= 0 with x*r <= 1 (exact in fp64); 0 for x <= 0 or non-finite x.
+__device__ float rcp_floor(float x) {
+  if (!(x > 0.0f) || x > kFltMax) return 0.0f;
+  float r = 1.0f / x;
+  if (r > kFltMax) r = kFltMax;
+  for (int it = 0; it < 4 && (double)x * (double)r > 1.0; ++it) r = u2f(f2u(r) - 1u);
+  for (int it = 0; it < 4; ++it) {
+    if (r == kFltMax) break;
+    const float up = u2f(f2u(r) + 1u);
+    if ((double)x * (double)up <= 1.0) r = up; else break;
+  }
+  return r;
+}
+
+// Fixed halving tree over the 256 slots: p[i] += p[i+h], h = 128 .. 1.  Returns the total in every thread.
+__device__ double block_tree(double v, double *red) {
+  const int t = threadIdx.x;
+  red[t] = v;
+  __syncthreads();
+#pragma unroll
+  for (int h = kThreads / 2; h >= 1; h >>= 1) {
+    if (t < h) red[t] = red[t] + red[t + h];
+    __syncthreads();
+  }
+  const double total = red[0];
+  __syncthreads();
+  return total;
+}
+
+// Philox4x32-10 (Salmon et al., SC'11).
+__device__ __forceinline__ void philox4x32_10(unsigned int c0, unsigned int c1, unsigned int c2, unsigned int c3,
+                                               unsigned int k0, unsigned int k1, unsigned int out[4]) {
+  constexpr unsigned long long M0 = 0xD2511F53ull, M1 = 0xCD9E8D57ull;
+  constexpr unsigned int W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    if (r > 0) { k0 += W0; k1 += W1; }
+    const unsigned long long p0 = M0 * (unsigned long long)c0;
+    const unsigned long long p1 = M1 * (unsigned long long)c2;
+    const unsigned int n0 = (unsigned int)(p1 >> 32) ^ c1 ^ k0;
+    const unsigned int n1 = (unsigned int)p1;
+    const unsigned int n2 = (unsigned int)(p0 >> 32) ^ c3 ^ k1;
+    const unsigned int n3 = (unsigned int)p0;
+    c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// Four coordinates e..e+3 of a layer of d entries; entries past the end read as +0.
+__device__ __forceinline__ void load4(const float *__restrict__ v, long long e, long long d, float x[4]) {
+  if (e + 4 <= d) {
+    const float4 q = *reinterpret_cast<const float4 *>(v + e);
+    x[0] = q.x; x[1] = q.y; x[2] = q.z; x[3] = q.w;
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) x[j] = (e + j < d) ? v[e + j] : 0.0f;
+  }
+}
+
+__device__ __forceinline__ void store4(float *__restrict__ v, long long e, long long d, const float x[4]) {
+  if (e + 4 <= d) {
+    *reinterpret_cast<float4 *>(v + e) = make_float4(x[0], x[1], x[2], x[3]);
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (e + j < d) v[e + j] = x[j];
+  }
+}
+
+// Decode the four coordinates of lane `lane` from one packed block: sign ? -T[h] : T[h], h clamped to S-1.
+template <int PLANES>
+__device__ __forceinline__ void decode4(const unsigned long long *__restrict__ pw, int lane, const float *T, int S,
+                                        float out[4]) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const unsigned int sign = (unsigned int)(pw[j] >> lane) & 1u;
+    unsigned int h = 0;
+#pragma unroll
+    for (int p = 1; p < PLANES; ++p) h |= ((unsigned int)(pw[p * 4 + j] >> lane) & 1u) << (p - 1);
+    h = min(h, (unsigned int)(S - 1));
+    const float t = T[h];
+    out[j] = sign ? -t : t;
+  }
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------ zero fill
+__global__ void k_zero_u32(unsigned int *p, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) p[i] = 0u;
+}
+
+// ------------------------------------------------------------------------------------------------ pass 1
+// Sum of squares of one tile in fp64 (Sec. 2.2, L2 norm before the root), optionally with the histogram of the
+// top 11 magnitude bits (the distribution estimate of Alg. 1 line 4).
+template <bool HIST>
+__global__ void __launch_bounds__(kThreads) k_sumsq(Dev a) {
+  __shared__ double red[kThreads];
+  __shared__ unsigned int lh[HIST ? kHistBins : 1];
+  const int2 tile = a.tiles[blockIdx.x];
+  const int l = tile.x;
+  const int k = a.node0 + blockIdx.y;
+  const LayerMeta m = a.meta[l];
+  const float *__restrict__ v = a.grad[(size_t)k * a.L + l];
+  const int t = threadIdx.x;
+  const int w = t >> 6, i = t & 63;
+  if (HIST) {
+    for (int b = t; b < kHistBins; b += kThreads) lh[b] = 0u;
+    __syncthreads();
+  }
+  const long long base = (long long)tile.y * kChunkCoords + (long long)w * 16 * kBlockCoords + 4 * i;
+  double acc = 0.0;
+  if ((long long)(tile.y + 1) * kChunkCoords <= m.d) {
+    float4 q[16];
+#pragma unroll
+    for (int s = 0; s < 16; ++s) q[s] = *reinterpret_cast<const float4 *>(v + base + (long long)s * kBlockCoords);
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {
+      const float x[4] = {q[s].x, q[s].y, q[s].z, q[s].w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const double xd = (double)x[j];
+        acc = __builtin_fma(xd, xd, acc);   // the product is exact in fp64, so this equals acc + xd*xd
+        if (HIST) atomicAdd(&lh[(f2u(x[j]) & 0x7FFFFFFFu) >> 20], 1u);
+      }
+    }
+  } else {
+    for (int s = 0; s < 16; ++s) {
+      const long long e = base + (long long)s * kBlockCoords;
+      if (e >= m.d) break;
+      float x[4];
+      load4(v, e, m.d, x);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const double xd = (double)x[j];
+        acc = __builtin_fma(xd, xd, acc);
+        if (HIST && e + j < m.d) atomicAdd(&lh[(f2u(x[j]) & 0x7FFFFFFFu) >> 20], 1u);
+      }
+    }
+  }
+  const double total = block_tree(acc, red);
+  if (t == 0) a.partial[(size_t)k * a.G + blockIdx.x] = total;
+  if (HIST) {
+    __syncthreads();
+    unsigned int *gh = a.hist + ((size_t)k * a.L + l) * kHistBins;
+    for (int b = t; b < kHistBins; b += kThreads) {
+      const unsigned int c = lh[b];
+      if (c) atomicAdd(&gh[b], c);
+    }
+  }
+}
+
+// Combine the tile sums of one (node, layer): slot j takes tiles j, j+256, ... in increasing order, then the
+// halving tree; then norm = sqrt_floor(sum), inv = rcp_floor(norm).
+__global__ void __launch_bounds__(kThreads) k_norm_finalize(Dev a) {
+  __shared__ double red[kThreads];
+  const int l = blockIdx.x;
+  const int k = a.node0 + blockIdx.y;
+  const LayerMeta m = a.meta[l];
+  const double *p = a.partial + (size_t)k * a.G + m.first_chunk;
+  double acc = 0.0;
+  for (int c = threadIdx.x; c < m.nchunks; c += kThreads) acc = acc + p[c];
+  const double s = block_tree(acc, red);
+  if (threadIdx.x == 0) {
+    const double lim = (double)kFltMax * (double)kFltMax;
+    const bool finite = (s >= 0.0) && (s <= lim);
+    const float n = finite ? sqrt_floor(s) : 0.0f;
+    const size_t idx = (size_t)k * a.L + l;
+    a.sumsq[idx] = s;
+    a.norm[idx] = n;
+    a.inv[idx] = rcp_floor(n);
+    if (!finite) atomicOr(a.status, 1u);
+  }
+}
+
+// Message header: {norm, levels[S]} per layer (Sec. 3.2: the norm in C_q = 32 bits; the levels ride along).
+__global__ void k_write_header(Dev a) {
+  const int l = blockIdx.x;
+  const int k = a.node0 + blockIdx.y;
+  const LayerMeta m = a.meta[l];
+  float *h = reinterpret_cast<float *>(a.msg[k] + m.hdr_off);
+  const float *lev = a.lev + (size_t)m.type * kMaxPoints;
+  for (int j = threadIdx.x; j <= m.S; j += blockDim.x) h[j] = (j == 0) ? a.norm[(size_t)k * a.L + l] : lev[j - 1];
+}
+
+// ------------------------------------------------------------------------------------------------ pass 2
+// Quantize + pack one tile (Sec. 3.1, Sec. 3.2) and accumulate the squared distance to the node's previous
+// decoded message (the step-size term of eq. (general_stepsize)).
+template <int PLANES>
+__device__ __forceinline__ void quantize_tile(const Dev &a, const LayerMeta &m, int l, int k, int chunk,
+                                              const unsigned char *lut, const float4 *tab, const float *tcur,
+                                              const float *tprev, double *red) {
+  const int t = threadIdx.x;
+  const int w = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int i = t & 63;
+  const float *__restrict__ v = a.grad[(size_t)k * a.L + l];
+  unsigned char *msg = a.msg[k] + m.body_off;
+  const unsigned char *prev = (a.prev != nullptr && a.prev[k] != nullptr) ? a.prev[k] + m.body_off : nullptr;
+  const float inv = a.inv[(size_t)k * a.L + l];
+  const int S = m.S;
+  const unsigned int k0 = (unsigned int)a.seed, k1 = (unsigned int)(a.seed >> 32);
+  double acc = 0.0;
+  for (int pair = 0; pair < 8; ++pair) {
+    const long long B0 = (long long)chunk * 64 + w * 16 + 2 * pair;   // block index inside the layer
+    if (B0 >= m.nblk) break;
+    unsigned int o[4];
+    philox4x32_10((unsigned int)((B0 >> 1) * 64 + i), (unsigned int)l, a.round, (unsigned int)k, k0, k1, o);
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const long long B = B0 + half;
+      if (B >= m.nblk) break;
+      const long long e = B * kBlockCoords + 4 * i;
+      float x[4];
+      load4(v, e, m.d, x);
+      float prevv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+      if (prev) decode4<PLANES>(reinterpret_cast<const unsigned long long *>(prev + B * 32 * PLANES), i, tprev, S, prevv);
+      unsigned long long mine = 0ull;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const unsigned int w16 = half ? (o[j] >> 16) : (o[j] & 0xFFFFu);
+        const unsigned int sign = f2u(x[j]) >> 31;
+        const float u = fminf(fabsf(x[j]) * inv, 1.0f);
+        int tau = lut[f2u(u) >> 20];
+        float4 lv = tab[tau];                              // {l_tau, 1/gap, l_tau+1, -}
+        while (tau < S - 2 && lv.z <= u) { ++tau; lv = tab[tau]; }
+        const float xi = (u - lv.x) * lv.y;
+        const bool up = ((float)w16 + 0.5f) < xi * 65536.0f;
+        const unsigned int h = (unsigned int)tau + (up ? 1u : 0u);
+        const float tc = tcur[h];
+        const float cur = sign ? -tc : tc;
+        const float diff = cur - prevv[j];
+        acc = __builtin_fma((double)diff, (double)diff, acc);
+        const unsigned long long sb = __ballot(sign != 0u);
+        if (i == j) mine = sb;
+#pragma unroll
+        for (int p = 1; p < PLANES; ++p) {
+          const unsigned long long pb = __ballot(((h >> (p - 1)) & 1u) != 0u);
+          if (i == p * 4 + j) mine = pb;
+        }
+      }
+      if (i < 4 * PLANES) reinterpret_cast<unsigned long long *>(msg + B * 32 * PLANES)[i] = mine;
+    }
+  }
+  const double total = block_tree(acc, red);
+  if (t == 0) a.dpartial[(size_t)k * a.G + blockIdx.x] = total;
+}
+
+__global__ void __launch_bounds__(kThreads) k_quantize(Dev a) {
+  __shared__ unsigned char lut[kLutSize];
+  __shared__ float4 tab[kMaxPoints];
+  __shared__ float tcur[kMaxPoints];
+  __shared__ float tprev[kMaxPoints];
+  __shared__ double red[kThreads];
+  const int2 tile = a.tiles[blockIdx.x];
+  const int l = tile.x;
+  const int k = a.node0 + blockIdx.y;
+  const LayerMeta m = a.meta[l];
+  const int t = threadIdx.x;
+  const float *lev = a.lev + (size_t)m.type * kMaxPoints;
+  const float *rg = a.rgap + (size_t)m.type * kMaxPoints;
+  reinterpret_cast<unsigned int *>(lut)[t] = reinterpret_cast<const unsigned int *>(a.lut + (size_t)m.type * kLutSize)[t];
+  const float norm = a.norm[(size_t)k * a.L + l];
+  const unsigned char *prevmsg = (a.prev != nullptr) ? a.prev[k] : nullptr;
+  if (t < m.S) {
+    const float lj = lev[t];
+    const float ln = (t + 1 < m.S) ? lev[t + 1] : 1.0f;
+    tab[t] = make_float4(lj, rg[t], ln, 0.0f);
+    tcur[t] = norm * lj;
+    if (prevmsg) {
+      const float *hp = reinterpret_cast<const float *>(prevmsg + m.hdr_off);
+      tprev[t] = hp[0] * hp[1 + t];
+    } else {
+      tprev[t] = 0.0f;
+    }
+  }
+  __syncthreads();
+  switch (m.planes) {
+    case 2: quantize_tile<2>(a, m, l, k, tile.y, lut, tab, tcur, tprev, red); break;
+    case 3: quantize_tile<3>(a, m, l, k, tile.y, lut, tab, tcur, tprev, red); break;
+    case 4: quantize_tile<4>(a, m, l, k, tile.y, lut, tab, tcur, tprev, red); break;
+    case 5: quantize_tile<5>(a, m, l, k, tile.y, lut, tab, tcur, tprev, red); break;
+    case 6: quantize_tile<6>(a, m, l, k, tile.y, lut, tab, tcur, tprev, red); break;
+    case 7: quantize_tile<7>(a, m, l, k, tile.y, lut, tab, tcur, tprev, red); break;
+    case 8: quantize_tile<8>(a, m, l, k, tile.y, lut, tab, tcur, tprev, red); break;
+    default: quantize_tile<9>(a, m, l, k, tile.y, lut, tab, tcur, tprev, red); break;
+  }
+}
+
+// delta_k: slot j takes the node's tiles j, j+256, ... (all layers, in order), then the halving tree.
+__global__ void __launch_bounds__(kThreads) k_delta_finalize(Dev a) {
+  __shared__ double red[kThreads];
+  const int k = a.node0 + blockIdx.x;
+  const double *p = a.dpartial + (size_t)k * a.G;
+  double acc = 0.0;
+  for (int g = threadIdx.x; g < a.G; g += kThreads) acc = acc + p[g];
+  const double s = block_tree(acc, red);
+  if (threadIdx.x == 0) a.delta[k] = s;
+}
+
+// ------------------------------------------------------------------------------------------------ step
+// eq. (general_stepsize): acc += (sum_k delta_k) / K^2 ; eta = gamma = (1 + acc)^(-1/2), taken as
+// rcp_floor(sqrt_floor(1 + acc)).
+__global__ void k_step_scalars(Dev a) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  double sum = a.delta[0];
+  for (int k = 1; k < a.K; ++k) sum = sum + a.delta[k];
+  const double acc = *a.acc + sum * a.invK2;
+  *a.acc = acc;
+  const float eta = rcp_floor(sqrt_floor(1.0 + acc));
+  a.eta[0] = eta;
+  a.eta[1] = eta;
+  if (a.eta_out) { a.eta_out[0] = eta; a.eta_out[1] = eta; }
+}
+
+// DECODE + K-way mean (+ eq. (ODA) update when UPDATE): one pass over Y, X_1 and the K messages.
+template <int PLANES, bool UPDATE>
+__device__ __forceinline__ void decode_tile(const Dev &a, const LayerMeta &m, int l, int chunk, const float *T) {
+  const int t = threadIdx.x;
+  const int w = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int i = t & 63;
+  const int S = m.S;
+  float eta = 0.0f, gamma = 0.0f;
+  if (UPDATE) { eta = a.eta[0]; gamma = a.eta[1]; }
+  for (int s = 0; s < 16; ++s) {
+    const long long B = (long long)chunk * 64 + w * 16 + s;
+    if (B >= m.nblk) break;
+    const long long e = B * kBlockCoords + 4 * i;
+    float sum[4];
+    for (int k = 0; k < a.K; ++k) {
+      const unsigned long long *pw =
+          reinterpret_cast<const unsigned long long *>(a.msgs_in[k] + m.body_off + B * 32 * PLANES);
+      float val[4];
+      decode4<PLANES>(pw, i, T + k * S, S, val);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) sum[j] = (k == 0) ? val[j] : sum[j] + val[j];
+    }
+    float mean[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) mean[j] = sum[j] * a.invK;
+    if (!UPDATE) {
+      store4(a.mean_out[l], e, m.d, mean);
+    } else {
+      float y[4], x1[4], xn[4], xh[4];
+      load4(a.y[l], e, m.d, y);
+      load4(a.x1[l], e, m.d, x1);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        y[j] = y[j] - mean[j];
+        const float ey = eta * y[j];
+        xn[j] = x1[j] + ey;
+        const float gm = gamma * mean[j];
+        xh[j] = xn[j] - gm;
+      }
+      store4(a.y[l], e, m.d, y);
+      store4(a.x_half[l], e, m.d, xh);
+      if (a.x_next) store4(a.x_next[l], e, m.d, xn);
+    }
+  }
+}
+
+template <bool UPDATE>
+__global__ void __launch_bounds__(kThreads) k_decode(Dev a) {
+  extern __shared__ float T[];   // [K][S]: norm_k * level_h of this layer, from the K message headers
+  const int2 tile = a.tiles[blockIdx.x];
+  const int l = tile.x;
+  const LayerMeta m = a.meta[l];
+  for (int idx = threadIdx.x; idx < a.K * m.S; idx += kThreads) {
+    const int k = idx / m.S, h = idx - k * m.S;
+    const float *hp = reinterpret_cast<const float *>(a.msgs_in[k] + m.hdr_off);
+    T[idx] = hp[0] * hp[1 + h];
+  }
+  __syncthreads();
+  switch (m.planes) {
+    case 2: decode_tile<2, UPDATE>(a, m, l, tile.y, T); break;
+    case 3: decode_tile<3, UPDATE>(a, m, l, tile.y, T); break;
+    case 4: decode_tile<4, UPDATE>(a, m, l, tile.y, T); break;
+    case 5: decode_tile<5, UPDATE>(a, m, l, tile.y, T); break;
+    case 6: decode_tile<6, UPDATE>(a, m, l, tile.y, T); break;
+    case 7: decode_tile<7, UPDATE>(a, m, l, tile.y, T); break;
+    case 8: decode_tile<8, UPDATE>(a, m, l, tile.y, T); break;
+    default: decode_tile<9, UPDATE>(a, m, l, tile.y, T); break;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------ level fit
+// Largest sum of squares of a type -> its binary exponent (fixed-point scale of the weights lambda_z).
+__global__ void __launch_bounds__(kThreads) k_fit_typemax(Dev a) {
+  __shared__ double red[kThreads];
+  __shared__ int bad[1];
+  const int mtype = blockIdx.x;
+  if (threadIdx.x == 0) bad[0] = 0;
+  __syncthreads();
+  const double lim = (double)kFltMax * (double)kFltMax;
+  double mx = 0.0;
+  for (int idx = threadIdx.x; idx < a.K * a.L; idx += kThreads) {
+    const int l = idx % a.L;
+    if (a.meta[l].type != mtype) continue;
+    const double s = a.sumsq[idx];
+    if (!(s >= 0.0) || !(s <= lim)) bad[0] = 1;
+    else if (s > mx) mx = s;
+  }
+  red[threadIdx.x] = mx;
+  __syncthreads();
+  for (int h = kThreads / 2; h >= 1; h >>= 1) {
+    if (threadIdx.x < h) red[threadIdx.x] = fmax(red[threadIdx.x], red[threadIdx.x + h]);
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const double smax = red[0];
+    int ex = kTypeSkip;
+    if (!bad[0] && smax > 0.0) ex = (int)((__double_as_longlong(smax) >> 52) & 0x7FF) - 1023;
+    a.type_exp[mtype] = ex;
+  }
+}
+
+// Re-bin one (node, layer) histogram onto the normalised grid with weight floor(sumsq * 2^(23 - exponent)).
+__global__ void __launch_bounds__(kThreads) k_fit_pool(Dev a) {
+  const int l = blockIdx.x, k = blockIdx.y;
+  const LayerMeta m = a.meta[l];
+  const int ex = a.type_exp[m.type];
+  if (ex == kTypeSkip) return;
+  const size_t idx = (size_t)k * a.L + l;
+  const unsigned long long wfix = (unsigned long long)floor(ldexp(a.sumsq[idx], 23 - ex));
+  const float inv = a.inv[idx];
+  if (wfix == 0ull || inv == 0.0f) return;
+  const unsigned int *cnt = a.hist + idx * kHistBins;
+  unsigned long long *W = a.pooled + (size_t)m.type * kGridPoints;
+  for (int b = threadIdx.x; b < kHistBins; b += kThreads) {
+    if (b == 0) continue;
+    const unsigned int c = cnt[b];
+    if (c == 0u) continue;
+    const float mid = u2f(((unsigned int)b << 20) | (1u << 19));
+    const float uc = fminf(mid * inv, 1.0f);
+    int j = (int)(f2u(uc) >> 20) - kGridBase;
+    j = max(0, min(j, kGridPoints - 1));
+    atomicAdd(&W[j], wfix * (unsigned long long)c);
+  }
+}
+
+__device__ __forceinline__ float grid_value(int j) { return u2f((unsigned int)(j + kGridBase) << 20); }
+
+// Search tables of one type from its levels (in shared memory): reciprocal gaps and the bin -> index table.
+__device__ void build_tables(const Dev &a, int mtype, int S, const float *slev) {
+  float *rg = a.rgap + (size_t)mtype * kMaxPoints;
+  unsigned char *lut = a.lut + (size_t)mtype * kLutSize;
+  for (int j = threadIdx.x; j < kMaxPoints; j += kThreads) rg[j] = (j < S - 1) ? rcp_floor(slev[j + 1] - slev[j]) : 0.0f;
+  for (int q = threadIdx.x; q < kLutSize; q += kThreads) {
+    const float edge = u2f((unsigned int)q << 20);
+    int tau = 0;
+    if (q > 1016) {
+      tau = S - 2;
+    } else {
+      for (int j = 1; j <= S - 2; ++j)
+        if (slev[j] <= edge) tau = j;
+    }
+    lut[q] = (unsigned char)tau;
+  }
+}
+
+__global__ void __launch_bounds__(kThreads) k_build_tables(Dev a, int mtype) {
+  __shared__ float slev[kMaxPoints];
+  const int S = a.type_points[mtype];
+  for (int j = threadIdx.x; j < S; j += kThreads) slev[j] = a.lev[(size_t)mtype * kMaxPoints + j];
+  __syncthreads();
+  build_tables(a, mtype, S, slev);
+}
+
+// Exact minimisation of eq. (Qada2) over interior levels on the grid by dynamic programming; one workgroup per type.
+__global__ void __launch_bounds__(kThreads) k_fit_dp(Dev a) {
+  __shared__ double P0[kGridPoints + 1], P1[kGridPoints + 1], P2[kGridPoints + 1];
+  __shared__ double D[2][kGridPoints];
+  __shared__ double gd[kGridPoints];
+  __shared__ float slev[kMaxPoints];
+  __shared__ int go[1];
+  const int mtype = blockIdx.x;
+  const int S = a.type_points[mtype];
+  const int t = threadIdx.x;
+  const unsigned long long *W = a.pooled + (size_t)mtype * kGridPoints;
+  const int last = kGridPoints - 1;
+  for (int j = t; j < kGridPoints; j += kThreads) gd[j] = (double)grid_value(j);
+  if (t == 0) {
+    P0[0] = 0.0; P1[0] = 0.0; P2[0] = 0.0;
+    for (int j = 0; j < kGridPoints; ++j) {
+      const double wj = (double)W[j];
+      const double mid = (j == last) ? 1.0 : (double)u2f(((unsigned int)(j + kGridBase) << 20) | (1u << 19));
+      const double wm = wj * mid;
+      P0[j + 1] = P0[j] + wj;
+      P1[j + 1] = P1[j] + wm;
+      P2[j + 1] = P2[j] + wm * mid;
+    }
+    go[0] = (a.type_exp[mtype] != kTypeSkip) ? 1 : 0;
+  }
+  __syncthreads();
+  if (!go[0]) return;
+  const double inf = __longlong_as_double(0x7FF0000000000000ll);
+  short *arg = a.dp_arg + a.dp_arg_off[mtype];
+  if (S > 2) {
+    for (int b = t; b < kGridPoints; b += kThreads)
+      D[1][b] = (b >= 1 && b <= last - (S - 2)) ? (gd[b] * P1[b] - P2[b]) : inf;
+    __syncthreads();
+    for (int s = 2; s <= S - 2; ++s) {
+      const double *Dp = D[(s - 1) & 1];
+      double *Dc = D[s & 1];
+      for (int b = t; b < kGridPoints; b += kThreads) {
+        double best = inf;
+        int besta = -1;
+        if (b >= s && b <= last - (S - 1 - s)) {
+          const double gb = gd[b], p0b = P0[b], p1b = P1[b], p2b = P2[b];
+          for (int aa = s - 1; aa <= b - 1; ++aa) {
+            const double ga = gd[aa];
+            const double cost = ((ga + gb) * (p1b - P1[aa]) - (p2b - P2[aa])) - (ga * gb) * (p0b - P0[aa]);
+            const double c = Dp[aa] + cost;
+            if (c < best) { best = c; besta = aa; }
+          }
+        }
+        Dc[b] = best;
+        arg[(size_t)s * kGridPoints + b] = (short)besta;
+      }
+      __syncthreads();
+    }
+  }
+  if (t == 0) {
+    slev[0] = 0.0f;
+    slev[S - 1] = 1.0f;
+    if (S > 2) {
+      const double *Dp = D[(S - 2) & 1];
+      const double gb = gd[last], p0b = P0[last], p1b = P1[last], p2b = P2[last];
+      double best = inf;
+      int besta = -1;
+      for (int aa = S - 2; aa <= last - 1; ++aa) {
+        const double ga = gd[aa];
+        const double cost = ((ga + gb) * (p1b - P1[aa]) - (p2b - P2[aa])) - (ga * gb) * (p0b - P0[aa]);
+        const double c = Dp[aa] + cost;
+        if (c < best) { best = c; besta = aa; }
+      }
+      int b = besta;
+      for (int s = S - 2; s >= 1; --s) {
+        b = max(1, min(b, last - 1));   // cannot trigger for finite costs; keeps a corrupted table in bounds
+        slev[s] = grid_value(b);
+        if (s >= 2) b = arg[(size_t)s * kGridPoints + b];
+      }
+    }
+    for (int j = 0; j < S; ++j) a.lev[(size_t)mtype * kMaxPoints + j] = slev[j];
+  }
+  __syncthreads();
+  build_tables(a, mtype, S, slev);
+}
+
+// ------------------------------------------------------------------------------------------------ launchers
+hipError_t launch_zero_u32(unsigned int *p, size_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  const unsigned int blocks = (unsigned int)((n + 1023) / 1024 < 65535 ? (n + 1023) / 1024 : 65535);
+  hipLaunchKernelGGL(k_zero_u32, dim3(blocks), dim3(256), 0, s, p, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_sumsq(const Dev &a, bool with_hist, hipStream_t s) {
+  if (a.G == 0 || a.nnodes == 0) return hipSuccess;
+  if (with_hist) hipLaunchKernelGGL(k_sumsq<true>, dim3(a.G, a.nnodes), dim3(kThreads), 0, s, a);
+  else hipLaunchKernelGGL(k_sumsq<false>, dim3(a.G, a.nnodes), dim3(kThreads), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_norm_finalize(const Dev &a, hipStream_t s) {
+  hipLaunchKernelGGL(k_norm_finalize, dim3(a.L, a.nnodes), dim3(kThreads), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_write_header(const Dev &a, hipStream_t s) {
+  hipLaunchKernelGGL(k_write_header, dim3(a.L, a.nnodes), dim3(64), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_quantize(const Dev &a, hipStream_t s) {
+  if (a.G == 0 || a.nnodes == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_quantize, dim3(a.G, a.nnodes), dim3(kThreads), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_delta_finalize(const Dev &a, hipStream_t s) {
+  hipLaunchKernelGGL(k_delta_finalize, dim3(a.nnodes), dim3(kThreads), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_step_scalars(const Dev &a, hipStream_t s) {
+  hipLaunchKernelGGL(k_step_scalars, dim3(1), dim3(64), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_decode(const Dev &a, bool update, size_t lds_bytes, hipStream_t s) {
+  if (a.G == 0) return hipSuccess;
+  if (update) hipLaunchKernelGGL(k_decode<true>, dim3(a.G), dim3(kThreads), lds_bytes, s, a);
+  else hipLaunchKernelGGL(k_decode<false>, dim3(a.G), dim3(kThreads), lds_bytes, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_fit(const Dev &a, hipStream_t s) {
+  hipLaunchKernelGGL(k_fit_typemax, dim3(a.M), dim3(kThreads), 0, s, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_fit_pool, dim3(a.L, a.K), dim3(kThreads), 0, s, a);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_fit_dp, dim3(a.M), dim3(kThreads), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_build_tables(const Dev &a, int type, hipStream_t s) {
+  hipLaunchKernelGGL(k_build_tables, dim3(1), dim3(kThreads), 0, s, a, type);
+  return hipGetLastError();
+}
+
+}  // namespace qoda

@@ -1,0 +1,199 @@
+"""Thin ctypes binding over libqoda.so (the C ABI of include/qoda.h).
+
+Argument marshalling only: every step of the hot path runs in the library's HIP kernels.  Device memory is
+passed as integer addresses (``tensor.data_ptr()``) and streams as ``torch.cuda.Stream.cuda_stream`` integers;
+there is no CPU fallback -- a missing library is an ImportError-like failure at first use.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libqoda.so")
+
+OK, EINVAL, ENOMEM, EHIP, ENONFINITE = 0, -1, -2, -3, -4
+BUF_SUMSQ, BUF_NORM, BUF_INV, BUF_DELTA, BUF_HIST, BUF_POOLED = range(6)
+HIST_BINS, GRID_POINTS = 2048, 257
+
+_lib = None
+
+
+class QodaError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"qoda error {code}: {msg}")
+        self.code = code
+
+
+class _Config(C.Structure):
+    _fields_ = [("num_layers", C.c_int32), ("layer_size", C.POINTER(C.c_int64)), ("layer_type", C.POINTER(C.c_int32)),
+                ("num_types", C.c_int32), ("type_points", C.POINTER(C.c_int32)), ("num_nodes", C.c_int32),
+                ("norm_kind", C.c_int32), ("seed", C.c_uint64)]
+
+
+class _State(C.Structure):
+    _fields_ = [("x1_dev", C.POINTER(C.c_void_p)), ("y_dev", C.POINTER(C.c_void_p)),
+                ("x_half_dev", C.POINTER(C.c_void_p)), ("x_next_dev", C.POINTER(C.c_void_p)),
+                ("acc_dev", C.c_void_p), ("eta_dev", C.c_void_p)]
+
+
+def load():
+    """Open libqoda.so (built by ``paper_2505_14371_amd.build``); raises if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise QodaError(EINVAL, f"{LIB_PATH} is missing: build it with `python -m paper_2505_14371_amd.build` "
+                                "(there is no CPU fallback)")
+    L = C.CDLL(LIB_PATH)
+    vp, pp = C.c_void_p, C.POINTER(C.c_void_p)
+    L.qoda_create.argtypes = [C.POINTER(_Config), C.POINTER(vp)]
+    L.qoda_destroy.argtypes = [vp]
+    L.qoda_message_bytes.argtypes = [vp]
+    L.qoda_message_bytes.restype = C.c_size_t
+    L.qoda_message_layout.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+    L.qoda_set_levels.argtypes = [vp, C.c_int32, C.POINTER(C.c_float), vp]
+    L.qoda_get_levels.argtypes = [vp, C.c_int32, C.POINTER(C.c_float), vp]
+    L.qoda_fit_levels.argtypes = [vp, pp, C.c_uint32, vp]
+    L.qoda_quantize.argtypes = [vp, C.c_int32, pp, C.c_uint32, vp, vp, vp]
+    L.qoda_quantize_all.argtypes = [vp, pp, C.c_uint32, pp, pp, vp]
+    L.qoda_dequant_aggregate.argtypes = [vp, pp, pp, vp]
+    L.qoda_step.argtypes = [vp, pp, C.POINTER(_State), vp]
+    L.qoda_read_buffer.argtypes = [vp, C.c_int32, vp, C.c_size_t, vp]
+    L.qoda_status.argtypes = [vp, vp]
+    L.qoda_last_error.argtypes = [vp]
+    L.qoda_last_error.restype = C.c_char_p
+    for name in ("qoda_create", "qoda_destroy", "qoda_message_layout", "qoda_set_levels", "qoda_get_levels",
+                 "qoda_fit_levels", "qoda_quantize", "qoda_quantize_all", "qoda_dequant_aggregate", "qoda_step",
+                 "qoda_read_buffer", "qoda_status"):
+        getattr(L, name).restype = C.c_int
+    _lib = L
+    return L
+
+
+def _addr(x) -> Optional[int]:
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return int(x.data_ptr())
+
+
+def _ptrs(xs: Sequence) -> C.Array:
+    arr = (C.c_void_p * len(xs))()
+    for i, x in enumerate(xs):
+        arr[i] = _addr(x)
+    return arr
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+class Context:
+    """One model: layer sizes, layer -> type map, grid points per type, K nodes, generator seed."""
+
+    def __init__(self, layer_size: Sequence[int], layer_type: Sequence[int], type_points: Sequence[int],
+                 num_nodes: int, seed: int):
+        self._lib = load()
+        self.layer_size = np.ascontiguousarray(layer_size, dtype=np.int64)
+        self.layer_type = np.ascontiguousarray(layer_type, dtype=np.int32)
+        self.type_points = np.ascontiguousarray(type_points, dtype=np.int32)
+        self.L, self.M, self.K = int(self.layer_size.size), int(self.type_points.size), int(num_nodes)
+        cfg = _Config(self.L, self.layer_size.ctypes.data_as(C.POINTER(C.c_int64)),
+                      self.layer_type.ctypes.data_as(C.POINTER(C.c_int32)), self.M,
+                      self.type_points.ctypes.data_as(C.POINTER(C.c_int32)), self.K, 2, seed)
+        h = C.c_void_p()
+        rc = self._lib.qoda_create(C.byref(cfg), C.byref(h))
+        if rc != OK:
+            raise QodaError(rc, "qoda_create failed (bad configuration, or no usable GPU)")
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._lib.qoda_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc: int):
+        if rc != OK:
+            raise QodaError(rc, self._lib.qoda_last_error(self._h).decode())
+
+    # -- layout
+    def message_bytes(self) -> int:
+        return int(self._lib.qoda_message_bytes(self._h))
+
+    def message_layout(self):
+        h = np.zeros(self.L, dtype=np.int64)
+        b = np.zeros(self.L, dtype=np.int64)
+        self._check(self._lib.qoda_message_layout(self._h, h.ctypes.data_as(C.POINTER(C.c_int64)),
+                                                  b.ctypes.data_as(C.POINTER(C.c_int64))))
+        return h, b
+
+    # -- levels
+    def set_levels(self, type_: int, levels, stream=None):
+        lev = np.ascontiguousarray(levels, dtype=np.float32)
+        if lev.size != self.type_points[type_]:
+            raise QodaError(EINVAL, "set_levels: wrong number of levels")
+        self._check(self._lib.qoda_set_levels(self._h, type_, lev.ctypes.data_as(C.POINTER(C.c_float)), _stream(stream)))
+
+    def get_levels(self, type_: int, stream=None) -> np.ndarray:
+        lev = np.zeros(int(self.type_points[type_]), dtype=np.float32)
+        self._check(self._lib.qoda_get_levels(self._h, type_, lev.ctypes.data_as(C.POINTER(C.c_float)), _stream(stream)))
+        return lev
+
+    def fit_levels(self, grads: Sequence, round_: int, stream=None):
+        """grads: K*L device tensors/addresses, entry k*L+l."""
+        assert len(grads) == self.K * self.L
+        self._check(self._lib.qoda_fit_levels(self._h, _ptrs(grads), round_, _stream(stream)))
+
+    # -- hot path
+    def quantize(self, node: int, grads: Sequence, round_: int, msg, msg_prev=None, stream=None):
+        assert len(grads) == self.L
+        self._check(self._lib.qoda_quantize(self._h, node, _ptrs(grads), round_, _addr(msg), _addr(msg_prev),
+                                            _stream(stream)))
+
+    def quantize_all(self, grads: Sequence, round_: int, msgs: Sequence, msgs_prev: Optional[Sequence] = None,
+                     stream=None):
+        assert len(grads) == self.K * self.L and len(msgs) == self.K
+        prev = None if msgs_prev is None else _ptrs(msgs_prev)
+        self._check(self._lib.qoda_quantize_all(self._h, _ptrs(grads), round_, _ptrs(msgs), prev, _stream(stream)))
+
+    def dequant_aggregate(self, msgs: Sequence, mean_out: Sequence, stream=None):
+        assert len(msgs) == self.K and len(mean_out) == self.L
+        self._check(self._lib.qoda_dequant_aggregate(self._h, _ptrs(msgs), _ptrs(mean_out), _stream(stream)))
+
+    def step(self, msgs: Sequence, x1: Sequence, y: Sequence, x_half: Sequence, acc, x_next: Optional[Sequence] = None,
+             eta=None, stream=None):
+        assert len(msgs) == self.K
+        st = _State(_ptrs(x1), _ptrs(y), _ptrs(x_half), None if x_next is None else _ptrs(x_next), _addr(acc), _addr(eta))
+        self._check(self._lib.qoda_step(self._h, _ptrs(msgs), C.byref(st), _stream(stream)))
+
+    # -- diagnostics
+    def read_buffer(self, which: int, stream=None) -> np.ndarray:
+        KL = self.K * self.L
+        shape, dt = {BUF_SUMSQ: ((self.K, self.L), np.float64), BUF_NORM: ((self.K, self.L), np.float32),
+                     BUF_INV: ((self.K, self.L), np.float32), BUF_DELTA: ((self.K,), np.float64),
+                     BUF_HIST: ((self.K, self.L, HIST_BINS), np.uint32),
+                     BUF_POOLED: ((self.M, GRID_POINTS), np.uint64)}[which]
+        out = np.zeros(shape, dtype=dt)
+        del KL
+        self._check(self._lib.qoda_read_buffer(self._h, which, out.ctypes.data, out.nbytes, _stream(stream)))
+        return out
+
+    def status(self, stream=None) -> int:
+        return int(self._lib.qoda_status(self._h, _stream(stream)))

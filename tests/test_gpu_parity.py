@@ -1,0 +1,324 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same seeded inputs.
+Bit-exact on norms-derived scalars, level indices, packed message bytes, histogram and pooled fit weights;
+<= 1e-6 relative on decoded / aggregated / updated fp32 values (they are expected to be identical too)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import helpers  # noqa: E402
+from paper_2505_14371_amd import qoda, workloads  # noqa: E402
+
+REL = 1e-6
+
+
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.fail("a GPU test was selected but no GPU is visible")
+
+
+def gm(*a, **k):
+    _need_gpu()
+    import gpu_harness
+
+    return gpu_harness.GpuModel(*a, **k)
+
+
+def close(a, b, scale=None):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    s = np.abs(b).max() if scale is None else scale
+    return np.all(np.abs(a - b) <= REL * np.maximum(np.abs(b), 1e-30) + REL * 1e-3 * s)
+
+
+def irregular_levels(S, seed):
+    rng = np.random.default_rng(seed)
+    inner = np.sort(rng.uniform(0.0, 1.0, S - 2) ** 3).astype(np.float32)
+    lev = np.concatenate([[0.0], inner, [1.0]]).astype(np.float32)
+    for j in range(1, S):
+        if not lev[j] > lev[j - 1]:
+            lev[j] = np.nextafter(lev[j - 1], np.float32(2.0))
+    lev[-1] = 1.0
+    assert np.all(np.diff(lev) > 0)
+    return lev
+
+
+RAGGED = [1, 3, 4, 255, 256, 257, 1023, 4100, 16383, 16384, 16385, 40001, 70000, 16384 * 3 + 7]
+
+
+def test_norms_are_bit_exact(oracle):
+    sizes = RAGGED + [0, 16384 * 257 + 13]
+    K = 2
+    m = gm(sizes, [0] * len(sizes), [4], K, seed=1)
+    rng = np.random.default_rng(0)
+    grads = [[(rng.standard_t(3, s) * 10.0 ** rng.uniform(-6, 3)).astype(np.float32) for s in sizes] for _ in range(K)]
+    grads[1][3][:] = 0.0                                   # an all-zero layer
+    grads[0][4][:] = np.float32(1e-30)                     # squares far below fp32 range: fp64 keeps them
+    m.set_grads(grads)
+    m.quantize_all(1)
+    ss = m.ctx.read_buffer(qoda.BUF_SUMSQ)
+    nr = m.ctx.read_buffer(qoda.BUF_NORM)
+    iv = m.ctx.read_buffer(qoda.BUF_INV)
+    assert m.ctx.status() == qoda.OK
+    for k in range(K):
+        for l, s in enumerate(sizes):
+            want = oracle.sumsq(grads[k][l])
+            assert ss[k, l] == want, (k, l, s)
+            n = oracle.sqrt_floor(want)
+            assert nr[k, l] == n and iv[k, l] == oracle.rcp_floor(n)
+
+
+@pytest.mark.parametrize("S", [2, 3, 4, 5, 8, 16, 17, 64, 256])
+def test_messages_are_bit_exact_for_every_code_width(oracle, S):
+    sizes = [1, 5, 255, 256, 257, 1000, 16384, 16385, 40001]
+    K = 2
+    m = gm(sizes, [0, 1] * 4 + [0], [S, S], K, seed=77 + S)
+    lev = [helpers.uniform_levels(S), irregular_levels(S, S)]
+    m.ctx.set_levels(0, lev[0])
+    m.ctx.set_levels(1, lev[1])
+    assert np.array_equal(m.ctx.get_levels(1), lev[1])
+    w = workloads.get("dcgan")
+    grads = [[workloads.layer_numpy(w, k, l % 10, 1, n=s) for l, s in enumerate(sizes)] for k in range(K)]
+    grads[0][5][::7] = 0.0
+    grads[0][5][3] = -0.0
+    m.set_grads(grads)
+    m.quantize_all(3)
+    got = m.messages()
+    delta = m.ctx.read_buffer(qoda.BUF_DELTA)
+    layer_levels = [lev[t] for t in [0, 1] * 4 + [0]]
+    assert m.mbytes == oracle.message_bytes(sizes, [S] * len(sizes))
+    for k in range(K):
+        want, _, dl, st = oracle.quantize(sizes, [S] * len(sizes), layer_levels, grads[k], 77 + S, 3, k)
+        assert st == 0
+        assert np.array_equal(got[k], want), f"node {k}: first difference at byte {np.flatnonzero(got[k] != want)[:5]}"
+        assert delta[k] == dl
+
+
+def test_second_round_uses_the_previous_message_and_per_node_calls_agree(oracle):
+    w = workloads.mini("txl", max_layer=30000, max_layers=9)
+    S, K = 8, 3
+    L = len(w.sizes)
+    m = gm(w.sizes, [0] * L, [S], K, seed=5)
+    lev1, lev2 = helpers.uniform_levels(S), irregular_levels(S, 1)
+    g1 = [workloads.node_numpy(w, k, 1) for k in range(K)]
+    g2 = [workloads.node_numpy(w, k, 2) for k in range(K)]
+    m.set_grads(g1)
+    m.quantize_all(1)
+    first = m.messages()
+    m.cur, m.have_prev = 1, True
+    m.ctx.set_levels(0, lev2)
+    m.set_grads(g2)
+    m.quantize_all(2)
+    second = m.messages()
+    delta = m.ctx.read_buffer(qoda.BUF_DELTA)
+    for k in range(K):
+        w1, _, _, _ = oracle.quantize(w.sizes, [S] * L, [lev1] * L, g1[k], 5, 1, k)
+        w2, _, d2, _ = oracle.quantize(w.sizes, [S] * L, [lev2] * L, g2[k], 5, 2, k, msg_prev=w1)
+        assert np.array_equal(first[k], w1) and np.array_equal(second[k], w2)
+        assert delta[k] == d2
+    # node-by-node calls write the same bytes and deltas
+    for t in m.msg[1]:
+        t.zero_()
+    m.quantize_each(2)
+    again = m.messages()
+    assert all(np.array_equal(a, b) for a, b in zip(again, second))
+    assert np.array_equal(m.ctx.read_buffer(qoda.BUF_DELTA), delta)
+
+
+@pytest.mark.parametrize("K,S", [(1, 16), (3, 4), (8, 8), (16, 4)])
+def test_dequant_aggregate_matches(oracle, K, S):
+    sizes = [257, 16385, 5000, 3]
+    m = gm(sizes, [0] * 4, [S], K, seed=9)
+    w = workloads.get("txl")
+    grads = [[workloads.layer_numpy(w, k, l + 3, 1, n=s) for l, s in enumerate(sizes)] for k in range(K)]
+    m.set_grads(grads)
+    m.quantize_all(1)
+    m.aggregate()
+    got = m.layers(m.mean)
+    want = oracle.dequant_aggregate(sizes, [S] * 4, m.messages())
+    for l in range(4):
+        assert close(got[l], want[l])
+        assert np.array_equal(got[l], want[l])        # same fp32 operations in the same order
+
+
+def test_bilinear_game_lockstep_and_free_running(oracle):
+    """Config 1, all 200 rounds.  Free-running: GPU and oracle each carry their own state.  Lock-step: the
+    oracle's state is overwritten with the GPU's after every round, so one differing bit cannot hide later ones."""
+    wl = workloads.get("bilinear")
+    A, x0, y0 = workloads.bilinear_game(seed=wl.seed)
+    op = lambda x, y, k, t: workloads.bilinear_operator(A, x, y, k, t, seed=wl.seed, sigma=0.1)
+    n, K, S = 512, wl.num_nodes, wl.points
+    m = gm([n, n], [0, 0], [S], K, seed=wl.seed)
+    m.set_layers(m.x1, [x0, y0])
+    m.set_layers(m.x_half, [x0, y0])
+    lev = helpers.uniform_levels(S)
+    free = helpers.OracleQODA([n, n], [S, S], [lev, lev], K, [x0, y0], wl.seed)
+    lock = helpers.OracleQODA([n, n], [S, S], [lev, lev], K, [x0, y0], wl.seed)
+    worst = 0.0
+    for t in range(1, wl.rounds + 1):
+        xq, yq = m.layers(m.x_half)
+        grads = [list(op(xq, yq, k, t)) for k in range(K)]
+        m.set_grads(grads)
+        m.quantize_all(t)
+        msgs = m.messages()
+        deltas = m.ctx.read_buffer(qoda.BUF_DELTA)
+        m.step()
+        gy, gxn, gxh = m.layers(m.y), m.layers(m.x_next), m.layers(m.x_half)
+        eta = m.eta.cpu().numpy()
+        # lock-step oracle, fed the same gradients, starting from the GPU's previous state
+        lm, ld, _ = lock.round_(grads, t)
+        for k in range(K):
+            assert np.array_equal(msgs[k], lm[k]), (t, k)
+            assert deltas[k] == ld[k], (t, k)
+        assert eta[0] == lock.eta and eta[1] == lock.eta, t
+        for l in range(2):
+            assert close(gy[l], lock.y[l]) and close(gxn[l], lock.x_next[l]) and close(gxh[l], lock.x_half[l]), t
+            worst = max(worst, float(np.abs(gxh[l].astype(np.float64) - lock.x_half[l]).max()))
+        lock.y = [a.copy() for a in gy]
+        lock.x_half = [a.copy() for a in gxh]
+        lock.acc = float(m.acc.cpu().numpy()[0])
+        # free-running oracle evaluates the operator at ITS OWN query point
+        fx, fy = free.x_half
+        free.round_([list(op(fx, fy, k, t)) for k in range(K)], t)
+    for l in range(2):
+        assert close(m.layers(m.x_half)[l], free.x_half[l]), "free-running trajectories separated"
+        assert close(m.layers(m.y)[l], free.y[l])
+    assert float(m.acc.cpu().numpy()[0]) == pytest.approx(free.acc, rel=1e-12)
+    assert worst == 0.0      # in practice every iterate is identical, not merely within 1e-6
+
+
+def test_microbenchmark_full_size(oracle):
+    """Config 2: 2^24 N(0,1) entries, one layer, 16 uniform levels, K = 1, seed 1: one quantize + dequantize."""
+    wl = workloads.get("microbench")
+    m = gm(wl.sizes, [0], [wl.points], 1, seed=wl.seed)
+    g = workloads.layer_numpy(wl, 0, 0, 1)
+    m.set_grads([[g]])
+    m.quantize_all(1)
+    m.aggregate()
+    got = m.messages()[0]
+    lev = helpers.uniform_levels(wl.points)
+    want, ss, dl, st = oracle.quantize(wl.sizes, [wl.points], [lev], [g], wl.seed, 1, 0)
+    assert np.array_equal(got, want)
+    assert m.ctx.read_buffer(qoda.BUF_SUMSQ)[0, 0] == ss[0] and m.ctx.read_buffer(qoda.BUF_DELTA)[0] == dl
+    dec = oracle.dequant_aggregate(wl.sizes, [wl.points], [want])[0]
+    assert np.array_equal(m.layers(m.mean)[0], dec)
+    # the quantized vector is an unbiased estimate: its error is orthogonal-ish to v and matches eq. (Var)
+    norm = float(oracle.sqrt_floor(ss[0]))
+    u = np.minimum(np.abs(g.astype(np.float64)) / norm, 1.0)
+    tau = np.minimum((u * 15).astype(np.int64), 14)
+    var = norm ** 2 * float(np.sum(((tau + 1) / 15 - u) * (u - tau / 15)))
+    err = float(np.sum((dec.astype(np.float64) - g) ** 2))
+    assert abs(err - var) < 0.01 * var
+
+
+def test_fit_levels_matches_and_feeds_the_quantizer(oracle):
+    """Config 3 shapes shrunk: histogram, pooled grid weights and fitted levels identical; the quantize that
+    follows (reusing the norms of the fit pass) writes the oracle's bytes; so does a quantize that recomputes them."""
+    w = workloads.mini("dcgan", max_layer=50000, max_layers=10)
+    L, K, S = len(w.sizes), 4, 16
+    types = [0, 1, 2, 3, 4, 4, 3, 2, 1, 5]                 # some layers share a type
+    M = 6
+    points = [16, 16, 8, 4, 16, 3]
+    m = gm(w.sizes, types, points, K, seed=3)
+    grads = [workloads.node_numpy(w, k, 1) for k in range(K)]
+    m.set_grads(grads)
+    m.fit(1)
+    m.quantize_all(1)
+    got = m.messages()
+    flat = [grads[k][l] for k in range(K) for l in range(L)]
+    init = [helpers.uniform_levels(s) for s in points]
+    levs, hist, pooled, st = oracle.fit_levels(w.sizes, types, points, K, flat, init)
+    assert np.array_equal(m.ctx.read_buffer(qoda.BUF_HIST), hist)
+    assert np.array_equal(m.ctx.read_buffer(qoda.BUF_POOLED), pooled)
+    for t in range(M):
+        assert np.array_equal(m.ctx.get_levels(t), levs[t]), t
+    pts = [points[t] for t in types]
+    ll = [levs[t] for t in types]
+    for k in range(K):
+        want, _, _, _ = oracle.quantize(w.sizes, pts, ll, grads[k], 3, 1, k)
+        assert np.array_equal(got[k], want)
+    for t in m.msg[m.cur]:
+        t.zero_()
+    m.quantize_all(2)                                      # another round number: norms are recomputed
+    again = m.messages()
+    for k in range(K):
+        want, _, _, _ = oracle.quantize(w.sizes, pts, ll, grads[k], 3, 2, k)
+        assert np.array_equal(again[k], want)
+    del S
+
+
+@pytest.mark.parametrize("name,rounds", [("dcgan", 3), ("txl", 2), ("gpt1p3b", 2)])
+def test_adaptive_rounds_on_shrunken_workloads(oracle, name, rounds):
+    """Configs 3-5 shrunk (same distributions, node counts and level counts, ragged layer sizes): fit every
+    round, quantize, fused step; every message byte, delta, step size and iterate is compared each round."""
+    w = workloads.mini(name, max_layer=20000, max_layers=14)
+    L, K, S = len(w.sizes), w.num_nodes, w.points
+    m = gm(w.sizes, list(range(L)), [S] * L, K, seed=w.seed)
+    rng = np.random.default_rng(w.seed)
+    x1 = [rng.standard_normal(s).astype(np.float32) for s in w.sizes]
+    m.set_layers(m.x1, x1)
+    st = helpers.OracleQODA(w.sizes, [S] * L, [helpers.uniform_levels(S)] * L, K, x1, w.seed)
+    for t in range(1, rounds + 1):
+        grads = [workloads.node_numpy(w, k, t) for k in range(K)]
+        m.set_grads(grads)
+        m.fit(t)
+        m.quantize_all(t)
+        msgs = m.messages()
+        deltas = m.ctx.read_buffer(qoda.BUF_DELTA)
+        m.step()
+        flat = [grads[k][l] for k in range(K) for l in range(L)]
+        levs, _, _, _ = oracle.fit_levels(w.sizes, list(range(L)), [S] * L, K, flat, st.levels)
+        st.levels = levs
+        om, od, _ = st.round_(grads, t)
+        for k in range(K):
+            assert np.array_equal(msgs[k], om[k]), (t, k)
+            assert deltas[k] == od[k]
+        assert m.eta.cpu().numpy()[0] == st.eta
+        for l in range(L):
+            assert close(m.layers(m.y)[l], st.y[l]) and close(m.layers(m.x_half)[l], st.x_half[l])
+            assert close(m.layers(m.x_next)[l], st.x_next[l])
+    assert m.ctx.status() == qoda.OK
+
+
+def test_runs_are_deterministic():
+    w = workloads.mini("txl", max_layer=30000, max_layers=6)
+    L, K = len(w.sizes), 4
+    outs = []
+    for _ in range(2):
+        m = gm(w.sizes, [0] * L, [8], K, seed=1)
+        m.set_grads([workloads.node_numpy(w, k, 1) for k in range(K)])
+        m.fit(1)
+        m.quantize_all(1)
+        m.step()
+        outs.append((m.messages(0), m.layers(m.x_half), m.ctx.get_levels(0)))
+    assert all(np.array_equal(a, b) for a, b in zip(outs[0][0], outs[1][0]))
+    assert all(np.array_equal(a, b) for a, b in zip(outs[0][1], outs[1][1]))
+    assert np.array_equal(outs[0][2], outs[1][2])
+
+
+def test_nonfinite_flag_and_argument_errors():
+    m = gm([1000, 300], [0, 0], [4], 2, seed=1)
+    g = [[np.ones(1000, np.float32), np.ones(300, np.float32)] for _ in range(2)]
+    g[1][0][5] = np.inf
+    m.set_grads(g)
+    m.quantize_all(1)
+    assert m.ctx.status() == qoda.ENONFINITE
+    assert m.ctx.status() == qoda.OK                        # the flag is cleared by reading it
+    with pytest.raises(qoda.QodaError):
+        m.ctx.set_levels(0, [0.0, 0.5, 0.4, 1.0])           # not increasing
+    with pytest.raises(qoda.QodaError):
+        m.ctx.set_levels(0, [0.1, 0.2, 0.4, 1.0])           # does not start at 0
+    with pytest.raises(qoda.QodaError):
+        m.ctx.quantize(5, m.layer_ptrs(m.grad_flat[0]), 1, m.msg[0][0])                  # node out of range
+    with pytest.raises(qoda.QodaError):
+        m.ctx.quantize(0, [p + 4 for p in m.layer_ptrs(m.grad_flat[0])], 1, m.msg[0][0])   # misaligned layer
+    with pytest.raises(qoda.QodaError):
+        m.ctx.quantize(0, m.layer_ptrs(m.grad_flat[0]), 1, m.msg[0][0], m.msg[0][0])     # prev aliases out
+    with pytest.raises(qoda.QodaError):
+        m.ctx.quantize_all(m.grad_ptrs(), 1, [m.msg[0][0], None])                        # null message
+    with pytest.raises(qoda.QodaError):
+        qoda.Context([10], [0], [1], 1, 0)                   # S < 2
+    with pytest.raises(qoda.QodaError):
+        qoda.Context([10], [1], [4], 1, 0)                   # type out of range
