@@ -1,0 +1,213 @@
+#!/usr/bin/env python3
+"""Throughput of the QODA hot path on one MI355X.
+
+One step = one round of Alg. 1's device work over all K simulated nodes: (level fit when the workload is adaptive)
+-> quantize + pack all nodes -> fused decode + K-way mean + dual-averaging update.  Inputs (the K nodes' synthetic
+gradients, state and message buffers) are resident in HBM before the timed region.
+
+Prints ONE JSON line: whole-job GB/s of fp32 gradient pushed through the path, the roofline of the dominant kernel
+from HIP-event timings taken inside the timed region, and the CPU oracle timed on a bounded sample of the same data.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+
+
+def _library():
+    from paper_2505_14371_amd import qoda
+
+    if not os.path.exists(qoda.LIB_PATH):
+        from paper_2505_14371_amd import build
+
+        build.build()
+    return qoda
+
+
+def _cpu_baseline(w, model, K, sample_target=2.5e7):
+    """The oracle, as it stands, single-threaded, on a bounded sample of the same data: a run of consecutive
+    tensors (skipping a leading embedding-sized one) for up to 4 nodes, one full round."""
+    import oracle
+
+    L = len(w.sizes)
+    Ks = min(K, 4)
+    start = 1 if (L > 2 and w.sizes[0] > sample_target) else 0
+    layers, tot = [], 0
+    for l in range(start, L):
+        layers.append(l)
+        tot += w.sizes[l]
+        if tot >= sample_target:
+            break
+    sizes = [w.sizes[l] for l in layers]
+    S = w.points
+    grads = []
+    for k in range(Ks):
+        flat = model["grad"][k]
+        grads.append([flat[int(model["off"][l]): int(model["off"][l]) + w.sizes[l]].cpu().numpy() for l in layers])
+    lev = [(np.arange(S, dtype=np.float64) / (S - 1)).astype(np.float32) for _ in sizes]
+    x1 = [np.zeros(s, np.float32) for s in sizes]
+    y = [np.zeros(s, np.float32) for s in sizes]
+    t0 = time.perf_counter()
+    if w.adaptive:
+        flat = [grads[k][i] for k in range(Ks) for i in range(len(sizes))]
+        lev, _, _, _ = oracle.fit_levels(sizes, list(range(len(sizes))), [S] * len(sizes), Ks, flat, lev)
+    msgs, deltas = [], []
+    for k in range(Ks):
+        m, _, dl, _ = oracle.quantize(sizes, [S] * len(sizes), lev, grads[k], w.seed, 1, k)
+        msgs.append(m)
+        deltas.append(dl)
+    mean = oracle.dequant_aggregate(sizes, [S] * len(sizes), msgs)
+    _, eta = oracle.step_size(deltas, 0.0)
+    for i in range(len(sizes)):
+        oracle.oda_update(mean[i], x1[i], y[i], eta, eta, want_next=False)
+    dt = time.perf_counter() - t0
+    gbytes = 4.0 * Ks * tot / 1e9
+    return {"value": gbytes / dt, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"one round, nodes 0..{Ks - 1}, tensors {layers[0]}..{layers[-1]} "
+                      f"({tot} coordinates per node, {Ks * tot} node-coordinates) in {dt:.1f} s",
+            "ns_per_node_coordinate": dt / (Ks * tot) * 1e9}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="gpt1p3b", choices=["bilinear", "microbench", "dcgan", "txl", "gpt1p3b"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--x-next", action="store_true", help="also materialise X_{t+1}")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the K nodes are K message buffers on one device); "
+              "--gpus must be 1", file=sys.stderr)
+        return 2
+
+    import torch
+
+    qoda = _library()
+    from paper_2505_14371_amd import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    dev = torch.device("cuda:0")
+    w = workloads.get(args.workload)
+    L, K, S, d = len(w.sizes), w.num_nodes, w.points, w.total
+    ctx = qoda.Context(w.sizes, list(range(L)), [S] * L, K, w.seed)
+    off, flat_len = workloads.padded_offsets(w.sizes)
+
+    def ptrs(t):
+        base = t.data_ptr()
+        return [base + 4 * int(o) for o in off]
+
+    grad = [workloads.node_torch(w, k, 1, dev)[0] for k in range(K)]
+    mbytes = ctx.message_bytes()
+    msg = [[torch.zeros(mbytes, dtype=torch.uint8, device=dev) for _ in range(K)] for _ in range(2)]
+    x1 = torch.randn(flat_len, dtype=torch.float32, device=dev)
+    y = torch.zeros(flat_len, dtype=torch.float32, device=dev)
+    xh = torch.zeros(flat_len, dtype=torch.float32, device=dev)
+    xn = torch.zeros(flat_len, dtype=torch.float32, device=dev) if args.x_next else None
+    acc = torch.zeros(1, dtype=torch.float64, device=dev)
+    eta = torch.ones(2, dtype=torch.float32, device=dev)
+    gptrs = [p for k in range(K) for p in ptrs(grad[k])]
+    x1p, yp, xhp = ptrs(x1), ptrs(y), ptrs(xh)
+    xnp = ptrs(xn) if xn is not None else None
+    state = {"cur": 0, "t": 0}
+
+    def one_round():
+        state["t"] += 1
+        t, cur = state["t"], state["cur"]
+        if w.adaptive:
+            ctx.fit_levels(gptrs, t)
+        ctx.quantize_all(gptrs, t, msg[cur], msg[1 - cur] if t > 1 else None)
+        ctx.step(msg[cur], x1p, yp, xhp, acc, xnp, eta)
+        state["cur"] = 1 - cur
+
+    for _ in range(args.warmup):
+        one_round()
+    torch.cuda.synchronize()
+    ctx.profile_read()
+    ctx.profile_enable(True)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t_host0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        one_round()
+    e1.record()
+    torch.cuda.synchronize()
+    t_host = time.perf_counter() - t_host0
+    total_ms = e0.elapsed_time(e1)
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    if ctx.status() != qoda.OK:
+        print("bench.py: non-finite input flagged", file=sys.stderr)
+        return 1
+
+    # a plain copy of known size, after the timed region: the kernel that byte counters are scaled by
+    nb = min(flat_len * 4, 1 << 30) // 16 * 16
+    ctx.profile_enable(True)
+    for _ in range(3):
+        ctx.copy_calibration(y, xh, nb)
+    copy_ms, copy_n = ctx.profile_read()["k_copy_f4"]
+    ctx.profile_enable(False)
+
+    _, body_off = ctx.message_layout()
+    body_bytes = mbytes - int(body_off[0])            # packed bytes per node without the header
+    alg = {"k_sumsq<false>": 4.0 * K * d, "k_sumsq<true>": 4.0 * K * d,
+           "k_quantize": 4.0 * K * d + 2.0 * K * body_bytes,
+           "k_decode<true>": float(K * body_bytes) + (20.0 if xn is not None else 16.0) * d}
+    kernels = {name: {"avg_ms": ms / n, "launches": n} for name, (ms, n) in prof.items()}
+    dom = max((n for n in kernels if n in alg), key=lambda n: prof[n][0])
+    dom_ms = kernels[dom]["avg_ms"]
+    achieved = alg[dom] / (dom_ms * 1e-3) / 1e9
+    for name in kernels:
+        if name in alg:
+            kernels[name]["algorithmic_GBps"] = alg[name] / (kernels[name]["avg_ms"] * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(args.workload, {}).get(dom)
+        except Exception:
+            traffic = None
+
+    ms_per_step = total_ms / args.steps
+    grad_bytes = 4.0 * K * d
+    alg_round = sum(alg[n] for n in (("k_sumsq<true>" if w.adaptive else "k_sumsq<false>"), "k_quantize", "k_decode<true>"))
+    out = {
+        "metric": "GB/s fp32 gradient through quantize+aggregate+QODA step; % of HBM peak",
+        "value": grad_bytes / (ms_per_step * 1e-3) / 1e9,
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "num_nodes": K, "coordinates": d, "tensors": L, "level_points": S,
+                   "adaptive_levels": w.adaptive, "message_bytes_per_node": mbytes, "x_next": xn is not None},
+        "hbm_peak_fraction_algorithmic": alg_round / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "algorithmic_bytes_per_step": alg_round,
+        "host_wall_ms_per_step": t_host / args.steps * 1e3,
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "avg_ms": dom_ms,
+                     "algorithmic_bytes_per_launch": alg[dom]},
+        "copy_kernel_GBps": 2.0 * nb / (copy_ms / copy_n * 1e-3) / 1e9,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = _cpu_baseline(w, {"grad": grad, "off": off}, K)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -50,6 +50,13 @@ struct qoda_ctx {
   uint32_t norms_round = 0;
   std::vector<const float *> norms_grad;
   std::vector<float> h_lev;   // host shadow of the level tables (source of asynchronous uploads)
+  // optional per-kernel event timing
+  struct ProfRec { int id; hipEvent_t a, b; };
+  bool prof_on = false;
+  std::vector<ProfRec> prof_recs;
+  std::vector<hipEvent_t> prof_pool;
+  double prof_ms[kNumKernelIds] = {};
+  long long prof_n[kNumKernelIds] = {};
   std::string err;
 };
 
@@ -73,6 +80,27 @@ int fail(qoda_ctx *c, int code, const char *fmt, ...) {
     if (e_ != hipSuccess)                                                                       \
       return fail((c), e_ == hipErrorOutOfMemory ? QODA_ENOMEM : QODA_EHIP, "%s: %s", #call,    \
                   hipGetErrorString(e_));                                                       \
+  } while (0)
+
+hipError_t prof_event(qoda_ctx *c, hipEvent_t *e) {
+  if (!c->prof_pool.empty()) { *e = c->prof_pool.back(); c->prof_pool.pop_back(); return hipSuccess; }
+  return hipEventCreate(e);
+}
+
+// Enqueue one kernel class; with profiling on, bracket it with two events on the same stream.
+#define LAUNCH(c, id, s, call)                                                   \
+  do {                                                                           \
+    qoda_ctx::ProfRec r_{(id), nullptr, nullptr};                                \
+    if ((c)->prof_on) {                                                          \
+      HIP_TRY((c), prof_event((c), &r_.a));                                      \
+      HIP_TRY((c), prof_event((c), &r_.b));                                      \
+      HIP_TRY((c), hipEventRecord(r_.a, (s)));                                   \
+    }                                                                            \
+    HIP_TRY((c), (call));                                                        \
+    if ((c)->prof_on) {                                                          \
+      HIP_TRY((c), hipEventRecord(r_.b, (s)));                                   \
+      (c)->prof_recs.push_back(r_);                                              \
+    }                                                                            \
   } while (0)
 
 int index_bits(int S) {
@@ -158,12 +186,14 @@ void free_all(qoda_ctx *c) {
   for (void *p : ptrs)
     if (p) (void)hipFree(p);
   if (c->upload_done) (void)hipEventDestroy(c->upload_done);
+  for (auto &r : c->prof_recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+  for (hipEvent_t e : c->prof_pool) (void)hipEventDestroy(e);
 }
 
 // norms of nodes [node0, node0+n) from the gradient table already on the device
 int run_norm_pass(qoda_ctx *c, Dev a, bool with_hist, hipStream_t s) {
-  HIP_TRY(c, launch_sumsq(a, with_hist, s));
-  HIP_TRY(c, launch_norm_finalize(a, s));
+  LAUNCH(c, with_hist ? kIdSumsqHist : kIdSumsq, s, launch_sumsq(a, with_hist, s));
+  LAUNCH(c, kIdNormFinalize, s, launch_norm_finalize(a, s));
   return QODA_OK;
 }
 
@@ -186,9 +216,9 @@ int quantize_impl(qoda_ctx *c, int node0, int nnodes, const float *const *grad_f
     int rc = run_norm_pass(c, a, false, s);
     if (rc) return rc;
   }
-  HIP_TRY(c, launch_write_header(a, s));
-  HIP_TRY(c, launch_quantize(a, s));
-  HIP_TRY(c, launch_delta_finalize(a, s));
+  LAUNCH(c, kIdWriteHeader, s, launch_write_header(a, s));
+  LAUNCH(c, kIdQuantize, s, launch_quantize(a, s));
+  LAUNCH(c, kIdDeltaFinalize, s, launch_delta_finalize(a, s));
   return QODA_OK;
 }
 
@@ -340,7 +370,7 @@ int qoda_set_levels(qoda_ctx *c, int32_t type, const float *lev, void *stream) {
   HIP_TRY(c, hipEventRecord(c->upload_done, s));
   c->upload_pending = true;
   Dev a = base_args(c);
-  HIP_TRY(c, launch_build_tables(a, type, s));
+  LAUNCH(c, kIdBuildTables, s, launch_build_tables(a, type, s));
   return QODA_OK;
 }
 
@@ -367,11 +397,13 @@ int qoda_fit_levels(qoda_ctx *c, const float *const *grad_dev, uint32_t round, v
   Dev a = base_args(c);
   a.grad = reinterpret_cast<const float *const *>(c->t_grad.dev);
   a.round = round;
-  HIP_TRY(c, launch_zero_u32(c->d_hist, KL * kHistBins, s));
-  HIP_TRY(c, launch_zero_u32(reinterpret_cast<unsigned int *>(c->d_pooled), (size_t)c->M * kGridPoints * 2, s));
+  LAUNCH(c, kIdZero, s, launch_zero_u32(c->d_hist, KL * kHistBins, s));
+  LAUNCH(c, kIdZero, s, launch_zero_u32(reinterpret_cast<unsigned int *>(c->d_pooled), (size_t)c->M * kGridPoints * 2, s));
   rc = run_norm_pass(c, a, true, s);
   if (rc) return rc;
-  HIP_TRY(c, launch_fit(a, s));
+  LAUNCH(c, kIdFitTypemax, s, launch_fit_typemax(a, s));
+  LAUNCH(c, kIdFitPool, s, launch_fit_pool(a, s));
+  LAUNCH(c, kIdFitDp, s, launch_fit_dp(a, s));
   c->norms_grad.assign(grad_dev, grad_dev + KL);
   c->norms_round = round;
   c->norms_valid = true;
@@ -458,7 +490,7 @@ int qoda_dequant_aggregate(qoda_ctx *c, const void *const *msgs_dev, float *cons
   rc = sync_table(c, c->t_mean, reinterpret_cast<const void *const *>(mean_out_dev), c->L, s);
   if (rc) return rc;
   a.mean_out = reinterpret_cast<float *const *>(c->t_mean.dev);
-  HIP_TRY(c, launch_decode(a, false, (size_t)c->K * c->maxS * sizeof(float), s));
+  LAUNCH(c, kIdDecodeMean, s, launch_decode(a, false, (size_t)c->K * c->maxS * sizeof(float), s));
   return QODA_OK;
 }
 
@@ -487,8 +519,8 @@ int qoda_step(qoda_ctx *c, const void *const *msgs_dev, const qoda_state *st, vo
   a.x_next = st->x_next_dev ? reinterpret_cast<float *const *>(c->t_xn.dev) : nullptr;
   a.acc = st->acc_dev;
   a.eta_out = st->eta_dev;
-  HIP_TRY(c, launch_step_scalars(a, s));
-  HIP_TRY(c, launch_decode(a, true, (size_t)c->K * c->maxS * sizeof(float), s));
+  LAUNCH(c, kIdStepScalars, s, launch_step_scalars(a, s));
+  LAUNCH(c, kIdDecodeUpdate, s, launch_decode(a, true, (size_t)c->K * c->maxS * sizeof(float), s));
   return QODA_OK;
 }
 
@@ -524,6 +556,53 @@ int qoda_status(qoda_ctx *c, void *stream) {
     HIP_TRY(c, launch_zero_u32(c->d_status, 1, s));
     return fail(c, QODA_ENONFINITE, "a layer's sum of squares was not a finite number");
   }
+  return QODA_OK;
+}
+
+int qoda_profile_enable(qoda_ctx *c, int32_t on) {
+  if (!c) return QODA_EINVAL;
+  c->prof_on = on != 0;
+  return QODA_OK;
+}
+
+int qoda_profile_read(qoda_ctx *c, double *ms, int64_t *launches, void *stream) {
+  if (!c) return QODA_EINVAL;
+  if (!ms || !launches) return fail(c, QODA_EINVAL, "qoda_profile_read: null output");
+  HIP_TRY(c, hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+  for (auto &r : c->prof_recs) {
+    float t = 0.0f;
+    HIP_TRY(c, hipEventSynchronize(r.b));
+    HIP_TRY(c, hipEventElapsedTime(&t, r.a, r.b));
+    c->prof_ms[r.id] += (double)t;
+    c->prof_n[r.id] += 1;
+    c->prof_pool.push_back(r.a);
+    c->prof_pool.push_back(r.b);
+  }
+  c->prof_recs.clear();
+  for (int i = 0; i < kNumKernelIds; ++i) {
+    ms[i] = c->prof_ms[i];
+    launches[i] = c->prof_n[i];
+    c->prof_ms[i] = 0.0;
+    c->prof_n[i] = 0;
+  }
+  return QODA_OK;
+}
+
+const char *qoda_kernel_name(int32_t id) {
+  static const char *names[kNumKernelIds] = {"k_zero_u32", "k_sumsq<false>", "k_sumsq<true>", "k_norm_finalize",
+                                             "k_write_header", "k_quantize", "k_delta_finalize", "k_step_scalars",
+                                             "k_decode<false>", "k_decode<true>", "k_fit_typemax", "k_fit_pool",
+                                             "k_fit_dp", "k_build_tables", "k_copy_f4"};
+  return (id >= 0 && id < kNumKernelIds) ? names[id] : "";
+}
+
+int qoda_copy_calibration(qoda_ctx *c, const void *src_dev, void *dst_dev, size_t bytes, void *stream) {
+  if (!c) return QODA_EINVAL;
+  if (!src_dev || !dst_dev || bytes % 16 != 0 || reinterpret_cast<uintptr_t>(src_dev) % 16 != 0 ||
+      reinterpret_cast<uintptr_t>(dst_dev) % 16 != 0)
+    return fail(c, QODA_EINVAL, "qoda_copy_calibration: pointers and size must be multiples of 16 bytes");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  LAUNCH(c, kIdCopy, s, launch_copy(src_dev, dst_dev, bytes, s));
   return QODA_OK;
 }
 

@@ -70,6 +70,12 @@ struct Dev {
   double invK2;
 };
 
+// Kernel classes, for the optional per-kernel event timing of the host API.
+enum KernelId {
+  kIdZero = 0, kIdSumsq, kIdSumsqHist, kIdNormFinalize, kIdWriteHeader, kIdQuantize, kIdDeltaFinalize, kIdStepScalars,
+  kIdDecodeMean, kIdDecodeUpdate, kIdFitTypemax, kIdFitPool, kIdFitDp, kIdBuildTables, kIdCopy, kNumKernelIds
+};
+
 // Launch wrappers (each checks nothing: the host API validates shapes before calling).
 hipError_t launch_zero_u32(unsigned int *p, size_t n, hipStream_t s);
 hipError_t launch_sumsq(const Dev &a, bool with_hist, hipStream_t s);
@@ -79,7 +85,10 @@ hipError_t launch_quantize(const Dev &a, hipStream_t s);
 hipError_t launch_delta_finalize(const Dev &a, hipStream_t s);
 hipError_t launch_step_scalars(const Dev &a, hipStream_t s);
 hipError_t launch_decode(const Dev &a, bool update, size_t lds_bytes, hipStream_t s);
-hipError_t launch_fit(const Dev &a, hipStream_t s);
+hipError_t launch_fit_typemax(const Dev &a, hipStream_t s);
+hipError_t launch_fit_pool(const Dev &a, hipStream_t s);
+hipError_t launch_fit_dp(const Dev &a, hipStream_t s);
+hipError_t launch_copy(const void *src, void *dst, size_t bytes, hipStream_t s);
 hipError_t launch_build_tables(const Dev &a, int type, hipStream_t s);
 
 }  // namespace qoda

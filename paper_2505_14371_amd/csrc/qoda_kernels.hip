@@ -586,7 +586,25 @@ __global__ void __launch_bounds__(kThreads) k_fit_dp(Dev a) {
   build_tables(a, mtype, S, slev);
 }
 
+// ------------------------------------------------------------------------------------------------ calibration
+// Plain 128-bit copy of n float4: the known-size kernel that hardware byte counters are calibrated against.
+__global__ void __launch_bounds__(kThreads) k_copy_f4(const float4 *__restrict__ src, float4 *__restrict__ dst, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) dst[i] = src[i];
+}
+
 // ------------------------------------------------------------------------------------------------ launchers
+hipError_t launch_copy(const void *src, void *dst, size_t bytes, hipStream_t s) {
+  const size_t n = bytes / 16;
+  if (n == 0) return hipSuccess;
+  const size_t want = (n + kThreads * 4 - 1) / (kThreads * 4);
+  const unsigned int blocks = (unsigned int)(want < 1048576 ? want : 1048576);
+  hipLaunchKernelGGL(k_copy_f4, dim3(blocks), dim3(kThreads), 0, s, reinterpret_cast<const float4 *>(src),
+                     reinterpret_cast<float4 *>(dst), n);
+  return hipGetLastError();
+}
+
 hipError_t launch_zero_u32(unsigned int *p, size_t n, hipStream_t s) {
   if (n == 0) return hipSuccess;
   const unsigned int blocks = (unsigned int)((n + 1023) / 1024 < 65535 ? (n + 1023) / 1024 : 65535);
@@ -634,13 +652,17 @@ hipError_t launch_decode(const Dev &a, bool update, size_t lds_bytes, hipStream_
   return hipGetLastError();
 }
 
-hipError_t launch_fit(const Dev &a, hipStream_t s) {
+hipError_t launch_fit_typemax(const Dev &a, hipStream_t s) {
   hipLaunchKernelGGL(k_fit_typemax, dim3(a.M), dim3(kThreads), 0, s, a);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  return hipGetLastError();
+}
+
+hipError_t launch_fit_pool(const Dev &a, hipStream_t s) {
   hipLaunchKernelGGL(k_fit_pool, dim3(a.L, a.K), dim3(kThreads), 0, s, a);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  return hipGetLastError();
+}
+
+hipError_t launch_fit_dp(const Dev &a, hipStream_t s) {
   hipLaunchKernelGGL(k_fit_dp, dim3(a.M), dim3(kThreads), 0, s, a);
   return hipGetLastError();
 }

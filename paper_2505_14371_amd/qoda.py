@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libqoda.so")
 
 OK, EINVAL, ENOMEM, EHIP, ENONFINITE = 0, -1, -2, -3, -4
 BUF_SUMSQ, BUF_NORM, BUF_INV, BUF_DELTA, BUF_HIST, BUF_POOLED = range(6)
+NUM_KERNELS = 15
 HIST_BINS, GRID_POINTS = 2048, 257
 
 _lib = None
@@ -64,11 +65,16 @@ def load():
     L.qoda_step.argtypes = [vp, pp, C.POINTER(_State), vp]
     L.qoda_read_buffer.argtypes = [vp, C.c_int32, vp, C.c_size_t, vp]
     L.qoda_status.argtypes = [vp, vp]
+    L.qoda_profile_enable.argtypes = [vp, C.c_int32]
+    L.qoda_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), vp]
+    L.qoda_kernel_name.argtypes = [C.c_int32]
+    L.qoda_kernel_name.restype = C.c_char_p
+    L.qoda_copy_calibration.argtypes = [vp, vp, vp, C.c_size_t, vp]
     L.qoda_last_error.argtypes = [vp]
     L.qoda_last_error.restype = C.c_char_p
     for name in ("qoda_create", "qoda_destroy", "qoda_message_layout", "qoda_set_levels", "qoda_get_levels",
                  "qoda_fit_levels", "qoda_quantize", "qoda_quantize_all", "qoda_dequant_aggregate", "qoda_step",
-                 "qoda_read_buffer", "qoda_status"):
+                 "qoda_read_buffer", "qoda_status", "qoda_profile_enable", "qoda_profile_read", "qoda_copy_calibration"):
         getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -197,3 +203,21 @@ class Context:
 
     def status(self, stream=None) -> int:
         return int(self._lib.qoda_status(self._h, _stream(stream)))
+
+    # -- measurement aids
+    def profile_enable(self, on: bool = True):
+        self._check(self._lib.qoda_profile_enable(self._h, 1 if on else 0))
+
+    def profile_read(self, stream=None):
+        """{kernel name: (total ms, launches)} since the last read."""
+        ms = (C.c_double * NUM_KERNELS)()
+        n = (C.c_int64 * NUM_KERNELS)()
+        self._check(self._lib.qoda_profile_read(self._h, ms, n, _stream(stream)))
+        return {kernel_name(i): (float(ms[i]), int(n[i])) for i in range(NUM_KERNELS) if n[i]}
+
+    def copy_calibration(self, src, dst, nbytes: int, stream=None):
+        self._check(self._lib.qoda_copy_calibration(self._h, _addr(src), _addr(dst), nbytes, _stream(stream)))
+
+
+def kernel_name(i: int) -> str:
+    return load().qoda_kernel_name(i).decode()
