@@ -1,0 +1,93 @@
+"""Turn rocprofv3 CSV output of the qoda_probe driver into the short text summaries kept under profiles/.
+
+    python -m paper_2505_14371_amd.profile_summary --name txl --stats DIR --fetch DIR --write DIR \\
+        --probe-log FILE --command "..." --out profiles/
+
+Reads <DIR>/**/*_kernel_stats.csv (from --kernel-trace --stats) and <DIR>/**/*_counter_collection.csv (from
+--pmc FETCH_SIZE / --pmc WRITE_SIZE, values in KiB per dispatch).  The byte counters are scaled by what the same
+counter reads for the plain copy kernel k_copy_f4, whose true size the probe log states.  Writes
+<out>/<name>_kernels.txt and merges the per-kernel traffic into <out>/traffic.json (read by bench.py).
+"""
+from __future__ import annotations
+
+import argparse
+import collections
+import csv
+import glob
+import json
+import os
+import re
+
+
+def _one(pattern: str) -> str:
+    hits = sorted(glob.glob(pattern, recursive=True))
+    if not hits:
+        raise SystemExit(f"no file matches {pattern}")
+    return hits[-1]
+
+
+def _short(name: str) -> str:
+    m = re.search(r"(k_[a-z0-9_]+(<[a-z]+>)?)", name)
+    return m.group(1) if m else name[:60]
+
+
+def _counters(directory: str):
+    rows = csv.DictReader(open(_one(os.path.join(directory, "**", "*_counter_collection.csv"))))
+    agg = collections.defaultdict(list)
+    for r in rows:
+        agg[_short(r["Kernel_Name"])].append(float(r["Counter_Value"]) * 1024.0)
+    return agg
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--name", required=True)
+    ap.add_argument("--stats", required=True)
+    ap.add_argument("--fetch")
+    ap.add_argument("--write")
+    ap.add_argument("--probe-log", required=True)
+    ap.add_argument("--command", required=True)
+    ap.add_argument("--out", default="profiles")
+    a = ap.parse_args()
+    log = open(a.probe_log).read()
+    copy_bytes = int(re.search(r"k_copy_f4.*bytes_read=(\d+)", log).group(1))
+    lines = [f"# rocprofv3 summary: {a.name}", "# command:", "#   " + a.command, "#", "# probe output:"]
+    lines += ["#   " + l for l in log.strip().splitlines()]
+    lines += ["", "kernel-trace --stats (ours only):", f"{'kernel':<22}{'calls':>7}{'avg_us':>12}{'min_us':>12}{'max_us':>12}{'pct':>8}"]
+    for r in csv.DictReader(open(_one(os.path.join(a.stats, "**", "*_kernel_stats.csv")))):
+        if "qoda::" not in r["Name"]:
+            continue
+        lines.append(f"{_short(r['Name']):<22}{r['Calls']:>7}{float(r['AverageNs']) / 1e3:>12.1f}"
+                     f"{float(r['MinNs']) / 1e3:>12.1f}{float(r['MaxNs']) / 1e3:>12.1f}{float(r['Percentage']):>8.2f}")
+    traffic = {}
+    if a.fetch and a.write:
+        fetch, write = _counters(a.fetch), _counters(a.write)
+        f_scale = copy_bytes / (sum(fetch["k_copy_f4"]) / len(fetch["k_copy_f4"]))
+        w_scale = copy_bytes / (sum(write["k_copy_f4"]) / len(write["k_copy_f4"]))
+        lines += ["", f"--pmc FETCH_SIZE / WRITE_SIZE per dispatch, scaled by the copy kernel ({copy_bytes} B each way):",
+                  f"scale factors: FETCH_SIZE x {f_scale:.4f}, WRITE_SIZE x {w_scale:.4f}",
+                  f"{'kernel':<22}{'dispatches':>11}{'fetch_MB':>12}{'write_MB':>12}{'total_MB':>12}"]
+        for k in sorted(set(fetch) | set(write)):
+            if not k.startswith("k_"):
+                continue
+            # the first dispatch (warm-up round, no previous message) is left out when there are later ones
+            fv = fetch.get(k, [0.0])
+            wv = write.get(k, [0.0])
+            fv = fv[1:] if len(fv) > 1 else fv
+            wv = wv[1:] if len(wv) > 1 else wv
+            fb, wb = f_scale * sum(fv) / len(fv), w_scale * sum(wv) / len(wv)
+            traffic[k] = fb + wb
+            lines.append(f"{k:<22}{len(fv):>11}{fb / 1e6:>12.2f}{wb / 1e6:>12.2f}{(fb + wb) / 1e6:>12.2f}")
+    os.makedirs(a.out, exist_ok=True)
+    with open(os.path.join(a.out, f"{a.name}_kernels.txt"), "w") as f:
+        f.write("\n".join(lines) + "\n")
+    tpath = os.path.join(a.out, "traffic.json")
+    allt = json.load(open(tpath)) if os.path.exists(tpath) else {}
+    if traffic:
+        allt[a.name] = traffic
+        json.dump(allt, open(tpath, "w"), indent=1, sort_keys=True)
+    print("\n".join(lines))
+
+
+if __name__ == "__main__":
+    main()

@@ -172,3 +172,10 @@ def bilinear_operator(A: np.ndarray, x: np.ndarray, y: np.ndarray, node: int, ro
     gx = A.astype(np.float64) @ y.astype(np.float64) + sigma * rng.standard_normal(x.size)
     gy = -(A.astype(np.float64).T @ x.astype(np.float64)) + sigma * rng.standard_normal(y.size)
     return gx.astype(np.float32), gy.astype(np.float32)
+
+
+if __name__ == "__main__":
+    import sys
+
+    # `python -m paper_2505_14371_amd.workloads txl` prints one layer size per line (input of the qoda_probe driver)
+    print("\n".join(str(s) for s in get(sys.argv[1]).sizes))
