@@ -23,13 +23,14 @@ struct qoda_ctx {
   std::vector<int> type_points;
   size_t message_bytes = 0, header_bytes = 0;
   int maxS = 0;
+  int maxSP = 0;   // largest 2^b over the layers: stride of the per-node decode tables in LDS
   // device memory owned by the context
   LayerMeta *d_meta = nullptr;
   int2 *d_tiles = nullptr;
   int *d_type_points = nullptr;
   double *d_partial = nullptr, *d_dpartial = nullptr, *d_sumsq = nullptr, *d_delta = nullptr;
   float *d_norm = nullptr, *d_inv = nullptr, *d_lev = nullptr, *d_rgap = nullptr, *d_eta = nullptr;
-  unsigned char *d_lut = nullptr;
+  unsigned short *d_lut = nullptr;
   unsigned int *d_hist = nullptr, *d_status = nullptr;
   unsigned long long *d_pooled = nullptr;
   int *d_type_exp = nullptr;
@@ -258,9 +259,10 @@ int qoda_create(const qoda_config *cfg, qoda_ctx **out) {
     m.nchunks = (int)((d + kChunkCoords - 1) / kChunkCoords);
     chunks += m.nchunks;
     if (m.S > c->maxS) c->maxS = m.S;
+    if ((1 << (m.planes - 1)) > c->maxSP) c->maxSP = 1 << (m.planes - 1);
     if (hdr > (1u << 30) || chunks > (1ll << 30)) { delete c; return QODA_EINVAL; }
   }
-  if ((size_t)c->K * c->maxS * sizeof(float) > 64 * 1024) { delete c; return QODA_EINVAL; }   // decode tables must fit LDS
+  if ((size_t)c->K * c->maxSP * sizeof(float) > 64 * 1024) { delete c; return QODA_EINVAL; }   // decode tables must fit LDS
   c->header_bytes = round_up(hdr, 256);
   size_t off = c->header_bytes;
   for (int l = 0; l < c->L; ++l) {
@@ -490,7 +492,7 @@ int qoda_dequant_aggregate(qoda_ctx *c, const void *const *msgs_dev, float *cons
   rc = sync_table(c, c->t_mean, reinterpret_cast<const void *const *>(mean_out_dev), c->L, s);
   if (rc) return rc;
   a.mean_out = reinterpret_cast<float *const *>(c->t_mean.dev);
-  LAUNCH(c, kIdDecodeMean, s, launch_decode(a, false, (size_t)c->K * c->maxS * sizeof(float), s));
+  LAUNCH(c, kIdDecodeMean, s, launch_decode(a, false, (size_t)c->K * c->maxSP * sizeof(float), s));
   return QODA_OK;
 }
 
@@ -520,7 +522,7 @@ int qoda_step(qoda_ctx *c, const void *const *msgs_dev, const qoda_state *st, vo
   a.acc = st->acc_dev;
   a.eta_out = st->eta_dev;
   LAUNCH(c, kIdStepScalars, s, launch_step_scalars(a, s));
-  LAUNCH(c, kIdDecodeUpdate, s, launch_decode(a, true, (size_t)c->K * c->maxS * sizeof(float), s));
+  LAUNCH(c, kIdDecodeUpdate, s, launch_decode(a, true, (size_t)c->K * c->maxSP * sizeof(float), s));
   return QODA_OK;
 }
 

@@ -16,6 +16,8 @@ namespace qoda {
 
 namespace {
 
+typedef float v4f __attribute__((ext_vector_type(4)));   // plain vector type: usable behind address-space pointers
+
 __device__ __forceinline__ unsigned int f2u(float f) { return __float_as_uint(f); }
 __device__ __forceinline__ float u2f(unsigned int u) { return __uint_as_float(u); }
 
@@ -84,41 +86,56 @@ __device__ __forceinline__ void philox4x32_10(unsigned int c0, unsigned int c1, 
   out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
+// Loads through pointers read from device tables: tell the compiler they point to global memory.
+template <class T>
+__device__ __forceinline__ const __attribute__((address_space(1))) T *as_global(const T *p) {
+  return (const __attribute__((address_space(1))) T *)p;
+}
+
 // Four coordinates e..e+3 of a layer of d entries; entries past the end read as +0.
 __device__ __forceinline__ void load4(const float *__restrict__ v, long long e, long long d, float x[4]) {
+  const auto *g = as_global(v);
   if (e + 4 <= d) {
-    const float4 q = *reinterpret_cast<const float4 *>(v + e);
+    const v4f q = *reinterpret_cast<const __attribute__((address_space(1))) v4f *>(g + e);
     x[0] = q.x; x[1] = q.y; x[2] = q.z; x[3] = q.w;
   } else {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) x[j] = (e + j < d) ? v[e + j] : 0.0f;
+    for (int j = 0; j < 4; ++j) x[j] = (e + j < d) ? g[e + j] : 0.0f;
   }
 }
 
 __device__ __forceinline__ void store4(float *__restrict__ v, long long e, long long d, const float x[4]) {
+  auto *g = (__attribute__((address_space(1))) float *)v;
   if (e + 4 <= d) {
-    *reinterpret_cast<float4 *>(v + e) = make_float4(x[0], x[1], x[2], x[3]);
+    v4f q;
+    q.x = x[0]; q.y = x[1]; q.z = x[2]; q.w = x[3];
+    *reinterpret_cast<__attribute__((address_space(1))) v4f *>(g + e) = q;
   } else {
 #pragma unroll
     for (int j = 0; j < 4; ++j)
-      if (e + j < d) v[e + j] = x[j];
+      if (e + j < d) g[e + j] = x[j];
   }
 }
 
-// Decode the four coordinates of lane `lane` from one packed block: sign ? -T[h] : T[h], h clamped to S-1.
+// Broadcast the 64-bit value held by lane `lane` (a compile-time constant after unrolling) to the whole wave.
+__device__ __forceinline__ unsigned long long bcast64(unsigned long long v, int lane) {
+  const unsigned int lo = (unsigned int)__builtin_amdgcn_readlane((int)(unsigned int)v, lane);
+  const unsigned int hi = (unsigned int)__builtin_amdgcn_readlane((int)(unsigned int)(v >> 32), lane);
+  return ((unsigned long long)hi << 32) | lo;
+}
+
+// Decode component j of this lane from one packed block whose 4*PLANES words sit one per lane in `mw`
+// (lane p*4+j holds plane p of component j).  A wave-uniform 64-bit plane is turned back into one bit per lane
+// by a mask-select; the level index becomes a byte offset into a table of 2^(PLANES-1) floats (entries past
+// S-1 repeat the last level, which is the clamp of an out-of-range index).
 template <int PLANES>
-__device__ __forceinline__ void decode4(const unsigned long long *__restrict__ pw, int lane, const float *T, int S,
-                                        float out[4]) {
+__device__ __forceinline__ float decode_component(unsigned long long mw, int j, const float *table) {
+  unsigned int off = 0;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const unsigned int sign = (unsigned int)(pw[j] >> lane) & 1u;
-    unsigned int h = 0;
-#pragma unroll
-    for (int p = 1; p < PLANES; ++p) h |= ((unsigned int)(pw[p * 4 + j] >> lane) & 1u) << (p - 1);
-    h = min(h, (unsigned int)(S - 1));
-    const float t = T[h];
-    out[j] = sign ? -t : t;
-  }
+  for (int p = 1; p < PLANES; ++p)
+    off |= __builtin_amdgcn_inverse_ballot_w64(bcast64(mw, p * 4 + j)) ? (4u << (p - 1)) : 0u;
+  const float t = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(table) + off);
+  return __builtin_amdgcn_inverse_ballot_w64(bcast64(mw, j)) ? -t : t;
 }
 
 }  // namespace
@@ -151,9 +168,10 @@ __global__ void __launch_bounds__(kThreads) k_sumsq(Dev a) {
   const long long base = (long long)tile.y * kChunkCoords + (long long)w * 16 * kBlockCoords + 4 * i;
   double acc = 0.0;
   if ((long long)(tile.y + 1) * kChunkCoords <= m.d) {
-    float4 q[16];
+    v4f q[16];
 #pragma unroll
-    for (int s = 0; s < 16; ++s) q[s] = *reinterpret_cast<const float4 *>(v + base + (long long)s * kBlockCoords);
+    for (int s = 0; s < 16; ++s)
+      q[s] = *reinterpret_cast<const __attribute__((address_space(1))) v4f *>(as_global(v) + base + (long long)s * kBlockCoords);
 #pragma unroll
     for (int s = 0; s < 16; ++s) {
       const float x[4] = {q[s].x, q[s].y, q[s].z, q[s].w};
@@ -226,10 +244,18 @@ __global__ void k_write_header(Dev a) {
 // ------------------------------------------------------------------------------------------------ pass 2
 // Quantize + pack one tile (Sec. 3.1, Sec. 3.2) and accumulate the squared distance to the node's previous
 // decoded message (the step-size term of eq. (general_stepsize)).
+// Place a wave-uniform 64-bit word into lane `lane` (compile-time constant) of a per-lane 64-bit register.
+__device__ __forceinline__ void put_word(unsigned int &lo, unsigned int &hi, unsigned long long word, int lane) {
+  const bool me = (int)(threadIdx.x & 63) == lane;
+  lo = me ? (unsigned int)word : lo;
+  hi = me ? (unsigned int)(word >> 32) : hi;
+}
+
 template <int PLANES>
 __device__ __forceinline__ void quantize_tile(const Dev &a, const LayerMeta &m, int l, int k, int chunk,
-                                              const unsigned char *lut, const float4 *tab, const float *tcur,
-                                              const float *tprev, double *red) {
+                                              const unsigned short *lut, const float4 *tab, const float *tprev,
+                                              double *red) {
+  constexpr int W = 4 * PLANES;   // 64-bit words per packed block
   const int t = threadIdx.x;
   const int w = __builtin_amdgcn_readfirstlane(t >> 6);
   const int i = t & 63;
@@ -237,7 +263,7 @@ __device__ __forceinline__ void quantize_tile(const Dev &a, const LayerMeta &m, 
   unsigned char *msg = a.msg[k] + m.body_off;
   const unsigned char *prev = (a.prev != nullptr && a.prev[k] != nullptr) ? a.prev[k] + m.body_off : nullptr;
   const float inv = a.inv[(size_t)k * a.L + l];
-  const int S = m.S;
+  const float norm = a.norm[(size_t)k * a.L + l];
   const unsigned int k0 = (unsigned int)a.seed, k1 = (unsigned int)(a.seed >> 32);
   double acc = 0.0;
   for (int pair = 0; pair < 8; ++pair) {
@@ -252,33 +278,51 @@ __device__ __forceinline__ void quantize_tile(const Dev &a, const LayerMeta &m, 
       const long long e = B * kBlockCoords + 4 * i;
       float x[4];
       load4(v, e, m.d, x);
-      float prevv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-      if (prev) decode4<PLANES>(reinterpret_cast<const unsigned long long *>(prev + B * 32 * PLANES), i, tprev, S, prevv);
-      unsigned long long mine = 0ull;
+      unsigned long long pw = 0ull;   // lane q < W holds word q of the previous message's block
+      if (prev != nullptr && i < W)
+        pw = reinterpret_cast<const __attribute__((address_space(1))) unsigned long long *>(as_global(prev) + B * 32 * PLANES)[i];
+      // level search (Sec. 3.1): the table entry of u's bin gives tau at the bin's lower edge and how many
+      // further levels lie inside the bin; only lanes in such a bin walk on.
+      float u[4];
+      unsigned int ent[4];
+      int tau[4];
+      float4 lv[4];                                          // {l_tau, 1/gap, l_tau+1, norm*l_tau}
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        u[j] = fminf(fabsf(x[j]) * inv, 1.0f);
+        ent[j] = lut[f2u(u[j]) >> 20];
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        tau[j] = (int)(ent[j] & 0xFFu);
+        lv[j] = tab[tau[j]];
+      }
+      if (__ballot(((ent[0] | ent[1] | ent[2] | ent[3]) >> 8) != 0u) != 0ull) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          for (int n = (int)(ent[j] >> 8); n > 0 && lv[j].z <= u[j]; --n) { ++tau[j]; lv[j] = tab[tau[j]]; }
+      }
+      unsigned int mlo = 0u, mhi = 0u;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const unsigned int w16 = half ? (o[j] >> 16) : (o[j] & 0xFFFFu);
-        const unsigned int sign = f2u(x[j]) >> 31;
-        const float u = fminf(fabsf(x[j]) * inv, 1.0f);
-        int tau = lut[f2u(u) >> 20];
-        float4 lv = tab[tau];                              // {l_tau, 1/gap, l_tau+1, -}
-        while (tau < S - 2 && lv.z <= u) { ++tau; lv = tab[tau]; }
-        const float xi = (u - lv.x) * lv.y;
-        const bool up = ((float)w16 + 0.5f) < xi * 65536.0f;
-        const unsigned int h = (unsigned int)tau + (up ? 1u : 0u);
-        const float tc = tcur[h];
-        const float cur = sign ? -tc : tc;
-        const float diff = cur - prevv[j];
+        const float xi = (u[j] - lv[j].x) * lv[j].y;
+        // (w16 + 0.5) < xi * 65536  <=>  w16 < xi * 65536 - 0.5 : the scaling by 2^16 is exact, and the
+        // subtraction is exact whenever its result is not negative, so one fused operation decides the same.
+        const bool up = (float)w16 < __builtin_fmaf(xi, 65536.0f, -0.5f);
+        const unsigned int h = (unsigned int)tau[j] + (up ? 1u : 0u);
+        const float mag = up ? norm * lv[j].z : lv[j].w;     // norm * l_h, the value the decoder will rebuild
+        const float cur = __builtin_copysignf(mag, x[j]);
+        const float pv = (prev != nullptr) ? decode_component<PLANES>(pw, j, tprev) : 0.0f;
+        const float diff = cur - pv;
         acc = __builtin_fma((double)diff, (double)diff, acc);
-        const unsigned long long sb = __ballot(sign != 0u);
-        if (i == j) mine = sb;
+        put_word(mlo, mhi, __ballot((int)f2u(x[j]) < 0), j);
 #pragma unroll
-        for (int p = 1; p < PLANES; ++p) {
-          const unsigned long long pb = __ballot(((h >> (p - 1)) & 1u) != 0u);
-          if (i == p * 4 + j) mine = pb;
-        }
+        for (int p = 1; p < PLANES; ++p) put_word(mlo, mhi, __ballot((h & (1u << (p - 1))) != 0u), p * 4 + j);
       }
-      if (i < 4 * PLANES) reinterpret_cast<unsigned long long *>(msg + B * 32 * PLANES)[i] = mine;
+      if (i < W)
+        reinterpret_cast<__attribute__((address_space(1))) unsigned long long *>(
+            (__attribute__((address_space(1))) unsigned char *)msg + B * 32 * PLANES)[i] = ((unsigned long long)mhi << 32) | mlo;
     }
   }
   const double total = block_tree(acc, red);
@@ -286,9 +330,8 @@ __device__ __forceinline__ void quantize_tile(const Dev &a, const LayerMeta &m, 
 }
 
 __global__ void __launch_bounds__(kThreads) k_quantize(Dev a) {
-  __shared__ unsigned char lut[kLutSize];
+  __shared__ unsigned short lut[kLutSize];
   __shared__ float4 tab[kMaxPoints];
-  __shared__ float tcur[kMaxPoints];
   __shared__ float tprev[kMaxPoints];
   __shared__ double red[kThreads];
   const int2 tile = a.tiles[blockIdx.x];
@@ -298,31 +341,31 @@ __global__ void __launch_bounds__(kThreads) k_quantize(Dev a) {
   const int t = threadIdx.x;
   const float *lev = a.lev + (size_t)m.type * kMaxPoints;
   const float *rg = a.rgap + (size_t)m.type * kMaxPoints;
-  reinterpret_cast<unsigned int *>(lut)[t] = reinterpret_cast<const unsigned int *>(a.lut + (size_t)m.type * kLutSize)[t];
+  reinterpret_cast<uint2 *>(lut)[t] = reinterpret_cast<const uint2 *>(a.lut + (size_t)m.type * kLutSize)[t];
   const float norm = a.norm[(size_t)k * a.L + l];
   const unsigned char *prevmsg = (a.prev != nullptr) ? a.prev[k] : nullptr;
-  if (t < m.S) {
-    const float lj = lev[t];
-    const float ln = (t + 1 < m.S) ? lev[t + 1] : 1.0f;
-    tab[t] = make_float4(lj, rg[t], ln, 0.0f);
-    tcur[t] = norm * lj;
+  if (t < (1 << (m.planes - 1))) {       // tables padded to 2^b entries; entries past S-1 repeat the last level
+    const int tj = min(t, m.S - 1);
+    const float lj = lev[tj];
+    const float ln = (tj + 1 < m.S) ? lev[tj + 1] : 1.0f;
+    tab[t] = make_float4(lj, rg[tj], ln, norm * lj);
+    float pv = 0.0f;
     if (prevmsg) {
       const float *hp = reinterpret_cast<const float *>(prevmsg + m.hdr_off);
-      tprev[t] = hp[0] * hp[1 + t];
-    } else {
-      tprev[t] = 0.0f;
+      pv = hp[0] * hp[1 + tj];
     }
+    tprev[t] = pv;
   }
   __syncthreads();
   switch (m.planes) {
-    case 2: quantize_tile<2>(a, m, l, k, tile.y, lut, tab, tcur, tprev, red); break;
-    case 3: quantize_tile<3>(a, m, l, k, tile.y, lut, tab, tcur, tprev, red); break;
-    case 4: quantize_tile<4>(a, m, l, k, tile.y, lut, tab, tcur, tprev, red); break;
-    case 5: quantize_tile<5>(a, m, l, k, tile.y, lut, tab, tcur, tprev, red); break;
-    case 6: quantize_tile<6>(a, m, l, k, tile.y, lut, tab, tcur, tprev, red); break;
-    case 7: quantize_tile<7>(a, m, l, k, tile.y, lut, tab, tcur, tprev, red); break;
-    case 8: quantize_tile<8>(a, m, l, k, tile.y, lut, tab, tcur, tprev, red); break;
-    default: quantize_tile<9>(a, m, l, k, tile.y, lut, tab, tcur, tprev, red); break;
+    case 2: quantize_tile<2>(a, m, l, k, tile.y, lut, tab, tprev, red); break;
+    case 3: quantize_tile<3>(a, m, l, k, tile.y, lut, tab, tprev, red); break;
+    case 4: quantize_tile<4>(a, m, l, k, tile.y, lut, tab, tprev, red); break;
+    case 5: quantize_tile<5>(a, m, l, k, tile.y, lut, tab, tprev, red); break;
+    case 6: quantize_tile<6>(a, m, l, k, tile.y, lut, tab, tprev, red); break;
+    case 7: quantize_tile<7>(a, m, l, k, tile.y, lut, tab, tprev, red); break;
+    case 8: quantize_tile<8>(a, m, l, k, tile.y, lut, tab, tprev, red); break;
+    default: quantize_tile<9>(a, m, l, k, tile.y, lut, tab, tprev, red); break;
   }
 }
 
@@ -355,24 +398,44 @@ __global__ void k_step_scalars(Dev a) {
 // DECODE + K-way mean (+ eq. (ODA) update when UPDATE): one pass over Y, X_1 and the K messages.
 template <int PLANES, bool UPDATE>
 __device__ __forceinline__ void decode_tile(const Dev &a, const LayerMeta &m, int l, int chunk, const float *T) {
+  constexpr int W = 4 * PLANES;
+  constexpr int SP = 1 << (PLANES - 1);   // table stride per node
+  constexpr int NB = 8;                   // nodes whose words are fetched together
   const int t = threadIdx.x;
   const int w = __builtin_amdgcn_readfirstlane(t >> 6);
   const int i = t & 63;
-  const int S = m.S;
   float eta = 0.0f, gamma = 0.0f;
   if (UPDATE) { eta = a.eta[0]; gamma = a.eta[1]; }
   for (int s = 0; s < 16; ++s) {
     const long long B = (long long)chunk * 64 + w * 16 + s;
     if (B >= m.nblk) break;
     const long long e = B * kBlockCoords + 4 * i;
-    float sum[4];
-    for (int k = 0; k < a.K; ++k) {
-      const unsigned long long *pw =
-          reinterpret_cast<const unsigned long long *>(a.msgs_in[k] + m.body_off + B * 32 * PLANES);
-      float val[4];
-      decode4<PLANES>(pw, i, T + k * S, S, val);
+    float y[4], x1[4];
+    if (UPDATE) {
+      load4(a.y[l], e, m.d, y);
+      load4(a.x1[l], e, m.d, x1);
+    }
+    float sum[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int kb = 0; kb < a.K; kb += NB) {
+      unsigned long long mw[NB];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) sum[j] = (k == 0) ? val[j] : sum[j] + val[j];
+      for (int q = 0; q < NB; ++q) {
+        mw[q] = 0ull;
+        if (kb + q < a.K && i < W)
+          mw[q] = reinterpret_cast<const __attribute__((address_space(1))) unsigned long long *>(
+              as_global(a.msgs_in[kb + q]) + m.body_off + B * 32 * PLANES)[i];
+      }
+#pragma unroll
+      for (int q = 0; q < NB; ++q) {
+        if (kb + q < a.K) {
+          const float *Tk = T + (kb + q) * SP;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const float val = decode_component<PLANES>(mw[q], j, Tk);
+            sum[j] = (kb + q == 0) ? val : sum[j] + val;
+          }
+        }
+      }
     }
     float mean[4];
 #pragma unroll
@@ -380,9 +443,7 @@ __device__ __forceinline__ void decode_tile(const Dev &a, const LayerMeta &m, in
     if (!UPDATE) {
       store4(a.mean_out[l], e, m.d, mean);
     } else {
-      float y[4], x1[4], xn[4], xh[4];
-      load4(a.y[l], e, m.d, y);
-      load4(a.x1[l], e, m.d, x1);
+      float xn[4], xh[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         y[j] = y[j] - mean[j];
@@ -400,12 +461,13 @@ __device__ __forceinline__ void decode_tile(const Dev &a, const LayerMeta &m, in
 
 template <bool UPDATE>
 __global__ void __launch_bounds__(kThreads) k_decode(Dev a) {
-  extern __shared__ float T[];   // [K][S]: norm_k * level_h of this layer, from the K message headers
+  extern __shared__ float T[];   // [K][2^b]: norm_k * level_h of this layer, from the K message headers
   const int2 tile = a.tiles[blockIdx.x];
   const int l = tile.x;
   const LayerMeta m = a.meta[l];
-  for (int idx = threadIdx.x; idx < a.K * m.S; idx += kThreads) {
-    const int k = idx / m.S, h = idx - k * m.S;
+  const int SP = 1 << (m.planes - 1);
+  for (int idx = threadIdx.x; idx < a.K * SP; idx += kThreads) {
+    const int k = idx / SP, h = min(idx - k * SP, m.S - 1);
     const float *hp = reinterpret_cast<const float *>(a.msgs_in[k] + m.hdr_off);
     T[idx] = hp[0] * hp[1 + h];
   }
@@ -482,18 +544,22 @@ __device__ __forceinline__ float grid_value(int j) { return u2f((unsigned int)(j
 // Search tables of one type from its levels (in shared memory): reciprocal gaps and the bin -> index table.
 __device__ void build_tables(const Dev &a, int mtype, int S, const float *slev) {
   float *rg = a.rgap + (size_t)mtype * kMaxPoints;
-  unsigned char *lut = a.lut + (size_t)mtype * kLutSize;
+  unsigned short *lut = a.lut + (size_t)mtype * kLutSize;
   for (int j = threadIdx.x; j < kMaxPoints; j += kThreads) rg[j] = (j < S - 1) ? rcp_floor(slev[j + 1] - slev[j]) : 0.0f;
+  // entry q serves the values whose bit pattern >> 20 is q, i.e. [lo, hi]: low byte = tau(lo), high byte =
+  // tau(hi) - tau(lo) = number of levels that lie inside the bin above its lower edge.
   for (int q = threadIdx.x; q < kLutSize; q += kThreads) {
-    const float edge = u2f((unsigned int)q << 20);
-    int tau = 0;
+    const float lo = u2f((unsigned int)q << 20), hi = u2f(((unsigned int)q << 20) | 0xFFFFFu);
+    int tlo = 0, thi = 0;
     if (q > 1016) {
-      tau = S - 2;
+      tlo = thi = S - 2;
     } else {
-      for (int j = 1; j <= S - 2; ++j)
-        if (slev[j] <= edge) tau = j;
+      for (int j = 1; j <= S - 2; ++j) {
+        if (slev[j] <= lo) tlo = j;
+        if (slev[j] <= hi) thi = j;
+      }
     }
-    lut[q] = (unsigned char)tau;
+    lut[q] = (unsigned short)(tlo | ((thi - tlo) << 8));
   }
 }
 
