@@ -25,9 +25,11 @@
  * Message format (ENCODE / DECODE of Sec. 3.2 and App. C.1, fixed width, no entropy code):
  *   header   for each layer, in order: fp32 norm (the paper's C_q = 32 bits), then its S fp32 level values
  *            (so that a stored previous-round message stays decodable after the levels change); padded to 256 B;
- *   body     for each layer, ceil(d_l/256) blocks of 256 coordinates, each block 4*(1+b) little-endian 64-bit
- *            words; word p*4+j holds plane p (0 = sign, p >= 1 = bit p-1 of the level index) of the coordinates
- *            256*B + 4*i + j, i = bit position 0..63.  Padding coordinates carry code 0.
+ *   body     for each layer, ceil(d_l/2048) octets of 2048 coordinates, 256*(1+b) bytes each.  A coordinate's
+ *            code is sign | index << 1 (1+b bits).  Inside an octet, "lane" i = (e mod 256)/4 owns the 32
+ *            coordinates 256*bb + 4*i + j (bb = 0..7, j = 0..3), numbered jj = 4*bb + j; their codes form a
+ *            little-endian bit string (code jj at bit (1+b)*jj), i.e. 1+b 32-bit words; word r of lane i is the
+ *            32-bit word r*64 + i of the octet.  Padding coordinates carry code 0.
  */
 #ifndef QODA_H_
 #define QODA_H_
@@ -88,7 +90,7 @@ int qoda_fit_levels(qoda_ctx *ctx, const float *const *grad_dev, uint32_t round,
 
 /* ENCODE(Q(V_{k,t+1/2})), Alg. 1 line 12 (Sec. 2.2, 3.1, 3.2): per-layer L2 norm, u = min(|v| / ||v||, 1), level
  * search, stochastic rounding with one 16-bit counter-based draw per coordinate (counter = coordinate, layer,
- * round, node), sign + index bit planes.  Also leaves delta_k = ||Vhat_{k,t+1/2} - Vhat_{k,t-1/2}||^2 in the
+ * round, node), sign + index codes shifted into per-lane records.  Also leaves delta_k = ||Vhat_{k,t+1/2} - Vhat_{k,t-1/2}||^2 in the
  * context for the step size (eq. (general_stepsize)); msg_prev_dev == NULL means Vhat_{k,t-1/2} = 0 (round 1).
  * grad_dev: host array [L] (node k's layers).  msg_dev / msg_prev_dev must not overlap. */
 int qoda_quantize(qoda_ctx *ctx, int32_t node, const float *const *grad_dev, uint32_t round, void *msg_dev,

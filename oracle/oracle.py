@@ -17,6 +17,7 @@ HIST_BINS = 2048
 GRID_POINTS = 257
 GRID_BASE = 760
 BLOCK = 256
+OCTET = 2048
 CHUNK = 16384
 
 _lib = None
@@ -207,7 +208,7 @@ def pack_layer(sign, idx, S: int) -> np.ndarray:
     idx = np.ascontiguousarray(idx, dtype=np.uint8)
     d = sign.size
     planes = 1 + index_bits(S)
-    region = np.zeros(((d + BLOCK - 1) // BLOCK) * 32 * planes, dtype=np.uint8)
+    region = np.zeros(((d + OCTET - 1) // OCTET) * 256 * planes, dtype=np.uint8)
     lib().oracle_pack_layer(_p(sign, C.c_uint8), _p(idx, C.c_uint8), d, S, _p(region, C.c_uint8))
     return region
 

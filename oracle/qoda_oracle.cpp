@@ -42,7 +42,8 @@
 
 namespace {
 
-constexpr int64_t kBlock = 256;     // coordinates per packed block
+constexpr int64_t kBlock = 256;     // coordinates per block (64 lanes x 4 consecutive coordinates)
+constexpr int64_t kOctet = 2048;    // coordinates per packed record group (8 blocks)
 constexpr int64_t kChunk = 16384;   // coordinates per reduction chunk (64 blocks)
 constexpr int kSlots = 256;         // reduction slots per chunk
 constexpr int kHistBins = 2048;     // histogram bins on the top 11 magnitude bits of a float
@@ -188,7 +189,7 @@ inline float decode_value(uint8_t sign, int h, float norm, const float *lev, int
 // ----- message layout.
 struct Layout {
   int L;
-  std::vector<int64_t> d, nblk, hdr_off, msg_off;
+  std::vector<int64_t> d, noct, hdr_off, msg_off;
   std::vector<int> S, planes;
   int64_t header_bytes, message_bytes;
   int64_t total_chunks;
@@ -204,7 +205,7 @@ Layout make_layout(int L, const int64_t *d, const int32_t *S) {
     lay.d.push_back(d[l]);
     lay.S.push_back(S[l]);
     lay.planes.push_back(1 + index_bits(S[l]));
-    lay.nblk.push_back((d[l] + kBlock - 1) / kBlock);
+    lay.noct.push_back((d[l] + kOctet - 1) / kOctet);
     lay.hdr_off.push_back(h);
     h += 4 * (1 + (int64_t)S[l]);
   }
@@ -213,7 +214,7 @@ Layout make_layout(int L, const int64_t *d, const int32_t *S) {
   int64_t chunks = 0;
   for (int l = 0; l < L; ++l) {
     lay.msg_off.push_back(off);
-    off += lay.nblk[l] * 32 * lay.planes[l];
+    off += lay.noct[l] * 256 * lay.planes[l];
     chunks += (d[l] + kChunk - 1) / kChunk;
   }
   lay.message_bytes = round_up(off, 256);
@@ -221,28 +222,37 @@ Layout make_layout(int L, const int64_t *d, const int32_t *S) {
   return lay;
 }
 
-// bit (plane p) of coordinate e of a layer inside a message: word p*4 + (e mod 4) of block e/256, bit (e mod 256)/4.
-inline uint64_t *word_ptr(uint8_t *layer_base, int planes, int64_t e, int p) {
-  return reinterpret_cast<uint64_t *>(layer_base + (e / kBlock) * 32 * planes) + (p * 4 + (e & 3));
+// Packed body of a layer (fixed width, c1 = 1 + b bits per coordinate, code = sign | index << 1).
+// Coordinates are grouped in octets of 8 blocks (2048 coordinates).  Inside an octet, "lane" i = (e mod 256)/4
+// owns the 32 coordinates {256*bb + 4*i + j : bb = 0..7, j = 0..3}, numbered jj = 4*bb + j; their codes form a
+// little-endian bit string of 32*c1 bits (code jj at bits [c1*jj, c1*jj + c1)), i.e. c1 32-bit words per lane.
+// Word r of lane i of octet O is the 32-bit word number O*64*c1 + r*64 + i of the layer's body, so that the 64
+// lanes' words r are contiguous.  Padding coordinates carry code 0.
+inline void set_bit(uint8_t *layer_base, int c1, int64_t e, int t, bool v) {
+  const int64_t O = e / kOctet;
+  const int bb = (int)((e % kOctet) / kBlock), i = (int)((e % kBlock) / 4), j = (int)(e % 4);
+  const int P = c1 * (4 * bb + j) + t;
+  uint32_t *w = reinterpret_cast<uint32_t *>(layer_base) + (O * 64 * c1 + (int64_t)(P / 32) * 64 + i);
+  if (v) *w |= (uint32_t)1 << (P % 32);
 }
-inline const uint64_t *word_ptr(const uint8_t *layer_base, int planes, int64_t e, int p) {
-  return reinterpret_cast<const uint64_t *>(layer_base + (e / kBlock) * 32 * planes) + (p * 4 + (e & 3));
+inline int get_bit(const uint8_t *layer_base, int c1, int64_t e, int t) {
+  const int64_t O = e / kOctet;
+  const int bb = (int)((e % kOctet) / kBlock), i = (int)((e % kBlock) / 4), j = (int)(e % 4);
+  const int P = c1 * (4 * bb + j) + t;
+  const uint32_t *w = reinterpret_cast<const uint32_t *>(layer_base) + (O * 64 * c1 + (int64_t)(P / 32) * 64 + i);
+  return (int)((*w >> (P % 32)) & 1u);
 }
-inline int bit_of(int64_t e) { return (int)((e % kBlock) / 4); }
 
 void put_code(uint8_t *layer_base, int planes, int64_t e, Code c) {
-  const int i = bit_of(e);
-  if (c.sign) *word_ptr(layer_base, planes, e, 0) |= (uint64_t)1 << i;
-  for (int p = 1; p < planes; ++p)
-    if ((c.h >> (p - 1)) & 1) *word_ptr(layer_base, planes, e, p) |= (uint64_t)1 << i;
+  set_bit(layer_base, planes, e, 0, c.sign != 0);
+  for (int p = 1; p < planes; ++p) set_bit(layer_base, planes, e, p, ((c.h >> (p - 1)) & 1) != 0);
 }
 
 Code get_code(const uint8_t *layer_base, int planes, int64_t e) {
-  const int i = bit_of(e);
   Code c;
-  c.sign = (uint8_t)((*word_ptr(layer_base, planes, e, 0) >> i) & 1);
+  c.sign = (uint8_t)get_bit(layer_base, planes, e, 0);
   int h = 0;
-  for (int p = 1; p < planes; ++p) h |= (int)((*word_ptr(layer_base, planes, e, p) >> i) & 1) << (p - 1);
+  for (int p = 1; p < planes; ++p) h |= get_bit(layer_base, planes, e, p) << (p - 1);
   c.h = (uint8_t)h;
   return c;
 }
@@ -318,11 +328,11 @@ void oracle_layout(int32_t L, const int64_t *d, const int32_t *S, int64_t *hdr_o
   for (int l = 0; l < L; ++l) { hdr_off[l] = lay.hdr_off[l]; msg_off[l] = lay.msg_off[l]; }
 }
 
-// pack / unpack the codes of one layer into its block region (region must hold nblk*32*planes bytes).
+// pack / unpack the codes of one layer into its body (region must hold ceil(d/2048)*256*planes bytes).
 void oracle_pack_layer(const uint8_t *sign, const uint8_t *index, int64_t d, int32_t S, uint8_t *region) {
   const int planes = 1 + index_bits(S);
-  const int64_t nblk = (d + kBlock - 1) / kBlock;
-  std::memset(region, 0, (size_t)(nblk * 32 * planes));
+  const int64_t noct = (d + kOctet - 1) / kOctet;
+  std::memset(region, 0, (size_t)(noct * 256 * planes));
   for (int64_t e = 0; e < d; ++e) { Code c; c.sign = sign[e]; c.h = index[e]; put_code(region, planes, e, c); }
 }
 void oracle_unpack_layer(const uint8_t *region, int64_t d, int32_t S, uint8_t *sign, uint8_t *index) {

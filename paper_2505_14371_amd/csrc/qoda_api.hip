@@ -23,7 +23,8 @@ struct qoda_ctx {
   std::vector<int> type_points;
   size_t message_bytes = 0, header_bytes = 0;
   int maxS = 0;
-  int maxSP = 0;   // largest 2^b over the layers: stride of the per-node decode tables in LDS
+  unsigned int planes_mask = 0;   // bit p set when some layer's code width is p bits
+  int maxSP = 0;   // largest 2^(1+b) over the layers: entries of a per-node decode table (indexed by code) in LDS
   // device memory owned by the context
   LayerMeta *d_meta = nullptr;
   int2 *d_tiles = nullptr;
@@ -218,7 +219,7 @@ int quantize_impl(qoda_ctx *c, int node0, int nnodes, const float *const *grad_f
     if (rc) return rc;
   }
   LAUNCH(c, kIdWriteHeader, s, launch_write_header(a, s));
-  LAUNCH(c, kIdQuantize, s, launch_quantize(a, s));
+  LAUNCH(c, kIdQuantize, s, launch_quantize(a, c->planes_mask, s));
   LAUNCH(c, kIdDeltaFinalize, s, launch_delta_finalize(a, s));
   return QODA_OK;
 }
@@ -259,7 +260,8 @@ int qoda_create(const qoda_config *cfg, qoda_ctx **out) {
     m.nchunks = (int)((d + kChunkCoords - 1) / kChunkCoords);
     chunks += m.nchunks;
     if (m.S > c->maxS) c->maxS = m.S;
-    if ((1 << (m.planes - 1)) > c->maxSP) c->maxSP = 1 << (m.planes - 1);
+    if ((1 << m.planes) > c->maxSP) c->maxSP = 1 << m.planes;
+    c->planes_mask |= 1u << m.planes;
     if (hdr > (1u << 30) || chunks > (1ll << 30)) { delete c; return QODA_EINVAL; }
   }
   if ((size_t)c->K * c->maxSP * sizeof(float) > 64 * 1024) { delete c; return QODA_EINVAL; }   // decode tables must fit LDS
@@ -267,7 +269,7 @@ int qoda_create(const qoda_config *cfg, qoda_ctx **out) {
   size_t off = c->header_bytes;
   for (int l = 0; l < c->L; ++l) {
     c->meta[l].body_off = (long long)off;
-    off += (size_t)c->meta[l].nblk * 32 * c->meta[l].planes;
+    off += (size_t)((c->meta[l].nblk + 7) / 8) * 256 * c->meta[l].planes;   // octets of 8 blocks, planes*256 bytes each
   }
   c->message_bytes = round_up(off, 256);
   c->G = (int)chunks;
@@ -492,7 +494,7 @@ int qoda_dequant_aggregate(qoda_ctx *c, const void *const *msgs_dev, float *cons
   rc = sync_table(c, c->t_mean, reinterpret_cast<const void *const *>(mean_out_dev), c->L, s);
   if (rc) return rc;
   a.mean_out = reinterpret_cast<float *const *>(c->t_mean.dev);
-  LAUNCH(c, kIdDecodeMean, s, launch_decode(a, false, (size_t)c->K * c->maxSP * sizeof(float), s));
+  LAUNCH(c, kIdDecodeMean, s, launch_decode(a, false, c->planes_mask, s));
   return QODA_OK;
 }
 
@@ -522,7 +524,7 @@ int qoda_step(qoda_ctx *c, const void *const *msgs_dev, const qoda_state *st, vo
   a.acc = st->acc_dev;
   a.eta_out = st->eta_dev;
   LAUNCH(c, kIdStepScalars, s, launch_step_scalars(a, s));
-  LAUNCH(c, kIdDecodeUpdate, s, launch_decode(a, true, (size_t)c->K * c->maxSP * sizeof(float), s));
+  LAUNCH(c, kIdDecodeUpdate, s, launch_decode(a, true, c->planes_mask, s));
   return QODA_OK;
 }
 

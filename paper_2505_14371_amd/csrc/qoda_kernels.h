@@ -81,10 +81,10 @@ hipError_t launch_zero_u32(unsigned int *p, size_t n, hipStream_t s);
 hipError_t launch_sumsq(const Dev &a, bool with_hist, hipStream_t s);
 hipError_t launch_norm_finalize(const Dev &a, hipStream_t s);
 hipError_t launch_write_header(const Dev &a, hipStream_t s);
-hipError_t launch_quantize(const Dev &a, hipStream_t s);
+hipError_t launch_quantize(const Dev &a, unsigned int planes_mask, hipStream_t s);
 hipError_t launch_delta_finalize(const Dev &a, hipStream_t s);
 hipError_t launch_step_scalars(const Dev &a, hipStream_t s);
-hipError_t launch_decode(const Dev &a, bool update, size_t lds_bytes, hipStream_t s);
+hipError_t launch_decode(const Dev &a, bool update, unsigned int planes_mask, hipStream_t s);
 hipError_t launch_fit_typemax(const Dev &a, hipStream_t s);
 hipError_t launch_fit_pool(const Dev &a, hipStream_t s);
 hipError_t launch_fit_dp(const Dev &a, hipStream_t s);

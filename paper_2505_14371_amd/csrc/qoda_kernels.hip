@@ -1,11 +1,12 @@
-// gfx950 kernels of the QODA hot path (arXiv 2505.14371): per-layer norms, stochastic quantization + bit-plane
+// gfx950 kernels of the QODA hot path (arXiv 2505.14371): per-layer norms, stochastic quantization + code
 // packing, fused decode + K-way mean + optimistic dual averaging update, and the histogram level fit.
 //
 // Execution shape used throughout: one workgroup = 256 threads = 4 wave64 = one tile of 16384 coordinates of
 // one (node, layer).  Wave w owns the 16 consecutive 256-coordinate blocks 16w..16w+15 of the tile; in a block,
-// lane i owns coordinates 4i..4i+3 (one 128-bit load, 1 KB contiguous per wave).  A wave-wide ballot of one
-// component j is therefore exactly one 64-bit word of the packed message, and thread t = 64w+i is reduction
-// slot t of the fixed-order fp64 sums.
+// lane i owns coordinates 4i..4i+3 (one 128-bit load, 1 KB contiguous per wave).  Thread t = 64w+i is reduction
+// slot t of the fixed-order fp64 sums.  The packed message is lane-local: the codes of the 32 coordinates a lane
+// owns in 8 consecutive blocks (an octet) are shifted into C1 = 1 + b 32-bit words per lane, and word r of the
+// 64 lanes is one contiguous 256-byte store.
 //
 // Arithmetic that feeds an integer decision (level index, rounding direction, packed bits, histogram bin) is
 // written as single IEEE operations with contraction off, so that it has one well-defined result.
@@ -117,25 +118,50 @@ __device__ __forceinline__ void store4(float *__restrict__ v, long long e, long 
   }
 }
 
-// Broadcast the 64-bit value held by lane `lane` (a compile-time constant after unrolling) to the whole wave.
-__device__ __forceinline__ unsigned long long bcast64(unsigned long long v, int lane) {
-  const unsigned int lo = (unsigned int)__builtin_amdgcn_readlane((int)(unsigned int)v, lane);
-  const unsigned int hi = (unsigned int)__builtin_amdgcn_readlane((int)(unsigned int)(v >> 32), lane);
-  return ((unsigned long long)hi << 32) | lo;
+// ---- packed lane records (message body).  A lane's 32 codes of an octet (8 blocks x 4 coordinates, code
+// number jj = 4*block + component, C1 bits each: sign | index << 1) form a little-endian bit string kept in C1
+// 32-bit registers.  jj is a compile-time constant wherever these are called (fully unrolled loops), so every
+// shift below is an immediate.
+template <int C1>
+__device__ __forceinline__ void insert_code(unsigned int (&D)[C1], unsigned int code, int jj) {
+  const int pos = C1 * jj, r = pos >> 5, sh = pos & 31;
+  D[r] |= code << sh;
+  if (sh + C1 > 32) D[r + 1] |= code >> (32 - sh);
 }
 
-// Decode component j of this lane from one packed block whose 4*PLANES words sit one per lane in `mw`
-// (lane p*4+j holds plane p of component j).  A wave-uniform 64-bit plane is turned back into one bit per lane
-// by a mask-select; the level index becomes a byte offset into a table of 2^(PLANES-1) floats (entries past
-// S-1 repeat the last level, which is the clamp of an out-of-range index).
-template <int PLANES>
-__device__ __forceinline__ float decode_component(unsigned long long mw, int j, const float *table) {
-  unsigned int off = 0;
+template <int C1>
+__device__ __forceinline__ unsigned int extract_code(const unsigned int (&D)[C1], int jj) {
+  const int pos = C1 * jj, r = pos >> 5, sh = pos & 31;
+  unsigned int v = D[r] >> sh;
+  if (sh + C1 > 32) v |= D[r + 1] << (32 - sh);
+  return v & ((1u << C1) - 1u);
+}
+
+// Shift a C1-word little-endian bit string right by 8*C1 bits (one block pair's worth of codes).
+template <int C1>
+__device__ __forceinline__ void shift_out_pair(unsigned int (&D)[C1]) {
+  constexpr int wq = (8 * C1) >> 5, bq = (8 * C1) & 31;
 #pragma unroll
-  for (int p = 1; p < PLANES; ++p)
-    off |= __builtin_amdgcn_inverse_ballot_w64(bcast64(mw, p * 4 + j)) ? (4u << (p - 1)) : 0u;
-  const float t = *reinterpret_cast<const float *>(reinterpret_cast<const char *>(table) + off);
-  return __builtin_amdgcn_inverse_ballot_w64(bcast64(mw, j)) ? -t : t;
+  for (int r = 0; r < C1; ++r) {
+    const unsigned int lo = (r + wq < C1) ? D[r + wq] : 0u;
+    const unsigned int hi = (r + wq + 1 < C1) ? D[r + wq + 1] : 0u;
+    D[r] = (bq == 0) ? lo : ((lo >> bq) | (hi << (32 - bq)));
+  }
+}
+
+// The C1 record words of lane i of one octet: word r is the 32-bit word r*64 + i of the octet's 256*C1 bytes.
+template <int C1>
+__device__ __forceinline__ void load_record(const unsigned char *octet, int i, unsigned int (&D)[C1]) {
+  const auto *g = reinterpret_cast<const __attribute__((address_space(1))) unsigned int *>(as_global(octet));
+#pragma unroll
+  for (int r = 0; r < C1; ++r) D[r] = g[r * 64 + i];
+}
+
+template <int C1>
+__device__ __forceinline__ void store_record(unsigned char *octet, int i, const unsigned int (&D)[C1]) {
+  auto *g = (__attribute__((address_space(1))) unsigned int *)octet;
+#pragma unroll
+  for (int r = 0; r < C1; ++r) g[r * 64 + i] = D[r];
 }
 
 }  // namespace
@@ -244,129 +270,146 @@ __global__ void k_write_header(Dev a) {
 // ------------------------------------------------------------------------------------------------ pass 2
 // Quantize + pack one tile (Sec. 3.1, Sec. 3.2) and accumulate the squared distance to the node's previous
 // decoded message (the step-size term of eq. (general_stepsize)).
-// Place a wave-uniform 64-bit word into lane `lane` (compile-time constant) of a per-lane 64-bit register.
-__device__ __forceinline__ void put_word(unsigned int &lo, unsigned int &hi, unsigned long long word, int lane) {
-  const bool me = (int)(threadIdx.x & 63) == lane;
-  lo = me ? (unsigned int)word : lo;
-  hi = me ? (unsigned int)(word >> 32) : hi;
+// One octet (8 blocks = 2048 coordinates) of one (node, layer) for one wave: 4 block pairs, each with one
+// generator call and 8 coordinates per lane.  The lane record is built as a shift register: every pair shifts it
+// right by 8*C1 bits and writes its 8 codes into the top quarter, so that after four pairs pair 0 sits at bit 0;
+// the previous message's record is consumed from the bottom the same way.  The pair loop is deliberately not
+// unrolled: unrolled, the compiler interleaves the pairs and needs more than 256 registers.
+// FAST: the whole octet lies inside the layer (no bounds checks anywhere).
+template <int C1, bool FAST>
+__device__ __forceinline__ void quantize_octet(const Dev &a, const LayerMeta &m, int l, int k, long long O,
+                                               const float *__restrict__ v, unsigned char *body,
+                                               const unsigned char *prevbody, float inv, float norm,
+                                               const unsigned short *lut, const float4 *tab, const float *tprev, int i,
+                                               double &acc) {
+  const unsigned int k0 = (unsigned int)a.seed, k1 = (unsigned int)(a.seed >> 32);
+  unsigned int D[C1], Dp[C1];
+#pragma unroll
+  for (int r = 0; r < C1; ++r) { D[r] = 0u; Dp[r] = 0u; }
+  if (prevbody != nullptr) load_record<C1>(prevbody + O * 256 * C1, i, Dp);
+#pragma unroll 1
+  for (int pp = 0; pp < 4; ++pp) {
+    const long long B0 = O * 8 + 2 * pp;   // block index inside the layer
+    shift_out_pair<C1>(D);
+    if (FAST || B0 < m.nblk) {
+      unsigned int o[4];
+      philox4x32_10((unsigned int)((B0 >> 1) * 64 + i), (unsigned int)l, a.round, (unsigned int)k, k0, k1, o);
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        const long long B = B0 + half;
+        if (FAST || B < m.nblk) {
+          const long long e = B * kBlockCoords + 4 * i;
+          float x[4];
+          if (FAST) {
+            const v4f q = *reinterpret_cast<const __attribute__((address_space(1))) v4f *>(as_global(v) + e);
+            x[0] = q.x; x[1] = q.y; x[2] = q.z; x[3] = q.w;
+          } else {
+            load4(v, e, m.d, x);
+          }
+          // level search (Sec. 3.1): the table entry of u's bin gives tau at the bin's lower edge and how many
+          // further levels lie inside the bin; only lanes in such a bin walk on.
+          float u[4];
+          unsigned int ent[4];
+          int tau[4];
+          float4 lv[4];                                      // {l_tau, 1/gap, l_tau+1, norm*l_tau}
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            u[j] = fminf(fabsf(x[j]) * inv, 1.0f);
+            ent[j] = lut[f2u(u[j]) >> 20];
+          }
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            tau[j] = (int)(ent[j] & 0xFFu);
+            lv[j] = tab[tau[j]];
+          }
+          if (__ballot(((ent[0] | ent[1] | ent[2] | ent[3]) >> 8) != 0u) != 0ull) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              for (int n = (int)(ent[j] >> 8); n > 0 && lv[j].z <= u[j]; --n) { ++tau[j]; lv[j] = tab[tau[j]]; }
+          }
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int jl = 4 * half + j;                       // position of the coordinate inside the pair
+            const unsigned int w16 = half ? (o[j] >> 16) : (o[j] & 0xFFFFu);
+            const float xi = (u[j] - lv[j].x) * lv[j].y;
+            // (w16 + 0.5) < xi * 65536  <=>  w16 < xi * 65536 - 0.5 : the scaling by 2^16 is exact, and the
+            // subtraction is exact whenever its result is not negative, so one fused operation decides the same.
+            const bool up = (float)w16 < __builtin_fmaf(xi, 65536.0f, -0.5f);
+            const unsigned int h = (unsigned int)tau[j] + (up ? 1u : 0u);
+            const float mag = up ? norm * lv[j].z : lv[j].w;   // norm * l_h, the value the decoder will rebuild
+            const float cur = __builtin_copysignf(mag, x[j]);
+            insert_code<C1>(D, (h << 1) | (f2u(x[j]) >> 31), 24 + jl);
+            const float pv = tprev[extract_code<C1>(Dp, jl)];  // all zero when there is no previous message
+            const float diff = cur - pv;
+            acc = __builtin_fma((double)diff, (double)diff, acc);
+          }
+        }
+      }
+    }
+    shift_out_pair<C1>(Dp);
+  }
+  store_record<C1>(body + O * 256 * C1, i, D);
 }
 
-template <int PLANES>
+template <int C1>
 __device__ __forceinline__ void quantize_tile(const Dev &a, const LayerMeta &m, int l, int k, int chunk,
                                               const unsigned short *lut, const float4 *tab, const float *tprev,
                                               double *red) {
-  constexpr int W = 4 * PLANES;   // 64-bit words per packed block
   const int t = threadIdx.x;
   const int w = __builtin_amdgcn_readfirstlane(t >> 6);
   const int i = t & 63;
   const float *__restrict__ v = a.grad[(size_t)k * a.L + l];
-  unsigned char *msg = a.msg[k] + m.body_off;
-  const unsigned char *prev = (a.prev != nullptr && a.prev[k] != nullptr) ? a.prev[k] + m.body_off : nullptr;
+  unsigned char *body = a.msg[k] + m.body_off;
+  const unsigned char *prevbody = (a.prev != nullptr && a.prev[k] != nullptr) ? a.prev[k] + m.body_off : nullptr;
   const float inv = a.inv[(size_t)k * a.L + l];
   const float norm = a.norm[(size_t)k * a.L + l];
-  const unsigned int k0 = (unsigned int)a.seed, k1 = (unsigned int)(a.seed >> 32);
+  const long long noct = (m.nblk + 7) >> 3;
   double acc = 0.0;
-  for (int pair = 0; pair < 8; ++pair) {
-    const long long B0 = (long long)chunk * 64 + w * 16 + 2 * pair;   // block index inside the layer
-    if (B0 >= m.nblk) break;
-    unsigned int o[4];
-    philox4x32_10((unsigned int)((B0 >> 1) * 64 + i), (unsigned int)l, a.round, (unsigned int)k, k0, k1, o);
-#pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      const long long B = B0 + half;
-      if (B >= m.nblk) break;
-      const long long e = B * kBlockCoords + 4 * i;
-      float x[4];
-      load4(v, e, m.d, x);
-      unsigned long long pw = 0ull;   // lane q < W holds word q of the previous message's block
-      if (prev != nullptr && i < W)
-        pw = reinterpret_cast<const __attribute__((address_space(1))) unsigned long long *>(as_global(prev) + B * 32 * PLANES)[i];
-      // level search (Sec. 3.1): the table entry of u's bin gives tau at the bin's lower edge and how many
-      // further levels lie inside the bin; only lanes in such a bin walk on.
-      float u[4];
-      unsigned int ent[4];
-      int tau[4];
-      float4 lv[4];                                          // {l_tau, 1/gap, l_tau+1, norm*l_tau}
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        u[j] = fminf(fabsf(x[j]) * inv, 1.0f);
-        ent[j] = lut[f2u(u[j]) >> 20];
-      }
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        tau[j] = (int)(ent[j] & 0xFFu);
-        lv[j] = tab[tau[j]];
-      }
-      if (__ballot(((ent[0] | ent[1] | ent[2] | ent[3]) >> 8) != 0u) != 0ull) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          for (int n = (int)(ent[j] >> 8); n > 0 && lv[j].z <= u[j]; --n) { ++tau[j]; lv[j] = tab[tau[j]]; }
-      }
-      unsigned int mlo = 0u, mhi = 0u;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const unsigned int w16 = half ? (o[j] >> 16) : (o[j] & 0xFFFFu);
-        const float xi = (u[j] - lv[j].x) * lv[j].y;
-        // (w16 + 0.5) < xi * 65536  <=>  w16 < xi * 65536 - 0.5 : the scaling by 2^16 is exact, and the
-        // subtraction is exact whenever its result is not negative, so one fused operation decides the same.
-        const bool up = (float)w16 < __builtin_fmaf(xi, 65536.0f, -0.5f);
-        const unsigned int h = (unsigned int)tau[j] + (up ? 1u : 0u);
-        const float mag = up ? norm * lv[j].z : lv[j].w;     // norm * l_h, the value the decoder will rebuild
-        const float cur = __builtin_copysignf(mag, x[j]);
-        const float pv = (prev != nullptr) ? decode_component<PLANES>(pw, j, tprev) : 0.0f;
-        const float diff = cur - pv;
-        acc = __builtin_fma((double)diff, (double)diff, acc);
-        put_word(mlo, mhi, __ballot((int)f2u(x[j]) < 0), j);
-#pragma unroll
-        for (int p = 1; p < PLANES; ++p) put_word(mlo, mhi, __ballot((h & (1u << (p - 1))) != 0u), p * 4 + j);
-      }
-      if (i < W)
-        reinterpret_cast<__attribute__((address_space(1))) unsigned long long *>(
-            (__attribute__((address_space(1))) unsigned char *)msg + B * 32 * PLANES)[i] = ((unsigned long long)mhi << 32) | mlo;
-    }
+  for (int oo = 0; oo < 2; ++oo) {
+    const long long O = (long long)chunk * 8 + w * 2 + oo;   // octet index inside the layer
+    if (O >= noct) break;
+    if ((O + 1) * 2048 <= m.d)
+      quantize_octet<C1, true>(a, m, l, k, O, v, body, prevbody, inv, norm, lut, tab, tprev, i, acc);
+    else
+      quantize_octet<C1, false>(a, m, l, k, O, v, body, prevbody, inv, norm, lut, tab, tprev, i, acc);
   }
   const double total = block_tree(acc, red);
   if (t == 0) a.dpartial[(size_t)k * a.G + blockIdx.x] = total;
 }
 
+template <int C1>
 __global__ void __launch_bounds__(kThreads) k_quantize(Dev a) {
   __shared__ unsigned short lut[kLutSize];
   __shared__ float4 tab[kMaxPoints];
-  __shared__ float tprev[kMaxPoints];
+  __shared__ float tprev[2 * kMaxPoints];   // previous message's decode table indexed by code = sign | h << 1
   __shared__ double red[kThreads];
   const int2 tile = a.tiles[blockIdx.x];
   const int l = tile.x;
   const int k = a.node0 + blockIdx.y;
   const LayerMeta m = a.meta[l];
+  if (m.planes != C1) return;   // layers of another code width are served by another instantiation
   const int t = threadIdx.x;
   const float *lev = a.lev + (size_t)m.type * kMaxPoints;
   const float *rg = a.rgap + (size_t)m.type * kMaxPoints;
   reinterpret_cast<uint2 *>(lut)[t] = reinterpret_cast<const uint2 *>(a.lut + (size_t)m.type * kLutSize)[t];
   const float norm = a.norm[(size_t)k * a.L + l];
   const unsigned char *prevmsg = (a.prev != nullptr) ? a.prev[k] : nullptr;
-  if (t < (1 << (m.planes - 1))) {       // tables padded to 2^b entries; entries past S-1 repeat the last level
-    const int tj = min(t, m.S - 1);
-    const float lj = lev[tj];
-    const float ln = (tj + 1 < m.S) ? lev[tj + 1] : 1.0f;
-    tab[t] = make_float4(lj, rg[tj], ln, norm * lj);
+  if (t < m.S) {
+    const float lj = lev[t];
+    const float ln = (t + 1 < m.S) ? lev[t + 1] : 1.0f;
+    tab[t] = make_float4(lj, rg[t], ln, norm * lj);
+  }
+  for (int c = t; c < (1 << m.planes); c += kThreads) {   // codes past S-1 decode as the last level
     float pv = 0.0f;
     if (prevmsg) {
       const float *hp = reinterpret_cast<const float *>(prevmsg + m.hdr_off);
-      pv = hp[0] * hp[1 + tj];
+      const float mag = hp[0] * hp[1 + min(c >> 1, m.S - 1)];
+      pv = (c & 1) ? -mag : mag;
     }
-    tprev[t] = pv;
+    tprev[c] = pv;
   }
   __syncthreads();
-  switch (m.planes) {
-    case 2: quantize_tile<2>(a, m, l, k, tile.y, lut, tab, tprev, red); break;
-    case 3: quantize_tile<3>(a, m, l, k, tile.y, lut, tab, tprev, red); break;
-    case 4: quantize_tile<4>(a, m, l, k, tile.y, lut, tab, tprev, red); break;
-    case 5: quantize_tile<5>(a, m, l, k, tile.y, lut, tab, tprev, red); break;
-    case 6: quantize_tile<6>(a, m, l, k, tile.y, lut, tab, tprev, red); break;
-    case 7: quantize_tile<7>(a, m, l, k, tile.y, lut, tab, tprev, red); break;
-    case 8: quantize_tile<8>(a, m, l, k, tile.y, lut, tab, tprev, red); break;
-    default: quantize_tile<9>(a, m, l, k, tile.y, lut, tab, tprev, red); break;
-  }
+  quantize_tile<C1>(a, m, l, k, tile.y, lut, tab, tprev, red);
 }
 
 // delta_k: slot j takes the node's tiles j, j+256, ... (all layers, in order), then the halving tree.
@@ -396,92 +439,91 @@ __global__ void k_step_scalars(Dev a) {
 }
 
 // DECODE + K-way mean (+ eq. (ODA) update when UPDATE): one pass over Y, X_1 and the K messages.
-template <int PLANES, bool UPDATE>
+// One octet per wave at a time: 32 running sums per lane, K records of C1 words, then 8 blocks of state.
+template <int C1, bool UPDATE, bool FAST>
+__device__ __forceinline__ void decode_octet(const Dev &a, const LayerMeta &m, int l, long long O, const float *T, int i,
+                                             float eta, float gamma) {
+  constexpr int TS = 1 << C1;   // table entries per node, indexed by code = sign | h << 1
+  const long long boff = m.body_off + O * 256 * C1;
+  float sum[32];
+  unsigned int Dc[C1], Dn[C1];
+  load_record<C1>(a.msgs_in[0] + boff, i, Dc);
+  for (int k = 0; k < a.K; ++k) {
+#pragma unroll
+    for (int r = 0; r < C1; ++r) Dn[r] = 0u;
+    if (k + 1 < a.K) load_record<C1>(a.msgs_in[k + 1] + boff, i, Dn);
+    const float *Tk = T + k * TS;
+#pragma unroll
+    for (int jj = 0; jj < 32; ++jj) {
+      const float val = Tk[extract_code<C1>(Dc, jj)];
+      sum[jj] = (k == 0) ? val : sum[jj] + val;
+    }
+#pragma unroll
+    for (int r = 0; r < C1; ++r) Dc[r] = Dn[r];
+  }
+#pragma unroll
+  for (int bb = 0; bb < 8; ++bb) {
+    const long long B = O * 8 + bb;
+    if (FAST || B < m.nblk) {
+      const long long e = B * kBlockCoords + 4 * i;
+      const long long dlim = FAST ? e + 4 : m.d;   // FAST: the whole block is inside the layer
+      float mean[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) mean[j] = sum[4 * bb + j] * a.invK;
+      if (!UPDATE) {
+        store4(a.mean_out[l], e, dlim, mean);
+      } else {
+        float y[4], x1[4], xn[4], xh[4];
+        load4(a.y[l], e, dlim, y);
+        load4(a.x1[l], e, dlim, x1);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          y[j] = y[j] - mean[j];
+          const float ey = eta * y[j];
+          xn[j] = x1[j] + ey;
+          const float gm = gamma * mean[j];
+          xh[j] = xn[j] - gm;
+        }
+        store4(a.y[l], e, dlim, y);
+        store4(a.x_half[l], e, dlim, xh);
+        if (a.x_next) store4(a.x_next[l], e, dlim, xn);
+      }
+    }
+  }
+}
+
+template <int C1, bool UPDATE>
 __device__ __forceinline__ void decode_tile(const Dev &a, const LayerMeta &m, int l, int chunk, const float *T) {
-  constexpr int W = 4 * PLANES;
-  constexpr int SP = 1 << (PLANES - 1);   // table stride per node
-  constexpr int NB = 8;                   // nodes whose words are fetched together
   const int t = threadIdx.x;
   const int w = __builtin_amdgcn_readfirstlane(t >> 6);
   const int i = t & 63;
   float eta = 0.0f, gamma = 0.0f;
   if (UPDATE) { eta = a.eta[0]; gamma = a.eta[1]; }
-  for (int s = 0; s < 16; ++s) {
-    const long long B = (long long)chunk * 64 + w * 16 + s;
-    if (B >= m.nblk) break;
-    const long long e = B * kBlockCoords + 4 * i;
-    float y[4], x1[4];
-    if (UPDATE) {
-      load4(a.y[l], e, m.d, y);
-      load4(a.x1[l], e, m.d, x1);
-    }
-    float sum[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-    for (int kb = 0; kb < a.K; kb += NB) {
-      unsigned long long mw[NB];
-#pragma unroll
-      for (int q = 0; q < NB; ++q) {
-        mw[q] = 0ull;
-        if (kb + q < a.K && i < W)
-          mw[q] = reinterpret_cast<const __attribute__((address_space(1))) unsigned long long *>(
-              as_global(a.msgs_in[kb + q]) + m.body_off + B * 32 * PLANES)[i];
-      }
-#pragma unroll
-      for (int q = 0; q < NB; ++q) {
-        if (kb + q < a.K) {
-          const float *Tk = T + (kb + q) * SP;
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const float val = decode_component<PLANES>(mw[q], j, Tk);
-            sum[j] = (kb + q == 0) ? val : sum[j] + val;
-          }
-        }
-      }
-    }
-    float mean[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) mean[j] = sum[j] * a.invK;
-    if (!UPDATE) {
-      store4(a.mean_out[l], e, m.d, mean);
-    } else {
-      float xn[4], xh[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        y[j] = y[j] - mean[j];
-        const float ey = eta * y[j];
-        xn[j] = x1[j] + ey;
-        const float gm = gamma * mean[j];
-        xh[j] = xn[j] - gm;
-      }
-      store4(a.y[l], e, m.d, y);
-      store4(a.x_half[l], e, m.d, xh);
-      if (a.x_next) store4(a.x_next[l], e, m.d, xn);
-    }
+  const long long noct = (m.nblk + 7) >> 3;
+  for (int oo = 0; oo < 2; ++oo) {
+    const long long O = (long long)chunk * 8 + w * 2 + oo;
+    if (O >= noct) break;
+    if ((O + 1) * 2048 <= m.d) decode_octet<C1, UPDATE, true>(a, m, l, O, T, i, eta, gamma);
+    else decode_octet<C1, UPDATE, false>(a, m, l, O, T, i, eta, gamma);
   }
 }
 
-template <bool UPDATE>
+template <int C1, bool UPDATE>
 __global__ void __launch_bounds__(kThreads) k_decode(Dev a) {
-  extern __shared__ float T[];   // [K][2^b]: norm_k * level_h of this layer, from the K message headers
+  extern __shared__ float T[];   // [K][2^C1]: +-norm_k * level_h of this layer, from the K message headers
   const int2 tile = a.tiles[blockIdx.x];
   const int l = tile.x;
   const LayerMeta m = a.meta[l];
-  const int SP = 1 << (m.planes - 1);
-  for (int idx = threadIdx.x; idx < a.K * SP; idx += kThreads) {
-    const int k = idx / SP, h = min(idx - k * SP, m.S - 1);
+  if (m.planes != C1) return;
+  const int TS = 1 << C1;
+  for (int idx = threadIdx.x; idx < a.K * TS; idx += kThreads) {
+    const int k = idx / TS, c = idx - k * TS;
     const float *hp = reinterpret_cast<const float *>(a.msgs_in[k] + m.hdr_off);
-    T[idx] = hp[0] * hp[1 + h];
+    const float mag = hp[0] * hp[1 + min(c >> 1, m.S - 1)];
+    T[idx] = (c & 1) ? -mag : mag;
   }
   __syncthreads();
-  switch (m.planes) {
-    case 2: decode_tile<2, UPDATE>(a, m, l, tile.y, T); break;
-    case 3: decode_tile<3, UPDATE>(a, m, l, tile.y, T); break;
-    case 4: decode_tile<4, UPDATE>(a, m, l, tile.y, T); break;
-    case 5: decode_tile<5, UPDATE>(a, m, l, tile.y, T); break;
-    case 6: decode_tile<6, UPDATE>(a, m, l, tile.y, T); break;
-    case 7: decode_tile<7, UPDATE>(a, m, l, tile.y, T); break;
-    case 8: decode_tile<8, UPDATE>(a, m, l, tile.y, T); break;
-    default: decode_tile<9, UPDATE>(a, m, l, tile.y, T); break;
-  }
+  decode_tile<C1, UPDATE>(a, m, l, tile.y, T);
 }
 
 // ------------------------------------------------------------------------------------------------ level fit
@@ -695,9 +737,18 @@ hipError_t launch_write_header(const Dev &a, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_quantize(const Dev &a, hipStream_t s) {
+// planes_mask: bit p set when some layer has code width p (2..9); one launch per width present.
+hipError_t launch_quantize(const Dev &a, unsigned int planes_mask, hipStream_t s) {
   if (a.G == 0 || a.nnodes == 0) return hipSuccess;
-  hipLaunchKernelGGL(k_quantize, dim3(a.G, a.nnodes), dim3(kThreads), 0, s, a);
+  const dim3 grid(a.G, a.nnodes), block(kThreads);
+  if (planes_mask & (1u << 2)) hipLaunchKernelGGL(k_quantize<2>, grid, block, 0, s, a);
+  if (planes_mask & (1u << 3)) hipLaunchKernelGGL(k_quantize<3>, grid, block, 0, s, a);
+  if (planes_mask & (1u << 4)) hipLaunchKernelGGL(k_quantize<4>, grid, block, 0, s, a);
+  if (planes_mask & (1u << 5)) hipLaunchKernelGGL(k_quantize<5>, grid, block, 0, s, a);
+  if (planes_mask & (1u << 6)) hipLaunchKernelGGL(k_quantize<6>, grid, block, 0, s, a);
+  if (planes_mask & (1u << 7)) hipLaunchKernelGGL(k_quantize<7>, grid, block, 0, s, a);
+  if (planes_mask & (1u << 8)) hipLaunchKernelGGL(k_quantize<8>, grid, block, 0, s, a);
+  if (planes_mask & (1u << 9)) hipLaunchKernelGGL(k_quantize<9>, grid, block, 0, s, a);
   return hipGetLastError();
 }
 
@@ -711,10 +762,22 @@ hipError_t launch_step_scalars(const Dev &a, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_decode(const Dev &a, bool update, size_t lds_bytes, hipStream_t s) {
+template <int C1>
+static void launch_decode_width(const Dev &a, bool update, size_t lds_bytes, hipStream_t s) {
+  if (update) hipLaunchKernelGGL((k_decode<C1, true>), dim3(a.G), dim3(kThreads), lds_bytes, s, a);
+  else hipLaunchKernelGGL((k_decode<C1, false>), dim3(a.G), dim3(kThreads), lds_bytes, s, a);
+}
+
+hipError_t launch_decode(const Dev &a, bool update, unsigned int planes_mask, hipStream_t s) {
   if (a.G == 0) return hipSuccess;
-  if (update) hipLaunchKernelGGL(k_decode<true>, dim3(a.G), dim3(kThreads), lds_bytes, s, a);
-  else hipLaunchKernelGGL(k_decode<false>, dim3(a.G), dim3(kThreads), lds_bytes, s, a);
+  if (planes_mask & (1u << 2)) launch_decode_width<2>(a, update, (size_t)a.K * 4 * sizeof(float), s);
+  if (planes_mask & (1u << 3)) launch_decode_width<3>(a, update, (size_t)a.K * 8 * sizeof(float), s);
+  if (planes_mask & (1u << 4)) launch_decode_width<4>(a, update, (size_t)a.K * 16 * sizeof(float), s);
+  if (planes_mask & (1u << 5)) launch_decode_width<5>(a, update, (size_t)a.K * 32 * sizeof(float), s);
+  if (planes_mask & (1u << 6)) launch_decode_width<6>(a, update, (size_t)a.K * 64 * sizeof(float), s);
+  if (planes_mask & (1u << 7)) launch_decode_width<7>(a, update, (size_t)a.K * 128 * sizeof(float), s);
+  if (planes_mask & (1u << 8)) launch_decode_width<8>(a, update, (size_t)a.K * 256 * sizeof(float), s);
+  if (planes_mask & (1u << 9)) launch_decode_width<9>(a, update, (size_t)a.K * 512 * sizeof(float), s);
   return hipGetLastError();
 }
 

@@ -1,5 +1,5 @@
 """Pins for the oracle's fixed-width ENCODE / DECODE (Sec. 3.2, App. C.1) and the K-way mean (Alg. 1 l.15-17).
-The bit layout is this build's own (the paper gives none), so its pin is the round trip plus byte accounting;
+The bit layout is this build's own (the paper gives none), so its pin is the round trip plus bit accounting;
 DECODE is pinned to the definition +-||v|| * l_h and the mean to the textbook mean."""
 import numpy as np
 import pytest
@@ -20,29 +20,39 @@ def test_pack_unpack_round_trip(oracle, S, d):
     region = oracle.pack_layer(sign, idx, S)
     b = max(1, int(np.ceil(np.log2(S))))
     assert oracle.index_bits(S) == b
-    assert region.size == ((d + 255) // 256) * 32 * (1 + b)          # (1 + b) bits per padded coordinate
+    assert region.size == ((d + 2047) // 2048) * 256 * (1 + b)       # (1 + b) bits per coordinate, padded to 2048
     s2, i2 = oracle.unpack_layer(region, d, S)
     assert np.array_equal(s2, sign) and np.array_equal(i2, idx)
-    # population count of every plane equals the number of set bits it has to carry: nothing is lost or doubled
-    words = region.view(np.uint64).reshape(-1, 1 + b, 4)
-    assert int(np.unpackbits(words[:, 0].copy().view(np.uint8)).sum()) == int(sign.sum())
-    for p in range(b):
-        assert int(np.unpackbits(words[:, 1 + p].copy().view(np.uint8)).sum()) == int(((idx >> p) & 1).sum())
+    # the body carries exactly the set bits of the codes: nothing is lost, doubled, or written into padding
+    want = int(sign.sum()) + sum(int(((idx >> p) & 1).sum()) for p in range(b))
+    assert int(np.unpackbits(region).sum()) == want
 
 
 def test_bit_position_of_a_single_coordinate(oracle):
-    # coordinate e sits in block e/256, word (plane*4 + e%4), bit (e%256)/4: the ballot of component e%4
-    S, d = 8, 1000
-    for e in [0, 1, 5, 255, 256, 700, 999]:
+    """Coordinate e = 2048*O + 256*bb + 4*i + j is code number jj = 4*bb + j of lane i in octet O; the lane's 32
+    codes form a little-endian bit string whose 32-bit word r is word O*64*c1 + r*64 + i of the body."""
+    S, d, c1 = 8, 5000, 4
+    for e in [0, 1, 5, 255, 256, 700, 2047, 2048, 4999]:
         sign = np.zeros(d, np.uint8)
         idx = np.zeros(d, np.uint8)
         sign[e] = 1
-        idx[e] = 5                                                      # bits 0 and 2
-        words = oracle.pack_layer(sign, idx, S).view(np.uint64).reshape(-1, 4, 4)
+        idx[e] = 5                                                      # code = 1 | 5 << 1 = 0b1011
+        words = oracle.pack_layer(sign, idx, S).view(np.uint32)
+        O, bb, i, j = e // 2048, (e % 2048) // 256, (e % 256) // 4, e % 4
+        pos = c1 * (4 * bb + j)
         want = np.zeros_like(words)
-        for plane in (0, 1, 3):
-            want[e // 256, plane, e % 4] = np.uint64(1) << np.uint64((e % 256) // 4)
+        want[O * 64 * c1 + (pos // 32) * 64 + i] = np.uint32(0b1011) << np.uint32(pos % 32)
         assert np.array_equal(words, want)
+    # a 5-bit code that straddles two 32-bit words (S = 16: jj = 6 sits at bits 30..34)
+    S, c1, e = 16, 5, 256 * 1 + 4 * 9 + 2                               # bb = 1, i = 9, j = 2 -> jj = 6
+    sign = np.zeros(3000, np.uint8)
+    idx = np.zeros(3000, np.uint8)
+    sign[e], idx[e] = 1, 15                                             # code = 0b11111
+    words = oracle.pack_layer(sign, idx, S).view(np.uint32)
+    want = np.zeros_like(words)
+    want[0 * 64 + 9] = np.uint32(0b11) << np.uint32(30)
+    want[1 * 64 + 9] = np.uint32(0b111)
+    assert np.array_equal(words, want)
 
 
 def test_message_layout_and_size(oracle):
@@ -53,11 +63,11 @@ def test_message_layout_and_size(oracle):
     hb = oracle.header_bytes(sizes, points)
     assert hb == 1280 and hb % 256 == 0                                # 144 + 4*257 = 1172 -> 1280
     planes = [4, 3, 5, 3, 9]
-    nblk = [4, 0, 1, 274, 1]
+    noct = [1, 0, 1, 35, 1]
     want = hb
     for l in range(5):
         assert off[l] == want
-        want += nblk[l] * 32 * planes[l]
+        want += noct[l] * 256 * planes[l]
     assert oracle.message_bytes(sizes, points) == (want + 255) // 256 * 256
 
 
@@ -80,7 +90,7 @@ def test_message_is_header_plus_packed_codes_and_decodes_to_norm_times_level(ora
             assert head[0] == norm and np.array_equal(head[1:], levels[l])
             sign, idx = oracle.quantize_range(grads[k][l], 0, d, inv, levels[l], 9, 2, k, l)
             planes = 1 + oracle.index_bits(points[l])
-            region = msg[off[l]: off[l] + ((d + 255) // 256) * 32 * planes]
+            region = msg[off[l]: off[l] + ((d + 2047) // 2048) * 256 * planes]
             assert np.array_equal(region, oracle.pack_layer(sign, idx, points[l]))
             q = oracle.decode(sign, idx, norm, levels[l])
             assert np.array_equal(q, np.where(sign == 1, -1.0, 1.0).astype(np.float32) * (norm * levels[l][idx]))
