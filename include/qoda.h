@@ -80,7 +80,8 @@ int qoda_get_levels(qoda_ctx *ctx, int32_t type, float *levels_host, void *strea
 
 /* Level fit, Alg. 1 lines 2-7 / eq. (Qada2) with the weights lambda_z: the K nodes' current vectors are the Z
  * samples; every coordinate of (node, layer) weighs ||v_{k,l}||^2; layers of one type pool.  The distribution is
- * estimated by a histogram on the top 11 magnitude bits of each entry and the objective is minimised exactly
+ * estimated by a histogram on the top 11 magnitude bits of a fixed quarter of the entries (256-coordinate blocks
+ * 0, 4, 8, ... of each layer) and the objective is minimised exactly
  * over level positions on a 257-point grid (3 mantissa bits per octave down to 2^-32).  A type whose vectors are
  * all zero keeps its levels.  grad_dev: host array [K*L], entry k*L+l.
  * Side effect: the per-(node, layer) norms of these vectors stay in the context tagged with `round`; a following

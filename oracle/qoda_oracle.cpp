@@ -366,8 +366,10 @@ int32_t oracle_quantize(int32_t L, const int64_t *d, const int32_t *S, const flo
     uint8_t *region = msg + lay.msg_off[l];
     const int64_t nchunks = (d[l] + kChunk - 1) / kChunk;
     for (int64_t c = 0; c < nchunks; ++c) {
-      double p[kSlots];
-      for (int j = 0; j < kSlots; ++j) p[j] = 0.0;
+      // a slot's (at most 64) squared differences are accumulated in fp32 with a fused multiply-add, in
+      // increasing coordinate; the 256 slot sums are then combined in fp64
+      float p32[kSlots];
+      for (int j = 0; j < kSlots; ++j) p32[j] = 0.0f;
       const int64_t e1 = std::min(d[l], (c + 1) * kChunk);   // padding coordinates carry code 0 and add nothing
       for (int64_t e = c * kChunk; e < e1; ++e) {
         const Code code =
@@ -381,8 +383,10 @@ int32_t oracle_quantize(int32_t L, const int64_t *d, const int32_t *S, const flo
           prev = decode_value(pc.sign, pc.h, hp.norm, hp.lev, S[l]);
         }
         const float diff = cur - prev;
-        p[slot_of(e)] = p[slot_of(e)] + (double)diff * (double)diff;
+        p32[slot_of(e)] = std::fmaf(diff, diff, p32[slot_of(e)]);
       }
+      double p[kSlots];
+      for (int j = 0; j < kSlots; ++j) p[j] = (double)p32[j];
       delta_chunks.push_back(halving_tree(p));
     }
   }
@@ -439,7 +443,8 @@ void oracle_oda_update(int64_t n, const float *mean, const float *x1, float *y, 
 // The K nodes' current vectors are the Z samples.  Every coordinate of (node k, layer l) carries weight
 // ||v_{k,l}||^2 (the factor that multiplies its normalised variance in eq. (MQV)/(Qada2)); layers of the
 // same type pool.  The distribution is estimated by a histogram:
-//   1. bin |v| on its top 11 magnitude bits (8 exponent + 3 mantissa bits): counts[k][l][2048];
+//   1. bin |v| on its top 11 magnitude bits (8 exponent + 3 mantissa bits): counts[k][l][2048]; the estimate
+//      uses a fixed quarter of the coordinates: those in 256-coordinate blocks number 0, 4, 8, ... of the layer;
 //   2. map each bin's midpoint c to u = min(c * inv_norm, 1), re-bin u the same way onto the 257-point
 //      grid g_j (g_0 = 2^-32, ..., g_256 = 1), adding weight wfix(k,l) * count, where
 //      wfix = floor(sumsq(k,l) * 2^(23 - e)) and e is the binary exponent of the largest sumsq of the type;
@@ -448,7 +453,8 @@ void oracle_oda_update(int64_t n, const float *mean, const float *x1, float *y, 
 // hist_out (optional): K*L*2048 uint32 counts.  pooled_out (optional): M*257 uint64 weights.
 // levels_io: M pointers to S_m floats; a type whose sampled vectors are all zero keeps its levels.
 void oracle_histogram(const float *v, int64_t d, uint32_t *counts /* 2048, accumulated into */) {
-  for (int64_t e = 0; e < d; ++e) counts[(f2u(v[e]) & 0x7FFFFFFFu) >> 20] += 1;
+  for (int64_t e = 0; e < d; ++e)
+    if (((e / kBlock) % 4) == 0) counts[(f2u(v[e]) & 0x7FFFFFFFu) >> 20] += 1;
 }
 
 // objective of eq. (Qada2) for given levels on pooled grid weights W[257] (used by the fit and by its pins)

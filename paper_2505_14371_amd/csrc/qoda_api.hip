@@ -31,7 +31,7 @@ struct qoda_ctx {
   int *d_type_points = nullptr;
   double *d_partial = nullptr, *d_dpartial = nullptr, *d_sumsq = nullptr, *d_delta = nullptr;
   float *d_norm = nullptr, *d_inv = nullptr, *d_lev = nullptr, *d_rgap = nullptr, *d_eta = nullptr;
-  unsigned short *d_lut = nullptr;
+  unsigned char *d_lut = nullptr;
   unsigned int *d_hist = nullptr, *d_status = nullptr;
   unsigned long long *d_pooled = nullptr;
   int *d_type_exp = nullptr;

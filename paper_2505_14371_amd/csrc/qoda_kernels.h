@@ -46,7 +46,7 @@ struct Dev {
   double *delta;      // [K]
   float *lev;         // [M*256]
   float *rgap;        // [M*256]
-  unsigned short *lut;  // [M*1024] level-search table: low byte tau(bin lower edge), high byte levels inside the bin
+  unsigned char *lut;  // [M*1024] level-search table: tau at the lower edge of the bin bits(u) >> 20
   unsigned int *hist;          // [K*L*2048]
   unsigned long long *pooled;  // [M*257]
   int *type_exp;               // [M]

@@ -78,9 +78,9 @@ __device__ __forceinline__ void philox4x32_10(unsigned int c0, unsigned int c1, 
     if (r > 0) { k0 += W0; k1 += W1; }
     const unsigned long long p0 = M0 * (unsigned long long)c0;
     const unsigned long long p1 = M1 * (unsigned long long)c2;
-    const unsigned int n0 = (unsigned int)(p1 >> 32) ^ c1 ^ k0;
+    const unsigned int n0 = __builtin_amdgcn_bitop3_b32((unsigned int)(p1 >> 32), c1, k0, 0x96);   // 3-input xor
     const unsigned int n1 = (unsigned int)p1;
-    const unsigned int n2 = (unsigned int)(p0 >> 32) ^ c3 ^ k1;
+    const unsigned int n2 = __builtin_amdgcn_bitop3_b32((unsigned int)(p0 >> 32), c3, k1, 0x96);
     const unsigned int n3 = (unsigned int)p0;
     c0 = n0; c1 = n1; c2 = n2; c3 = n3;
   }
@@ -97,7 +97,8 @@ __device__ __forceinline__ const __attribute__((address_space(1))) T *as_global(
 __device__ __forceinline__ void load4(const float *__restrict__ v, long long e, long long d, float x[4]) {
   const auto *g = as_global(v);
   if (e + 4 <= d) {
-    const v4f q = *reinterpret_cast<const __attribute__((address_space(1))) v4f *>(g + e);
+    // every big array here is streamed once per pass: nontemporal accesses measurably raise the read rate
+    const v4f q = __builtin_nontemporal_load(reinterpret_cast<const __attribute__((address_space(1))) v4f *>(g + e));
     x[0] = q.x; x[1] = q.y; x[2] = q.z; x[3] = q.w;
   } else {
 #pragma unroll
@@ -110,7 +111,7 @@ __device__ __forceinline__ void store4(float *__restrict__ v, long long e, long 
   if (e + 4 <= d) {
     v4f q;
     q.x = x[0]; q.y = x[1]; q.z = x[2]; q.w = x[3];
-    *reinterpret_cast<__attribute__((address_space(1))) v4f *>(g + e) = q;
+    __builtin_nontemporal_store(q, reinterpret_cast<__attribute__((address_space(1))) v4f *>(g + e));
   } else {
 #pragma unroll
     for (int j = 0; j < 4; ++j)
@@ -137,6 +138,20 @@ __device__ __forceinline__ unsigned int extract_code(const unsigned int (&D)[C1]
   return v & ((1u << C1) - 1u);
 }
 
+// Byte offset (code * 4) of code jj into a table of floats: two instructions (shift or funnel shift, mask).
+template <int C1>
+__device__ __forceinline__ unsigned int extract_off(const unsigned int (&D)[C1], int jj) {
+  const int pos = C1 * jj, r = pos >> 5, sh = pos & 31;
+  unsigned int v;
+  if (sh + C1 <= 32) v = (sh >= 2) ? (D[r] >> (sh - 2)) : (D[r] << (2 - sh));
+  else v = __builtin_amdgcn_alignbit(D[r + 1], D[r], sh - 2);   // straddles two words; then sh >= 23
+  return v & (((1u << C1) - 1u) << 2);
+}
+
+__device__ __forceinline__ float lds_float_at(const float *table, unsigned int byte_off) {
+  return *reinterpret_cast<const float *>(reinterpret_cast<const char *>(table) + byte_off);
+}
+
 // Shift a C1-word little-endian bit string right by 8*C1 bits (one block pair's worth of codes).
 template <int C1>
 __device__ __forceinline__ void shift_out_pair(unsigned int (&D)[C1]) {
@@ -154,14 +169,14 @@ template <int C1>
 __device__ __forceinline__ void load_record(const unsigned char *octet, int i, unsigned int (&D)[C1]) {
   const auto *g = reinterpret_cast<const __attribute__((address_space(1))) unsigned int *>(as_global(octet));
 #pragma unroll
-  for (int r = 0; r < C1; ++r) D[r] = g[r * 64 + i];
+  for (int r = 0; r < C1; ++r) D[r] = __builtin_nontemporal_load(g + r * 64 + i);
 }
 
 template <int C1>
 __device__ __forceinline__ void store_record(unsigned char *octet, int i, const unsigned int (&D)[C1]) {
   auto *g = (__attribute__((address_space(1))) unsigned int *)octet;
 #pragma unroll
-  for (int r = 0; r < C1; ++r) g[r * 64 + i] = D[r];
+  for (int r = 0; r < C1; ++r) __builtin_nontemporal_store(D[r], g + r * 64 + i);
 }
 
 }  // namespace
@@ -175,7 +190,8 @@ __global__ void k_zero_u32(unsigned int *p, size_t n) {
 
 // ------------------------------------------------------------------------------------------------ pass 1
 // Sum of squares of one tile in fp64 (Sec. 2.2, L2 norm before the root), optionally with the histogram of the
-// top 11 magnitude bits (the distribution estimate of Alg. 1 line 4).
+// top 11 magnitude bits (the distribution estimate of Alg. 1 line 4), taken over a fixed quarter of the
+// coordinates (every fourth 256-coordinate block) to keep the shared-memory atomics off the critical path.
 template <bool HIST>
 __global__ void __launch_bounds__(kThreads) k_sumsq(Dev a) {
   __shared__ double red[kThreads];
@@ -197,7 +213,8 @@ __global__ void __launch_bounds__(kThreads) k_sumsq(Dev a) {
     v4f q[16];
 #pragma unroll
     for (int s = 0; s < 16; ++s)
-      q[s] = *reinterpret_cast<const __attribute__((address_space(1))) v4f *>(as_global(v) + base + (long long)s * kBlockCoords);
+      q[s] = __builtin_nontemporal_load(
+          reinterpret_cast<const __attribute__((address_space(1))) v4f *>(as_global(v) + base + (long long)s * kBlockCoords));
 #pragma unroll
     for (int s = 0; s < 16; ++s) {
       const float x[4] = {q[s].x, q[s].y, q[s].z, q[s].w};
@@ -205,7 +222,7 @@ __global__ void __launch_bounds__(kThreads) k_sumsq(Dev a) {
       for (int j = 0; j < 4; ++j) {
         const double xd = (double)x[j];
         acc = __builtin_fma(xd, xd, acc);   // the product is exact in fp64, so this equals acc + xd*xd
-        if (HIST) atomicAdd(&lh[(f2u(x[j]) & 0x7FFFFFFFu) >> 20], 1u);
+        if (HIST && (s & 3) == 0) atomicAdd(&lh[(f2u(x[j]) & 0x7FFFFFFFu) >> 20], 1u);   // blocks 0, 4, 8, ... only
       }
     }
   } else {
@@ -218,7 +235,7 @@ __global__ void __launch_bounds__(kThreads) k_sumsq(Dev a) {
       for (int j = 0; j < 4; ++j) {
         const double xd = (double)x[j];
         acc = __builtin_fma(xd, xd, acc);
-        if (HIST && e + j < m.d) atomicAdd(&lh[(f2u(x[j]) & 0x7FFFFFFFu) >> 20], 1u);
+        if (HIST && (s & 3) == 0 && e + j < m.d) atomicAdd(&lh[(f2u(x[j]) & 0x7FFFFFFFu) >> 20], 1u);
       }
     }
   }
@@ -270,81 +287,103 @@ __global__ void k_write_header(Dev a) {
 // ------------------------------------------------------------------------------------------------ pass 2
 // Quantize + pack one tile (Sec. 3.1, Sec. 3.2) and accumulate the squared distance to the node's previous
 // decoded message (the step-size term of eq. (general_stepsize)).
+// Quantize the four coordinates a lane owns in one block (Sec. 3.1), append their codes to the record and add
+// their squared distance to the previous decoded message (eq. (general_stepsize)).  jl0 = 0 or 4: position of
+// the block inside its pair.
+template <int C1>
+__device__ __forceinline__ void quantize_block(const float (&x)[4], const unsigned int (&o)[4], int half, float inv,
+                                               float norm, const unsigned char *lut, const float4 *tab,
+                                               const float *tprev, unsigned int (&D)[C1], const unsigned int (&Dp)[C1],
+                                               float &acc) {
+  float u[4];
+  int tau[4];
+  float4 lv[4];                    // {l_tau, 1/gap, l_tau+1, norm*l_tau}; entry S-1 = {1, 0, +inf, norm}
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    u[j] = fminf(fabsf(x[j]) * inv, 1.0f);
+    tau[j] = lut[f2u(u[j]) >> 20];
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) lv[j] = tab[tau[j]];
+  // The table gave tau at the lower edge of u's bin; a level inside the bin (never the case for fitted levels,
+  // which sit on bin edges) makes some lanes walk on.  At u = 1 the walk ends on the entry of the last level
+  // itself (xi = 0, never rounds up), which yields the same code and value as tau = S-2 rounding up.
+  if (__ballot((lv[0].z <= u[0]) | (lv[1].z <= u[1]) | (lv[2].z <= u[2]) | (lv[3].z <= u[3])) != 0ull) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      while (lv[j].z <= u[j]) { ++tau[j]; lv[j] = tab[tau[j]]; }
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int jl = 4 * half + j;                       // position of the coordinate inside the pair
+    const unsigned int w16 = half ? (o[j] >> 16) : (o[j] & 0xFFFFu);
+    const float xi = (u[j] - lv[j].x) * lv[j].y;
+    // (w16 + 0.5) < xi * 65536  <=>  w16 < xi * 65536 - 0.5 : the scaling by 2^16 is exact, and the subtraction
+    // is exact whenever its result is not negative, so one fused operation decides the same.
+    const bool up = (float)w16 < __builtin_fmaf(xi, 65536.0f, -0.5f);
+    const unsigned int h = (unsigned int)tau[j] + (up ? 1u : 0u);
+    const float mag = up ? norm * lv[j].z : lv[j].w;   // norm * l_h, the value the decoder will rebuild
+    const float cur = __builtin_copysignf(mag, x[j]);
+    insert_code<C1>(D, (h << 1) | (f2u(x[j]) >> 31), 24 + jl);
+    const float pv = lds_float_at(tprev, extract_off<C1>(Dp, jl));  // all zero without a previous message
+    const float diff = cur - pv;
+    acc = __builtin_fmaf(diff, diff, acc);
+  }
+}
+
+__device__ __forceinline__ void load_block_fast(const float *__restrict__ v, long long B, int i, float (&x)[4]) {
+  const v4f q = __builtin_nontemporal_load(
+      reinterpret_cast<const __attribute__((address_space(1))) v4f *>(as_global(v) + B * kBlockCoords + 4 * i));
+  x[0] = q.x; x[1] = q.y; x[2] = q.z; x[3] = q.w;
+}
+
 // One octet (8 blocks = 2048 coordinates) of one (node, layer) for one wave: 4 block pairs, each with one
 // generator call and 8 coordinates per lane.  The lane record is built as a shift register: every pair shifts it
 // right by 8*C1 bits and writes its 8 codes into the top quarter, so that after four pairs pair 0 sits at bit 0;
 // the previous message's record is consumed from the bottom the same way.  The pair loop is deliberately not
-// unrolled: unrolled, the compiler interleaves the pairs and needs more than 256 registers.
+// unrolled: unrolled, the compiler interleaves the pairs and needs more than 256 registers.  The next pair's
+// gradient values are requested before the current pair is processed.
 // FAST: the whole octet lies inside the layer (no bounds checks anywhere).
 template <int C1, bool FAST>
 __device__ __forceinline__ void quantize_octet(const Dev &a, const LayerMeta &m, int l, int k, long long O,
                                                const float *__restrict__ v, unsigned char *body,
                                                const unsigned char *prevbody, float inv, float norm,
-                                               const unsigned short *lut, const float4 *tab, const float *tprev, int i,
-                                               double &acc) {
+                                               const unsigned char *lut, const float4 *tab, const float *tprev, int i,
+                                               float &acc) {
   const unsigned int k0 = (unsigned int)a.seed, k1 = (unsigned int)(a.seed >> 32);
   unsigned int D[C1], Dp[C1];
 #pragma unroll
   for (int r = 0; r < C1; ++r) { D[r] = 0u; Dp[r] = 0u; }
   if (prevbody != nullptr) load_record<C1>(prevbody + O * 256 * C1, i, Dp);
+  float xa[4] = {0.0f, 0.0f, 0.0f, 0.0f}, xb[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  if (FAST) {
+    load_block_fast(v, O * 8, i, xa);
+    load_block_fast(v, O * 8 + 1, i, xb);
+  }
 #pragma unroll 1
   for (int pp = 0; pp < 4; ++pp) {
     const long long B0 = O * 8 + 2 * pp;   // block index inside the layer
     shift_out_pair<C1>(D);
     if (FAST || B0 < m.nblk) {
+      float x0[4], x1[4];
+      if (FAST) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { x0[j] = xa[j]; x1[j] = xb[j]; }
+        if (pp < 3) {
+          load_block_fast(v, B0 + 2, i, xa);
+          load_block_fast(v, B0 + 3, i, xb);
+        }
+      } else {
+        load4(v, B0 * kBlockCoords + 4 * i, m.d, x0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) x1[j] = 0.0f;
+        if (B0 + 1 < m.nblk) load4(v, (B0 + 1) * kBlockCoords + 4 * i, m.d, x1);
+      }
       unsigned int o[4];
       philox4x32_10((unsigned int)((B0 >> 1) * 64 + i), (unsigned int)l, a.round, (unsigned int)k, k0, k1, o);
-#pragma unroll
-      for (int half = 0; half < 2; ++half) {
-        const long long B = B0 + half;
-        if (FAST || B < m.nblk) {
-          const long long e = B * kBlockCoords + 4 * i;
-          float x[4];
-          if (FAST) {
-            const v4f q = *reinterpret_cast<const __attribute__((address_space(1))) v4f *>(as_global(v) + e);
-            x[0] = q.x; x[1] = q.y; x[2] = q.z; x[3] = q.w;
-          } else {
-            load4(v, e, m.d, x);
-          }
-          // level search (Sec. 3.1): the table entry of u's bin gives tau at the bin's lower edge and how many
-          // further levels lie inside the bin; only lanes in such a bin walk on.
-          float u[4];
-          unsigned int ent[4];
-          int tau[4];
-          float4 lv[4];                                      // {l_tau, 1/gap, l_tau+1, norm*l_tau}
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            u[j] = fminf(fabsf(x[j]) * inv, 1.0f);
-            ent[j] = lut[f2u(u[j]) >> 20];
-          }
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            tau[j] = (int)(ent[j] & 0xFFu);
-            lv[j] = tab[tau[j]];
-          }
-          if (__ballot(((ent[0] | ent[1] | ent[2] | ent[3]) >> 8) != 0u) != 0ull) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-              for (int n = (int)(ent[j] >> 8); n > 0 && lv[j].z <= u[j]; --n) { ++tau[j]; lv[j] = tab[tau[j]]; }
-          }
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const int jl = 4 * half + j;                       // position of the coordinate inside the pair
-            const unsigned int w16 = half ? (o[j] >> 16) : (o[j] & 0xFFFFu);
-            const float xi = (u[j] - lv[j].x) * lv[j].y;
-            // (w16 + 0.5) < xi * 65536  <=>  w16 < xi * 65536 - 0.5 : the scaling by 2^16 is exact, and the
-            // subtraction is exact whenever its result is not negative, so one fused operation decides the same.
-            const bool up = (float)w16 < __builtin_fmaf(xi, 65536.0f, -0.5f);
-            const unsigned int h = (unsigned int)tau[j] + (up ? 1u : 0u);
-            const float mag = up ? norm * lv[j].z : lv[j].w;   // norm * l_h, the value the decoder will rebuild
-            const float cur = __builtin_copysignf(mag, x[j]);
-            insert_code<C1>(D, (h << 1) | (f2u(x[j]) >> 31), 24 + jl);
-            const float pv = tprev[extract_code<C1>(Dp, jl)];  // all zero when there is no previous message
-            const float diff = cur - pv;
-            acc = __builtin_fma((double)diff, (double)diff, acc);
-          }
-        }
-      }
+      quantize_block<C1>(x0, o, 0, inv, norm, lut, tab, tprev, D, Dp, acc);
+      // a block past the end of the layer is all padding: +0 inputs give code 0 and add nothing, as required
+      quantize_block<C1>(x1, o, 1, inv, norm, lut, tab, tprev, D, Dp, acc);
     }
     shift_out_pair<C1>(Dp);
   }
@@ -353,7 +392,7 @@ __device__ __forceinline__ void quantize_octet(const Dev &a, const LayerMeta &m,
 
 template <int C1>
 __device__ __forceinline__ void quantize_tile(const Dev &a, const LayerMeta &m, int l, int k, int chunk,
-                                              const unsigned short *lut, const float4 *tab, const float *tprev,
+                                              const unsigned char *lut, const float4 *tab, const float *tprev,
                                               double *red) {
   const int t = threadIdx.x;
   const int w = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -364,7 +403,7 @@ __device__ __forceinline__ void quantize_tile(const Dev &a, const LayerMeta &m, 
   const float inv = a.inv[(size_t)k * a.L + l];
   const float norm = a.norm[(size_t)k * a.L + l];
   const long long noct = (m.nblk + 7) >> 3;
-  double acc = 0.0;
+  float acc = 0.0f;   // this slot's squared differences: an fp32 fused multiply-add chain in increasing coordinate
   for (int oo = 0; oo < 2; ++oo) {
     const long long O = (long long)chunk * 8 + w * 2 + oo;   // octet index inside the layer
     if (O >= noct) break;
@@ -373,13 +412,13 @@ __device__ __forceinline__ void quantize_tile(const Dev &a, const LayerMeta &m, 
     else
       quantize_octet<C1, false>(a, m, l, k, O, v, body, prevbody, inv, norm, lut, tab, tprev, i, acc);
   }
-  const double total = block_tree(acc, red);
+  const double total = block_tree((double)acc, red);
   if (t == 0) a.dpartial[(size_t)k * a.G + blockIdx.x] = total;
 }
 
 template <int C1>
 __global__ void __launch_bounds__(kThreads) k_quantize(Dev a) {
-  __shared__ unsigned short lut[kLutSize];
+  __shared__ unsigned char lut[kLutSize];
   __shared__ float4 tab[kMaxPoints];
   __shared__ float tprev[2 * kMaxPoints];   // previous message's decode table indexed by code = sign | h << 1
   __shared__ double red[kThreads];
@@ -391,13 +430,13 @@ __global__ void __launch_bounds__(kThreads) k_quantize(Dev a) {
   const int t = threadIdx.x;
   const float *lev = a.lev + (size_t)m.type * kMaxPoints;
   const float *rg = a.rgap + (size_t)m.type * kMaxPoints;
-  reinterpret_cast<uint2 *>(lut)[t] = reinterpret_cast<const uint2 *>(a.lut + (size_t)m.type * kLutSize)[t];
+  reinterpret_cast<unsigned int *>(lut)[t] = reinterpret_cast<const unsigned int *>(a.lut + (size_t)m.type * kLutSize)[t];
   const float norm = a.norm[(size_t)k * a.L + l];
   const unsigned char *prevmsg = (a.prev != nullptr) ? a.prev[k] : nullptr;
   if (t < m.S) {
     const float lj = lev[t];
-    const float ln = (t + 1 < m.S) ? lev[t + 1] : 1.0f;
-    tab[t] = make_float4(lj, rg[t], ln, norm * lj);
+    const float ln = (t + 1 < m.S) ? lev[t + 1] : __builtin_inff();   // the last entry stops every walk
+    tab[t] = make_float4(lj, (t + 1 < m.S) ? rg[t] : 0.0f, ln, norm * lj);
   }
   for (int c = t; c < (1 << m.planes); c += kThreads) {   // codes past S-1 decode as the last level
     float pv = 0.0f;
@@ -455,7 +494,7 @@ __device__ __forceinline__ void decode_octet(const Dev &a, const LayerMeta &m, i
     const float *Tk = T + k * TS;
 #pragma unroll
     for (int jj = 0; jj < 32; ++jj) {
-      const float val = Tk[extract_code<C1>(Dc, jj)];
+      const float val = lds_float_at(Tk, extract_off<C1>(Dc, jj));
       sum[jj] = (k == 0) ? val : sum[jj] + val;
     }
 #pragma unroll
@@ -586,22 +625,19 @@ __device__ __forceinline__ float grid_value(int j) { return u2f((unsigned int)(j
 // Search tables of one type from its levels (in shared memory): reciprocal gaps and the bin -> index table.
 __device__ void build_tables(const Dev &a, int mtype, int S, const float *slev) {
   float *rg = a.rgap + (size_t)mtype * kMaxPoints;
-  unsigned short *lut = a.lut + (size_t)mtype * kLutSize;
+  unsigned char *lut = a.lut + (size_t)mtype * kLutSize;
   for (int j = threadIdx.x; j < kMaxPoints; j += kThreads) rg[j] = (j < S - 1) ? rcp_floor(slev[j + 1] - slev[j]) : 0.0f;
-  // entry q serves the values whose bit pattern >> 20 is q, i.e. [lo, hi]: low byte = tau(lo), high byte =
-  // tau(hi) - tau(lo) = number of levels that lie inside the bin above its lower edge.
+  // entry q serves the values whose bit pattern >> 20 is q: tau at the lower edge of that bin.
   for (int q = threadIdx.x; q < kLutSize; q += kThreads) {
-    const float lo = u2f((unsigned int)q << 20), hi = u2f(((unsigned int)q << 20) | 0xFFFFFu);
-    int tlo = 0, thi = 0;
+    const float lo = u2f((unsigned int)q << 20);
+    int tau = 0;
     if (q > 1016) {
-      tlo = thi = S - 2;
+      tau = S - 2;
     } else {
-      for (int j = 1; j <= S - 2; ++j) {
-        if (slev[j] <= lo) tlo = j;
-        if (slev[j] <= hi) thi = j;
-      }
+      for (int j = 1; j <= S - 2; ++j)
+        if (slev[j] <= lo) tau = j;
     }
-    lut[q] = (unsigned short)(tlo | ((thi - tlo) << 8));
+    lut[q] = (unsigned char)tau;
   }
 }
 

@@ -95,7 +95,8 @@ def test_message_is_header_plus_packed_codes_and_decodes_to_norm_times_level(ora
             q = oracle.decode(sign, idx, norm, levels[l])
             assert np.array_equal(q, np.where(sign == 1, -1.0, 1.0).astype(np.float32) * (norm * levels[l][idx]))
             want_delta += float(np.sum(q.astype(np.float64) ** 2))
-        assert delta == pytest.approx(want_delta, rel=1e-12)          # no previous message: delta = ||Vhat||^2
+        assert delta == pytest.approx(want_delta, rel=1e-5)           # no previous message: delta = ||Vhat||^2
+        # (each reduction slot adds its 64 squares in fp32, so the sum is good to a few 1e-7)
         msgs.append(msg)
     # K = 1: the aggregate is the decoded vector itself
     one = oracle.dequant_aggregate(w.sizes, points, msgs[:1])
@@ -127,8 +128,8 @@ def test_delta_is_the_squared_distance_to_the_previous_decoded_message(oracle):
     v1 = oracle.dequant_aggregate(w.sizes, points, [m1])
     v2 = oracle.dequant_aggregate(w.sizes, points, [m2])      # each message carries its own levels
     want = sum(float(np.sum((a.astype(np.float64) - b.astype(np.float64)) ** 2)) for a, b in zip(v2, v1))
-    assert d2 == pytest.approx(want, rel=1e-6)
-    assert d1 == pytest.approx(sum(float(np.sum(a.astype(np.float64) ** 2)) for a in v1), rel=1e-12)
+    assert d2 == pytest.approx(want, rel=1e-5)
+    assert d1 == pytest.approx(sum(float(np.sum(a.astype(np.float64) ** 2)) for a in v1), rel=1e-5)
 
 
 def test_nonfinite_input_raises_the_status_flag(oracle):
