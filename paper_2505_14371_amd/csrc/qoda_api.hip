@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -28,6 +29,10 @@ struct qoda_ctx {
   // device memory owned by the context
   LayerMeta *d_meta = nullptr;
   int2 *d_tiles = nullptr;
+  int4 *d_stiles = nullptr;
+  int *d_empty = nullptr;
+  int n_empty = 0;
+  int GS = 0;
   int *d_type_points = nullptr;
   double *d_partial = nullptr, *d_dpartial = nullptr, *d_sumsq = nullptr, *d_delta = nullptr;
   float *d_norm = nullptr, *d_inv = nullptr, *d_lev = nullptr, *d_rgap = nullptr, *d_eta = nullptr;
@@ -140,6 +145,10 @@ Dev base_args(const qoda_ctx *c) {
   std::memset(&a, 0, sizeof a);
   a.meta = c->d_meta;
   a.tiles = c->d_tiles;
+  a.stiles = c->d_stiles;
+  a.empty_layers = c->d_empty;
+  a.n_empty = c->n_empty;
+  a.GS = c->GS;
   a.L = c->L; a.G = c->G; a.K = c->K; a.M = c->M;
   a.type_points = c->d_type_points;
   a.partial = c->d_partial; a.dpartial = c->d_dpartial; a.sumsq = c->d_sumsq;
@@ -181,7 +190,7 @@ int check_msg_ptrs(qoda_ctx *c, const void *const *p, size_t n, const char *what
 }
 
 void free_all(qoda_ctx *c) {
-  void *ptrs[] = {c->d_meta, c->d_tiles, c->d_type_points, c->d_partial, c->d_dpartial, c->d_sumsq, c->d_delta,
+  void *ptrs[] = {c->d_meta, c->d_tiles, c->d_stiles, c->d_empty, c->d_type_points, c->d_partial, c->d_dpartial, c->d_sumsq, c->d_delta,
                   c->d_norm, c->d_inv, c->d_lev, c->d_rgap, c->d_eta, c->d_lut, c->d_hist, c->d_status, c->d_pooled,
                   c->d_type_exp, c->d_dp_arg, c->d_dp_arg_off, c->t_grad.dev, c->t_msg.dev, c->t_prev.dev, c->t_in.dev,
                   c->t_x1.dev, c->t_y.dev, c->t_xh.dev, c->t_xn.dev, c->t_mean.dev};
@@ -218,7 +227,6 @@ int quantize_impl(qoda_ctx *c, int node0, int nnodes, const float *const *grad_f
     int rc = run_norm_pass(c, a, false, s);
     if (rc) return rc;
   }
-  LAUNCH(c, kIdWriteHeader, s, launch_write_header(a, s));
   LAUNCH(c, kIdQuantize, s, launch_quantize(a, c->planes_mask, s));
   LAUNCH(c, kIdDeltaFinalize, s, launch_delta_finalize(a, s));
   return QODA_OK;
@@ -278,6 +286,15 @@ int qoda_create(const qoda_config *cfg, qoda_ctx **out) {
   std::vector<int2> tiles((size_t)c->G);
   for (int l = 0; l < c->L; ++l)
     for (int ch = 0; ch < c->meta[l].nchunks; ++ch) tiles[(size_t)c->meta[l].first_chunk + ch] = make_int2(l, ch);
+  std::vector<int4> stiles;
+  for (int l = 0; l < c->L; ++l)
+    for (int ch = 0; ch < c->meta[l].nchunks; ch += kSuperTile)
+      stiles.push_back(make_int4(l, ch, std::min(kSuperTile, c->meta[l].nchunks - ch), 0));
+  c->GS = (int)stiles.size();
+  std::vector<int> empty;
+  for (int l = 0; l < c->L; ++l)
+    if (c->meta[l].d == 0) empty.push_back(l);
+  c->n_empty = (int)empty.size();
   std::vector<long long> arg_off(c->M);
   long long arg_total = 0;
   for (int m = 0; m < c->M; ++m) { arg_off[m] = arg_total; arg_total += (long long)c->type_points[m] * kGridPoints; }
@@ -287,6 +304,8 @@ int qoda_create(const qoda_config *cfg, qoda_ctx **out) {
   auto A = [&](hipError_t r) { if (e == hipSuccess) e = r; };
   A(dev_alloc(&c->d_meta, (size_t)c->L));
   A(dev_alloc(&c->d_tiles, (size_t)c->G));
+  A(dev_alloc(&c->d_stiles, (size_t)c->GS));
+  A(dev_alloc(&c->d_empty, (size_t)c->n_empty));
   A(dev_alloc(&c->d_type_points, (size_t)c->M));
   A(dev_alloc(&c->d_partial, KG));
   A(dev_alloc(&c->d_dpartial, KG));
@@ -309,6 +328,8 @@ int qoda_create(const qoda_config *cfg, qoda_ctx **out) {
   A(hipEventCreateWithFlags(&c->upload_done, hipEventDisableTiming));
   if (e == hipSuccess) A(hipMemcpy(c->d_meta, c->meta.data(), c->L * sizeof(LayerMeta), hipMemcpyHostToDevice));
   if (e == hipSuccess && c->G) A(hipMemcpy(c->d_tiles, tiles.data(), c->G * sizeof(int2), hipMemcpyHostToDevice));
+  if (e == hipSuccess && c->GS) A(hipMemcpy(c->d_stiles, stiles.data(), c->GS * sizeof(int4), hipMemcpyHostToDevice));
+  if (e == hipSuccess && c->n_empty) A(hipMemcpy(c->d_empty, empty.data(), c->n_empty * sizeof(int), hipMemcpyHostToDevice));
   if (e == hipSuccess) A(hipMemcpy(c->d_type_points, c->type_points.data(), c->M * sizeof(int), hipMemcpyHostToDevice));
   if (e == hipSuccess) A(hipMemcpy(c->d_dp_arg_off, arg_off.data(), c->M * sizeof(long long), hipMemcpyHostToDevice));
   if (e == hipSuccess) A(hipMemset(c->d_status, 0, sizeof(unsigned int)));
@@ -402,7 +423,6 @@ int qoda_fit_levels(qoda_ctx *c, const float *const *grad_dev, uint32_t round, v
   a.grad = reinterpret_cast<const float *const *>(c->t_grad.dev);
   a.round = round;
   LAUNCH(c, kIdZero, s, launch_zero_u32(c->d_hist, KL * kHistBins, s));
-  LAUNCH(c, kIdZero, s, launch_zero_u32(reinterpret_cast<unsigned int *>(c->d_pooled), (size_t)c->M * kGridPoints * 2, s));
   rc = run_norm_pass(c, a, true, s);
   if (rc) return rc;
   LAUNCH(c, kIdFitTypemax, s, launch_fit_typemax(a, s));

@@ -8,6 +8,7 @@ namespace qoda {
 
 constexpr int kBlockCoords = 256;    // coordinates per packed block (one wave64 step of 128-bit loads)
 constexpr int kChunkCoords = 16384;  // coordinates per workgroup tile (64 blocks) = one reduction chunk
+constexpr int kSuperTile = 8;        // tiles per workgroup in the norm pass
 constexpr int kThreads = 256;        // workgroup size everywhere: 4 waves, 256 reduction slots
 constexpr int kHistBins = 2048;      // top 11 magnitude bits of an fp32 value
 constexpr int kGridBase = 760;       // (127 - 32) << 3
@@ -32,8 +33,11 @@ struct LayerMeta {
 struct Dev {
   const LayerMeta *meta;
   const int2 *tiles;  // per tile: (layer, chunk inside layer)
-  int L, G, K, M;
+  const int4 *stiles; // per run of up to kSuperTile tiles of one layer: (layer, first chunk inside layer, chunks, -)
+  int L, G, GS, K, M; // GS = number of runs
   const int *type_points;          // [M]
+  const int *empty_layers;         // indices of the layers with d = 0
+  int n_empty;
   const float *const *grad;        // [K*L] layer pointers
   unsigned char *const *msg;       // [K]
   const unsigned char *const *prev;  // [K] or nullptr
@@ -80,7 +84,6 @@ enum KernelId {
 hipError_t launch_zero_u32(unsigned int *p, size_t n, hipStream_t s);
 hipError_t launch_sumsq(const Dev &a, bool with_hist, hipStream_t s);
 hipError_t launch_norm_finalize(const Dev &a, hipStream_t s);
-hipError_t launch_write_header(const Dev &a, hipStream_t s);
 hipError_t launch_quantize(const Dev &a, unsigned int planes_mask, hipStream_t s);
 hipError_t launch_delta_finalize(const Dev &a, hipStream_t s);
 hipError_t launch_step_scalars(const Dev &a, hipStream_t s);

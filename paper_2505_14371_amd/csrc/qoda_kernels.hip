@@ -53,19 +53,21 @@ __device__ float rcp_floor(float x) {
   return r;
 }
 
-// Fixed halving tree over the 256 slots: p[i] += p[i+h], h = 128 .. 1.  Returns the total in every thread.
+// Fixed halving tree over the 256 slots: p[i] += p[i+h], h = 128 .. 1.  The two cross-wave steps are one pass
+// through shared memory, the six in-wave steps are shuffles (lane i < h adds lane i + h, exactly the tree).
+// The total is valid in thread 0 only.
 __device__ double block_tree(double v, double *red) {
   const int t = threadIdx.x;
   red[t] = v;
   __syncthreads();
+  double r = 0.0;
+  if (t < 64) {
+    r = (red[t] + red[t + 128]) + (red[t + 64] + red[t + 192]);
 #pragma unroll
-  for (int h = kThreads / 2; h >= 1; h >>= 1) {
-    if (t < h) red[t] = red[t] + red[t + h];
-    __syncthreads();
+    for (int h = 32; h >= 1; h >>= 1) r = r + __shfl_down(r, h, 64);
   }
-  const double total = red[0];
-  __syncthreads();
-  return total;
+  __syncthreads();   // red may be reused by the caller
+  return r;
 }
 
 // Philox4x32-10 (Salmon et al., SC'11).
@@ -196,8 +198,10 @@ template <bool HIST>
 __global__ void __launch_bounds__(kThreads) k_sumsq(Dev a) {
   __shared__ double red[kThreads];
   __shared__ unsigned int lh[HIST ? kHistBins : 1];
-  const int2 tile = a.tiles[blockIdx.x];
-  const int l = tile.x;
+  // a workgroup takes up to kSuperTile consecutive tiles of one layer, so that the histogram is flushed to
+  // global memory (integer atomics on a few hot addresses) once per run instead of once per tile
+  const int4 st = a.stiles[blockIdx.x];   // (layer, first chunk inside the layer, chunks)
+  const int l = st.x;
   const int k = a.node0 + blockIdx.y;
   const LayerMeta m = a.meta[l];
   const float *__restrict__ v = a.grad[(size_t)k * a.L + l];
@@ -207,40 +211,43 @@ __global__ void __launch_bounds__(kThreads) k_sumsq(Dev a) {
     for (int b = t; b < kHistBins; b += kThreads) lh[b] = 0u;
     __syncthreads();
   }
-  const long long base = (long long)tile.y * kChunkCoords + (long long)w * 16 * kBlockCoords + 4 * i;
-  double acc = 0.0;
-  if ((long long)(tile.y + 1) * kChunkCoords <= m.d) {
-    v4f q[16];
+  for (int cc = 0; cc < st.z; ++cc) {
+    const int chunk = st.y + cc;
+    const long long base = (long long)chunk * kChunkCoords + (long long)w * 16 * kBlockCoords + 4 * i;
+    double acc = 0.0;
+    if ((long long)(chunk + 1) * kChunkCoords <= m.d) {
+      v4f q[16];
 #pragma unroll
-    for (int s = 0; s < 16; ++s)
-      q[s] = __builtin_nontemporal_load(
-          reinterpret_cast<const __attribute__((address_space(1))) v4f *>(as_global(v) + base + (long long)s * kBlockCoords));
+      for (int s = 0; s < 16; ++s)
+        q[s] = __builtin_nontemporal_load(reinterpret_cast<const __attribute__((address_space(1))) v4f *>(
+            as_global(v) + base + (long long)s * kBlockCoords));
 #pragma unroll
-    for (int s = 0; s < 16; ++s) {
-      const float x[4] = {q[s].x, q[s].y, q[s].z, q[s].w};
+      for (int s = 0; s < 16; ++s) {
+        const float x[4] = {q[s].x, q[s].y, q[s].z, q[s].w};
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const double xd = (double)x[j];
-        acc = __builtin_fma(xd, xd, acc);   // the product is exact in fp64, so this equals acc + xd*xd
-        if (HIST && (s & 3) == 0) atomicAdd(&lh[(f2u(x[j]) & 0x7FFFFFFFu) >> 20], 1u);   // blocks 0, 4, 8, ... only
+        for (int j = 0; j < 4; ++j) {
+          const double xd = (double)x[j];
+          acc = __builtin_fma(xd, xd, acc);   // the product is exact in fp64, so this equals acc + xd*xd
+          if (HIST && (s & 3) == 0) atomicAdd(&lh[(f2u(x[j]) & 0x7FFFFFFFu) >> 20], 1u);   // blocks 0, 4, 8, ... only
+        }
+      }
+    } else {
+      for (int s = 0; s < 16; ++s) {
+        const long long e = base + (long long)s * kBlockCoords;
+        if (e >= m.d) break;
+        float x[4];
+        load4(v, e, m.d, x);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const double xd = (double)x[j];
+          acc = __builtin_fma(xd, xd, acc);
+          if (HIST && (s & 3) == 0 && e + j < m.d) atomicAdd(&lh[(f2u(x[j]) & 0x7FFFFFFFu) >> 20], 1u);
+        }
       }
     }
-  } else {
-    for (int s = 0; s < 16; ++s) {
-      const long long e = base + (long long)s * kBlockCoords;
-      if (e >= m.d) break;
-      float x[4];
-      load4(v, e, m.d, x);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const double xd = (double)x[j];
-        acc = __builtin_fma(xd, xd, acc);
-        if (HIST && (s & 3) == 0 && e + j < m.d) atomicAdd(&lh[(f2u(x[j]) & 0x7FFFFFFFu) >> 20], 1u);
-      }
-    }
+    const double total = block_tree(acc, red);
+    if (t == 0) a.partial[(size_t)k * a.G + m.first_chunk + chunk] = total;
   }
-  const double total = block_tree(acc, red);
-  if (t == 0) a.partial[(size_t)k * a.G + blockIdx.x] = total;
   if (HIST) {
     __syncthreads();
     unsigned int *gh = a.hist + ((size_t)k * a.L + l) * kHistBins;
@@ -272,16 +279,6 @@ __global__ void __launch_bounds__(kThreads) k_norm_finalize(Dev a) {
     a.inv[idx] = rcp_floor(n);
     if (!finite) atomicOr(a.status, 1u);
   }
-}
-
-// Message header: {norm, levels[S]} per layer (Sec. 3.2: the norm in C_q = 32 bits; the levels ride along).
-__global__ void k_write_header(Dev a) {
-  const int l = blockIdx.x;
-  const int k = a.node0 + blockIdx.y;
-  const LayerMeta m = a.meta[l];
-  float *h = reinterpret_cast<float *>(a.msg[k] + m.hdr_off);
-  const float *lev = a.lev + (size_t)m.type * kMaxPoints;
-  for (int j = threadIdx.x; j <= m.S; j += blockDim.x) h[j] = (j == 0) ? a.norm[(size_t)k * a.L + l] : lev[j - 1];
 }
 
 // ------------------------------------------------------------------------------------------------ pass 2
@@ -438,6 +435,10 @@ __global__ void __launch_bounds__(kThreads) k_quantize(Dev a) {
     const float ln = (t + 1 < m.S) ? lev[t + 1] : __builtin_inff();   // the last entry stops every walk
     tab[t] = make_float4(lj, (t + 1 < m.S) ? rg[t] : 0.0f, ln, norm * lj);
   }
+  if (tile.y == 0) {   // message header of this layer: {norm, levels[S]} (Sec. 3.2: the norm in C_q = 32 bits)
+    float *h = reinterpret_cast<float *>(a.msg[k] + m.hdr_off);
+    for (int j = t; j <= m.S; j += kThreads) h[j] = (j == 0) ? norm : lev[j - 1];
+  }
   for (int c = t; c < (1 << m.planes); c += kThreads) {   // codes past S-1 decode as the last level
     float pv = 0.0f;
     if (prevmsg) {
@@ -460,6 +461,13 @@ __global__ void __launch_bounds__(kThreads) k_delta_finalize(Dev a) {
   for (int g = threadIdx.x; g < a.G; g += kThreads) acc = acc + p[g];
   const double s = block_tree(acc, red);
   if (threadIdx.x == 0) a.delta[k] = s;
+  // layers without coordinates have no tile: their header entries (norm 0, levels) are written here
+  for (int q = 0; q < a.n_empty; ++q) {
+    const LayerMeta m = a.meta[a.empty_layers[q]];
+    float *h = reinterpret_cast<float *>(a.msg[k] + m.hdr_off);
+    const float *lev = a.lev + (size_t)m.type * kMaxPoints;
+    for (int j = threadIdx.x; j <= m.S; j += kThreads) h[j] = (j == 0) ? 0.0f : lev[j - 1];
+  }
 }
 
 // ------------------------------------------------------------------------------------------------ step
@@ -572,6 +580,7 @@ __global__ void __launch_bounds__(kThreads) k_fit_typemax(Dev a) {
   __shared__ int bad[1];
   const int mtype = blockIdx.x;
   if (threadIdx.x == 0) bad[0] = 0;
+  for (int j = threadIdx.x; j < kGridPoints; j += kThreads) a.pooled[(size_t)mtype * kGridPoints + j] = 0ull;
   __syncthreads();
   const double lim = (double)kFltMax * (double)kFltMax;
   double mx = 0.0;
@@ -626,9 +635,9 @@ __device__ __forceinline__ float grid_value(int j) { return u2f((unsigned int)(j
 __device__ void build_tables(const Dev &a, int mtype, int S, const float *slev) {
   float *rg = a.rgap + (size_t)mtype * kMaxPoints;
   unsigned char *lut = a.lut + (size_t)mtype * kLutSize;
-  for (int j = threadIdx.x; j < kMaxPoints; j += kThreads) rg[j] = (j < S - 1) ? rcp_floor(slev[j + 1] - slev[j]) : 0.0f;
+  for (int j = threadIdx.x; j < kMaxPoints; j += (int)blockDim.x) rg[j] = (j < S - 1) ? rcp_floor(slev[j + 1] - slev[j]) : 0.0f;
   // entry q serves the values whose bit pattern >> 20 is q: tau at the lower edge of that bin.
-  for (int q = threadIdx.x; q < kLutSize; q += kThreads) {
+  for (int q = threadIdx.x; q < kLutSize; q += (int)blockDim.x) {
     const float lo = u2f((unsigned int)q << 20);
     int tau = 0;
     if (q > 1016) {
@@ -650,74 +659,113 @@ __global__ void __launch_bounds__(kThreads) k_build_tables(Dev a, int mtype) {
 }
 
 // Exact minimisation of eq. (Qada2) over interior levels on the grid by dynamic programming; one workgroup per type.
-__global__ void __launch_bounds__(kThreads) k_fit_dp(Dev a) {
-  __shared__ double P0[kGridPoints + 1], P1[kGridPoints + 1], P2[kGridPoints + 1];
+// cost(a, b) = sum over bins i in [a, b) of W_i (g_b - mid_i)(mid_i - g_a), from prefix sums P0, P1, P2 of W, W*mid,
+// W*mid^2 taken sequentially in increasing bin (fp64; the same operation order as the CPU checker).
+struct __attribute__((aligned(32))) FitRow { double p0, p1, p2, g; };
+
+__device__ __forceinline__ double fit_cost(const FitRow &ra, const FitRow &rb) {
+  return ((ra.g + rb.g) * (rb.p1 - ra.p1) - (rb.p2 - ra.p2)) - (ra.g * rb.g) * (rb.p0 - ra.p0);
+}
+
+constexpr int kFitThreads = 1024;   // 4 threads per grid index b: each scans a quarter of the candidates a
+
+__global__ void __launch_bounds__(kFitThreads) k_fit_dp(Dev a) {
+  __shared__ FitRow row[kGridPoints + 1];
   __shared__ double D[2][kGridPoints];
-  __shared__ double gd[kGridPoints];
+  __shared__ double wd[kGridPoints];
+  __shared__ double rv[kThreads];
+  __shared__ int ri[kThreads];
   __shared__ float slev[kMaxPoints];
-  __shared__ int go[1];
   const int mtype = blockIdx.x;
+  if (a.type_exp[mtype] == kTypeSkip) return;   // all-zero or non-finite vectors: the type keeps its levels
   const int S = a.type_points[mtype];
   const int t = threadIdx.x;
   const unsigned long long *W = a.pooled + (size_t)mtype * kGridPoints;
   const int last = kGridPoints - 1;
-  for (int j = t; j < kGridPoints; j += kThreads) gd[j] = (double)grid_value(j);
-  if (t == 0) {
-    P0[0] = 0.0; P1[0] = 0.0; P2[0] = 0.0;
-    for (int j = 0; j < kGridPoints; ++j) {
-      const double wj = (double)W[j];
-      const double mid = (j == last) ? 1.0 : (double)u2f(((unsigned int)(j + kGridBase) << 20) | (1u << 19));
-      const double wm = wj * mid;
-      P0[j + 1] = P0[j] + wj;
-      P1[j + 1] = P1[j] + wm;
-      P2[j + 1] = P2[j] + wm * mid;
-    }
-    go[0] = (a.type_exp[mtype] != kTypeSkip) ? 1 : 0;
+  for (int j = t; j < kGridPoints; j += kFitThreads) {
+    wd[j] = (double)W[j];
+    row[j].g = (double)grid_value(j);
   }
   __syncthreads();
-  if (!go[0]) return;
+  if (t == 0) {
+    double p0 = 0.0, p1 = 0.0, p2 = 0.0;
+    row[0].p0 = 0.0; row[0].p1 = 0.0; row[0].p2 = 0.0;
+    row[kGridPoints].g = 0.0;
+    for (int j = 0; j < kGridPoints; ++j) {
+      const double wj = wd[j];
+      const double mid = (j == last) ? 1.0 : (double)u2f(((unsigned int)(j + kGridBase) << 20) | (1u << 19));
+      const double wm = wj * mid;
+      p0 = p0 + wj;
+      p1 = p1 + wm;
+      p2 = p2 + wm * mid;
+      row[j + 1].p0 = p0; row[j + 1].p1 = p1; row[j + 1].p2 = p2;
+    }
+  }
+  __syncthreads();
   const double inf = __longlong_as_double(0x7FF0000000000000ll);
   short *arg = a.dp_arg + a.dp_arg_off[mtype];
   if (S > 2) {
-    for (int b = t; b < kGridPoints; b += kThreads)
-      D[1][b] = (b >= 1 && b <= last - (S - 2)) ? (gd[b] * P1[b] - P2[b]) : inf;
+    // level 1 at grid index b: cost of the bins below g_b against the levels 0 and g_b
+    for (int b = t; b < kGridPoints; b += kFitThreads)
+      D[1][b] = (b >= 1 && b <= last - (S - 2)) ? (row[b].g * row[b].p1 - row[b].p2) : inf;
     __syncthreads();
+    const int b = t >> 2, q = t & 3;   // interior levels only ever sit at b <= 255
     for (int s = 2; s <= S - 2; ++s) {
       const double *Dp = D[(s - 1) & 1];
       double *Dc = D[s & 1];
-      for (int b = t; b < kGridPoints; b += kThreads) {
-        double best = inf;
-        int besta = -1;
-        if (b >= s && b <= last - (S - 1 - s)) {
-          const double gb = gd[b], p0b = P0[b], p1b = P1[b], p2b = P2[b];
-          for (int aa = s - 1; aa <= b - 1; ++aa) {
-            const double ga = gd[aa];
-            const double cost = ((ga + gb) * (p1b - P1[aa]) - (p2b - P2[aa])) - (ga * gb) * (p0b - P0[aa]);
-            const double c = Dp[aa] + cost;
-            if (c < best) { best = c; besta = aa; }
-          }
+      double best = inf;
+      int besta = 0x7FFFFFFF;
+      if (b >= s && b <= last - (S - 1 - s)) {
+        const FitRow rb = row[b];
+#pragma unroll 2
+        for (int aa = s - 1 + q; aa <= b - 1; aa += 4) {
+          const FitRow ra = row[aa];
+          const double c = Dp[aa] + fit_cost(ra, rb);
+          if (c < best) { best = c; besta = aa; }
         }
+      }
+      // smallest cost over the four strided scans; on equal cost the smallest a, as one scan in increasing a gives
+#pragma unroll
+      for (int x = 1; x <= 2; x <<= 1) {
+        const double ov = __shfl_xor(best, x, 64);
+        const int oa = __shfl_xor(besta, x, 64);
+        if (ov < best || (ov == best && oa < besta)) { best = ov; besta = oa; }
+      }
+      if (q == 0) {
         Dc[b] = best;
-        arg[(size_t)s * kGridPoints + b] = (short)besta;
+        arg[(size_t)s * kGridPoints + b] = (short)(best < inf ? besta : -1);
+      }
+      if (t == 0) Dc[last] = inf;
+      __syncthreads();
+    }
+    // last level (1.0) at grid index `last`: one candidate per thread, then the smallest cost (ties: smallest index)
+    {
+      const double *Dp = D[(S - 2) & 1];
+      double c = inf;
+      if (t < kThreads && t >= S - 2 && t <= last - 1) {
+        const FitRow ra = row[t], rb = row[last];
+        c = Dp[t] + fit_cost(ra, rb);
+      }
+      if (t < kThreads) {
+        rv[t] = c;
+        ri[t] = (c < inf) ? t : 0x7FFFFFFF;
       }
       __syncthreads();
+      for (int h = kThreads / 2; h >= 1; h >>= 1) {
+        if (t < h) {
+          const double ov = rv[t + h];
+          const int oi = ri[t + h];
+          if (ov < rv[t] || (ov == rv[t] && oi < ri[t])) { rv[t] = ov; ri[t] = oi; }
+        }
+        __syncthreads();
+      }
     }
   }
   if (t == 0) {
     slev[0] = 0.0f;
     slev[S - 1] = 1.0f;
     if (S > 2) {
-      const double *Dp = D[(S - 2) & 1];
-      const double gb = gd[last], p0b = P0[last], p1b = P1[last], p2b = P2[last];
-      double best = inf;
-      int besta = -1;
-      for (int aa = S - 2; aa <= last - 1; ++aa) {
-        const double ga = gd[aa];
-        const double cost = ((ga + gb) * (p1b - P1[aa]) - (p2b - P2[aa])) - (ga * gb) * (p0b - P0[aa]);
-        const double c = Dp[aa] + cost;
-        if (c < best) { best = c; besta = aa; }
-      }
-      int b = besta;
+      int b = ri[0];
       for (int s = S - 2; s >= 1; --s) {
         b = max(1, min(b, last - 1));   // cannot trigger for finite costs; keeps a corrupted table in bounds
         slev[s] = grid_value(b);
@@ -757,19 +805,14 @@ hipError_t launch_zero_u32(unsigned int *p, size_t n, hipStream_t s) {
 }
 
 hipError_t launch_sumsq(const Dev &a, bool with_hist, hipStream_t s) {
-  if (a.G == 0 || a.nnodes == 0) return hipSuccess;
-  if (with_hist) hipLaunchKernelGGL(k_sumsq<true>, dim3(a.G, a.nnodes), dim3(kThreads), 0, s, a);
-  else hipLaunchKernelGGL(k_sumsq<false>, dim3(a.G, a.nnodes), dim3(kThreads), 0, s, a);
+  if (a.GS == 0 || a.nnodes == 0) return hipSuccess;
+  if (with_hist) hipLaunchKernelGGL(k_sumsq<true>, dim3(a.GS, a.nnodes), dim3(kThreads), 0, s, a);
+  else hipLaunchKernelGGL(k_sumsq<false>, dim3(a.GS, a.nnodes), dim3(kThreads), 0, s, a);
   return hipGetLastError();
 }
 
 hipError_t launch_norm_finalize(const Dev &a, hipStream_t s) {
   hipLaunchKernelGGL(k_norm_finalize, dim3(a.L, a.nnodes), dim3(kThreads), 0, s, a);
-  return hipGetLastError();
-}
-
-hipError_t launch_write_header(const Dev &a, hipStream_t s) {
-  hipLaunchKernelGGL(k_write_header, dim3(a.L, a.nnodes), dim3(64), 0, s, a);
   return hipGetLastError();
 }
 
@@ -828,7 +871,7 @@ hipError_t launch_fit_pool(const Dev &a, hipStream_t s) {
 }
 
 hipError_t launch_fit_dp(const Dev &a, hipStream_t s) {
-  hipLaunchKernelGGL(k_fit_dp, dim3(a.M), dim3(kThreads), 0, s, a);
+  hipLaunchKernelGGL(k_fit_dp, dim3(a.M), dim3(kFitThreads), 0, s, a);
   return hipGetLastError();
 }
 
