@@ -134,11 +134,17 @@ def main() -> int:
         ctx.step(msg[cur], x1p, yp, xhp, acc, xnp, eta)
         state["cur"] = 1 - cur
 
-    for _ in range(args.warmup):
+    # warm-up rounds, all kernel classes timed: gives the per-kernel breakdown and names the dominant kernel
+    ctx.profile_enable(True)
+    for _ in range(max(args.warmup, 1)):
         one_round()
     torch.cuda.synchronize()
-    ctx.profile_read()
-    ctx.profile_enable(True)
+    warm = ctx.profile_read()
+    timed_classes = ("k_sumsq<false>", "k_sumsq<true>", "k_quantize", "k_decode<true>")
+    dom = max((n for n in warm if n in timed_classes), key=lambda n: warm[n][0])
+    # timed region: only the dominant kernel is bracketed by events (every timed launch costs a few microseconds
+    # of idle time around it, which matters for the millisecond-scale workloads)
+    ctx.profile_enable([dom])
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t_host0 = time.perf_counter()
@@ -157,20 +163,20 @@ def main() -> int:
 
     # a plain copy of known size, after the timed region: the kernel that byte counters are scaled by
     nb = min(flat_len * 4, 1 << 30) // 16 * 16
-    ctx.profile_enable(True)
+    ctx.profile_enable(["k_copy_f4"])
     for _ in range(3):
         ctx.copy_calibration(y, xh, nb)
     copy_ms, copy_n = ctx.profile_read()["k_copy_f4"]
     ctx.profile_enable(False)
 
-    _, body_off = ctx.message_layout()
-    body_bytes = mbytes - int(body_off[0])            # packed bytes per node without the header
+    c1_bits = 1 + max(1, int(np.ceil(np.log2(S))))
+    body_bytes = c1_bits / 8.0 * d                    # packed code bytes per node (sign + index), no padding
     alg = {"k_sumsq<false>": 4.0 * K * d, "k_sumsq<true>": 4.0 * K * d,
            "k_quantize": 4.0 * K * d + 2.0 * K * body_bytes,
            "k_decode<true>": float(K * body_bytes) + (20.0 if xn is not None else 16.0) * d}
-    kernels = {name: {"avg_ms": ms / n, "launches": n} for name, (ms, n) in prof.items()}
-    dom = max((n for n in kernels if n in alg), key=lambda n: prof[n][0])
-    dom_ms = kernels[dom]["avg_ms"]
+    kernels = {name: {"avg_ms": ms / n, "launches": n, "from": "warm-up rounds"} for name, (ms, n) in warm.items()}
+    dom_ms = prof[dom][0] / prof[dom][1]                 # from the timed region
+    kernels[dom] = {"avg_ms": dom_ms, "launches": prof[dom][1], "from": "timed region"}
     achieved = alg[dom] / (dom_ms * 1e-3) / 1e9
     for name in kernels:
         if name in alg:

@@ -139,7 +139,9 @@ int qoda_read_buffer(qoda_ctx *ctx, int32_t which, void *dst_host, size_t bytes,
 int qoda_status(qoda_ctx *ctx, void *stream);
 
 /* Measurement aids (no part of the method).
- * qoda_profile_enable: when on, every kernel launch is bracketed by two HIP events on the launch stream.
+ * qoda_profile_enable: launches of the kernel classes whose bit is set in class_mask (bit i = class i, see
+ *   qoda_kernel_name; 0 = off, 0xFFFFFFFF = all) are bracketed by two HIP events on the launch stream.  Each timed
+ *   launch costs a few microseconds of idle time around it.
  * qoda_profile_read: waits for `stream`, then returns, per kernel class, the summed elapsed milliseconds and the
  *   number of launches since the last read (host arrays of QODA_NUM_KERNELS entries) and resets both.
  * qoda_kernel_name: the kernel's name for a class index (as it appears in a profiler's kernel trace), "" if out
@@ -147,7 +149,7 @@ int qoda_status(qoda_ctx *ctx, void *stream);
  * qoda_copy_calibration: a plain 128-bit copy kernel of `bytes` bytes (multiple of 16; 16-byte aligned device
  *   pointers): the known-traffic kernel that hardware byte counters are scaled by. */
 #define QODA_NUM_KERNELS 15
-int qoda_profile_enable(qoda_ctx *ctx, int32_t on);
+int qoda_profile_enable(qoda_ctx *ctx, uint32_t class_mask);
 int qoda_profile_read(qoda_ctx *ctx, double *ms, int64_t *launches, void *stream);
 const char *qoda_kernel_name(int32_t id);
 int qoda_copy_calibration(qoda_ctx *ctx, const void *src_dev, void *dst_dev, size_t bytes, void *stream);

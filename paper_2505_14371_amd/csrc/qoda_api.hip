@@ -59,7 +59,7 @@ struct qoda_ctx {
   std::vector<float> h_lev;   // host shadow of the level tables (source of asynchronous uploads)
   // optional per-kernel event timing
   struct ProfRec { int id; hipEvent_t a, b; };
-  bool prof_on = false;
+  unsigned int prof_mask = 0;   // bit i: time kernel class i
   std::vector<ProfRec> prof_recs;
   std::vector<hipEvent_t> prof_pool;
   double prof_ms[kNumKernelIds] = {};
@@ -98,13 +98,14 @@ hipError_t prof_event(qoda_ctx *c, hipEvent_t *e) {
 #define LAUNCH(c, id, s, call)                                                   \
   do {                                                                           \
     qoda_ctx::ProfRec r_{(id), nullptr, nullptr};                                \
-    if ((c)->prof_on) {                                                          \
+    const bool timed_ = (((c)->prof_mask >> (id)) & 1u) != 0u;                  \
+    if (timed_) {                                                                \
       HIP_TRY((c), prof_event((c), &r_.a));                                      \
       HIP_TRY((c), prof_event((c), &r_.b));                                      \
       HIP_TRY((c), hipEventRecord(r_.a, (s)));                                   \
     }                                                                            \
     HIP_TRY((c), (call));                                                        \
-    if ((c)->prof_on) {                                                          \
+    if (timed_) {                                                                \
       HIP_TRY((c), hipEventRecord(r_.b, (s)));                                   \
       (c)->prof_recs.push_back(r_);                                              \
     }                                                                            \
@@ -583,9 +584,9 @@ int qoda_status(qoda_ctx *c, void *stream) {
   return QODA_OK;
 }
 
-int qoda_profile_enable(qoda_ctx *c, int32_t on) {
+int qoda_profile_enable(qoda_ctx *c, uint32_t class_mask) {
   if (!c) return QODA_EINVAL;
-  c->prof_on = on != 0;
+  c->prof_mask = class_mask;
   return QODA_OK;
 }
 

@@ -1,6 +1,6 @@
 // qoda_probe: a torch-free driver of libqoda's C ABI for profilers and hardware counters.
 //
-//   qoda_probe <sizes.txt> <K> <S> <rounds> [adaptive=1] [copy_mib=1024]
+//   qoda_probe <sizes.txt> <K> <S> <rounds> [adaptive=1] [copy_mib=1024] [time_classes=0xFFFFFFFF]
 //
 // sizes.txt holds one layer size per line (python -m paper_2505_14371_amd.workloads <name> writes it).  The
 // probe fills K gradient buffers with heavy-tailed synthetic values (one scale per layer), runs `rounds` rounds
@@ -51,6 +51,7 @@ int main(int argc, char **argv) {
   const int L = (int)sizes.size(), K = atoi(argv[2]), S = atoi(argv[3]), rounds = atoi(argv[4]);
   const bool adaptive = argc > 5 ? atoi(argv[5]) != 0 : true;
   const size_t copy_bytes = (size_t)(argc > 6 ? atoll(argv[6]) : 1024) << 20;
+  const uint32_t time_classes = argc > 7 ? (uint32_t)strtoul(argv[7], nullptr, 0) : 0xFFFFFFFFu;
   if (L < 1 || K < 1 || S < 2 || rounds < 1) { fprintf(stderr, "bad arguments\n"); return 2; }
 
   std::vector<int32_t> types(L), points(L, S);
@@ -97,7 +98,7 @@ int main(int argc, char **argv) {
     x1p[l] = x1 + off[l]; yp[l] = y + off[l]; xhp[l] = xh + off[l];
   }
   qoda_state st = {x1p.data(), yp.data(), xhp.data(), nullptr, acc, nullptr};
-  QK(qoda_profile_enable(ctx, 1));
+  QK(qoda_profile_enable(ctx, time_classes));
   hipEvent_t e0, e1;
   CK(hipEventCreate(&e0));
   CK(hipEventCreate(&e1));
@@ -127,6 +128,7 @@ int main(int argc, char **argv) {
   const int status = qoda_status(ctx, nullptr);
   printf("status=%d\n", status);
 
+  QK(qoda_profile_enable(ctx, 0xFFFFFFFFu));
   size_t cb = copy_bytes;
   if (cb > (size_t)total * 4) cb = (size_t)total * 4 / 16 * 16;
   for (int i = 0; i < 3; ++i) QK(qoda_copy_calibration(ctx, y, xh, cb, nullptr));

@@ -27,8 +27,12 @@ def _one(pattern: str) -> str:
 
 
 def _short(name: str) -> str:
-    m = re.search(r"(k_[a-z0-9_]+(<[a-z]+>)?)", name)
-    return m.group(1) if m else name[:60]
+    """qoda::k_decode<4, true>(qoda::Dev) -> k_decode<true>; qoda::k_quantize<4>(...) -> k_quantize."""
+    m = re.search(r"(k_[a-z0-9_]+)(<[^>]*>)?", name)
+    if not m:
+        return name[:60]
+    args = [a.strip() for a in (m.group(2) or "<>")[1:-1].split(",") if a.strip() and not a.strip().isdigit()]
+    return m.group(1) + ("<" + ", ".join(args) + ">" if args else "")
 
 
 def _counters(directory: str):
@@ -45,14 +49,24 @@ def main():
     ap.add_argument("--stats", required=True)
     ap.add_argument("--fetch")
     ap.add_argument("--write")
-    ap.add_argument("--probe-log", required=True)
+    ap.add_argument("--probe-log", help="stdout of qoda_probe (states the copy kernel's true size); needed with --fetch/--write")
+    ap.add_argument("--bench-json", help="the JSON line bench.py printed under the same rocprofv3 run")
     ap.add_argument("--command", required=True)
     ap.add_argument("--out", default="profiles")
     a = ap.parse_args()
-    log = open(a.probe_log).read()
-    copy_bytes = int(re.search(r"k_copy_f4.*bytes_read=(\d+)", log).group(1))
-    lines = [f"# rocprofv3 summary: {a.name}", "# command:", "#   " + a.command, "#", "# probe output:"]
-    lines += ["#   " + l for l in log.strip().splitlines()]
+    lines = [f"# rocprofv3 summary: {a.name}", "# command:", "#   " + a.command, "#"]
+    copy_bytes = None
+    if a.probe_log:
+        log = open(a.probe_log).read()
+        copy_bytes = int(re.search(r"k_copy_f4.*bytes_read=(\d+)", log).group(1))
+        lines += ["# probe output:"] + ["#   " + l for l in log.strip().splitlines()]
+    if a.bench_json:
+        b = json.loads(open(a.bench_json).read().strip().splitlines()[-1])
+        r = b["roofline"]
+        lines += ["# bench.py line of this run (HIP events inside the timed region):",
+                  f"#   workload={b['config']['workload']} ms_per_step={b['ms_per_step']:.4f} value={b['value']:.1f} {b['unit']} "
+                  f"hbm_peak_fraction_algorithmic={b['hbm_peak_fraction_algorithmic']:.4f}",
+                  f"#   roofline: kernel={r['kernel']} avg_ms={r['avg_ms']:.4f} achieved={r['achieved']:.1f} GB/s frac={r['frac']:.4f}"]
     lines += ["", "kernel-trace --stats (ours only):", f"{'kernel':<22}{'calls':>7}{'avg_us':>12}{'min_us':>12}{'max_us':>12}{'pct':>8}"]
     for r in csv.DictReader(open(_one(os.path.join(a.stats, "**", "*_kernel_stats.csv")))):
         if "qoda::" not in r["Name"]:

@@ -65,7 +65,7 @@ def load():
     L.qoda_step.argtypes = [vp, pp, C.POINTER(_State), vp]
     L.qoda_read_buffer.argtypes = [vp, C.c_int32, vp, C.c_size_t, vp]
     L.qoda_status.argtypes = [vp, vp]
-    L.qoda_profile_enable.argtypes = [vp, C.c_int32]
+    L.qoda_profile_enable.argtypes = [vp, C.c_uint32]
     L.qoda_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), vp]
     L.qoda_kernel_name.argtypes = [C.c_int32]
     L.qoda_kernel_name.restype = C.c_char_p
@@ -205,8 +205,18 @@ class Context:
         return int(self._lib.qoda_status(self._h, _stream(stream)))
 
     # -- measurement aids
-    def profile_enable(self, on: bool = True):
-        self._check(self._lib.qoda_profile_enable(self._h, 1 if on else 0))
+    def profile_enable(self, classes=True):
+        """classes: True (all kernel classes), False (off), or an iterable of kernel names to time."""
+        if classes is True:
+            mask = 0xFFFFFFFF
+        elif not classes:
+            mask = 0
+        else:
+            names = [kernel_name(i) for i in range(NUM_KERNELS)]
+            mask = 0
+            for n in classes:
+                mask |= 1 << names.index(n)
+        self._check(self._lib.qoda_profile_enable(self._h, mask))
 
     def profile_read(self, stream=None):
         """{kernel name: (total ms, launches)} since the last read."""
