@@ -72,6 +72,8 @@ def lib():
         L.oracle_unpack_layer.restype = None
         L.oracle_quantize.argtypes = [C.c_int32, i64p, i32p, pp, pp, C.c_uint64, C.c_uint32, C.c_uint32, u8p, u8p, dp, dp]
         L.oracle_quantize.restype = C.c_int32
+        L.oracle_delta_from_messages.argtypes = [C.c_int32, i64p, i32p, u8p, u8p]
+        L.oracle_delta_from_messages.restype = C.c_double
         L.oracle_dequant_aggregate.argtypes = [C.c_int32, i64p, i32p, C.c_int32, pp, pp]
         L.oracle_dequant_aggregate.restype = None
         L.oracle_step_size.argtypes = [C.c_int32, dp, dp, fp]
@@ -241,6 +243,14 @@ def quantize(sizes, points, levels: Sequence[np.ndarray], grads: Sequence[np.nda
                                node, _p(msg, C.c_uint8), None if prev is None else _p(prev, C.c_uint8),
                                _p(ss, C.c_double), _p(delta, C.c_double))
     return msg, ss, float(delta[0]), int(st)
+
+
+def delta_from_messages(sizes, points, msg, msg_prev=None) -> float:
+    d, S = _dims(sizes, points)
+    m = np.ascontiguousarray(msg, dtype=np.uint8)
+    p = None if msg_prev is None else np.ascontiguousarray(msg_prev, dtype=np.uint8)
+    return float(lib().oracle_delta_from_messages(d.size, _p(d, C.c_int64), _p(S, C.c_int32), _p(m, C.c_uint8),
+                                                  None if p is None else _p(p, C.c_uint8)))
 
 
 def dequant_aggregate(sizes, points, msgs: Sequence[np.ndarray]) -> List[np.ndarray]:

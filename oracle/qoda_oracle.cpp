@@ -394,6 +394,40 @@ int32_t oracle_quantize(int32_t L, const int64_t *d, const int32_t *S, const flo
   return status;
 }
 
+// ---------------------------------------------------------------- step-size term from two stored messages
+// || DECODE(msg) - DECODE(msg_prev) ||^2 in the same order as oracle_quantize accumulates it (msg_prev NULL: zeros).
+// Lets a test check delta_k of a full-size model without quantizing it on the CPU.
+double oracle_delta_from_messages(int32_t L, const int64_t *d, const int32_t *S, const uint8_t *msg,
+                                  const uint8_t *msg_prev) {
+  const Layout lay = make_layout(L, d, S);
+  std::vector<double> delta_chunks;
+  for (int l = 0; l < L; ++l) {
+    const HeaderView hc = header_of(msg, lay, l);
+    const int64_t nchunks = (d[l] + kChunk - 1) / kChunk;
+    for (int64_t c = 0; c < nchunks; ++c) {
+      float p32[kSlots];
+      for (int j = 0; j < kSlots; ++j) p32[j] = 0.0f;
+      const int64_t e1 = std::min(d[l], (c + 1) * kChunk);
+      for (int64_t e = c * kChunk; e < e1; ++e) {
+        const Code cc = get_code(msg + lay.msg_off[l], lay.planes[l], e);
+        const float cur = decode_value(cc.sign, cc.h, hc.norm, hc.lev, S[l]);
+        float prev = 0.0f;
+        if (msg_prev) {
+          const HeaderView hp = header_of(msg_prev, lay, l);
+          const Code pc = get_code(msg_prev + lay.msg_off[l], lay.planes[l], e);
+          prev = decode_value(pc.sign, pc.h, hp.norm, hp.lev, S[l]);
+        }
+        const float diff = cur - prev;
+        p32[slot_of(e)] = std::fmaf(diff, diff, p32[slot_of(e)]);
+      }
+      double p[kSlots];
+      for (int j = 0; j < kSlots; ++j) p[j] = (double)p32[j];
+      delta_chunks.push_back(halving_tree(p));
+    }
+  }
+  return combine_chunks(delta_chunks);
+}
+
 // ---------------------------------------------------------------- DECODE + mean over the K nodes: Alg. 1 lines 15-17
 // mean_out[l][e] = ((Vhat_0 + Vhat_1) + ... + Vhat_{K-1}) * (1/K), all in fp32, k increasing.
 void oracle_dequant_aggregate(int32_t L, const int64_t *d, const int32_t *S, int32_t K, const uint8_t *const *msgs,

@@ -1,0 +1,178 @@
+"""Full-size GPU parity, in the launch configuration bench.py times (all K nodes, every tensor of the workload,
+fit -> quantize_all -> step, two rounds so that the previous-message path is exercised).
+
+The oracle cannot redo 10^9..2*10^10 (node, coordinate) pairs in test time, so the big workloads are checked on
+pieces it can compute one by one: whole small tensors, and octet-aligned slices (first, middle, ragged tail) of
+the big ones -- norms, histograms, fitted levels, packed codes, the per-node step-size term (recomputed by the
+oracle from the two stored messages of a node), and the updated iterates on those pieces.  The DCGAN-shaped
+workload is small enough to be compared in full."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from paper_2505_14371_amd import qoda, workloads  # noqa: E402
+
+OCT = 2048
+
+
+def uniform_levels(S):
+    return (np.arange(S, dtype=np.float64) / (S - 1)).astype(np.float32)
+
+
+class Full:
+    def __init__(self, name):
+        if not torch.cuda.is_available():
+            pytest.fail("a GPU test was selected but no GPU is visible")
+        self.dev = torch.device("cuda:0")
+        self.w = w = workloads.get(name)
+        self.L, self.K, self.S = len(w.sizes), w.num_nodes, w.points
+        self.ctx = qoda.Context(w.sizes, list(range(self.L)), [self.S] * self.L, self.K, w.seed)
+        self.off, self.n = workloads.padded_offsets(w.sizes)
+        self.grad = [torch.zeros(self.n, dtype=torch.float32, device=self.dev) for _ in range(self.K)]
+        self.mbytes = self.ctx.message_bytes()
+        self.msg = [[torch.zeros(self.mbytes, dtype=torch.uint8, device=self.dev) for _ in range(self.K)] for _ in range(2)]
+        gen = torch.Generator(device=self.dev)
+        gen.manual_seed(1234 + w.seed)
+        self.x1 = torch.randn(self.n, dtype=torch.float32, device=self.dev, generator=gen)
+        self.y = torch.zeros_like(self.x1)
+        self.xh = torch.zeros_like(self.x1)
+        self.acc = torch.zeros(1, dtype=torch.float64, device=self.dev)
+        self.eta = torch.ones(2, dtype=torch.float32, device=self.dev)
+        self.hdr_off, self.body_off = self.ctx.message_layout()
+        self.c1 = 1 + max(1, int(np.ceil(np.log2(self.S))))
+
+    def ptrs(self, t):
+        return [t.data_ptr() + 4 * int(o) for o in self.off]
+
+    def gptrs(self):
+        return [p for k in range(self.K) for p in self.ptrs(self.grad[k])]
+
+    def fill(self, round_):
+        for k in range(self.K):
+            workloads.node_torch(self.w, k, round_, self.dev, out=self.grad[k])
+
+    def layer(self, flat, l, e0=0, e1=None):
+        e1 = self.w.sizes[l] if e1 is None else e1
+        return flat[int(self.off[l]) + e0: int(self.off[l]) + e1].cpu().numpy()
+
+    def round_(self, t):
+        cur = (t - 1) & 1
+        if self.w.adaptive:
+            self.ctx.fit_levels(self.gptrs(), t)
+        self.ctx.quantize_all(self.gptrs(), t, self.msg[cur], self.msg[1 - cur] if t > 1 else None)
+        deltas = self.ctx.read_buffer(qoda.BUF_DELTA)
+        acc_before = float(self.acc.cpu()[0])
+        self.ctx.step(self.msg[cur], self.ptrs(self.x1), self.ptrs(self.y), self.ptrs(self.xh), self.acc, None, self.eta)
+        torch.cuda.synchronize()
+        return cur, deltas, acc_before
+
+    def header(self, msg_host, l):
+        h = msg_host[int(self.hdr_off[l]): int(self.hdr_off[l]) + 4 * (1 + self.S)].view(np.float32)
+        return h[0], h[1:].copy()
+
+    def body_slice(self, msg, l, e0, e1):
+        """Packed bytes of the octets covering coordinates [e0, e1) of layer l (e0 a multiple of 2048)."""
+        o0, o1 = e0 // OCT, (e1 + OCT - 1) // OCT
+        b0 = int(self.body_off[l]) + o0 * 256 * self.c1
+        return msg[b0: b0 + (o1 - o0) * 256 * self.c1].cpu().numpy()
+
+
+def pieces_for(w, whole_limit=3_000_000):
+    """(layer, e0, e1): whole tensors when small, else the first octets, a middle run and the ragged tail."""
+    L = len(w.sizes)
+    big = int(np.argmax(w.sizes))
+    layers = sorted({0, 1, 2, 3, min(10, L - 1), big, L - 2, L - 1} & set(range(L)))
+    out = []
+    for l in layers:
+        d = w.sizes[l]
+        if d <= whole_limit:
+            out.append((l, 0, d))
+        else:
+            mid = (d // 2) // OCT * OCT
+            tail = (d - 1) // OCT * OCT - 2 * OCT
+            out += [(l, 0, 3 * OCT), (l, mid, mid + 2 * OCT), (l, tail, d)]
+    return out
+
+
+@pytest.mark.timeout(1200)
+@pytest.mark.parametrize("name", ["dcgan", "txl", "gpt1p3b"])
+def test_full_size_two_rounds(oracle, name):
+    f = Full(name)
+    w, K, L, S = f.w, f.K, f.L, f.S
+    pieces = [(l, 0, w.sizes[l]) for l in range(L)] if name == "dcgan" else pieces_for(w)
+    layers = sorted({p[0] for p in pieces})
+    check_nodes = list(range(K)) if name == "dcgan" else [0, K - 1]
+    prev_levels = {l: uniform_levels(S) for l in layers}
+    prev_msgs_host = None
+    for t in (1, 2):
+        f.fill(t)
+        y_old = {p: f.layer(f.y, p[0], p[1], p[2]) for p in pieces}
+        cur, deltas, acc_before = f.round_(t)
+        assert f.ctx.status() == qoda.OK
+        ss = f.ctx.read_buffer(qoda.BUF_SUMSQ)
+        nr = f.ctx.read_buffer(qoda.BUF_NORM)
+        iv = f.ctx.read_buffer(qoda.BUF_INV)
+        hist = f.ctx.read_buffer(qoda.BUF_HIST) if w.adaptive else None
+        pooled = f.ctx.read_buffer(qoda.BUF_POOLED) if w.adaptive else None
+        # ---- per layer: norms of every node, histogram + pooled weights + fitted levels
+        levels = {}
+        for l in layers:
+            host = [f.layer(f.grad[k], l) for k in range(K)]
+            for k in range(K):
+                s = oracle.sumsq(host[k])
+                assert ss[k, l] == s, (t, k, l)
+                n = oracle.sqrt_floor(s)
+                assert nr[k, l] == n and iv[k, l] == oracle.rcp_floor(n)
+            if w.adaptive:
+                levs, oh, op, st = oracle.fit_levels([w.sizes[l]], [0], [S], K, host, [prev_levels[l]])
+                assert st == 0
+                assert np.array_equal(hist[:, l, :], oh[:, 0, :]), (t, l)
+                assert np.array_equal(pooled[l], op[0]), (t, l)
+                levels[l] = levs[0]
+                assert np.array_equal(f.ctx.get_levels(l), levs[0]), (t, l)
+            else:
+                levels[l] = prev_levels[l]
+            # ---- packed codes of the checked nodes on this layer's pieces
+            for k in check_nodes:
+                mh_norm, mh_lev = f.header(f.msg[cur][k][: int(f.body_off[0])].cpu().numpy(), l)
+                assert mh_norm == nr[k, l] and np.array_equal(mh_lev, levels[l])
+                for (pl, e0, e1) in pieces:
+                    if pl != l:
+                        continue
+                    sign, idx = oracle.quantize_range(host[k], e0, e1, iv[k, l], levels[l], w.seed, t, k, l)
+                    gs, gi = oracle.unpack_layer(f.body_slice(f.msg[cur][k], l, e0, e1), e1 - e0, S)
+                    assert np.array_equal(gs, sign) and np.array_equal(gi, idx), (t, k, l, e0)
+            del host
+        prev_levels = levels
+        # ---- step-size term of one node, recomputed by the oracle from the node's two stored messages
+        k = check_nodes[-1]
+        cur_host = f.msg[cur][k].cpu().numpy()
+        prev_host = f.msg[1 - cur][k].cpu().numpy() if t > 1 else None
+        if name != "gpt1p3b" or t == 2:          # 1.3e9 coordinates take the oracle about a minute: once is enough
+            want = oracle.delta_from_messages(w.sizes, [S] * L, cur_host, prev_host)
+            assert deltas[k] == want, (t, k)
+        del cur_host, prev_host
+        acc, eta = oracle.step_size(deltas, acc_before)
+        assert float(f.acc.cpu()[0]) == acc and float(f.eta.cpu()[0]) == float(eta)
+        # ---- decode + mean + update on the pieces: sub-messages (header entry + octets of the piece) per node
+        for (l, e0, e1) in pieces:
+            sub = []
+            for kk in range(K):
+                hdr = f.msg[cur][kk][int(f.hdr_off[l]): int(f.hdr_off[l]) + 4 * (1 + S)].cpu().numpy()
+                body = f.body_slice(f.msg[cur][kk], l, e0, e1)
+                hb = oracle.header_bytes([e1 - e0], [S])
+                m = np.zeros(oracle.message_bytes([e1 - e0], [S]), np.uint8)
+                m[: hdr.size] = hdr
+                m[hb: hb + body.size] = body
+                sub.append(m)
+            mean = oracle.dequant_aggregate([e1 - e0], [S], sub)[0]
+            yv = y_old[(l, e0, e1)].copy()
+            x1 = f.layer(f.x1, l, e0, e1)
+            _, xh = oracle.oda_update(mean, x1, yv, eta, eta, want_next=False)
+            gy, gxh = f.layer(f.y, l, e0, e1), f.layer(f.xh, l, e0, e1)
+            for a, b in ((gy, yv), (gxh, xh)):
+                tol = 1e-6 * np.abs(b) + 1e-9 * np.abs(b).max()
+                assert np.all(np.abs(a.astype(np.float64) - b) <= tol), (t, l, e0)

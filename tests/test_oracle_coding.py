@@ -129,6 +129,8 @@ def test_delta_is_the_squared_distance_to_the_previous_decoded_message(oracle):
     v2 = oracle.dequant_aggregate(w.sizes, points, [m2])      # each message carries its own levels
     want = sum(float(np.sum((a.astype(np.float64) - b.astype(np.float64)) ** 2)) for a, b in zip(v2, v1))
     assert d2 == pytest.approx(want, rel=1e-5)
+    assert oracle.delta_from_messages(w.sizes, points, m2, m1) == d2       # same terms, same order
+    assert oracle.delta_from_messages(w.sizes, points, m1) == d1
     assert d1 == pytest.approx(sum(float(np.sum(a.astype(np.float64) ** 2)) for a in v1), rel=1e-5)
 
 
