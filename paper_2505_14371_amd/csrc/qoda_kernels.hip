@@ -294,10 +294,12 @@ __device__ __forceinline__ void quantize_block(const float (&x)[4], const unsign
                                                float &acc) {
   float u[4];
   int tau[4];
-  float4 lv[4];                    // {l_tau, 1/gap, l_tau+1, norm*l_tau}; entry S-1 = {1, 0, +inf, norm}
+  float4 lv[4];                    // {l_tau, 1/gap, l_tau+1, -}; entry S-1 = {1, 0, +inf, -}
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    u[j] = fminf(fabsf(x[j]) * inv, 1.0f);
+    // min(|v| * inv, 1): the product is never negative or NaN for finite input, so the [0, 1] clamp of the
+    // multiply instruction is the same thing
+    u[j] = __builtin_amdgcn_fmed3f(fabsf(x[j]) * inv, 0.0f, 1.0f);
     tau[j] = lut[f2u(u[j]) >> 20];
   }
 #pragma unroll
@@ -319,7 +321,8 @@ __device__ __forceinline__ void quantize_block(const float (&x)[4], const unsign
     // is exact whenever its result is not negative, so one fused operation decides the same.
     const bool up = (float)w16 < __builtin_fmaf(xi, 65536.0f, -0.5f);
     const unsigned int h = (unsigned int)tau[j] + (up ? 1u : 0u);
-    const float mag = up ? norm * lv[j].z : lv[j].w;   // norm * l_h, the value the decoder will rebuild
+    // norm * l_h, the value the decoder will rebuild (the +inf of the last entry is never selected: there xi = 0)
+    const float mag = norm * (up ? lv[j].z : lv[j].x);
     const float cur = __builtin_copysignf(mag, x[j]);
     insert_code<C1>(D, (h << 1) | (f2u(x[j]) >> 31), 24 + jl);
     const float pv = lds_float_at(tprev, extract_off<C1>(Dp, jl));  // all zero without a previous message
@@ -433,7 +436,7 @@ __global__ void __launch_bounds__(kThreads) k_quantize(Dev a) {
   if (t < m.S) {
     const float lj = lev[t];
     const float ln = (t + 1 < m.S) ? lev[t + 1] : __builtin_inff();   // the last entry stops every walk
-    tab[t] = make_float4(lj, (t + 1 < m.S) ? rg[t] : 0.0f, ln, norm * lj);
+    tab[t] = make_float4(lj, (t + 1 < m.S) ? rg[t] : 0.0f, ln, 0.0f);
   }
   if (tile.y == 0) {   // message header of this layer: {norm, levels[S]} (Sec. 3.2: the norm in C_q = 32 bits)
     float *h = reinterpret_cast<float *>(a.msg[k] + m.hdr_off);
