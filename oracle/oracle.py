@@ -80,6 +80,12 @@ def lib():
         L.oracle_step_size.restype = None
         L.oracle_oda_update.argtypes = [C.c_int64, fp, fp, fp, fp, fp, C.c_float, C.c_float]
         L.oracle_oda_update.restype = None
+        L.oracle_alt_step_size.argtypes = [C.c_double, C.c_double, C.c_double, fp, fp]
+        L.oracle_alt_step_size.restype = None
+        L.oracle_alt_advance.argtypes = [C.c_int32, dp, C.c_double, dp, dp]
+        L.oracle_alt_advance.restype = None
+        L.oracle_oda_update_alt.argtypes = [C.c_int32, i64p, pp, pp, pp, pp, pp, C.c_float, C.c_float, C.c_float]
+        L.oracle_oda_update_alt.restype = C.c_double
         L.oracle_histogram.argtypes = [fp, C.c_int64, u32p]
         L.oracle_histogram.restype = None
         L.oracle_fit_objective.argtypes = [u64p, fp, C.c_int32]
@@ -281,6 +287,38 @@ def oda_update(mean, x1, y, eta, gamma, want_next: bool = True):
                             None if xn is None else _p(xn, C.c_float), _p(xh, C.c_float), C.c_float(float(eta)),
                             C.c_float(float(gamma)))
     return xn, xh
+
+
+def alt_step_size(lam: float, mu: float, q_hat: float):
+    """eq. (Alt): returns (eta, gamma) from the lagged sums."""
+    eta = np.zeros(1, dtype=np.float32)
+    gamma = np.zeros(1, dtype=np.float32)
+    lib().oracle_alt_step_size(float(lam), float(mu), float(q_hat), _p(eta, C.c_float), _p(gamma, C.c_float))
+    return np.float32(eta[0]), np.float32(gamma[0])
+
+
+def alt_advance(delta: Sequence[float], dx2: float, lam: float, mu: float):
+    """Returns the sums (lambda, mu) after a round."""
+    dl = np.ascontiguousarray(delta, dtype=np.float64)
+    a = np.array([lam], dtype=np.float64)
+    b = np.array([mu], dtype=np.float64)
+    lib().oracle_alt_advance(dl.size, _p(dl, C.c_double), float(dx2), _p(a, C.c_double), _p(b, C.c_double))
+    return float(a[0]), float(b[0])
+
+
+def oda_update_alt(sizes, mean, x1, y, eta_prev, eta, gamma, want_next: bool = True):
+    """All layers, in place on the ``y`` arrays.  Returns (x_next list or None, x_half list, ||X_t - X_{t+1}||^2)."""
+    d = np.ascontiguousarray(sizes, dtype=np.int64)
+    mean = [_f32(a) for a in mean]
+    x1 = [_f32(a) for a in x1]
+    for a in y:
+        assert a.dtype == np.float32 and a.flags.c_contiguous
+    xn = [np.zeros_like(a) for a in y] if want_next else None
+    xh = [np.zeros_like(a) for a in y]
+    dx2 = lib().oracle_oda_update_alt(d.size, _p(d, C.c_int64), _ptr_array(mean), _ptr_array(x1), _ptr_array(y),
+                                      None if xn is None else _ptr_array(xn), _ptr_array(xh),
+                                      C.c_float(float(eta_prev)), C.c_float(float(eta)), C.c_float(float(gamma)))
+    return xn, xh, float(dx2)
 
 
 # ------------------------------------------------------------------ level fit

@@ -17,6 +17,7 @@
 //                                                                                 the weights lambda_z
 //   * optimistic dual averaging update and adaptive step size                -- Sec. 4, eq. (ODA),
 //                                                                                 eq. (general_stepsize), Alg. 1
+//   * the alternative pair of step sizes lagged by two rounds                  -- Sec. 6, eq. (Alt)
 //
 // Pin status (see tests/test_oracle_*.py): every function below is pinned to something the paper or the
 // mathematics fixes EXCEPT the Philox generator's known-answer vectors: no published known-answer
@@ -471,6 +472,72 @@ void oracle_oda_update(int64_t n, const float *mean, const float *x1, float *y, 
     if (x_next) x_next[e] = xn;
     x_half[e] = xn - gm;
   }
+}
+
+// ---------------------------------------------------------------- alternative step sizes: eq. (Alt), Sec. 6
+// With lambda = sum_{s<=t-2} sum_k ||Vhat_{k,s+1/2}||^2 / K^2 and mu = sum_{s<=t-2} ||X_s - X_{s+1}||^2:
+//   eta_t = (1 + lambda + mu)^(-1/2),  gamma_t = (1 + lambda)^(q - 1/2),  0 < q <= 1/4.
+// (The main text and the appendix's choice of rates both sum the K squared norms; the appendix's lemma
+// notation squares the norm of the sum instead.  The first form is taken here.)
+// eta is taken as in eq. (general_stepsize): rcp_floor(sqrt_floor(.)).  The power with the free exponent q is
+// built from correctly rounded operations only, so that it does not depend on a library's pow: q is cut to its
+// first 32 binary digits q = sum_j b_j 2^-j, r_j = sqrt(r_{j-1}) with r_0 = 1 + lambda, (1+lambda)^q = product of
+// the r_j with b_j = 1 (j increasing, fp64), gamma = fp32((1+lambda)^q / sqrt(1+lambda)).
+void oracle_alt_step_size(double lambda, double mu, double q, float *eta_out, float *gamma_out) {
+  *eta_out = rcp_floor(sqrt_floor(1.0 + lambda + mu));
+  const double base = 1.0 + lambda;
+  const uint64_t digits = (uint64_t)std::floor(std::ldexp(q, 32));   // b_1 is the most significant of 32 bits
+  double r = base, p = 1.0;
+  for (int j = 1; j <= 32; ++j) {
+    r = std::sqrt(r);
+    if ((digits >> (32 - j)) & 1u) p = p * r;
+  }
+  *gamma_out = (float)(p / std::sqrt(base));
+}
+
+// After round t: lambda <- lambda + (delta_0 + ... + delta_{K-1}) / K^2 with delta_k = ||Vhat_{k,t+1/2}||^2 (the
+// quantizer's squared-distance output against an all-zero previous message), mu <- mu + ||X_t - X_{t+1}||^2.
+void oracle_alt_advance(int32_t K, const double *delta, double dx2, double *lambda, double *mu) {
+  double sum = 0.0;
+  for (int k = 0; k < K; ++k) sum = (k == 0) ? delta[k] : sum + delta[k];
+  const double invK2 = 1.0 / ((double)K * (double)K);
+  *lambda = *lambda + sum * invK2;
+  *mu = *mu + dx2;
+}
+
+// eq. (ODA) over all layers with the two rates of eq. (Alt), returning ||X_t - X_{t+1}||^2 where
+// X_t = X_1 + eta_prev * Y_t is rebuilt from the state (the same two fp32 operations that produced it).
+// The squared differences are summed like the step-size term of the main rule: per slot an fp32 fused chain in
+// increasing coordinate, slots widened to fp64 and reduced by the tree, chunks numbered through all layers.
+double oracle_oda_update_alt(int32_t L, const int64_t *d, const float *const *mean, const float *const *x1,
+                             float *const *y, float *const *x_next /* may be NULL */, float *const *x_half,
+                             float eta_prev, float eta, float gamma) {
+  std::vector<double> chunks;
+  for (int l = 0; l < L; ++l) {
+    const int64_t nchunks = (d[l] + kChunk - 1) / kChunk;
+    for (int64_t c = 0; c < nchunks; ++c) {
+      float p32[kSlots];
+      for (int j = 0; j < kSlots; ++j) p32[j] = 0.0f;
+      const int64_t e1 = std::min(d[l], (c + 1) * kChunk);
+      for (int64_t e = c * kChunk; e < e1; ++e) {
+        const float ey_old = eta_prev * y[l][e];
+        const float xt = x1[l][e] + ey_old;          // X_t
+        const float yn = y[l][e] - mean[l][e];       // Y_{t+1}
+        const float ey = eta * yn;
+        const float xn = x1[l][e] + ey;              // X_{t+1}
+        const float gm = gamma * mean[l][e];
+        y[l][e] = yn;
+        if (x_next) x_next[l][e] = xn;
+        x_half[l][e] = xn - gm;                      // X_{t+3/2}
+        const float diff = xt - xn;
+        p32[slot_of(e)] = std::fmaf(diff, diff, p32[slot_of(e)]);
+      }
+      double p[kSlots];
+      for (int j = 0; j < kSlots; ++j) p[j] = (double)p32[j];
+      chunks.push_back(halving_tree(p));
+    }
+  }
+  return combine_chunks(chunks);
 }
 
 // ---------------------------------------------------------------- level fit: eq. (Qada2), weights lambda_z
