@@ -87,6 +87,8 @@ def main() -> int:
     ap.add_argument("--workload", default="gpt1p3b", choices=["bilinear", "microbench", "dcgan", "txl", "gpt1p3b"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--x-next", action="store_true", help="also materialise X_{t+1}")
+    ap.add_argument("--q-hat", type=float, default=0.0,
+                    help="> 0: the step sizes of eq. (Alt) with this exponent instead of eq. (general_stepsize)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (the K nodes are K message buffers on one device); "
@@ -120,6 +122,8 @@ def main() -> int:
     xn = torch.zeros(flat_len, dtype=torch.float32, device=dev) if args.x_next else None
     acc = torch.zeros(1, dtype=torch.float64, device=dev)
     eta = torch.ones(2, dtype=torch.float32, device=dev)
+    alt = args.q_hat > 0.0
+    alt_sums = torch.zeros(2, dtype=torch.float64, device=dev)
     gptrs = [p for k in range(K) for p in ptrs(grad[k])]
     x1p, yp, xhp = ptrs(x1), ptrs(y), ptrs(xh)
     xnp = ptrs(xn) if xn is not None else None
@@ -130,8 +134,11 @@ def main() -> int:
         t, cur = state["t"], state["cur"]
         if w.adaptive:
             ctx.fit_levels(gptrs, t)
-        ctx.quantize_all(gptrs, t, msg[cur], msg[1 - cur] if t > 1 else None)
-        ctx.step(msg[cur], x1p, yp, xhp, acc, xnp, eta)
+        ctx.quantize_all(gptrs, t, msg[cur], msg[1 - cur] if (t > 1 and not alt) else None)
+        if alt:
+            ctx.step_alt(msg[cur], x1p, yp, xhp, alt_sums, eta, args.q_hat, xnp)
+        else:
+            ctx.step(msg[cur], x1p, yp, xhp, acc, xnp, eta)
         state["cur"] = 1 - cur
 
     # warm-up rounds, all kernel classes timed: gives the per-kernel breakdown and names the dominant kernel
@@ -140,7 +147,8 @@ def main() -> int:
         one_round()
     torch.cuda.synchronize()
     warm = ctx.profile_read()
-    timed_classes = ("k_sumsq<false>", "k_sumsq<true>", "k_quantize", "k_decode<true>")
+    dec = "k_decode<alt>" if alt else "k_decode<true>"
+    timed_classes = ("k_sumsq<false>", "k_sumsq<true>", "k_quantize", dec)
     dom = max((n for n in warm if n in timed_classes), key=lambda n: warm[n][0])
     # timed region: only the dominant kernel is bracketed by events (every timed launch costs a few microseconds
     # of idle time around it, which matters for the millisecond-scale workloads)
@@ -172,8 +180,8 @@ def main() -> int:
     c1_bits = 1 + max(1, int(np.ceil(np.log2(S))))
     body_bytes = c1_bits / 8.0 * d                    # packed code bytes per node (sign + index), no padding
     alg = {"k_sumsq<false>": 4.0 * K * d, "k_sumsq<true>": 4.0 * K * d,
-           "k_quantize": 4.0 * K * d + 2.0 * K * body_bytes,
-           "k_decode<true>": float(K * body_bytes) + (20.0 if xn is not None else 16.0) * d}
+           "k_quantize": 4.0 * K * d + (1.0 if alt else 2.0) * K * body_bytes,   # eq. (Alt) reads no previous message
+           dec: float(K * body_bytes) + (20.0 if xn is not None else 16.0) * d}
     kernels = {name: {"avg_ms": ms / n, "launches": n, "from": "warm-up rounds"} for name, (ms, n) in warm.items()}
     dom_ms = prof[dom][0] / prof[dom][1]                 # from the timed region
     kernels[dom] = {"avg_ms": dom_ms, "launches": prof[dom][1], "from": "timed region"}
@@ -185,13 +193,14 @@ def main() -> int:
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(args.workload, {}).get(dom)
+            # counters were collected under the main rule; eq. (Alt) reads no previous message in the quantizer
+            traffic = json.load(open(tpath)).get(args.workload + ("+alt" if alt else ""), {}).get(dom)
         except Exception:
             traffic = None
 
     ms_per_step = total_ms / args.steps
     grad_bytes = 4.0 * K * d
-    alg_round = sum(alg[n] for n in (("k_sumsq<true>" if w.adaptive else "k_sumsq<false>"), "k_quantize", "k_decode<true>"))
+    alg_round = sum(alg[n] for n in (("k_sumsq<true>" if w.adaptive else "k_sumsq<false>"), "k_quantize", dec))
     out = {
         "metric": "GB/s fp32 gradient through quantize+aggregate+QODA step; % of HBM peak",
         "value": grad_bytes / (ms_per_step * 1e-3) / 1e9,
@@ -199,7 +208,8 @@ def main() -> int:
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "num_nodes": K, "coordinates": d, "tensors": L, "level_points": S,
-                   "adaptive_levels": w.adaptive, "message_bytes_per_node": mbytes, "x_next": xn is not None},
+                   "adaptive_levels": w.adaptive, "message_bytes_per_node": mbytes, "x_next": xn is not None,
+                   "step_sizes": f"eq. (Alt), q_hat={args.q_hat}" if alt else "eq. (general_stepsize)"},
         "hbm_peak_fraction_algorithmic": alg_round / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "algorithmic_bytes_per_step": alg_round,
         "host_wall_ms_per_step": t_host / args.steps * 1e3,

@@ -125,6 +125,31 @@ typedef struct {
  * msgs_dev: host [K]. */
 int qoda_step(qoda_ctx *ctx, const void *const *msgs_dev, const qoda_state *state, void *stream);
 
+/* Solver state under the alternative pair of step sizes, Sec. 6 eq. (Alt) (all caller-owned device memory).
+ * sums_dev: device double[2] = {lambda, mu}, both starting at 0:
+ *   lambda = sum over finished rounds s of sum_k ||Vhat_{k,s+1/2}||^2 / K^2,  mu = sum_s ||X_s - X_{s+1}||^2.
+ * eta_dev: device float[2], required, in/out: on entry [0] holds eta_t, the rate that produced X_t (start: 1); on
+ * exit {eta_{t+1}, gamma_{t+1}}.  The other fields are those of qoda_state. */
+typedef struct {
+  const float *const *x1_dev;
+  float *const *y_dev;
+  float *const *x_half_dev;
+  float *const *x_next_dev; /* may be NULL */
+  double *sums_dev;
+  float *eta_dev;
+} qoda_alt_state;
+
+/* qoda_step with the rates of eq. (Alt), which use sums over the rounds BEFORE this one only (two-round lag):
+ *   eta_{t+1} = (1 + lambda + mu)^(-1/2),  gamma_{t+1} = (1 + lambda)^(q_hat - 1/2),  0 < q_hat <= 1/4;
+ *   mean, Y, X_{t+1}, X_{t+3/2} as in qoda_step with these two rates;
+ *   then lambda += (sum_k delta_k) / K^2 and mu += ||X_t - X_{t+1}||^2, X_t = X_1 + eta_t Y_t rebuilt from the state.
+ * delta_k must be ||Vhat_{k,t+1/2}||^2: run this round's quantize calls with msg_prev_dev = NULL.
+ * q_hat is used to 32 binary digits; the power is built from square roots (no library pow), so the rates are
+ * reproducible bit for bit.  Of the two forms the paper prints for lambda (sum of the K squared norms in the main
+ * text and in the appendix's choice of rates; squared norm of the sum in the appendix's lemma notation) the first is
+ * taken.  Errors: QODA_EINVAL for q_hat outside (0, 1/4] or below 2^-32, null sums_dev or eta_dev. */
+int qoda_step_alt(qoda_ctx *ctx, const void *const *msgs_dev, const qoda_alt_state *state, double q_hat, void *stream);
+
 /* Read an internal device buffer into host memory (waits for `stream`); for tests and diagnostics. */
 #define QODA_BUF_SUMSQ 0  /* double[K*L]  canonical per-layer sums of squares of the last norm pass        */
 #define QODA_BUF_NORM 1   /* float [K*L]  norms                                                            */
@@ -148,7 +173,7 @@ int qoda_status(qoda_ctx *ctx, void *stream);
  *   of range.
  * qoda_copy_calibration: a plain 128-bit copy kernel of `bytes` bytes (multiple of 16; 16-byte aligned device
  *   pointers): the known-traffic kernel that hardware byte counters are scaled by. */
-#define QODA_NUM_KERNELS 15
+#define QODA_NUM_KERNELS 18
 int qoda_profile_enable(qoda_ctx *ctx, uint32_t class_mask);
 int qoda_profile_read(qoda_ctx *ctx, double *ms, int64_t *launches, void *stream);
 const char *qoda_kernel_name(int32_t id);

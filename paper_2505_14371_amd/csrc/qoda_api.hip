@@ -316,7 +316,7 @@ int qoda_create(const qoda_config *cfg, qoda_ctx **out) {
   A(dev_alloc(&c->d_inv, KL));
   A(dev_alloc(&c->d_lev, (size_t)c->M * kMaxPoints));
   A(dev_alloc(&c->d_rgap, (size_t)c->M * kMaxPoints));
-  A(dev_alloc(&c->d_eta, 2));
+  A(dev_alloc(&c->d_eta, 3));
   A(dev_alloc(&c->d_lut, (size_t)c->M * kLutSize));
   A(dev_alloc(&c->d_status, 1));
   A(dev_alloc(&c->d_pooled, (size_t)c->M * kGridPoints));
@@ -337,7 +337,7 @@ int qoda_create(const qoda_config *cfg, qoda_ctx **out) {
   if (e == hipSuccess) A(hipMemset(c->d_delta, 0, c->K * sizeof(double)));
   if (e == hipSuccess) A(hipMemset(c->d_pooled, 0, (size_t)c->M * kGridPoints * sizeof(unsigned long long)));
   if (e == hipSuccess) {
-    const float one[2] = {1.0f, 1.0f};
+    const float one[3] = {1.0f, 1.0f, 1.0f};
     A(hipMemcpy(c->d_eta, one, sizeof one, hipMemcpyHostToDevice));
   }
   if (e != hipSuccess) {
@@ -515,7 +515,32 @@ int qoda_dequant_aggregate(qoda_ctx *c, const void *const *msgs_dev, float *cons
   rc = sync_table(c, c->t_mean, reinterpret_cast<const void *const *>(mean_out_dev), c->L, s);
   if (rc) return rc;
   a.mean_out = reinterpret_cast<float *const *>(c->t_mean.dev);
-  LAUNCH(c, kIdDecodeMean, s, launch_decode(a, false, c->planes_mask, s));
+  LAUNCH(c, kIdDecodeMean, s, launch_decode(a, kDecodeMean, c->planes_mask, s));
+  return QODA_OK;
+}
+
+// Shared by the two step entry points: checks and uploads the K message pointers and the four state tables.
+static int step_common(qoda_ctx *c, const void *const *msgs_dev, const float *const *x1, float *const *y,
+                       float *const *xh, float *const *xn, Dev &a, hipStream_t s, const char *who) {
+  const std::string w(who);
+  int rc = decode_common(c, msgs_dev, a, s, (w + ": msgs_dev").c_str());
+  if (rc) return rc;
+  const struct { const void *const *p; qoda_ctx::Table *t; std::string name; bool optional; } tabs[] = {
+      {reinterpret_cast<const void *const *>(x1), &c->t_x1, w + ": x1_dev", false},
+      {reinterpret_cast<const void *const *>(y), &c->t_y, w + ": y_dev", false},
+      {reinterpret_cast<const void *const *>(xh), &c->t_xh, w + ": x_half_dev", false},
+      {reinterpret_cast<const void *const *>(xn), &c->t_xn, w + ": x_next_dev", true}};
+  for (const auto &t : tabs) {
+    if (!t.p && t.optional) continue;
+    rc = check_layer_ptrs(c, t.p, c->L, t.name.c_str(), true);
+    if (rc) return rc;
+    rc = sync_table(c, *t.t, t.p, c->L, s);
+    if (rc) return rc;
+  }
+  a.x1 = reinterpret_cast<const float *const *>(c->t_x1.dev);
+  a.y = reinterpret_cast<float *const *>(c->t_y.dev);
+  a.x_half = reinterpret_cast<float *const *>(c->t_xh.dev);
+  a.x_next = xn ? reinterpret_cast<float *const *>(c->t_xn.dev) : nullptr;
   return QODA_OK;
 }
 
@@ -524,28 +549,31 @@ int qoda_step(qoda_ctx *c, const void *const *msgs_dev, const qoda_state *st, vo
   if (!st || !st->acc_dev) return fail(c, QODA_EINVAL, "qoda_step: null state or accumulator");
   hipStream_t s = static_cast<hipStream_t>(stream);
   Dev a = base_args(c);
-  int rc = decode_common(c, msgs_dev, a, s, "qoda_step: msgs_dev");
+  const int rc = step_common(c, msgs_dev, st->x1_dev, st->y_dev, st->x_half_dev, st->x_next_dev, a, s, "qoda_step");
   if (rc) return rc;
-  const struct { const void *const *p; qoda_ctx::Table *t; const char *name; bool optional; } tabs[] = {
-      {reinterpret_cast<const void *const *>(st->x1_dev), &c->t_x1, "qoda_step: x1_dev", false},
-      {reinterpret_cast<const void *const *>(st->y_dev), &c->t_y, "qoda_step: y_dev", false},
-      {reinterpret_cast<const void *const *>(st->x_half_dev), &c->t_xh, "qoda_step: x_half_dev", false},
-      {reinterpret_cast<const void *const *>(st->x_next_dev), &c->t_xn, "qoda_step: x_next_dev", true}};
-  for (const auto &t : tabs) {
-    if (!t.p && t.optional) continue;
-    rc = check_layer_ptrs(c, t.p, c->L, t.name, true);
-    if (rc) return rc;
-    rc = sync_table(c, *t.t, t.p, c->L, s);
-    if (rc) return rc;
-  }
-  a.x1 = reinterpret_cast<const float *const *>(c->t_x1.dev);
-  a.y = reinterpret_cast<float *const *>(c->t_y.dev);
-  a.x_half = reinterpret_cast<float *const *>(c->t_xh.dev);
-  a.x_next = st->x_next_dev ? reinterpret_cast<float *const *>(c->t_xn.dev) : nullptr;
   a.acc = st->acc_dev;
   a.eta_out = st->eta_dev;
   LAUNCH(c, kIdStepScalars, s, launch_step_scalars(a, s));
-  LAUNCH(c, kIdDecodeUpdate, s, launch_decode(a, true, c->planes_mask, s));
+  LAUNCH(c, kIdDecodeUpdate, s, launch_decode(a, kDecodeUpdate, c->planes_mask, s));
+  return QODA_OK;
+}
+
+int qoda_step_alt(qoda_ctx *c, const void *const *msgs_dev, const qoda_alt_state *st, double q_hat, void *stream) {
+  if (!c) return QODA_EINVAL;
+  if (!st || !st->sums_dev || !st->eta_dev) return fail(c, QODA_EINVAL, "qoda_step_alt: null state, sums or rates");
+  if (!(q_hat > 0.0) || !(q_hat <= 0.25)) return fail(c, QODA_EINVAL, "qoda_step_alt: the exponent must lie in (0, 1/4]");
+  const double digits = std::floor(std::ldexp(q_hat, 32));
+  if (digits < 1.0) return fail(c, QODA_EINVAL, "qoda_step_alt: the exponent is below 2^-32");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  Dev a = base_args(c);
+  const int rc = step_common(c, msgs_dev, st->x1_dev, st->y_dev, st->x_half_dev, st->x_next_dev, a, s, "qoda_step_alt");
+  if (rc) return rc;
+  a.alt_sums = st->sums_dev;
+  a.eta_out = st->eta_dev;
+  a.q_digits = (unsigned int)digits;
+  LAUNCH(c, kIdAltScalars, s, launch_alt_scalars(a, s));
+  LAUNCH(c, kIdDecodeAlt, s, launch_decode(a, kDecodeUpdateAlt, c->planes_mask, s));
+  LAUNCH(c, kIdAltFinalize, s, launch_alt_finalize(a, s));
   return QODA_OK;
 }
 
@@ -617,7 +645,8 @@ const char *qoda_kernel_name(int32_t id) {
   static const char *names[kNumKernelIds] = {"k_zero_u32", "k_sumsq<false>", "k_sumsq<true>", "k_norm_finalize",
                                              "k_write_header", "k_quantize", "k_delta_finalize", "k_step_scalars",
                                              "k_decode<false>", "k_decode<true>", "k_fit_typemax", "k_fit_pool",
-                                             "k_fit_dp", "k_build_tables", "k_copy_f4"};
+                                             "k_fit_dp", "k_build_tables", "k_copy_f4", "k_alt_scalars",
+                                             "k_decode<alt>", "k_alt_finalize"};
   return (id >= 0 && id < kNumKernelIds) ? names[id] : "";
 }
 

@@ -57,7 +57,7 @@ struct Dev {
   short *dp_arg;               // DP back-pointers, type m at dp_arg_off[m]
   const long long *dp_arg_off; // [M]
   unsigned int *status;
-  float *eta;                  // [2] eta, gamma
+  float *eta;                  // [3] eta, gamma, previous eta (the last one only under eq. (Alt))
   // step / aggregate
   const float *const *x1;
   float *const *y;
@@ -66,6 +66,8 @@ struct Dev {
   float *const *mean_out;
   double *acc;
   float *eta_out;  // may be nullptr
+  double *alt_sums;        // eq. (Alt): [2] lambda, mu (caller's)
+  unsigned int q_digits;   // eq. (Alt): the exponent's first 32 binary digits
   unsigned long long seed;
   unsigned int round;
   int node0;    // first node handled by this launch
@@ -74,10 +76,15 @@ struct Dev {
   double invK2;
 };
 
+// What the decode kernel does after the K-way mean: store it, apply eq. (ODA), or apply eq. (ODA) with the two
+// rates of eq. (Alt) and accumulate ||X_t - X_{t+1}||^2.
+enum DecodeMode { kDecodeMean = 0, kDecodeUpdate = 1, kDecodeUpdateAlt = 2 };
+
 // Kernel classes, for the optional per-kernel event timing of the host API.
 enum KernelId {
   kIdZero = 0, kIdSumsq, kIdSumsqHist, kIdNormFinalize, kIdWriteHeader, kIdQuantize, kIdDeltaFinalize, kIdStepScalars,
-  kIdDecodeMean, kIdDecodeUpdate, kIdFitTypemax, kIdFitPool, kIdFitDp, kIdBuildTables, kIdCopy, kNumKernelIds
+  kIdDecodeMean, kIdDecodeUpdate, kIdFitTypemax, kIdFitPool, kIdFitDp, kIdBuildTables, kIdCopy, kIdAltScalars,
+  kIdDecodeAlt, kIdAltFinalize, kNumKernelIds
 };
 
 // Launch wrappers (each checks nothing: the host API validates shapes before calling).
@@ -87,7 +94,9 @@ hipError_t launch_norm_finalize(const Dev &a, hipStream_t s);
 hipError_t launch_quantize(const Dev &a, unsigned int planes_mask, hipStream_t s);
 hipError_t launch_delta_finalize(const Dev &a, hipStream_t s);
 hipError_t launch_step_scalars(const Dev &a, hipStream_t s);
-hipError_t launch_decode(const Dev &a, bool update, unsigned int planes_mask, hipStream_t s);
+hipError_t launch_decode(const Dev &a, int mode, unsigned int planes_mask, hipStream_t s);   // mode: DecodeMode
+hipError_t launch_alt_scalars(const Dev &a, hipStream_t s);
+hipError_t launch_alt_finalize(const Dev &a, hipStream_t s);
 hipError_t launch_fit_typemax(const Dev &a, hipStream_t s);
 hipError_t launch_fit_pool(const Dev &a, hipStream_t s);
 hipError_t launch_fit_dp(const Dev &a, hipStream_t s);

@@ -488,11 +488,49 @@ __global__ void k_step_scalars(Dev a) {
   if (a.eta_out) { a.eta_out[0] = eta; a.eta_out[1] = eta; }
 }
 
-// DECODE + K-way mean (+ eq. (ODA) update when UPDATE): one pass over Y, X_1 and the K messages.
+// eq. (Alt), Sec. 6: the rates for the update of this round from the sums over the rounds before it,
+//   eta = (1 + lambda + mu)^(-1/2) as rcp_floor(sqrt_floor(.)),  gamma = (1 + lambda)^(q - 1/2),
+// the power built from correctly rounded fp64 operations only: r_j = sqrt(r_{j-1}), r_0 = 1 + lambda, and
+// (1 + lambda)^q = product of the r_j whose binary digit of q is set (j increasing).  Then lambda takes this
+// round's sum_k ||Vhat_k||^2 / K^2 (the quantizer's distance output against an all-zero previous message).
+__global__ void k_alt_scalars(Dev a) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  const double lambda = a.alt_sums[0], mu = a.alt_sums[1];
+  const float eta_prev = a.eta_out[0];
+  const float eta = rcp_floor(sqrt_floor(1.0 + lambda + mu));
+  const double base = 1.0 + lambda;
+  double r = base, p = 1.0;
+  for (int j = 1; j <= 32; ++j) {
+    r = __dsqrt_rn(r);
+    if ((a.q_digits >> (32 - j)) & 1u) p = p * r;
+  }
+  const float gamma = (float)__ddiv_rn(p, __dsqrt_rn(base));
+  a.eta[0] = eta;
+  a.eta[1] = gamma;
+  a.eta[2] = eta_prev;
+  a.eta_out[0] = eta;
+  a.eta_out[1] = gamma;
+  double sum = a.delta[0];
+  for (int k = 1; k < a.K; ++k) sum = sum + a.delta[k];
+  a.alt_sums[0] = lambda + sum * a.invK2;
+}
+
+// mu += ||X_t - X_{t+1}||^2: slot j takes the tiles j, j+256, ... (all layers, in order), then the halving tree.
+__global__ void __launch_bounds__(kThreads) k_alt_finalize(Dev a) {
+  __shared__ double red[kThreads];
+  double acc = 0.0;
+  for (int g = threadIdx.x; g < a.G; g += kThreads) acc = acc + a.dpartial[g];
+  const double s = block_tree(acc, red);
+  if (threadIdx.x == 0) a.alt_sums[1] = a.alt_sums[1] + s;
+}
+
+// DECODE + K-way mean (+ eq. (ODA) update unless MODE is kDecodeMean): one pass over Y, X_1 and the K messages.
 // One octet per wave at a time: 32 running sums per lane, K records of C1 words, then 8 blocks of state.
-template <int C1, bool UPDATE, bool FAST>
+// Under kDecodeUpdateAlt the lane also rebuilds X_t = X_1 + eta_prev * Y_t and adds (X_t - X_{t+1})^2 to its
+// slot's fp32 fused chain (coordinates in increasing order, as in the quantizer's distance term).
+template <int C1, int MODE, bool FAST>
 __device__ __forceinline__ void decode_octet(const Dev &a, const LayerMeta &m, int l, long long O, const float *T, int i,
-                                             float eta, float gamma) {
+                                             float eta, float gamma, float eta_prev, float &accx) {
   constexpr int TS = 1 << C1;   // table entries per node, indexed by code = sign | h << 1
   const long long boff = m.body_off + O * 256 * C1;
   float sum[32];
@@ -520,19 +558,28 @@ __device__ __forceinline__ void decode_octet(const Dev &a, const LayerMeta &m, i
       float mean[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) mean[j] = sum[4 * bb + j] * a.invK;
-      if (!UPDATE) {
+      if (MODE == kDecodeMean) {
         store4(a.mean_out[l], e, dlim, mean);
       } else {
         float y[4], x1[4], xn[4], xh[4];
-        load4(a.y[l], e, dlim, y);
+        load4(a.y[l], e, dlim, y);      // coordinates past the end of the layer read as 0 and add nothing below
         load4(a.x1[l], e, dlim, x1);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
+          float xt = 0.0f;
+          if (MODE == kDecodeUpdateAlt) {
+            const float ey_old = eta_prev * y[j];
+            xt = x1[j] + ey_old;
+          }
           y[j] = y[j] - mean[j];
           const float ey = eta * y[j];
           xn[j] = x1[j] + ey;
           const float gm = gamma * mean[j];
           xh[j] = xn[j] - gm;
+          if (MODE == kDecodeUpdateAlt) {
+            const float diff = xt - xn[j];
+            accx = __builtin_fmaf(diff, diff, accx);
+          }
         }
         store4(a.y[l], e, dlim, y);
         store4(a.x_half[l], e, dlim, xh);
@@ -542,25 +589,32 @@ __device__ __forceinline__ void decode_octet(const Dev &a, const LayerMeta &m, i
   }
 }
 
-template <int C1, bool UPDATE>
-__device__ __forceinline__ void decode_tile(const Dev &a, const LayerMeta &m, int l, int chunk, const float *T) {
+template <int C1, int MODE>
+__device__ __forceinline__ void decode_tile(const Dev &a, const LayerMeta &m, int l, int chunk, const float *T,
+                                            double *red) {
   const int t = threadIdx.x;
   const int w = __builtin_amdgcn_readfirstlane(t >> 6);
   const int i = t & 63;
-  float eta = 0.0f, gamma = 0.0f;
-  if (UPDATE) { eta = a.eta[0]; gamma = a.eta[1]; }
+  float eta = 0.0f, gamma = 0.0f, eta_prev = 0.0f, accx = 0.0f;
+  if (MODE != kDecodeMean) { eta = a.eta[0]; gamma = a.eta[1]; }
+  if (MODE == kDecodeUpdateAlt) eta_prev = a.eta[2];
   const long long noct = (m.nblk + 7) >> 3;
   for (int oo = 0; oo < 2; ++oo) {
     const long long O = (long long)chunk * 8 + w * 2 + oo;
     if (O >= noct) break;
-    if ((O + 1) * 2048 <= m.d) decode_octet<C1, UPDATE, true>(a, m, l, O, T, i, eta, gamma);
-    else decode_octet<C1, UPDATE, false>(a, m, l, O, T, i, eta, gamma);
+    if ((O + 1) * 2048 <= m.d) decode_octet<C1, MODE, true>(a, m, l, O, T, i, eta, gamma, eta_prev, accx);
+    else decode_octet<C1, MODE, false>(a, m, l, O, T, i, eta, gamma, eta_prev, accx);
+  }
+  if (MODE == kDecodeUpdateAlt) {
+    const double total = block_tree((double)accx, red);
+    if (t == 0) a.dpartial[blockIdx.x] = total;
   }
 }
 
-template <int C1, bool UPDATE>
+template <int C1, int MODE>
 __global__ void __launch_bounds__(kThreads) k_decode(Dev a) {
   extern __shared__ float T[];   // [K][2^C1]: +-norm_k * level_h of this layer, from the K message headers
+  __shared__ double red[MODE == kDecodeUpdateAlt ? kThreads : 1];
   const int2 tile = a.tiles[blockIdx.x];
   const int l = tile.x;
   const LayerMeta m = a.meta[l];
@@ -573,7 +627,7 @@ __global__ void __launch_bounds__(kThreads) k_decode(Dev a) {
     T[idx] = (c & 1) ? -mag : mag;
   }
   __syncthreads();
-  decode_tile<C1, UPDATE>(a, m, l, tile.y, T);
+  decode_tile<C1, MODE>(a, m, l, tile.y, T, red);
 }
 
 // ------------------------------------------------------------------------------------------------ level fit
@@ -845,21 +899,33 @@ hipError_t launch_step_scalars(const Dev &a, hipStream_t s) {
 }
 
 template <int C1>
-static void launch_decode_width(const Dev &a, bool update, size_t lds_bytes, hipStream_t s) {
-  if (update) hipLaunchKernelGGL((k_decode<C1, true>), dim3(a.G), dim3(kThreads), lds_bytes, s, a);
-  else hipLaunchKernelGGL((k_decode<C1, false>), dim3(a.G), dim3(kThreads), lds_bytes, s, a);
+static void launch_decode_width(const Dev &a, int mode, size_t lds_bytes, hipStream_t s) {
+  const dim3 grid(a.G), block(kThreads);
+  if (mode == kDecodeUpdateAlt) hipLaunchKernelGGL((k_decode<C1, kDecodeUpdateAlt>), grid, block, lds_bytes, s, a);
+  else if (mode == kDecodeUpdate) hipLaunchKernelGGL((k_decode<C1, kDecodeUpdate>), grid, block, lds_bytes, s, a);
+  else hipLaunchKernelGGL((k_decode<C1, kDecodeMean>), grid, block, lds_bytes, s, a);
 }
 
-hipError_t launch_decode(const Dev &a, bool update, unsigned int planes_mask, hipStream_t s) {
+hipError_t launch_decode(const Dev &a, int mode, unsigned int planes_mask, hipStream_t s) {
   if (a.G == 0) return hipSuccess;
-  if (planes_mask & (1u << 2)) launch_decode_width<2>(a, update, (size_t)a.K * 4 * sizeof(float), s);
-  if (planes_mask & (1u << 3)) launch_decode_width<3>(a, update, (size_t)a.K * 8 * sizeof(float), s);
-  if (planes_mask & (1u << 4)) launch_decode_width<4>(a, update, (size_t)a.K * 16 * sizeof(float), s);
-  if (planes_mask & (1u << 5)) launch_decode_width<5>(a, update, (size_t)a.K * 32 * sizeof(float), s);
-  if (planes_mask & (1u << 6)) launch_decode_width<6>(a, update, (size_t)a.K * 64 * sizeof(float), s);
-  if (planes_mask & (1u << 7)) launch_decode_width<7>(a, update, (size_t)a.K * 128 * sizeof(float), s);
-  if (planes_mask & (1u << 8)) launch_decode_width<8>(a, update, (size_t)a.K * 256 * sizeof(float), s);
-  if (planes_mask & (1u << 9)) launch_decode_width<9>(a, update, (size_t)a.K * 512 * sizeof(float), s);
+  if (planes_mask & (1u << 2)) launch_decode_width<2>(a, mode, (size_t)a.K * 4 * sizeof(float), s);
+  if (planes_mask & (1u << 3)) launch_decode_width<3>(a, mode, (size_t)a.K * 8 * sizeof(float), s);
+  if (planes_mask & (1u << 4)) launch_decode_width<4>(a, mode, (size_t)a.K * 16 * sizeof(float), s);
+  if (planes_mask & (1u << 5)) launch_decode_width<5>(a, mode, (size_t)a.K * 32 * sizeof(float), s);
+  if (planes_mask & (1u << 6)) launch_decode_width<6>(a, mode, (size_t)a.K * 64 * sizeof(float), s);
+  if (planes_mask & (1u << 7)) launch_decode_width<7>(a, mode, (size_t)a.K * 128 * sizeof(float), s);
+  if (planes_mask & (1u << 8)) launch_decode_width<8>(a, mode, (size_t)a.K * 256 * sizeof(float), s);
+  if (planes_mask & (1u << 9)) launch_decode_width<9>(a, mode, (size_t)a.K * 512 * sizeof(float), s);
+  return hipGetLastError();
+}
+
+hipError_t launch_alt_scalars(const Dev &a, hipStream_t s) {
+  hipLaunchKernelGGL(k_alt_scalars, dim3(1), dim3(64), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_alt_finalize(const Dev &a, hipStream_t s) {
+  hipLaunchKernelGGL(k_alt_finalize, dim3(1), dim3(kThreads), 0, s, a);
   return hipGetLastError();
 }
 

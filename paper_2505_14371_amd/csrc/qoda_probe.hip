@@ -41,7 +41,7 @@ __global__ void fill_layer(float *p, long long n, float scale, uint32_t salt) {
 }
 
 int main(int argc, char **argv) {
-  if (argc < 5) { fprintf(stderr, "usage: %s sizes.txt K S rounds [adaptive=1] [copy_mib=1024]\n", argv[0]); return 2; }
+  if (argc < 5) { fprintf(stderr, "usage: %s sizes.txt K S rounds [adaptive=1] [copy_mib=1024] [time_classes=0xFFFFFFFF] [q_hat=0]\n", argv[0]); return 2; }
   std::vector<int64_t> sizes;
   FILE *f = fopen(argv[1], "r");
   if (!f) { perror(argv[1]); return 2; }
@@ -52,6 +52,7 @@ int main(int argc, char **argv) {
   const bool adaptive = argc > 5 ? atoi(argv[5]) != 0 : true;
   const size_t copy_bytes = (size_t)(argc > 6 ? atoll(argv[6]) : 1024) << 20;
   const uint32_t time_classes = argc > 7 ? (uint32_t)strtoul(argv[7], nullptr, 0) : 0xFFFFFFFFu;
+  const double q_hat = argc > 8 ? atof(argv[8]) : 0.0;   // > 0: the step sizes of eq. (Alt) instead of the main rule
   if (L < 1 || K < 1 || S < 2 || rounds < 1) { fprintf(stderr, "bad arguments\n"); return 2; }
 
   std::vector<int32_t> types(L), points(L, S);
@@ -98,6 +99,14 @@ int main(int argc, char **argv) {
     x1p[l] = x1 + off[l]; yp[l] = y + off[l]; xhp[l] = xh + off[l];
   }
   qoda_state st = {x1p.data(), yp.data(), xhp.data(), nullptr, acc, nullptr};
+  double *alt_sums;
+  float *alt_eta;
+  const float ones[2] = {1.0f, 1.0f};
+  CK(hipMalloc(&alt_sums, 2 * sizeof(double)));
+  CK(hipMalloc(&alt_eta, 2 * sizeof(float)));
+  CK(hipMemset(alt_sums, 0, 2 * sizeof(double)));
+  CK(hipMemcpy(alt_eta, ones, sizeof ones, hipMemcpyHostToDevice));
+  qoda_alt_state ast = {x1p.data(), yp.data(), xhp.data(), nullptr, alt_sums, alt_eta};
   QK(qoda_profile_enable(ctx, time_classes));
   hipEvent_t e0, e1;
   CK(hipEventCreate(&e0));
@@ -112,15 +121,17 @@ int main(int argc, char **argv) {
     }
     if (adaptive) QK(qoda_fit_levels(ctx, gp.data(), (uint32_t)t, nullptr));
     QK(qoda_quantize_all(ctx, gp.data(), (uint32_t)t, msg.data() + cur * K,
-                         t > 1 ? (const void *const *)(msg.data() + (1 - cur) * K) : nullptr, nullptr));
-    QK(qoda_step(ctx, (const void *const *)(msg.data() + cur * K), &st, nullptr));
+                         (t > 1 && q_hat <= 0.0) ? (const void *const *)(msg.data() + (1 - cur) * K) : nullptr, nullptr));
+    if (q_hat > 0.0) QK(qoda_step_alt(ctx, (const void *const *)(msg.data() + cur * K), &ast, q_hat, nullptr));
+    else QK(qoda_step(ctx, (const void *const *)(msg.data() + cur * K), &st, nullptr));
   }
   CK(hipEventRecord(e1, 0));
   CK(hipEventSynchronize(e1));
   CK(hipEventElapsedTime(&ms_total, e0, e1));
   double ms[QODA_NUM_KERNELS]; int64_t n[QODA_NUM_KERNELS];
   QK(qoda_profile_read(ctx, ms, n, nullptr));
-  printf("workload: L=%d d=%lld K=%d S=%d adaptive=%d message_bytes=%zu\n", L, (long long)d, K, S, (int)adaptive, mbytes);
+  printf("workload: L=%d d=%lld K=%d S=%d adaptive=%d q_hat=%g message_bytes=%zu\n", L, (long long)d, K, S, (int)adaptive,
+         q_hat, mbytes);
   printf("rounds=%d ms_per_round=%.4f fp32_gradient_GBps=%.1f\n", rounds, ms_total / rounds,
          4.0 * K * (double)d / (ms_total / rounds * 1e-3) / 1e9);
   for (int i = 0; i < QODA_NUM_KERNELS; ++i)

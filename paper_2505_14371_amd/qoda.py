@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libqoda.so")
 
 OK, EINVAL, ENOMEM, EHIP, ENONFINITE = 0, -1, -2, -3, -4
 BUF_SUMSQ, BUF_NORM, BUF_INV, BUF_DELTA, BUF_HIST, BUF_POOLED = range(6)
-NUM_KERNELS = 15
+NUM_KERNELS = 18
 HIST_BINS, GRID_POINTS = 2048, 257
 
 _lib = None
@@ -39,6 +39,12 @@ class _State(C.Structure):
     _fields_ = [("x1_dev", C.POINTER(C.c_void_p)), ("y_dev", C.POINTER(C.c_void_p)),
                 ("x_half_dev", C.POINTER(C.c_void_p)), ("x_next_dev", C.POINTER(C.c_void_p)),
                 ("acc_dev", C.c_void_p), ("eta_dev", C.c_void_p)]
+
+
+class _AltState(C.Structure):
+    _fields_ = [("x1_dev", C.POINTER(C.c_void_p)), ("y_dev", C.POINTER(C.c_void_p)),
+                ("x_half_dev", C.POINTER(C.c_void_p)), ("x_next_dev", C.POINTER(C.c_void_p)),
+                ("sums_dev", C.c_void_p), ("eta_dev", C.c_void_p)]
 
 
 def load():
@@ -63,6 +69,7 @@ def load():
     L.qoda_quantize_all.argtypes = [vp, pp, C.c_uint32, pp, pp, vp]
     L.qoda_dequant_aggregate.argtypes = [vp, pp, pp, vp]
     L.qoda_step.argtypes = [vp, pp, C.POINTER(_State), vp]
+    L.qoda_step_alt.argtypes = [vp, pp, C.POINTER(_AltState), C.c_double, vp]
     L.qoda_read_buffer.argtypes = [vp, C.c_int32, vp, C.c_size_t, vp]
     L.qoda_status.argtypes = [vp, vp]
     L.qoda_profile_enable.argtypes = [vp, C.c_uint32]
@@ -73,7 +80,7 @@ def load():
     L.qoda_last_error.argtypes = [vp]
     L.qoda_last_error.restype = C.c_char_p
     for name in ("qoda_create", "qoda_destroy", "qoda_message_layout", "qoda_set_levels", "qoda_get_levels",
-                 "qoda_fit_levels", "qoda_quantize", "qoda_quantize_all", "qoda_dequant_aggregate", "qoda_step",
+                 "qoda_fit_levels", "qoda_quantize", "qoda_quantize_all", "qoda_dequant_aggregate", "qoda_step", "qoda_step_alt",
                  "qoda_read_buffer", "qoda_status", "qoda_profile_enable", "qoda_profile_read", "qoda_copy_calibration"):
         getattr(L, name).restype = C.c_int
     _lib = L
@@ -188,6 +195,13 @@ class Context:
         assert len(msgs) == self.K
         st = _State(_ptrs(x1), _ptrs(y), _ptrs(x_half), None if x_next is None else _ptrs(x_next), _addr(acc), _addr(eta))
         self._check(self._lib.qoda_step(self._h, _ptrs(msgs), C.byref(st), _stream(stream)))
+
+    def step_alt(self, msgs: Sequence, x1: Sequence, y: Sequence, x_half: Sequence, sums, eta, q_hat: float,
+                 x_next: Optional[Sequence] = None, stream=None):
+        assert len(msgs) == self.K
+        st = _AltState(_ptrs(x1), _ptrs(y), _ptrs(x_half), None if x_next is None else _ptrs(x_next), _addr(sums),
+                       _addr(eta))
+        self._check(self._lib.qoda_step_alt(self._h, _ptrs(msgs), C.byref(st), float(q_hat), _stream(stream)))
 
     # -- diagnostics
     def read_buffer(self, which: int, stream=None) -> np.ndarray:

@@ -34,6 +34,7 @@ class GpuModel:
         self.mean = torch.zeros_like(self.x1)
         self.acc = torch.zeros(1, dtype=torch.float64, device=dev())
         self.eta = torch.ones(2, dtype=torch.float32, device=dev())
+        self.alt_sums = torch.zeros(2, dtype=torch.float64, device=dev())      # lambda, mu of eq. (Alt)
 
     # ---- views
     def layer_ptrs(self, flat: torch.Tensor) -> List[int]:
@@ -74,6 +75,17 @@ class GpuModel:
         self.ctx.step(self.msg[self.cur], self.layer_ptrs(self.x1), self.layer_ptrs(self.y),
                       self.layer_ptrs(self.x_half), self.acc, self.layer_ptrs(self.x_next) if want_next else None,
                       self.eta)
+        self.cur = 1 - self.cur
+        self.have_prev = True
+
+    def quantize_all_alt(self, round_: int):
+        """eq. (Alt): the per-node term is ||Vhat_k||^2, i.e. the distance to an all-zero previous message."""
+        self.ctx.quantize_all(self.grad_ptrs(), round_, self.msg[self.cur], None)
+
+    def step_alt(self, q_hat: float, want_next: bool = True):
+        self.ctx.step_alt(self.msg[self.cur], self.layer_ptrs(self.x1), self.layer_ptrs(self.y),
+                          self.layer_ptrs(self.x_half), self.alt_sums, self.eta, q_hat,
+                          self.layer_ptrs(self.x_next) if want_next else None)
         self.cur = 1 - self.cur
         self.have_prev = True
 

@@ -1,0 +1,116 @@
+"""GPU parity for the alternative step sizes (Sec. 6, eq. (Alt)): the two rates, both running sums and the
+squared iterate distance bit for bit against the oracle, iterates within 1e-6 relative (identical in practice)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import helpers  # noqa: E402
+from paper_2505_14371_amd import qoda, workloads  # noqa: E402
+
+REL = 1e-6
+
+
+def gm(*a, **k):
+    if not torch.cuda.is_available():
+        pytest.fail("a GPU test was selected but no GPU is visible")
+    import gpu_harness
+
+    return gpu_harness.GpuModel(*a, **k)
+
+
+def close(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    s = np.abs(b).max() if b.size else 0.0
+    return np.all(np.abs(a - b) <= REL * np.maximum(np.abs(b), 1e-30) + REL * 1e-3 * s)
+
+
+def test_rates_match_for_many_sums():
+    """The scalar kernel alone: preset (lambda, mu), one step on a tiny model, read the rates back."""
+    import oracle
+
+    m = gm([300], [0], [4], 1, seed=3)
+    g = [[np.linspace(-1, 1, 300).astype(np.float32)]]
+    m.set_grads(g)
+    m.quantize_all_alt(1)
+    rng = np.random.default_rng(5)
+    cases = [(0.0, 0.0, 0.25), (15.0, 0.0, 0.25), (255.0, 768.0, 0.125), (80.0, 0.0, 0.25), (1e-9, 1e-12, 2.0 ** -31)]
+    cases += [(float(10.0 ** rng.uniform(-8, 14)), float(10.0 ** rng.uniform(-8, 14)), float(rng.uniform(1e-6, 0.25)))
+              for _ in range(120)]
+    for lam, mu, q in cases:
+        m.alt_sums.copy_(torch.tensor([lam, mu], dtype=torch.float64))
+        m.cur = 0
+        m.step_alt(q)
+        eta = m.eta.cpu().numpy()
+        we, wg = oracle.alt_step_size(lam, mu, q)
+        assert eta[0] == we and eta[1] == wg, (lam, mu, q)
+    with pytest.raises(qoda.QodaError):
+        m.step_alt(0.3)
+    with pytest.raises(qoda.QodaError):
+        m.step_alt(0.0)
+    with pytest.raises(qoda.QodaError):
+        m.step_alt(1e-12)
+
+
+@pytest.mark.parametrize("S,K", [(8, 3), (4, 16), (256, 2)])
+def test_rounds_match_the_oracle(oracle, S, K):
+    w = workloads.mini("txl", max_layer=70000, max_layers=7)
+    sizes = list(w.sizes) + [0, 16384 * 2 + 5, 3]
+    L = len(sizes)
+    q = 0.2
+    rng = np.random.default_rng(S)
+    x1 = [rng.standard_normal(s).astype(np.float32) for s in sizes]
+    m = gm(sizes, [0] * L, [S], K, seed=9)
+    m.set_layers(m.x1, x1)
+    ref = helpers.OracleQODA(sizes, [S] * L, [helpers.uniform_levels(S)] * L, K, x1, 9, q_hat=q)
+    for t in range(1, 5):
+        grads = [[(rng.standard_t(4, s) * 10.0 ** rng.uniform(-2, 1)).astype(np.float32) for s in sizes] for _ in range(K)]
+        m.set_grads(grads)
+        m.quantize_all_alt(t)
+        msgs = m.messages()
+        deltas = m.ctx.read_buffer(qoda.BUF_DELTA)
+        m.step_alt(q, want_next=(t % 2 == 1))
+        om, od, _ = ref.round_(grads, t)
+        for k in range(K):
+            assert np.array_equal(msgs[k], om[k]), (t, k)
+            assert deltas[k] == od[k], (t, k)
+        eta = m.eta.cpu().numpy()
+        sums = m.alt_sums.cpu().numpy()
+        assert eta[0] == ref.eta and eta[1] == ref.gamma, t
+        assert sums[0] == ref.lam and sums[1] == ref.mu, (t, sums, ref.lam, ref.mu)
+        gy, gxh = m.layers(m.y), m.layers(m.x_half)
+        for l in range(L):
+            assert close(gy[l], ref.y[l]) and close(gxh[l], ref.x_half[l]), (t, l)
+            assert np.array_equal(gy[l], ref.y[l]) and np.array_equal(gxh[l], ref.x_half[l]), (t, l)
+        if t % 2 == 1:
+            gxn = m.layers(m.x_next)
+            assert all(np.array_equal(a, b) for a, b in zip(gxn, ref.x_next))
+    assert ref.mu > 0 and ref.lam > 0 and ref.gamma > ref.eta
+
+
+def test_bilinear_game_with_the_alternative_rates(oracle):
+    """Config 1 under eq. (Alt): 200 rounds, GPU and oracle each evaluating the operator at their own query point."""
+    wl = workloads.get("bilinear")
+    A, x0, y0 = workloads.bilinear_game(seed=wl.seed)
+    op = lambda x, y, k, t: workloads.bilinear_operator(A, x, y, k, t, seed=wl.seed, sigma=0.1)
+    n, K, S, q = 512, wl.num_nodes, wl.points, 0.25
+    m = gm([n, n], [0, 0], [S], K, seed=wl.seed)
+    m.set_layers(m.x1, [x0, y0])
+    m.set_layers(m.x_half, [x0, y0])
+    lev = helpers.uniform_levels(S)
+    free = helpers.OracleQODA([n, n], [S, S], [lev, lev], K, [x0, y0], wl.seed, q_hat=q)
+    for t in range(1, wl.rounds + 1):
+        xq, yq = m.layers(m.x_half)
+        m.set_grads([list(op(xq, yq, k, t)) for k in range(K)])
+        m.quantize_all_alt(t)
+        m.step_alt(q)
+        fx, fy = free.x_half
+        free.round_([list(op(fx, fy, k, t)) for k in range(K)], t)
+    sums = m.alt_sums.cpu().numpy()
+    assert sums[0] == free.lam and sums[1] == free.mu
+    for l in range(2):
+        assert np.array_equal(m.layers(m.x_half)[l], free.x_half[l])
+        assert np.array_equal(m.layers(m.y)[l], free.y[l])
