@@ -176,3 +176,61 @@ def test_full_size_two_rounds(oracle, name):
             for a, b in ((gy, yv), (gxh, xh)):
                 tol = 1e-6 * np.abs(b) + 1e-9 * np.abs(b).max()
                 assert np.all(np.abs(a.astype(np.float64) - b) <= tol), (t, l, e0)
+
+
+@pytest.mark.timeout(900)
+def test_full_size_alternative_step_sizes(oracle):
+    """eq. (Alt) on the Transformer-XL-shaped workload, two rounds: both rates bit for bit from the sums, lambda
+    from one node's norm term recomputed by the oracle from its stored message, mu against a float64 sum over the
+    GPU's own fp32 iterates (a property that holds at any size), iterates on the sampled pieces."""
+    f = Full("txl")
+    w, K, L, S = f.w, f.K, f.L, f.S
+    q = 0.25
+    sums = torch.zeros(2, dtype=torch.float64, device=f.dev)
+    xn = torch.zeros_like(f.x1)
+    pieces = pieces_for(w)
+    x_prev = f.x1.cpu().numpy().astype(np.float64)          # X_1
+    lam = mu = 0.0
+    for t in (1, 2):
+        f.fill(t)
+        cur = (t - 1) & 1
+        y_old = {p: f.layer(f.y, p[0], p[1], p[2]) for p in pieces}
+        f.ctx.fit_levels(f.gptrs(), t)
+        f.ctx.quantize_all(f.gptrs(), t, f.msg[cur], None)
+        deltas = f.ctx.read_buffer(qoda.BUF_DELTA)
+        eta_prev = float(f.eta.cpu()[0])
+        want_eta, want_gamma = oracle.alt_step_size(lam, mu, q)
+        f.ctx.step_alt(f.msg[cur], f.ptrs(f.x1), f.ptrs(f.y), f.ptrs(f.xh), sums, f.eta, q, f.ptrs(xn))
+        torch.cuda.synchronize()
+        assert f.ctx.status() == qoda.OK
+        eta = f.eta.cpu().numpy()
+        assert eta[0] == want_eta and eta[1] == want_gamma, t
+        got = sums.cpu().numpy()
+        k = K - 1
+        assert deltas[k] == oracle.delta_from_messages(w.sizes, [S] * L, f.msg[cur][k].cpu().numpy(), None)
+        lam, _ = oracle.alt_advance(deltas, 0.0, lam, mu)
+        assert got[0] == lam
+        x_cur = xn.cpu().numpy().astype(np.float64)
+        dx2 = sum(float(np.sum((x_prev[int(o): int(o) + d] - x_cur[int(o): int(o) + d]) ** 2))
+                  for o, d in zip(f.off, w.sizes))           # layers only: the padding between them is not state
+        assert got[1] - mu == pytest.approx(dx2, rel=1e-5), t
+        mu = float(got[1])
+        x_prev = x_cur
+        for (l, e0, e1) in pieces:
+            sub = []
+            for kk in range(K):
+                hdr = f.msg[cur][kk][int(f.hdr_off[l]): int(f.hdr_off[l]) + 4 * (1 + S)].cpu().numpy()
+                body = f.body_slice(f.msg[cur][kk], l, e0, e1)
+                hb = oracle.header_bytes([e1 - e0], [S])
+                m = np.zeros(oracle.message_bytes([e1 - e0], [S]), np.uint8)
+                m[: hdr.size] = hdr
+                m[hb: hb + body.size] = body
+                sub.append(m)
+            mean = oracle.dequant_aggregate([e1 - e0], [S], sub)
+            yv = [y_old[(l, e0, e1)].copy()]
+            x1 = [f.layer(f.x1, l, e0, e1)]
+            wxn, wxh, _ = oracle.oda_update_alt([e1 - e0], mean, x1, yv, eta_prev, eta[0], eta[1])
+            assert np.array_equal(f.layer(f.y, l, e0, e1), yv[0]), (t, l, e0)
+            assert np.array_equal(f.layer(f.xh, l, e0, e1), wxh[0]), (t, l, e0)
+            assert np.array_equal(f.layer(xn, l, e0, e1), wxn[0]), (t, l, e0)
+    assert mu > 0 and lam > 0
