@@ -19,6 +19,8 @@ GRID_BASE = 760
 BLOCK = 256
 OCTET = 2048
 CHUNK = 16384
+BUCKET = 128
+SCOPE_LAYER, SCOPE_VECTOR, SCOPE_BUCKET = 0, 1, 2   # what one norm covers: a layer, the whole vector, 128 coordinates
 
 _lib = None
 
@@ -60,21 +62,24 @@ def lib():
         L.oracle_quantize_with_draws.restype = None
         L.oracle_decode.argtypes = [u8p, u8p, C.c_int64, C.c_float, fp, C.c_int32, fp]
         L.oracle_decode.restype = None
-        L.oracle_message_bytes.argtypes = [C.c_int32, i64p, i32p]
+        L.oracle_message_bytes.argtypes = [C.c_int32, i64p, i32p, C.c_int32]
         L.oracle_message_bytes.restype = C.c_int64
-        L.oracle_header_bytes.argtypes = [C.c_int32, i64p, i32p]
+        L.oracle_header_bytes.argtypes = [C.c_int32, i64p, i32p, C.c_int32]
         L.oracle_header_bytes.restype = C.c_int64
-        L.oracle_layout.argtypes = [C.c_int32, i64p, i32p, i64p, i64p]
+        L.oracle_layout.argtypes = [C.c_int32, i64p, i32p, C.c_int32, i64p, i64p]
         L.oracle_layout.restype = None
-        L.oracle_pack_layer.argtypes = [u8p, u8p, C.c_int64, C.c_int32, u8p]
+        L.oracle_pack_layer.argtypes = [u8p, u8p, C.c_int64, C.c_int32, C.c_int32, fp, u8p]
         L.oracle_pack_layer.restype = None
-        L.oracle_unpack_layer.argtypes = [u8p, C.c_int64, C.c_int32, u8p, u8p]
+        L.oracle_unpack_layer.argtypes = [u8p, C.c_int64, C.c_int32, C.c_int32, u8p, u8p, fp]
+        L.oracle_bucket_sumsq.argtypes = [fp, C.c_int64]
+        L.oracle_bucket_sumsq.restype = C.c_double
         L.oracle_unpack_layer.restype = None
-        L.oracle_quantize.argtypes = [C.c_int32, i64p, i32p, pp, pp, C.c_uint64, C.c_uint32, C.c_uint32, u8p, u8p, dp, dp]
+        L.oracle_quantize.argtypes = [C.c_int32, i64p, i32p, pp, pp, C.c_uint64, C.c_uint32, C.c_uint32, C.c_int32, u8p, u8p,
+                                      dp, dp]
         L.oracle_quantize.restype = C.c_int32
-        L.oracle_delta_from_messages.argtypes = [C.c_int32, i64p, i32p, u8p, u8p]
+        L.oracle_delta_from_messages.argtypes = [C.c_int32, i64p, i32p, C.c_int32, u8p, u8p]
         L.oracle_delta_from_messages.restype = C.c_double
-        L.oracle_dequant_aggregate.argtypes = [C.c_int32, i64p, i32p, C.c_int32, pp, pp]
+        L.oracle_dequant_aggregate.argtypes = [C.c_int32, i64p, i32p, C.c_int32, C.c_int32, pp, pp]
         L.oracle_dequant_aggregate.restype = None
         L.oracle_step_size.argtypes = [C.c_int32, dp, dp, fp]
         L.oracle_step_size.restype = None
@@ -92,7 +97,7 @@ def lib():
         L.oracle_fit_objective.restype = C.c_double
         L.oracle_fit_dp.argtypes = [u64p, C.c_int32, fp]
         L.oracle_fit_dp.restype = None
-        L.oracle_fit_levels.argtypes = [C.c_int32, i64p, i32p, C.c_int32, i32p, C.c_int32, pp, pp, u32p, u64p]
+        L.oracle_fit_levels.argtypes = [C.c_int32, i64p, i32p, C.c_int32, i32p, C.c_int32, C.c_int32, pp, pp, u32p, u64p]
         L.oracle_fit_levels.restype = C.c_int32
         _lib = L
     return _lib
@@ -193,52 +198,67 @@ def _dims(sizes, points):
     return d, S
 
 
-def message_bytes(sizes, points) -> int:
+def message_bytes(sizes, points, scope: int = SCOPE_LAYER) -> int:
     d, S = _dims(sizes, points)
-    return int(lib().oracle_message_bytes(d.size, _p(d, C.c_int64), _p(S, C.c_int32)))
+    return int(lib().oracle_message_bytes(d.size, _p(d, C.c_int64), _p(S, C.c_int32), scope))
 
 
-def header_bytes(sizes, points) -> int:
+def header_bytes(sizes, points, scope: int = SCOPE_LAYER) -> int:
     d, S = _dims(sizes, points)
-    return int(lib().oracle_header_bytes(d.size, _p(d, C.c_int64), _p(S, C.c_int32)))
+    return int(lib().oracle_header_bytes(d.size, _p(d, C.c_int64), _p(S, C.c_int32), scope))
 
 
-def layout(sizes, points):
+def layout(sizes, points, scope: int = SCOPE_LAYER):
     d, S = _dims(sizes, points)
     h = np.zeros(d.size, dtype=np.int64)
     m = np.zeros(d.size, dtype=np.int64)
-    lib().oracle_layout(d.size, _p(d, C.c_int64), _p(S, C.c_int32), _p(h, C.c_int64), _p(m, C.c_int64))
+    lib().oracle_layout(d.size, _p(d, C.c_int64), _p(S, C.c_int32), scope, _p(h, C.c_int64), _p(m, C.c_int64))
     return h, m
 
 
-def pack_layer(sign, idx, S: int) -> np.ndarray:
+def octet_bytes(S: int, scope: int = SCOPE_LAYER) -> int:
+    """Bytes of one octet (2048 coordinates) of a layer's body."""
+    return 256 * (1 + index_bits(S)) + (64 if scope == SCOPE_BUCKET else 0)
+
+
+def pack_layer(sign, idx, S: int, scope: int = SCOPE_LAYER, bucket_norms=None) -> np.ndarray:
     sign = np.ascontiguousarray(sign, dtype=np.uint8)
     idx = np.ascontiguousarray(idx, dtype=np.uint8)
     d = sign.size
-    planes = 1 + index_bits(S)
-    region = np.zeros(((d + OCTET - 1) // OCTET) * 256 * planes, dtype=np.uint8)
-    lib().oracle_pack_layer(_p(sign, C.c_uint8), _p(idx, C.c_uint8), d, S, _p(region, C.c_uint8))
+    region = np.zeros(((d + OCTET - 1) // OCTET) * octet_bytes(S, scope), dtype=np.uint8)
+    bn = None if bucket_norms is None else _f32(bucket_norms)
+    lib().oracle_pack_layer(_p(sign, C.c_uint8), _p(idx, C.c_uint8), d, S, scope,
+                            None if bn is None else _p(bn, C.c_float), _p(region, C.c_uint8))
     return region
 
 
-def unpack_layer(region, d: int, S: int):
+def unpack_layer(region, d: int, S: int, scope: int = SCOPE_LAYER):
+    """Returns (sign, index), plus the bucket norms under bucket scope."""
     region = np.ascontiguousarray(region, dtype=np.uint8)
     sign = np.zeros(d, dtype=np.uint8)
     idx = np.zeros(d, dtype=np.uint8)
-    lib().oracle_unpack_layer(_p(region, C.c_uint8), d, S, _p(sign, C.c_uint8), _p(idx, C.c_uint8))
-    return sign, idx
+    bn = np.zeros((d + BUCKET - 1) // BUCKET, dtype=np.float32) if scope == SCOPE_BUCKET else None
+    lib().oracle_unpack_layer(_p(region, C.c_uint8), d, S, scope, _p(sign, C.c_uint8), _p(idx, C.c_uint8),
+                              None if bn is None else _p(bn, C.c_float))
+    return (sign, idx) if bn is None else (sign, idx, bn)
+
+
+def bucket_sumsq(v) -> float:
+    v = _f32(v)
+    assert v.size <= BUCKET
+    return float(lib().oracle_bucket_sumsq(_p(v, C.c_float), v.size))
 
 
 # ------------------------------------------------------------------ whole messages
 def quantize(sizes, points, levels: Sequence[np.ndarray], grads: Sequence[np.ndarray], seed: int, round_: int,
-             node: int, msg_prev: Optional[np.ndarray] = None):
+             node: int, msg_prev: Optional[np.ndarray] = None, scope: int = SCOPE_LAYER):
     """ENCODE(Q(V_k)) for one node.  Returns (msg bytes, sumsq per layer, delta, status)."""
     d, S = _dims(sizes, points)
     lev = [_f32(a) for a in levels]
     g = [_f32(a) for a in grads]
     for l in range(d.size):
         assert g[l].size == d[l] and lev[l].size == S[l]
-    msg = np.zeros(message_bytes(d, S), dtype=np.uint8)
+    msg = np.zeros(message_bytes(d, S, scope), dtype=np.uint8)
     ss = np.zeros(d.size, dtype=np.float64)
     delta = np.zeros(1, dtype=np.float64)
     prev = None
@@ -246,24 +266,25 @@ def quantize(sizes, points, levels: Sequence[np.ndarray], grads: Sequence[np.nda
         prev = np.ascontiguousarray(msg_prev, dtype=np.uint8)
         assert prev.size == msg.size
     st = lib().oracle_quantize(d.size, _p(d, C.c_int64), _p(S, C.c_int32), _ptr_array(lev), _ptr_array(g), seed, round_,
-                               node, _p(msg, C.c_uint8), None if prev is None else _p(prev, C.c_uint8),
+                               node, scope, _p(msg, C.c_uint8), None if prev is None else _p(prev, C.c_uint8),
                                _p(ss, C.c_double), _p(delta, C.c_double))
     return msg, ss, float(delta[0]), int(st)
 
 
-def delta_from_messages(sizes, points, msg, msg_prev=None) -> float:
+def delta_from_messages(sizes, points, msg, msg_prev=None, scope: int = SCOPE_LAYER) -> float:
     d, S = _dims(sizes, points)
     m = np.ascontiguousarray(msg, dtype=np.uint8)
     p = None if msg_prev is None else np.ascontiguousarray(msg_prev, dtype=np.uint8)
-    return float(lib().oracle_delta_from_messages(d.size, _p(d, C.c_int64), _p(S, C.c_int32), _p(m, C.c_uint8),
+    return float(lib().oracle_delta_from_messages(d.size, _p(d, C.c_int64), _p(S, C.c_int32), scope, _p(m, C.c_uint8),
                                                   None if p is None else _p(p, C.c_uint8)))
 
 
-def dequant_aggregate(sizes, points, msgs: Sequence[np.ndarray]) -> List[np.ndarray]:
+def dequant_aggregate(sizes, points, msgs: Sequence[np.ndarray], scope: int = SCOPE_LAYER) -> List[np.ndarray]:
     d, S = _dims(sizes, points)
     ms = [np.ascontiguousarray(m, dtype=np.uint8) for m in msgs]
     out = [np.zeros(int(n), dtype=np.float32) for n in d]
-    lib().oracle_dequant_aggregate(d.size, _p(d, C.c_int64), _p(S, C.c_int32), len(ms), _ptr_array(ms), _ptr_array(out))
+    lib().oracle_dequant_aggregate(d.size, _p(d, C.c_int64), _p(S, C.c_int32), scope, len(ms), _ptr_array(ms),
+                                   _ptr_array(out))
     return out
 
 
@@ -344,7 +365,8 @@ def fit_dp(W, S: int) -> np.ndarray:
     return lev
 
 
-def fit_levels(sizes, layer_type, type_points, K: int, grads: Sequence[np.ndarray], levels: Sequence[np.ndarray]):
+def fit_levels(sizes, layer_type, type_points, K: int, grads: Sequence[np.ndarray], levels: Sequence[np.ndarray],
+               scope: int = SCOPE_LAYER):
     """grads: K*L arrays (entry k*L+l).  levels: M arrays, updated copies returned with (hist, pooled, status)."""
     d = np.ascontiguousarray(sizes, dtype=np.int64)
     lt = np.ascontiguousarray(layer_type, dtype=np.int32)
@@ -355,8 +377,8 @@ def fit_levels(sizes, layer_type, type_points, K: int, grads: Sequence[np.ndarra
     lev = [_f32(a).copy() for a in levels]
     hist = np.zeros(K * L * HIST_BINS, dtype=np.uint32)
     pooled = np.zeros(M * GRID_POINTS, dtype=np.uint64)
-    st = lib().oracle_fit_levels(L, _p(d, C.c_int64), _p(lt, C.c_int32), M, _p(tp, C.c_int32), K, _ptr_array(g),
-                                 _ptr_array(lev), _p(hist, C.c_uint32), _p(pooled, C.c_uint64))
+    st = lib().oracle_fit_levels(L, _p(d, C.c_int64), _p(lt, C.c_int32), M, _p(tp, C.c_int32), K, scope,
+                                 _ptr_array(g), _ptr_array(lev), _p(hist, C.c_uint32), _p(pooled, C.c_uint64))
     return lev, hist.reshape(K, L, HIST_BINS), pooled.reshape(M, GRID_POINTS), int(st)
 
 

@@ -46,6 +46,10 @@ namespace {
 constexpr int64_t kBlock = 256;     // coordinates per block (64 lanes x 4 consecutive coordinates)
 constexpr int64_t kOctet = 2048;    // coordinates per packed record group (8 blocks)
 constexpr int64_t kChunk = 16384;   // coordinates per reduction chunk (64 blocks)
+constexpr int64_t kBucket = 128;    // coordinates per bucket when every bucket carries its own norm (Sec. 7)
+// What one norm covers (Sec. 2.2 normalises "the vector"; Sec. 3 quantizes layer by layer; the experiments of
+// Sec. 7 normalise buckets of 128 entries): a layer, the node's whole dual vector, or a bucket.
+enum Scope { kScopeLayer = 0, kScopeVector = 1, kScopeBucket = 2 };
 constexpr int kSlots = 256;         // reduction slots per chunk
 constexpr int kHistBins = 2048;     // histogram bins on the top 11 magnitude bits of a float
 constexpr int kGridBase = 760;      // (127-32)<<3 : bin of 2^-32 on the normalised grid
@@ -190,7 +194,8 @@ inline float decode_value(uint8_t sign, int h, float norm, const float *lev, int
 // ----- message layout.
 struct Layout {
   int L;
-  std::vector<int64_t> d, noct, hdr_off, msg_off;
+  int scope;
+  std::vector<int64_t> d, noct, hdr_off, msg_off, ostride;   // ostride: bytes per octet of a layer's body
   std::vector<int> S, planes;
   int64_t header_bytes, message_bytes;
   int64_t total_chunks;
@@ -198,15 +203,20 @@ struct Layout {
 
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
-Layout make_layout(int L, const int64_t *d, const int32_t *S) {
+// bytes of one octet of the body: 256*c1 bytes of codes, plus (bucket scope) the octet's 16 bucket norms
+inline int64_t octet_stride(int planes, int scope) { return 256 * (int64_t)planes + (scope == kScopeBucket ? 64 : 0); }
+
+Layout make_layout(int L, const int64_t *d, const int32_t *S, int scope) {
   Layout lay;
   lay.L = L;
+  lay.scope = scope;
   int64_t h = 0;
   for (int l = 0; l < L; ++l) {
     lay.d.push_back(d[l]);
     lay.S.push_back(S[l]);
     lay.planes.push_back(1 + index_bits(S[l]));
     lay.noct.push_back((d[l] + kOctet - 1) / kOctet);
+    lay.ostride.push_back(octet_stride(lay.planes[l], scope));
     lay.hdr_off.push_back(h);
     h += 4 * (1 + (int64_t)S[l]);
   }
@@ -215,7 +225,7 @@ Layout make_layout(int L, const int64_t *d, const int32_t *S) {
   int64_t chunks = 0;
   for (int l = 0; l < L; ++l) {
     lay.msg_off.push_back(off);
-    off += lay.noct[l] * 256 * lay.planes[l];
+    off += lay.noct[l] * lay.ostride[l];
     chunks += (d[l] + kChunk - 1) / kChunk;
   }
   lay.message_bytes = round_up(off, 256);
@@ -229,33 +239,62 @@ Layout make_layout(int L, const int64_t *d, const int32_t *S) {
 // little-endian bit string of 32*c1 bits (code jj at bits [c1*jj, c1*jj + c1)), i.e. c1 32-bit words per lane.
 // Word r of lane i of octet O is the 32-bit word number O*64*c1 + r*64 + i of the layer's body, so that the 64
 // lanes' words r are contiguous.  Padding coordinates carry code 0.
-inline void set_bit(uint8_t *layer_base, int c1, int64_t e, int t, bool v) {
+// Bucket scope: the 256*c1 code bytes of every octet are followed by its 16 bucket norms (fp32).  The bucket of
+// block bb (0..7) and half hf (0: lanes 0..31, i.e. coordinates 0..127 of the block; 1: the rest) sits at position
+// 8*hf + bb, so that the 8 norms a lane needs are contiguous.
+inline void set_bit(uint8_t *layer_base, int c1, int64_t ostride, int64_t e, int t, bool v) {
   const int64_t O = e / kOctet;
   const int bb = (int)((e % kOctet) / kBlock), i = (int)((e % kBlock) / 4), j = (int)(e % 4);
   const int P = c1 * (4 * bb + j) + t;
-  uint32_t *w = reinterpret_cast<uint32_t *>(layer_base) + (O * 64 * c1 + (int64_t)(P / 32) * 64 + i);
+  uint32_t *w = reinterpret_cast<uint32_t *>(layer_base + O * ostride) + ((int64_t)(P / 32) * 64 + i);
   if (v) *w |= (uint32_t)1 << (P % 32);
 }
-inline int get_bit(const uint8_t *layer_base, int c1, int64_t e, int t) {
+inline int get_bit(const uint8_t *layer_base, int c1, int64_t ostride, int64_t e, int t) {
   const int64_t O = e / kOctet;
   const int bb = (int)((e % kOctet) / kBlock), i = (int)((e % kBlock) / 4), j = (int)(e % 4);
   const int P = c1 * (4 * bb + j) + t;
-  const uint32_t *w = reinterpret_cast<const uint32_t *>(layer_base) + (O * 64 * c1 + (int64_t)(P / 32) * 64 + i);
+  const uint32_t *w = reinterpret_cast<const uint32_t *>(layer_base + O * ostride) + ((int64_t)(P / 32) * 64 + i);
   return (int)((*w >> (P % 32)) & 1u);
 }
 
-void put_code(uint8_t *layer_base, int planes, int64_t e, Code c) {
-  set_bit(layer_base, planes, e, 0, c.sign != 0);
-  for (int p = 1; p < planes; ++p) set_bit(layer_base, planes, e, p, ((c.h >> (p - 1)) & 1) != 0);
+void put_code(uint8_t *layer_base, int planes, int64_t ostride, int64_t e, Code c) {
+  set_bit(layer_base, planes, ostride, e, 0, c.sign != 0);
+  for (int p = 1; p < planes; ++p) set_bit(layer_base, planes, ostride, e, p, ((c.h >> (p - 1)) & 1) != 0);
 }
 
-Code get_code(const uint8_t *layer_base, int planes, int64_t e) {
+Code get_code(const uint8_t *layer_base, int planes, int64_t ostride, int64_t e) {
   Code c;
-  c.sign = (uint8_t)get_bit(layer_base, planes, e, 0);
+  c.sign = (uint8_t)get_bit(layer_base, planes, ostride, e, 0);
   int h = 0;
-  for (int p = 1; p < planes; ++p) h |= get_bit(layer_base, planes, e, p) << (p - 1);
+  for (int p = 1; p < planes; ++p) h |= get_bit(layer_base, planes, ostride, e, p) << (p - 1);
   c.h = (uint8_t)h;
   return c;
+}
+
+// address of the stored norm of the bucket that holds coordinate e (bucket scope only)
+inline float *bucket_norm_slot(uint8_t *layer_base, int planes, int64_t ostride, int64_t e) {
+  const int64_t O = e / kOctet;
+  const int bb = (int)((e % kOctet) / kBlock), hf = (int)((e % kBlock) / kBucket);
+  return reinterpret_cast<float *>(layer_base + O * ostride + 256 * (int64_t)planes) + (8 * hf + bb);
+}
+
+// Sum of squares of one bucket (n <= 128 coordinates, missing ones count as 0): "lane" i = (e mod 128)/4 adds the
+// squares of its four consecutive coordinates in order (products exact in fp64), then the 32 lane sums are combined
+// by the in-order binary tree (lanes 0+1, 2+3, ...; then pairs of those; ...).
+double bucket_sumsq(const float *v, int64_t n) {
+  double p[32];
+  for (int i = 0; i < 32; ++i) {
+    double acc = 0.0;
+    for (int j = 0; j < 4; ++j) {
+      const int64_t e = 4 * i + j;
+      const double x = (e < n) ? (double)v[e] : 0.0;
+      acc = acc + x * x;
+    }
+    p[i] = acc;
+  }
+  for (int w = 1; w < 32; w *= 2)
+    for (int i = 0; i < 32; i += 2 * w) p[i] = p[i] + p[i + w];
+  return p[0];
 }
 
 struct HeaderView { float norm; const float *lev; };
@@ -322,47 +361,90 @@ void oracle_decode(const uint8_t *sign, const uint8_t *index, int64_t n, float n
 }
 
 // ---------------------------------------------------------------- message layout (Sec. 3.2, fixed width)
-int64_t oracle_message_bytes(int32_t L, const int64_t *d, const int32_t *S) { return make_layout(L, d, S).message_bytes; }
-int64_t oracle_header_bytes(int32_t L, const int64_t *d, const int32_t *S) { return make_layout(L, d, S).header_bytes; }
-void oracle_layout(int32_t L, const int64_t *d, const int32_t *S, int64_t *hdr_off, int64_t *msg_off) {
-  const Layout lay = make_layout(L, d, S);
+int64_t oracle_message_bytes(int32_t L, const int64_t *d, const int32_t *S, int32_t scope) {
+  return make_layout(L, d, S, scope).message_bytes;
+}
+int64_t oracle_header_bytes(int32_t L, const int64_t *d, const int32_t *S, int32_t scope) {
+  return make_layout(L, d, S, scope).header_bytes;
+}
+void oracle_layout(int32_t L, const int64_t *d, const int32_t *S, int32_t scope, int64_t *hdr_off, int64_t *msg_off) {
+  const Layout lay = make_layout(L, d, S, scope);
   for (int l = 0; l < L; ++l) { hdr_off[l] = lay.hdr_off[l]; msg_off[l] = lay.msg_off[l]; }
 }
 
-// pack / unpack the codes of one layer into its body (region must hold ceil(d/2048)*256*planes bytes).
-void oracle_pack_layer(const uint8_t *sign, const uint8_t *index, int64_t d, int32_t S, uint8_t *region) {
+// pack / unpack the codes of one layer into its body (region must hold ceil(d/2048) octets of the scope's stride).
+// bucket scope: norms (ceil(d/128) floats, bucket order) are stored too / returned when the pointer is not NULL.
+void oracle_pack_layer(const uint8_t *sign, const uint8_t *index, int64_t d, int32_t S, int32_t scope,
+                       const float *bucket_norms, uint8_t *region) {
   const int planes = 1 + index_bits(S);
+  const int64_t os = octet_stride(planes, scope);
   const int64_t noct = (d + kOctet - 1) / kOctet;
-  std::memset(region, 0, (size_t)(noct * 256 * planes));
-  for (int64_t e = 0; e < d; ++e) { Code c; c.sign = sign[e]; c.h = index[e]; put_code(region, planes, e, c); }
+  std::memset(region, 0, (size_t)(noct * os));
+  for (int64_t e = 0; e < d; ++e) { Code c; c.sign = sign[e]; c.h = index[e]; put_code(region, planes, os, e, c); }
+  if (scope == kScopeBucket && bucket_norms)
+    for (int64_t b = 0; b * kBucket < d; ++b) *bucket_norm_slot(region, planes, os, b * kBucket) = bucket_norms[b];
 }
-void oracle_unpack_layer(const uint8_t *region, int64_t d, int32_t S, uint8_t *sign, uint8_t *index) {
+void oracle_unpack_layer(const uint8_t *region, int64_t d, int32_t S, int32_t scope, uint8_t *sign, uint8_t *index,
+                         float *bucket_norms) {
   const int planes = 1 + index_bits(S);
-  for (int64_t e = 0; e < d; ++e) { const Code c = get_code(region, planes, e); sign[e] = c.sign; index[e] = c.h; }
+  const int64_t os = octet_stride(planes, scope);
+  for (int64_t e = 0; e < d; ++e) { const Code c = get_code(region, planes, os, e); sign[e] = c.sign; index[e] = c.h; }
+  if (scope == kScopeBucket && bucket_norms)
+    for (int64_t b = 0; b * kBucket < d; ++b)
+      bucket_norms[b] = *bucket_norm_slot(const_cast<uint8_t *>(region), planes, os, b * kBucket);
 }
+
+double oracle_bucket_sumsq(const float *v, int64_t n) { return bucket_sumsq(v, n); }
+
+namespace {
+const double kFiniteLimit = (double)std::numeric_limits<float>::max() * (double)std::numeric_limits<float>::max();
+
+// the norm DECODE uses for coordinate e of layer l: the header's (layer and vector scope) or the bucket's
+inline float stored_norm(const uint8_t *msg, const Layout &lay, int l, int64_t e) {
+  if (lay.scope != kScopeBucket) return header_of(msg, lay, l).norm;
+  return *bucket_norm_slot(const_cast<uint8_t *>(msg) + lay.msg_off[l], lay.planes[l], lay.ostride[l], e);
+}
+}  // namespace
 
 // ---------------------------------------------------------------- ENCODE(Q(V_k)) for one node: Alg. 1 line 12
 // grads[l]  : layer l of the node's dual vector.      levels[l] : the S[l] levels of layer l's type.
 // msg       : message_bytes output.                    msg_prev  : previous-round message of this node or NULL.
-// sumsq_out : L canonical sums of squares (may be NULL).
+// scope     : what one norm covers.  Layer: the layer's canonical sum of squares.  Vector: the canonical
+//             combination of the L layer sums (slot j takes layers j, j+256, ...; then the tree), used by every
+//             layer.  Bucket: every 128 consecutive coordinates of a layer (bucket_sumsq); the norms travel in the body.
+// sumsq_out : L sums of squares (may be NULL): the layer's; under vector scope the whole vector's in every entry;
+//             under bucket scope the largest bucket sum of the layer.
 // delta_out : || Vhat_{k,t+1/2} - Vhat_{k,t-1/2} ||^2 (the step-size term of eq. (general_stepsize)); prev = 0 if NULL.
-// returns 0, or 1 if a layer's sum of squares is not finite.
+// returns 0, or 1 if a sum of squares is not finite or a norm exceeds the largest float.
 int32_t oracle_quantize(int32_t L, const int64_t *d, const int32_t *S, const float *const *levels,
-                        const float *const *grads, uint64_t seed, uint32_t round, uint32_t node, uint8_t *msg,
-                        const uint8_t *msg_prev, double *sumsq_out, double *delta_out) {
-  const Layout lay = make_layout(L, d, S);
+                        const float *const *grads, uint64_t seed, uint32_t round, uint32_t node, int32_t scope,
+                        uint8_t *msg, const uint8_t *msg_prev, double *sumsq_out, double *delta_out) {
+  const Layout lay = make_layout(L, d, S, scope);
   std::memset(msg, 0, (size_t)lay.message_bytes);
   int32_t status = 0;
+  std::vector<double> layer_sums(L, 0.0);
+  if (scope != kScopeBucket) {
+    for (int l = 0; l < L; ++l) layer_sums[l] = oracle_sumsq(grads[l], d[l]);
+    if (scope == kScopeVector) {
+      const double total = combine_chunks(layer_sums);
+      for (int l = 0; l < L; ++l) layer_sums[l] = total;
+    }
+  }
   std::vector<double> delta_chunks;
   for (int l = 0; l < L; ++l) {
-    const double s = oracle_sumsq(grads[l], d[l]);
-    if (sumsq_out) sumsq_out[l] = s;
-    const bool finite = (s >= 0.0) && (s <= (double)std::numeric_limits<float>::max() * (double)std::numeric_limits<float>::max());
-    if (!finite) status = 1;
-    const float norm = finite ? sqrt_floor(s) : 0.0f;
-    const float inv = rcp_floor(norm);
+    float norm = 0.0f, inv = 0.0f;
+    if (scope != kScopeBucket) {
+      const double s = layer_sums[l];
+      if (sumsq_out) sumsq_out[l] = s;
+      const bool finite = (s >= 0.0) && (s <= kFiniteLimit);
+      if (!finite) status = 1;
+      norm = finite ? sqrt_floor(s) : 0.0f;
+      inv = rcp_floor(norm);
+    } else if (sumsq_out) {
+      sumsq_out[l] = 0.0;
+    }
     float *hdr = reinterpret_cast<float *>(msg + lay.hdr_off[l]);
-    hdr[0] = norm;
+    hdr[0] = norm;   // bucket scope: unused, 0
     for (int j = 0; j < S[l]; ++j) hdr[1 + j] = levels[l][j];
     uint8_t *region = msg + lay.msg_off[l];
     const int64_t nchunks = (d[l] + kChunk - 1) / kChunk;
@@ -373,15 +455,24 @@ int32_t oracle_quantize(int32_t L, const int64_t *d, const int32_t *S, const flo
       for (int j = 0; j < kSlots; ++j) p32[j] = 0.0f;
       const int64_t e1 = std::min(d[l], (c + 1) * kChunk);   // padding coordinates carry code 0 and add nothing
       for (int64_t e = c * kChunk; e < e1; ++e) {
+        if (scope == kScopeBucket && e % kBucket == 0) {
+          const double s = bucket_sumsq(grads[l] + e, std::min<int64_t>(kBucket, d[l] - e));
+          const bool finite = (s >= 0.0) && (s <= kFiniteLimit);
+          if (!finite) status = 1;
+          norm = finite ? sqrt_floor(s) : 0.0f;
+          inv = rcp_floor(norm);
+          *bucket_norm_slot(region, lay.planes[l], lay.ostride[l], e) = norm;
+          if (sumsq_out && finite && s > sumsq_out[l]) sumsq_out[l] = s;
+        }
         const Code code =
             quantize_coord(grads[l][e], inv, levels[l], S[l], draw16(seed, round, node, (uint32_t)l, (uint64_t)e));
-        put_code(region, lay.planes[l], e, code);
+        put_code(region, lay.planes[l], lay.ostride[l], e, code);
         const float cur = decode_value(code.sign, code.h, norm, levels[l], S[l]);
         float prev = 0.0f;
         if (msg_prev) {
           const HeaderView hp = header_of(msg_prev, lay, l);
-          const Code pc = get_code(msg_prev + lay.msg_off[l], lay.planes[l], e);
-          prev = decode_value(pc.sign, pc.h, hp.norm, hp.lev, S[l]);
+          const Code pc = get_code(msg_prev + lay.msg_off[l], lay.planes[l], lay.ostride[l], e);
+          prev = decode_value(pc.sign, pc.h, stored_norm(msg_prev, lay, l, e), hp.lev, S[l]);
         }
         const float diff = cur - prev;
         p32[slot_of(e)] = std::fmaf(diff, diff, p32[slot_of(e)]);
@@ -398,9 +489,9 @@ int32_t oracle_quantize(int32_t L, const int64_t *d, const int32_t *S, const flo
 // ---------------------------------------------------------------- step-size term from two stored messages
 // || DECODE(msg) - DECODE(msg_prev) ||^2 in the same order as oracle_quantize accumulates it (msg_prev NULL: zeros).
 // Lets a test check delta_k of a full-size model without quantizing it on the CPU.
-double oracle_delta_from_messages(int32_t L, const int64_t *d, const int32_t *S, const uint8_t *msg,
+double oracle_delta_from_messages(int32_t L, const int64_t *d, const int32_t *S, int32_t scope, const uint8_t *msg,
                                   const uint8_t *msg_prev) {
-  const Layout lay = make_layout(L, d, S);
+  const Layout lay = make_layout(L, d, S, scope);
   std::vector<double> delta_chunks;
   for (int l = 0; l < L; ++l) {
     const HeaderView hc = header_of(msg, lay, l);
@@ -410,13 +501,13 @@ double oracle_delta_from_messages(int32_t L, const int64_t *d, const int32_t *S,
       for (int j = 0; j < kSlots; ++j) p32[j] = 0.0f;
       const int64_t e1 = std::min(d[l], (c + 1) * kChunk);
       for (int64_t e = c * kChunk; e < e1; ++e) {
-        const Code cc = get_code(msg + lay.msg_off[l], lay.planes[l], e);
-        const float cur = decode_value(cc.sign, cc.h, hc.norm, hc.lev, S[l]);
+        const Code cc = get_code(msg + lay.msg_off[l], lay.planes[l], lay.ostride[l], e);
+        const float cur = decode_value(cc.sign, cc.h, stored_norm(msg, lay, l, e), hc.lev, S[l]);
         float prev = 0.0f;
         if (msg_prev) {
           const HeaderView hp = header_of(msg_prev, lay, l);
-          const Code pc = get_code(msg_prev + lay.msg_off[l], lay.planes[l], e);
-          prev = decode_value(pc.sign, pc.h, hp.norm, hp.lev, S[l]);
+          const Code pc = get_code(msg_prev + lay.msg_off[l], lay.planes[l], lay.ostride[l], e);
+          prev = decode_value(pc.sign, pc.h, stored_norm(msg_prev, lay, l, e), hp.lev, S[l]);
         }
         const float diff = cur - prev;
         p32[slot_of(e)] = std::fmaf(diff, diff, p32[slot_of(e)]);
@@ -431,17 +522,17 @@ double oracle_delta_from_messages(int32_t L, const int64_t *d, const int32_t *S,
 
 // ---------------------------------------------------------------- DECODE + mean over the K nodes: Alg. 1 lines 15-17
 // mean_out[l][e] = ((Vhat_0 + Vhat_1) + ... + Vhat_{K-1}) * (1/K), all in fp32, k increasing.
-void oracle_dequant_aggregate(int32_t L, const int64_t *d, const int32_t *S, int32_t K, const uint8_t *const *msgs,
-                              float *const *mean_out) {
-  const Layout lay = make_layout(L, d, S);
+void oracle_dequant_aggregate(int32_t L, const int64_t *d, const int32_t *S, int32_t scope, int32_t K,
+                              const uint8_t *const *msgs, float *const *mean_out) {
+  const Layout lay = make_layout(L, d, S, scope);
   const float invK = 1.0f / (float)K;
   for (int l = 0; l < L; ++l)
     for (int64_t e = 0; e < d[l]; ++e) {
       float sum = 0.0f;
       for (int k = 0; k < K; ++k) {
         const HeaderView h = header_of(msgs[k], lay, l);
-        const Code c = get_code(msgs[k] + lay.msg_off[l], lay.planes[l], e);
-        const float val = decode_value(c.sign, c.h, h.norm, h.lev, S[l]);
+        const Code c = get_code(msgs[k] + lay.msg_off[l], lay.planes[l], lay.ostride[l], e);
+        const float val = decode_value(c.sign, c.h, stored_norm(msgs[k], lay, l, e), h.lev, S[l]);
         sum = (k == 0) ? val : sum + val;
       }
       mean_out[l][e] = sum * invK;
@@ -618,18 +709,73 @@ void oracle_fit_dp(const uint64_t *W, int32_t S, float *lev_out) {
 }
 
 int32_t oracle_fit_levels(int32_t L, const int64_t *d, const int32_t *layer_type, int32_t M, const int32_t *type_points,
-                          int32_t K, const float *const *grads /* K*L, entry k*L+l */, float *const *levels_io,
-                          uint32_t *hist_out, uint64_t *pooled_out) {
+                          int32_t K, int32_t scope, const float *const *grads /* K*L, entry k*L+l */,
+                          float *const *levels_io, uint32_t *hist_out, uint64_t *pooled_out) {
+  const double smax_ok = (double)std::numeric_limits<float>::max() * (double)std::numeric_limits<float>::max();
+  int32_t status = 0;
+  if (scope == kScopeBucket) {
+    // Every bucket is a vector of its own: weight = its sum of squares, normalisation = its norm.  Sampled
+    // coordinates (blocks 0, 4, 8, ... as above, minus those whose raw magnitude bin is 0) go straight onto the
+    // normalised grid: W[bin(min(|v| * inv_b, 1))] += floor(sumsq_b * 2^(23 - e)), e = binary exponent of the type's
+    // largest bucket sum.  There is no per-layer raw histogram in this scope (hist_out is left untouched).
+    for (int m = 0; m < M; ++m) {
+      std::vector<uint64_t> W(kGridPoints, 0);
+      double smax = 0.0;
+      bool finite = true;
+      for (int l = 0; l < L; ++l) {
+        if (layer_type[l] != m) continue;
+        for (int k = 0; k < K; ++k)
+          for (int64_t e = 0; e < d[l]; e += kBucket) {
+            const double v = bucket_sumsq(grads[(size_t)k * L + l] + e, std::min<int64_t>(kBucket, d[l] - e));
+            if (!(v >= 0.0) || !(v <= smax_ok)) finite = false;
+            else if (v > smax) smax = v;
+          }
+      }
+      if (!finite) status = 1;
+      if (finite && smax > 0.0) {
+        const int ex = std::ilogb(smax);
+        for (int l = 0; l < L; ++l) {
+          if (layer_type[l] != m) continue;
+          for (int k = 0; k < K; ++k) {
+            const float *g = grads[(size_t)k * L + l];
+            for (int64_t e0 = 0; e0 < d[l]; e0 += kBucket) {
+              if (((e0 / kBlock) % 4) != 0) continue;
+              const int64_t n = std::min<int64_t>(kBucket, d[l] - e0);
+              const double sv = bucket_sumsq(g + e0, n);
+              const uint64_t wfix = (uint64_t)std::floor(std::ldexp(sv, 23 - ex));
+              const float inv = rcp_floor(sqrt_floor(sv));
+              if (wfix == 0 || inv == 0.0f) continue;
+              for (int64_t e = e0; e < e0 + n; ++e) {
+                if (((f2u(g[e]) & 0x7FFFFFFFu) >> 20) == 0) continue;
+                const float uc = std::fmin(std::fabs(g[e]) * inv, 1.0f);
+                int j = (int)(f2u(uc) >> 20) - kGridBase;
+                if (j < 0) j = 0;
+                if (j > kGridPoints - 1) j = kGridPoints - 1;
+                W[j] += wfix;
+              }
+            }
+          }
+        }
+        oracle_fit_dp(W.data(), type_points[m], levels_io[m]);
+      }
+      if (pooled_out) std::memcpy(pooled_out + (size_t)m * kGridPoints, W.data(), kGridPoints * sizeof(uint64_t));
+    }
+    return status;
+  }
   std::vector<double> s((size_t)K * L);
   std::vector<uint32_t> hist((size_t)K * L * kHistBins, 0);
-  for (int k = 0; k < K; ++k)
+  for (int k = 0; k < K; ++k) {
     for (int l = 0; l < L; ++l) {
       s[(size_t)k * L + l] = oracle_sumsq(grads[(size_t)k * L + l], d[l]);
       oracle_histogram(grads[(size_t)k * L + l], d[l], &hist[((size_t)k * L + l) * kHistBins]);
     }
+    if (scope == kScopeVector) {   // one vector per node: its norm normalises, its squared norm weighs, every layer
+      const std::vector<double> sums(s.begin() + (size_t)k * L, s.begin() + (size_t)(k + 1) * L);
+      const double total = combine_chunks(sums);
+      for (int l = 0; l < L; ++l) s[(size_t)k * L + l] = total;
+    }
+  }
   if (hist_out) std::memcpy(hist_out, hist.data(), hist.size() * sizeof(uint32_t));
-  const double smax_ok = (double)std::numeric_limits<float>::max() * (double)std::numeric_limits<float>::max();
-  int32_t status = 0;
   for (int m = 0; m < M; ++m) {
     std::vector<uint64_t> W(kGridPoints, 0);
     double smax = 0.0;
