@@ -49,6 +49,19 @@ extern "C" {
 
 #define QODA_MAX_POINTS 256 /* S_m <= 256: level index fits 8 bits */
 
+/* What one norm covers (Sec. 2.2 normalises "the vector"; Sec. 3 quantizes layer by layer; the experiments of
+ * Sec. 7 normalise buckets of 128 entries).
+ *   LAYER   one norm per layer (the default of this library);
+ *   VECTOR  one norm for the node's whole dual vector: the L layer sums of squares are combined and every layer
+ *           uses that norm (each layer's header carries it); message format as under LAYER;
+ *   BUCKET  one norm per 128 consecutive coordinates of a layer, computed in the same pass that quantizes (the
+ *           gradient is read once).  The 256*(1+b) code bytes of every octet are followed by the octet's 16 bucket
+ *           norms (fp32; the bucket of block bb = 0..7, half hf = 0..1 of the octet at position 8*hf + bb), so an
+ *           octet takes 256*(1+b) + 64 bytes; the header's norm entry is 0 and unused. */
+#define QODA_SCOPE_LAYER 0
+#define QODA_SCOPE_VECTOR 1
+#define QODA_SCOPE_BUCKET 2
+
 typedef struct qoda_ctx qoda_ctx;
 
 typedef struct {
@@ -60,6 +73,7 @@ typedef struct {
   int32_t num_nodes;          /* K >= 1 */
   int32_t norm_kind;          /* 2 = L2 (the only kind built) */
   uint64_t seed;              /* key of the counter-based generator */
+  int32_t norm_scope;         /* QODA_SCOPE_*: what one norm covers */
 } qoda_config;
 
 /* Create / destroy.  qoda_create allocates all device scratch (a few MB plus 8 bytes per 16384 coordinates per
@@ -173,7 +187,7 @@ int qoda_status(qoda_ctx *ctx, void *stream);
  *   of range.
  * qoda_copy_calibration: a plain 128-bit copy kernel of `bytes` bytes (multiple of 16; 16-byte aligned device
  *   pointers): the known-traffic kernel that hardware byte counters are scaled by. */
-#define QODA_NUM_KERNELS 18
+#define QODA_NUM_KERNELS 21
 int qoda_profile_enable(qoda_ctx *ctx, uint32_t class_mask);
 int qoda_profile_read(qoda_ctx *ctx, double *ms, int64_t *launches, void *stream);
 const char *qoda_kernel_name(int32_t id);

@@ -717,7 +717,7 @@ int32_t oracle_fit_levels(int32_t L, const int64_t *d, const int32_t *layer_type
     // Every bucket is a vector of its own: weight = its sum of squares, normalisation = its norm.  Sampled
     // coordinates (blocks 0, 4, 8, ... as above, minus those whose raw magnitude bin is 0) go straight onto the
     // normalised grid: W[bin(min(|v| * inv_b, 1))] += floor(sumsq_b * 2^(23 - e)), e = binary exponent of the type's
-    // largest bucket sum.  There is no per-layer raw histogram in this scope (hist_out is left untouched).
+    // largest sampled bucket sum.  There is no per-layer raw histogram in this scope (hist_out is left untouched).
     for (int m = 0; m < M; ++m) {
       std::vector<uint64_t> W(kGridPoints, 0);
       double smax = 0.0;
@@ -726,6 +726,7 @@ int32_t oracle_fit_levels(int32_t L, const int64_t *d, const int32_t *layer_type
         if (layer_type[l] != m) continue;
         for (int k = 0; k < K; ++k)
           for (int64_t e = 0; e < d[l]; e += kBucket) {
+            if (((e / kBlock) % 4) != 0) continue;   // only sampled buckets carry weight, so only they set the scale
             const double v = bucket_sumsq(grads[(size_t)k * L + l] + e, std::min<int64_t>(kBucket, d[l] - e));
             if (!(v >= 0.0) || !(v <= smax_ok)) finite = false;
             else if (v > smax) smax = v;

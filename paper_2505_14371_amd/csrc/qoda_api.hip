@@ -19,6 +19,7 @@ using namespace qoda;
 
 struct qoda_ctx {
   int L = 0, M = 0, K = 0, G = 0;
+  int scope = 0;   // NormScope
   uint64_t seed = 0;
   std::vector<LayerMeta> meta;
   std::vector<int> type_points;
@@ -151,6 +152,7 @@ Dev base_args(const qoda_ctx *c) {
   a.n_empty = c->n_empty;
   a.GS = c->GS;
   a.L = c->L; a.G = c->G; a.K = c->K; a.M = c->M;
+  a.scope = c->scope;
   a.type_points = c->d_type_points;
   a.partial = c->d_partial; a.dpartial = c->d_dpartial; a.sumsq = c->d_sumsq;
   a.norm = c->d_norm; a.inv = c->d_inv; a.delta = c->d_delta;
@@ -206,6 +208,7 @@ void free_all(qoda_ctx *c) {
 int run_norm_pass(qoda_ctx *c, Dev a, bool with_hist, hipStream_t s) {
   LAUNCH(c, with_hist ? kIdSumsqHist : kIdSumsq, s, launch_sumsq(a, with_hist, s));
   LAUNCH(c, kIdNormFinalize, s, launch_norm_finalize(a, s));
+  if (c->scope == kScopeVector) LAUNCH(c, kIdNormVector, s, launch_norm_vector(a, s));
   return QODA_OK;
 }
 
@@ -223,6 +226,7 @@ int quantize_impl(qoda_ctx *c, int node0, int nnodes, const float *const *grad_f
     for (int k = node0; k < node0 + nnodes && cached; ++k)
       for (int l = 0; l < c->L; ++l)
         if (c->norms_grad[(size_t)k * c->L + l] != grad_full[(size_t)k * c->L + l]) { cached = false; break; }
+  if (c->scope == kScopeBucket) cached = true;   // the bucket norms are computed by the quantize kernel itself
   if (!cached) {
     c->norms_valid = false;   // the cached norms of these nodes are about to be overwritten
     int rc = run_norm_pass(c, a, false, s);
@@ -243,9 +247,11 @@ int qoda_create(const qoda_config *cfg, qoda_ctx **out) {
   if (!cfg || !cfg->layer_size || !cfg->layer_type || !cfg->type_points) return QODA_EINVAL;
   if (cfg->num_layers < 1 || cfg->num_types < 1 || cfg->num_nodes < 1 || cfg->num_nodes > 65535) return QODA_EINVAL;
   if (cfg->norm_kind != 2) return QODA_EINVAL;
+  if (cfg->norm_scope < QODA_SCOPE_LAYER || cfg->norm_scope > QODA_SCOPE_BUCKET) return QODA_EINVAL;
   qoda_ctx *c = new (std::nothrow) qoda_ctx;
   if (!c) return QODA_ENOMEM;
   c->L = cfg->num_layers; c->M = cfg->num_types; c->K = cfg->num_nodes; c->seed = cfg->seed;
+  c->scope = cfg->norm_scope;
   for (int m = 0; m < c->M; ++m) {
     if (cfg->type_points[m] < 2 || cfg->type_points[m] > QODA_MAX_POINTS) { delete c; return QODA_EINVAL; }
     c->type_points.push_back(cfg->type_points[m]);
@@ -278,7 +284,8 @@ int qoda_create(const qoda_config *cfg, qoda_ctx **out) {
   size_t off = c->header_bytes;
   for (int l = 0; l < c->L; ++l) {
     c->meta[l].body_off = (long long)off;
-    off += (size_t)((c->meta[l].nblk + 7) / 8) * 256 * c->meta[l].planes;   // octets of 8 blocks, planes*256 bytes each
+    // octets of 8 blocks: planes*256 bytes of codes each, plus the octet's 16 bucket norms under bucket scope
+    off += (size_t)((c->meta[l].nblk + 7) / 8) * (256 * c->meta[l].planes + (c->scope == kScopeBucket ? 64 : 0));
   }
   c->message_bytes = round_up(off, 256);
   c->G = (int)chunks;
@@ -424,6 +431,15 @@ int qoda_fit_levels(qoda_ctx *c, const float *const *grad_dev, uint32_t round, v
   a.grad = reinterpret_cast<const float *const *>(c->t_grad.dev);
   a.round = round;
   LAUNCH(c, kIdZero, s, launch_zero_u32(c->d_hist, KL * kHistBins, s));
+  if (c->scope == kScopeBucket) {
+    // two passes over the sampled quarter of the gradient: the scale of the weights, then the weighted histogram
+    LAUNCH(c, kIdZero, s, launch_zero_u32(reinterpret_cast<unsigned int *>(c->d_sumsq), 2 * KL, s));
+    LAUNCH(c, kIdBucketMax, s, launch_bucket_max(a, s));
+    LAUNCH(c, kIdFitTypemax, s, launch_fit_typemax(a, s));
+    LAUNCH(c, kIdBucketHist, s, launch_bucket_hist(a, s));
+    LAUNCH(c, kIdFitDp, s, launch_fit_dp(a, s));
+    return QODA_OK;
+  }
   rc = run_norm_pass(c, a, true, s);
   if (rc) return rc;
   LAUNCH(c, kIdFitTypemax, s, launch_fit_typemax(a, s));
@@ -646,7 +662,8 @@ const char *qoda_kernel_name(int32_t id) {
                                              "k_write_header", "k_quantize", "k_delta_finalize", "k_step_scalars",
                                              "k_decode<false>", "k_decode<true>", "k_fit_typemax", "k_fit_pool",
                                              "k_fit_dp", "k_build_tables", "k_copy_f4", "k_alt_scalars",
-                                             "k_decode<alt>", "k_alt_finalize"};
+                                             "k_decode<alt>", "k_alt_finalize", "k_norm_vector", "k_bucket_max",
+                                             "k_bucket_hist"};
   return (id >= 0 && id < kNumKernelIds) ? names[id] : "";
 }
 

@@ -16,6 +16,10 @@ constexpr int kGridPoints = 257;     // normalised grid g_0 = 2^-32 ... g_256 = 
 constexpr int kMaxPoints = 256;
 constexpr int kLutSize = 1024;       // level-search table indexed by bits(u) >> 20 (u in [0,1] -> 0..1016)
 constexpr int kTypeSkip = 0x7fffffff;
+constexpr int kBucketCoords = 128;   // coordinates per bucket when every bucket carries its own norm
+
+// What one norm covers: a layer, the node's whole vector, or a bucket of 128 consecutive coordinates of a layer.
+enum NormScope { kScopeLayer = 0, kScopeVector = 1, kScopeBucket = 2 };
 
 struct LayerMeta {
   long long d;         // elements
@@ -35,6 +39,7 @@ struct Dev {
   const int2 *tiles;  // per tile: (layer, chunk inside layer)
   const int4 *stiles; // per run of up to kSuperTile tiles of one layer: (layer, first chunk inside layer, chunks, -)
   int L, G, GS, K, M; // GS = number of runs
+  int scope;          // NormScope
   const int *type_points;          // [M]
   const int *empty_layers;         // indices of the layers with d = 0
   int n_empty;
@@ -84,19 +89,22 @@ enum DecodeMode { kDecodeMean = 0, kDecodeUpdate = 1, kDecodeUpdateAlt = 2 };
 enum KernelId {
   kIdZero = 0, kIdSumsq, kIdSumsqHist, kIdNormFinalize, kIdWriteHeader, kIdQuantize, kIdDeltaFinalize, kIdStepScalars,
   kIdDecodeMean, kIdDecodeUpdate, kIdFitTypemax, kIdFitPool, kIdFitDp, kIdBuildTables, kIdCopy, kIdAltScalars,
-  kIdDecodeAlt, kIdAltFinalize, kNumKernelIds
+  kIdDecodeAlt, kIdAltFinalize, kIdNormVector, kIdBucketMax, kIdBucketHist, kNumKernelIds
 };
 
 // Launch wrappers (each checks nothing: the host API validates shapes before calling).
 hipError_t launch_zero_u32(unsigned int *p, size_t n, hipStream_t s);
 hipError_t launch_sumsq(const Dev &a, bool with_hist, hipStream_t s);
 hipError_t launch_norm_finalize(const Dev &a, hipStream_t s);
+hipError_t launch_norm_vector(const Dev &a, hipStream_t s);
 hipError_t launch_quantize(const Dev &a, unsigned int planes_mask, hipStream_t s);
 hipError_t launch_delta_finalize(const Dev &a, hipStream_t s);
 hipError_t launch_step_scalars(const Dev &a, hipStream_t s);
 hipError_t launch_decode(const Dev &a, int mode, unsigned int planes_mask, hipStream_t s);   // mode: DecodeMode
 hipError_t launch_alt_scalars(const Dev &a, hipStream_t s);
 hipError_t launch_alt_finalize(const Dev &a, hipStream_t s);
+hipError_t launch_bucket_max(const Dev &a, hipStream_t s);    // bucket scope: a.sumsq must be zero
+hipError_t launch_bucket_hist(const Dev &a, hipStream_t s);   // bucket scope: grid histograms, then pooling
 hipError_t launch_fit_typemax(const Dev &a, hipStream_t s);
 hipError_t launch_fit_pool(const Dev &a, hipStream_t s);
 hipError_t launch_fit_dp(const Dev &a, hipStream_t s);

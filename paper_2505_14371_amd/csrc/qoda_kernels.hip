@@ -281,6 +281,32 @@ __global__ void __launch_bounds__(kThreads) k_norm_finalize(Dev a) {
   }
 }
 
+// Whole-vector scope (the literal normalisation of Sec. 2.2 / Sec. 3.1): the L layer sums of a node are combined
+// (slot j takes layers j, j+256, ... in increasing order, then the halving tree) and every layer of the node gets
+// that sum, its root and the root's reciprocal.
+__global__ void __launch_bounds__(kThreads) k_norm_vector(Dev a) {
+  __shared__ double red[kThreads];
+  __shared__ double tot[1];
+  const int k = a.node0 + blockIdx.x;
+  double acc = 0.0;
+  for (int l = threadIdx.x; l < a.L; l += kThreads) acc = acc + a.sumsq[(size_t)k * a.L + l];
+  const double s = block_tree(acc, red);
+  if (threadIdx.x == 0) tot[0] = s;
+  __syncthreads();
+  const double total = tot[0];
+  const double lim = (double)kFltMax * (double)kFltMax;
+  const bool finite = (total >= 0.0) && (total <= lim);
+  const float n = finite ? sqrt_floor(total) : 0.0f;
+  const float r = rcp_floor(n);
+  for (int l = threadIdx.x; l < a.L; l += kThreads) {
+    const size_t idx = (size_t)k * a.L + l;
+    a.sumsq[idx] = total;
+    a.norm[idx] = n;
+    a.inv[idx] = r;
+  }
+  if (threadIdx.x == 0 && !finite) atomicOr(a.status, 1u);
+}
+
 // ------------------------------------------------------------------------------------------------ pass 2
 // Quantize + pack one tile (Sec. 3.1, Sec. 3.2) and accumulate the squared distance to the node's previous
 // decoded message (the step-size term of eq. (general_stepsize)).
@@ -455,6 +481,215 @@ __global__ void __launch_bounds__(kThreads) k_quantize(Dev a) {
   quantize_tile<C1>(a, m, l, k, tile.y, lut, tab, tprev, red);
 }
 
+// ------------------------------------------------------------------------------------------------ bucket scope
+// One norm per 128 consecutive coordinates (the experiments' setting, Sec. 7): the norms are computed by the wave
+// that quantizes, so the gradient is read from memory once (the second touch of an octet, a few microseconds after
+// the first, is served by the cache).
+//
+// Per-wave shared memory of the bucket-scope quantizer.
+struct BucketWave {
+  alignas(16) double psum[8][64];   // [block][lane]: the lane's sum of its 4 squares (fp64 chain in coordinate order)
+  float norm[16];       // [8*half + block] of the current octet
+  float inv[16];
+  float pnorm[16];      // the previous message's norms of the same buckets
+};
+
+// Sums of squares of the 16 buckets of one octet -> norm, inv (shared memory) and the octet's norm trailer.
+// Lane L finishes bucket q = L/4 (block q/2, half q%2): it adds 8 consecutive lane sums by the in-order binary
+// tree, then the four lanes of the quad combine (neighbour, then pair), which continues the same tree.
+template <bool FAST>
+__device__ __forceinline__ void bucket_norms(const Dev &a, const LayerMeta &m, long long O, const float *__restrict__ v,
+                                             float *trailer, const float *prev_trailer, BucketWave &bw, int i) {
+#pragma unroll
+  for (int bb = 0; bb < 8; ++bb) {
+    const long long e = (O * 8 + bb) * kBlockCoords + 4 * i;
+    float x[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (FAST) {
+      const v4f q = *reinterpret_cast<const __attribute__((address_space(1))) v4f *>(as_global(v) + e);
+      x[0] = q.x; x[1] = q.y; x[2] = q.z; x[3] = q.w;
+    } else if (e < m.d) {
+      load4(v, e, m.d, x);
+    }
+    double acc = 0.0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const double xd = (double)x[j];
+      acc = __builtin_fma(xd, xd, acc);   // the product is exact in fp64, so this equals acc + xd*xd
+    }
+    bw.psum[bb][i] = acc;
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  const int q = i >> 2, r = i & 3;
+  const int bb = q >> 1, hf = q & 1;
+  const double *p = &bw.psum[bb][hf * 32 + r * 8];
+  double s = ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+  s = s + __shfl_xor(s, 1, 64);
+  s = s + __shfl_xor(s, 2, 64);
+  const double lim = (double)kFltMax * (double)kFltMax;
+  const bool finite = (s >= 0.0) && (s <= lim);
+  const float n = finite ? sqrt_floor(s) : 0.0f;
+  const float rinv = rcp_floor(n);
+  if (!finite) atomicOr(a.status, 1u);
+  if (r == 0) {
+    bw.norm[8 * hf + bb] = n;
+    bw.inv[8 * hf + bb] = rinv;
+    trailer[8 * hf + bb] = n;
+  }
+  if (i < 16) bw.pnorm[i] = prev_trailer ? prev_trailer[i] : 0.0f;
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// quantize_block with the block's own (bucket) norm, reciprocal and previous norm; the tables hold plain levels.
+template <int C1>
+__device__ __forceinline__ void quantize_block_b(const float (&x)[4], const unsigned int (&o)[4], int half, float inv,
+                                                 float norm, float pnorm, const unsigned char *lut, const float4 *tab,
+                                                 const float *tprev, unsigned int (&D)[C1],
+                                                 const unsigned int (&Dp)[C1], float &acc) {
+  float u[4];
+  int tau[4];
+  float4 lv[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    u[j] = __builtin_amdgcn_fmed3f(fabsf(x[j]) * inv, 0.0f, 1.0f);
+    tau[j] = lut[f2u(u[j]) >> 20];
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) lv[j] = tab[tau[j]];
+  if (__ballot((lv[0].z <= u[0]) | (lv[1].z <= u[1]) | (lv[2].z <= u[2]) | (lv[3].z <= u[3])) != 0ull) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      while (lv[j].z <= u[j]) { ++tau[j]; lv[j] = tab[tau[j]]; }
+  }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int jl = 4 * half + j;
+    const unsigned int w16 = half ? (o[j] >> 16) : (o[j] & 0xFFFFu);
+    const float xi = (u[j] - lv[j].x) * lv[j].y;
+    const bool up = (float)w16 < __builtin_fmaf(xi, 65536.0f, -0.5f);
+    const unsigned int h = (unsigned int)tau[j] + (up ? 1u : 0u);
+    const float mag = norm * (up ? lv[j].z : lv[j].x);
+    const float cur = __builtin_copysignf(mag, x[j]);
+    insert_code<C1>(D, (h << 1) | (f2u(x[j]) >> 31), 24 + jl);
+    const float pl = lds_float_at(tprev, extract_off<C1>(Dp, jl));   // +-level of the previous code
+    const float pv = pnorm * pl;
+    const float diff = cur - pv;
+    acc = __builtin_fmaf(diff, diff, acc);
+  }
+}
+
+template <int C1, bool FAST>
+__device__ __forceinline__ void quantize_octet_b(const Dev &a, const LayerMeta &m, int l, int k, long long O,
+                                                 const float *__restrict__ v, unsigned char *body,
+                                                 const unsigned char *prevbody, const unsigned char *lut,
+                                                 const float4 *tab, const float *tprev, BucketWave &bw, int i,
+                                                 float &acc) {
+  constexpr long long OS = 256 * C1 + 64;   // bytes per octet: codes, then the 16 bucket norms
+  const unsigned int k0 = (unsigned int)a.seed, k1 = (unsigned int)(a.seed >> 32);
+  unsigned char *oct = body + O * OS;
+  const unsigned char *poct = prevbody ? prevbody + O * OS : nullptr;
+  bucket_norms<FAST>(a, m, O, v, reinterpret_cast<float *>(oct + 256 * C1),
+                     poct ? reinterpret_cast<const float *>(poct + 256 * C1) : nullptr, bw, i);
+  unsigned int D[C1], Dp[C1];
+#pragma unroll
+  for (int r = 0; r < C1; ++r) { D[r] = 0u; Dp[r] = 0u; }
+  if (poct != nullptr) load_record<C1>(poct, i, Dp);
+  float xa[4] = {0.0f, 0.0f, 0.0f, 0.0f}, xb[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  if (FAST) {
+    load_block_fast(v, O * 8, i, xa);
+    load_block_fast(v, O * 8 + 1, i, xb);
+  }
+  const int hf8 = (i >> 5) * 8;
+#pragma unroll 1
+  for (int pp = 0; pp < 4; ++pp) {
+    const long long B0 = O * 8 + 2 * pp;
+    shift_out_pair<C1>(D);
+    if (FAST || B0 < m.nblk) {
+      float x0[4], x1[4];
+      if (FAST) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { x0[j] = xa[j]; x1[j] = xb[j]; }
+        if (pp < 3) {
+          load_block_fast(v, B0 + 2, i, xa);
+          load_block_fast(v, B0 + 3, i, xb);
+        }
+      } else {
+        load4(v, B0 * kBlockCoords + 4 * i, m.d, x0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) x1[j] = 0.0f;
+        if (B0 + 1 < m.nblk) load4(v, (B0 + 1) * kBlockCoords + 4 * i, m.d, x1);
+      }
+      const float2 nn = *reinterpret_cast<const float2 *>(&bw.norm[hf8 + 2 * pp]);
+      const float2 ii = *reinterpret_cast<const float2 *>(&bw.inv[hf8 + 2 * pp]);
+      const float2 pn = *reinterpret_cast<const float2 *>(&bw.pnorm[hf8 + 2 * pp]);
+      unsigned int o[4];
+      philox4x32_10((unsigned int)((B0 >> 1) * 64 + i), (unsigned int)l, a.round, (unsigned int)k, k0, k1, o);
+      quantize_block_b<C1>(x0, o, 0, ii.x, nn.x, pn.x, lut, tab, tprev, D, Dp, acc);
+      quantize_block_b<C1>(x1, o, 1, ii.y, nn.y, pn.y, lut, tab, tprev, D, Dp, acc);
+    }
+    shift_out_pair<C1>(Dp);
+  }
+  store_record<C1>(oct, i, D);
+}
+
+template <int C1>
+__global__ void __launch_bounds__(kThreads) k_quantize_b(Dev a) {
+  __shared__ unsigned char lut[kLutSize];
+  __shared__ float4 tab[kMaxPoints];
+  __shared__ float tprev[2 * kMaxPoints];   // +-level of the previous message, indexed by code = sign | h << 1
+  __shared__ double red[kThreads];
+  __shared__ BucketWave bws[kThreads / 64];
+  const int2 tile = a.tiles[blockIdx.x];
+  const int l = tile.x;
+  const int k = a.node0 + blockIdx.y;
+  const LayerMeta m = a.meta[l];
+  if (m.planes != C1) return;
+  const int t = threadIdx.x;
+  const float *lev = a.lev + (size_t)m.type * kMaxPoints;
+  const float *rg = a.rgap + (size_t)m.type * kMaxPoints;
+  reinterpret_cast<unsigned int *>(lut)[t] = reinterpret_cast<const unsigned int *>(a.lut + (size_t)m.type * kLutSize)[t];
+  const unsigned char *prevmsg = (a.prev != nullptr) ? a.prev[k] : nullptr;
+  if (t < m.S) {
+    const float lj = lev[t];
+    const float ln = (t + 1 < m.S) ? lev[t + 1] : __builtin_inff();
+    tab[t] = make_float4(lj, (t + 1 < m.S) ? rg[t] : 0.0f, ln, 0.0f);
+  }
+  if (tile.y == 0) {   // header of this layer: the norm entry is unused under bucket scope
+    float *h = reinterpret_cast<float *>(a.msg[k] + m.hdr_off);
+    for (int j = t; j <= m.S; j += kThreads) h[j] = (j == 0) ? 0.0f : lev[j - 1];
+  }
+  for (int c = t; c < (1 << m.planes); c += kThreads) {
+    float pl = 0.0f;
+    if (prevmsg) {
+      const float *hp = reinterpret_cast<const float *>(prevmsg + m.hdr_off);
+      const float lvl = hp[1 + min(c >> 1, m.S - 1)];
+      pl = (c & 1) ? -lvl : lvl;
+    }
+    tprev[c] = pl;
+  }
+  __syncthreads();
+  const int w = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int i = t & 63;
+  const float *__restrict__ v = a.grad[(size_t)k * a.L + l];
+  unsigned char *body = a.msg[k] + m.body_off;
+  const unsigned char *prevbody = prevmsg ? prevmsg + m.body_off : nullptr;
+  const long long noct = (m.nblk + 7) >> 3;
+  float acc = 0.0f;
+  for (int oo = 0; oo < 2; ++oo) {
+    const long long O = (long long)tile.y * 8 + w * 2 + oo;
+    if (O >= noct) break;
+    if ((O + 1) * 2048 <= m.d)
+      quantize_octet_b<C1, true>(a, m, l, k, O, v, body, prevbody, lut, tab, tprev, bws[w], i, acc);
+    else
+      quantize_octet_b<C1, false>(a, m, l, k, O, v, body, prevbody, lut, tab, tprev, bws[w], i, acc);
+  }
+  const double total = block_tree((double)acc, red);
+  if (t == 0) a.dpartial[(size_t)k * a.G + blockIdx.x] = total;
+}
+
 // delta_k: slot j takes the node's tiles j, j+256, ... (all layers, in order), then the halving tree.
 __global__ void __launch_bounds__(kThreads) k_delta_finalize(Dev a) {
   __shared__ double red[kThreads];
@@ -469,7 +704,8 @@ __global__ void __launch_bounds__(kThreads) k_delta_finalize(Dev a) {
     const LayerMeta m = a.meta[a.empty_layers[q]];
     float *h = reinterpret_cast<float *>(a.msg[k] + m.hdr_off);
     const float *lev = a.lev + (size_t)m.type * kMaxPoints;
-    for (int j = threadIdx.x; j <= m.S; j += kThreads) h[j] = (j == 0) ? 0.0f : lev[j - 1];
+    const float n0 = (a.scope == kScopeBucket) ? 0.0f : a.norm[(size_t)k * a.L + a.empty_layers[q]];
+    for (int j = threadIdx.x; j <= m.S; j += kThreads) h[j] = (j == 0) ? n0 : lev[j - 1];
   }
 }
 
@@ -528,26 +764,44 @@ __global__ void __launch_bounds__(kThreads) k_alt_finalize(Dev a) {
 // One octet per wave at a time: 32 running sums per lane, K records of C1 words, then 8 blocks of state.
 // Under kDecodeUpdateAlt the lane also rebuilds X_t = X_1 + eta_prev * Y_t and adds (X_t - X_{t+1})^2 to its
 // slot's fp32 fused chain (coordinates in increasing order, as in the quantizer's distance term).
-template <int C1, int MODE, bool FAST>
+// The 8 bucket norms a lane needs from one octet's trailer (its half's, blocks 0..7): two 128-bit loads.
+__device__ __forceinline__ void load_bucket_norms(const unsigned char *trailer, int i, float (&n)[8]) {
+  const auto *g = reinterpret_cast<const __attribute__((address_space(1))) v4f *>(as_global(trailer)) + 2 * (i >> 5);
+  const v4f a = g[0], b = g[1];
+  n[0] = a.x; n[1] = a.y; n[2] = a.z; n[3] = a.w; n[4] = b.x; n[5] = b.y; n[6] = b.z; n[7] = b.w;
+}
+
+template <int C1, int MODE, bool FAST, bool BUCKET>
 __device__ __forceinline__ void decode_octet(const Dev &a, const LayerMeta &m, int l, long long O, const float *T, int i,
                                              float eta, float gamma, float eta_prev, float &accx) {
   constexpr int TS = 1 << C1;   // table entries per node, indexed by code = sign | h << 1
-  const long long boff = m.body_off + O * 256 * C1;
+  constexpr long long OS = 256 * C1 + (BUCKET ? 64 : 0);   // bytes per octet (bucket scope: codes + 16 norms)
+  const long long boff = m.body_off + O * OS;
   float sum[32];
   unsigned int Dc[C1], Dn[C1];
+  float nc[8], nn[8];   // bucket scope: this node's and the next node's bucket norms for the lane's 8 blocks
   load_record<C1>(a.msgs_in[0] + boff, i, Dc);
+  if (BUCKET) load_bucket_norms(a.msgs_in[0] + boff + 256 * C1, i, nc);
   for (int k = 0; k < a.K; ++k) {
 #pragma unroll
     for (int r = 0; r < C1; ++r) Dn[r] = 0u;
-    if (k + 1 < a.K) load_record<C1>(a.msgs_in[k + 1] + boff, i, Dn);
+    if (k + 1 < a.K) {
+      load_record<C1>(a.msgs_in[k + 1] + boff, i, Dn);
+      if (BUCKET) load_bucket_norms(a.msgs_in[k + 1] + boff + 256 * C1, i, nn);
+    }
     const float *Tk = T + k * TS;
 #pragma unroll
     for (int jj = 0; jj < 32; ++jj) {
-      const float val = lds_float_at(Tk, extract_off<C1>(Dc, jj));
+      float val = lds_float_at(Tk, extract_off<C1>(Dc, jj));   // layer / vector scope: +-norm_k * level
+      if (BUCKET) val = nc[jj >> 2] * val;                     // bucket scope: the table holds +-level
       sum[jj] = (k == 0) ? val : sum[jj] + val;
     }
 #pragma unroll
     for (int r = 0; r < C1; ++r) Dc[r] = Dn[r];
+    if (BUCKET) {
+#pragma unroll
+      for (int b = 0; b < 8; ++b) nc[b] = nn[b];
+    }
   }
 #pragma unroll
   for (int bb = 0; bb < 8; ++bb) {
@@ -589,7 +843,7 @@ __device__ __forceinline__ void decode_octet(const Dev &a, const LayerMeta &m, i
   }
 }
 
-template <int C1, int MODE>
+template <int C1, int MODE, bool BUCKET>
 __device__ __forceinline__ void decode_tile(const Dev &a, const LayerMeta &m, int l, int chunk, const float *T,
                                             double *red) {
   const int t = threadIdx.x;
@@ -602,8 +856,8 @@ __device__ __forceinline__ void decode_tile(const Dev &a, const LayerMeta &m, in
   for (int oo = 0; oo < 2; ++oo) {
     const long long O = (long long)chunk * 8 + w * 2 + oo;
     if (O >= noct) break;
-    if ((O + 1) * 2048 <= m.d) decode_octet<C1, MODE, true>(a, m, l, O, T, i, eta, gamma, eta_prev, accx);
-    else decode_octet<C1, MODE, false>(a, m, l, O, T, i, eta, gamma, eta_prev, accx);
+    if ((O + 1) * 2048 <= m.d) decode_octet<C1, MODE, true, BUCKET>(a, m, l, O, T, i, eta, gamma, eta_prev, accx);
+    else decode_octet<C1, MODE, false, BUCKET>(a, m, l, O, T, i, eta, gamma, eta_prev, accx);
   }
   if (MODE == kDecodeUpdateAlt) {
     const double total = block_tree((double)accx, red);
@@ -611,9 +865,9 @@ __device__ __forceinline__ void decode_tile(const Dev &a, const LayerMeta &m, in
   }
 }
 
-template <int C1, int MODE>
+template <int C1, int MODE, bool BUCKET>
 __global__ void __launch_bounds__(kThreads) k_decode(Dev a) {
-  extern __shared__ float T[];   // [K][2^C1]: +-norm_k * level_h of this layer, from the K message headers
+  extern __shared__ float T[];   // [K][2^C1]: +-norm_k * level_h (bucket scope: +-level_h) from the K message headers
   __shared__ double red[MODE == kDecodeUpdateAlt ? kThreads : 1];
   const int2 tile = a.tiles[blockIdx.x];
   const int l = tile.x;
@@ -623,11 +877,12 @@ __global__ void __launch_bounds__(kThreads) k_decode(Dev a) {
   for (int idx = threadIdx.x; idx < a.K * TS; idx += kThreads) {
     const int k = idx / TS, c = idx - k * TS;
     const float *hp = reinterpret_cast<const float *>(a.msgs_in[k] + m.hdr_off);
-    const float mag = hp[0] * hp[1 + min(c >> 1, m.S - 1)];
+    const float lvl = hp[1 + min(c >> 1, m.S - 1)];
+    const float mag = BUCKET ? lvl : hp[0] * lvl;
     T[idx] = (c & 1) ? -mag : mag;
   }
   __syncthreads();
-  decode_tile<C1, MODE>(a, m, l, tile.y, T, red);
+  decode_tile<C1, MODE, BUCKET>(a, m, l, tile.y, T, red);
 }
 
 // ------------------------------------------------------------------------------------------------ level fit
@@ -683,6 +938,120 @@ __global__ void __launch_bounds__(kThreads) k_fit_pool(Dev a) {
     int j = (int)(f2u(uc) >> 20) - kGridBase;
     j = max(0, min(j, kGridPoints - 1));
     atomicAdd(&W[j], wfix * (unsigned long long)c);
+  }
+}
+
+// ---- level fit under bucket scope.  Only the sampled blocks (0, 4, 8, ... of a layer, i.e. blocks 0 and 4 of every
+// octet) are read: a quarter of the gradient per pass.
+// Sum of squares of the lane's bucket (half of block B) by the in-order binary tree, valid in all its 32 lanes.
+__device__ __forceinline__ double sampled_bucket_sum(const LayerMeta &m, const float *__restrict__ v, long long B, int i,
+                                                     float (&x)[4]) {
+  const long long e = B * kBlockCoords + 4 * i;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) x[j] = 0.0f;
+  if (e < m.d) load4(v, e, m.d, x);
+  double s = 0.0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const double xd = (double)x[j];
+    s = __builtin_fma(xd, xd, s);
+  }
+#pragma unroll
+  for (int w = 1; w < 32; w *= 2) s = s + __shfl_xor(s, w, 64);
+  return s;
+}
+
+// Largest sampled bucket sum of every (node, layer), as the bit pattern of a non-negative double (ordered like an
+// integer); a sum that is not a finite number in range leaves +infinity.  a.sumsq must be zero on entry.
+__global__ void __launch_bounds__(kThreads) k_bucket_max(Dev a) {
+  __shared__ unsigned long long wmax[kThreads / 64];
+  const int4 st = a.stiles[blockIdx.x];
+  const int l = st.x, k = blockIdx.y;
+  const LayerMeta m = a.meta[l];
+  const float *__restrict__ v = a.grad[(size_t)k * a.L + l];
+  const int t = threadIdx.x, w = t >> 6, i = t & 63;
+  const double lim = (double)kFltMax * (double)kFltMax;
+  unsigned long long best = 0ull;
+  for (int cc = 0; cc < st.z; ++cc)
+    for (int oo = 0; oo < 2; ++oo) {
+      const long long O = (long long)(st.y + cc) * 8 + w * 2 + oo;
+#pragma unroll
+      for (int bb = 0; bb < 8; bb += 4) {
+        const long long B = O * 8 + bb;
+        if (B >= m.nblk) continue;
+        float x[4];
+        const double s = sampled_bucket_sum(m, v, B, i, x);
+        const bool finite = (s >= 0.0) && (s <= lim);
+        const unsigned long long bits = finite ? (unsigned long long)__double_as_longlong(s) : 0x7FF0000000000000ull;
+        best = bits > best ? bits : best;
+      }
+    }
+  // both halves of the wave, then the four waves
+  const unsigned long long other = __shfl_xor(best, 32, 64);
+  best = other > best ? other : best;
+  if (i == 0) wmax[w] = best;
+  __syncthreads();
+  if (t == 0) {
+    for (int q = 1; q < kThreads / 64; ++q) best = wmax[q] > best ? wmax[q] : best;
+    if (best) atomicMax(reinterpret_cast<unsigned long long *>(a.sumsq) + ((size_t)k * a.L + l), best);
+  }
+}
+
+// Weighted histogram of the normalised magnitudes of the sampled coordinates of every (node, layer) on the 257-point
+// grid: weight floor(bucket sum * 2^(23 - exponent of the type)), integer adds, kept per (node, layer) in the first
+// 257 64-bit words of its histogram area.
+__global__ void __launch_bounds__(kThreads) k_bucket_hist(Dev a) {
+  __shared__ unsigned long long lh[kGridPoints];
+  const int4 st = a.stiles[blockIdx.x];
+  const int l = st.x, k = blockIdx.y;
+  const LayerMeta m = a.meta[l];
+  const int ex = a.type_exp[m.type];
+  if (ex == kTypeSkip) return;
+  const float *__restrict__ v = a.grad[(size_t)k * a.L + l];
+  const int t = threadIdx.x, w = t >> 6, i = t & 63;
+  for (int j = t; j < kGridPoints; j += kThreads) lh[j] = 0ull;
+  __syncthreads();
+  for (int cc = 0; cc < st.z; ++cc)
+    for (int oo = 0; oo < 2; ++oo) {
+      const long long O = (long long)(st.y + cc) * 8 + w * 2 + oo;
+#pragma unroll
+      for (int bb = 0; bb < 8; bb += 4) {
+        const long long B = O * 8 + bb;
+        if (B >= m.nblk) continue;
+        float x[4];
+        const double s = sampled_bucket_sum(m, v, B, i, x);
+        const unsigned long long wfix = (unsigned long long)floor(ldexp(s, 23 - ex));
+        const float inv = rcp_floor(sqrt_floor(s));
+        if (wfix == 0ull || inv == 0.0f) continue;
+        const long long e = B * kBlockCoords + 4 * i;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if (e + j >= m.d || ((f2u(x[j]) & 0x7FFFFFFFu) >> 20) == 0u) continue;
+          const float uc = fminf(fabsf(x[j]) * inv, 1.0f);
+          int g = (int)(f2u(uc) >> 20) - kGridBase;
+          g = max(0, min(g, kGridPoints - 1));
+          atomicAdd(&lh[g], wfix);
+        }
+      }
+    }
+  __syncthreads();
+  unsigned long long *gh = reinterpret_cast<unsigned long long *>(a.hist + ((size_t)k * a.L + l) * kHistBins);
+  for (int j = t; j < kGridPoints; j += kThreads) {
+    const unsigned long long c = lh[j];
+    if (c) atomicAdd(&gh[j], c);
+  }
+}
+
+// Pool the per-(node, layer) grid histograms of a type.
+__global__ void __launch_bounds__(kThreads) k_fit_pool_b(Dev a) {
+  const int l = blockIdx.x, k = blockIdx.y;
+  const LayerMeta m = a.meta[l];
+  if (a.type_exp[m.type] == kTypeSkip) return;
+  const unsigned long long *gh = reinterpret_cast<const unsigned long long *>(a.hist + ((size_t)k * a.L + l) * kHistBins);
+  unsigned long long *W = a.pooled + (size_t)m.type * kGridPoints;
+  for (int j = threadIdx.x; j < kGridPoints; j += kThreads) {
+    const unsigned long long c = gh[j];
+    if (c) atomicAdd(&W[j], c);
   }
 }
 
@@ -877,6 +1246,17 @@ hipError_t launch_norm_finalize(const Dev &a, hipStream_t s) {
 hipError_t launch_quantize(const Dev &a, unsigned int planes_mask, hipStream_t s) {
   if (a.G == 0 || a.nnodes == 0) return hipSuccess;
   const dim3 grid(a.G, a.nnodes), block(kThreads);
+  if (a.scope == kScopeBucket) {
+    if (planes_mask & (1u << 2)) hipLaunchKernelGGL(k_quantize_b<2>, grid, block, 0, s, a);
+    if (planes_mask & (1u << 3)) hipLaunchKernelGGL(k_quantize_b<3>, grid, block, 0, s, a);
+    if (planes_mask & (1u << 4)) hipLaunchKernelGGL(k_quantize_b<4>, grid, block, 0, s, a);
+    if (planes_mask & (1u << 5)) hipLaunchKernelGGL(k_quantize_b<5>, grid, block, 0, s, a);
+    if (planes_mask & (1u << 6)) hipLaunchKernelGGL(k_quantize_b<6>, grid, block, 0, s, a);
+    if (planes_mask & (1u << 7)) hipLaunchKernelGGL(k_quantize_b<7>, grid, block, 0, s, a);
+    if (planes_mask & (1u << 8)) hipLaunchKernelGGL(k_quantize_b<8>, grid, block, 0, s, a);
+    if (planes_mask & (1u << 9)) hipLaunchKernelGGL(k_quantize_b<9>, grid, block, 0, s, a);
+    return hipGetLastError();
+  }
   if (planes_mask & (1u << 2)) hipLaunchKernelGGL(k_quantize<2>, grid, block, 0, s, a);
   if (planes_mask & (1u << 3)) hipLaunchKernelGGL(k_quantize<3>, grid, block, 0, s, a);
   if (planes_mask & (1u << 4)) hipLaunchKernelGGL(k_quantize<4>, grid, block, 0, s, a);
@@ -893,17 +1273,28 @@ hipError_t launch_delta_finalize(const Dev &a, hipStream_t s) {
   return hipGetLastError();
 }
 
+hipError_t launch_norm_vector(const Dev &a, hipStream_t s) {
+  hipLaunchKernelGGL(k_norm_vector, dim3(a.nnodes), dim3(kThreads), 0, s, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_step_scalars(const Dev &a, hipStream_t s) {
   hipLaunchKernelGGL(k_step_scalars, dim3(1), dim3(64), 0, s, a);
   return hipGetLastError();
 }
 
+template <int C1, bool BUCKET>
+static void launch_decode_scope(const Dev &a, int mode, size_t lds_bytes, hipStream_t s) {
+  const dim3 grid(a.G), block(kThreads);
+  if (mode == kDecodeUpdateAlt) hipLaunchKernelGGL((k_decode<C1, kDecodeUpdateAlt, BUCKET>), grid, block, lds_bytes, s, a);
+  else if (mode == kDecodeUpdate) hipLaunchKernelGGL((k_decode<C1, kDecodeUpdate, BUCKET>), grid, block, lds_bytes, s, a);
+  else hipLaunchKernelGGL((k_decode<C1, kDecodeMean, BUCKET>), grid, block, lds_bytes, s, a);
+}
+
 template <int C1>
 static void launch_decode_width(const Dev &a, int mode, size_t lds_bytes, hipStream_t s) {
-  const dim3 grid(a.G), block(kThreads);
-  if (mode == kDecodeUpdateAlt) hipLaunchKernelGGL((k_decode<C1, kDecodeUpdateAlt>), grid, block, lds_bytes, s, a);
-  else if (mode == kDecodeUpdate) hipLaunchKernelGGL((k_decode<C1, kDecodeUpdate>), grid, block, lds_bytes, s, a);
-  else hipLaunchKernelGGL((k_decode<C1, kDecodeMean>), grid, block, lds_bytes, s, a);
+  if (a.scope == kScopeBucket) launch_decode_scope<C1, true>(a, mode, lds_bytes, s);
+  else launch_decode_scope<C1, false>(a, mode, lds_bytes, s);
 }
 
 hipError_t launch_decode(const Dev &a, int mode, unsigned int planes_mask, hipStream_t s) {
@@ -926,6 +1317,19 @@ hipError_t launch_alt_scalars(const Dev &a, hipStream_t s) {
 
 hipError_t launch_alt_finalize(const Dev &a, hipStream_t s) {
   hipLaunchKernelGGL(k_alt_finalize, dim3(1), dim3(kThreads), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_bucket_max(const Dev &a, hipStream_t s) {
+  if (a.GS == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_bucket_max, dim3(a.GS, a.K), dim3(kThreads), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_bucket_hist(const Dev &a, hipStream_t s) {
+  if (a.GS == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_bucket_hist, dim3(a.GS, a.K), dim3(kThreads), 0, s, a);
+  hipLaunchKernelGGL(k_fit_pool_b, dim3(a.L, a.K), dim3(kThreads), 0, s, a);
   return hipGetLastError();
 }
 

@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libqoda.so")
 
 OK, EINVAL, ENOMEM, EHIP, ENONFINITE = 0, -1, -2, -3, -4
 BUF_SUMSQ, BUF_NORM, BUF_INV, BUF_DELTA, BUF_HIST, BUF_POOLED = range(6)
-NUM_KERNELS = 18
+NUM_KERNELS = 21
+SCOPE_LAYER, SCOPE_VECTOR, SCOPE_BUCKET = 0, 1, 2
 HIST_BINS, GRID_POINTS = 2048, 257
 
 _lib = None
@@ -32,7 +33,7 @@ class QodaError(RuntimeError):
 class _Config(C.Structure):
     _fields_ = [("num_layers", C.c_int32), ("layer_size", C.POINTER(C.c_int64)), ("layer_type", C.POINTER(C.c_int32)),
                 ("num_types", C.c_int32), ("type_points", C.POINTER(C.c_int32)), ("num_nodes", C.c_int32),
-                ("norm_kind", C.c_int32), ("seed", C.c_uint64)]
+                ("norm_kind", C.c_int32), ("seed", C.c_uint64), ("norm_scope", C.c_int32)]
 
 
 class _State(C.Structure):
@@ -116,15 +117,16 @@ class Context:
     """One model: layer sizes, layer -> type map, grid points per type, K nodes, generator seed."""
 
     def __init__(self, layer_size: Sequence[int], layer_type: Sequence[int], type_points: Sequence[int],
-                 num_nodes: int, seed: int):
+                 num_nodes: int, seed: int, norm_scope: int = SCOPE_LAYER):
         self._lib = load()
+        self.norm_scope = int(norm_scope)
         self.layer_size = np.ascontiguousarray(layer_size, dtype=np.int64)
         self.layer_type = np.ascontiguousarray(layer_type, dtype=np.int32)
         self.type_points = np.ascontiguousarray(type_points, dtype=np.int32)
         self.L, self.M, self.K = int(self.layer_size.size), int(self.type_points.size), int(num_nodes)
         cfg = _Config(self.L, self.layer_size.ctypes.data_as(C.POINTER(C.c_int64)),
                       self.layer_type.ctypes.data_as(C.POINTER(C.c_int32)), self.M,
-                      self.type_points.ctypes.data_as(C.POINTER(C.c_int32)), self.K, 2, seed)
+                      self.type_points.ctypes.data_as(C.POINTER(C.c_int32)), self.K, 2, seed, self.norm_scope)
         h = C.c_void_p()
         rc = self._lib.qoda_create(C.byref(cfg), C.byref(h))
         if rc != OK:

@@ -17,10 +17,11 @@ class GpuModel:
     """Buffers for one model on the GPU: K nodes' gradients (one flat buffer per node, layers 256-byte aligned),
     two message buffers per node, and the solver state."""
 
-    def __init__(self, sizes: Sequence[int], layer_type: Sequence[int], type_points: Sequence[int], K: int, seed: int):
+    def __init__(self, sizes: Sequence[int], layer_type: Sequence[int], type_points: Sequence[int], K: int, seed: int,
+                 norm_scope: int = 0):
         self.sizes = [int(s) for s in sizes]
         self.L, self.K = len(self.sizes), K
-        self.ctx = qoda.Context(self.sizes, layer_type, type_points, K, seed)
+        self.ctx = qoda.Context(self.sizes, layer_type, type_points, K, seed, norm_scope=norm_scope)
         self.off, self.flat_len = workloads.padded_offsets(self.sizes)
         self.grad_flat = [torch.zeros(self.flat_len, dtype=torch.float32, device=dev()) for _ in range(K)]
         self.mbytes = self.ctx.message_bytes()

@@ -1,0 +1,160 @@
+"""GPU parity under the other norm scopes (whole vector; buckets of 128, Sec. 7): packed messages including the
+bucket norms, distance terms, fitted levels and pooled weights bit for bit; aggregated and updated values
+identical (bar: 1e-6 relative)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import helpers  # noqa: E402
+from paper_2505_14371_amd import qoda, workloads  # noqa: E402
+
+VECTOR, BUCKET = qoda.SCOPE_VECTOR, qoda.SCOPE_BUCKET
+RAGGED = [1, 3, 127, 128, 129, 255, 256, 257, 1023, 2047, 2048, 2049, 4100, 16383, 16384, 16385, 40001, 0, 16384 * 3 + 7]
+
+
+def gm(*a, **k):
+    if not torch.cuda.is_available():
+        pytest.fail("a GPU test was selected but no GPU is visible")
+    import gpu_harness
+
+    return gpu_harness.GpuModel(*a, **k)
+
+
+def irregular_levels(S, seed):
+    rng = np.random.default_rng(seed)
+    inner = np.sort(rng.uniform(0.0, 1.0, S - 2) ** 3).astype(np.float32)
+    lev = np.concatenate([[0.0], inner, [1.0]]).astype(np.float32)
+    for j in range(1, S):
+        if not lev[j] > lev[j - 1]:
+            lev[j] = np.nextafter(lev[j - 1], np.float32(2.0))
+    lev[-1] = 1.0
+    return lev
+
+
+@pytest.mark.parametrize("scope", [VECTOR, BUCKET])
+@pytest.mark.parametrize("S", [2, 4, 5, 8, 16, 17, 256])
+def test_messages_match_for_every_code_width(oracle, scope, S):
+    sizes = RAGGED
+    L, K = len(sizes), 2
+    m = gm(sizes, [0] * L, [S], K, seed=21, norm_scope=scope)
+    lev = irregular_levels(S, S) if S > 2 else helpers.uniform_levels(2)
+    m.ctx.set_levels(0, lev)
+    rng = np.random.default_rng(S)
+    grads = [[(rng.standard_t(3, s) * 10.0 ** rng.uniform(-6, 3)).astype(np.float32) for s in sizes] for _ in range(K)]
+    grads[1][4][:] = 0.0
+    grads[0][5][:] = np.float32(1e-30)
+    grads[0][9][100:228] = 0.0                                   # one all-zero bucket inside a layer
+    m.set_grads(grads)
+    m.quantize_all(1)
+    msgs = m.messages()
+    delta = m.ctx.read_buffer(qoda.BUF_DELTA)
+    assert m.ctx.status() == qoda.OK
+    assert m.mbytes == oracle.message_bytes(sizes, [S] * L, scope)
+    for k in range(K):
+        want, _, dl, st = oracle.quantize(sizes, [S] * L, [lev] * L, grads[k], 21, 1, k, scope=scope)
+        assert st == 0
+        assert np.array_equal(msgs[k], want), (k, int(np.argmax(msgs[k] != want)))
+        assert delta[k] == dl
+    m.aggregate()
+    mean = m.layers(m.mean)
+    want = oracle.dequant_aggregate(sizes, [S] * L, msgs, scope=scope)
+    for l in range(L):
+        assert np.array_equal(mean[l], want[l]), l
+
+
+@pytest.mark.parametrize("scope", [VECTOR, BUCKET])
+@pytest.mark.parametrize("alt", [False, True])
+def test_rounds_with_fit_previous_message_and_update(oracle, scope, alt):
+    w = workloads.mini("txl", max_layer=50000, max_layers=8)
+    sizes = list(w.sizes) + [16384 * 2 + 300, 0, 77]
+    L, K, S = len(sizes), 3, 8
+    types = [l % 3 for l in range(L)]
+    q = 0.25
+    rng = np.random.default_rng(3)
+    x1 = [rng.standard_normal(s).astype(np.float32) for s in sizes]
+    m = gm(sizes, types, [S, S, S], K, seed=4, norm_scope=scope)
+    m.set_layers(m.x1, x1)
+    levels = [helpers.uniform_levels(S) for _ in range(3)]
+    y = [np.zeros(s, np.float32) for s in sizes]
+    prev = [None] * K
+    acc, lam, mu, eta = 0.0, 0.0, 0.0, np.float32(1.0)
+    for t in range(1, 4):
+        grads = [[(rng.standard_t(4, s) * 10.0 ** rng.uniform(-3, 1)).astype(np.float32) for s in sizes] for _ in range(K)]
+        m.set_grads(grads)
+        m.fit(t)
+        flat = [grads[k][l] for k in range(K) for l in range(L)]
+        levels, _, pooled, st = oracle.fit_levels(sizes, types, [S] * 3, K, flat, levels, scope=scope)
+        assert st == 0
+        assert np.array_equal(m.ctx.read_buffer(qoda.BUF_POOLED), pooled), t
+        for ty in range(3):
+            assert np.array_equal(m.ctx.get_levels(ty), levels[ty]), (t, ty)
+        if alt:
+            m.quantize_all_alt(t)
+        else:
+            m.quantize_all(t)
+        msgs = m.messages()
+        delta = m.ctx.read_buffer(qoda.BUF_DELTA)
+        lev_l = [levels[types[l]] for l in range(L)]
+        want_msgs, want_delta = [], []
+        for k in range(K):
+            wm, _, dl, st = oracle.quantize(sizes, [S] * L, lev_l, grads[k], 4, t, k,
+                                            msg_prev=None if alt else prev[k], scope=scope)
+            assert np.array_equal(msgs[k], wm), (t, k)
+            assert delta[k] == dl, (t, k)
+            want_msgs.append(wm)
+            want_delta.append(dl)
+        prev = want_msgs
+        mean = oracle.dequant_aggregate(sizes, [S] * L, want_msgs, scope=scope)
+        if alt:
+            eta_prev = eta
+            eta, gamma = oracle.alt_step_size(lam, mu, q)
+            xn, xh, dx2 = oracle.oda_update_alt(sizes, mean, x1, y, eta_prev, eta, gamma)
+            lam, mu = oracle.alt_advance(want_delta, dx2, lam, mu)
+            m.step_alt(q)
+            sums = m.alt_sums.cpu().numpy()
+            assert sums[0] == lam and sums[1] == mu, t
+        else:
+            acc, eta = oracle.step_size(want_delta, acc)
+            gamma = eta
+            xn, xh = [], []
+            for l in range(L):
+                a, b = oracle.oda_update(mean[l], x1[l], y[l], eta, eta)
+                xn.append(a)
+                xh.append(b)
+            m.step()
+            assert float(m.acc.cpu()[0]) == acc
+        e = m.eta.cpu().numpy()
+        assert e[0] == eta and e[1] == gamma, t
+        gy, gxh, gxn = m.layers(m.y), m.layers(m.x_half), m.layers(m.x_next)
+        for l in range(L):
+            assert np.array_equal(gy[l], y[l]) and np.array_equal(gxh[l], xh[l]) and np.array_equal(gxn[l], xn[l]), (t, l)
+
+
+def test_per_node_calls_agree_in_bucket_scope(oracle):
+    sizes, K, S = [5000, 20000, 130], 3, 16
+    m = gm(sizes, [0, 0, 0], [S], K, seed=8, norm_scope=BUCKET)
+    rng = np.random.default_rng(1)
+    grads = [[rng.standard_normal(s).astype(np.float32) for s in sizes] for _ in range(K)]
+    m.set_grads(grads)
+    m.quantize_all(1)
+    a = m.messages()
+    da = m.ctx.read_buffer(qoda.BUF_DELTA)
+    for t in m.msg[0]:
+        t.zero_()
+    m.quantize_each(1)
+    b = m.messages()
+    assert all(np.array_equal(x, y) for x, y in zip(a, b))
+    assert np.array_equal(m.ctx.read_buffer(qoda.BUF_DELTA), da)
+
+
+def test_nonfinite_bucket_is_flagged():
+    m = gm([1000], [0], [4], 1, seed=1, norm_scope=BUCKET)
+    g = [[np.ones(1000, np.float32)]]
+    g[0][0][300] = np.inf
+    m.set_grads(g)
+    m.quantize_all(1)
+    assert m.ctx.status() == qoda.ENONFINITE
+    assert m.ctx.status() == qoda.OK
