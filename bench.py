@@ -35,7 +35,7 @@ def _library():
     return qoda
 
 
-def _cpu_baseline(w, model, K, sample_target=2.5e7):
+def _cpu_baseline(w, model, K, scope=0, sample_target=2.5e7):
     """The oracle, as it stands, single-threaded, on a bounded sample of the same data: a run of consecutive
     tensors (skipping a leading embedding-sized one) for up to 4 nodes, one full round."""
     import oracle
@@ -61,13 +61,13 @@ def _cpu_baseline(w, model, K, sample_target=2.5e7):
     t0 = time.perf_counter()
     if w.adaptive:
         flat = [grads[k][i] for k in range(Ks) for i in range(len(sizes))]
-        lev, _, _, _ = oracle.fit_levels(sizes, list(range(len(sizes))), [S] * len(sizes), Ks, flat, lev)
+        lev, _, _, _ = oracle.fit_levels(sizes, list(range(len(sizes))), [S] * len(sizes), Ks, flat, lev, scope=scope)
     msgs, deltas = [], []
     for k in range(Ks):
-        m, _, dl, _ = oracle.quantize(sizes, [S] * len(sizes), lev, grads[k], w.seed, 1, k)
+        m, _, dl, _ = oracle.quantize(sizes, [S] * len(sizes), lev, grads[k], w.seed, 1, k, scope=scope)
         msgs.append(m)
         deltas.append(dl)
-    mean = oracle.dequant_aggregate(sizes, [S] * len(sizes), msgs)
+    mean = oracle.dequant_aggregate(sizes, [S] * len(sizes), msgs, scope=scope)
     _, eta = oracle.step_size(deltas, 0.0)
     for i in range(len(sizes)):
         oracle.oda_update(mean[i], x1[i], y[i], eta, eta, want_next=False)
@@ -87,6 +87,8 @@ def main() -> int:
     ap.add_argument("--workload", default="gpt1p3b", choices=["bilinear", "microbench", "dcgan", "txl", "gpt1p3b"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--x-next", action="store_true", help="also materialise X_{t+1}")
+    ap.add_argument("--norm-scope", default="layer", choices=["layer", "vector", "bucket"],
+                    help="what one norm covers: a layer (default), the node's whole vector, or buckets of 128 entries")
     ap.add_argument("--q-hat", type=float, default=0.0,
                     help="> 0: the step sizes of eq. (Alt) with this exponent instead of eq. (general_stepsize)")
     args = ap.parse_args()
@@ -106,7 +108,9 @@ def main() -> int:
     dev = torch.device("cuda:0")
     w = workloads.get(args.workload)
     L, K, S, d = len(w.sizes), w.num_nodes, w.points, w.total
-    ctx = qoda.Context(w.sizes, list(range(L)), [S] * L, K, w.seed)
+    scope = {"layer": qoda.SCOPE_LAYER, "vector": qoda.SCOPE_VECTOR, "bucket": qoda.SCOPE_BUCKET}[args.norm_scope]
+    bucket = scope == qoda.SCOPE_BUCKET
+    ctx = qoda.Context(w.sizes, list(range(L)), [S] * L, K, w.seed, norm_scope=scope)
     off, flat_len = workloads.padded_offsets(w.sizes)
 
     def ptrs(t):
@@ -148,7 +152,7 @@ def main() -> int:
     torch.cuda.synchronize()
     warm = ctx.profile_read()
     dec = "k_decode<alt>" if alt else "k_decode<true>"
-    timed_classes = ("k_sumsq<false>", "k_sumsq<true>", "k_quantize", dec)
+    timed_classes = ("k_sumsq<false>", "k_sumsq<true>", "k_quantize", dec, "k_bucket_max", "k_bucket_hist")
     dom = max((n for n in warm if n in timed_classes), key=lambda n: warm[n][0])
     # timed region: only the dominant kernel is bracketed by events (every timed launch costs a few microseconds
     # of idle time around it, which matters for the millisecond-scale workloads)
@@ -178,8 +182,10 @@ def main() -> int:
     ctx.profile_enable(False)
 
     c1_bits = 1 + max(1, int(np.ceil(np.log2(S))))
-    body_bytes = c1_bits / 8.0 * d                    # packed code bytes per node (sign + index), no padding
+    # packed bytes per node (sign + index, plus one fp32 norm per 128 entries under bucket scope), no padding
+    body_bytes = (c1_bits / 8.0 + (4.0 / 128.0 if bucket else 0.0)) * d
     alg = {"k_sumsq<false>": 4.0 * K * d, "k_sumsq<true>": 4.0 * K * d,
+           "k_bucket_max": 1.0 * K * d, "k_bucket_hist": 1.0 * K * d,       # a quarter of the gradient each
            "k_quantize": 4.0 * K * d + (1.0 if alt else 2.0) * K * body_bytes,   # eq. (Alt) reads no previous message
            dec: float(K * body_bytes) + (20.0 if xn is not None else 16.0) * d}
     kernels = {name: {"avg_ms": ms / n, "launches": n, "from": "warm-up rounds"} for name, (ms, n) in warm.items()}
@@ -194,13 +200,17 @@ def main() -> int:
     if os.path.exists(tpath):
         try:
             # counters were collected under the main rule; eq. (Alt) reads no previous message in the quantizer
-            traffic = json.load(open(tpath)).get(args.workload + ("+alt" if alt else ""), {}).get(dom)
+            key = args.workload + ("+alt" if alt else "") + ("" if scope == qoda.SCOPE_LAYER else "+" + args.norm_scope)
+            traffic = json.load(open(tpath)).get(key, {}).get(dom)
         except Exception:
             traffic = None
 
     ms_per_step = total_ms / args.steps
     grad_bytes = 4.0 * K * d
-    alg_round = sum(alg[n] for n in (("k_sumsq<true>" if w.adaptive else "k_sumsq<false>"), "k_quantize", dec))
+    if bucket:   # the norms are computed inside the quantize pass; the fit is two quarter-data passes
+        alg_round = alg["k_quantize"] + alg[dec] + ((alg["k_bucket_max"] + alg["k_bucket_hist"]) if w.adaptive else 0.0)
+    else:
+        alg_round = sum(alg[n] for n in (("k_sumsq<true>" if w.adaptive else "k_sumsq<false>"), "k_quantize", dec))
     out = {
         "metric": "GB/s fp32 gradient through quantize+aggregate+QODA step; % of HBM peak",
         "value": grad_bytes / (ms_per_step * 1e-3) / 1e9,
@@ -209,7 +219,8 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "num_nodes": K, "coordinates": d, "tensors": L, "level_points": S,
                    "adaptive_levels": w.adaptive, "message_bytes_per_node": mbytes, "x_next": xn is not None,
-                   "step_sizes": f"eq. (Alt), q_hat={args.q_hat}" if alt else "eq. (general_stepsize)"},
+                   "step_sizes": f"eq. (Alt), q_hat={args.q_hat}" if alt else "eq. (general_stepsize)",
+                   "norm_scope": args.norm_scope},
         "hbm_peak_fraction_algorithmic": alg_round / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "algorithmic_bytes_per_step": alg_round,
         "host_wall_ms_per_step": t_host / args.steps * 1e3,
@@ -220,7 +231,7 @@ def main() -> int:
         "kernels": kernels,
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = _cpu_baseline(w, {"grad": grad, "off": off}, K)
+        out["cpu_baseline"] = _cpu_baseline(w, {"grad": grad, "off": off}, K, scope)
     print(json.dumps(out))
     return 0
 
