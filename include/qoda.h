@@ -164,6 +164,14 @@ typedef struct {
  * taken.  Errors: QODA_EINVAL for q_hat outside (0, 1/4] or below 2^-32, null sums_dev or eta_dev. */
 int qoda_step_alt(qoda_ctx *ctx, const void *const *msgs_dev, const qoda_alt_state *state, double q_hat, void *stream);
 
+/* DECODE + mean + one plain step: out[l][e] = x[l][e] - gamma * mean[l][e] (two fp32 operations), mean as in
+ * qoda_dequant_aggregate.  This is the leg that an extra-gradient method (the two-call scheme QODA is compared with in
+ * Sec. 4: X_{t+1/2} = X_t - gamma * mean of the vectors at X_t, then X_{t+1} = X_t - gamma * mean of the vectors at
+ * X_{t+1/2}) runs twice per round, each with its own quantize + exchange; the library offers it so that this baseline
+ * runs on the same kernels.  x_dev, out_dev: host [L] (may alias each other layer by layer); gamma_dev: device float. */
+int qoda_extrapolate(qoda_ctx *ctx, const void *const *msgs_dev, const float *const *x_dev, float *const *out_dev,
+                     const float *gamma_dev, void *stream);
+
 /* Read an internal device buffer into host memory (waits for `stream`); for tests and diagnostics. */
 #define QODA_BUF_SUMSQ 0  /* double[K*L]  canonical per-layer sums of squares of the last norm pass        */
 #define QODA_BUF_NORM 1   /* float [K*L]  norms                                                            */
@@ -187,7 +195,7 @@ int qoda_status(qoda_ctx *ctx, void *stream);
  *   of range.
  * qoda_copy_calibration: a plain 128-bit copy kernel of `bytes` bytes (multiple of 16; 16-byte aligned device
  *   pointers): the known-traffic kernel that hardware byte counters are scaled by. */
-#define QODA_NUM_KERNELS 21
+#define QODA_NUM_KERNELS 22
 int qoda_profile_enable(qoda_ctx *ctx, uint32_t class_mask);
 int qoda_profile_read(qoda_ctx *ctx, double *ms, int64_t *launches, void *stream);
 const char *qoda_kernel_name(int32_t id);

@@ -85,6 +85,8 @@ def lib():
         L.oracle_step_size.restype = None
         L.oracle_oda_update.argtypes = [C.c_int64, fp, fp, fp, fp, fp, C.c_float, C.c_float]
         L.oracle_oda_update.restype = None
+        L.oracle_extrapolate.argtypes = [C.c_int64, fp, fp, C.c_float, fp]
+        L.oracle_extrapolate.restype = None
         L.oracle_alt_step_size.argtypes = [C.c_double, C.c_double, C.c_double, fp, fp]
         L.oracle_alt_step_size.restype = None
         L.oracle_alt_advance.argtypes = [C.c_int32, dp, C.c_double, dp, dp]
@@ -308,6 +310,14 @@ def oda_update(mean, x1, y, eta, gamma, want_next: bool = True):
                             None if xn is None else _p(xn, C.c_float), _p(xh, C.c_float), C.c_float(float(eta)),
                             C.c_float(float(gamma)))
     return xn, xh
+
+
+def extrapolate(mean, x, gamma) -> np.ndarray:
+    """x - gamma * mean (one leg of an extra-gradient round)."""
+    mean, x = _f32(mean), _f32(x)
+    out = np.zeros_like(x)
+    lib().oracle_extrapolate(x.size, _p(mean, C.c_float), _p(x, C.c_float), C.c_float(float(gamma)), _p(out, C.c_float))
+    return out
 
 
 def alt_step_size(lam: float, mu: float, q_hat: float):

@@ -565,6 +565,16 @@ void oracle_oda_update(int64_t n, const float *mean, const float *x1, float *y, 
   }
 }
 
+// ---------------------------------------------------------------- one plain step (extra-gradient leg, Sec. 4)
+// out = x - gamma * mean.  An extra-gradient method, the two-call scheme the paper compares QODA with, applies it
+// twice per round: X_{t+1/2} = X_t - gamma * mean_k Vhat_k(X_t), then X_{t+1} = X_t - gamma * mean_k Vhat_k(X_{t+1/2}).
+void oracle_extrapolate(int64_t n, const float *mean, const float *x, float gamma, float *out) {
+  for (int64_t e = 0; e < n; ++e) {
+    const float gm = gamma * mean[e];
+    out[e] = x[e] - gm;
+  }
+}
+
 // ---------------------------------------------------------------- alternative step sizes: eq. (Alt), Sec. 6
 // With lambda = sum_{s<=t-2} sum_k ||Vhat_{k,s+1/2}||^2 / K^2 and mu = sum_{s<=t-2} ||X_s - X_{s+1}||^2:
 //   eta_t = (1 + lambda + mu)^(-1/2),  gamma_t = (1 + lambda)^(q - 1/2),  0 < q <= 1/4.

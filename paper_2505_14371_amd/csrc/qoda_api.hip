@@ -574,6 +574,29 @@ int qoda_step(qoda_ctx *c, const void *const *msgs_dev, const qoda_state *st, vo
   return QODA_OK;
 }
 
+int qoda_extrapolate(qoda_ctx *c, const void *const *msgs_dev, const float *const *x_dev, float *const *out_dev,
+                     const float *gamma_dev, void *stream) {
+  if (!c) return QODA_EINVAL;
+  if (!gamma_dev) return fail(c, QODA_EINVAL, "qoda_extrapolate: null step size");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  Dev a = base_args(c);
+  int rc = decode_common(c, msgs_dev, a, s, "qoda_extrapolate: msgs_dev");
+  if (rc) return rc;
+  rc = check_layer_ptrs(c, reinterpret_cast<const void *const *>(x_dev), c->L, "qoda_extrapolate: x_dev", true);
+  if (rc) return rc;
+  rc = check_layer_ptrs(c, reinterpret_cast<const void *const *>(out_dev), c->L, "qoda_extrapolate: out_dev", true);
+  if (rc) return rc;
+  rc = sync_table(c, c->t_x1, reinterpret_cast<const void *const *>(x_dev), c->L, s);
+  if (rc) return rc;
+  rc = sync_table(c, c->t_xh, reinterpret_cast<const void *const *>(out_dev), c->L, s);
+  if (rc) return rc;
+  a.x1 = reinterpret_cast<const float *const *>(c->t_x1.dev);
+  a.x_half = reinterpret_cast<float *const *>(c->t_xh.dev);
+  a.gamma_in = gamma_dev;
+  LAUNCH(c, kIdDecodeExtrapolate, s, launch_decode(a, kDecodeExtrapolate, c->planes_mask, s));
+  return QODA_OK;
+}
+
 int qoda_step_alt(qoda_ctx *c, const void *const *msgs_dev, const qoda_alt_state *st, double q_hat, void *stream) {
   if (!c) return QODA_EINVAL;
   if (!st || !st->sums_dev || !st->eta_dev) return fail(c, QODA_EINVAL, "qoda_step_alt: null state, sums or rates");
@@ -663,7 +686,7 @@ const char *qoda_kernel_name(int32_t id) {
                                              "k_decode<false>", "k_decode<true>", "k_fit_typemax", "k_fit_pool",
                                              "k_fit_dp", "k_build_tables", "k_copy_f4", "k_alt_scalars",
                                              "k_decode<alt>", "k_alt_finalize", "k_norm_vector", "k_bucket_max",
-                                             "k_bucket_hist"};
+                                             "k_bucket_hist", "k_decode<extrapolate>"};
   return (id >= 0 && id < kNumKernelIds) ? names[id] : "";
 }
 

@@ -71,6 +71,7 @@ struct Dev {
   float *const *mean_out;
   double *acc;
   float *eta_out;  // may be nullptr
+  const float *gamma_in;   // extrapolate mode: device scalar
   double *alt_sums;        // eq. (Alt): [2] lambda, mu (caller's)
   unsigned int q_digits;   // eq. (Alt): the exponent's first 32 binary digits
   unsigned long long seed;
@@ -81,15 +82,16 @@ struct Dev {
   double invK2;
 };
 
-// What the decode kernel does after the K-way mean: store it, apply eq. (ODA), or apply eq. (ODA) with the two
-// rates of eq. (Alt) and accumulate ||X_t - X_{t+1}||^2.
-enum DecodeMode { kDecodeMean = 0, kDecodeUpdate = 1, kDecodeUpdateAlt = 2 };
+// What the decode kernel does after the K-way mean: store it, apply eq. (ODA), apply eq. (ODA) with the two
+// rates of eq. (Alt) and accumulate ||X_t - X_{t+1}||^2, or take one plain step out = x - gamma * mean (the leg an
+// extra-gradient method repeats twice per round, Sec. 4).
+enum DecodeMode { kDecodeMean = 0, kDecodeUpdate = 1, kDecodeUpdateAlt = 2, kDecodeExtrapolate = 3 };
 
 // Kernel classes, for the optional per-kernel event timing of the host API.
 enum KernelId {
   kIdZero = 0, kIdSumsq, kIdSumsqHist, kIdNormFinalize, kIdWriteHeader, kIdQuantize, kIdDeltaFinalize, kIdStepScalars,
   kIdDecodeMean, kIdDecodeUpdate, kIdFitTypemax, kIdFitPool, kIdFitDp, kIdBuildTables, kIdCopy, kIdAltScalars,
-  kIdDecodeAlt, kIdAltFinalize, kIdNormVector, kIdBucketMax, kIdBucketHist, kNumKernelIds
+  kIdDecodeAlt, kIdAltFinalize, kIdNormVector, kIdBucketMax, kIdBucketHist, kIdDecodeExtrapolate, kNumKernelIds
 };
 
 // Launch wrappers (each checks nothing: the host API validates shapes before calling).

@@ -814,6 +814,15 @@ __device__ __forceinline__ void decode_octet(const Dev &a, const LayerMeta &m, i
       for (int j = 0; j < 4; ++j) mean[j] = sum[4 * bb + j] * a.invK;
       if (MODE == kDecodeMean) {
         store4(a.mean_out[l], e, dlim, mean);
+      } else if (MODE == kDecodeExtrapolate) {   // out = x - gamma * mean (x in a.x1, out in a.x_half)
+        float x[4], out[4];
+        load4(a.x1[l], e, dlim, x);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float gm = gamma * mean[j];
+          out[j] = x[j] - gm;
+        }
+        store4(a.x_half[l], e, dlim, out);
       } else {
         float y[4], x1[4], xn[4], xh[4];
         load4(a.y[l], e, dlim, y);      // coordinates past the end of the layer read as 0 and add nothing below
@@ -850,8 +859,9 @@ __device__ __forceinline__ void decode_tile(const Dev &a, const LayerMeta &m, in
   const int w = __builtin_amdgcn_readfirstlane(t >> 6);
   const int i = t & 63;
   float eta = 0.0f, gamma = 0.0f, eta_prev = 0.0f, accx = 0.0f;
-  if (MODE != kDecodeMean) { eta = a.eta[0]; gamma = a.eta[1]; }
+  if (MODE == kDecodeUpdate || MODE == kDecodeUpdateAlt) { eta = a.eta[0]; gamma = a.eta[1]; }
   if (MODE == kDecodeUpdateAlt) eta_prev = a.eta[2];
+  if (MODE == kDecodeExtrapolate) gamma = a.gamma_in[0];
   const long long noct = (m.nblk + 7) >> 3;
   for (int oo = 0; oo < 2; ++oo) {
     const long long O = (long long)chunk * 8 + w * 2 + oo;
@@ -1286,7 +1296,8 @@ hipError_t launch_step_scalars(const Dev &a, hipStream_t s) {
 template <int C1, bool BUCKET>
 static void launch_decode_scope(const Dev &a, int mode, size_t lds_bytes, hipStream_t s) {
   const dim3 grid(a.G), block(kThreads);
-  if (mode == kDecodeUpdateAlt) hipLaunchKernelGGL((k_decode<C1, kDecodeUpdateAlt, BUCKET>), grid, block, lds_bytes, s, a);
+  if (mode == kDecodeExtrapolate) hipLaunchKernelGGL((k_decode<C1, kDecodeExtrapolate, BUCKET>), grid, block, lds_bytes, s, a);
+  else if (mode == kDecodeUpdateAlt) hipLaunchKernelGGL((k_decode<C1, kDecodeUpdateAlt, BUCKET>), grid, block, lds_bytes, s, a);
   else if (mode == kDecodeUpdate) hipLaunchKernelGGL((k_decode<C1, kDecodeUpdate, BUCKET>), grid, block, lds_bytes, s, a);
   else hipLaunchKernelGGL((k_decode<C1, kDecodeMean, BUCKET>), grid, block, lds_bytes, s, a);
 }

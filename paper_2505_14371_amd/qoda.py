@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libqoda.so")
 
 OK, EINVAL, ENOMEM, EHIP, ENONFINITE = 0, -1, -2, -3, -4
 BUF_SUMSQ, BUF_NORM, BUF_INV, BUF_DELTA, BUF_HIST, BUF_POOLED = range(6)
-NUM_KERNELS = 21
+NUM_KERNELS = 22
 SCOPE_LAYER, SCOPE_VECTOR, SCOPE_BUCKET = 0, 1, 2
 HIST_BINS, GRID_POINTS = 2048, 257
 
@@ -71,6 +71,7 @@ def load():
     L.qoda_dequant_aggregate.argtypes = [vp, pp, pp, vp]
     L.qoda_step.argtypes = [vp, pp, C.POINTER(_State), vp]
     L.qoda_step_alt.argtypes = [vp, pp, C.POINTER(_AltState), C.c_double, vp]
+    L.qoda_extrapolate.argtypes = [vp, pp, pp, pp, vp, vp]
     L.qoda_read_buffer.argtypes = [vp, C.c_int32, vp, C.c_size_t, vp]
     L.qoda_status.argtypes = [vp, vp]
     L.qoda_profile_enable.argtypes = [vp, C.c_uint32]
@@ -81,7 +82,7 @@ def load():
     L.qoda_last_error.argtypes = [vp]
     L.qoda_last_error.restype = C.c_char_p
     for name in ("qoda_create", "qoda_destroy", "qoda_message_layout", "qoda_set_levels", "qoda_get_levels",
-                 "qoda_fit_levels", "qoda_quantize", "qoda_quantize_all", "qoda_dequant_aggregate", "qoda_step", "qoda_step_alt",
+                 "qoda_fit_levels", "qoda_quantize", "qoda_quantize_all", "qoda_dequant_aggregate", "qoda_step", "qoda_step_alt", "qoda_extrapolate",
                  "qoda_read_buffer", "qoda_status", "qoda_profile_enable", "qoda_profile_read", "qoda_copy_calibration"):
         getattr(L, name).restype = C.c_int
     _lib = L
@@ -204,6 +205,10 @@ class Context:
         st = _AltState(_ptrs(x1), _ptrs(y), _ptrs(x_half), None if x_next is None else _ptrs(x_next), _addr(sums),
                        _addr(eta))
         self._check(self._lib.qoda_step_alt(self._h, _ptrs(msgs), C.byref(st), float(q_hat), _stream(stream)))
+
+    def extrapolate(self, msgs: Sequence, x: Sequence, out: Sequence, gamma, stream=None):
+        assert len(msgs) == self.K and len(x) == self.L and len(out) == self.L
+        self._check(self._lib.qoda_extrapolate(self._h, _ptrs(msgs), _ptrs(x), _ptrs(out), _addr(gamma), _stream(stream)))
 
     # -- diagnostics
     def read_buffer(self, which: int, stream=None) -> np.ndarray:
