@@ -85,6 +85,12 @@ def lib():
         L.oracle_step_size.restype = None
         L.oracle_oda_update.argtypes = [C.c_int64, fp, fp, fp, fp, fp, C.c_float, C.c_float]
         L.oracle_oda_update.restype = None
+        L.oracle_index_counts.argtypes = [C.c_int32, i64p, i32p, i32p, C.c_int32, u8p, u64p]
+        L.oracle_index_counts.restype = None
+        L.oracle_huffman_bits.argtypes = [u64p, C.c_int32]
+        L.oracle_huffman_bits.restype = C.c_double
+        L.oracle_code_length.argtypes = [C.c_int32, i32p, u64p, C.c_double, dp]
+        L.oracle_code_length.restype = None
         L.oracle_extrapolate.argtypes = [C.c_int64, fp, fp, C.c_float, fp]
         L.oracle_extrapolate.restype = None
         L.oracle_alt_step_size.argtypes = [C.c_double, C.c_double, C.c_double, fp, fp]
@@ -310,6 +316,32 @@ def oda_update(mean, x1, y, eta, gamma, want_next: bool = True):
                             None if xn is None else _p(xn, C.c_float), _p(xh, C.c_float), C.c_float(float(eta)),
                             C.c_float(float(gamma)))
     return xn, xh
+
+
+def index_counts(sizes, points, layer_type, num_types: int, msgs: Sequence[np.ndarray], scope: int = SCOPE_LAYER):
+    """Occurrences of every level index per type over the given messages: uint64 [num_types, 256]."""
+    d, S = _dims(sizes, points)
+    lt = np.ascontiguousarray(layer_type, dtype=np.int32)
+    counts = np.zeros((num_types, 256), dtype=np.uint64)
+    for m in msgs:
+        m = np.ascontiguousarray(m, dtype=np.uint8)
+        lib().oracle_index_counts(d.size, _p(d, C.c_int64), _p(S, C.c_int32), _p(lt, C.c_int32), scope, _p(m, C.c_uint8),
+                                  _p(counts, C.c_uint64))
+    return counts
+
+
+def huffman_bits(counts) -> float:
+    c = np.ascontiguousarray(counts, dtype=np.uint64)
+    return float(lib().oracle_huffman_bits(_p(c, C.c_uint64), c.size))
+
+
+def code_length(type_points, counts, num_norms: float) -> dict:
+    tp = np.ascontiguousarray(type_points, dtype=np.int32)
+    c = np.ascontiguousarray(counts, dtype=np.uint64)
+    assert c.shape == (tp.size, 256)
+    out = np.zeros(6, dtype=np.float64)
+    lib().oracle_code_length(tp.size, _p(tp, C.c_int32), _p(c, C.c_uint64), float(num_norms), _p(out, C.c_double))
+    return dict(zip(("fixed_bits", "paper_bits", "entropy_bits", "huffman_bits", "nonzeros", "coordinates"), out.tolist()))
 
 
 def extrapolate(mean, x, gamma) -> np.ndarray:

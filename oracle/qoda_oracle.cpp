@@ -18,6 +18,9 @@
 //   * optimistic dual averaging update and adaptive step size                -- Sec. 4, eq. (ODA),
 //                                                                                 eq. (general_stepsize), Alg. 1
 //   * the alternative pair of step sizes lagged by two rounds                  -- Sec. 6, eq. (Alt)
+//   * norm scopes (whole vector, buckets of 128), the extra-gradient leg,
+//     index counts and code lengths (fixed width, entropy, Huffman)            -- Sec. 2.2, Sec. 7, Sec. 4,
+//                                                                                 Thm 5.3 / App. C
 //
 // Pin status (see tests/test_oracle_*.py): every function below is pinned to something the paper or the
 // mathematics fixes EXCEPT the Philox generator's known-answer vectors: no published known-answer
@@ -35,6 +38,7 @@
 //
 // Build: g++ -O2 -std=c++17 -ffp-contract=off -fno-fast-math -shared -fPIC qoda_oracle.cpp -o libqoda_oracle.so
 
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
 #include <cstring>
@@ -563,6 +567,73 @@ void oracle_oda_update(int64_t n, const float *mean, const float *x1, float *y, 
     if (x_next) x_next[e] = xn;
     x_half[e] = xn - gm;
   }
+}
+
+// ---------------------------------------------------------------- code-length accounting (Sec. 5 Thm 5.3, App. C.1, C.3)
+// Occurrences of every level index among the real coordinates of one message, per type: counts[m*256 + h] += 1.
+void oracle_index_counts(int32_t L, const int64_t *d, const int32_t *S, const int32_t *layer_type, int32_t scope,
+                         const uint8_t *msg, uint64_t *counts) {
+  const Layout lay = make_layout(L, d, S, scope);
+  for (int l = 0; l < L; ++l)
+    for (int64_t e = 0; e < d[l]; ++e) {
+      const Code c = get_code(msg + lay.msg_off[l], lay.planes[l], lay.ostride[l], e);
+      counts[(size_t)layer_type[l] * 256 + c.h] += 1;
+    }
+}
+
+// Total length of an optimal prefix code (Huffman) for symbols with the given occurrence counts: sum_j c_j len_j.
+// Built the plain way: repeatedly merge the two lightest subtrees; every merge adds the merged weight to the total.
+// A single used symbol still takes one bit per occurrence.
+double oracle_huffman_bits(const uint64_t *counts, int32_t n) {
+  std::vector<double> w;
+  for (int j = 0; j < n; ++j)
+    if (counts[j]) w.push_back((double)counts[j]);
+  if (w.empty()) return 0.0;
+  if (w.size() == 1) return w[0];
+  double total = 0.0;
+  while (w.size() > 1) {
+    std::sort(w.begin(), w.end());
+    const double merged = w[0] + w[1];
+    total += merged;
+    w.erase(w.begin(), w.begin() + 2);
+    w.push_back(merged);
+  }
+  return total;
+}
+
+// Bit counts for the coordinates behind `counts` (M types x 256 indices), with `num_norms` 32-bit norms sent:
+//   out[0] fixed width, the format of this library: 32 num_norms + sum_m n_m (1 + ceil(log2 S_m));
+//   out[1] the expression in the proof of Thm 5.3 with the empirical occurrence probabilities p_j = c_j / n_m:
+//          32 num_norms + sum_m [ (n_m - c_0) + n_m (1 - sum_{j=1}^{alpha_m} p_j log2 p_j) ]   (alpha_m = S_m - 2:
+//          the sum runs over the interior levels, as printed; one sign bit per non-zero entry);
+//   out[2] entropy: 32 num_norms + (non-zeros) + sum_m n_m H_m, H_m = -sum_{j=0}^{S_m-1} p_j log2 p_j;
+//   out[3] Huffman: 32 num_norms + (non-zeros) + sum_m (Huffman total of type m);
+//   out[4] non-zero entries sum_m (n_m - c_0)  (the lemma on expected non-zeros, App. C.1);  out[5] coordinates.
+void oracle_code_length(int32_t M, const int32_t *type_points, const uint64_t *counts, double num_norms, double *out) {
+  double fixed = 32.0 * num_norms, paper = fixed, entropy = fixed, huff = fixed, nonzero = 0.0, coords = 0.0;
+  for (int m = 0; m < M; ++m) {
+    const uint64_t *c = counts + (size_t)m * 256;
+    const int Sm = type_points[m];
+    double n = 0.0;
+    for (int j = 0; j < 256; ++j) n += (double)c[j];
+    if (n == 0.0) continue;
+    const double nz = n - (double)c[0];
+    double h_all = 0.0, h_int = 0.0;
+    for (int j = 0; j < 256; ++j) {
+      if (!c[j]) continue;
+      const double p = (double)c[j] / n;
+      const double t = -p * std::log2(p);
+      h_all += t;
+      if (j >= 1 && j <= Sm - 2) h_int += t;
+    }
+    fixed += n * (1.0 + (double)index_bits(Sm));
+    paper += nz + n * (1.0 + h_int);
+    entropy += nz + n * h_all;
+    huff += nz + oracle_huffman_bits(c, 256);
+    nonzero += nz;
+    coords += n;
+  }
+  out[0] = fixed; out[1] = paper; out[2] = entropy; out[3] = huff; out[4] = nonzero; out[5] = coords;
 }
 
 // ---------------------------------------------------------------- one plain step (extra-gradient leg, Sec. 4)
