@@ -172,6 +172,27 @@ int qoda_step_alt(qoda_ctx *ctx, const void *const *msgs_dev, const qoda_alt_sta
 int qoda_extrapolate(qoda_ctx *ctx, const void *const *msgs_dev, const float *const *x_dev, float *const *out_dev,
                      const float *gamma_dev, void *stream);
 
+/* Code-length accounting (Thm 5.3 and its proof in App. C.1; Huffman coding, App. C.3).  The library transmits
+ * fixed-width codes; these two calls report what an entropy code on top would save.
+ * qoda_index_counts: occurrences of every level index among the real coordinates of the K messages, per type:
+ *   counts[m*256 + h] (host array of M*256 entries, overwritten); waits for `stream`.  msgs_dev: host [K].
+ * qoda_code_length (host arithmetic only): bit counts for the coordinates behind `counts`, gathered from
+ *   `num_messages` messages, with p_j = c_j / n_m the empirical occurrence probabilities of type m:
+ *     fixed_bits    32 per norm + (1 + ceil(log2 S_m)) per coordinate (this library's format without level tables
+ *                   and padding; norms per message: one per non-empty layer, one in all under vector scope, one per
+ *                   bucket under bucket scope);
+ *     paper_bits    the expression in the proof of Thm 5.3: C_q + sum_m (1 - p_0) n_m + sum_m (H(l^m) + 1) n_m with
+ *                   H(l^m) = -sum_{j=1}^{alpha_m} p_j log2 p_j over the interior levels, as printed;
+ *     entropy_bits  32 per norm + one sign bit per non-zero entry + sum_m n_m * (-sum_j p_j log2 p_j), all indices;
+ *     huffman_bits  32 per norm + one sign bit per non-zero entry + the total length of a Huffman code per type;
+ *     nonzeros      entries with index > 0 (lemma on the expected number of non-zeros, App. C.1);
+ *     coordinates   sum_m n_m;   message_bits  8 * qoda_message_bytes() * num_messages. */
+typedef struct {
+  double fixed_bits, paper_bits, entropy_bits, huffman_bits, nonzeros, coordinates, message_bits;
+} qoda_code_length_report;
+int qoda_index_counts(qoda_ctx *ctx, const void *const *msgs_dev, uint64_t *counts, void *stream);
+int qoda_code_length(qoda_ctx *ctx, const uint64_t *counts, uint32_t num_messages, qoda_code_length_report *out);
+
 /* Read an internal device buffer into host memory (waits for `stream`); for tests and diagnostics. */
 #define QODA_BUF_SUMSQ 0  /* double[K*L]  canonical per-layer sums of squares of the last norm pass        */
 #define QODA_BUF_NORM 1   /* float [K*L]  norms                                                            */
@@ -195,7 +216,7 @@ int qoda_status(qoda_ctx *ctx, void *stream);
  *   of range.
  * qoda_copy_calibration: a plain 128-bit copy kernel of `bytes` bytes (multiple of 16; 16-byte aligned device
  *   pointers): the known-traffic kernel that hardware byte counters are scaled by. */
-#define QODA_NUM_KERNELS 22
+#define QODA_NUM_KERNELS 23
 int qoda_profile_enable(qoda_ctx *ctx, uint32_t class_mask);
 int qoda_profile_read(qoda_ctx *ctx, double *ms, int64_t *launches, void *stream);
 const char *qoda_kernel_name(int32_t id);

@@ -43,6 +43,7 @@ struct qoda_ctx {
   int *d_type_exp = nullptr;
   short *d_dp_arg = nullptr;
   long long *d_dp_arg_off = nullptr;
+  unsigned long long *d_index_counts = nullptr;   // [M*256], allocated by the first qoda_index_counts
   // device pointer tables (uploaded when their host shadow changes)
   struct Table {
     void **dev = nullptr;
@@ -194,7 +195,7 @@ int check_msg_ptrs(qoda_ctx *c, const void *const *p, size_t n, const char *what
 
 void free_all(qoda_ctx *c) {
   void *ptrs[] = {c->d_meta, c->d_tiles, c->d_stiles, c->d_empty, c->d_type_points, c->d_partial, c->d_dpartial, c->d_sumsq, c->d_delta,
-                  c->d_norm, c->d_inv, c->d_lev, c->d_rgap, c->d_eta, c->d_lut, c->d_hist, c->d_status, c->d_pooled,
+                  c->d_norm, c->d_inv, c->d_lev, c->d_rgap, c->d_eta, c->d_lut, c->d_hist, c->d_status, c->d_pooled, c->d_index_counts,
                   c->d_type_exp, c->d_dp_arg, c->d_dp_arg_off, c->t_grad.dev, c->t_msg.dev, c->t_prev.dev, c->t_in.dev,
                   c->t_x1.dev, c->t_y.dev, c->t_xh.dev, c->t_xn.dev, c->t_mean.dev};
   for (void *p : ptrs)
@@ -574,6 +575,102 @@ int qoda_step(qoda_ctx *c, const void *const *msgs_dev, const qoda_state *st, vo
   return QODA_OK;
 }
 
+int qoda_index_counts(qoda_ctx *c, const void *const *msgs_dev, uint64_t *counts, void *stream) {
+  if (!c) return QODA_EINVAL;
+  if (!counts) return fail(c, QODA_EINVAL, "qoda_index_counts: null output");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const size_t n = (size_t)c->M * 256;
+  if (!c->d_index_counts) HIP_TRY(c, dev_alloc(&c->d_index_counts, n));
+  Dev a = base_args(c);
+  int rc = decode_common(c, msgs_dev, a, s, "qoda_index_counts: msgs_dev");
+  if (rc) return rc;
+  a.index_counts = c->d_index_counts;
+  LAUNCH(c, kIdZero, s, launch_zero_u32(reinterpret_cast<unsigned int *>(c->d_index_counts), 2 * n, s));
+  LAUNCH(c, kIdIndexHist, s, launch_index_hist(a, c->planes_mask, s));
+  static_assert(sizeof(uint64_t) == sizeof(unsigned long long), "64-bit counters");
+  HIP_TRY(c, hipMemcpyAsync(counts, c->d_index_counts, n * sizeof(uint64_t), hipMemcpyDeviceToHost, s));
+  HIP_TRY(c, hipStreamSynchronize(s));
+  for (int l = 0; l < c->L; ++l) {   // padding coordinates carry index 0
+    const LayerMeta &m = c->meta[l];
+    const uint64_t pad = (uint64_t)(((m.nblk + 7) / 8) * 2048 - m.d) * (uint64_t)c->K;
+    counts[(size_t)m.type * 256] -= pad;
+  }
+  return QODA_OK;
+}
+
+// Total length of an optimal prefix code for the given occurrence counts: the counts are sorted once, then the two
+// lightest subtrees are always at the heads of two queues (leaves in sorted order, merged weights in creation order),
+// as App. C.3 notes; every merge adds its weight to the total.
+static double huffman_total(const uint64_t *cnt, int n) {
+  std::vector<double> leaf;
+  for (int j = 0; j < n; ++j)
+    if (cnt[j]) leaf.push_back((double)cnt[j]);
+  if (leaf.empty()) return 0.0;
+  if (leaf.size() == 1) return leaf[0];   // a lone symbol still takes one bit per occurrence
+  std::sort(leaf.begin(), leaf.end());
+  std::vector<double> merged;
+  merged.reserve(leaf.size());
+  size_t li = 0, mi = 0;
+  double total = 0.0;
+  auto take = [&]() {
+    if (mi >= merged.size() || (li < leaf.size() && leaf[li] <= merged[mi])) return leaf[li++];
+    return merged[mi++];
+  };
+  const size_t merges = leaf.size() - 1;
+  for (size_t q = 0; q < merges; ++q) {
+    const double a0 = take();
+    const double a1 = take();
+    merged.push_back(a0 + a1);
+    total += a0 + a1;
+  }
+  return total;
+}
+
+int qoda_code_length(qoda_ctx *c, const uint64_t *counts, uint32_t num_messages, qoda_code_length_report *out) {
+  if (!c) return QODA_EINVAL;
+  if (!counts || !out) return fail(c, QODA_EINVAL, "qoda_code_length: null argument");
+  double norms = 0.0;   // 32-bit norms one message carries
+  if (c->scope == kScopeVector) norms = 1.0;
+  else
+    for (int l = 0; l < c->L; ++l) {
+      const long long d = c->meta[l].d;
+      if (d == 0) continue;
+      norms += (c->scope == kScopeBucket) ? (double)((d + kBucketCoords - 1) / kBucketCoords) : 1.0;
+    }
+  const double cq = 32.0 * norms * (double)num_messages;
+  double fixed = cq, paper = cq, entropy = cq, huff = cq, nonzero = 0.0, coords = 0.0;
+  for (int m = 0; m < c->M; ++m) {
+    const uint64_t *cm = counts + (size_t)m * 256;
+    const int Sm = c->type_points[m];
+    double n = 0.0;
+    for (int j = 0; j < 256; ++j) n += (double)cm[j];
+    if (n == 0.0) continue;
+    const double nz = n - (double)cm[0];
+    double h_all = 0.0, h_int = 0.0;
+    for (int j = 0; j < 256; ++j) {
+      if (!cm[j]) continue;
+      const double p = (double)cm[j] / n;
+      const double t = -p * std::log2(p);
+      h_all += t;
+      if (j >= 1 && j <= Sm - 2) h_int += t;
+    }
+    fixed += n * (double)(1 + index_bits(Sm));
+    paper += nz + n * (1.0 + h_int);
+    entropy += nz + n * h_all;
+    huff += nz + huffman_total(cm, 256);
+    nonzero += nz;
+    coords += n;
+  }
+  out->fixed_bits = fixed;
+  out->paper_bits = paper;
+  out->entropy_bits = entropy;
+  out->huffman_bits = huff;
+  out->nonzeros = nonzero;
+  out->coordinates = coords;
+  out->message_bits = 8.0 * (double)c->message_bytes * (double)num_messages;
+  return QODA_OK;
+}
+
 int qoda_extrapolate(qoda_ctx *c, const void *const *msgs_dev, const float *const *x_dev, float *const *out_dev,
                      const float *gamma_dev, void *stream) {
   if (!c) return QODA_EINVAL;
@@ -686,7 +783,7 @@ const char *qoda_kernel_name(int32_t id) {
                                              "k_decode<false>", "k_decode<true>", "k_fit_typemax", "k_fit_pool",
                                              "k_fit_dp", "k_build_tables", "k_copy_f4", "k_alt_scalars",
                                              "k_decode<alt>", "k_alt_finalize", "k_norm_vector", "k_bucket_max",
-                                             "k_bucket_hist", "k_decode<extrapolate>"};
+                                             "k_bucket_hist", "k_decode<extrapolate>", "k_index_hist"};
   return (id >= 0 && id < kNumKernelIds) ? names[id] : "";
 }
 

@@ -72,6 +72,7 @@ struct Dev {
   double *acc;
   float *eta_out;  // may be nullptr
   const float *gamma_in;   // extrapolate mode: device scalar
+  unsigned long long *index_counts;   // [M*256] occurrences of every level index per type (code-length accounting)
   double *alt_sums;        // eq. (Alt): [2] lambda, mu (caller's)
   unsigned int q_digits;   // eq. (Alt): the exponent's first 32 binary digits
   unsigned long long seed;
@@ -91,7 +92,7 @@ enum DecodeMode { kDecodeMean = 0, kDecodeUpdate = 1, kDecodeUpdateAlt = 2, kDec
 enum KernelId {
   kIdZero = 0, kIdSumsq, kIdSumsqHist, kIdNormFinalize, kIdWriteHeader, kIdQuantize, kIdDeltaFinalize, kIdStepScalars,
   kIdDecodeMean, kIdDecodeUpdate, kIdFitTypemax, kIdFitPool, kIdFitDp, kIdBuildTables, kIdCopy, kIdAltScalars,
-  kIdDecodeAlt, kIdAltFinalize, kIdNormVector, kIdBucketMax, kIdBucketHist, kIdDecodeExtrapolate, kNumKernelIds
+  kIdDecodeAlt, kIdAltFinalize, kIdNormVector, kIdBucketMax, kIdBucketHist, kIdDecodeExtrapolate, kIdIndexHist, kNumKernelIds
 };
 
 // Launch wrappers (each checks nothing: the host API validates shapes before calling).
@@ -104,6 +105,7 @@ hipError_t launch_delta_finalize(const Dev &a, hipStream_t s);
 hipError_t launch_step_scalars(const Dev &a, hipStream_t s);
 hipError_t launch_decode(const Dev &a, int mode, unsigned int planes_mask, hipStream_t s);   // mode: DecodeMode
 hipError_t launch_alt_scalars(const Dev &a, hipStream_t s);
+hipError_t launch_index_hist(const Dev &a, unsigned int planes_mask, hipStream_t s);   // counts every code of every octet
 hipError_t launch_alt_finalize(const Dev &a, hipStream_t s);
 hipError_t launch_bucket_max(const Dev &a, hipStream_t s);    // bucket scope: a.sumsq must be zero
 hipError_t launch_bucket_hist(const Dev &a, hipStream_t s);   // bucket scope: grid histograms, then pooling

@@ -895,6 +895,43 @@ __global__ void __launch_bounds__(kThreads) k_decode(Dev a) {
   decode_tile<C1, MODE, BUCKET>(a, m, l, tile.y, T, red);
 }
 
+// ------------------------------------------------------------------------------------------------ code lengths
+// Occurrences of every level index in the K messages, per type (the empirical p_j of Thm 5.3).  Every code of every
+// octet is counted, padding included (index 0): the host subtracts the padding.  Each lane counts into its own column
+// of a shared-memory table [index][lane], so no two lanes of a wave ever meet on an address.
+template <int C1, bool BUCKET>
+__global__ void __launch_bounds__(kThreads) k_index_hist(Dev a) {
+  extern __shared__ unsigned int cnt[];   // [2^(C1-1)][64]
+  constexpr int NI = 1 << (C1 - 1);
+  constexpr long long OS = 256 * C1 + (BUCKET ? 64 : 0);
+  const int4 st = a.stiles[blockIdx.x];   // a run of up to kSuperTile tiles of one layer: one flush per run
+  const int l = st.x, k = blockIdx.y;
+  const LayerMeta m = a.meta[l];
+  if (m.planes != C1) return;
+  const int t = threadIdx.x, w = t >> 6, i = t & 63;
+  for (int q = t; q < NI * 64; q += kThreads) cnt[q] = 0u;
+  __syncthreads();
+  const long long noct = (m.nblk + 7) >> 3;
+  for (int cc = 0; cc < st.z; ++cc)
+    for (int oo = 0; oo < 2; ++oo) {
+      const long long O = (long long)(st.y + cc) * 8 + w * 2 + oo;
+      if (O >= noct) break;
+      unsigned int D[C1];
+      load_record<C1>(a.msgs_in[k] + m.body_off + O * OS, i, D);
+#pragma unroll
+      for (int jj = 0; jj < 32; ++jj) {
+        const unsigned int h = extract_code<C1>(D, jj) >> 1;
+        atomicAdd(&cnt[h * 64 + i], 1u);
+      }
+    }
+  __syncthreads();
+  for (int h = t; h < NI; h += kThreads) {
+    unsigned long long sum = 0ull;
+    for (int q = 0; q < 64; ++q) sum += cnt[h * 64 + ((q + h) & 63)];
+    if (sum) atomicAdd(&a.index_counts[(size_t)m.type * 256 + h], sum);
+  }
+}
+
 // ------------------------------------------------------------------------------------------------ level fit
 // Largest sum of squares of a type -> its binary exponent (fixed-point scale of the weights lambda_z).
 __global__ void __launch_bounds__(kThreads) k_fit_typemax(Dev a) {
@@ -1318,6 +1355,27 @@ hipError_t launch_decode(const Dev &a, int mode, unsigned int planes_mask, hipSt
   if (planes_mask & (1u << 7)) launch_decode_width<7>(a, mode, (size_t)a.K * 128 * sizeof(float), s);
   if (planes_mask & (1u << 8)) launch_decode_width<8>(a, mode, (size_t)a.K * 256 * sizeof(float), s);
   if (planes_mask & (1u << 9)) launch_decode_width<9>(a, mode, (size_t)a.K * 512 * sizeof(float), s);
+  return hipGetLastError();
+}
+
+template <int C1>
+static void launch_index_hist_width(const Dev &a, hipStream_t s) {
+  const dim3 grid(a.GS, a.K), block(kThreads);
+  const size_t lds = (size_t)(1 << (C1 - 1)) * 64 * sizeof(unsigned int);
+  if (a.scope == kScopeBucket) hipLaunchKernelGGL((k_index_hist<C1, true>), grid, block, lds, s, a);
+  else hipLaunchKernelGGL((k_index_hist<C1, false>), grid, block, lds, s, a);
+}
+
+hipError_t launch_index_hist(const Dev &a, unsigned int planes_mask, hipStream_t s) {
+  if (a.G == 0) return hipSuccess;
+  if (planes_mask & (1u << 2)) launch_index_hist_width<2>(a, s);
+  if (planes_mask & (1u << 3)) launch_index_hist_width<3>(a, s);
+  if (planes_mask & (1u << 4)) launch_index_hist_width<4>(a, s);
+  if (planes_mask & (1u << 5)) launch_index_hist_width<5>(a, s);
+  if (planes_mask & (1u << 6)) launch_index_hist_width<6>(a, s);
+  if (planes_mask & (1u << 7)) launch_index_hist_width<7>(a, s);
+  if (planes_mask & (1u << 8)) launch_index_hist_width<8>(a, s);
+  if (planes_mask & (1u << 9)) launch_index_hist_width<9>(a, s);
   return hipGetLastError();
 }
 

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libqoda.so")
 
 OK, EINVAL, ENOMEM, EHIP, ENONFINITE = 0, -1, -2, -3, -4
 BUF_SUMSQ, BUF_NORM, BUF_INV, BUF_DELTA, BUF_HIST, BUF_POOLED = range(6)
-NUM_KERNELS = 22
+NUM_KERNELS = 23
 SCOPE_LAYER, SCOPE_VECTOR, SCOPE_BUCKET = 0, 1, 2
 HIST_BINS, GRID_POINTS = 2048, 257
 
@@ -48,6 +48,11 @@ class _AltState(C.Structure):
                 ("sums_dev", C.c_void_p), ("eta_dev", C.c_void_p)]
 
 
+class _CodeLength(C.Structure):
+    _fields_ = [(n, C.c_double) for n in ("fixed_bits", "paper_bits", "entropy_bits", "huffman_bits", "nonzeros",
+                                          "coordinates", "message_bits")]
+
+
 def load():
     """Open libqoda.so (built by ``paper_2505_14371_amd.build``); raises if it is not there."""
     global _lib
@@ -72,6 +77,8 @@ def load():
     L.qoda_step.argtypes = [vp, pp, C.POINTER(_State), vp]
     L.qoda_step_alt.argtypes = [vp, pp, C.POINTER(_AltState), C.c_double, vp]
     L.qoda_extrapolate.argtypes = [vp, pp, pp, pp, vp, vp]
+    L.qoda_index_counts.argtypes = [vp, pp, C.POINTER(C.c_uint64), vp]
+    L.qoda_code_length.argtypes = [vp, C.POINTER(C.c_uint64), C.c_uint32, C.POINTER(_CodeLength)]
     L.qoda_read_buffer.argtypes = [vp, C.c_int32, vp, C.c_size_t, vp]
     L.qoda_status.argtypes = [vp, vp]
     L.qoda_profile_enable.argtypes = [vp, C.c_uint32]
@@ -82,7 +89,7 @@ def load():
     L.qoda_last_error.argtypes = [vp]
     L.qoda_last_error.restype = C.c_char_p
     for name in ("qoda_create", "qoda_destroy", "qoda_message_layout", "qoda_set_levels", "qoda_get_levels",
-                 "qoda_fit_levels", "qoda_quantize", "qoda_quantize_all", "qoda_dequant_aggregate", "qoda_step", "qoda_step_alt", "qoda_extrapolate",
+                 "qoda_fit_levels", "qoda_quantize", "qoda_quantize_all", "qoda_dequant_aggregate", "qoda_step", "qoda_step_alt", "qoda_extrapolate", "qoda_index_counts", "qoda_code_length",
                  "qoda_read_buffer", "qoda_status", "qoda_profile_enable", "qoda_profile_read", "qoda_copy_calibration"):
         getattr(L, name).restype = C.c_int
     _lib = L
@@ -209,6 +216,22 @@ class Context:
     def extrapolate(self, msgs: Sequence, x: Sequence, out: Sequence, gamma, stream=None):
         assert len(msgs) == self.K and len(x) == self.L and len(out) == self.L
         self._check(self._lib.qoda_extrapolate(self._h, _ptrs(msgs), _ptrs(x), _ptrs(out), _addr(gamma), _stream(stream)))
+
+    def index_counts(self, msgs: Sequence, stream=None) -> np.ndarray:
+        """Occurrences of every level index per type over the K messages: uint64 [M, 256]."""
+        assert len(msgs) == self.K
+        out = np.zeros((self.M, 256), dtype=np.uint64)
+        self._check(self._lib.qoda_index_counts(self._h, _ptrs(msgs), out.ctypes.data_as(C.POINTER(C.c_uint64)),
+                                                _stream(stream)))
+        return out
+
+    def code_length(self, counts: np.ndarray, num_messages: Optional[int] = None) -> dict:
+        c = np.ascontiguousarray(counts, dtype=np.uint64)
+        assert c.shape == (self.M, 256)
+        rep = _CodeLength()
+        self._check(self._lib.qoda_code_length(self._h, c.ctypes.data_as(C.POINTER(C.c_uint64)),
+                                               self.K if num_messages is None else int(num_messages), C.byref(rep)))
+        return {n: getattr(rep, n) for n, _ in _CodeLength._fields_}
 
     # -- diagnostics
     def read_buffer(self, which: int, stream=None) -> np.ndarray:
