@@ -20,6 +20,7 @@ BLOCK = 256
 OCTET = 2048
 CHUNK = 16384
 BUCKET = 128
+TYPE_SKIP = 0x7FFFFFFF   # "no weight scale for this type"
 SCOPE_LAYER, SCOPE_VECTOR, SCOPE_BUCKET = 0, 1, 2   # what one norm covers: a layer, the whole vector, 128 coordinates
 
 _lib = None
@@ -75,7 +76,7 @@ def lib():
         L.oracle_bucket_sumsq.restype = C.c_double
         L.oracle_unpack_layer.restype = None
         L.oracle_quantize.argtypes = [C.c_int32, i64p, i32p, pp, pp, C.c_uint64, C.c_uint32, C.c_uint32, C.c_int32, u8p, u8p,
-                                      dp, dp]
+                                      dp, dp, i32p, u64p, dp]
         L.oracle_quantize.restype = C.c_int32
         L.oracle_delta_from_messages.argtypes = [C.c_int32, i64p, i32p, C.c_int32, u8p, u8p]
         L.oracle_delta_from_messages.restype = C.c_double
@@ -107,6 +108,8 @@ def lib():
         L.oracle_fit_dp.restype = None
         L.oracle_fit_levels.argtypes = [C.c_int32, i64p, i32p, C.c_int32, i32p, C.c_int32, C.c_int32, pp, pp, u32p, u64p]
         L.oracle_fit_levels.restype = C.c_int32
+        L.oracle_fit_from_stats.argtypes = [C.c_int32, i32p, C.c_int32, i32p, C.c_int32, u64p, dp, i32p, pp, u64p]
+        L.oracle_fit_from_stats.restype = C.c_int32
         _lib = L
     return _lib
 
@@ -259,8 +262,10 @@ def bucket_sumsq(v) -> float:
 
 # ------------------------------------------------------------------ whole messages
 def quantize(sizes, points, levels: Sequence[np.ndarray], grads: Sequence[np.ndarray], seed: int, round_: int,
-             node: int, msg_prev: Optional[np.ndarray] = None, scope: int = SCOPE_LAYER):
-    """ENCODE(Q(V_k)) for one node.  Returns (msg bytes, sumsq per layer, delta, status)."""
+             node: int, msg_prev: Optional[np.ndarray] = None, scope: int = SCOPE_LAYER, stats_exp=None):
+    """ENCODE(Q(V_k)) for one node.  Returns (msg bytes, sumsq per layer, delta, status); with ``stats_exp`` (the
+    weight scale of every layer's type, bucket scope) also the gathered (grid histograms [L, 257], largest sampled
+    bucket sums [L])."""
     d, S = _dims(sizes, points)
     lev = [_f32(a) for a in levels]
     g = [_f32(a) for a in grads]
@@ -273,10 +278,20 @@ def quantize(sizes, points, levels: Sequence[np.ndarray], grads: Sequence[np.nda
     if msg_prev is not None:
         prev = np.ascontiguousarray(msg_prev, dtype=np.uint8)
         assert prev.size == msg.size
+    if stats_exp is not None:
+        sexp = np.ascontiguousarray(stats_exp, dtype=np.int32)
+        assert sexp.size == d.size
+        shist = np.zeros((d.size, GRID_POINTS), dtype=np.uint64)
+        smax = np.zeros(d.size, dtype=np.float64)
     st = lib().oracle_quantize(d.size, _p(d, C.c_int64), _p(S, C.c_int32), _ptr_array(lev), _ptr_array(g), seed, round_,
                                node, scope, _p(msg, C.c_uint8), None if prev is None else _p(prev, C.c_uint8),
-                               _p(ss, C.c_double), _p(delta, C.c_double))
-    return msg, ss, float(delta[0]), int(st)
+                               _p(ss, C.c_double), _p(delta, C.c_double),
+                               None if stats_exp is None else _p(sexp, C.c_int32),
+                               None if stats_exp is None else _p(shist, C.c_uint64),
+                               None if stats_exp is None else _p(smax, C.c_double))
+    if stats_exp is None:
+        return msg, ss, float(delta[0]), int(st)
+    return msg, ss, float(delta[0]), int(st), shist, smax
 
 
 def delta_from_messages(sizes, points, msg, msg_prev=None, scope: int = SCOPE_LAYER) -> float:
@@ -422,6 +437,23 @@ def fit_levels(sizes, layer_type, type_points, K: int, grads: Sequence[np.ndarra
     st = lib().oracle_fit_levels(L, _p(d, C.c_int64), _p(lt, C.c_int32), M, _p(tp, C.c_int32), K, scope,
                                  _ptr_array(g), _ptr_array(lev), _p(hist, C.c_uint32), _p(pooled, C.c_uint64))
     return lev, hist.reshape(K, L, HIST_BINS), pooled.reshape(M, GRID_POINTS), int(st)
+
+
+def fit_from_stats(layer_type, type_points, K: int, hist, bmax, exps, levels: Sequence[np.ndarray]):
+    """hist: [K, L, 257] uint64, bmax: [K, L] float64, exps: [M] int32 (the scales the histograms were gathered with).
+    Returns (levels, pooled [M, 257], new exps [M], status)."""
+    lt = np.ascontiguousarray(layer_type, dtype=np.int32)
+    tp = np.ascontiguousarray(type_points, dtype=np.int32)
+    L, M = lt.size, tp.size
+    h = np.ascontiguousarray(hist, dtype=np.uint64)
+    b = np.ascontiguousarray(bmax, dtype=np.float64)
+    assert h.shape == (K, L, GRID_POINTS) and b.shape == (K, L)
+    ex = np.ascontiguousarray(exps, dtype=np.int32).copy()
+    lev = [_f32(a).copy() for a in levels]
+    pooled = np.zeros(M * GRID_POINTS, dtype=np.uint64)
+    st = lib().oracle_fit_from_stats(L, _p(lt, C.c_int32), M, _p(tp, C.c_int32), K, _p(h, C.c_uint64), _p(b, C.c_double),
+                                     _p(ex, C.c_int32), _ptr_array(lev), _p(pooled, C.c_uint64))
+    return lev, pooled.reshape(M, GRID_POINTS), ex, int(st)
 
 
 def grid_values() -> np.ndarray:

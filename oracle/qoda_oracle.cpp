@@ -401,6 +401,15 @@ void oracle_unpack_layer(const uint8_t *region, int64_t d, int32_t S, int32_t sc
 double oracle_bucket_sumsq(const float *v, int64_t n) { return bucket_sumsq(v, n); }
 
 namespace {
+constexpr int32_t kTypeSkip = 0x7fffffff;   // "this type has no weight scale": nothing is gathered / fitted for it
+
+// integer weight of a bucket with sum of squares s under the scale 2^ex: floor(s * 2^(23 - ex)), capped at 2^30 (a
+// scale taken from the previous round can be exceeded; the cap keeps every 64-bit total far from overflow)
+inline uint64_t stat_weight(double s, int ex) {
+  const double w = std::floor(std::ldexp(s, 23 - ex));
+  return (uint64_t)std::fmin(w, 1073741824.0);
+}
+
 const double kFiniteLimit = (double)std::numeric_limits<float>::max() * (double)std::numeric_limits<float>::max();
 
 // the norm DECODE uses for coordinate e of layer l: the header's (layer and vector scope) or the bucket's
@@ -420,9 +429,16 @@ inline float stored_norm(const uint8_t *msg, const Layout &lay, int l, int64_t e
 //             under bucket scope the largest bucket sum of the layer.
 // delta_out : || Vhat_{k,t+1/2} - Vhat_{k,t-1/2} ||^2 (the step-size term of eq. (general_stepsize)); prev = 0 if NULL.
 // returns 0, or 1 if a sum of squares is not finite or a norm exceeds the largest float.
+// Bucket scope can also gather the level fit's statistics while it quantizes (Alg. 1 runs lines 3-5 before the round's
+// vectors exist, so the estimate can only come from earlier vectors: those of the previous round, seen by the pass
+// that quantized them).  layer_exp[l] (NULL: gather nothing) is the weight scale of layer l's type, kTypeSkip for
+// "no scale yet"; stats_hist (L*257, added to) receives floor(sumsq_b * 2^(23 - exp)), capped at 2^30, at the grid
+// bin of every sampled coordinate as in oracle_fit_levels; stats_max (L, maximised) the largest sampled bucket sum,
+// +infinity if one is not finite.
 int32_t oracle_quantize(int32_t L, const int64_t *d, const int32_t *S, const float *const *levels,
                         const float *const *grads, uint64_t seed, uint32_t round, uint32_t node, int32_t scope,
-                        uint8_t *msg, const uint8_t *msg_prev, double *sumsq_out, double *delta_out) {
+                        uint8_t *msg, const uint8_t *msg_prev, double *sumsq_out, double *delta_out,
+                        const int32_t *layer_exp, uint64_t *stats_hist, double *stats_max) {
   const Layout lay = make_layout(L, d, S, scope);
   std::memset(msg, 0, (size_t)lay.message_bytes);
   int32_t status = 0;
@@ -467,6 +483,22 @@ int32_t oracle_quantize(int32_t L, const int64_t *d, const int32_t *S, const flo
           inv = rcp_floor(norm);
           *bucket_norm_slot(region, lay.planes[l], lay.ostride[l], e) = norm;
           if (sumsq_out && finite && s > sumsq_out[l]) sumsq_out[l] = s;
+          if (layer_exp && ((e / kBlock) % 4) == 0) {
+            const double sm = finite ? s : std::numeric_limits<double>::infinity();
+            if (sm > stats_max[l]) stats_max[l] = sm;
+            const uint64_t wfix = (layer_exp[l] == kTypeSkip || !finite) ? 0 : stat_weight(s, layer_exp[l]);
+            if (wfix != 0 && inv != 0.0f) {
+              const int64_t n = std::min<int64_t>(kBucket, d[l] - e);
+              for (int64_t q = e; q < e + n; ++q) {
+                if (((f2u(grads[l][q]) & 0x7FFFFFFFu) >> 20) == 0) continue;
+                const float uc = std::fmin(std::fabs(grads[l][q]) * inv, 1.0f);
+                int j = (int)(f2u(uc) >> 20) - kGridBase;
+                if (j < 0) j = 0;
+                if (j > kGridPoints - 1) j = kGridPoints - 1;
+                stats_hist[(size_t)l * kGridPoints + j] += wfix;
+              }
+            }
+          }
         }
         const Code code =
             quantize_coord(grads[l][e], inv, levels[l], S[l], draw16(seed, round, node, (uint32_t)l, (uint64_t)e));
@@ -789,6 +821,14 @@ void oracle_fit_dp(const uint64_t *W, int32_t S, float *lev_out) {
   }
 }
 
+namespace {
+inline bool any_weight(const std::vector<uint64_t> &W) {
+  for (uint64_t w : W)
+    if (w) return true;
+  return false;
+}
+}  // namespace
+
 int32_t oracle_fit_levels(int32_t L, const int64_t *d, const int32_t *layer_type, int32_t M, const int32_t *type_points,
                           int32_t K, int32_t scope, const float *const *grads /* K*L, entry k*L+l */,
                           float *const *levels_io, uint32_t *hist_out, uint64_t *pooled_out) {
@@ -824,7 +864,7 @@ int32_t oracle_fit_levels(int32_t L, const int64_t *d, const int32_t *layer_type
               if (((e0 / kBlock) % 4) != 0) continue;
               const int64_t n = std::min<int64_t>(kBucket, d[l] - e0);
               const double sv = bucket_sumsq(g + e0, n);
-              const uint64_t wfix = (uint64_t)std::floor(std::ldexp(sv, 23 - ex));
+              const uint64_t wfix = stat_weight(sv, ex);
               const float inv = rcp_floor(sqrt_floor(sv));
               if (wfix == 0 || inv == 0.0f) continue;
               for (int64_t e = e0; e < e0 + n; ++e) {
@@ -838,7 +878,7 @@ int32_t oracle_fit_levels(int32_t L, const int64_t *d, const int32_t *layer_type
             }
           }
         }
-        oracle_fit_dp(W.data(), type_points[m], levels_io[m]);
+        if (any_weight(W)) oracle_fit_dp(W.data(), type_points[m], levels_io[m]);   // no sampled mass: keep the levels
       }
       if (pooled_out) std::memcpy(pooled_out + (size_t)m * kGridPoints, W.data(), kGridPoints * sizeof(uint64_t));
     }
@@ -892,9 +932,39 @@ int32_t oracle_fit_levels(int32_t L, const int64_t *d, const int32_t *layer_type
           }
         }
       }
-      oracle_fit_dp(W.data(), type_points[m], levels_io[m]);
+      if (any_weight(W)) oracle_fit_dp(W.data(), type_points[m], levels_io[m]);   // no sampled mass: keep the levels
     }
     if (pooled_out) std::memcpy(pooled_out + (size_t)m * kGridPoints, W.data(), kGridPoints * sizeof(uint64_t));
+  }
+  return status;
+}
+
+// The level fit from statistics gathered by oracle_quantize (bucket scope) over the K nodes of the previous round:
+// pool the grid histograms of every type, fit (a type without a scale, or without any sampled mass, keeps its levels),
+// then derive the scale of the next gathering pass from the largest sampled bucket sum of the type.
+// hist: K*L*257 (entry (k*L + l)*257 + j), bmax: K*L, exp_io: M (in: the scale the histograms were gathered with).
+int32_t oracle_fit_from_stats(int32_t L, const int32_t *layer_type, int32_t M, const int32_t *type_points, int32_t K,
+                              const uint64_t *hist, const double *bmax, int32_t *exp_io, float *const *levels_io,
+                              uint64_t *pooled_out) {
+  int32_t status = 0;
+  for (int m = 0; m < M; ++m) {
+    std::vector<uint64_t> W(kGridPoints, 0);
+    double smax = 0.0;
+    bool finite = true;
+    for (int l = 0; l < L; ++l) {
+      if (layer_type[l] != m) continue;
+      for (int k = 0; k < K; ++k) {
+        const size_t idx = (size_t)k * L + l;
+        for (int j = 0; j < kGridPoints; ++j) W[j] += hist[idx * kGridPoints + j];
+        const double v = bmax[idx];
+        if (!(v >= 0.0) || !(v <= kFiniteLimit)) finite = false;
+        else if (v > smax) smax = v;
+      }
+    }
+    if (exp_io[m] != kTypeSkip && any_weight(W)) oracle_fit_dp(W.data(), type_points[m], levels_io[m]);
+    if (pooled_out) std::memcpy(pooled_out + (size_t)m * kGridPoints, W.data(), kGridPoints * sizeof(uint64_t));
+    if (!finite) status = 1;
+    exp_io[m] = (finite && smax > 0.0) ? std::ilogb(smax) : kTypeSkip;
   }
   return status;
 }

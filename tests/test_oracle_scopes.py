@@ -267,3 +267,52 @@ def test_fit_lowers_the_variance_in_bucket_scope(oracle):
         return tot
 
     assert exact_var(lev[0]) < 0.8 * exact_var(uniform_levels(S))
+
+
+def test_statistics_gathered_while_quantizing_equal_the_explicit_fit(oracle):
+    """Alg. 1 updates the levels before the round's vectors exist, so the estimate comes from the previous round:
+    the pass that quantizes (bucket scope) gathers the same pooled weights as the explicit fit on those vectors when it
+    is given the same scale, and the fit from the gathered statistics gives the same levels; the scale it hands on is
+    the exponent of the largest sampled bucket sum; without a scale nothing is gathered and the levels stay."""
+    S, K = 8, 2
+    sizes, types = [5000, 1300, 0, 70000], [0, 0, 1, 1]
+    L = len(sizes)
+    rng = np.random.default_rng(9)
+    g = [[(rng.standard_t(3, s) * 10.0 ** rng.uniform(-3, 1)).astype(np.float32) for s in sizes] for _ in range(K)]
+    flat = [g[k][l] for k in range(K) for l in range(L)]
+    lev0 = [uniform_levels(S), uniform_levels(S)]
+    want_lev, _, want_pooled, _ = oracle.fit_levels(sizes, types, [S, S], K, flat, lev0, scope=BUCKET)
+    # the explicit fit's scale: exponent of the largest sampled bucket sum of the type
+    exps = []
+    for m in range(2):
+        smax = 0.0
+        for k in range(K):
+            for l in range(L):
+                if types[l] != m:
+                    continue
+                for b in range(0, sizes[l], 128):
+                    if (b // 256) % 4 == 0:
+                        smax = max(smax, oracle.bucket_sumsq(g[k][l][b: b + 128]))
+        exps.append(int(np.floor(np.log2(smax))))
+    lev_l = [lev0[types[l]] for l in range(L)]
+    hist = np.zeros((K, L, 257), np.uint64)
+    bmax = np.zeros((K, L))
+    for k in range(K):
+        plain = oracle.quantize(sizes, [S] * L, lev_l, g[k], 5, 1, k, scope=BUCKET)
+        out = oracle.quantize(sizes, [S] * L, lev_l, g[k], 5, 1, k, scope=BUCKET, stats_exp=[exps[t] for t in types])
+        assert np.array_equal(plain[0], out[0]) and plain[2] == out[2]          # gathering does not change the message
+        hist[k], bmax[k] = out[4], out[5]
+    lev, pooled, new_exps, st = oracle.fit_from_stats(types, [S, S], K, hist, bmax, exps, lev0)
+    assert st == 0 and np.array_equal(pooled, want_pooled)
+    assert all(np.array_equal(a, b) for a, b in zip(lev, want_lev))
+    assert list(new_exps) == exps
+    # no scale yet: nothing gathered, levels kept, but the next scale is produced
+    out = oracle.quantize(sizes, [S] * L, lev_l, g[0], 5, 1, 0, scope=BUCKET, stats_exp=[oracle.TYPE_SKIP] * L)
+    assert out[4].sum() == 0 and out[5].max() > 0
+    h1 = np.zeros((K, L, 257), np.uint64)
+    lev, pooled, e2, _ = oracle.fit_from_stats(types, [S, S], K, h1, bmax, [oracle.TYPE_SKIP] * 2, lev0)
+    assert all(np.array_equal(a, b) for a, b in zip(lev, lev0)) and list(e2) == exps
+    # a scale from an earlier, much smaller round: weights hit the cap 2^30 instead of overflowing
+    out = oracle.quantize(sizes, [S] * L, lev_l, g[0], 5, 1, 0, scope=BUCKET, stats_exp=[e - 40 for e in [exps[t] for t in types]])
+    sampled = sum(int(np.sum((np.arange(s) // 256) % 4 == 0)) for s in sizes)
+    assert (1 << 30) <= int(out[4].max()) and int(out[4].sum()) <= sampled * (1 << 30)
