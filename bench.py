@@ -137,7 +137,9 @@ def main() -> int:
         state["t"] += 1
         t, cur = state["t"], state["cur"]
         if w.adaptive:
-            ctx.fit_levels(gptrs, t)
+            # bucket scope: after the first round the fit uses the statistics gathered by the previous quantize pass
+            # (the order of Alg. 1: the levels are updated before the round's vectors exist) and reads no gradient
+            ctx.fit_levels(gptrs if (not bucket or t == 1) else None, t)
         ctx.quantize_all(gptrs, t, msg[cur], msg[1 - cur] if (t > 1 and not alt) else None)
         if alt:
             ctx.step_alt(msg[cur], x1p, yp, xhp, alt_sums, eta, args.q_hat, xnp)
@@ -207,8 +209,8 @@ def main() -> int:
 
     ms_per_step = total_ms / args.steps
     grad_bytes = 4.0 * K * d
-    if bucket:   # the norms are computed inside the quantize pass; the fit is two quarter-data passes
-        alg_round = alg["k_quantize"] + alg[dec] + ((alg["k_bucket_max"] + alg["k_bucket_hist"]) if w.adaptive else 0.0)
+    if bucket:   # norms and fit statistics are computed inside the quantize pass
+        alg_round = alg["k_quantize"] + alg[dec]
     else:
         alg_round = sum(alg[n] for n in (("k_sumsq<true>" if w.adaptive else "k_sumsq<false>"), "k_quantize", dec))
     out = {

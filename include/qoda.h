@@ -77,7 +77,8 @@ typedef struct {
 } qoda_config;
 
 /* Create / destroy.  qoda_create allocates all device scratch (a few MB plus 8 bytes per 16384 coordinates per
- * node; the fit's histogram, 8 KB per (node, layer), is allocated on the first qoda_fit_levels).  Levels start
+ * node; the fit's histogram, 8 KB per (node, layer), is allocated on the first qoda_fit_levels, under bucket scope
+ * at once).  Levels start
  * uniform: l_j = j/(S-1).  On failure *out is NULL. */
 int qoda_create(const qoda_config *cfg, qoda_ctx **out);
 int qoda_destroy(qoda_ctx *ctx);
@@ -100,7 +101,15 @@ int qoda_get_levels(qoda_ctx *ctx, int32_t type, float *levels_host, void *strea
  * all zero keeps its levels.  grad_dev: host array [K*L], entry k*L+l.
  * Side effect: the per-(node, layer) norms of these vectors stay in the context tagged with `round`; a following
  * qoda_quantize / qoda_quantize_all with the same `round` and the same pointers reuses them instead of reading
- * the vectors a second time.  The caller must not change the vectors in between. */
+ * the vectors a second time.  The caller must not change the vectors in between.
+ * Bucket scope: every bucket is a vector of its own (weight = its sum of squares, normalisation = its norm); with
+ * grad_dev the fit takes two passes over the sampled quarter of these vectors (scale of the weights, then the weighted
+ * grid histogram).  With grad_dev == NULL (bucket scope only) it reads nothing: it uses the statistics that the last
+ * quantize pass of every node gathered while it quantized -- Alg. 1 runs lines 3-5 before the round's vectors exist,
+ * so the estimate comes from the previous round's vectors -- and hands the next pass its weight scale (exponent of the
+ * largest sampled bucket sum per type; weights are floor(sum * 2^(23 - exponent)) capped at 2^30).  A pass gathers a
+ * histogram only once some fit has produced a scale: call the fit with vectors once (or with NULL twice, the first of
+ * which only sets the scale), then with NULL at every later update step. */
 int qoda_fit_levels(qoda_ctx *ctx, const float *const *grad_dev, uint32_t round, void *stream);
 
 /* ENCODE(Q(V_{k,t+1/2})), Alg. 1 line 12 (Sec. 2.2, 3.1, 3.2): per-layer L2 norm, u = min(|v| / ||v||, 1), level

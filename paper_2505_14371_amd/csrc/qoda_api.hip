@@ -43,6 +43,7 @@ struct qoda_ctx {
   int *d_type_exp = nullptr;
   short *d_dp_arg = nullptr;
   long long *d_dp_arg_off = nullptr;
+  int *d_type_exp_next = nullptr;   // bucket scope: the weight scales the next gathering pass will use
   unsigned long long *d_index_counts = nullptr;   // [M*256], allocated by the first qoda_index_counts
   // device pointer tables (uploaded when their host shadow changes)
   struct Table {
@@ -195,7 +196,7 @@ int check_msg_ptrs(qoda_ctx *c, const void *const *p, size_t n, const char *what
 
 void free_all(qoda_ctx *c) {
   void *ptrs[] = {c->d_meta, c->d_tiles, c->d_stiles, c->d_empty, c->d_type_points, c->d_partial, c->d_dpartial, c->d_sumsq, c->d_delta,
-                  c->d_norm, c->d_inv, c->d_lev, c->d_rgap, c->d_eta, c->d_lut, c->d_hist, c->d_status, c->d_pooled, c->d_index_counts,
+                  c->d_norm, c->d_inv, c->d_lev, c->d_rgap, c->d_eta, c->d_lut, c->d_hist, c->d_status, c->d_pooled, c->d_index_counts, c->d_type_exp_next,
                   c->d_type_exp, c->d_dp_arg, c->d_dp_arg_off, c->t_grad.dev, c->t_msg.dev, c->t_prev.dev, c->t_in.dev,
                   c->t_x1.dev, c->t_y.dev, c->t_xh.dev, c->t_xn.dev, c->t_mean.dev};
   for (void *p : ptrs)
@@ -227,7 +228,13 @@ int quantize_impl(qoda_ctx *c, int node0, int nnodes, const float *const *grad_f
     for (int k = node0; k < node0 + nnodes && cached; ++k)
       for (int l = 0; l < c->L; ++l)
         if (c->norms_grad[(size_t)k * c->L + l] != grad_full[(size_t)k * c->L + l]) { cached = false; break; }
-  if (c->scope == kScopeBucket) cached = true;   // the bucket norms are computed by the quantize kernel itself
+  if (c->scope == kScopeBucket) {
+    cached = true;   // the bucket norms are computed by the quantize kernel itself, which also gathers the fit's
+                     // statistics of these nodes: their histograms and running maxima start from zero
+    const size_t n0 = (size_t)node0 * c->L, nn = (size_t)nnodes * c->L;
+    LAUNCH(c, kIdZero, s, launch_zero_u32(c->d_hist + n0 * kHistBins, nn * kHistBins, s));
+    LAUNCH(c, kIdZero, s, launch_zero_u32(reinterpret_cast<unsigned int *>(c->d_sumsq + n0), 2 * nn, s));
+  }
   if (!cached) {
     c->norms_valid = false;   // the cached norms of these nodes are about to be overwritten
     int rc = run_norm_pass(c, a, false, s);
@@ -329,6 +336,10 @@ int qoda_create(const qoda_config *cfg, qoda_ctx **out) {
   A(dev_alloc(&c->d_status, 1));
   A(dev_alloc(&c->d_pooled, (size_t)c->M * kGridPoints));
   A(dev_alloc(&c->d_type_exp, (size_t)c->M));
+  if (c->scope == kScopeBucket) {   // the quantize pass gathers the fit's statistics itself
+    A(dev_alloc(&c->d_type_exp_next, (size_t)c->M));
+    A(dev_alloc(&c->d_hist, KL * kHistBins));
+  }
   A(dev_alloc(&c->d_dp_arg, (size_t)arg_total));
   A(dev_alloc(&c->d_dp_arg_off, (size_t)c->M));
   qoda_ctx::Table *tabs[] = {&c->t_grad, &c->t_msg, &c->t_prev, &c->t_in, &c->t_x1, &c->t_y, &c->t_xh, &c->t_xn, &c->t_mean};
@@ -341,6 +352,10 @@ int qoda_create(const qoda_config *cfg, qoda_ctx **out) {
   if (e == hipSuccess && c->n_empty) A(hipMemcpy(c->d_empty, empty.data(), c->n_empty * sizeof(int), hipMemcpyHostToDevice));
   if (e == hipSuccess) A(hipMemcpy(c->d_type_points, c->type_points.data(), c->M * sizeof(int), hipMemcpyHostToDevice));
   if (e == hipSuccess) A(hipMemcpy(c->d_dp_arg_off, arg_off.data(), c->M * sizeof(long long), hipMemcpyHostToDevice));
+  if (e == hipSuccess) {   // no weight scale yet: nothing is gathered until a fit has produced one
+    const std::vector<int> skip((size_t)c->M, kTypeSkip);
+    A(hipMemcpy(c->d_type_exp, skip.data(), c->M * sizeof(int), hipMemcpyHostToDevice));
+  }
   if (e == hipSuccess) A(hipMemset(c->d_status, 0, sizeof(unsigned int)));
   if (e == hipSuccess) A(hipMemset(c->d_delta, 0, c->K * sizeof(double)));
   if (e == hipSuccess) A(hipMemset(c->d_pooled, 0, (size_t)c->M * kGridPoints * sizeof(unsigned long long)));
@@ -421,6 +436,20 @@ int qoda_get_levels(qoda_ctx *c, int32_t type, float *lev, void *stream) {
 int qoda_fit_levels(qoda_ctx *c, const float *const *grad_dev, uint32_t round, void *stream) {
   if (!c) return QODA_EINVAL;
   const size_t KL = (size_t)c->K * c->L;
+  if (!grad_dev && c->scope == kScopeBucket) {
+    // from the statistics the last quantize pass of every node gathered: pool, fit (with the scale they were gathered
+    // under), then the scale for the next pass from the gathered maxima
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Dev a = base_args(c);
+    a.round = round;
+    Dev nx = a;
+    nx.type_exp = c->d_type_exp_next;
+    LAUNCH(c, kIdFitTypemax, s, launch_fit_typemax(nx, s));   // also clears the pooled weights
+    LAUNCH(c, kIdFitPool, s, launch_fit_pool_b(a, s));
+    LAUNCH(c, kIdFitDp, s, launch_fit_dp(a, s));
+    HIP_TRY(c, hipMemcpyAsync(c->d_type_exp, c->d_type_exp_next, c->M * sizeof(int), hipMemcpyDeviceToDevice, s));
+    return QODA_OK;
+  }
   int rc = check_layer_ptrs(c, reinterpret_cast<const void *const *>(grad_dev), KL, "qoda_fit_levels: grad_dev", true);
   if (rc) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);

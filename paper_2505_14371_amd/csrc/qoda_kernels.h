@@ -109,6 +109,7 @@ hipError_t launch_index_hist(const Dev &a, unsigned int planes_mask, hipStream_t
 hipError_t launch_alt_finalize(const Dev &a, hipStream_t s);
 hipError_t launch_bucket_max(const Dev &a, hipStream_t s);    // bucket scope: a.sumsq must be zero
 hipError_t launch_bucket_hist(const Dev &a, hipStream_t s);   // bucket scope: grid histograms, then pooling
+hipError_t launch_fit_pool_b(const Dev &a, hipStream_t s);    // bucket scope: pooling of gathered grid histograms
 hipError_t launch_fit_typemax(const Dev &a, hipStream_t s);
 hipError_t launch_fit_pool(const Dev &a, hipStream_t s);
 hipError_t launch_fit_dp(const Dev &a, hipStream_t s);

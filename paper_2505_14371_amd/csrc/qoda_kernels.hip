@@ -53,6 +53,41 @@ __device__ float rcp_floor(float x) {
   return r;
 }
 
+// The same two functions for the per-bucket norms, where they run once per 128 coordinates and their cost shows:
+// straight-line code for arguments in a comfortable range (sums of squares in [2^-200, 2^200]), the general
+// routines otherwise.  Both return exactly what sqrt_floor / rcp_floor return (the definitions are by exact
+// comparisons, so any way of finding the largest float that passes them gives the same bits).
+__device__ __forceinline__ void norm_and_inverse(double s, float &n_out, float &r_out) {
+  const long long bits = __double_as_longlong(s);
+  const int e = (int)((bits >> 52) & 0x7FF) - 1023;
+  if (e < -200 || e > 200) {   // zero, tiny, huge or not a number: the general path
+    n_out = sqrt_floor(s);
+    r_out = rcp_floor(n_out);
+    return;
+  }
+  // s = sp * 4^k with sp in [1, 4): root in single precision, then the candidates around it are tested exactly
+  const int k = e >> 1;
+  const double sp = __longlong_as_double(bits - ((long long)(2 * k) << 52));
+  const float r0 = __builtin_sqrtf((float)sp);   // within one unit of the last place of the true root of sp
+  float n = u2f(f2u(r0) + 1u);
+#pragma unroll
+  for (int it = 0; it < 3; ++it) {
+    const double nd = (double)n;
+    if (nd * nd > sp) n = u2f(f2u(n) - 1u);
+  }
+  n = u2f(f2u(n) + ((unsigned int)k << 23));   // times 2^k: exact, the result is a normal number
+  // reciprocal: hardware estimate, then the same exact test on the candidates around it
+  const float q0 = __builtin_amdgcn_rcpf(n);
+  float r = u2f(f2u(q0) + 1u);
+  const double nd = (double)n;
+#pragma unroll
+  for (int it = 0; it < 3; ++it) {
+    if (nd * (double)r > 1.0) r = u2f(f2u(r) - 1u);
+  }
+  n_out = n;
+  r_out = r;
+}
+
 // Fixed halving tree over the 256 slots: p[i] += p[i+h], h = 128 .. 1.  The two cross-wave steps are one pass
 // through shared memory, the six in-wave steps are shuffles (lane i < h adds lane i + h, exactly the tree).
 // The total is valid in thread 0 only.
@@ -492,14 +527,18 @@ struct BucketWave {
   float norm[16];       // [8*half + block] of the current octet
   float inv[16];
   float pnorm[16];      // the previous message's norms of the same buckets
+  unsigned int wfix[16];   // fit statistics: integer weight of the bucket (0: gathers nothing)
 };
 
 // Sums of squares of the 16 buckets of one octet -> norm, inv (shared memory) and the octet's norm trailer.
 // Lane L finishes bucket q = L/4 (block q/2, half q%2): it adds 8 consecutive lane sums by the in-order binary
 // tree, then the four lanes of the quad combine (neighbour, then pair), which continues the same tree.
+// ex: weight scale of the layer's type for the fit statistics (kTypeSkip: none); best: running maximum of the bit
+// patterns of the lane's sampled bucket sums (blocks 0 and 4 of the octet, i.e. every fourth block of the layer).
 template <bool FAST>
 __device__ __forceinline__ void bucket_norms(const Dev &a, const LayerMeta &m, long long O, const float *__restrict__ v,
-                                             float *trailer, const float *prev_trailer, BucketWave &bw, int i) {
+                                             float *trailer, const float *prev_trailer, BucketWave &bw, int i, int ex,
+                                             unsigned long long &best) {
 #pragma unroll
   for (int bb = 0; bb < 8; ++bb) {
     const long long e = (O * 8 + bb) * kBlockCoords + 4 * i;
@@ -529,12 +568,19 @@ __device__ __forceinline__ void bucket_norms(const Dev &a, const LayerMeta &m, l
   s = s + __shfl_xor(s, 2, 64);
   const double lim = (double)kFltMax * (double)kFltMax;
   const bool finite = (s >= 0.0) && (s <= lim);
-  const float n = finite ? sqrt_floor(s) : 0.0f;
-  const float rinv = rcp_floor(n);
+  float n = 0.0f, rinv = 0.0f;
+  if (finite) norm_and_inverse(s, n, rinv);
   if (!finite) atomicOr(a.status, 1u);
+  if ((bb & 3) == 0) {
+    const unsigned long long bits = finite ? (unsigned long long)__double_as_longlong(s) : 0x7FF0000000000000ull;
+    best = bits > best ? bits : best;
+  }
+  unsigned int wf = 0u;
+  if (ex != kTypeSkip && finite && rinv != 0.0f) wf = (unsigned int)fmin(floor(ldexp(s, 23 - ex)), 1073741824.0);
   if (r == 0) {
     bw.norm[8 * hf + bb] = n;
     bw.inv[8 * hf + bb] = rinv;
+    bw.wfix[8 * hf + bb] = wf;
     trailer[8 * hf + bb] = n;
   }
   if (i < 16) bw.pnorm[i] = prev_trailer ? prev_trailer[i] : 0.0f;
@@ -548,7 +594,8 @@ template <int C1>
 __device__ __forceinline__ void quantize_block_b(const float (&x)[4], const unsigned int (&o)[4], int half, float inv,
                                                  float norm, float pnorm, const unsigned char *lut, const float4 *tab,
                                                  const float *tprev, unsigned int (&D)[C1],
-                                                 const unsigned int (&Dp)[C1], float &acc) {
+                                                 const unsigned int (&Dp)[C1], float &acc, unsigned int wfix,
+                                                 unsigned long long *lh) {
   float u[4];
   int tau[4];
   float4 lv[4];
@@ -556,6 +603,15 @@ __device__ __forceinline__ void quantize_block_b(const float (&x)[4], const unsi
   for (int j = 0; j < 4; ++j) {
     u[j] = __builtin_amdgcn_fmed3f(fabsf(x[j]) * inv, 0.0f, 1.0f);
     tau[j] = lut[f2u(u[j]) >> 20];
+  }
+  if (wfix != 0u) {   // a sampled block of a bucket with weight: the fit's grid histogram (integer adds)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (((f2u(x[j]) & 0x7FFFFFFFu) >> 20) == 0u) continue;   // also skips the +0 padding past the end of the layer
+      int g = (int)(f2u(u[j]) >> 20) - kGridBase;
+      g = max(0, min(g, kGridPoints - 1));
+      atomicAdd(&lh[g], (unsigned long long)wfix);
+    }
   }
 #pragma unroll
   for (int j = 0; j < 4; ++j) lv[j] = tab[tau[j]];
@@ -586,13 +642,14 @@ __device__ __forceinline__ void quantize_octet_b(const Dev &a, const LayerMeta &
                                                  const float *__restrict__ v, unsigned char *body,
                                                  const unsigned char *prevbody, const unsigned char *lut,
                                                  const float4 *tab, const float *tprev, BucketWave &bw, int i,
-                                                 float &acc) {
+                                                 float &acc, int ex, unsigned long long &best,
+                                                 unsigned long long *lh) {
   constexpr long long OS = 256 * C1 + 64;   // bytes per octet: codes, then the 16 bucket norms
   const unsigned int k0 = (unsigned int)a.seed, k1 = (unsigned int)(a.seed >> 32);
   unsigned char *oct = body + O * OS;
   const unsigned char *poct = prevbody ? prevbody + O * OS : nullptr;
   bucket_norms<FAST>(a, m, O, v, reinterpret_cast<float *>(oct + 256 * C1),
-                     poct ? reinterpret_cast<const float *>(poct + 256 * C1) : nullptr, bw, i);
+                     poct ? reinterpret_cast<const float *>(poct + 256 * C1) : nullptr, bw, i, ex, best);
   unsigned int D[C1], Dp[C1];
 #pragma unroll
   for (int r = 0; r < C1; ++r) { D[r] = 0u; Dp[r] = 0u; }
@@ -627,8 +684,10 @@ __device__ __forceinline__ void quantize_octet_b(const Dev &a, const LayerMeta &
       const float2 pn = *reinterpret_cast<const float2 *>(&bw.pnorm[hf8 + 2 * pp]);
       unsigned int o[4];
       philox4x32_10((unsigned int)((B0 >> 1) * 64 + i), (unsigned int)l, a.round, (unsigned int)k, k0, k1, o);
-      quantize_block_b<C1>(x0, o, 0, ii.x, nn.x, pn.x, lut, tab, tprev, D, Dp, acc);
-      quantize_block_b<C1>(x1, o, 1, ii.y, nn.y, pn.y, lut, tab, tprev, D, Dp, acc);
+      // blocks 0 and 4 of the octet (first block of pairs 0 and 2) are the sampled ones
+      const unsigned int wf = ((pp & 1) == 0) ? bw.wfix[hf8 + 2 * pp] : 0u;
+      quantize_block_b<C1>(x0, o, 0, ii.x, nn.x, pn.x, lut, tab, tprev, D, Dp, acc, wf, lh);
+      quantize_block_b<C1>(x1, o, 1, ii.y, nn.y, pn.y, lut, tab, tprev, D, Dp, acc, 0u, lh);
     }
     shift_out_pair<C1>(Dp);
   }
@@ -642,8 +701,12 @@ __global__ void __launch_bounds__(kThreads) k_quantize_b(Dev a) {
   __shared__ float tprev[2 * kMaxPoints];   // +-level of the previous message, indexed by code = sign | h << 1
   __shared__ double red[kThreads];
   __shared__ BucketWave bws[kThreads / 64];
-  const int2 tile = a.tiles[blockIdx.x];
-  const int l = tile.x;
+  __shared__ unsigned long long lh[kGridPoints];        // fit statistics of this run: weighted grid histogram
+  __shared__ unsigned long long wmax[kThreads / 64];
+  // a workgroup takes a run of up to kSuperTile consecutive tiles of one layer: the tables are set up and the
+  // statistics flushed once per run
+  const int4 st = a.stiles[blockIdx.x];
+  const int l = st.x;
   const int k = a.node0 + blockIdx.y;
   const LayerMeta m = a.meta[l];
   if (m.planes != C1) return;
@@ -652,12 +715,13 @@ __global__ void __launch_bounds__(kThreads) k_quantize_b(Dev a) {
   const float *rg = a.rgap + (size_t)m.type * kMaxPoints;
   reinterpret_cast<unsigned int *>(lut)[t] = reinterpret_cast<const unsigned int *>(a.lut + (size_t)m.type * kLutSize)[t];
   const unsigned char *prevmsg = (a.prev != nullptr) ? a.prev[k] : nullptr;
+  const int ex = a.type_exp[m.type];
   if (t < m.S) {
     const float lj = lev[t];
     const float ln = (t + 1 < m.S) ? lev[t + 1] : __builtin_inff();
     tab[t] = make_float4(lj, (t + 1 < m.S) ? rg[t] : 0.0f, ln, 0.0f);
   }
-  if (tile.y == 0) {   // header of this layer: the norm entry is unused under bucket scope
+  if (st.y == 0) {   // header of this layer: the norm entry is unused under bucket scope
     float *h = reinterpret_cast<float *>(a.msg[k] + m.hdr_off);
     for (int j = t; j <= m.S; j += kThreads) h[j] = (j == 0) ? 0.0f : lev[j - 1];
   }
@@ -670,6 +734,7 @@ __global__ void __launch_bounds__(kThreads) k_quantize_b(Dev a) {
     }
     tprev[c] = pl;
   }
+  for (int j = t; j < kGridPoints; j += kThreads) lh[j] = 0ull;
   __syncthreads();
   const int w = __builtin_amdgcn_readfirstlane(t >> 6);
   const int i = t & 63;
@@ -677,17 +742,41 @@ __global__ void __launch_bounds__(kThreads) k_quantize_b(Dev a) {
   unsigned char *body = a.msg[k] + m.body_off;
   const unsigned char *prevbody = prevmsg ? prevmsg + m.body_off : nullptr;
   const long long noct = (m.nblk + 7) >> 3;
-  float acc = 0.0f;
-  for (int oo = 0; oo < 2; ++oo) {
-    const long long O = (long long)tile.y * 8 + w * 2 + oo;
-    if (O >= noct) break;
-    if ((O + 1) * 2048 <= m.d)
-      quantize_octet_b<C1, true>(a, m, l, k, O, v, body, prevbody, lut, tab, tprev, bws[w], i, acc);
-    else
-      quantize_octet_b<C1, false>(a, m, l, k, O, v, body, prevbody, lut, tab, tprev, bws[w], i, acc);
+  unsigned long long best = 0ull;
+  for (int cc = 0; cc < st.z; ++cc) {
+    const int chunk = st.y + cc;
+    float acc = 0.0f;
+    for (int oo = 0; oo < 2; ++oo) {
+      const long long O = (long long)chunk * 8 + w * 2 + oo;
+      if (O >= noct) break;
+      if ((O + 1) * 2048 <= m.d)
+        quantize_octet_b<C1, true>(a, m, l, k, O, v, body, prevbody, lut, tab, tprev, bws[w], i, acc, ex, best, lh);
+      else
+        quantize_octet_b<C1, false>(a, m, l, k, O, v, body, prevbody, lut, tab, tprev, bws[w], i, acc, ex, best, lh);
+    }
+    const double total = block_tree((double)acc, red);
+    if (t == 0) a.dpartial[(size_t)k * a.G + m.first_chunk + chunk] = total;
   }
-  const double total = block_tree((double)acc, red);
-  if (t == 0) a.dpartial[(size_t)k * a.G + blockIdx.x] = total;
+  // statistics of the run: largest sampled bucket sum (bit pattern of a non-negative double) and the histogram
+#pragma unroll
+  for (int sh = 1; sh < 64; sh *= 2) {
+    const unsigned long long other = __shfl_xor(best, sh, 64);
+    best = other > best ? other : best;
+  }
+  if (i == 0) wmax[w] = best;
+  __syncthreads();
+  const size_t idx = (size_t)k * a.L + l;
+  if (t == 0) {
+    for (int q = 1; q < kThreads / 64; ++q) best = wmax[q] > best ? wmax[q] : best;
+    if (best) atomicMax(reinterpret_cast<unsigned long long *>(a.sumsq) + idx, best);
+  }
+  if (ex != kTypeSkip) {
+    unsigned long long *gh = reinterpret_cast<unsigned long long *>(a.hist + idx * kHistBins);
+    for (int j = t; j < kGridPoints; j += kThreads) {
+      const unsigned long long c = lh[j];
+      if (c) atomicAdd(&gh[j], c);
+    }
+  }
 }
 
 // delta_k: slot j takes the node's tiles j, j+256, ... (all layers, in order), then the halving tree.
@@ -1175,6 +1264,7 @@ __global__ void __launch_bounds__(kFitThreads) k_fit_dp(Dev a) {
     }
   }
   __syncthreads();
+  if (row[kGridPoints].p0 == 0.0) return;   // no sampled mass at all: the type keeps its levels
   const double inf = __longlong_as_double(0x7FF0000000000000ll);
   short *arg = a.dp_arg + a.dp_arg_off[mtype];
   if (S > 2) {
@@ -1294,14 +1384,15 @@ hipError_t launch_quantize(const Dev &a, unsigned int planes_mask, hipStream_t s
   if (a.G == 0 || a.nnodes == 0) return hipSuccess;
   const dim3 grid(a.G, a.nnodes), block(kThreads);
   if (a.scope == kScopeBucket) {
-    if (planes_mask & (1u << 2)) hipLaunchKernelGGL(k_quantize_b<2>, grid, block, 0, s, a);
-    if (planes_mask & (1u << 3)) hipLaunchKernelGGL(k_quantize_b<3>, grid, block, 0, s, a);
-    if (planes_mask & (1u << 4)) hipLaunchKernelGGL(k_quantize_b<4>, grid, block, 0, s, a);
-    if (planes_mask & (1u << 5)) hipLaunchKernelGGL(k_quantize_b<5>, grid, block, 0, s, a);
-    if (planes_mask & (1u << 6)) hipLaunchKernelGGL(k_quantize_b<6>, grid, block, 0, s, a);
-    if (planes_mask & (1u << 7)) hipLaunchKernelGGL(k_quantize_b<7>, grid, block, 0, s, a);
-    if (planes_mask & (1u << 8)) hipLaunchKernelGGL(k_quantize_b<8>, grid, block, 0, s, a);
-    if (planes_mask & (1u << 9)) hipLaunchKernelGGL(k_quantize_b<9>, grid, block, 0, s, a);
+    const dim3 rgrid(a.GS, a.nnodes);   // runs of tiles
+    if (planes_mask & (1u << 2)) hipLaunchKernelGGL(k_quantize_b<2>, rgrid, block, 0, s, a);
+    if (planes_mask & (1u << 3)) hipLaunchKernelGGL(k_quantize_b<3>, rgrid, block, 0, s, a);
+    if (planes_mask & (1u << 4)) hipLaunchKernelGGL(k_quantize_b<4>, rgrid, block, 0, s, a);
+    if (planes_mask & (1u << 5)) hipLaunchKernelGGL(k_quantize_b<5>, rgrid, block, 0, s, a);
+    if (planes_mask & (1u << 6)) hipLaunchKernelGGL(k_quantize_b<6>, rgrid, block, 0, s, a);
+    if (planes_mask & (1u << 7)) hipLaunchKernelGGL(k_quantize_b<7>, rgrid, block, 0, s, a);
+    if (planes_mask & (1u << 8)) hipLaunchKernelGGL(k_quantize_b<8>, rgrid, block, 0, s, a);
+    if (planes_mask & (1u << 9)) hipLaunchKernelGGL(k_quantize_b<9>, rgrid, block, 0, s, a);
     return hipGetLastError();
   }
   if (planes_mask & (1u << 2)) hipLaunchKernelGGL(k_quantize<2>, grid, block, 0, s, a);
@@ -1398,6 +1489,11 @@ hipError_t launch_bucket_max(const Dev &a, hipStream_t s) {
 hipError_t launch_bucket_hist(const Dev &a, hipStream_t s) {
   if (a.GS == 0) return hipSuccess;
   hipLaunchKernelGGL(k_bucket_hist, dim3(a.GS, a.K), dim3(kThreads), 0, s, a);
+  hipLaunchKernelGGL(k_fit_pool_b, dim3(a.L, a.K), dim3(kThreads), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_fit_pool_b(const Dev &a, hipStream_t s) {
   hipLaunchKernelGGL(k_fit_pool_b, dim3(a.L, a.K), dim3(kThreads), 0, s, a);
   return hipGetLastError();
 }

@@ -179,10 +179,11 @@ class Context:
         self._check(self._lib.qoda_get_levels(self._h, type_, lev.ctypes.data_as(C.POINTER(C.c_float)), _stream(stream)))
         return lev
 
-    def fit_levels(self, grads: Sequence, round_: int, stream=None):
-        """grads: K*L device tensors/addresses, entry k*L+l."""
-        assert len(grads) == self.K * self.L
-        self._check(self._lib.qoda_fit_levels(self._h, _ptrs(grads), round_, _stream(stream)))
+    def fit_levels(self, grads: Optional[Sequence], round_: int, stream=None):
+        """grads: K*L device tensors/addresses, entry k*L+l; None (bucket scope): fit from the statistics gathered by
+        the last quantize pass."""
+        assert grads is None or len(grads) == self.K * self.L
+        self._check(self._lib.qoda_fit_levels(self._h, None if grads is None else _ptrs(grads), round_, _stream(stream)))
 
     # -- hot path
     def quantize(self, node: int, grads: Sequence, round_: int, msg, msg_prev=None, stream=None):

@@ -158,3 +158,56 @@ def test_nonfinite_bucket_is_flagged():
     m.quantize_all(1)
     assert m.ctx.status() == qoda.ENONFINITE
     assert m.ctx.status() == qoda.OK
+
+
+def test_fit_from_statistics_gathered_by_the_quantize_pass(oracle):
+    """Bucket scope, the literal order of Alg. 1: the levels for round t come from the vectors of round t-1, whose
+    statistics the quantize pass gathered.  Round 1 bootstraps the weight scale with the explicit fit; afterwards
+    qoda_fit_levels(NULL) reads no gradient.  The vectors grow threefold per round, so the scale always lags."""
+    sizes = [5000, 1300, 0, 70000, 16384 * 9 + 77, 3]
+    types = [0, 0, 1, 1, 2, 2]
+    L, K, S, M = len(sizes), 3, 8, 3
+    m = gm(sizes, types, [S] * M, K, seed=12, norm_scope=BUCKET)
+    rng = np.random.default_rng(5)
+    levels = [helpers.uniform_levels(S) for _ in range(M)]
+    prev = [None] * K
+    exps = None
+    hist = bmax = None
+    for t in range(1, 5):
+        grads = [[(rng.standard_t(3, s) * 3.0 ** t * 10.0 ** rng.uniform(-3, 0)).astype(np.float32) for s in sizes]
+                 for _ in range(K)]
+        m.set_grads(grads)
+        if t == 1:
+            m.fit(1)                                                     # explicit: two quarter passes over these vectors
+            flat = [grads[k][l] for k in range(K) for l in range(L)]
+            levels, _, pooled, st = oracle.fit_levels(sizes, types, [S] * M, K, flat, levels, scope=BUCKET)
+            # its scale, from the oracle's own gathering routine run without a scale
+            b0 = np.stack([oracle.quantize(sizes, [S] * L, [levels[ty] for ty in types], grads[k], 12, 0, k, scope=BUCKET,
+                                           stats_exp=[oracle.TYPE_SKIP] * L)[5] for k in range(K)])
+            _, _, exps, _ = oracle.fit_from_stats(types, [S] * M, K, np.zeros((K, L, 257), np.uint64), b0,
+                                                  [oracle.TYPE_SKIP] * M, levels)
+        else:
+            m.ctx.fit_levels(None, t)                                    # from the statistics of round t-1
+            levels, pooled, exps, st = oracle.fit_from_stats(types, [S] * M, K, hist, bmax, exps, levels)
+        assert st == 0
+        assert np.array_equal(m.ctx.read_buffer(qoda.BUF_POOLED), pooled), t
+        for ty in range(M):
+            assert np.array_equal(m.ctx.get_levels(ty), levels[ty]), (t, ty)
+        if t == 3:
+            m.quantize_each(t)                                           # node by node gathers the same
+        else:
+            m.quantize_all(t)
+        msgs = m.messages()
+        lev_l = [levels[ty] for ty in types]
+        hist = np.zeros((K, L, 257), np.uint64)
+        bmax = np.zeros((K, L))
+        want = []
+        for k in range(K):
+            out = oracle.quantize(sizes, [S] * L, lev_l, grads[k], 12, t, k, msg_prev=prev[k], scope=BUCKET,
+                                  stats_exp=[int(exps[ty]) for ty in types])
+            assert np.array_equal(msgs[k], out[0]), (t, k)
+            hist[k], bmax[k] = out[4], out[5]
+            want.append(out[0])
+        prev = want
+        m.step()
+    assert not np.array_equal(levels[0], helpers.uniform_levels(S))
