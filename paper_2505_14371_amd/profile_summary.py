@@ -27,12 +27,21 @@ def _one(pattern: str) -> str:
 
 
 def _short(name: str) -> str:
-    """qoda::k_decode<4, true>(qoda::Dev) -> k_decode<true>; qoda::k_quantize<4>(...) -> k_quantize."""
+    """Kernel symbol -> the library's kernel class name (qoda_kernel_name): qoda::k_decode<4, 1, false>(qoda::Dev) ->
+    k_decode<true>; qoda::k_quantize<4>(...) and qoda::k_quantize_b<4>(...) -> k_quantize; k_sumsq<true> stays."""
     m = re.search(r"(k_[a-z0-9_]+)(<[^>]*>)?", name)
     if not m:
         return name[:60]
-    args = [a.strip() for a in (m.group(2) or "<>")[1:-1].split(",") if a.strip() and not a.strip().isdigit()]
-    return m.group(1) + ("<" + ", ".join(args) + ">" if args else "")
+    base = m.group(1)
+    raw = [a.strip() for a in (m.group(2) or "<>")[1:-1].split(",") if a.strip()]
+    if base == "k_decode" and len(raw) >= 2:
+        return "k_decode<" + {"0": "false", "1": "true", "2": "alt", "3": "extrapolate"}.get(raw[1], raw[1]) + ">"
+    if base == "k_quantize_b":
+        return "k_quantize"
+    if base == "k_index_hist":
+        return base
+    args = [a for a in raw if not a.isdigit()]
+    return base + ("<" + ", ".join(args) + ">" if args else "")
 
 
 def _counters(directory: str):
@@ -46,6 +55,8 @@ def _counters(directory: str):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--name", required=True)
+    ap.add_argument("--key", help="entry of traffic.json to write (default: --name); bench.py looks up "
+                                  "<workload>[+alt][+vector|+bucket]")
     ap.add_argument("--stats", required=True)
     ap.add_argument("--fetch")
     ap.add_argument("--write")
@@ -98,7 +109,7 @@ def main():
     tpath = os.path.join(a.out, "traffic.json")
     allt = json.load(open(tpath)) if os.path.exists(tpath) else {}
     if traffic:
-        allt[a.name] = traffic
+        allt[a.key or a.name] = traffic
         json.dump(allt, open(tpath, "w"), indent=1, sort_keys=True)
     print("\n".join(lines))
 
