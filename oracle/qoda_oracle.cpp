@@ -23,12 +23,10 @@
 //                                                                                 Thm 5.3 / App. C
 //
 // Pin status (see tests/test_oracle_*.py): every function below is pinned to something the paper or the
-// mathematics fixes EXCEPT the Philox generator's known-answer vectors: no published known-answer
-// file is available here, so philox4x32_10 is pinned only statistically (uniformity, independence,
-// unbiasedness of the rounding it drives) -- "external KAT: parity unpinned".
+// mathematics fixes; the Philox generator also against the published known-answer vectors of its authors.
 // The level fit minimises the paper's objective exactly on a histogram grid; the paper delegates the
 // optimiser itself to third-party code it does not describe, so optimality relative to that code is
-// also "parity unpinned".
+// "parity unpinned".
 //
 // Arithmetic contract (the GPU library follows the same written contract independently):
 //   fp32 operations are single IEEE operations, never fused; sums that feed integer decisions are
