@@ -66,11 +66,12 @@ typedef struct qoda_ctx qoda_ctx;
 
 typedef struct {
   int32_t num_layers;         /* L >= 1 */
-  const int64_t *layer_size;  /* d_l >= 0 elements, host array [L], copied; d_l < 2^31 * 8 */
+  const int64_t *layer_size;  /* d_l >= 0 elements, host array [L], copied; d_l < 2^34 */
   const int32_t *layer_type;  /* m(l) in [0, M), host array [L], copied */
   int32_t num_types;          /* M >= 1 */
   const int32_t *type_points; /* S_m in [2, 256], host array [M], copied */
-  int32_t num_nodes;          /* K >= 1 */
+  int32_t num_nodes;          /* K >= 1, K <= 65535, and K * 2^(1+b_max) <= 16384 with b_max = ceil(log2 max_m S_m)
+                                 (the decode tables of all K nodes are kept in shared memory), else QODA_EINVAL */
   int32_t norm_kind;          /* 2 = L2 (the only kind built) */
   uint64_t seed;              /* key of the counter-based generator */
   int32_t norm_scope;         /* QODA_SCOPE_*: what one norm covers */

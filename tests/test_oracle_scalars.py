@@ -1,6 +1,6 @@
 """Pins for the oracle's scalar building blocks: exact-comparison square root / reciprocal, the canonical
-fp64 sum of squares, and the counter-based generator (statistical pins only: no published known-answer
-vectors are available here)."""
+fp64 sum of squares, and the counter-based generator (its published known-answer vectors, plus statistical pins
+on the way the draws are indexed)."""
 import math
 from fractions import Fraction
 
