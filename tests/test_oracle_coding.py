@@ -143,3 +143,21 @@ def test_nonfinite_input_raises_the_status_flag(oracle):
     g[17] = np.nan
     _, _, _, st = oracle.quantize(sizes, points, [uniform_levels(4)], [g], 1, 1, 0)
     assert st == 1
+
+
+def test_oracle_outputs_match_the_stored_digests(oracle):
+    """tests/golden/oracle_digests.txt is written by tests/golden/make_oracle_digests.py from the oracle alone: a
+    change of the oracle's arithmetic shows up here and has to be made on purpose."""
+    import importlib.util
+    import os
+
+    here = os.path.join(os.path.dirname(__file__), "golden")
+    spec = importlib.util.spec_from_file_location("make_oracle_digests", os.path.join(here, "make_oracle_digests.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    stored = dict((ln.split("  ", 1)[1].strip(), ln.split("  ", 1)[0]) for ln in open(os.path.join(here, "oracle_digests.txt"))
+                  if not ln.startswith("#"))
+    got = dict(mod.cases())
+    assert got.keys() == stored.keys()
+    for name, d in got.items():
+        assert stored[name] == d, name
