@@ -348,7 +348,7 @@ __global__ void __launch_bounds__(kThreads) k_norm_vector(Dev a) {
 // Quantize the four coordinates a lane owns in one block (Sec. 3.1), append their codes to the record and add
 // their squared distance to the previous decoded message (eq. (general_stepsize)).  jl0 = 0 or 4: position of
 // the block inside its pair.
-template <int C1>
+template <int C1, bool PREV>
 __device__ __forceinline__ void quantize_block(const float (&x)[4], const unsigned int (&o)[4], int half, float inv,
                                                float norm, const unsigned char *lut, const float4 *tab,
                                                const float *tprev, unsigned int (&D)[C1], const unsigned int (&Dp)[C1],
@@ -386,8 +386,8 @@ __device__ __forceinline__ void quantize_block(const float (&x)[4], const unsign
     const float mag = norm * (up ? lv[j].z : lv[j].x);
     const float cur = __builtin_copysignf(mag, x[j]);
     insert_code<C1>(D, (h << 1) | (f2u(x[j]) >> 31), 24 + jl);
-    const float pv = lds_float_at(tprev, extract_off<C1>(Dp, jl));  // all zero without a previous message
-    const float diff = cur - pv;
+    float diff = cur;   // PREV == false: no node has a previous message (first round, or the rule of eq. (Alt))
+    if (PREV) diff = cur - lds_float_at(tprev, extract_off<C1>(Dp, jl));   // table all zero for a node without one
     acc = __builtin_fmaf(diff, diff, acc);
   }
 }
@@ -405,7 +405,7 @@ __device__ __forceinline__ void load_block_fast(const float *__restrict__ v, lon
 // unrolled: unrolled, the compiler interleaves the pairs and needs more than 256 registers.  The next pair's
 // gradient values are requested before the current pair is processed.
 // FAST: the whole octet lies inside the layer (no bounds checks anywhere).
-template <int C1, bool FAST>
+template <int C1, bool FAST, bool PREV>
 __device__ __forceinline__ void quantize_octet(const Dev &a, const LayerMeta &m, int l, int k, long long O,
                                                const float *__restrict__ v, unsigned char *body,
                                                const unsigned char *prevbody, float inv, float norm,
@@ -415,7 +415,7 @@ __device__ __forceinline__ void quantize_octet(const Dev &a, const LayerMeta &m,
   unsigned int D[C1], Dp[C1];
 #pragma unroll
   for (int r = 0; r < C1; ++r) { D[r] = 0u; Dp[r] = 0u; }
-  if (prevbody != nullptr) load_record<C1>(prevbody + O * 256 * C1, i, Dp);
+  if (PREV && prevbody != nullptr) load_record<C1>(prevbody + O * 256 * C1, i, Dp);
   float xa[4] = {0.0f, 0.0f, 0.0f, 0.0f}, xb[4] = {0.0f, 0.0f, 0.0f, 0.0f};
   if (FAST) {
     load_block_fast(v, O * 8, i, xa);
@@ -442,16 +442,16 @@ __device__ __forceinline__ void quantize_octet(const Dev &a, const LayerMeta &m,
       }
       unsigned int o[4];
       philox4x32_10((unsigned int)((B0 >> 1) * 64 + i), (unsigned int)l, a.round, (unsigned int)k, k0, k1, o);
-      quantize_block<C1>(x0, o, 0, inv, norm, lut, tab, tprev, D, Dp, acc);
+      quantize_block<C1, PREV>(x0, o, 0, inv, norm, lut, tab, tprev, D, Dp, acc);
       // a block past the end of the layer is all padding: +0 inputs give code 0 and add nothing, as required
-      quantize_block<C1>(x1, o, 1, inv, norm, lut, tab, tprev, D, Dp, acc);
+      quantize_block<C1, PREV>(x1, o, 1, inv, norm, lut, tab, tprev, D, Dp, acc);
     }
-    shift_out_pair<C1>(Dp);
+    if (PREV) shift_out_pair<C1>(Dp);
   }
   store_record<C1>(body + O * 256 * C1, i, D);
 }
 
-template <int C1>
+template <int C1, bool PREV>
 __device__ __forceinline__ void quantize_tile(const Dev &a, const LayerMeta &m, int l, int k, int chunk,
                                               const unsigned char *lut, const float4 *tab, const float *tprev,
                                               double *red) {
@@ -469,15 +469,15 @@ __device__ __forceinline__ void quantize_tile(const Dev &a, const LayerMeta &m, 
     const long long O = (long long)chunk * 8 + w * 2 + oo;   // octet index inside the layer
     if (O >= noct) break;
     if ((O + 1) * 2048 <= m.d)
-      quantize_octet<C1, true>(a, m, l, k, O, v, body, prevbody, inv, norm, lut, tab, tprev, i, acc);
+      quantize_octet<C1, true, PREV>(a, m, l, k, O, v, body, prevbody, inv, norm, lut, tab, tprev, i, acc);
     else
-      quantize_octet<C1, false>(a, m, l, k, O, v, body, prevbody, inv, norm, lut, tab, tprev, i, acc);
+      quantize_octet<C1, false, PREV>(a, m, l, k, O, v, body, prevbody, inv, norm, lut, tab, tprev, i, acc);
   }
   const double total = block_tree((double)acc, red);
   if (t == 0) a.dpartial[(size_t)k * a.G + blockIdx.x] = total;
 }
 
-template <int C1>
+template <int C1, bool PREV>
 __global__ void __launch_bounds__(kThreads) k_quantize(Dev a) {
   __shared__ unsigned char lut[kLutSize];
   __shared__ float4 tab[kMaxPoints];
@@ -513,7 +513,7 @@ __global__ void __launch_bounds__(kThreads) k_quantize(Dev a) {
     tprev[c] = pv;
   }
   __syncthreads();
-  quantize_tile<C1>(a, m, l, k, tile.y, lut, tab, tprev, red);
+  quantize_tile<C1, PREV>(a, m, l, k, tile.y, lut, tab, tprev, red);
 }
 
 // ------------------------------------------------------------------------------------------------ bucket scope
@@ -590,7 +590,7 @@ __device__ __forceinline__ void bucket_norms(const Dev &a, const LayerMeta &m, l
 }
 
 // quantize_block with the block's own (bucket) norm, reciprocal and previous norm; the tables hold plain levels.
-template <int C1>
+template <int C1, bool PREV>
 __device__ __forceinline__ void quantize_block_b(const float (&x)[4], const unsigned int (&o)[4], int half, float inv,
                                                  float norm, float pnorm, const unsigned char *lut, const float4 *tab,
                                                  const float *tprev, unsigned int (&D)[C1],
@@ -630,14 +630,17 @@ __device__ __forceinline__ void quantize_block_b(const float (&x)[4], const unsi
     const float mag = norm * (up ? lv[j].z : lv[j].x);
     const float cur = __builtin_copysignf(mag, x[j]);
     insert_code<C1>(D, (h << 1) | (f2u(x[j]) >> 31), 24 + jl);
-    const float pl = lds_float_at(tprev, extract_off<C1>(Dp, jl));   // +-level of the previous code
-    const float pv = pnorm * pl;
-    const float diff = cur - pv;
+    float diff = cur;
+    if (PREV) {
+      const float pl = lds_float_at(tprev, extract_off<C1>(Dp, jl));   // +-level of the previous code
+      const float pv = pnorm * pl;
+      diff = cur - pv;
+    }
     acc = __builtin_fmaf(diff, diff, acc);
   }
 }
 
-template <int C1, bool FAST>
+template <int C1, bool FAST, bool PREV>
 __device__ __forceinline__ void quantize_octet_b(const Dev &a, const LayerMeta &m, int l, int k, long long O,
                                                  const float *__restrict__ v, unsigned char *body,
                                                  const unsigned char *prevbody, const unsigned char *lut,
@@ -653,7 +656,7 @@ __device__ __forceinline__ void quantize_octet_b(const Dev &a, const LayerMeta &
   unsigned int D[C1], Dp[C1];
 #pragma unroll
   for (int r = 0; r < C1; ++r) { D[r] = 0u; Dp[r] = 0u; }
-  if (poct != nullptr) load_record<C1>(poct, i, Dp);
+  if (PREV && poct != nullptr) load_record<C1>(poct, i, Dp);
   float xa[4] = {0.0f, 0.0f, 0.0f, 0.0f}, xb[4] = {0.0f, 0.0f, 0.0f, 0.0f};
   if (FAST) {
     load_block_fast(v, O * 8, i, xa);
@@ -686,15 +689,15 @@ __device__ __forceinline__ void quantize_octet_b(const Dev &a, const LayerMeta &
       philox4x32_10((unsigned int)((B0 >> 1) * 64 + i), (unsigned int)l, a.round, (unsigned int)k, k0, k1, o);
       // blocks 0 and 4 of the octet (first block of pairs 0 and 2) are the sampled ones
       const unsigned int wf = ((pp & 1) == 0) ? bw.wfix[hf8 + 2 * pp] : 0u;
-      quantize_block_b<C1>(x0, o, 0, ii.x, nn.x, pn.x, lut, tab, tprev, D, Dp, acc, wf, lh);
-      quantize_block_b<C1>(x1, o, 1, ii.y, nn.y, pn.y, lut, tab, tprev, D, Dp, acc, 0u, lh);
+      quantize_block_b<C1, PREV>(x0, o, 0, ii.x, nn.x, pn.x, lut, tab, tprev, D, Dp, acc, wf, lh);
+      quantize_block_b<C1, PREV>(x1, o, 1, ii.y, nn.y, pn.y, lut, tab, tprev, D, Dp, acc, 0u, lh);
     }
-    shift_out_pair<C1>(Dp);
+    if (PREV) shift_out_pair<C1>(Dp);
   }
   store_record<C1>(oct, i, D);
 }
 
-template <int C1>
+template <int C1, bool PREV>
 __global__ void __launch_bounds__(kThreads) k_quantize_b(Dev a) {
   __shared__ unsigned char lut[kLutSize];
   __shared__ float4 tab[kMaxPoints];
@@ -750,9 +753,9 @@ __global__ void __launch_bounds__(kThreads) k_quantize_b(Dev a) {
       const long long O = (long long)chunk * 8 + w * 2 + oo;
       if (O >= noct) break;
       if ((O + 1) * 2048 <= m.d)
-        quantize_octet_b<C1, true>(a, m, l, k, O, v, body, prevbody, lut, tab, tprev, bws[w], i, acc, ex, best, lh);
+        quantize_octet_b<C1, true, PREV>(a, m, l, k, O, v, body, prevbody, lut, tab, tprev, bws[w], i, acc, ex, best, lh);
       else
-        quantize_octet_b<C1, false>(a, m, l, k, O, v, body, prevbody, lut, tab, tprev, bws[w], i, acc, ex, best, lh);
+        quantize_octet_b<C1, false, PREV>(a, m, l, k, O, v, body, prevbody, lut, tab, tprev, bws[w], i, acc, ex, best, lh);
     }
     const double total = block_tree((double)acc, red);
     if (t == 0) a.dpartial[(size_t)k * a.G + m.first_chunk + chunk] = total;
@@ -1380,29 +1383,31 @@ hipError_t launch_norm_finalize(const Dev &a, hipStream_t s) {
 }
 
 // planes_mask: bit p set when some layer has code width p (2..9); one launch per width present.
+template <int C1>
+static void launch_quantize_width(const Dev &a, hipStream_t s) {
+  const dim3 block(kThreads);
+  const bool prev = a.prev != nullptr;   // no node has a previous message: the kernels skip that half of the work
+  if (a.scope == kScopeBucket) {
+    const dim3 grid(a.GS, a.nnodes);   // runs of tiles
+    if (prev) hipLaunchKernelGGL((k_quantize_b<C1, true>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((k_quantize_b<C1, false>), grid, block, 0, s, a);
+  } else {
+    const dim3 grid(a.G, a.nnodes);
+    if (prev) hipLaunchKernelGGL((k_quantize<C1, true>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((k_quantize<C1, false>), grid, block, 0, s, a);
+  }
+}
+
 hipError_t launch_quantize(const Dev &a, unsigned int planes_mask, hipStream_t s) {
   if (a.G == 0 || a.nnodes == 0) return hipSuccess;
-  const dim3 grid(a.G, a.nnodes), block(kThreads);
-  if (a.scope == kScopeBucket) {
-    const dim3 rgrid(a.GS, a.nnodes);   // runs of tiles
-    if (planes_mask & (1u << 2)) hipLaunchKernelGGL(k_quantize_b<2>, rgrid, block, 0, s, a);
-    if (planes_mask & (1u << 3)) hipLaunchKernelGGL(k_quantize_b<3>, rgrid, block, 0, s, a);
-    if (planes_mask & (1u << 4)) hipLaunchKernelGGL(k_quantize_b<4>, rgrid, block, 0, s, a);
-    if (planes_mask & (1u << 5)) hipLaunchKernelGGL(k_quantize_b<5>, rgrid, block, 0, s, a);
-    if (planes_mask & (1u << 6)) hipLaunchKernelGGL(k_quantize_b<6>, rgrid, block, 0, s, a);
-    if (planes_mask & (1u << 7)) hipLaunchKernelGGL(k_quantize_b<7>, rgrid, block, 0, s, a);
-    if (planes_mask & (1u << 8)) hipLaunchKernelGGL(k_quantize_b<8>, rgrid, block, 0, s, a);
-    if (planes_mask & (1u << 9)) hipLaunchKernelGGL(k_quantize_b<9>, rgrid, block, 0, s, a);
-    return hipGetLastError();
-  }
-  if (planes_mask & (1u << 2)) hipLaunchKernelGGL(k_quantize<2>, grid, block, 0, s, a);
-  if (planes_mask & (1u << 3)) hipLaunchKernelGGL(k_quantize<3>, grid, block, 0, s, a);
-  if (planes_mask & (1u << 4)) hipLaunchKernelGGL(k_quantize<4>, grid, block, 0, s, a);
-  if (planes_mask & (1u << 5)) hipLaunchKernelGGL(k_quantize<5>, grid, block, 0, s, a);
-  if (planes_mask & (1u << 6)) hipLaunchKernelGGL(k_quantize<6>, grid, block, 0, s, a);
-  if (planes_mask & (1u << 7)) hipLaunchKernelGGL(k_quantize<7>, grid, block, 0, s, a);
-  if (planes_mask & (1u << 8)) hipLaunchKernelGGL(k_quantize<8>, grid, block, 0, s, a);
-  if (planes_mask & (1u << 9)) hipLaunchKernelGGL(k_quantize<9>, grid, block, 0, s, a);
+  if (planes_mask & (1u << 2)) launch_quantize_width<2>(a, s);
+  if (planes_mask & (1u << 3)) launch_quantize_width<3>(a, s);
+  if (planes_mask & (1u << 4)) launch_quantize_width<4>(a, s);
+  if (planes_mask & (1u << 5)) launch_quantize_width<5>(a, s);
+  if (planes_mask & (1u << 6)) launch_quantize_width<6>(a, s);
+  if (planes_mask & (1u << 7)) launch_quantize_width<7>(a, s);
+  if (planes_mask & (1u << 8)) launch_quantize_width<8>(a, s);
+  if (planes_mask & (1u << 9)) launch_quantize_width<9>(a, s);
   return hipGetLastError();
 }
 
