@@ -114,3 +114,28 @@ def test_bilinear_game_with_the_alternative_rates(oracle):
     for l in range(2):
         assert np.array_equal(m.layers(m.x_half)[l], free.x_half[l])
         assert np.array_equal(m.layers(m.y)[l], free.y[l])
+
+
+def test_argument_errors_of_the_added_entry_points():
+    m = gm([1000, 300], [0, 0], [4], 2, seed=1)
+    g = [[np.ones(1000, np.float32), np.ones(300, np.float32)] for _ in range(2)]
+    m.set_grads(g)
+    m.quantize_all_alt(1)
+    x1, y, xh = m.layer_ptrs(m.x1), m.layer_ptrs(m.y), m.layer_ptrs(m.x_half)
+    with pytest.raises(qoda.QodaError):
+        m.ctx.step_alt(m.msg[0], x1, y, xh, None, m.eta, 0.25)                 # no sums
+    with pytest.raises(qoda.QodaError):
+        m.ctx.step_alt(m.msg[0], x1, y, xh, m.alt_sums, None, 0.25)            # the rates are in/out: required
+    with pytest.raises(qoda.QodaError):
+        m.ctx.step_alt([m.msg[0][0], None], x1, y, xh, m.alt_sums, m.eta, 0.25)  # a null message
+    with pytest.raises(qoda.QodaError):
+        m.ctx.extrapolate(m.msg[0], x1, xh, None)                               # no step size
+    with pytest.raises(qoda.QodaError):
+        m.ctx.extrapolate(m.msg[0], [x1[0] + 4, x1[1]], xh, m.eta)              # misaligned layer
+    with pytest.raises(qoda.QodaError):
+        m.ctx.fit_levels(None, 2)                                               # statistics exist under bucket scope only
+    with pytest.raises(qoda.QodaError):
+        qoda.Context([10], [0], [4], 1, 0, norm_scope=7)                        # unknown scope
+    with pytest.raises(qoda.QodaError):
+        m.ctx.index_counts([m.msg[0][0], None])
+    assert m.ctx.status() == qoda.OK
