@@ -523,7 +523,10 @@ __global__ void __launch_bounds__(kThreads) k_quantize(Dev a) {
 //
 // Per-wave shared memory of the bucket-scope quantizer.
 struct BucketWave {
-  alignas(16) double psum[8][64];   // [block][lane]: the lane's sum of its 4 squares (fp64 chain in coordinate order)
+  // the lane's sum of its 4 squares (fp64 chain in coordinate order) for block bb, lane i, at index
+  // 72*bb + i + i/8: one word of padding after every 8, so that the transposed read below (lane L reads the 8
+  // consecutive entries 8L .. 8L+7, i.e. a stride of 9 words between lanes) spreads over all banks
+  double psum[8 * 72];
   float norm[16];       // [8*half + block] of the current octet
   float inv[16];
   float pnorm[16];      // the previous message's norms of the same buckets
@@ -555,14 +558,14 @@ __device__ __forceinline__ void bucket_norms(const Dev &a, const LayerMeta &m, l
       const double xd = (double)x[j];
       acc = __builtin_fma(xd, xd, acc);   // the product is exact in fp64, so this equals acc + xd*xd
     }
-    bw.psum[bb][i] = acc;
+    bw.psum[72 * bb + i + (i >> 3)] = acc;
   }
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   const int q = i >> 2, r = i & 3;
   const int bb = q >> 1, hf = q & 1;
-  const double *p = &bw.psum[bb][hf * 32 + r * 8];
+  const double *p = &bw.psum[72 * bb + 36 * hf + 9 * r];   // lanes 32*hf + 8*r .. +7 of block bb in the padded layout
   double s = ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
   s = s + __shfl_xor(s, 1, 64);
   s = s + __shfl_xor(s, 2, 64);
@@ -607,9 +610,9 @@ __device__ __forceinline__ void quantize_block_b(const float (&x)[4], const unsi
   if (wfix != 0u) {   // a sampled block of a bucket with weight: the fit's grid histogram (integer adds)
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      if (((f2u(x[j]) & 0x7FFFFFFFu) >> 20) == 0u) continue;   // also skips the +0 padding past the end of the layer
-      int g = (int)(f2u(u[j]) >> 20) - kGridBase;
-      g = max(0, min(g, kGridPoints - 1));
+      if ((f2u(x[j]) & 0x7FF00000u) == 0u) continue;   // raw magnitude bin 0; also the +0 padding past the layer's end
+      // u <= 1, so its bin never exceeds the last grid index: only the lower clamp is needed (saturating subtract)
+      const unsigned int g = __builtin_elementwise_sub_sat(f2u(u[j]) >> 20, (unsigned int)kGridBase);
       atomicAdd(&lh[g], (unsigned long long)wfix);
     }
   }
