@@ -281,18 +281,21 @@ inline float *bucket_norm_slot(uint8_t *layer_base, int planes, int64_t ostride,
 }
 
 // Sum of squares of one bucket (n <= 128 coordinates, missing ones count as 0): "lane" i = (e mod 128)/4 adds the
-// squares of its four consecutive coordinates in order (products exact in fp64), then the 32 lane sums are combined
-// by the in-order binary tree (lanes 0+1, 2+3, ...; then pairs of those; ...).
+// squares of its four consecutive coordinates in order with an fp32 fused chain (acc = fma(x, x, acc) from 0), the 32
+// lane sums are widened to fp64 and combined by the in-order binary tree (lanes 0+1, 2+3, ...; then pairs of those; ...).
+// Single precision inside a lane is what a bucket norm needs (relative error about 1e-7) and what keeps the pass that
+// computes it cheap; squares below the fp32 range vanish and squares above it overflow (then the bucket is reported
+// as not finite), unlike the per-layer sums, which are exact in fp64.
 double bucket_sumsq(const float *v, int64_t n) {
   double p[32];
   for (int i = 0; i < 32; ++i) {
-    double acc = 0.0;
+    float acc = 0.0f;
     for (int j = 0; j < 4; ++j) {
       const int64_t e = 4 * i + j;
-      const double x = (e < n) ? (double)v[e] : 0.0;
-      acc = acc + x * x;
+      const float x = (e < n) ? v[e] : 0.0f;
+      acc = std::fmaf(x, x, acc);
     }
-    p[i] = acc;
+    p[i] = (double)acc;
   }
   for (int w = 1; w < 32; w *= 2)
     for (int i = 0; i < 32; i += 2 * w) p[i] = p[i] + p[i + w];

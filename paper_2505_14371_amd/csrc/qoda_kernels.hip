@@ -523,10 +523,10 @@ __global__ void __launch_bounds__(kThreads) k_quantize(Dev a) {
 //
 // Per-wave shared memory of the bucket-scope quantizer.
 struct BucketWave {
-  // the lane's sum of its 4 squares (fp64 chain in coordinate order) for block bb, lane i, at index
+  // the lane's sum of its 4 squares (fp32 fused chain in coordinate order) for block bb, lane i, at index
   // 72*bb + i + i/8: one word of padding after every 8, so that the transposed read below (lane L reads the 8
   // consecutive entries 8L .. 8L+7, i.e. a stride of 9 words between lanes) spreads over all banks
-  double psum[8 * 72];
+  float psum[8 * 72];
   float norm[16];       // [8*half + block] of the current octet
   float inv[16];
   float pnorm[16];      // the previous message's norms of the same buckets
@@ -534,8 +534,9 @@ struct BucketWave {
 };
 
 // Sums of squares of the 16 buckets of one octet -> norm, inv (shared memory) and the octet's norm trailer.
-// Lane L finishes bucket q = L/4 (block q/2, half q%2): it adds 8 consecutive lane sums by the in-order binary
-// tree, then the four lanes of the quad combine (neighbour, then pair), which continues the same tree.
+// A lane's four squares are an fp32 fused chain; lane L then finishes bucket q = L/4 (block q/2, half q%2): it adds 8
+// consecutive lane sums, widened to fp64, by the in-order binary tree, then the four lanes of the quad combine
+// (neighbour, then pair), which continues the same tree.
 // ex: weight scale of the layer's type for the fit statistics (kTypeSkip: none); best: running maximum of the bit
 // patterns of the lane's sampled bucket sums (blocks 0 and 4 of the octet, i.e. every fourth block of the layer).
 template <bool FAST>
@@ -552,12 +553,9 @@ __device__ __forceinline__ void bucket_norms(const Dev &a, const LayerMeta &m, l
     } else if (e < m.d) {
       load4(v, e, m.d, x);
     }
-    double acc = 0.0;
+    float acc = 0.0f;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const double xd = (double)x[j];
-      acc = __builtin_fma(xd, xd, acc);   // the product is exact in fp64, so this equals acc + xd*xd
-    }
+    for (int j = 0; j < 4; ++j) acc = __builtin_fmaf(x[j], x[j], acc);
     bw.psum[72 * bb + i + (i >> 3)] = acc;
   }
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -565,8 +563,9 @@ __device__ __forceinline__ void bucket_norms(const Dev &a, const LayerMeta &m, l
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   const int q = i >> 2, r = i & 3;
   const int bb = q >> 1, hf = q & 1;
-  const double *p = &bw.psum[72 * bb + 36 * hf + 9 * r];   // lanes 32*hf + 8*r .. +7 of block bb in the padded layout
-  double s = ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+  const float *p = &bw.psum[72 * bb + 36 * hf + 9 * r];   // lanes 32*hf + 8*r .. +7 of block bb in the padded layout
+  double s = (((double)p[0] + (double)p[1]) + ((double)p[2] + (double)p[3])) +
+             (((double)p[4] + (double)p[5]) + ((double)p[6] + (double)p[7]));
   s = s + __shfl_xor(s, 1, 64);
   s = s + __shfl_xor(s, 2, 64);
   const double lim = (double)kFltMax * (double)kFltMax;
@@ -1092,12 +1091,10 @@ __device__ __forceinline__ double sampled_bucket_sum(const LayerMeta &m, const f
 #pragma unroll
   for (int j = 0; j < 4; ++j) x[j] = 0.0f;
   if (e < m.d) load4(v, e, m.d, x);
-  double s = 0.0;
+  float acc = 0.0f;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const double xd = (double)x[j];
-    s = __builtin_fma(xd, xd, s);
-  }
+  for (int j = 0; j < 4; ++j) acc = __builtin_fmaf(x[j], x[j], acc);
+  double s = (double)acc;
 #pragma unroll
   for (int w = 1; w < 32; w *= 2) s = s + __shfl_xor(s, w, 64);
   return s;
