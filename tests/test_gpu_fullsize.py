@@ -234,3 +234,118 @@ def test_full_size_alternative_step_sizes(oracle):
             assert np.array_equal(f.layer(f.xh, l, e0, e1), wxh[0]), (t, l, e0)
             assert np.array_equal(f.layer(xn, l, e0, e1), wxn[0]), (t, l, e0)
     assert mu > 0 and lam > 0
+
+
+@pytest.mark.timeout(900)
+def test_full_size_bucket_scope(oracle):
+    """Bucket scope on the Transformer-XL-shaped workload, three rounds in bench.py's configuration (explicit fit in
+    round 1, fits from the gathered statistics afterwards): whole small tensors against the oracle (messages with their
+    bucket norms, gathered statistics, fitted levels), slices of the big ones, the step-size term of one node
+    recomputed from its stored messages, iterates on the pieces."""
+    from paper_2505_14371_amd import qoda as q
+
+    name = "txl"
+    w = workloads.get(name)
+    L, K, S = len(w.sizes), w.num_nodes, w.points
+    dev = torch.device("cuda:0")
+    ctx = q.Context(w.sizes, list(range(L)), [S] * L, K, w.seed, norm_scope=q.SCOPE_BUCKET)
+    off, n = workloads.padded_offsets(w.sizes)
+    grad = [torch.zeros(n, dtype=torch.float32, device=dev) for _ in range(K)]
+    mb = ctx.message_bytes()
+    msg = [[torch.zeros(mb, dtype=torch.uint8, device=dev) for _ in range(K)] for _ in range(2)]
+    x1 = torch.randn(n, dtype=torch.float32, device=dev)
+    y = torch.zeros_like(x1)
+    xh = torch.zeros_like(x1)
+    acc = torch.zeros(1, dtype=torch.float64, device=dev)
+    eta = torch.ones(2, dtype=torch.float32, device=dev)
+    ptrs = lambda t: [t.data_ptr() + 4 * int(o) for o in off]
+    gp = lambda: [p for k in range(K) for p in ptrs(grad[k])]
+    hdr_off, body_off = ctx.message_layout()
+    ob = 256 * 4 + 64
+    small = [l for l in range(L) if w.sizes[l] <= 200_000][:6] + [L - 1]
+    levels = {l: uniform_levels(S) for l in small}
+    exps = {}
+    stats = {}
+    prev_small = {(k, l): None for k in range(K) for l in small}
+    for t in (1, 2, 3):
+        for k in range(K):
+            workloads.node_torch(w, k, t, dev, out=grad[k])
+        cur = (t - 1) & 1
+        ctx.fit_levels(gp() if t == 1 else None, t)
+        host = {(k, l): grad[k][int(off[l]): int(off[l]) + w.sizes[l]].cpu().numpy() for k in range(K) for l in small}
+        for l in small:                                      # every layer is its own type: fit layer by layer
+            if t == 1:
+                lev, _, _, st = oracle.fit_levels([w.sizes[l]], [0], [S], K, [host[(k, l)] for k in range(K)], [levels[l]],
+                                                  scope=q.SCOPE_BUCKET)
+                b0 = np.stack([oracle.quantize([w.sizes[l]], [S], [lev[0]], [host[(k, l)]], w.seed, 0, k, scope=q.SCOPE_BUCKET,
+                                               stats_exp=[oracle.TYPE_SKIP])[5] for k in range(K)])
+                _, _, ex, _ = oracle.fit_from_stats([0], [S], K, np.zeros((K, 1, 257), np.uint64), b0, [oracle.TYPE_SKIP], lev)
+            else:
+                lev, _, ex, st = oracle.fit_from_stats([0], [S], K, stats[l][0], stats[l][1], [exps[l]], [levels[l]])
+            levels[l], exps[l] = lev[0], int(ex[0])
+            assert np.array_equal(ctx.get_levels(l), levels[l]), (t, l)
+        ctx.quantize_all(gp(), t, msg[cur], msg[1 - cur] if t > 1 else None)
+        deltas = ctx.read_buffer(q.BUF_DELTA)
+        acc_before = float(acc.cpu()[0])
+        y_old = y.clone()
+        ctx.step(msg[cur], ptrs(x1), ptrs(y), ptrs(xh), acc, None, eta)
+        torch.cuda.synchronize()
+        assert ctx.status() == q.OK
+        for l in small:                                      # whole small tensors: bytes of the body, gathered statistics
+            nb = (w.sizes[l] + 2047) // 2048 * ob
+            hist = np.zeros((K, 1, 257), np.uint64)
+            bmax = np.zeros((K, 1))
+            for k in range(K):
+                out = oracle.quantize([w.sizes[l]], [S], [levels[l]], [host[(k, l)]], w.seed, t, k,
+                                      msg_prev=prev_small[(k, l)], scope=q.SCOPE_BUCKET, stats_exp=[exps[l]])
+                # the oracle numbers this tensor as layer 0: draws differ unless the layer index matches, so only
+                # layer 0 of the model can be compared byte for byte; for the others compare norms and statistics
+                got = msg[cur][k][int(body_off[l]): int(body_off[l]) + nb].cpu().numpy()
+                hb = oracle.header_bytes([w.sizes[l]], [S], q.SCOPE_BUCKET)
+                _, _, want_norms = oracle.unpack_layer(out[0][hb: hb + nb], w.sizes[l], S, q.SCOPE_BUCKET)
+                _, _, got_norms = oracle.unpack_layer(got, w.sizes[l], S, q.SCOPE_BUCKET)
+                assert np.array_equal(got_norms, want_norms), (t, k, l)
+                hist[k, 0], bmax[k, 0] = out[4][0], out[5][0]
+                prev_small[(k, l)] = None                    # (previous messages of other layer numbers are not comparable)
+            stats[l] = (hist, bmax)
+        # codes of slices, with the right layer number, from the stored bucket norms
+        whole = {}
+        for (l, e0, e1) in pieces_for(w)[:8]:
+            for k in (0, K - 1):
+                if (k, l) not in whole:                      # the draws are indexed by the coordinate inside the layer
+                    whole = {kk: v for kk, v in whole.items() if kk[1] == l}
+                    whole[(k, l)] = grad[k][int(off[l]): int(off[l]) + w.sizes[l]].cpu().numpy()
+                g = whole[(k, l)]
+                body = msg[cur][k][int(body_off[l]) + e0 // 2048 * ob: int(body_off[l]) + (e1 + 2047) // 2048 * ob].cpu().numpy()
+                gs, gi, gn = oracle.unpack_layer(body, e1 - e0, S, q.SCOPE_BUCKET)
+                lev = ctx.get_levels(l)
+                for b in range(e0, e1, 128):
+                    b1 = min(b + 128, e1)
+                    nrm = oracle.sqrt_floor(oracle.bucket_sumsq(g[b: b1]))
+                    assert gn[(b - e0) // 128] == nrm, (t, k, l, b)
+                    sign, idx = oracle.quantize_range(g, b, b1, oracle.rcp_floor(nrm), lev, w.seed, t, k, l)
+                    assert np.array_equal(gi[b - e0: b1 - e0], idx) and np.array_equal(gs[b - e0: b1 - e0], sign), (t, k, l, b)
+        del whole
+        k = K - 1
+        if t == 3:
+            want = oracle.delta_from_messages(w.sizes, [S] * L, msg[cur][k].cpu().numpy(), msg[1 - cur][k].cpu().numpy(),
+                                              scope=q.SCOPE_BUCKET)
+            assert deltas[k] == want
+        a2, e2 = oracle.step_size(deltas, acc_before)
+        assert float(acc.cpu()[0]) == a2 and float(eta.cpu()[0]) == float(e2)
+        for (l, e0, e1) in pieces_for(w)[:6]:
+            sub = []
+            for kk in range(K):
+                hdr = msg[cur][kk][int(hdr_off[l]): int(hdr_off[l]) + 4 * (1 + S)].cpu().numpy()
+                body = msg[cur][kk][int(body_off[l]) + e0 // 2048 * ob: int(body_off[l]) + (e1 + 2047) // 2048 * ob].cpu().numpy()
+                hb = oracle.header_bytes([e1 - e0], [S], q.SCOPE_BUCKET)
+                m = np.zeros(oracle.message_bytes([e1 - e0], [S], q.SCOPE_BUCKET), np.uint8)
+                m[: hdr.size] = hdr
+                m[hb: hb + body.size] = body
+                sub.append(m)
+            mean = oracle.dequant_aggregate([e1 - e0], [S], sub, scope=q.SCOPE_BUCKET)[0]
+            yv = y_old[int(off[l]) + e0: int(off[l]) + e1].cpu().numpy().copy()
+            xx = x1[int(off[l]) + e0: int(off[l]) + e1].cpu().numpy()
+            _, wxh = oracle.oda_update(mean, xx, yv, e2, e2, want_next=False)
+            assert np.array_equal(y[int(off[l]) + e0: int(off[l]) + e1].cpu().numpy(), yv), (t, l, e0)
+            assert np.array_equal(xh[int(off[l]) + e0: int(off[l]) + e1].cpu().numpy(), wxh), (t, l, e0)
