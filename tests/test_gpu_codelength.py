@@ -83,6 +83,8 @@ def test_full_size_accounting(oracle):
     out = dict(rep, workload="txl", k_index_hist_ms=ms[0] / ms[1],
                bits_per_coordinate={k: rep[k] / rep["coordinates"] for k in
                                     ("fixed_bits", "paper_bits", "entropy_bits", "huffman_bits", "message_bits")})
-    os.makedirs("gpurun_out", exist_ok=True)
-    with open("gpurun_out/codelength_txl.json", "w") as f:
-        json.dump(out, f)
+    report_dir = os.environ.get("QODA_REPORT_DIR")          # optional: keep the figures of this run
+    if report_dir:
+        os.makedirs(report_dir, exist_ok=True)
+        with open(os.path.join(report_dir, "codelength_txl.json"), "w") as f:
+            json.dump(out, f)
