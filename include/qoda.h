@@ -15,6 +15,10 @@
  *   - Every call returns QODA_OK (0) or a negative error code and then qoda_last_error() describes it.  Nothing
  *     throws across this boundary.  Bad arguments are rejected before anything is launched.
  *   - A context is not thread-safe: use it from one host thread at a time, on one stream at a time.
+ *   - The library keeps a few device copies of every pointer array it is given; once each distinct set of arrays has
+ *     been used, the calls of a round enqueue kernels (and, for the statistics-based fit, one device-to-device copy)
+ *     only: no upload, no wait.  Such a steady-state round can be captured into a HIP graph; pointers and the round
+ *     number are then fixed in the captured launches.  The calls that wait (see above) cannot be captured.
  *   - Non-finite input (a layer whose sum of squares is not a finite number or whose norm exceeds FLT_MAX) sets
  *     a sticky device-side flag reported by qoda_status(); that layer's output is then unspecified (but in
  *     bounds).

@@ -46,11 +46,24 @@ struct qoda_ctx {
   int *d_type_exp_next = nullptr;   // bucket scope: the weight scales the next gathering pass will use
   unsigned long long *d_index_counts = nullptr;   // [M*256], allocated by the first qoda_index_counts
   // device pointer tables (uploaded when their host shadow changes)
+  // A few device copies per table, each remembering the host array it was filled from: a caller that alternates
+  // between a few pointer sets (two message buffers per node, say) causes no upload after the first use of each set,
+  // so a steady-state round enqueues kernels only and can be captured into a graph.
   struct Table {
-    void **dev = nullptr;
-    std::vector<void *> host;
-    size_t n = 0;
-    bool valid = false;
+    static constexpr int kSlots = 4;
+    struct Slot {
+      void **dev = nullptr;
+      std::vector<void *> host;
+      size_t n = 0;
+      bool valid = false;
+      unsigned long long stamp = 0;
+    };
+    Slot slots[kSlots];
+    int cur = 0;
+    unsigned long long clock = 0;
+    void **dev() const { return slots[cur].dev; }
+    const std::vector<void *> &host() const { return slots[cur].host; }
+    bool valid() const { return slots[cur].valid; }
   };
   Table t_grad, t_msg, t_prev, t_in, t_x1, t_y, t_xh, t_xn, t_mean;
   hipEvent_t upload_done = nullptr;
@@ -129,18 +142,31 @@ hipError_t dev_alloc(T **p, size_t n) {
 
 // Upload a table of device pointers if it differs from what the device copy holds.
 int sync_table(qoda_ctx *c, qoda_ctx::Table &t, const void *const *src, size_t n, hipStream_t s) {
-  if (t.valid && t.n == n && std::memcmp(t.host.data(), src, n * sizeof(void *)) == 0) return QODA_OK;
-  if (c->upload_pending) {   // the previous asynchronous upload may still be reading a host shadow
+  int victim = 0;
+  for (int q = 0; q < qoda_ctx::Table::kSlots; ++q) {
+    qoda_ctx::Table::Slot &sl = t.slots[q];
+    if (sl.valid && sl.n == n && std::memcmp(sl.host.data(), src, n * sizeof(void *)) == 0) {
+      t.cur = q;
+      sl.stamp = ++t.clock;
+      return QODA_OK;
+    }
+    if (!sl.valid) victim = q;
+    else if (t.slots[victim].valid && sl.stamp < t.slots[victim].stamp) victim = q;
+  }
+  if (c->upload_pending) {   // an earlier asynchronous upload may still be reading a host shadow
     HIP_TRY(c, hipEventSynchronize(c->upload_done));
     c->upload_pending = false;
   }
-  t.host.resize(n);
-  std::memcpy(t.host.data(), src, n * sizeof(void *));
-  t.n = n;
-  HIP_TRY(c, hipMemcpyAsync(t.dev, t.host.data(), n * sizeof(void *), hipMemcpyHostToDevice, s));
+  qoda_ctx::Table::Slot &sl = t.slots[victim];
+  sl.host.resize(n);
+  std::memcpy(sl.host.data(), src, n * sizeof(void *));
+  sl.n = n;
+  HIP_TRY(c, hipMemcpyAsync(sl.dev, sl.host.data(), n * sizeof(void *), hipMemcpyHostToDevice, s));
   HIP_TRY(c, hipEventRecord(c->upload_done, s));
   c->upload_pending = true;
-  t.valid = true;
+  sl.valid = true;
+  sl.stamp = ++t.clock;
+  t.cur = victim;
   return QODA_OK;
 }
 
@@ -197,10 +223,13 @@ int check_msg_ptrs(qoda_ctx *c, const void *const *p, size_t n, const char *what
 void free_all(qoda_ctx *c) {
   void *ptrs[] = {c->d_meta, c->d_tiles, c->d_stiles, c->d_empty, c->d_type_points, c->d_partial, c->d_dpartial, c->d_sumsq, c->d_delta,
                   c->d_norm, c->d_inv, c->d_lev, c->d_rgap, c->d_eta, c->d_lut, c->d_hist, c->d_status, c->d_pooled, c->d_index_counts, c->d_type_exp_next,
-                  c->d_type_exp, c->d_dp_arg, c->d_dp_arg_off, c->t_grad.dev, c->t_msg.dev, c->t_prev.dev, c->t_in.dev,
-                  c->t_x1.dev, c->t_y.dev, c->t_xh.dev, c->t_xn.dev, c->t_mean.dev};
+                  c->d_type_exp, c->d_dp_arg, c->d_dp_arg_off};
   for (void *p : ptrs)
     if (p) (void)hipFree(p);
+  qoda_ctx::Table *tabs[] = {&c->t_grad, &c->t_msg, &c->t_prev, &c->t_in, &c->t_x1, &c->t_y, &c->t_xh, &c->t_xn, &c->t_mean};
+  for (qoda_ctx::Table *t : tabs)
+    for (auto &sl : t->slots)
+      if (sl.dev) (void)hipFree(sl.dev);
   if (c->upload_done) (void)hipEventDestroy(c->upload_done);
   for (auto &r : c->prof_recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
   for (hipEvent_t e : c->prof_pool) (void)hipEventDestroy(e);
@@ -217,9 +246,9 @@ int run_norm_pass(qoda_ctx *c, Dev a, bool with_hist, hipStream_t s) {
 int quantize_impl(qoda_ctx *c, int node0, int nnodes, const float *const *grad_full /* K*L shadow */, uint32_t round,
                   hipStream_t s, bool have_prev) {
   Dev a = base_args(c);
-  a.grad = reinterpret_cast<const float *const *>(c->t_grad.dev);
-  a.msg = reinterpret_cast<unsigned char *const *>(c->t_msg.dev);
-  a.prev = have_prev ? reinterpret_cast<const unsigned char *const *>(c->t_prev.dev) : nullptr;
+  a.grad = reinterpret_cast<const float *const *>(c->t_grad.dev());
+  a.msg = reinterpret_cast<unsigned char *const *>(c->t_msg.dev());
+  a.prev = have_prev ? reinterpret_cast<const unsigned char *const *>(c->t_prev.dev()) : nullptr;
   a.round = round;
   a.node0 = node0;
   a.nnodes = nnodes;
@@ -344,7 +373,8 @@ int qoda_create(const qoda_config *cfg, qoda_ctx **out) {
   A(dev_alloc(&c->d_dp_arg_off, (size_t)c->M));
   qoda_ctx::Table *tabs[] = {&c->t_grad, &c->t_msg, &c->t_prev, &c->t_in, &c->t_x1, &c->t_y, &c->t_xh, &c->t_xn, &c->t_mean};
   const size_t tab_n[] = {KL, (size_t)c->K, (size_t)c->K, (size_t)c->K, (size_t)c->L, (size_t)c->L, (size_t)c->L, (size_t)c->L, (size_t)c->L};
-  for (int i = 0; i < 9; ++i) A(dev_alloc(&tabs[i]->dev, tab_n[i]));
+  for (int i = 0; i < 9; ++i)
+    for (auto &sl : tabs[i]->slots) A(dev_alloc(&sl.dev, tab_n[i]));
   A(hipEventCreateWithFlags(&c->upload_done, hipEventDisableTiming));
   if (e == hipSuccess) A(hipMemcpy(c->d_meta, c->meta.data(), c->L * sizeof(LayerMeta), hipMemcpyHostToDevice));
   if (e == hipSuccess && c->G) A(hipMemcpy(c->d_tiles, tiles.data(), c->G * sizeof(int2), hipMemcpyHostToDevice));
@@ -458,7 +488,7 @@ int qoda_fit_levels(qoda_ctx *c, const float *const *grad_dev, uint32_t round, v
   if (rc) return rc;
   c->norms_valid = false;
   Dev a = base_args(c);
-  a.grad = reinterpret_cast<const float *const *>(c->t_grad.dev);
+  a.grad = reinterpret_cast<const float *const *>(c->t_grad.dev());
   a.round = round;
   LAUNCH(c, kIdZero, s, launch_zero_u32(c->d_hist, KL * kHistBins, s));
   if (c->scope == kScopeBucket) {
@@ -523,13 +553,13 @@ int qoda_quantize(qoda_ctx *c, int32_t node, const float *const *grad_dev, uint3
   hipStream_t s = static_cast<hipStream_t>(stream);
   // splice this node's pointers into full-size shadows of the K*L / K tables
   const size_t KL = (size_t)c->K * c->L;
-  std::vector<void *> g(c->t_grad.valid ? c->t_grad.host : std::vector<void *>(KL, nullptr));
+  std::vector<void *> g(c->t_grad.valid() ? c->t_grad.host() : std::vector<void *>(KL, nullptr));
   g.resize(KL, nullptr);
   for (int l = 0; l < c->L; ++l) g[(size_t)node * c->L + l] = const_cast<float *>(grad_dev[l]);
-  std::vector<void *> m(c->t_msg.valid ? c->t_msg.host : std::vector<void *>(c->K, nullptr));
+  std::vector<void *> m(c->t_msg.valid() ? c->t_msg.host() : std::vector<void *>(c->K, nullptr));
   m.resize(c->K, nullptr);
   m[node] = msg_dev;
-  std::vector<void *> p(c->t_prev.valid ? c->t_prev.host : std::vector<void *>(c->K, nullptr));
+  std::vector<void *> p(c->t_prev.valid() ? c->t_prev.host() : std::vector<void *>(c->K, nullptr));
   p.resize(c->K, nullptr);
   p[node] = const_cast<void *>(msg_prev_dev);
   rc = sync_table(c, c->t_grad, g.data(), KL, s);
@@ -538,7 +568,7 @@ int qoda_quantize(qoda_ctx *c, int32_t node, const float *const *grad_dev, uint3
   if (rc) return rc;
   rc = sync_table(c, c->t_prev, p.data(), c->K, s);
   if (rc) return rc;
-  return quantize_impl(c, node, 1, reinterpret_cast<const float *const *>(c->t_grad.host.data()), round, s, true);
+  return quantize_impl(c, node, 1, reinterpret_cast<const float *const *>(c->t_grad.host().data()), round, s, true);
 }
 
 static int decode_common(qoda_ctx *c, const void *const *msgs_dev, Dev &a, hipStream_t s, const char *who) {
@@ -546,7 +576,7 @@ static int decode_common(qoda_ctx *c, const void *const *msgs_dev, Dev &a, hipSt
   if (rc) return rc;
   rc = sync_table(c, c->t_in, msgs_dev, c->K, s);
   if (rc) return rc;
-  a.msgs_in = reinterpret_cast<const unsigned char *const *>(c->t_in.dev);
+  a.msgs_in = reinterpret_cast<const unsigned char *const *>(c->t_in.dev());
   return QODA_OK;
 }
 
@@ -560,7 +590,7 @@ int qoda_dequant_aggregate(qoda_ctx *c, const void *const *msgs_dev, float *cons
   if (rc) return rc;
   rc = sync_table(c, c->t_mean, reinterpret_cast<const void *const *>(mean_out_dev), c->L, s);
   if (rc) return rc;
-  a.mean_out = reinterpret_cast<float *const *>(c->t_mean.dev);
+  a.mean_out = reinterpret_cast<float *const *>(c->t_mean.dev());
   LAUNCH(c, kIdDecodeMean, s, launch_decode(a, kDecodeMean, c->planes_mask, s));
   return QODA_OK;
 }
@@ -583,10 +613,10 @@ static int step_common(qoda_ctx *c, const void *const *msgs_dev, const float *co
     rc = sync_table(c, *t.t, t.p, c->L, s);
     if (rc) return rc;
   }
-  a.x1 = reinterpret_cast<const float *const *>(c->t_x1.dev);
-  a.y = reinterpret_cast<float *const *>(c->t_y.dev);
-  a.x_half = reinterpret_cast<float *const *>(c->t_xh.dev);
-  a.x_next = xn ? reinterpret_cast<float *const *>(c->t_xn.dev) : nullptr;
+  a.x1 = reinterpret_cast<const float *const *>(c->t_x1.dev());
+  a.y = reinterpret_cast<float *const *>(c->t_y.dev());
+  a.x_half = reinterpret_cast<float *const *>(c->t_xh.dev());
+  a.x_next = xn ? reinterpret_cast<float *const *>(c->t_xn.dev()) : nullptr;
   return QODA_OK;
 }
 
@@ -716,8 +746,8 @@ int qoda_extrapolate(qoda_ctx *c, const void *const *msgs_dev, const float *cons
   if (rc) return rc;
   rc = sync_table(c, c->t_xh, reinterpret_cast<const void *const *>(out_dev), c->L, s);
   if (rc) return rc;
-  a.x1 = reinterpret_cast<const float *const *>(c->t_x1.dev);
-  a.x_half = reinterpret_cast<float *const *>(c->t_xh.dev);
+  a.x1 = reinterpret_cast<const float *const *>(c->t_x1.dev());
+  a.x_half = reinterpret_cast<float *const *>(c->t_xh.dev());
   a.gamma_in = gamma_dev;
   LAUNCH(c, kIdDecodeExtrapolate, s, launch_decode(a, kDecodeExtrapolate, c->planes_mask, s));
   return QODA_OK;
