@@ -1233,14 +1233,16 @@ __device__ __forceinline__ double fit_cost(const FitRow &ra, const FitRow &rb) {
 }
 
 constexpr int kFitThreads = 1024;   // 4 threads per grid index b: each scans a quarter of the candidates a
+constexpr int kFitLdsPoints = 128;  // up to this many level points the back-pointers stay in shared memory
 
 __global__ void __launch_bounds__(kFitThreads) k_fit_dp(Dev a) {
   __shared__ FitRow row[kGridPoints + 1];
   __shared__ double D[2][kGridPoints];
-  __shared__ double wd[kGridPoints];
+  __shared__ double wd[3][kGridPoints];   // W, W*mid, (W*mid)*mid per bin
   __shared__ double rv[kThreads];
   __shared__ int ri[kThreads];
   __shared__ float slev[kMaxPoints];
+  __shared__ unsigned char sarg[kFitLdsPoints * 256];   // back-pointers of the stages, when S is small enough
   const int mtype = blockIdx.x;
   if (a.type_exp[mtype] == kTypeSkip) return;   // all-zero or non-finite vectors: the type keeps its levels
   const int S = a.type_points[mtype];
@@ -1248,34 +1250,45 @@ __global__ void __launch_bounds__(kFitThreads) k_fit_dp(Dev a) {
   const unsigned long long *W = a.pooled + (size_t)mtype * kGridPoints;
   const int last = kGridPoints - 1;
   for (int j = t; j < kGridPoints; j += kFitThreads) {
-    wd[j] = (double)W[j];
+    const double wj = (double)W[j];
+    const double mid = (j == last) ? 1.0 : (double)u2f(((unsigned int)(j + kGridBase) << 20) | (1u << 19));
+    const double wm = wj * mid;
+    wd[0][j] = wj;
+    wd[1][j] = wm;
+    wd[2][j] = wm * mid;
     row[j].g = (double)grid_value(j);
   }
   __syncthreads();
-  if (t == 0) {
-    double p0 = 0.0, p1 = 0.0, p2 = 0.0;
-    row[0].p0 = 0.0; row[0].p1 = 0.0; row[0].p2 = 0.0;
-    row[kGridPoints].g = 0.0;
+  // the three running sums, each by one thread of its own wave, bin after bin
+  if ((t & 63) == 0 && t < 3 * 64) {
+    const int f = t >> 6;
+    const double *src = wd[f];
+    double *dst = &row[0].p0 + f;   // p0, p1, p2 are the first three doubles of a row
+    double p = 0.0;
+    dst[0] = 0.0;
+#pragma unroll 8
     for (int j = 0; j < kGridPoints; ++j) {
-      const double wj = wd[j];
-      const double mid = (j == last) ? 1.0 : (double)u2f(((unsigned int)(j + kGridBase) << 20) | (1u << 19));
-      const double wm = wj * mid;
-      p0 = p0 + wj;
-      p1 = p1 + wm;
-      p2 = p2 + wm * mid;
-      row[j + 1].p0 = p0; row[j + 1].p1 = p1; row[j + 1].p2 = p2;
+      p = p + src[j];
+      dst[4 * (j + 1)] = p;
     }
+    if (f == 0) row[kGridPoints].g = 0.0;
   }
   __syncthreads();
   if (row[kGridPoints].p0 == 0.0) return;   // no sampled mass at all: the type keeps its levels
   const double inf = __longlong_as_double(0x7FF0000000000000ll);
   short *arg = a.dp_arg + a.dp_arg_off[mtype];
+  const bool lds_arg = S <= kFitLdsPoints;   // candidates a are at most 254: a byte each, 255 for "none"
   if (S > 2) {
     // level 1 at grid index b: cost of the bins below g_b against the levels 0 and g_b
     for (int b = t; b < kGridPoints; b += kFitThreads)
       D[1][b] = (b >= 1 && b <= last - (S - 2)) ? (row[b].g * row[b].p1 - row[b].p2) : inf;
     __syncthreads();
-    const int b = t >> 2, q = t & 3;   // interior levels only ever sit at b <= 255
+    // Four threads per grid index b (interior levels only ever sit at b <= 255), each scanning a quarter of the
+    // candidates a.  A wave covers 16 consecutive b and its work grows with b; the waves take the blocks of 16 in
+    // serpentine order so that the four waves sharing a SIMD (every fourth wave) carry equal work in total.
+    const int wv = t >> 6;
+    const int blk = (wv & 4) ? (wv ^ 3) : wv;
+    const int b = blk * 16 + ((t >> 2) & 15), q = t & 3;
     for (int s = 2; s <= S - 2; ++s) {
       const double *Dp = D[(s - 1) & 1];
       double *Dc = D[s & 1];
@@ -1299,7 +1312,8 @@ __global__ void __launch_bounds__(kFitThreads) k_fit_dp(Dev a) {
       }
       if (q == 0) {
         Dc[b] = best;
-        arg[(size_t)s * kGridPoints + b] = (short)(best < inf ? besta : -1);
+        if (lds_arg) sarg[s * 256 + b] = (unsigned char)(best < inf ? besta : 255);
+        else arg[(size_t)s * kGridPoints + b] = (short)(best < inf ? besta : -1);
       }
       if (t == 0) Dc[last] = inf;
       __syncthreads();
@@ -1335,7 +1349,7 @@ __global__ void __launch_bounds__(kFitThreads) k_fit_dp(Dev a) {
       for (int s = S - 2; s >= 1; --s) {
         b = max(1, min(b, last - 1));   // cannot trigger for finite costs; keeps a corrupted table in bounds
         slev[s] = grid_value(b);
-        if (s >= 2) b = arg[(size_t)s * kGridPoints + b];
+        if (s >= 2) b = lds_arg ? (int)sarg[s * 256 + b] : (int)arg[(size_t)s * kGridPoints + b];
       }
     }
     for (int j = 0; j < S; ++j) a.lev[(size_t)mtype * kMaxPoints + j] = slev[j];
