@@ -14,7 +14,8 @@
  *     waits for the device except qoda_get_levels, qoda_read_buffer and qoda_status, which say so.
  *   - Every call returns QODA_OK (0) or a negative error code and then qoda_last_error() describes it.  Nothing
  *     throws across this boundary.  Bad arguments are rejected before anything is launched.
- *   - A context is not thread-safe: use it from one host thread at a time, on one stream at a time.
+ *   - A context is not thread-safe: use it from one host thread at a time, on one stream at a time.  It belongs to
+ *     the device that was current in qoda_create; a call made with another device current returns QODA_EINVAL.
  *   - The library keeps a few device copies of every pointer array it is given; once each distinct set of arrays has
  *     been used, the calls of a round enqueue kernels (and, for the statistics-based fit, one device-to-device copy)
  *     only: no upload, no wait.  Such a steady-state round can be captured into a HIP graph; pointers and the round

@@ -20,6 +20,7 @@ using namespace qoda;
 struct qoda_ctx {
   int L = 0, M = 0, K = 0, G = 0;
   int scope = 0;   // NormScope
+  int device = 0;  // the device that was current at creation: owns every allocation of the context
   uint64_t seed = 0;
   std::vector<LayerMeta> meta;
   std::vector<int> type_points;
@@ -95,6 +96,28 @@ int fail(qoda_ctx *c, int code, const char *fmt, ...) {
     c->err = buf;
   }
   return code;
+}
+
+// No exception may cross the C boundary: every entry point that can allocate host memory runs its body through this.
+template <class F>
+int guarded(qoda_ctx *c, F &&body) {
+  try {
+    return body();
+  } catch (const std::bad_alloc &) {
+    if (c) c->err.clear();   // no allocation on this path
+    return QODA_ENOMEM;
+  } catch (...) {
+    if (c) c->err.clear();
+    return QODA_EHIP;
+  }
+}
+
+// The context's buffers live on one device; a call made with another device current would launch there.
+int check_device(qoda_ctx *c) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return fail(c, QODA_EHIP, "hipGetDevice failed");
+  if (dev != c->device) return fail(c, QODA_EINVAL, "the context was created on device %d but device %d is current", c->device, dev);
+  return QODA_OK;
 }
 
 #define HIP_TRY(c, call)                                                                        \
@@ -278,19 +301,12 @@ int quantize_impl(qoda_ctx *c, int node0, int nnodes, const float *const *grad_f
 
 extern "C" {
 
-int qoda_create(const qoda_config *cfg, qoda_ctx **out) {
-  if (!out) return QODA_EINVAL;
-  *out = nullptr;
-  if (!cfg || !cfg->layer_size || !cfg->layer_type || !cfg->type_points) return QODA_EINVAL;
-  if (cfg->num_layers < 1 || cfg->num_types < 1 || cfg->num_nodes < 1 || cfg->num_nodes > 65535) return QODA_EINVAL;
-  if (cfg->norm_kind != 2) return QODA_EINVAL;
-  if (cfg->norm_scope < QODA_SCOPE_LAYER || cfg->norm_scope > QODA_SCOPE_BUCKET) return QODA_EINVAL;
-  qoda_ctx *c = new (std::nothrow) qoda_ctx;
-  if (!c) return QODA_ENOMEM;
+// Fills a fresh context from the configuration; on failure the caller releases whatever was allocated so far.
+static int create_impl(const qoda_config *cfg, qoda_ctx *c) {
   c->L = cfg->num_layers; c->M = cfg->num_types; c->K = cfg->num_nodes; c->seed = cfg->seed;
   c->scope = cfg->norm_scope;
   for (int m = 0; m < c->M; ++m) {
-    if (cfg->type_points[m] < 2 || cfg->type_points[m] > QODA_MAX_POINTS) { delete c; return QODA_EINVAL; }
+    if (cfg->type_points[m] < 2 || cfg->type_points[m] > QODA_MAX_POINTS) return QODA_EINVAL;
     c->type_points.push_back(cfg->type_points[m]);
   }
   size_t hdr = 0;
@@ -299,7 +315,7 @@ int qoda_create(const qoda_config *cfg, qoda_ctx **out) {
   for (int l = 0; l < c->L; ++l) {
     const long long d = cfg->layer_size[l];
     const int ty = cfg->layer_type[l];
-    if (d < 0 || d >= (1ll << 34) || ty < 0 || ty >= c->M) { delete c; return QODA_EINVAL; }
+    if (d < 0 || d >= (1ll << 34) || ty < 0 || ty >= c->M) return QODA_EINVAL;
     LayerMeta &m = c->meta[l];
     m.d = d;
     m.type = ty;
@@ -314,9 +330,9 @@ int qoda_create(const qoda_config *cfg, qoda_ctx **out) {
     if (m.S > c->maxS) c->maxS = m.S;
     if ((1 << m.planes) > c->maxSP) c->maxSP = 1 << m.planes;
     c->planes_mask |= 1u << m.planes;
-    if (hdr > (1u << 30) || chunks > (1ll << 30)) { delete c; return QODA_EINVAL; }
+    if (hdr > (1u << 30) || chunks > (1ll << 30)) return QODA_EINVAL;
   }
-  if ((size_t)c->K * c->maxSP * sizeof(float) > 64 * 1024) { delete c; return QODA_EINVAL; }   // decode tables must fit LDS
+  if ((size_t)c->K * c->maxSP * sizeof(float) > 64 * 1024) return QODA_EINVAL;   // decode tables must fit LDS
   c->header_bytes = round_up(hdr, 256);
   size_t off = c->header_bytes;
   for (int l = 0; l < c->L; ++l) {
@@ -393,11 +409,7 @@ int qoda_create(const qoda_config *cfg, qoda_ctx **out) {
     const float one[3] = {1.0f, 1.0f, 1.0f};
     A(hipMemcpy(c->d_eta, one, sizeof one, hipMemcpyHostToDevice));
   }
-  if (e != hipSuccess) {
-    free_all(c);
-    delete c;
-    return e == hipErrorOutOfMemory ? QODA_ENOMEM : QODA_EHIP;
-  }
+  if (e != hipSuccess) return e == hipErrorOutOfMemory ? QODA_ENOMEM : QODA_EHIP;
   // uniform initial levels l_j = j / (S - 1)
   for (int m = 0; m < c->M; ++m) {
     const int S = c->type_points[m];
@@ -405,9 +417,29 @@ int qoda_create(const qoda_config *cfg, qoda_ctx **out) {
     for (int j = 0; j < S; ++j) lev[j] = (float)((double)j / (double)(S - 1));
     lev[S - 1] = 1.0f;
     int rc = qoda_set_levels(c, m, lev.data(), nullptr);
-    if (rc != QODA_OK) { free_all(c); delete c; return rc; }
+    if (rc != QODA_OK) return rc;
   }
-  if (hipDeviceSynchronize() != hipSuccess) { free_all(c); delete c; return QODA_EHIP; }
+  if (hipDeviceSynchronize() != hipSuccess) return QODA_EHIP;
+  return QODA_OK;
+}
+
+
+int qoda_create(const qoda_config *cfg, qoda_ctx **out) {
+  if (!out) return QODA_EINVAL;
+  *out = nullptr;
+  if (!cfg || !cfg->layer_size || !cfg->layer_type || !cfg->type_points) return QODA_EINVAL;
+  if (cfg->num_layers < 1 || cfg->num_types < 1 || cfg->num_nodes < 1 || cfg->num_nodes > 65535) return QODA_EINVAL;
+  if (cfg->norm_kind != 2) return QODA_EINVAL;
+  if (cfg->norm_scope < QODA_SCOPE_LAYER || cfg->norm_scope > QODA_SCOPE_BUCKET) return QODA_EINVAL;
+  qoda_ctx *c = new (std::nothrow) qoda_ctx;
+  if (!c) return QODA_ENOMEM;
+  int rc = (hipGetDevice(&c->device) == hipSuccess) ? QODA_OK : QODA_EHIP;
+  if (rc == QODA_OK) rc = guarded(c, [&]() -> int { return create_impl(cfg, c); });
+  if (rc != QODA_OK) {
+    free_all(c);
+    delete c;
+    return rc;
+  }
   *out = c;
   return QODA_OK;
 }
@@ -433,142 +465,157 @@ int qoda_message_layout(const qoda_ctx *c, int64_t *hdr_off, int64_t *body_off) 
 
 int qoda_set_levels(qoda_ctx *c, int32_t type, const float *lev, void *stream) {
   if (!c) return QODA_EINVAL;
-  if (type < 0 || type >= c->M || !lev) return fail(c, QODA_EINVAL, "qoda_set_levels: bad type or null levels");
-  const int S = c->type_points[type];
-  if (lev[0] != 0.0f || lev[S - 1] != 1.0f) return fail(c, QODA_EINVAL, "qoda_set_levels: levels must start at 0 and end at 1");
-  for (int j = 0; j + 1 < S; ++j)
-    if (!(lev[j] < lev[j + 1])) return fail(c, QODA_EINVAL, "qoda_set_levels: levels must be strictly increasing");
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  if (c->upload_pending) {   // an earlier asynchronous upload may still be reading a host shadow
-    HIP_TRY(c, hipEventSynchronize(c->upload_done));
-    c->upload_pending = false;
-  }
-  float *shadow = c->h_lev.data() + (size_t)type * kMaxPoints;
-  std::memcpy(shadow, lev, S * sizeof(float));
-  HIP_TRY(c, hipMemcpyAsync(c->d_lev + (size_t)type * kMaxPoints, shadow, S * sizeof(float), hipMemcpyHostToDevice, s));
-  HIP_TRY(c, hipEventRecord(c->upload_done, s));
-  c->upload_pending = true;
-  Dev a = base_args(c);
-  LAUNCH(c, kIdBuildTables, s, launch_build_tables(a, type, s));
-  return QODA_OK;
+  return guarded(c, [&]() -> int {
+    if (const int rc_ = check_device(c)) return rc_;
+    if (type < 0 || type >= c->M || !lev) return fail(c, QODA_EINVAL, "qoda_set_levels: bad type or null levels");
+    const int S = c->type_points[type];
+    if (lev[0] != 0.0f || lev[S - 1] != 1.0f) return fail(c, QODA_EINVAL, "qoda_set_levels: levels must start at 0 and end at 1");
+    for (int j = 0; j + 1 < S; ++j)
+      if (!(lev[j] < lev[j + 1])) return fail(c, QODA_EINVAL, "qoda_set_levels: levels must be strictly increasing");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (c->upload_pending) {   // an earlier asynchronous upload may still be reading a host shadow
+      HIP_TRY(c, hipEventSynchronize(c->upload_done));
+      c->upload_pending = false;
+    }
+    float *shadow = c->h_lev.data() + (size_t)type * kMaxPoints;
+    std::memcpy(shadow, lev, S * sizeof(float));
+    HIP_TRY(c, hipMemcpyAsync(c->d_lev + (size_t)type * kMaxPoints, shadow, S * sizeof(float), hipMemcpyHostToDevice, s));
+    HIP_TRY(c, hipEventRecord(c->upload_done, s));
+    c->upload_pending = true;
+    Dev a = base_args(c);
+    LAUNCH(c, kIdBuildTables, s, launch_build_tables(a, type, s));
+    return QODA_OK;
+  });
 }
 
 int qoda_get_levels(qoda_ctx *c, int32_t type, float *lev, void *stream) {
   if (!c) return QODA_EINVAL;
-  if (type < 0 || type >= c->M || !lev) return fail(c, QODA_EINVAL, "qoda_get_levels: bad type or null output");
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  HIP_TRY(c, hipMemcpyAsync(lev, c->d_lev + (size_t)type * kMaxPoints, c->type_points[type] * sizeof(float),
-                            hipMemcpyDeviceToHost, s));
-  HIP_TRY(c, hipStreamSynchronize(s));
-  return QODA_OK;
+  return guarded(c, [&]() -> int {
+    if (const int rc_ = check_device(c)) return rc_;
+    if (type < 0 || type >= c->M || !lev) return fail(c, QODA_EINVAL, "qoda_get_levels: bad type or null output");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    HIP_TRY(c, hipMemcpyAsync(lev, c->d_lev + (size_t)type * kMaxPoints, c->type_points[type] * sizeof(float),
+                              hipMemcpyDeviceToHost, s));
+    HIP_TRY(c, hipStreamSynchronize(s));
+    return QODA_OK;
+  });
 }
 
 int qoda_fit_levels(qoda_ctx *c, const float *const *grad_dev, uint32_t round, void *stream) {
   if (!c) return QODA_EINVAL;
-  const size_t KL = (size_t)c->K * c->L;
-  if (!grad_dev && c->scope == kScopeBucket) {
-    // from the statistics the last quantize pass of every node gathered: pool, fit (with the scale they were gathered
-    // under), then the scale for the next pass from the gathered maxima
+  return guarded(c, [&]() -> int {
+    if (const int rc_ = check_device(c)) return rc_;
+    const size_t KL = (size_t)c->K * c->L;
+    if (!grad_dev && c->scope == kScopeBucket) {
+      // from the statistics the last quantize pass of every node gathered: pool, fit (with the scale they were gathered
+      // under), then the scale for the next pass from the gathered maxima
+      hipStream_t s = static_cast<hipStream_t>(stream);
+      Dev a = base_args(c);
+      a.round = round;
+      Dev nx = a;
+      nx.type_exp = c->d_type_exp_next;
+      LAUNCH(c, kIdFitTypemax, s, launch_fit_typemax(nx, s));   // also clears the pooled weights
+      LAUNCH(c, kIdFitPool, s, launch_fit_pool_b(a, s));
+      LAUNCH(c, kIdFitDp, s, launch_fit_dp(a, s));
+      HIP_TRY(c, hipMemcpyAsync(c->d_type_exp, c->d_type_exp_next, c->M * sizeof(int), hipMemcpyDeviceToDevice, s));
+      return QODA_OK;
+    }
+    int rc = check_layer_ptrs(c, reinterpret_cast<const void *const *>(grad_dev), KL, "qoda_fit_levels: grad_dev", true);
+    if (rc) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!c->d_hist) HIP_TRY(c, dev_alloc(&c->d_hist, KL * kHistBins));
+    rc = sync_table(c, c->t_grad, reinterpret_cast<const void *const *>(grad_dev), KL, s);
+    if (rc) return rc;
+    c->norms_valid = false;
     Dev a = base_args(c);
+    a.grad = reinterpret_cast<const float *const *>(c->t_grad.dev());
     a.round = round;
-    Dev nx = a;
-    nx.type_exp = c->d_type_exp_next;
-    LAUNCH(c, kIdFitTypemax, s, launch_fit_typemax(nx, s));   // also clears the pooled weights
-    LAUNCH(c, kIdFitPool, s, launch_fit_pool_b(a, s));
-    LAUNCH(c, kIdFitDp, s, launch_fit_dp(a, s));
-    HIP_TRY(c, hipMemcpyAsync(c->d_type_exp, c->d_type_exp_next, c->M * sizeof(int), hipMemcpyDeviceToDevice, s));
-    return QODA_OK;
-  }
-  int rc = check_layer_ptrs(c, reinterpret_cast<const void *const *>(grad_dev), KL, "qoda_fit_levels: grad_dev", true);
-  if (rc) return rc;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  if (!c->d_hist) HIP_TRY(c, dev_alloc(&c->d_hist, KL * kHistBins));
-  rc = sync_table(c, c->t_grad, reinterpret_cast<const void *const *>(grad_dev), KL, s);
-  if (rc) return rc;
-  c->norms_valid = false;
-  Dev a = base_args(c);
-  a.grad = reinterpret_cast<const float *const *>(c->t_grad.dev());
-  a.round = round;
-  LAUNCH(c, kIdZero, s, launch_zero_u32(c->d_hist, KL * kHistBins, s));
-  if (c->scope == kScopeBucket) {
-    // two passes over the sampled quarter of the gradient: the scale of the weights, then the weighted histogram
-    LAUNCH(c, kIdZero, s, launch_zero_u32(reinterpret_cast<unsigned int *>(c->d_sumsq), 2 * KL, s));
-    LAUNCH(c, kIdBucketMax, s, launch_bucket_max(a, s));
+    LAUNCH(c, kIdZero, s, launch_zero_u32(c->d_hist, KL * kHistBins, s));
+    if (c->scope == kScopeBucket) {
+      // two passes over the sampled quarter of the gradient: the scale of the weights, then the weighted histogram
+      LAUNCH(c, kIdZero, s, launch_zero_u32(reinterpret_cast<unsigned int *>(c->d_sumsq), 2 * KL, s));
+      LAUNCH(c, kIdBucketMax, s, launch_bucket_max(a, s));
+      LAUNCH(c, kIdFitTypemax, s, launch_fit_typemax(a, s));
+      LAUNCH(c, kIdBucketHist, s, launch_bucket_hist(a, s));
+      LAUNCH(c, kIdFitDp, s, launch_fit_dp(a, s));
+      return QODA_OK;
+    }
+    rc = run_norm_pass(c, a, true, s);
+    if (rc) return rc;
     LAUNCH(c, kIdFitTypemax, s, launch_fit_typemax(a, s));
-    LAUNCH(c, kIdBucketHist, s, launch_bucket_hist(a, s));
+    LAUNCH(c, kIdFitPool, s, launch_fit_pool(a, s));
     LAUNCH(c, kIdFitDp, s, launch_fit_dp(a, s));
+    c->norms_grad.assign(grad_dev, grad_dev + KL);
+    c->norms_round = round;
+    c->norms_valid = true;
     return QODA_OK;
-  }
-  rc = run_norm_pass(c, a, true, s);
-  if (rc) return rc;
-  LAUNCH(c, kIdFitTypemax, s, launch_fit_typemax(a, s));
-  LAUNCH(c, kIdFitPool, s, launch_fit_pool(a, s));
-  LAUNCH(c, kIdFitDp, s, launch_fit_dp(a, s));
-  c->norms_grad.assign(grad_dev, grad_dev + KL);
-  c->norms_round = round;
-  c->norms_valid = true;
-  return QODA_OK;
+  });
 }
 
 int qoda_quantize_all(qoda_ctx *c, const float *const *grad_dev, uint32_t round, void *const *msg_dev,
                       const void *const *msg_prev_dev, void *stream) {
   if (!c) return QODA_EINVAL;
-  const size_t KL = (size_t)c->K * c->L;
-  int rc = check_layer_ptrs(c, reinterpret_cast<const void *const *>(grad_dev), KL, "qoda_quantize_all: grad_dev", true);
-  if (rc) return rc;
-  rc = check_msg_ptrs(c, reinterpret_cast<const void *const *>(msg_dev), c->K, "qoda_quantize_all: msg_dev", false);
-  if (rc) return rc;
-  if (msg_prev_dev) {
-    rc = check_msg_ptrs(c, msg_prev_dev, c->K, "qoda_quantize_all: msg_prev_dev", true);
+  return guarded(c, [&]() -> int {
+    if (const int rc_ = check_device(c)) return rc_;
+    const size_t KL = (size_t)c->K * c->L;
+    int rc = check_layer_ptrs(c, reinterpret_cast<const void *const *>(grad_dev), KL, "qoda_quantize_all: grad_dev", true);
     if (rc) return rc;
-    for (int k = 0; k < c->K; ++k)
-      if (msg_prev_dev[k] == msg_dev[k]) return fail(c, QODA_EINVAL, "qoda_quantize_all: msg_prev_dev[%d] aliases msg_dev", k);
-  }
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  rc = sync_table(c, c->t_grad, reinterpret_cast<const void *const *>(grad_dev), KL, s);
-  if (rc) return rc;
-  rc = sync_table(c, c->t_msg, reinterpret_cast<const void *const *>(msg_dev), c->K, s);
-  if (rc) return rc;
-  if (msg_prev_dev) {
-    rc = sync_table(c, c->t_prev, msg_prev_dev, c->K, s);
+    rc = check_msg_ptrs(c, reinterpret_cast<const void *const *>(msg_dev), c->K, "qoda_quantize_all: msg_dev", false);
     if (rc) return rc;
-  }
-  return quantize_impl(c, 0, c->K, grad_dev, round, s, msg_prev_dev != nullptr);
+    if (msg_prev_dev) {
+      rc = check_msg_ptrs(c, msg_prev_dev, c->K, "qoda_quantize_all: msg_prev_dev", true);
+      if (rc) return rc;
+      for (int k = 0; k < c->K; ++k)
+        if (msg_prev_dev[k] == msg_dev[k]) return fail(c, QODA_EINVAL, "qoda_quantize_all: msg_prev_dev[%d] aliases msg_dev", k);
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    rc = sync_table(c, c->t_grad, reinterpret_cast<const void *const *>(grad_dev), KL, s);
+    if (rc) return rc;
+    rc = sync_table(c, c->t_msg, reinterpret_cast<const void *const *>(msg_dev), c->K, s);
+    if (rc) return rc;
+    if (msg_prev_dev) {
+      rc = sync_table(c, c->t_prev, msg_prev_dev, c->K, s);
+      if (rc) return rc;
+    }
+    return quantize_impl(c, 0, c->K, grad_dev, round, s, msg_prev_dev != nullptr);
+  });
 }
 
 int qoda_quantize(qoda_ctx *c, int32_t node, const float *const *grad_dev, uint32_t round, void *msg_dev,
                   const void *msg_prev_dev, void *stream) {
   if (!c) return QODA_EINVAL;
-  if (node < 0 || node >= c->K) return fail(c, QODA_EINVAL, "qoda_quantize: node %d out of range", node);
-  int rc = check_layer_ptrs(c, reinterpret_cast<const void *const *>(grad_dev), c->L, "qoda_quantize: grad_dev", true);
-  if (rc) return rc;
-  const void *mp[1] = {msg_dev};
-  rc = check_msg_ptrs(c, mp, 1, "qoda_quantize: msg_dev", false);
-  if (rc) return rc;
-  const void *pp[1] = {msg_prev_dev};
-  rc = check_msg_ptrs(c, pp, 1, "qoda_quantize: msg_prev_dev", true);
-  if (rc) return rc;
-  if (msg_prev_dev == msg_dev) return fail(c, QODA_EINVAL, "qoda_quantize: msg_prev_dev aliases msg_dev");
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  // splice this node's pointers into full-size shadows of the K*L / K tables
-  const size_t KL = (size_t)c->K * c->L;
-  std::vector<void *> g(c->t_grad.valid() ? c->t_grad.host() : std::vector<void *>(KL, nullptr));
-  g.resize(KL, nullptr);
-  for (int l = 0; l < c->L; ++l) g[(size_t)node * c->L + l] = const_cast<float *>(grad_dev[l]);
-  std::vector<void *> m(c->t_msg.valid() ? c->t_msg.host() : std::vector<void *>(c->K, nullptr));
-  m.resize(c->K, nullptr);
-  m[node] = msg_dev;
-  std::vector<void *> p(c->t_prev.valid() ? c->t_prev.host() : std::vector<void *>(c->K, nullptr));
-  p.resize(c->K, nullptr);
-  p[node] = const_cast<void *>(msg_prev_dev);
-  rc = sync_table(c, c->t_grad, g.data(), KL, s);
-  if (rc) return rc;
-  rc = sync_table(c, c->t_msg, m.data(), c->K, s);
-  if (rc) return rc;
-  rc = sync_table(c, c->t_prev, p.data(), c->K, s);
-  if (rc) return rc;
-  return quantize_impl(c, node, 1, reinterpret_cast<const float *const *>(c->t_grad.host().data()), round, s, true);
+  return guarded(c, [&]() -> int {
+    if (const int rc_ = check_device(c)) return rc_;
+    if (node < 0 || node >= c->K) return fail(c, QODA_EINVAL, "qoda_quantize: node %d out of range", node);
+    int rc = check_layer_ptrs(c, reinterpret_cast<const void *const *>(grad_dev), c->L, "qoda_quantize: grad_dev", true);
+    if (rc) return rc;
+    const void *mp[1] = {msg_dev};
+    rc = check_msg_ptrs(c, mp, 1, "qoda_quantize: msg_dev", false);
+    if (rc) return rc;
+    const void *pp[1] = {msg_prev_dev};
+    rc = check_msg_ptrs(c, pp, 1, "qoda_quantize: msg_prev_dev", true);
+    if (rc) return rc;
+    if (msg_prev_dev == msg_dev) return fail(c, QODA_EINVAL, "qoda_quantize: msg_prev_dev aliases msg_dev");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // splice this node's pointers into full-size shadows of the K*L / K tables
+    const size_t KL = (size_t)c->K * c->L;
+    std::vector<void *> g(c->t_grad.valid() ? c->t_grad.host() : std::vector<void *>(KL, nullptr));
+    g.resize(KL, nullptr);
+    for (int l = 0; l < c->L; ++l) g[(size_t)node * c->L + l] = const_cast<float *>(grad_dev[l]);
+    std::vector<void *> m(c->t_msg.valid() ? c->t_msg.host() : std::vector<void *>(c->K, nullptr));
+    m.resize(c->K, nullptr);
+    m[node] = msg_dev;
+    std::vector<void *> p(c->t_prev.valid() ? c->t_prev.host() : std::vector<void *>(c->K, nullptr));
+    p.resize(c->K, nullptr);
+    p[node] = const_cast<void *>(msg_prev_dev);
+    rc = sync_table(c, c->t_grad, g.data(), KL, s);
+    if (rc) return rc;
+    rc = sync_table(c, c->t_msg, m.data(), c->K, s);
+    if (rc) return rc;
+    rc = sync_table(c, c->t_prev, p.data(), c->K, s);
+    if (rc) return rc;
+    return quantize_impl(c, node, 1, reinterpret_cast<const float *const *>(c->t_grad.host().data()), round, s, true);
+  });
 }
 
 static int decode_common(qoda_ctx *c, const void *const *msgs_dev, Dev &a, hipStream_t s, const char *who) {
@@ -582,17 +629,20 @@ static int decode_common(qoda_ctx *c, const void *const *msgs_dev, Dev &a, hipSt
 
 int qoda_dequant_aggregate(qoda_ctx *c, const void *const *msgs_dev, float *const *mean_out_dev, void *stream) {
   if (!c) return QODA_EINVAL;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  Dev a = base_args(c);
-  int rc = decode_common(c, msgs_dev, a, s, "qoda_dequant_aggregate: msgs_dev");
-  if (rc) return rc;
-  rc = check_layer_ptrs(c, reinterpret_cast<const void *const *>(mean_out_dev), c->L, "qoda_dequant_aggregate: mean_out_dev", true);
-  if (rc) return rc;
-  rc = sync_table(c, c->t_mean, reinterpret_cast<const void *const *>(mean_out_dev), c->L, s);
-  if (rc) return rc;
-  a.mean_out = reinterpret_cast<float *const *>(c->t_mean.dev());
-  LAUNCH(c, kIdDecodeMean, s, launch_decode(a, kDecodeMean, c->planes_mask, s));
-  return QODA_OK;
+  return guarded(c, [&]() -> int {
+    if (const int rc_ = check_device(c)) return rc_;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Dev a = base_args(c);
+    int rc = decode_common(c, msgs_dev, a, s, "qoda_dequant_aggregate: msgs_dev");
+    if (rc) return rc;
+    rc = check_layer_ptrs(c, reinterpret_cast<const void *const *>(mean_out_dev), c->L, "qoda_dequant_aggregate: mean_out_dev", true);
+    if (rc) return rc;
+    rc = sync_table(c, c->t_mean, reinterpret_cast<const void *const *>(mean_out_dev), c->L, s);
+    if (rc) return rc;
+    a.mean_out = reinterpret_cast<float *const *>(c->t_mean.dev());
+    LAUNCH(c, kIdDecodeMean, s, launch_decode(a, kDecodeMean, c->planes_mask, s));
+    return QODA_OK;
+  });
 }
 
 // Shared by the two step entry points: checks and uploads the K message pointers and the four state tables.
@@ -622,39 +672,45 @@ static int step_common(qoda_ctx *c, const void *const *msgs_dev, const float *co
 
 int qoda_step(qoda_ctx *c, const void *const *msgs_dev, const qoda_state *st, void *stream) {
   if (!c) return QODA_EINVAL;
-  if (!st || !st->acc_dev) return fail(c, QODA_EINVAL, "qoda_step: null state or accumulator");
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  Dev a = base_args(c);
-  const int rc = step_common(c, msgs_dev, st->x1_dev, st->y_dev, st->x_half_dev, st->x_next_dev, a, s, "qoda_step");
-  if (rc) return rc;
-  a.acc = st->acc_dev;
-  a.eta_out = st->eta_dev;
-  LAUNCH(c, kIdStepScalars, s, launch_step_scalars(a, s));
-  LAUNCH(c, kIdDecodeUpdate, s, launch_decode(a, kDecodeUpdate, c->planes_mask, s));
-  return QODA_OK;
+  return guarded(c, [&]() -> int {
+    if (const int rc_ = check_device(c)) return rc_;
+    if (!st || !st->acc_dev) return fail(c, QODA_EINVAL, "qoda_step: null state or accumulator");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Dev a = base_args(c);
+    const int rc = step_common(c, msgs_dev, st->x1_dev, st->y_dev, st->x_half_dev, st->x_next_dev, a, s, "qoda_step");
+    if (rc) return rc;
+    a.acc = st->acc_dev;
+    a.eta_out = st->eta_dev;
+    LAUNCH(c, kIdStepScalars, s, launch_step_scalars(a, s));
+    LAUNCH(c, kIdDecodeUpdate, s, launch_decode(a, kDecodeUpdate, c->planes_mask, s));
+    return QODA_OK;
+  });
 }
 
 int qoda_index_counts(qoda_ctx *c, const void *const *msgs_dev, uint64_t *counts, void *stream) {
   if (!c) return QODA_EINVAL;
-  if (!counts) return fail(c, QODA_EINVAL, "qoda_index_counts: null output");
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  const size_t n = (size_t)c->M * 256;
-  if (!c->d_index_counts) HIP_TRY(c, dev_alloc(&c->d_index_counts, n));
-  Dev a = base_args(c);
-  int rc = decode_common(c, msgs_dev, a, s, "qoda_index_counts: msgs_dev");
-  if (rc) return rc;
-  a.index_counts = c->d_index_counts;
-  LAUNCH(c, kIdZero, s, launch_zero_u32(reinterpret_cast<unsigned int *>(c->d_index_counts), 2 * n, s));
-  LAUNCH(c, kIdIndexHist, s, launch_index_hist(a, c->planes_mask, s));
-  static_assert(sizeof(uint64_t) == sizeof(unsigned long long), "64-bit counters");
-  HIP_TRY(c, hipMemcpyAsync(counts, c->d_index_counts, n * sizeof(uint64_t), hipMemcpyDeviceToHost, s));
-  HIP_TRY(c, hipStreamSynchronize(s));
-  for (int l = 0; l < c->L; ++l) {   // padding coordinates carry index 0
-    const LayerMeta &m = c->meta[l];
-    const uint64_t pad = (uint64_t)(((m.nblk + 7) / 8) * 2048 - m.d) * (uint64_t)c->K;
-    counts[(size_t)m.type * 256] -= pad;
-  }
-  return QODA_OK;
+  return guarded(c, [&]() -> int {
+    if (const int rc_ = check_device(c)) return rc_;
+    if (!counts) return fail(c, QODA_EINVAL, "qoda_index_counts: null output");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t n = (size_t)c->M * 256;
+    if (!c->d_index_counts) HIP_TRY(c, dev_alloc(&c->d_index_counts, n));
+    Dev a = base_args(c);
+    int rc = decode_common(c, msgs_dev, a, s, "qoda_index_counts: msgs_dev");
+    if (rc) return rc;
+    a.index_counts = c->d_index_counts;
+    LAUNCH(c, kIdZero, s, launch_zero_u32(reinterpret_cast<unsigned int *>(c->d_index_counts), 2 * n, s));
+    LAUNCH(c, kIdIndexHist, s, launch_index_hist(a, c->planes_mask, s));
+    static_assert(sizeof(uint64_t) == sizeof(unsigned long long), "64-bit counters");
+    HIP_TRY(c, hipMemcpyAsync(counts, c->d_index_counts, n * sizeof(uint64_t), hipMemcpyDeviceToHost, s));
+    HIP_TRY(c, hipStreamSynchronize(s));
+    for (int l = 0; l < c->L; ++l) {   // padding coordinates carry index 0
+      const LayerMeta &m = c->meta[l];
+      const uint64_t pad = (uint64_t)(((m.nblk + 7) / 8) * 2048 - m.d) * (uint64_t)c->K;
+      counts[(size_t)m.type * 256] -= pad;
+    }
+    return QODA_OK;
+  });
 }
 
 // Total length of an optimal prefix code for the given occurrence counts: the counts are sorted once, then the two
@@ -687,124 +743,138 @@ static double huffman_total(const uint64_t *cnt, int n) {
 
 int qoda_code_length(qoda_ctx *c, const uint64_t *counts, uint32_t num_messages, qoda_code_length_report *out) {
   if (!c) return QODA_EINVAL;
-  if (!counts || !out) return fail(c, QODA_EINVAL, "qoda_code_length: null argument");
-  double norms = 0.0;   // 32-bit norms one message carries
-  if (c->scope == kScopeVector) norms = 1.0;
-  else
-    for (int l = 0; l < c->L; ++l) {
-      const long long d = c->meta[l].d;
-      if (d == 0) continue;
-      norms += (c->scope == kScopeBucket) ? (double)((d + kBucketCoords - 1) / kBucketCoords) : 1.0;
+  return guarded(c, [&]() -> int {
+    if (!counts || !out) return fail(c, QODA_EINVAL, "qoda_code_length: null argument");
+    double norms = 0.0;   // 32-bit norms one message carries
+    if (c->scope == kScopeVector) norms = 1.0;
+    else
+      for (int l = 0; l < c->L; ++l) {
+        const long long d = c->meta[l].d;
+        if (d == 0) continue;
+        norms += (c->scope == kScopeBucket) ? (double)((d + kBucketCoords - 1) / kBucketCoords) : 1.0;
+      }
+    const double cq = 32.0 * norms * (double)num_messages;
+    double fixed = cq, paper = cq, entropy = cq, huff = cq, nonzero = 0.0, coords = 0.0;
+    for (int m = 0; m < c->M; ++m) {
+      const uint64_t *cm = counts + (size_t)m * 256;
+      const int Sm = c->type_points[m];
+      double n = 0.0;
+      for (int j = 0; j < 256; ++j) n += (double)cm[j];
+      if (n == 0.0) continue;
+      const double nz = n - (double)cm[0];
+      double h_all = 0.0, h_int = 0.0;
+      for (int j = 0; j < 256; ++j) {
+        if (!cm[j]) continue;
+        const double p = (double)cm[j] / n;
+        const double t = -p * std::log2(p);
+        h_all += t;
+        if (j >= 1 && j <= Sm - 2) h_int += t;
+      }
+      fixed += n * (double)(1 + index_bits(Sm));
+      paper += nz + n * (1.0 + h_int);
+      entropy += nz + n * h_all;
+      huff += nz + huffman_total(cm, 256);
+      nonzero += nz;
+      coords += n;
     }
-  const double cq = 32.0 * norms * (double)num_messages;
-  double fixed = cq, paper = cq, entropy = cq, huff = cq, nonzero = 0.0, coords = 0.0;
-  for (int m = 0; m < c->M; ++m) {
-    const uint64_t *cm = counts + (size_t)m * 256;
-    const int Sm = c->type_points[m];
-    double n = 0.0;
-    for (int j = 0; j < 256; ++j) n += (double)cm[j];
-    if (n == 0.0) continue;
-    const double nz = n - (double)cm[0];
-    double h_all = 0.0, h_int = 0.0;
-    for (int j = 0; j < 256; ++j) {
-      if (!cm[j]) continue;
-      const double p = (double)cm[j] / n;
-      const double t = -p * std::log2(p);
-      h_all += t;
-      if (j >= 1 && j <= Sm - 2) h_int += t;
-    }
-    fixed += n * (double)(1 + index_bits(Sm));
-    paper += nz + n * (1.0 + h_int);
-    entropy += nz + n * h_all;
-    huff += nz + huffman_total(cm, 256);
-    nonzero += nz;
-    coords += n;
-  }
-  out->fixed_bits = fixed;
-  out->paper_bits = paper;
-  out->entropy_bits = entropy;
-  out->huffman_bits = huff;
-  out->nonzeros = nonzero;
-  out->coordinates = coords;
-  out->message_bits = 8.0 * (double)c->message_bytes * (double)num_messages;
-  return QODA_OK;
+    out->fixed_bits = fixed;
+    out->paper_bits = paper;
+    out->entropy_bits = entropy;
+    out->huffman_bits = huff;
+    out->nonzeros = nonzero;
+    out->coordinates = coords;
+    out->message_bits = 8.0 * (double)c->message_bytes * (double)num_messages;
+    return QODA_OK;
+  });
 }
 
 int qoda_extrapolate(qoda_ctx *c, const void *const *msgs_dev, const float *const *x_dev, float *const *out_dev,
                      const float *gamma_dev, void *stream) {
   if (!c) return QODA_EINVAL;
-  if (!gamma_dev) return fail(c, QODA_EINVAL, "qoda_extrapolate: null step size");
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  Dev a = base_args(c);
-  int rc = decode_common(c, msgs_dev, a, s, "qoda_extrapolate: msgs_dev");
-  if (rc) return rc;
-  rc = check_layer_ptrs(c, reinterpret_cast<const void *const *>(x_dev), c->L, "qoda_extrapolate: x_dev", true);
-  if (rc) return rc;
-  rc = check_layer_ptrs(c, reinterpret_cast<const void *const *>(out_dev), c->L, "qoda_extrapolate: out_dev", true);
-  if (rc) return rc;
-  rc = sync_table(c, c->t_x1, reinterpret_cast<const void *const *>(x_dev), c->L, s);
-  if (rc) return rc;
-  rc = sync_table(c, c->t_xh, reinterpret_cast<const void *const *>(out_dev), c->L, s);
-  if (rc) return rc;
-  a.x1 = reinterpret_cast<const float *const *>(c->t_x1.dev());
-  a.x_half = reinterpret_cast<float *const *>(c->t_xh.dev());
-  a.gamma_in = gamma_dev;
-  LAUNCH(c, kIdDecodeExtrapolate, s, launch_decode(a, kDecodeExtrapolate, c->planes_mask, s));
-  return QODA_OK;
+  return guarded(c, [&]() -> int {
+    if (const int rc_ = check_device(c)) return rc_;
+    if (!gamma_dev) return fail(c, QODA_EINVAL, "qoda_extrapolate: null step size");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Dev a = base_args(c);
+    int rc = decode_common(c, msgs_dev, a, s, "qoda_extrapolate: msgs_dev");
+    if (rc) return rc;
+    rc = check_layer_ptrs(c, reinterpret_cast<const void *const *>(x_dev), c->L, "qoda_extrapolate: x_dev", true);
+    if (rc) return rc;
+    rc = check_layer_ptrs(c, reinterpret_cast<const void *const *>(out_dev), c->L, "qoda_extrapolate: out_dev", true);
+    if (rc) return rc;
+    rc = sync_table(c, c->t_x1, reinterpret_cast<const void *const *>(x_dev), c->L, s);
+    if (rc) return rc;
+    rc = sync_table(c, c->t_xh, reinterpret_cast<const void *const *>(out_dev), c->L, s);
+    if (rc) return rc;
+    a.x1 = reinterpret_cast<const float *const *>(c->t_x1.dev());
+    a.x_half = reinterpret_cast<float *const *>(c->t_xh.dev());
+    a.gamma_in = gamma_dev;
+    LAUNCH(c, kIdDecodeExtrapolate, s, launch_decode(a, kDecodeExtrapolate, c->planes_mask, s));
+    return QODA_OK;
+  });
 }
 
 int qoda_step_alt(qoda_ctx *c, const void *const *msgs_dev, const qoda_alt_state *st, double q_hat, void *stream) {
   if (!c) return QODA_EINVAL;
-  if (!st || !st->sums_dev || !st->eta_dev) return fail(c, QODA_EINVAL, "qoda_step_alt: null state, sums or rates");
-  if (!(q_hat > 0.0) || !(q_hat <= 0.25)) return fail(c, QODA_EINVAL, "qoda_step_alt: the exponent must lie in (0, 1/4]");
-  const double digits = std::floor(std::ldexp(q_hat, 32));
-  if (digits < 1.0) return fail(c, QODA_EINVAL, "qoda_step_alt: the exponent is below 2^-32");
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  Dev a = base_args(c);
-  const int rc = step_common(c, msgs_dev, st->x1_dev, st->y_dev, st->x_half_dev, st->x_next_dev, a, s, "qoda_step_alt");
-  if (rc) return rc;
-  a.alt_sums = st->sums_dev;
-  a.eta_out = st->eta_dev;
-  a.q_digits = (unsigned int)digits;
-  LAUNCH(c, kIdAltScalars, s, launch_alt_scalars(a, s));
-  LAUNCH(c, kIdDecodeAlt, s, launch_decode(a, kDecodeUpdateAlt, c->planes_mask, s));
-  LAUNCH(c, kIdAltFinalize, s, launch_alt_finalize(a, s));
-  return QODA_OK;
+  return guarded(c, [&]() -> int {
+    if (const int rc_ = check_device(c)) return rc_;
+    if (!st || !st->sums_dev || !st->eta_dev) return fail(c, QODA_EINVAL, "qoda_step_alt: null state, sums or rates");
+    if (!(q_hat > 0.0) || !(q_hat <= 0.25)) return fail(c, QODA_EINVAL, "qoda_step_alt: the exponent must lie in (0, 1/4]");
+    const double digits = std::floor(std::ldexp(q_hat, 32));
+    if (digits < 1.0) return fail(c, QODA_EINVAL, "qoda_step_alt: the exponent is below 2^-32");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Dev a = base_args(c);
+    const int rc = step_common(c, msgs_dev, st->x1_dev, st->y_dev, st->x_half_dev, st->x_next_dev, a, s, "qoda_step_alt");
+    if (rc) return rc;
+    a.alt_sums = st->sums_dev;
+    a.eta_out = st->eta_dev;
+    a.q_digits = (unsigned int)digits;
+    LAUNCH(c, kIdAltScalars, s, launch_alt_scalars(a, s));
+    LAUNCH(c, kIdDecodeAlt, s, launch_decode(a, kDecodeUpdateAlt, c->planes_mask, s));
+    LAUNCH(c, kIdAltFinalize, s, launch_alt_finalize(a, s));
+    return QODA_OK;
+  });
 }
 
 int qoda_read_buffer(qoda_ctx *c, int32_t which, void *dst, size_t bytes, void *stream) {
   if (!c) return QODA_EINVAL;
-  if (!dst) return fail(c, QODA_EINVAL, "qoda_read_buffer: null destination");
-  const size_t KL = (size_t)c->K * c->L;
-  const void *src = nullptr;
-  size_t have = 0;
-  switch (which) {
-    case QODA_BUF_SUMSQ: src = c->d_sumsq; have = KL * sizeof(double); break;
-    case QODA_BUF_NORM: src = c->d_norm; have = KL * sizeof(float); break;
-    case QODA_BUF_INV: src = c->d_inv; have = KL * sizeof(float); break;
-    case QODA_BUF_DELTA: src = c->d_delta; have = c->K * sizeof(double); break;
-    case QODA_BUF_HIST: src = c->d_hist; have = c->d_hist ? KL * kHistBins * sizeof(unsigned int) : 0; break;
-    case QODA_BUF_POOLED: src = c->d_pooled; have = (size_t)c->M * kGridPoints * sizeof(unsigned long long); break;
-    default: return fail(c, QODA_EINVAL, "qoda_read_buffer: unknown buffer %d", which);
-  }
-  if (!src || bytes != have) return fail(c, QODA_EINVAL, "qoda_read_buffer: buffer %d holds %zu bytes, asked for %zu", which, have, bytes);
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  HIP_TRY(c, hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToHost, s));
-  HIP_TRY(c, hipStreamSynchronize(s));
-  return QODA_OK;
+  return guarded(c, [&]() -> int {
+    if (const int rc_ = check_device(c)) return rc_;
+    if (!dst) return fail(c, QODA_EINVAL, "qoda_read_buffer: null destination");
+    const size_t KL = (size_t)c->K * c->L;
+    const void *src = nullptr;
+    size_t have = 0;
+    switch (which) {
+      case QODA_BUF_SUMSQ: src = c->d_sumsq; have = KL * sizeof(double); break;
+      case QODA_BUF_NORM: src = c->d_norm; have = KL * sizeof(float); break;
+      case QODA_BUF_INV: src = c->d_inv; have = KL * sizeof(float); break;
+      case QODA_BUF_DELTA: src = c->d_delta; have = c->K * sizeof(double); break;
+      case QODA_BUF_HIST: src = c->d_hist; have = c->d_hist ? KL * kHistBins * sizeof(unsigned int) : 0; break;
+      case QODA_BUF_POOLED: src = c->d_pooled; have = (size_t)c->M * kGridPoints * sizeof(unsigned long long); break;
+      default: return fail(c, QODA_EINVAL, "qoda_read_buffer: unknown buffer %d", which);
+    }
+    if (!src || bytes != have) return fail(c, QODA_EINVAL, "qoda_read_buffer: buffer %d holds %zu bytes, asked for %zu", which, have, bytes);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    HIP_TRY(c, hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToHost, s));
+    HIP_TRY(c, hipStreamSynchronize(s));
+    return QODA_OK;
+  });
 }
 
 int qoda_status(qoda_ctx *c, void *stream) {
   if (!c) return QODA_EINVAL;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  unsigned int flag = 0;
-  HIP_TRY(c, hipMemcpyAsync(&flag, c->d_status, sizeof flag, hipMemcpyDeviceToHost, s));
-  HIP_TRY(c, hipStreamSynchronize(s));
-  if (flag) {
-    HIP_TRY(c, launch_zero_u32(c->d_status, 1, s));
-    return fail(c, QODA_ENONFINITE, "a layer's sum of squares was not a finite number");
-  }
-  return QODA_OK;
+  return guarded(c, [&]() -> int {
+    if (const int rc_ = check_device(c)) return rc_;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    unsigned int flag = 0;
+    HIP_TRY(c, hipMemcpyAsync(&flag, c->d_status, sizeof flag, hipMemcpyDeviceToHost, s));
+    HIP_TRY(c, hipStreamSynchronize(s));
+    if (flag) {
+      HIP_TRY(c, launch_zero_u32(c->d_status, 1, s));
+      return fail(c, QODA_ENONFINITE, "a layer's sum of squares was not a finite number");
+    }
+    return QODA_OK;
+  });
 }
 
 int qoda_profile_enable(qoda_ctx *c, uint32_t class_mask) {
@@ -815,25 +885,28 @@ int qoda_profile_enable(qoda_ctx *c, uint32_t class_mask) {
 
 int qoda_profile_read(qoda_ctx *c, double *ms, int64_t *launches, void *stream) {
   if (!c) return QODA_EINVAL;
-  if (!ms || !launches) return fail(c, QODA_EINVAL, "qoda_profile_read: null output");
-  HIP_TRY(c, hipStreamSynchronize(static_cast<hipStream_t>(stream)));
-  for (auto &r : c->prof_recs) {
-    float t = 0.0f;
-    HIP_TRY(c, hipEventSynchronize(r.b));
-    HIP_TRY(c, hipEventElapsedTime(&t, r.a, r.b));
-    c->prof_ms[r.id] += (double)t;
-    c->prof_n[r.id] += 1;
-    c->prof_pool.push_back(r.a);
-    c->prof_pool.push_back(r.b);
-  }
-  c->prof_recs.clear();
-  for (int i = 0; i < kNumKernelIds; ++i) {
-    ms[i] = c->prof_ms[i];
-    launches[i] = c->prof_n[i];
-    c->prof_ms[i] = 0.0;
-    c->prof_n[i] = 0;
-  }
-  return QODA_OK;
+  return guarded(c, [&]() -> int {
+    if (const int rc_ = check_device(c)) return rc_;
+    if (!ms || !launches) return fail(c, QODA_EINVAL, "qoda_profile_read: null output");
+    HIP_TRY(c, hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+    for (auto &r : c->prof_recs) {
+      float t = 0.0f;
+      HIP_TRY(c, hipEventSynchronize(r.b));
+      HIP_TRY(c, hipEventElapsedTime(&t, r.a, r.b));
+      c->prof_ms[r.id] += (double)t;
+      c->prof_n[r.id] += 1;
+      c->prof_pool.push_back(r.a);
+      c->prof_pool.push_back(r.b);
+    }
+    c->prof_recs.clear();
+    for (int i = 0; i < kNumKernelIds; ++i) {
+      ms[i] = c->prof_ms[i];
+      launches[i] = c->prof_n[i];
+      c->prof_ms[i] = 0.0;
+      c->prof_n[i] = 0;
+    }
+    return QODA_OK;
+  });
 }
 
 const char *qoda_kernel_name(int32_t id) {
@@ -848,12 +921,15 @@ const char *qoda_kernel_name(int32_t id) {
 
 int qoda_copy_calibration(qoda_ctx *c, const void *src_dev, void *dst_dev, size_t bytes, void *stream) {
   if (!c) return QODA_EINVAL;
-  if (!src_dev || !dst_dev || bytes % 16 != 0 || reinterpret_cast<uintptr_t>(src_dev) % 16 != 0 ||
-      reinterpret_cast<uintptr_t>(dst_dev) % 16 != 0)
-    return fail(c, QODA_EINVAL, "qoda_copy_calibration: pointers and size must be multiples of 16 bytes");
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  LAUNCH(c, kIdCopy, s, launch_copy(src_dev, dst_dev, bytes, s));
-  return QODA_OK;
+  return guarded(c, [&]() -> int {
+    if (const int rc_ = check_device(c)) return rc_;
+    if (!src_dev || !dst_dev || bytes % 16 != 0 || reinterpret_cast<uintptr_t>(src_dev) % 16 != 0 ||
+        reinterpret_cast<uintptr_t>(dst_dev) % 16 != 0)
+      return fail(c, QODA_EINVAL, "qoda_copy_calibration: pointers and size must be multiples of 16 bytes");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    LAUNCH(c, kIdCopy, s, launch_copy(src_dev, dst_dev, bytes, s));
+    return QODA_OK;
+  });
 }
 
 const char *qoda_last_error(const qoda_ctx *c) { return c ? c->err.c_str() : "null context"; }
