@@ -349,3 +349,157 @@ def test_full_size_bucket_scope(oracle):
             _, wxh = oracle.oda_update(mean, xx, yv, e2, e2, want_next=False)
             assert np.array_equal(y[int(off[l]) + e0: int(off[l]) + e1].cpu().numpy(), yv), (t, l, e0)
             assert np.array_equal(xh[int(off[l]) + e0: int(off[l]) + e1].cpu().numpy(), wxh), (t, l, e0)
+
+
+@pytest.mark.timeout(900)
+def test_layer_beyond_32_bit_indices(oracle):
+    """One tensor of 2^32 + 10317 entries (coordinate indices beyond both int32 and uint32; the second tensor's
+    body sits beyond 2^31 bytes inside the message), one node, fit -> quantize -> step: the sum of squares, the
+    histogram and the fitted levels of the big tensor against the oracle in full, codes and iterates on slices
+    around 0, 2^31, 2^32 and the ragged tail, the small tensor in full."""
+    if not torch.cuda.is_available():
+        pytest.fail("a GPU test was selected but no GPU is visible")
+    dev = torch.device("cuda:0")
+    sizes = [(1 << 32) + 5 * OCT + 77, 5000]
+    L, K, S, seed = 2, 1, 16, 77
+    ctx = qoda.Context(sizes, [0, 1], [S, S], K, seed)
+    off, n = workloads.padded_offsets(sizes)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(99)
+    grad = torch.empty(n, dtype=torch.float32, device=dev)
+    grad.normal_(generator=gen)
+    grad.mul_(3e-3)
+    x1 = torch.empty(n, dtype=torch.float32, device=dev)
+    x1.normal_(generator=gen)
+    y = torch.zeros_like(x1)
+    xh = torch.zeros_like(x1)
+    acc = torch.zeros(1, dtype=torch.float64, device=dev)
+    eta = torch.ones(2, dtype=torch.float32, device=dev)
+    mb = ctx.message_bytes()
+    hdr_off, body_off = ctx.message_layout()
+    assert int(body_off[1]) > (1 << 31)
+    msg = torch.zeros(mb, dtype=torch.uint8, device=dev)
+    ptrs = lambda t: [t.data_ptr() + 4 * int(o) for o in off]
+    ctx.fit_levels(ptrs(grad), 1)
+    ctx.quantize_all(ptrs(grad), 1, [msg], None)
+    deltas = ctx.read_buffer(qoda.BUF_DELTA)
+    ctx.step([msg], ptrs(x1), ptrs(y), ptrs(xh), acc, None, eta)
+    torch.cuda.synchronize()
+    assert ctx.status() == qoda.OK
+    ss = ctx.read_buffer(qoda.BUF_SUMSQ)
+    nr = ctx.read_buffer(qoda.BUF_NORM)
+    iv = ctx.read_buffer(qoda.BUF_INV)
+    hist = ctx.read_buffer(qoda.BUF_HIST)
+    acc2, eta2 = oracle.step_size(deltas, 0.0)
+    assert float(acc.cpu()[0]) == acc2 and float(eta.cpu()[0]) == float(eta2)
+    c1 = 5
+    d0 = sizes[0]
+    tail = (d0 - 1) // OCT * OCT - 2 * OCT
+    pieces = {0: [(0, 3 * OCT), ((1 << 31) - 2 * OCT, (1 << 31) + 2 * OCT), ((1 << 32) - 2 * OCT, (1 << 32) + 2 * OCT), (tail, d0)],
+              1: [(0, sizes[1])]}
+    for l in (0, 1):
+        host = grad[int(off[l]): int(off[l]) + sizes[l]].cpu().numpy()
+        s = oracle.sumsq(host)
+        assert ss[0, l] == s, l
+        assert nr[0, l] == oracle.sqrt_floor(s) and iv[0, l] == oracle.rcp_floor(nr[0, l])
+        levs, oh, _, st = oracle.fit_levels([sizes[l]], [0], [S], 1, [host], [uniform_levels(S)])
+        assert st == 0
+        assert np.array_equal(hist[0, l], oh[0, 0]), l
+        lev = ctx.get_levels(l)
+        assert np.array_equal(lev, levs[0]), l
+        for (e0, e1) in pieces[l]:
+            b0 = int(body_off[l]) + e0 // OCT * 256 * c1
+            body = msg[b0: b0 + (e1 - e0 + OCT - 1) // OCT * 256 * c1].cpu().numpy()
+            sign, idx = oracle.quantize_range(host, e0, e1, iv[0, l], lev, seed, 1, 0, l)
+            gs, gi = oracle.unpack_layer(body, e1 - e0, S)
+            assert np.array_equal(gs, sign) and np.array_equal(gi, idx), (l, e0)
+            hdr = msg[int(hdr_off[l]): int(hdr_off[l]) + 4 * (1 + S)].cpu().numpy()
+            hb = oracle.header_bytes([e1 - e0], [S])
+            m = np.zeros(oracle.message_bytes([e1 - e0], [S]), np.uint8)
+            m[: hdr.size] = hdr
+            m[hb: hb + body.size] = body
+            mean = oracle.dequant_aggregate([e1 - e0], [S], [m])[0]
+            yv = np.zeros(e1 - e0, np.float32)
+            xx = x1[int(off[l]) + e0: int(off[l]) + e1].cpu().numpy()
+            _, wxh = oracle.oda_update(mean, xx, yv, eta2, eta2, want_next=False)
+            assert np.array_equal(y[int(off[l]) + e0: int(off[l]) + e1].cpu().numpy(), yv), (l, e0)
+            assert np.array_equal(xh[int(off[l]) + e0: int(off[l]) + e1].cpu().numpy(), wxh), (l, e0)
+        del host
+    # the step-size term of the whole message (first round: the previous vectors are zero) against a float64 sum of the
+    # decoded values, a property that holds at any size: Y = -mean = -Vhat after one round from Y = 0.  The term is
+    # accumulated in fp32 inside each lane's 64 coordinates of a tile (rounding 2^-24 per operation), in fp64 above.
+    got = float(torch.sum(y.double() ** 2))
+    assert deltas[0] == pytest.approx(got, rel=2e-6)
+
+
+@pytest.mark.timeout(900)
+def test_layer_beyond_32_bit_indices_bucket_scope(oracle):
+    """The same oversized tensor under bucket scope (octets of 256*(1+b)+64 bytes: byte offsets beyond 2^32 inside
+    the message): fitted levels against the oracle in full; bucket norms, codes and iterates on the slices."""
+    if not torch.cuda.is_available():
+        pytest.fail("a GPU test was selected but no GPU is visible")
+    dev = torch.device("cuda:0")
+    sizes = [(1 << 32) + 5 * OCT + 77, 5000]
+    K, S, seed = 1, 16, 78
+    B = qoda.SCOPE_BUCKET
+    ctx = qoda.Context(sizes, [0, 1], [S, S], K, seed, norm_scope=B)
+    off, n = workloads.padded_offsets(sizes)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(100)
+    grad = torch.empty(n, dtype=torch.float32, device=dev)
+    grad.normal_(generator=gen)
+    grad.mul_(3e-3)
+    x1 = torch.empty(n, dtype=torch.float32, device=dev)
+    x1.normal_(generator=gen)
+    y = torch.zeros_like(x1)
+    xh = torch.zeros_like(x1)
+    acc = torch.zeros(1, dtype=torch.float64, device=dev)
+    eta = torch.ones(2, dtype=torch.float32, device=dev)
+    mb = ctx.message_bytes()
+    hdr_off, body_off = ctx.message_layout()
+    assert int(body_off[1]) > (1 << 31)
+    msg = torch.zeros(mb, dtype=torch.uint8, device=dev)
+    ptrs = lambda t: [t.data_ptr() + 4 * int(o) for o in off]
+    ctx.fit_levels(ptrs(grad), 1)
+    ctx.quantize_all(ptrs(grad), 1, [msg], None)
+    deltas = ctx.read_buffer(qoda.BUF_DELTA)
+    ctx.step([msg], ptrs(x1), ptrs(y), ptrs(xh), acc, None, eta)
+    torch.cuda.synchronize()
+    assert ctx.status() == qoda.OK
+    acc2, eta2 = oracle.step_size(deltas, 0.0)
+    assert float(acc.cpu()[0]) == acc2 and float(eta.cpu()[0]) == float(eta2)
+    ob = 256 * 5 + 64
+    d0 = sizes[0]
+    tail = (d0 - 1) // OCT * OCT - 2 * OCT
+    pieces = {0: [(0, 3 * OCT), ((1 << 31) - 2 * OCT, (1 << 31) + 2 * OCT), ((1 << 32) - 2 * OCT, (1 << 32) + 2 * OCT), (tail, d0)],
+              1: [(0, sizes[1])]}
+    for l in (0, 1):
+        host = grad[int(off[l]): int(off[l]) + sizes[l]].cpu().numpy()
+        levs, _, _, st = oracle.fit_levels([sizes[l]], [0], [S], 1, [host], [uniform_levels(S)], scope=B)
+        assert st == 0
+        lev = ctx.get_levels(l)
+        assert np.array_equal(lev, levs[0]), l
+        for (e0, e1) in pieces[l]:
+            b0 = int(body_off[l]) + e0 // OCT * ob
+            body = msg[b0: b0 + (e1 - e0 + OCT - 1) // OCT * ob].cpu().numpy()
+            gs, gi, gn = oracle.unpack_layer(body, e1 - e0, S, B)
+            for b in range(e0, e1, 128):
+                b1 = min(b + 128, e1)
+                nrm = oracle.sqrt_floor(oracle.bucket_sumsq(host[b: b1]))
+                assert gn[(b - e0) // 128] == nrm, (l, b)
+                sign, idx = oracle.quantize_range(host, b, b1, oracle.rcp_floor(nrm), lev, seed, 1, 0, l)
+                assert np.array_equal(gi[b - e0: b1 - e0], idx) and np.array_equal(gs[b - e0: b1 - e0], sign), (l, b)
+            hdr = msg[int(hdr_off[l]): int(hdr_off[l]) + 4 * (1 + S)].cpu().numpy()
+            hb = oracle.header_bytes([e1 - e0], [S], B)
+            m = np.zeros(oracle.message_bytes([e1 - e0], [S], B), np.uint8)
+            m[: hdr.size] = hdr
+            m[hb: hb + body.size] = body
+            mean = oracle.dequant_aggregate([e1 - e0], [S], [m], scope=B)[0]
+            yv = np.zeros(e1 - e0, np.float32)
+            xx = x1[int(off[l]) + e0: int(off[l]) + e1].cpu().numpy()
+            _, wxh = oracle.oda_update(mean, xx, yv, eta2, eta2, want_next=False)
+            assert np.array_equal(y[int(off[l]) + e0: int(off[l]) + e1].cpu().numpy(), yv), (l, e0)
+            assert np.array_equal(xh[int(off[l]) + e0: int(off[l]) + e1].cpu().numpy(), wxh), (l, e0)
+        del host
+    got = float(torch.sum(y.double() ** 2))
+    assert deltas[0] == pytest.approx(got, rel=2e-6)
