@@ -322,3 +322,51 @@ def test_nonfinite_flag_and_argument_errors():
         qoda.Context([10], [0], [1], 1, 0)                   # S < 2
     with pytest.raises(qoda.QodaError):
         qoda.Context([10], [1], [4], 1, 0)                   # type out of range
+
+
+@pytest.mark.parametrize("K,S", [(4096, 2), (2048, 4), (32, 256)])
+@pytest.mark.parametrize("scope", [qoda.SCOPE_LAYER, qoda.SCOPE_BUCKET])
+def test_largest_node_counts(oracle, K, S, scope):
+    """K at the documented limit K * 2^(1+b) = 16384 (the decode tables of all nodes fill the shared memory the
+    decode kernels reserve): two rounds, messages, step-size terms and iterates against the oracle."""
+    sizes = [2500, 300, 0, 2048]
+    L = len(sizes)
+    rng = np.random.default_rng(K + S)
+    x1 = [rng.standard_normal(s).astype(np.float32) for s in sizes]
+    m = gm(sizes, [0] * L, [S], K, seed=21, norm_scope=scope)
+    m.set_layers(m.x1, x1)
+    lev = helpers.uniform_levels(S)
+    acc, y = 0.0, [np.zeros(s, np.float32) for s in sizes]
+    prev = [None] * K
+    for t in (1, 2):
+        base = [(rng.standard_t(4, s) * 0.1).astype(np.float32) for s in sizes]
+        grads = [[(b * np.float32(1.0 + 0.001 * k)).astype(np.float32) for b in base] for k in range(K)]
+        m.set_grads(grads)
+        m.quantize_all(t)
+        msgs = m.messages()
+        deltas = m.ctx.read_buffer(qoda.BUF_DELTA)
+        m.step()
+        want_msgs, want_deltas = [], []
+        for k in range(K):
+            out = oracle.quantize(sizes, [S] * L, [lev] * L, grads[k], 21, t, k, msg_prev=prev[k], scope=scope)
+            assert out[3] == 0
+            want_msgs.append(out[0])
+            want_deltas.append(out[2])
+            assert np.array_equal(msgs[k], out[0]), (t, k)
+            assert deltas[k] == out[2], (t, k)
+        prev = want_msgs
+        mean = oracle.dequant_aggregate(sizes, [S] * L, want_msgs, scope=scope)
+        acc, eta = oracle.step_size(want_deltas, acc)
+        assert float(m.acc.cpu()[0]) == acc and float(m.eta.cpu()[0]) == float(eta)
+        gy, gxh, gxn = m.layers(m.y), m.layers(m.x_half), m.layers(m.x_next)
+        for l in range(L):
+            xn, xh = oracle.oda_update(mean[l], x1[l], y[l], eta, eta)
+            assert np.array_equal(gy[l], y[l]) and np.array_equal(gxh[l], xh) and np.array_equal(gxn[l], xn), (t, l)
+    assert m.ctx.status() == qoda.OK
+
+
+def test_node_counts_beyond_the_limit_are_rejected():
+    _need_gpu()
+    for K, S in [(4097, 2), (2049, 4), (33, 256), (65536, 2)]:
+        with pytest.raises(qoda.QodaError):
+            qoda.Context([1000], [0], [S], K, 0)
