@@ -370,3 +370,43 @@ def test_node_counts_beyond_the_limit_are_rejected():
     for K, S in [(4097, 2), (2049, 4), (33, 256), (65536, 2)]:
         with pytest.raises(qoda.QodaError):
             qoda.Context([1000], [0], [S], K, 0)
+
+
+@pytest.mark.parametrize("scope", [qoda.SCOPE_LAYER, qoda.SCOPE_BUCKET])
+def test_extreme_magnitudes(oracle, scope):
+    """Layers of subnormal entries (norm itself subnormal, reciprocal beyond fp32 range), of entries next to the
+    largest finite fp32, a single coordinate, and a lone huge entry among tiny ones: norms, packed bytes and the
+    decoded mean bit for bit."""
+    # bucket sums are accumulated in fp32 (squares beyond its range are "not finite" by that scope's definition)
+    big, lone = (1e36, -3e38) if scope == qoda.SCOPE_LAYER else (1e17, -1e19)
+    scales = [1e-44, 3e-42, 1e-39, 1e-38, 1e-20, 1e18 if scope == qoda.SCOPE_LAYER else 1e10, big, 1.0, 1.0]
+    sizes = [5000] * 7 + [1, 3000]
+    L, K, S = len(sizes), 2, 8
+    rng = np.random.default_rng(11)
+    grads = []
+    for k in range(K):
+        g = [(rng.standard_normal(s) * sc).astype(np.float32) for s, sc in zip(sizes, scales)]
+        g[8][:] = np.float32(1e-30)
+        g[8][1234] = np.float32(lone)
+        grads.append(g)
+    lev = irregular_levels(S, 5)
+    m = gm(sizes, [0] * L, [S], K, seed=13, norm_scope=scope)
+    m.ctx.set_levels(0, lev)
+    m.set_grads(grads)
+    m.quantize_all(1)
+    msgs = m.messages()
+    deltas = m.ctx.read_buffer(qoda.BUF_DELTA)
+    m.aggregate()
+    m.sync()
+    assert m.ctx.status() == qoda.OK
+    want = []
+    for k in range(K):
+        out = oracle.quantize(sizes, [S] * L, [lev] * L, grads[k], 13, 1, k, scope=scope)
+        assert out[3] == 0
+        assert np.array_equal(msgs[k], out[0]), k
+        assert deltas[k] == out[2], k
+        want.append(out[0])
+    mean = oracle.dequant_aggregate(sizes, [S] * L, want, scope=scope)
+    got = m.layers(m.mean)
+    for l in range(L):
+        assert np.array_equal(got[l], mean[l]), l
