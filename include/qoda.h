@@ -62,7 +62,10 @@ extern "C" {
  *   BUCKET  one norm per 128 consecutive coordinates of a layer, computed in the same pass that quantizes (the
  *           gradient is read once).  The 256*(1+b) code bytes of every octet are followed by the octet's 16 bucket
  *           norms (fp32; the bucket of block bb = 0..7, half hf = 0..1 of the octet at position 8*hf + bb), so an
- *           octet takes 256*(1+b) + 64 bytes; the header's norm entry is 0 and unused. */
+ *           octet takes 256*(1+b) + 64 bytes; the header's norm entry is 0 and unused.  A bucket's sum of squares is
+ *           accumulated in single precision: entries below about 1e-19 in magnitude add nothing to it (a bucket made
+ *           of such entries only has norm 0 and decodes to zeros), and a bucket with an entry above about 1.8e19 is
+ *           "not finite" (flagged as in the conventions above). */
 #define QODA_SCOPE_LAYER 0
 #define QODA_SCOPE_VECTOR 1
 #define QODA_SCOPE_BUCKET 2
