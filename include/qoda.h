@@ -63,7 +63,7 @@ extern "C" {
  *           gradient is read once).  The 256*(1+b) code bytes of every octet are followed by the octet's 16 bucket
  *           norms (fp32; the bucket of block bb = 0..7, half hf = 0..1 of the octet at position 8*hf + bb), so an
  *           octet takes 256*(1+b) + 64 bytes; the header's norm entry is 0 and unused.  A bucket's sum of squares is
- *           accumulated in single precision: entries below about 1e-19 in magnitude add nothing to it (a bucket made
+ *           accumulated in single precision: entries below about 4e-23 in magnitude add nothing to it (a bucket made
  *           of such entries only has norm 0 and decodes to zeros), and a bucket with an entry above about 1.8e19 is
  *           "not finite" (flagged as in the conventions above). */
 #define QODA_SCOPE_LAYER 0
