@@ -22,6 +22,7 @@ CHUNK = 16384
 BUCKET = 128
 TYPE_SKIP = 0x7FFFFFFF   # "no weight scale for this type"
 SCOPE_LAYER, SCOPE_VECTOR, SCOPE_BUCKET = 0, 1, 2   # what one norm covers: a layer, the whole vector, 128 coordinates
+NORM_LINF, NORM_L1, NORM_L2 = 0, 1, 2                # the q of the L^q normalisation (0 stands for q -> infinity)
 
 _lib = None
 
@@ -76,7 +77,7 @@ def lib():
         L.oracle_bucket_sumsq.restype = C.c_double
         L.oracle_unpack_layer.restype = None
         L.oracle_quantize.argtypes = [C.c_int32, i64p, i32p, pp, pp, C.c_uint64, C.c_uint32, C.c_uint32, C.c_int32, u8p, u8p,
-                                      dp, dp, i32p, u64p, dp]
+                                      dp, dp, i32p, u64p, dp, C.c_int32]
         L.oracle_quantize.restype = C.c_int32
         L.oracle_delta_from_messages.argtypes = [C.c_int32, i64p, i32p, C.c_int32, u8p, u8p]
         L.oracle_delta_from_messages.restype = C.c_double
@@ -106,10 +107,19 @@ def lib():
         L.oracle_fit_objective.restype = C.c_double
         L.oracle_fit_dp.argtypes = [u64p, C.c_int32, fp]
         L.oracle_fit_dp.restype = None
-        L.oracle_fit_levels.argtypes = [C.c_int32, i64p, i32p, C.c_int32, i32p, C.c_int32, C.c_int32, pp, pp, u32p, u64p]
+        L.oracle_fit_levels.argtypes = [C.c_int32, i64p, i32p, C.c_int32, i32p, C.c_int32, C.c_int32, pp, pp, u32p, u64p,
+                                        C.c_int32]
         L.oracle_fit_levels.restype = C.c_int32
-        L.oracle_fit_from_stats.argtypes = [C.c_int32, i32p, C.c_int32, i32p, C.c_int32, u64p, dp, i32p, pp, u64p]
+        L.oracle_fit_from_stats.argtypes = [C.c_int32, i32p, C.c_int32, i32p, C.c_int32, u64p, dp, i32p, pp, u64p, C.c_int32]
         L.oracle_fit_from_stats.restype = C.c_int32
+        L.oracle_norm_stat.argtypes = [fp, C.c_int64, C.c_int32]
+        L.oracle_norm_stat.restype = C.c_double
+        L.oracle_bucket_stat.argtypes = [fp, C.c_int64, C.c_int32]
+        L.oracle_bucket_stat.restype = C.c_double
+        L.oracle_norm_of.argtypes = [C.c_double, C.c_int32]
+        L.oracle_norm_of.restype = C.c_float
+        L.oracle_weight_of.argtypes = [C.c_double, C.c_int32]
+        L.oracle_weight_of.restype = C.c_double
         _lib = L
     return _lib
 
@@ -162,6 +172,27 @@ def index_bits(S: int) -> int:
 def sumsq(v) -> float:
     v = _f32(v)
     return float(lib().oracle_sumsq(_p(v, C.c_float), v.size))
+
+
+def norm_stat(v, norm_kind: int = NORM_L2) -> float:
+    """The reduced statistic of one layer: sum of squares, sum of magnitudes or largest magnitude."""
+    v = _f32(v)
+    return float(lib().oracle_norm_stat(_p(v, C.c_float), v.size, norm_kind))
+
+
+def bucket_stat(v, norm_kind: int = NORM_L2) -> float:
+    v = _f32(v)
+    assert v.size <= BUCKET
+    return float(lib().oracle_bucket_stat(_p(v, C.c_float), v.size, norm_kind))
+
+
+def norm_of(s: float, norm_kind: int = NORM_L2) -> np.float32:
+    """The fp32 norm a statistic yields (0 if the statistic is out of range)."""
+    return np.float32(lib().oracle_norm_of(float(s), norm_kind))
+
+
+def weight_of(s: float, norm_kind: int = NORM_L2) -> float:
+    return float(lib().oracle_weight_of(float(s), norm_kind))
 
 
 def norm_and_inv(v):
@@ -262,7 +293,8 @@ def bucket_sumsq(v) -> float:
 
 # ------------------------------------------------------------------ whole messages
 def quantize(sizes, points, levels: Sequence[np.ndarray], grads: Sequence[np.ndarray], seed: int, round_: int,
-             node: int, msg_prev: Optional[np.ndarray] = None, scope: int = SCOPE_LAYER, stats_exp=None):
+             node: int, msg_prev: Optional[np.ndarray] = None, scope: int = SCOPE_LAYER, stats_exp=None,
+             norm_kind: int = NORM_L2):
     """ENCODE(Q(V_k)) for one node.  Returns (msg bytes, sumsq per layer, delta, status); with ``stats_exp`` (the
     weight scale of every layer's type, bucket scope) also the gathered (grid histograms [L, 257], largest sampled
     bucket sums [L])."""
@@ -288,7 +320,7 @@ def quantize(sizes, points, levels: Sequence[np.ndarray], grads: Sequence[np.nda
                                _p(ss, C.c_double), _p(delta, C.c_double),
                                None if stats_exp is None else _p(sexp, C.c_int32),
                                None if stats_exp is None else _p(shist, C.c_uint64),
-                               None if stats_exp is None else _p(smax, C.c_double))
+                               None if stats_exp is None else _p(smax, C.c_double), norm_kind)
     if stats_exp is None:
         return msg, ss, float(delta[0]), int(st)
     return msg, ss, float(delta[0]), int(st), shist, smax
@@ -423,7 +455,7 @@ def fit_dp(W, S: int) -> np.ndarray:
 
 
 def fit_levels(sizes, layer_type, type_points, K: int, grads: Sequence[np.ndarray], levels: Sequence[np.ndarray],
-               scope: int = SCOPE_LAYER):
+               scope: int = SCOPE_LAYER, norm_kind: int = NORM_L2):
     """grads: K*L arrays (entry k*L+l).  levels: M arrays, updated copies returned with (hist, pooled, status)."""
     d = np.ascontiguousarray(sizes, dtype=np.int64)
     lt = np.ascontiguousarray(layer_type, dtype=np.int32)
@@ -435,11 +467,12 @@ def fit_levels(sizes, layer_type, type_points, K: int, grads: Sequence[np.ndarra
     hist = np.zeros(K * L * HIST_BINS, dtype=np.uint32)
     pooled = np.zeros(M * GRID_POINTS, dtype=np.uint64)
     st = lib().oracle_fit_levels(L, _p(d, C.c_int64), _p(lt, C.c_int32), M, _p(tp, C.c_int32), K, scope,
-                                 _ptr_array(g), _ptr_array(lev), _p(hist, C.c_uint32), _p(pooled, C.c_uint64))
+                                 _ptr_array(g), _ptr_array(lev), _p(hist, C.c_uint32), _p(pooled, C.c_uint64), norm_kind)
     return lev, hist.reshape(K, L, HIST_BINS), pooled.reshape(M, GRID_POINTS), int(st)
 
 
-def fit_from_stats(layer_type, type_points, K: int, hist, bmax, exps, levels: Sequence[np.ndarray]):
+def fit_from_stats(layer_type, type_points, K: int, hist, bmax, exps, levels: Sequence[np.ndarray],
+                   norm_kind: int = NORM_L2):
     """hist: [K, L, 257] uint64, bmax: [K, L] float64, exps: [M] int32 (the scales the histograms were gathered with).
     Returns (levels, pooled [M, 257], new exps [M], status)."""
     lt = np.ascontiguousarray(layer_type, dtype=np.int32)
@@ -452,7 +485,7 @@ def fit_from_stats(layer_type, type_points, K: int, hist, bmax, exps, levels: Se
     lev = [_f32(a).copy() for a in levels]
     pooled = np.zeros(M * GRID_POINTS, dtype=np.uint64)
     st = lib().oracle_fit_from_stats(L, _p(lt, C.c_int32), M, _p(tp, C.c_int32), K, _p(h, C.c_uint64), _p(b, C.c_double),
-                                     _p(ex, C.c_int32), _ptr_array(lev), _p(pooled, C.c_uint64))
+                                     _p(ex, C.c_int32), _ptr_array(lev), _p(pooled, C.c_uint64), norm_kind)
     return lev, pooled.reshape(M, GRID_POINTS), ex, int(st)
 
 

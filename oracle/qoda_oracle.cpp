@@ -21,6 +21,8 @@
 //   * norm scopes (whole vector, buckets of 128), the extra-gradient leg,
 //     index counts and code lengths (fixed width, entropy, Huffman)            -- Sec. 2.2, Sec. 7, Sec. 4,
 //                                                                                 Thm 5.3 / App. C
+//   * L^q normalisation for q = 1 and q -> infinity beside q = 2 (statistic,
+//     norm, fit weight ||v||_q^2)                                              -- Sec. 2.2, Thm 5.1, eq. (Qada2)
 //
 // Pin status (see tests/test_oracle_*.py): every function below is pinned to something the paper or the
 // mathematics fixes; the Philox generator also against the published known-answer vectors of its authors.
@@ -135,6 +137,55 @@ void chunk_sumsq(const float *v, int64_t d, std::vector<double> &out) {
   }
 }
 
+// ----- L^q normalisation (Sec. 2.2: u_i = |v_i| / ||v||_q).  Three kinds are defined here, named by q:
+// kNormL2 (q = 2), kNormL1 (q = 1) and kNormLinf (the limit q -> infinity, stored as 0).  Each has a statistic s that
+// is reduced over the vector (sum of squares, sum of magnitudes, largest magnitude), the norm derived from it, and
+// the weight ||v||_q^2 that eq. (Qada2) gives the vector in the level fit.
+constexpr int kNormLinf = 0, kNormL1 = 1, kNormL2 = 2;
+
+// largest magnitude of v as a double; +infinity if an entry is an infinity or not a number (the integer order of the
+// magnitude bits puts those above every finite value)
+double max_magnitude(const float *v, int64_t d) {
+  uint32_t mb = 0;
+  for (int64_t e = 0; e < d; ++e) mb = std::max(mb, f2u(v[e]) & 0x7FFFFFFFu);
+  return mb > 0x7F7FFFFFu ? std::numeric_limits<double>::infinity() : (double)u2f(mb);
+}
+
+// per-chunk sums of magnitudes of one layer, in the slot order of the sums of squares
+void chunk_sumabs(const float *v, int64_t d, std::vector<double> &out) {
+  const int64_t nchunks = (d + kChunk - 1) / kChunk;
+  for (int64_t c = 0; c < nchunks; ++c) {
+    double p[kSlots];
+    for (int j = 0; j < kSlots; ++j) p[j] = 0.0;
+    const int64_t e1 = std::min(d, (c + 1) * kChunk);
+    for (int64_t e = c * kChunk; e < e1; ++e) p[slot_of(e)] = p[slot_of(e)] + (double)std::fabs(v[e]);
+    out.push_back(halving_tree(p));
+  }
+}
+
+// the statistic of one layer
+double layer_stat(const float *v, int64_t d, int kind) {
+  if (kind == kNormLinf) return max_magnitude(v, d);
+  std::vector<double> cs;
+  if (kind == kNormL1) chunk_sumabs(v, d, cs);
+  else chunk_sumsq(v, d, cs);
+  return combine_chunks(cs);
+}
+
+// statistics of parts -> statistic of the whole (vector scope combines its layers with this)
+double combine_stats(const std::vector<double> &parts, int kind) {
+  if (kind != kNormLinf) return combine_chunks(parts);
+  double m = 0.0;
+  for (double x : parts) m = (x > m || x != x) ? x : m;
+  return m;
+}
+
+// a statistic whose norm is a finite float
+bool stat_finite(double s, int kind) {
+  const double fmax = (double)std::numeric_limits<float>::max();
+  return (s >= 0.0) && (s <= (kind == kNormL2 ? fmax * fmax : fmax));
+}
+
 // largest float n >= 0 with n*n <= s (n*n is exact in fp64).  s must be finite and >= 0.
 float sqrt_floor(double s) {
   if (!(s >= 0.0) || !(s <= (double)std::numeric_limits<float>::max() * (double)std::numeric_limits<float>::max()))
@@ -163,6 +214,13 @@ float rcp_floor(float x) {
   }
   return r;
 }
+
+// norm of a vector from its (finite) statistic: the floor root of a sum of squares; a sum of magnitudes rounded to
+// the nearest float (one IEEE conversion); a largest magnitude is a float already
+float norm_of(double s, int kind) { return kind == kNormL2 ? sqrt_floor(s) : (float)s; }
+
+// ||v||_q^2 as a double: the sum of squares itself, else the statistic squared (one rounding)
+double weight_of(double s, int kind) { return kind == kNormL2 ? s : s * s; }
 
 // tau(u) = largest j in [0, S-2] with level[j] <= u   (Sec. 3.1; at u = 1 the last interval is taken)
 int level_index(const float *lev, int S, float u) {
@@ -302,6 +360,25 @@ double bucket_sumsq(const float *v, int64_t n) {
   return p[0];
 }
 
+// The other kinds over a bucket, lane by lane as above: a lane adds its four magnitudes in order in fp32 from 0 (the
+// lane sums are widened and combined by the same in-order tree), or takes their maximum.
+double bucket_stat(const float *v, int64_t n, int kind) {
+  if (kind == kNormL2) return bucket_sumsq(v, n);
+  if (kind == kNormLinf) return max_magnitude(v, n);
+  double p[32];
+  for (int i = 0; i < 32; ++i) {
+    float acc = 0.0f;
+    for (int j = 0; j < 4; ++j) {
+      const int64_t e = 4 * i + j;
+      acc = acc + ((e < n) ? std::fabs(v[e]) : 0.0f);
+    }
+    p[i] = (double)acc;
+  }
+  for (int w = 1; w < 32; w *= 2)
+    for (int i = 0; i < 32; i += 2 * w) p[i] = p[i] + p[i + w];
+  return p[0];
+}
+
 struct HeaderView { float norm; const float *lev; };
 inline HeaderView header_of(const uint8_t *msg, const Layout &lay, int l) {
   HeaderView h;
@@ -400,6 +477,11 @@ void oracle_unpack_layer(const uint8_t *region, int64_t d, int32_t S, int32_t sc
 }
 
 double oracle_bucket_sumsq(const float *v, int64_t n) { return bucket_sumsq(v, n); }
+// the statistic of a layer / of a bucket under the given kind of norm, and the norm and fit weight it yields
+double oracle_norm_stat(const float *v, int64_t d, int32_t kind) { return layer_stat(v, d, kind); }
+double oracle_bucket_stat(const float *v, int64_t n, int32_t kind) { return bucket_stat(v, n, kind); }
+float oracle_norm_of(double s, int32_t kind) { return stat_finite(s, kind) ? norm_of(s, kind) : 0.0f; }
+double oracle_weight_of(double s, int32_t kind) { return weight_of(s, kind); }
 
 namespace {
 constexpr int32_t kTypeSkip = 0x7fffffff;   // "this type has no weight scale": nothing is gathered / fitted for it
@@ -411,7 +493,6 @@ inline uint64_t stat_weight(double s, int ex) {
   return (uint64_t)std::fmin(w, 1073741824.0);
 }
 
-const double kFiniteLimit = (double)std::numeric_limits<float>::max() * (double)std::numeric_limits<float>::max();
 
 // the norm DECODE uses for coordinate e of layer l: the header's (layer and vector scope) or the bucket's
 inline float stored_norm(const uint8_t *msg, const Layout &lay, int l, int64_t e) {
@@ -439,15 +520,15 @@ inline float stored_norm(const uint8_t *msg, const Layout &lay, int l, int64_t e
 int32_t oracle_quantize(int32_t L, const int64_t *d, const int32_t *S, const float *const *levels,
                         const float *const *grads, uint64_t seed, uint32_t round, uint32_t node, int32_t scope,
                         uint8_t *msg, const uint8_t *msg_prev, double *sumsq_out, double *delta_out,
-                        const int32_t *layer_exp, uint64_t *stats_hist, double *stats_max) {
+                        const int32_t *layer_exp, uint64_t *stats_hist, double *stats_max, int32_t norm_kind) {
   const Layout lay = make_layout(L, d, S, scope);
   std::memset(msg, 0, (size_t)lay.message_bytes);
   int32_t status = 0;
   std::vector<double> layer_sums(L, 0.0);
   if (scope != kScopeBucket) {
-    for (int l = 0; l < L; ++l) layer_sums[l] = oracle_sumsq(grads[l], d[l]);
+    for (int l = 0; l < L; ++l) layer_sums[l] = layer_stat(grads[l], d[l], norm_kind);
     if (scope == kScopeVector) {
-      const double total = combine_chunks(layer_sums);
+      const double total = combine_stats(layer_sums, norm_kind);
       for (int l = 0; l < L; ++l) layer_sums[l] = total;
     }
   }
@@ -457,9 +538,9 @@ int32_t oracle_quantize(int32_t L, const int64_t *d, const int32_t *S, const flo
     if (scope != kScopeBucket) {
       const double s = layer_sums[l];
       if (sumsq_out) sumsq_out[l] = s;
-      const bool finite = (s >= 0.0) && (s <= kFiniteLimit);
+      const bool finite = stat_finite(s, norm_kind);
       if (!finite) status = 1;
-      norm = finite ? sqrt_floor(s) : 0.0f;
+      norm = finite ? norm_of(s, norm_kind) : 0.0f;
       inv = rcp_floor(norm);
     } else if (sumsq_out) {
       sumsq_out[l] = 0.0;
@@ -477,17 +558,18 @@ int32_t oracle_quantize(int32_t L, const int64_t *d, const int32_t *S, const flo
       const int64_t e1 = std::min(d[l], (c + 1) * kChunk);   // padding coordinates carry code 0 and add nothing
       for (int64_t e = c * kChunk; e < e1; ++e) {
         if (scope == kScopeBucket && e % kBucket == 0) {
-          const double s = bucket_sumsq(grads[l] + e, std::min<int64_t>(kBucket, d[l] - e));
-          const bool finite = (s >= 0.0) && (s <= kFiniteLimit);
+          const double s = bucket_stat(grads[l] + e, std::min<int64_t>(kBucket, d[l] - e), norm_kind);
+          const bool finite = stat_finite(s, norm_kind);
           if (!finite) status = 1;
-          norm = finite ? sqrt_floor(s) : 0.0f;
+          norm = finite ? norm_of(s, norm_kind) : 0.0f;
           inv = rcp_floor(norm);
           *bucket_norm_slot(region, lay.planes[l], lay.ostride[l], e) = norm;
           if (sumsq_out && finite && s > sumsq_out[l]) sumsq_out[l] = s;
           if (layer_exp && ((e / kBlock) % 4) == 0) {
             const double sm = finite ? s : std::numeric_limits<double>::infinity();
             if (sm > stats_max[l]) stats_max[l] = sm;
-            const uint64_t wfix = (layer_exp[l] == kTypeSkip || !finite) ? 0 : stat_weight(s, layer_exp[l]);
+            const uint64_t wfix =
+                (layer_exp[l] == kTypeSkip || !finite) ? 0 : stat_weight(weight_of(s, norm_kind), layer_exp[l]);
             if (wfix != 0 && inv != 0.0f) {
               const int64_t n = std::min<int64_t>(kBucket, d[l] - e);
               for (int64_t q = e; q < e + n; ++q) {
@@ -832,8 +914,7 @@ inline bool any_weight(const std::vector<uint64_t> &W) {
 
 int32_t oracle_fit_levels(int32_t L, const int64_t *d, const int32_t *layer_type, int32_t M, const int32_t *type_points,
                           int32_t K, int32_t scope, const float *const *grads /* K*L, entry k*L+l */,
-                          float *const *levels_io, uint32_t *hist_out, uint64_t *pooled_out) {
-  const double smax_ok = (double)std::numeric_limits<float>::max() * (double)std::numeric_limits<float>::max();
+                          float *const *levels_io, uint32_t *hist_out, uint64_t *pooled_out, int32_t norm_kind) {
   int32_t status = 0;
   if (scope == kScopeBucket) {
     // Every bucket is a vector of its own: weight = its sum of squares, normalisation = its norm.  Sampled
@@ -849,8 +930,9 @@ int32_t oracle_fit_levels(int32_t L, const int64_t *d, const int32_t *layer_type
         for (int k = 0; k < K; ++k)
           for (int64_t e = 0; e < d[l]; e += kBucket) {
             if (((e / kBlock) % 4) != 0) continue;   // only sampled buckets carry weight, so only they set the scale
-            const double v = bucket_sumsq(grads[(size_t)k * L + l] + e, std::min<int64_t>(kBucket, d[l] - e));
-            if (!(v >= 0.0) || !(v <= smax_ok)) finite = false;
+            const double st = bucket_stat(grads[(size_t)k * L + l] + e, std::min<int64_t>(kBucket, d[l] - e), norm_kind);
+            const double v = weight_of(st, norm_kind);
+            if (!stat_finite(st, norm_kind)) finite = false;
             else if (v > smax) smax = v;
           }
       }
@@ -864,9 +946,9 @@ int32_t oracle_fit_levels(int32_t L, const int64_t *d, const int32_t *layer_type
             for (int64_t e0 = 0; e0 < d[l]; e0 += kBucket) {
               if (((e0 / kBlock) % 4) != 0) continue;
               const int64_t n = std::min<int64_t>(kBucket, d[l] - e0);
-              const double sv = bucket_sumsq(g + e0, n);
-              const uint64_t wfix = stat_weight(sv, ex);
-              const float inv = rcp_floor(sqrt_floor(sv));
+              const double sv = bucket_stat(g + e0, n, norm_kind);
+              const uint64_t wfix = stat_weight(weight_of(sv, norm_kind), ex);
+              const float inv = rcp_floor(norm_of(sv, norm_kind));
               if (wfix == 0 || inv == 0.0f) continue;
               for (int64_t e = e0; e < e0 + n; ++e) {
                 if (((f2u(g[e]) & 0x7FFFFFFFu) >> 20) == 0) continue;
@@ -889,12 +971,12 @@ int32_t oracle_fit_levels(int32_t L, const int64_t *d, const int32_t *layer_type
   std::vector<uint32_t> hist((size_t)K * L * kHistBins, 0);
   for (int k = 0; k < K; ++k) {
     for (int l = 0; l < L; ++l) {
-      s[(size_t)k * L + l] = oracle_sumsq(grads[(size_t)k * L + l], d[l]);
+      s[(size_t)k * L + l] = layer_stat(grads[(size_t)k * L + l], d[l], norm_kind);
       oracle_histogram(grads[(size_t)k * L + l], d[l], &hist[((size_t)k * L + l) * kHistBins]);
     }
     if (scope == kScopeVector) {   // one vector per node: its norm normalises, its squared norm weighs, every layer
       const std::vector<double> sums(s.begin() + (size_t)k * L, s.begin() + (size_t)(k + 1) * L);
-      const double total = combine_chunks(sums);
+      const double total = combine_stats(sums, norm_kind);
       for (int l = 0; l < L; ++l) s[(size_t)k * L + l] = total;
     }
   }
@@ -906,8 +988,8 @@ int32_t oracle_fit_levels(int32_t L, const int64_t *d, const int32_t *layer_type
     for (int l = 0; l < L; ++l) {
       if (layer_type[l] != m) continue;
       for (int k = 0; k < K; ++k) {
-        const double v = s[(size_t)k * L + l];
-        if (!(v >= 0.0) || !(v <= smax_ok)) finite = false;
+        const double v = weight_of(s[(size_t)k * L + l], norm_kind);
+        if (!stat_finite(s[(size_t)k * L + l], norm_kind)) finite = false;
         else if (v > smax) smax = v;
       }
     }
@@ -918,8 +1000,8 @@ int32_t oracle_fit_levels(int32_t L, const int64_t *d, const int32_t *layer_type
         if (layer_type[l] != m) continue;
         for (int k = 0; k < K; ++k) {
           const double sv = s[(size_t)k * L + l];
-          const uint64_t wfix = (uint64_t)std::floor(std::ldexp(sv, 23 - ex));
-          const float inv = rcp_floor(sqrt_floor(sv));
+          const uint64_t wfix = (uint64_t)std::floor(std::ldexp(weight_of(sv, norm_kind), 23 - ex));
+          const float inv = rcp_floor(norm_of(sv, norm_kind));
           if (wfix == 0 || inv == 0.0f) continue;
           const uint32_t *cnt = &hist[((size_t)k * L + l) * kHistBins];
           for (int b = 1; b < kHistBins; ++b) {
@@ -946,7 +1028,7 @@ int32_t oracle_fit_levels(int32_t L, const int64_t *d, const int32_t *layer_type
 // hist: K*L*257 (entry (k*L + l)*257 + j), bmax: K*L, exp_io: M (in: the scale the histograms were gathered with).
 int32_t oracle_fit_from_stats(int32_t L, const int32_t *layer_type, int32_t M, const int32_t *type_points, int32_t K,
                               const uint64_t *hist, const double *bmax, int32_t *exp_io, float *const *levels_io,
-                              uint64_t *pooled_out) {
+                              uint64_t *pooled_out, int32_t norm_kind) {
   int32_t status = 0;
   for (int m = 0; m < M; ++m) {
     std::vector<uint64_t> W(kGridPoints, 0);
@@ -957,8 +1039,8 @@ int32_t oracle_fit_from_stats(int32_t L, const int32_t *layer_type, int32_t M, c
       for (int k = 0; k < K; ++k) {
         const size_t idx = (size_t)k * L + l;
         for (int j = 0; j < kGridPoints; ++j) W[j] += hist[idx * kGridPoints + j];
-        const double v = bmax[idx];
-        if (!(v >= 0.0) || !(v <= kFiniteLimit)) finite = false;
+        const double v = weight_of(bmax[idx], norm_kind);   // bmax holds the statistic; the scale is that of the weights
+        if (!stat_finite(bmax[idx], norm_kind)) finite = false;
         else if (v > smax) smax = v;
       }
     }
