@@ -35,7 +35,7 @@ def _library():
     return qoda
 
 
-def _cpu_baseline(w, model, K, scope=0, sample_target=2.5e7):
+def _cpu_baseline(w, model, K, scope=0, kind=2, sample_target=2.5e7):
     """The oracle, as it stands, single-threaded, on a bounded sample of the same data: a run of consecutive
     tensors (skipping a leading embedding-sized one) for up to 4 nodes, one full round."""
     import oracle
@@ -61,10 +61,10 @@ def _cpu_baseline(w, model, K, scope=0, sample_target=2.5e7):
     t0 = time.perf_counter()
     if w.adaptive:
         flat = [grads[k][i] for k in range(Ks) for i in range(len(sizes))]
-        lev, _, _, _ = oracle.fit_levels(sizes, list(range(len(sizes))), [S] * len(sizes), Ks, flat, lev, scope=scope)
+        lev, _, _, _ = oracle.fit_levels(sizes, list(range(len(sizes))), [S] * len(sizes), Ks, flat, lev, scope=scope, norm_kind=kind)
     msgs, deltas = [], []
     for k in range(Ks):
-        m, _, dl, _ = oracle.quantize(sizes, [S] * len(sizes), lev, grads[k], w.seed, 1, k, scope=scope)
+        m, _, dl, _ = oracle.quantize(sizes, [S] * len(sizes), lev, grads[k], w.seed, 1, k, scope=scope, norm_kind=kind)
         msgs.append(m)
         deltas.append(dl)
     mean = oracle.dequant_aggregate(sizes, [S] * len(sizes), msgs, scope=scope)
@@ -89,6 +89,8 @@ def main() -> int:
     ap.add_argument("--x-next", action="store_true", help="also materialise X_{t+1}")
     ap.add_argument("--norm-scope", default="layer", choices=["layer", "vector", "bucket"],
                     help="what one norm covers: a layer (default), the node's whole vector, or buckets of 128 entries")
+    ap.add_argument("--norm-kind", default="l2", choices=["l2", "l1", "linf"],
+                    help="the q of the L^q normalisation (Sec. 2.2); the workloads' default is L2")
     ap.add_argument("--q-hat", type=float, default=0.0,
                     help="> 0: the step sizes of eq. (Alt) with this exponent instead of eq. (general_stepsize)")
     args = ap.parse_args()
@@ -110,7 +112,8 @@ def main() -> int:
     L, K, S, d = len(w.sizes), w.num_nodes, w.points, w.total
     scope = {"layer": qoda.SCOPE_LAYER, "vector": qoda.SCOPE_VECTOR, "bucket": qoda.SCOPE_BUCKET}[args.norm_scope]
     bucket = scope == qoda.SCOPE_BUCKET
-    ctx = qoda.Context(w.sizes, list(range(L)), [S] * L, K, w.seed, norm_scope=scope)
+    kind = {"l2": qoda.NORM_L2, "l1": qoda.NORM_L1, "linf": qoda.NORM_LINF}[args.norm_kind]
+    ctx = qoda.Context(w.sizes, list(range(L)), [S] * L, K, w.seed, norm_scope=scope, norm_kind=kind)
     off, flat_len = workloads.padded_offsets(w.sizes)
 
     def ptrs(t):
@@ -203,6 +206,7 @@ def main() -> int:
         try:
             # counters were collected under the main rule; eq. (Alt) reads no previous message in the quantizer
             key = args.workload + ("+alt" if alt else "") + ("" if scope == qoda.SCOPE_LAYER else "+" + args.norm_scope)
+            key += "" if kind == qoda.NORM_L2 else "+" + args.norm_kind   # (no counter runs for the other kinds)
             traffic = json.load(open(tpath)).get(key, {}).get(dom)
         except Exception:
             traffic = None
@@ -222,7 +226,7 @@ def main() -> int:
         "config": {"workload": args.workload, "num_nodes": K, "coordinates": d, "tensors": L, "level_points": S,
                    "adaptive_levels": w.adaptive, "message_bytes_per_node": mbytes, "x_next": xn is not None,
                    "step_sizes": f"eq. (Alt), q_hat={args.q_hat}" if alt else "eq. (general_stepsize)",
-                   "norm_scope": args.norm_scope},
+                   "norm_scope": args.norm_scope, "norm_kind": args.norm_kind},
         "hbm_peak_fraction_algorithmic": alg_round / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "algorithmic_bytes_per_step": alg_round,
         "host_wall_ms_per_step": t_host / args.steps * 1e3,
@@ -233,7 +237,7 @@ def main() -> int:
         "kernels": kernels,
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = _cpu_baseline(w, {"grad": grad, "off": off}, K, scope)
+        out["cpu_baseline"] = _cpu_baseline(w, {"grad": grad, "off": off}, K, scope, kind)
     print(json.dumps(out))
     return 0
 

@@ -70,6 +70,17 @@ extern "C" {
 #define QODA_SCOPE_VECTOR 1
 #define QODA_SCOPE_BUCKET 2
 
+/* The q of the L^q normalisation u_i = |v_i| / ||v||_q (Sec. 2.2; Thm 5.1 holds for every q, with d^(1/min(q,2))):
+ *   L2    norm = largest float whose square does not exceed the fp64 sum of squares (the default of the paper's
+ *         experiments and of this library's workloads);
+ *   L1    norm = the fp64 sum of magnitudes (same fixed summation order) rounded once to fp32;
+ *   LINF  norm = the largest magnitude (the limit q -> infinity), exact.
+ * A vector weighs ||v||_q^2 in the level fit (eq. (Qada2)).  Under bucket scope the sums run in single precision
+ * inside a lane, as for L2.  The step-size terms are Euclidean whatever q is. */
+#define QODA_NORM_LINF 0
+#define QODA_NORM_L1 1
+#define QODA_NORM_L2 2
+
 typedef struct qoda_ctx qoda_ctx;
 
 typedef struct {
@@ -80,7 +91,7 @@ typedef struct {
   const int32_t *type_points; /* S_m in [2, 256], host array [M], copied */
   int32_t num_nodes;          /* K >= 1, K <= 65535, and K * 2^(1+b_max) <= 16384 with b_max = ceil(log2 max_m S_m)
                                  (the decode tables of all K nodes are kept in shared memory), else QODA_EINVAL */
-  int32_t norm_kind;          /* 2 = L2 (the only kind built) */
+  int32_t norm_kind;          /* QODA_NORM_*: the q of the L^q normalisation */
   uint64_t seed;              /* key of the counter-based generator */
   int32_t norm_scope;         /* QODA_SCOPE_*: what one norm covers */
 } qoda_config;
@@ -212,7 +223,8 @@ int qoda_index_counts(qoda_ctx *ctx, const void *const *msgs_dev, uint64_t *coun
 int qoda_code_length(qoda_ctx *ctx, const uint64_t *counts, uint32_t num_messages, qoda_code_length_report *out);
 
 /* Read an internal device buffer into host memory (waits for `stream`); for tests and diagnostics. */
-#define QODA_BUF_SUMSQ 0  /* double[K*L]  canonical per-layer sums of squares of the last norm pass        */
+#define QODA_BUF_SUMSQ 0  /* double[K*L]  per-layer statistic of the last norm pass (sum of squares; L1: sum of
+                              magnitudes; LINF: largest magnitude); bucket scope: largest sampled bucket's */
 #define QODA_BUF_NORM 1   /* float [K*L]  norms                                                            */
 #define QODA_BUF_INV 2    /* float [K*L]  reciprocal norms                                                 */
 #define QODA_BUF_DELTA 3  /* double[K]    delta_k of the last quantize of each node                        */

@@ -20,6 +20,7 @@ using namespace qoda;
 struct qoda_ctx {
   int L = 0, M = 0, K = 0, G = 0;
   int scope = 0;   // NormScope
+  int kind = kNormL2;   // NormKind
   int device = 0;  // the device that was current at creation: owns every allocation of the context
   uint64_t seed = 0;
   std::vector<LayerMeta> meta;
@@ -204,6 +205,7 @@ Dev base_args(const qoda_ctx *c) {
   a.GS = c->GS;
   a.L = c->L; a.G = c->G; a.K = c->K; a.M = c->M;
   a.scope = c->scope;
+  a.kind = c->kind;
   a.type_points = c->d_type_points;
   a.partial = c->d_partial; a.dpartial = c->d_dpartial; a.sumsq = c->d_sumsq;
   a.norm = c->d_norm; a.inv = c->d_inv; a.delta = c->d_delta;
@@ -305,6 +307,7 @@ extern "C" {
 static int create_impl(const qoda_config *cfg, qoda_ctx *c) {
   c->L = cfg->num_layers; c->M = cfg->num_types; c->K = cfg->num_nodes; c->seed = cfg->seed;
   c->scope = cfg->norm_scope;
+  c->kind = cfg->norm_kind;
   for (int m = 0; m < c->M; ++m) {
     if (cfg->type_points[m] < 2 || cfg->type_points[m] > QODA_MAX_POINTS) return QODA_EINVAL;
     c->type_points.push_back(cfg->type_points[m]);
@@ -429,7 +432,7 @@ int qoda_create(const qoda_config *cfg, qoda_ctx **out) {
   *out = nullptr;
   if (!cfg || !cfg->layer_size || !cfg->layer_type || !cfg->type_points) return QODA_EINVAL;
   if (cfg->num_layers < 1 || cfg->num_types < 1 || cfg->num_nodes < 1 || cfg->num_nodes > 65535) return QODA_EINVAL;
-  if (cfg->norm_kind != 2) return QODA_EINVAL;
+  if (cfg->norm_kind != QODA_NORM_L2 && cfg->norm_kind != QODA_NORM_L1 && cfg->norm_kind != QODA_NORM_LINF) return QODA_EINVAL;
   if (cfg->norm_scope < QODA_SCOPE_LAYER || cfg->norm_scope > QODA_SCOPE_BUCKET) return QODA_EINVAL;
   qoda_ctx *c = new (std::nothrow) qoda_ctx;
   if (!c) return QODA_ENOMEM;

@@ -20,6 +20,10 @@ constexpr int kBucketCoords = 128;   // coordinates per bucket when every bucket
 
 // What one norm covers: a layer, the node's whole vector, or a bucket of 128 consecutive coordinates of a layer.
 enum NormScope { kScopeLayer = 0, kScopeVector = 1, kScopeBucket = 2 };
+// The q of the L^q normalisation (Sec. 2.2): 2, 1, or 0 standing for the limit q -> infinity.  Each kind reduces a
+// statistic over its vector (sum of squares, sum of magnitudes, largest magnitude), derives the fp32 norm from it
+// (floor root; one rounding; exact) and weighs the vector by ||v||_q^2 in the level fit.
+enum NormKind { kNormLinf = 0, kNormL1 = 1, kNormL2 = 2 };
 
 struct LayerMeta {
   long long d;         // elements
@@ -40,6 +44,7 @@ struct Dev {
   const int4 *stiles; // per run of up to kSuperTile tiles of one layer: (layer, first chunk inside layer, chunks, -)
   int L, G, GS, K, M; // GS = number of runs
   int scope;          // NormScope
+  int kind;           // NormKind
   const int *type_points;          // [M]
   const int *empty_layers;         // indices of the layers with d = 0
   int n_empty;
@@ -47,9 +52,9 @@ struct Dev {
   unsigned char *const *msg;       // [K]
   const unsigned char *const *prev;  // [K] or nullptr
   const unsigned char *const *msgs_in;  // [K] messages to decode
-  double *partial;    // [K*G] per-tile sums of squares
+  double *partial;    // [K*G] per-tile statistics (sums of squares, sums of magnitudes or largest magnitudes)
   double *dpartial;   // [K*G] per-tile squared differences
-  double *sumsq;      // [K*L]
+  double *sumsq;      // [K*L] the statistic of (node, layer); bucket scope: its largest sampled bucket statistic
   float *norm;        // [K*L]
   float *inv;         // [K*L]
   double *delta;      // [K]

@@ -105,6 +105,47 @@ __device__ double block_tree(double v, double *red) {
   return r;
 }
 
+// The same shape with the maximum instead of the sum (the order does not matter for a maximum; v >= 0, never NaN).
+__device__ double block_max(double v, double *red) {
+  const int t = threadIdx.x;
+  red[t] = v;
+  __syncthreads();
+  double r = 0.0;
+  if (t < 64) {
+    r = fmax(fmax(red[t], red[t + 128]), fmax(red[t + 64], red[t + 192]));
+#pragma unroll
+    for (int h = 32; h >= 1; h >>= 1) r = fmax(r, __shfl_down(r, h, 64));
+  }
+  __syncthreads();
+  return r;
+}
+
+// ----- the three kinds of norm: statistic -> finite?, norm, reciprocal, fit weight
+__device__ __forceinline__ bool stat_finite(double s, int kind) {
+  const double fm = (double)kFltMax;
+  return (s >= 0.0) && (s <= (kind == kNormL2 ? fm * fm : fm));
+}
+__device__ __forceinline__ float norm_of(double s, int kind) {
+  return kind == kNormL2 ? sqrt_floor(s) : __double2float_rn(s);
+}
+__device__ __forceinline__ double weight_of(double s, int kind) { return kind == kNormL2 ? s : s * s; }
+// largest magnitude from the running maximum of magnitude bit patterns: an infinity or a NaN pattern gives +infinity
+__device__ __forceinline__ float magnitude_from_bits(unsigned int mb) { return u2f(mb > 0x7F7FFFFFu ? 0x7F800000u : mb); }
+
+// rcp_floor for a norm in a comfortable range by straight-line code (estimate, then the exact test on the
+// candidates around it), the general routine otherwise: the same bits either way.
+__device__ __forceinline__ float inverse_of(float n) {
+  const int e = (int)((f2u(n) >> 23) & 0xFF) - 127;
+  if (e < -100 || e > 100) return rcp_floor(n);
+  float r = u2f(f2u(__builtin_amdgcn_rcpf(n)) + 1u);
+  const double nd = (double)n;
+#pragma unroll
+  for (int it = 0; it < 3; ++it) {
+    if (nd * (double)r > 1.0) r = u2f(f2u(r) - 1u);
+  }
+  return r;
+}
+
 // Philox4x32-10 (Salmon et al., SC'11).
 __device__ __forceinline__ void philox4x32_10(unsigned int c0, unsigned int c1, unsigned int c2, unsigned int c3,
                                                unsigned int k0, unsigned int k1, unsigned int out[4]) {
@@ -229,7 +270,7 @@ __global__ void k_zero_u32(unsigned int *p, size_t n) {
 // Sum of squares of one tile in fp64 (Sec. 2.2, L2 norm before the root), optionally with the histogram of the
 // top 11 magnitude bits (the distribution estimate of Alg. 1 line 4), taken over a fixed quarter of the
 // coordinates (every fourth 256-coordinate block) to keep the shared-memory atomics off the critical path.
-template <bool HIST>
+template <bool HIST, int KIND>
 __global__ void __launch_bounds__(kThreads) k_sumsq(Dev a) {
   __shared__ double red[kThreads];
   __shared__ unsigned int lh[HIST ? kHistBins : 1];
@@ -250,6 +291,7 @@ __global__ void __launch_bounds__(kThreads) k_sumsq(Dev a) {
     const int chunk = st.y + cc;
     const long long base = (long long)chunk * kChunkCoords + (long long)w * 16 * kBlockCoords + 4 * i;
     double acc = 0.0;
+    unsigned int mb = 0u;   // KIND == kNormLinf: largest magnitude bit pattern
     if ((long long)(chunk + 1) * kChunkCoords <= m.d) {
       v4f q[16];
 #pragma unroll
@@ -262,7 +304,9 @@ __global__ void __launch_bounds__(kThreads) k_sumsq(Dev a) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const double xd = (double)x[j];
-          acc = __builtin_fma(xd, xd, acc);   // the product is exact in fp64, so this equals acc + xd*xd
+          if (KIND == kNormL2) acc = __builtin_fma(xd, xd, acc);   // the product is exact in fp64, so this equals acc + xd*xd
+          else if (KIND == kNormL1) acc = acc + fabs(xd);
+          else mb = max(mb, f2u(x[j]) & 0x7FFFFFFFu);
           if (HIST && (s & 3) == 0) atomicAdd(&lh[(f2u(x[j]) & 0x7FFFFFFFu) >> 20], 1u);   // blocks 0, 4, 8, ... only
         }
       }
@@ -275,12 +319,14 @@ __global__ void __launch_bounds__(kThreads) k_sumsq(Dev a) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const double xd = (double)x[j];
-          acc = __builtin_fma(xd, xd, acc);
+          if (KIND == kNormL2) acc = __builtin_fma(xd, xd, acc);
+          else if (KIND == kNormL1) acc = acc + fabs(xd);
+          else mb = max(mb, f2u(x[j]) & 0x7FFFFFFFu);
           if (HIST && (s & 3) == 0 && e + j < m.d) atomicAdd(&lh[(f2u(x[j]) & 0x7FFFFFFFu) >> 20], 1u);
         }
       }
     }
-    const double total = block_tree(acc, red);
+    const double total = (KIND == kNormLinf) ? block_max((double)magnitude_from_bits(mb), red) : block_tree(acc, red);
     if (t == 0) a.partial[(size_t)k * a.G + m.first_chunk + chunk] = total;
   }
   if (HIST) {
@@ -302,12 +348,17 @@ __global__ void __launch_bounds__(kThreads) k_norm_finalize(Dev a) {
   const LayerMeta m = a.meta[l];
   const double *p = a.partial + (size_t)k * a.G + m.first_chunk;
   double acc = 0.0;
-  for (int c = threadIdx.x; c < m.nchunks; c += kThreads) acc = acc + p[c];
-  const double s = block_tree(acc, red);
+  double s;
+  if (a.kind == kNormLinf) {
+    for (int c = threadIdx.x; c < m.nchunks; c += kThreads) acc = fmax(acc, p[c]);
+    s = block_max(acc, red);
+  } else {
+    for (int c = threadIdx.x; c < m.nchunks; c += kThreads) acc = acc + p[c];
+    s = block_tree(acc, red);
+  }
   if (threadIdx.x == 0) {
-    const double lim = (double)kFltMax * (double)kFltMax;
-    const bool finite = (s >= 0.0) && (s <= lim);
-    const float n = finite ? sqrt_floor(s) : 0.0f;
+    const bool finite = stat_finite(s, a.kind);
+    const float n = finite ? norm_of(s, a.kind) : 0.0f;
     const size_t idx = (size_t)k * a.L + l;
     a.sumsq[idx] = s;
     a.norm[idx] = n;
@@ -324,14 +375,19 @@ __global__ void __launch_bounds__(kThreads) k_norm_vector(Dev a) {
   __shared__ double tot[1];
   const int k = a.node0 + blockIdx.x;
   double acc = 0.0;
-  for (int l = threadIdx.x; l < a.L; l += kThreads) acc = acc + a.sumsq[(size_t)k * a.L + l];
-  const double s = block_tree(acc, red);
+  double s;
+  if (a.kind == kNormLinf) {
+    for (int l = threadIdx.x; l < a.L; l += kThreads) acc = fmax(acc, a.sumsq[(size_t)k * a.L + l]);
+    s = block_max(acc, red);
+  } else {
+    for (int l = threadIdx.x; l < a.L; l += kThreads) acc = acc + a.sumsq[(size_t)k * a.L + l];
+    s = block_tree(acc, red);
+  }
   if (threadIdx.x == 0) tot[0] = s;
   __syncthreads();
   const double total = tot[0];
-  const double lim = (double)kFltMax * (double)kFltMax;
-  const bool finite = (total >= 0.0) && (total <= lim);
-  const float n = finite ? sqrt_floor(total) : 0.0f;
+  const bool finite = stat_finite(total, a.kind);
+  const float n = finite ? norm_of(total, a.kind) : 0.0f;
   const float r = rcp_floor(n);
   for (int l = threadIdx.x; l < a.L; l += kThreads) {
     const size_t idx = (size_t)k * a.L + l;
@@ -539,7 +595,7 @@ struct BucketWave {
 // (neighbour, then pair), which continues the same tree.
 // ex: weight scale of the layer's type for the fit statistics (kTypeSkip: none); best: running maximum of the bit
 // patterns of the lane's sampled bucket sums (blocks 0 and 4 of the octet, i.e. every fourth block of the layer).
-template <bool FAST>
+template <bool FAST, int KIND>
 __device__ __forceinline__ void bucket_norms(const Dev &a, const LayerMeta &m, long long O, const float *__restrict__ v,
                                              float *trailer, const float *prev_trailer, BucketWave &bw, int i, int ex,
                                              unsigned long long &best) {
@@ -554,8 +610,18 @@ __device__ __forceinline__ void bucket_norms(const Dev &a, const LayerMeta &m, l
       load4(v, e, m.d, x);
     }
     float acc = 0.0f;
+    if (KIND == kNormL2) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc = __builtin_fmaf(x[j], x[j], acc);
+      for (int j = 0; j < 4; ++j) acc = __builtin_fmaf(x[j], x[j], acc);
+    } else if (KIND == kNormL1) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc = acc + fabsf(x[j]);
+    } else {
+      unsigned int mb = 0u;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) mb = max(mb, f2u(x[j]) & 0x7FFFFFFFu);
+      acc = magnitude_from_bits(mb);
+    }
     bw.psum[72 * bb + i + (i >> 3)] = acc;
   }
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -564,21 +630,36 @@ __device__ __forceinline__ void bucket_norms(const Dev &a, const LayerMeta &m, l
   const int q = i >> 2, r = i & 3;
   const int bb = q >> 1, hf = q & 1;
   const float *p = &bw.psum[72 * bb + 36 * hf + 9 * r];   // lanes 32*hf + 8*r .. +7 of block bb in the padded layout
-  double s = (((double)p[0] + (double)p[1]) + ((double)p[2] + (double)p[3])) +
-             (((double)p[4] + (double)p[5]) + ((double)p[6] + (double)p[7]));
-  s = s + __shfl_xor(s, 1, 64);
-  s = s + __shfl_xor(s, 2, 64);
-  const double lim = (double)kFltMax * (double)kFltMax;
-  const bool finite = (s >= 0.0) && (s <= lim);
+  double s;
+  if (KIND == kNormLinf) {
+    const float mx = fmaxf(fmaxf(fmaxf(p[0], p[1]), fmaxf(p[2], p[3])), fmaxf(fmaxf(p[4], p[5]), fmaxf(p[6], p[7])));
+    s = (double)mx;
+    s = fmax(s, __shfl_xor(s, 1, 64));
+    s = fmax(s, __shfl_xor(s, 2, 64));
+  } else {
+    s = (((double)p[0] + (double)p[1]) + ((double)p[2] + (double)p[3])) +
+        (((double)p[4] + (double)p[5]) + ((double)p[6] + (double)p[7]));
+    s = s + __shfl_xor(s, 1, 64);
+    s = s + __shfl_xor(s, 2, 64);
+  }
+  const bool finite = stat_finite(s, KIND);
   float n = 0.0f, rinv = 0.0f;
-  if (finite) norm_and_inverse(s, n, rinv);
+  if (finite) {
+    if (KIND == kNormL2) {
+      norm_and_inverse(s, n, rinv);
+    } else {
+      n = __double2float_rn(s);
+      rinv = inverse_of(n);
+    }
+  }
   if (!finite) atomicOr(a.status, 1u);
   if ((bb & 3) == 0) {
     const unsigned long long bits = finite ? (unsigned long long)__double_as_longlong(s) : 0x7FF0000000000000ull;
     best = bits > best ? bits : best;
   }
   unsigned int wf = 0u;
-  if (ex != kTypeSkip && finite && rinv != 0.0f) wf = (unsigned int)fmin(floor(ldexp(s, 23 - ex)), 1073741824.0);
+  if (ex != kTypeSkip && finite && rinv != 0.0f)
+    wf = (unsigned int)fmin(floor(ldexp(weight_of(s, KIND), 23 - ex)), 1073741824.0);
   if (r == 0) {
     bw.norm[8 * hf + bb] = n;
     bw.inv[8 * hf + bb] = rinv;
@@ -642,7 +723,7 @@ __device__ __forceinline__ void quantize_block_b(const float (&x)[4], const unsi
   }
 }
 
-template <int C1, bool FAST, bool PREV>
+template <int C1, bool FAST, bool PREV, int KIND>
 __device__ __forceinline__ void quantize_octet_b(const Dev &a, const LayerMeta &m, int l, int k, long long O,
                                                  const float *__restrict__ v, unsigned char *body,
                                                  const unsigned char *prevbody, const unsigned char *lut,
@@ -653,7 +734,7 @@ __device__ __forceinline__ void quantize_octet_b(const Dev &a, const LayerMeta &
   const unsigned int k0 = (unsigned int)a.seed, k1 = (unsigned int)(a.seed >> 32);
   unsigned char *oct = body + O * OS;
   const unsigned char *poct = prevbody ? prevbody + O * OS : nullptr;
-  bucket_norms<FAST>(a, m, O, v, reinterpret_cast<float *>(oct + 256 * C1),
+  bucket_norms<FAST, KIND>(a, m, O, v, reinterpret_cast<float *>(oct + 256 * C1),
                      poct ? reinterpret_cast<const float *>(poct + 256 * C1) : nullptr, bw, i, ex, best);
   unsigned int D[C1], Dp[C1];
 #pragma unroll
@@ -699,7 +780,7 @@ __device__ __forceinline__ void quantize_octet_b(const Dev &a, const LayerMeta &
   store_record<C1>(oct, i, D);
 }
 
-template <int C1, bool PREV>
+template <int C1, bool PREV, int KIND>
 __global__ void __launch_bounds__(kThreads) k_quantize_b(Dev a) {
   __shared__ unsigned char lut[kLutSize];
   __shared__ float4 tab[kMaxPoints];
@@ -755,9 +836,9 @@ __global__ void __launch_bounds__(kThreads) k_quantize_b(Dev a) {
       const long long O = (long long)chunk * 8 + w * 2 + oo;
       if (O >= noct) break;
       if ((O + 1) * 2048 <= m.d)
-        quantize_octet_b<C1, true, PREV>(a, m, l, k, O, v, body, prevbody, lut, tab, tprev, bws[w], i, acc, ex, best, lh);
+        quantize_octet_b<C1, true, PREV, KIND>(a, m, l, k, O, v, body, prevbody, lut, tab, tprev, bws[w], i, acc, ex, best, lh);
       else
-        quantize_octet_b<C1, false, PREV>(a, m, l, k, O, v, body, prevbody, lut, tab, tprev, bws[w], i, acc, ex, best, lh);
+        quantize_octet_b<C1, false, PREV, KIND>(a, m, l, k, O, v, body, prevbody, lut, tab, tprev, bws[w], i, acc, ex, best, lh);
     }
     const double total = block_tree((double)acc, red);
     if (t == 0) a.dpartial[(size_t)k * a.G + m.first_chunk + chunk] = total;
@@ -1027,7 +1108,7 @@ __global__ void __launch_bounds__(kThreads) k_index_hist(Dev a) {
 }
 
 // ------------------------------------------------------------------------------------------------ level fit
-// Largest sum of squares of a type -> its binary exponent (fixed-point scale of the weights lambda_z).
+// Largest squared norm of a type -> its binary exponent (fixed-point scale of the weights lambda_z).
 __global__ void __launch_bounds__(kThreads) k_fit_typemax(Dev a) {
   __shared__ double red[kThreads];
   __shared__ int bad[1];
@@ -1035,14 +1116,13 @@ __global__ void __launch_bounds__(kThreads) k_fit_typemax(Dev a) {
   if (threadIdx.x == 0) bad[0] = 0;
   for (int j = threadIdx.x; j < kGridPoints; j += kThreads) a.pooled[(size_t)mtype * kGridPoints + j] = 0ull;
   __syncthreads();
-  const double lim = (double)kFltMax * (double)kFltMax;
-  double mx = 0.0;
+  double mx = 0.0;   // largest weight ||v||_q^2 of the type
   for (int idx = threadIdx.x; idx < a.K * a.L; idx += kThreads) {
     const int l = idx % a.L;
     if (a.meta[l].type != mtype) continue;
     const double s = a.sumsq[idx];
-    if (!(s >= 0.0) || !(s <= lim)) bad[0] = 1;
-    else if (s > mx) mx = s;
+    if (!stat_finite(s, a.kind)) bad[0] = 1;
+    else mx = fmax(mx, weight_of(s, a.kind));
   }
   red[threadIdx.x] = mx;
   __syncthreads();
@@ -1058,14 +1138,14 @@ __global__ void __launch_bounds__(kThreads) k_fit_typemax(Dev a) {
   }
 }
 
-// Re-bin one (node, layer) histogram onto the normalised grid with weight floor(sumsq * 2^(23 - exponent)).
+// Re-bin one (node, layer) histogram onto the normalised grid with weight floor(||v||_q^2 * 2^(23 - exponent)).
 __global__ void __launch_bounds__(kThreads) k_fit_pool(Dev a) {
   const int l = blockIdx.x, k = blockIdx.y;
   const LayerMeta m = a.meta[l];
   const int ex = a.type_exp[m.type];
   if (ex == kTypeSkip) return;
   const size_t idx = (size_t)k * a.L + l;
-  const unsigned long long wfix = (unsigned long long)floor(ldexp(a.sumsq[idx], 23 - ex));
+  const unsigned long long wfix = (unsigned long long)floor(ldexp(weight_of(a.sumsq[idx], a.kind), 23 - ex));
   const float inv = a.inv[idx];
   if (wfix == 0ull || inv == 0.0f) return;
   const unsigned int *cnt = a.hist + idx * kHistBins;
@@ -1086,22 +1166,36 @@ __global__ void __launch_bounds__(kThreads) k_fit_pool(Dev a) {
 // octet) are read: a quarter of the gradient per pass.
 // Sum of squares of the lane's bucket (half of block B) by the in-order binary tree, valid in all its 32 lanes.
 __device__ __forceinline__ double sampled_bucket_sum(const LayerMeta &m, const float *__restrict__ v, long long B, int i,
-                                                     float (&x)[4]) {
+                                                     float (&x)[4], int kind) {
   const long long e = B * kBlockCoords + 4 * i;
 #pragma unroll
   for (int j = 0; j < 4; ++j) x[j] = 0.0f;
   if (e < m.d) load4(v, e, m.d, x);
-  float acc = 0.0f;
+  if (kind == kNormLinf) {   // largest magnitude of the bucket
+    unsigned int mb = 0u;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) acc = __builtin_fmaf(x[j], x[j], acc);
+    for (int j = 0; j < 4; ++j) mb = max(mb, f2u(x[j]) & 0x7FFFFFFFu);
+    double s = (double)magnitude_from_bits(mb);
+#pragma unroll
+    for (int w = 1; w < 32; w *= 2) s = fmax(s, __shfl_xor(s, w, 64));
+    return s;
+  }
+  float acc = 0.0f;
+  if (kind == kNormL2) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc = __builtin_fmaf(x[j], x[j], acc);
+  } else {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc = acc + fabsf(x[j]);
+  }
   double s = (double)acc;
 #pragma unroll
   for (int w = 1; w < 32; w *= 2) s = s + __shfl_xor(s, w, 64);
   return s;
 }
 
-// Largest sampled bucket sum of every (node, layer), as the bit pattern of a non-negative double (ordered like an
-// integer); a sum that is not a finite number in range leaves +infinity.  a.sumsq must be zero on entry.
+// Largest sampled bucket statistic of every (node, layer), as the bit pattern of a non-negative double (ordered like
+// an integer); one that is not a finite number in range leaves +infinity.  a.sumsq must be zero on entry.
 __global__ void __launch_bounds__(kThreads) k_bucket_max(Dev a) {
   __shared__ unsigned long long wmax[kThreads / 64];
   const int4 st = a.stiles[blockIdx.x];
@@ -1109,7 +1203,6 @@ __global__ void __launch_bounds__(kThreads) k_bucket_max(Dev a) {
   const LayerMeta m = a.meta[l];
   const float *__restrict__ v = a.grad[(size_t)k * a.L + l];
   const int t = threadIdx.x, w = t >> 6, i = t & 63;
-  const double lim = (double)kFltMax * (double)kFltMax;
   unsigned long long best = 0ull;
   for (int cc = 0; cc < st.z; ++cc)
     for (int oo = 0; oo < 2; ++oo) {
@@ -1119,8 +1212,8 @@ __global__ void __launch_bounds__(kThreads) k_bucket_max(Dev a) {
         const long long B = O * 8 + bb;
         if (B >= m.nblk) continue;
         float x[4];
-        const double s = sampled_bucket_sum(m, v, B, i, x);
-        const bool finite = (s >= 0.0) && (s <= lim);
+        const double s = sampled_bucket_sum(m, v, B, i, x, a.kind);
+        const bool finite = stat_finite(s, a.kind);
         const unsigned long long bits = finite ? (unsigned long long)__double_as_longlong(s) : 0x7FF0000000000000ull;
         best = bits > best ? bits : best;
       }
@@ -1158,9 +1251,9 @@ __global__ void __launch_bounds__(kThreads) k_bucket_hist(Dev a) {
         const long long B = O * 8 + bb;
         if (B >= m.nblk) continue;
         float x[4];
-        const double s = sampled_bucket_sum(m, v, B, i, x);
-        const unsigned long long wfix = (unsigned long long)floor(ldexp(s, 23 - ex));
-        const float inv = rcp_floor(sqrt_floor(s));
+        const double s = sampled_bucket_sum(m, v, B, i, x, a.kind);
+        const unsigned long long wfix = (unsigned long long)floor(ldexp(weight_of(s, a.kind), 23 - ex));
+        const float inv = rcp_floor(norm_of(s, a.kind));
         if (wfix == 0ull || inv == 0.0f) continue;
         const long long e = B * kBlockCoords + 4 * i;
 #pragma unroll
@@ -1386,8 +1479,17 @@ hipError_t launch_zero_u32(unsigned int *p, size_t n, hipStream_t s) {
 
 hipError_t launch_sumsq(const Dev &a, bool with_hist, hipStream_t s) {
   if (a.GS == 0 || a.nnodes == 0) return hipSuccess;
-  if (with_hist) hipLaunchKernelGGL(k_sumsq<true>, dim3(a.GS, a.nnodes), dim3(kThreads), 0, s, a);
-  else hipLaunchKernelGGL(k_sumsq<false>, dim3(a.GS, a.nnodes), dim3(kThreads), 0, s, a);
+  const dim3 grid(a.GS, a.nnodes), block(kThreads);
+  if (a.kind == kNormL2) {
+    if (with_hist) hipLaunchKernelGGL((k_sumsq<true, kNormL2>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((k_sumsq<false, kNormL2>), grid, block, 0, s, a);
+  } else if (a.kind == kNormL1) {
+    if (with_hist) hipLaunchKernelGGL((k_sumsq<true, kNormL1>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((k_sumsq<false, kNormL1>), grid, block, 0, s, a);
+  } else {
+    if (with_hist) hipLaunchKernelGGL((k_sumsq<true, kNormLinf>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((k_sumsq<false, kNormLinf>), grid, block, 0, s, a);
+  }
   return hipGetLastError();
 }
 
@@ -1403,8 +1505,16 @@ static void launch_quantize_width(const Dev &a, hipStream_t s) {
   const bool prev = a.prev != nullptr;   // no node has a previous message: the kernels skip that half of the work
   if (a.scope == kScopeBucket) {
     const dim3 grid(a.GS, a.nnodes);   // runs of tiles
-    if (prev) hipLaunchKernelGGL((k_quantize_b<C1, true>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((k_quantize_b<C1, false>), grid, block, 0, s, a);
+    if (a.kind == kNormL2) {
+      if (prev) hipLaunchKernelGGL((k_quantize_b<C1, true, kNormL2>), grid, block, 0, s, a);
+      else hipLaunchKernelGGL((k_quantize_b<C1, false, kNormL2>), grid, block, 0, s, a);
+    } else if (a.kind == kNormL1) {
+      if (prev) hipLaunchKernelGGL((k_quantize_b<C1, true, kNormL1>), grid, block, 0, s, a);
+      else hipLaunchKernelGGL((k_quantize_b<C1, false, kNormL1>), grid, block, 0, s, a);
+    } else {
+      if (prev) hipLaunchKernelGGL((k_quantize_b<C1, true, kNormLinf>), grid, block, 0, s, a);
+      else hipLaunchKernelGGL((k_quantize_b<C1, false, kNormLinf>), grid, block, 0, s, a);
+    }
   } else {
     const dim3 grid(a.G, a.nnodes);
     if (prev) hipLaunchKernelGGL((k_quantize<C1, true>), grid, block, 0, s, a);

@@ -1,6 +1,7 @@
 // qoda_probe: a torch-free driver of libqoda's C ABI for profilers and hardware counters.
 //
-//   qoda_probe <sizes.txt> <K> <S> <rounds> [adaptive=1] [copy_mib=1024] [time_classes=0xFFFFFFFF]
+//   qoda_probe <sizes.txt> <K> <S> <rounds> [adaptive=1] [copy_mib=1024] [time_classes=0xFFFFFFFF] [q_hat=0]
+//              [norm_scope=0] [norm_kind=2]
 //
 // sizes.txt holds one layer size per line (python -m paper_2505_14371_amd.workloads <name> writes it).  The
 // probe fills K gradient buffers with heavy-tailed synthetic values (one scale per layer), runs `rounds` rounds
@@ -41,7 +42,7 @@ __global__ void fill_layer(float *p, long long n, float scale, uint32_t salt) {
 }
 
 int main(int argc, char **argv) {
-  if (argc < 5) { fprintf(stderr, "usage: %s sizes.txt K S rounds [adaptive=1] [copy_mib=1024] [time_classes=0xFFFFFFFF] [q_hat=0] [norm_scope=0]\n", argv[0]); return 2; }
+  if (argc < 5) { fprintf(stderr, "usage: %s sizes.txt K S rounds [adaptive=1] [copy_mib=1024] [time_classes=0xFFFFFFFF] [q_hat=0] [norm_scope=0] [norm_kind=2]\n", argv[0]); return 2; }
   std::vector<int64_t> sizes;
   FILE *f = fopen(argv[1], "r");
   if (!f) { perror(argv[1]); return 2; }
@@ -53,6 +54,7 @@ int main(int argc, char **argv) {
   const size_t copy_bytes = (size_t)(argc > 6 ? atoll(argv[6]) : 1024) << 20;
   const uint32_t time_classes = argc > 7 ? (uint32_t)strtoul(argv[7], nullptr, 0) : 0xFFFFFFFFu;
   const int scope = argc > 9 ? atoi(argv[9]) : QODA_SCOPE_LAYER;   // what one norm covers
+  const int kind = argc > 10 ? atoi(argv[10]) : QODA_NORM_L2;   // the q of the normalisation (0: infinity)
   const double q_hat = argc > 8 ? atof(argv[8]) : 0.0;   // > 0: the step sizes of eq. (Alt) instead of the main rule
   if (L < 1 || K < 1 || S < 2 || rounds < 1) { fprintf(stderr, "bad arguments\n"); return 2; }
 
@@ -61,7 +63,7 @@ int main(int argc, char **argv) {
   int64_t total = 0, d = 0;
   for (int l = 0; l < L; ++l) { types[l] = l; off[l] = total; total += (sizes[l] + 63) / 64 * 64; d += sizes[l]; }
   if (total == 0) total = 64;
-  qoda_config cfg = {L, sizes.data(), types.data(), L, points.data(), K, 2, 12345u, scope};
+  qoda_config cfg = {L, sizes.data(), types.data(), L, points.data(), K, kind, 12345u, scope};
   qoda_ctx *ctx = nullptr;
   if (qoda_create(&cfg, &ctx) != QODA_OK) { fprintf(stderr, "qoda_create failed\n"); return 1; }
   const size_t mbytes = qoda_message_bytes(ctx);
@@ -132,8 +134,8 @@ int main(int argc, char **argv) {
   CK(hipEventElapsedTime(&ms_total, e0, e1));
   double ms[QODA_NUM_KERNELS]; int64_t n[QODA_NUM_KERNELS];
   QK(qoda_profile_read(ctx, ms, n, nullptr));
-  printf("workload: L=%d d=%lld K=%d S=%d adaptive=%d q_hat=%g norm_scope=%d message_bytes=%zu\n", L, (long long)d, K, S,
-         (int)adaptive, q_hat, scope, mbytes);
+  printf("workload: L=%d d=%lld K=%d S=%d adaptive=%d q_hat=%g norm_scope=%d norm_kind=%d message_bytes=%zu\n", L,
+         (long long)d, K, S, (int)adaptive, q_hat, scope, kind, mbytes);
   printf("rounds=%d ms_per_round=%.4f fp32_gradient_GBps=%.1f\n", rounds, ms_total / rounds,
          4.0 * K * (double)d / (ms_total / rounds * 1e-3) / 1e9);
   for (int i = 0; i < QODA_NUM_KERNELS; ++i)

@@ -19,6 +19,7 @@ OK, EINVAL, ENOMEM, EHIP, ENONFINITE = 0, -1, -2, -3, -4
 BUF_SUMSQ, BUF_NORM, BUF_INV, BUF_DELTA, BUF_HIST, BUF_POOLED = range(6)
 NUM_KERNELS = 23
 SCOPE_LAYER, SCOPE_VECTOR, SCOPE_BUCKET = 0, 1, 2
+NORM_LINF, NORM_L1, NORM_L2 = 0, 1, 2
 HIST_BINS, GRID_POINTS = 2048, 257
 
 _lib = None
@@ -125,16 +126,17 @@ class Context:
     """One model: layer sizes, layer -> type map, grid points per type, K nodes, generator seed."""
 
     def __init__(self, layer_size: Sequence[int], layer_type: Sequence[int], type_points: Sequence[int],
-                 num_nodes: int, seed: int, norm_scope: int = SCOPE_LAYER):
+                 num_nodes: int, seed: int, norm_scope: int = SCOPE_LAYER, norm_kind: int = NORM_L2):
         self._lib = load()
         self.norm_scope = int(norm_scope)
+        self.norm_kind = int(norm_kind)
         self.layer_size = np.ascontiguousarray(layer_size, dtype=np.int64)
         self.layer_type = np.ascontiguousarray(layer_type, dtype=np.int32)
         self.type_points = np.ascontiguousarray(type_points, dtype=np.int32)
         self.L, self.M, self.K = int(self.layer_size.size), int(self.type_points.size), int(num_nodes)
         cfg = _Config(self.L, self.layer_size.ctypes.data_as(C.POINTER(C.c_int64)),
                       self.layer_type.ctypes.data_as(C.POINTER(C.c_int32)), self.M,
-                      self.type_points.ctypes.data_as(C.POINTER(C.c_int32)), self.K, 2, seed, self.norm_scope)
+                      self.type_points.ctypes.data_as(C.POINTER(C.c_int32)), self.K, self.norm_kind, seed, self.norm_scope)
         h = C.c_void_p()
         rc = self._lib.qoda_create(C.byref(cfg), C.byref(h))
         if rc != OK:

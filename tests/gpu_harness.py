@@ -18,10 +18,10 @@ class GpuModel:
     two message buffers per node, and the solver state."""
 
     def __init__(self, sizes: Sequence[int], layer_type: Sequence[int], type_points: Sequence[int], K: int, seed: int,
-                 norm_scope: int = 0):
+                 norm_scope: int = 0, norm_kind: int = 2):
         self.sizes = [int(s) for s in sizes]
         self.L, self.K = len(self.sizes), K
-        self.ctx = qoda.Context(self.sizes, layer_type, type_points, K, seed, norm_scope=norm_scope)
+        self.ctx = qoda.Context(self.sizes, layer_type, type_points, K, seed, norm_scope=norm_scope, norm_kind=norm_kind)
         self.off, self.flat_len = workloads.padded_offsets(self.sizes)
         self.grad_flat = [torch.zeros(self.flat_len, dtype=torch.float32, device=dev()) for _ in range(K)]
         self.mbytes = self.ctx.message_bytes()
