@@ -168,6 +168,13 @@ typedef struct {
  * msgs_dev: host [K]. */
 int qoda_step(qoda_ctx *ctx, const void *const *msgs_dev, const qoda_state *state, void *stream);
 
+/* The same fused pass with the caller's own schedule: Alg. 1 takes the learning rates {eta_t}, {gamma_t} as inputs
+ * (Sec. 4: any non-increasing pair with gamma_t >= eta_t > 0); eq. (general_stepsize) and eq. (Alt) are the paper's
+ * two proposals.  rates_dev: device float[2] = {eta_{t+1}, gamma_{t+1}}, read by the kernel when it runs.
+ * state->acc_dev and state->eta_dev are not used; nothing is accumulated. */
+int qoda_step_rates(qoda_ctx *ctx, const void *const *msgs_dev, const qoda_state *state, const float *rates_dev,
+                    void *stream);
+
 /* Solver state under the alternative pair of step sizes, Sec. 6 eq. (Alt) (all caller-owned device memory).
  * sums_dev: device double[2] = {lambda, mu}, both starting at 0:
  *   lambda = sum over finished rounds s of sum_k ||Vhat_{k,s+1/2}||^2 / K^2,  mu = sum_s ||X_s - X_{s+1}||^2.

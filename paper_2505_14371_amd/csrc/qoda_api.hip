@@ -690,6 +690,21 @@ int qoda_step(qoda_ctx *c, const void *const *msgs_dev, const qoda_state *st, vo
   });
 }
 
+int qoda_step_rates(qoda_ctx *c, const void *const *msgs_dev, const qoda_state *st, const float *rates_dev, void *stream) {
+  if (!c) return QODA_EINVAL;
+  return guarded(c, [&]() -> int {
+    if (const int rc_ = check_device(c)) return rc_;
+    if (!st || !rates_dev) return fail(c, QODA_EINVAL, "qoda_step_rates: null state or rates");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Dev a = base_args(c);
+    const int rc = step_common(c, msgs_dev, st->x1_dev, st->y_dev, st->x_half_dev, st->x_next_dev, a, s, "qoda_step_rates");
+    if (rc) return rc;
+    a.eta = const_cast<float *>(rates_dev);   // the update kernel only reads its two rates
+    LAUNCH(c, kIdDecodeUpdate, s, launch_decode(a, kDecodeUpdate, c->planes_mask, s));
+    return QODA_OK;
+  });
+}
+
 int qoda_index_counts(qoda_ctx *c, const void *const *msgs_dev, uint64_t *counts, void *stream) {
   if (!c) return QODA_EINVAL;
   return guarded(c, [&]() -> int {

@@ -77,6 +77,7 @@ def load():
     L.qoda_dequant_aggregate.argtypes = [vp, pp, pp, vp]
     L.qoda_step.argtypes = [vp, pp, C.POINTER(_State), vp]
     L.qoda_step_alt.argtypes = [vp, pp, C.POINTER(_AltState), C.c_double, vp]
+    L.qoda_step_rates.argtypes = [vp, pp, C.POINTER(_State), vp, vp]
     L.qoda_extrapolate.argtypes = [vp, pp, pp, pp, vp, vp]
     L.qoda_index_counts.argtypes = [vp, pp, C.POINTER(C.c_uint64), vp]
     L.qoda_code_length.argtypes = [vp, C.POINTER(C.c_uint64), C.c_uint32, C.POINTER(_CodeLength)]
@@ -90,7 +91,8 @@ def load():
     L.qoda_last_error.argtypes = [vp]
     L.qoda_last_error.restype = C.c_char_p
     for name in ("qoda_create", "qoda_destroy", "qoda_message_layout", "qoda_set_levels", "qoda_get_levels",
-                 "qoda_fit_levels", "qoda_quantize", "qoda_quantize_all", "qoda_dequant_aggregate", "qoda_step", "qoda_step_alt", "qoda_extrapolate", "qoda_index_counts", "qoda_code_length",
+                 "qoda_fit_levels", "qoda_quantize", "qoda_quantize_all", "qoda_dequant_aggregate", "qoda_step", "qoda_step_alt",
+                 "qoda_step_rates", "qoda_extrapolate", "qoda_index_counts", "qoda_code_length",
                  "qoda_read_buffer", "qoda_status", "qoda_profile_enable", "qoda_profile_read", "qoda_copy_calibration"):
         getattr(L, name).restype = C.c_int
     _lib = L
@@ -208,6 +210,13 @@ class Context:
         assert len(msgs) == self.K
         st = _State(_ptrs(x1), _ptrs(y), _ptrs(x_half), None if x_next is None else _ptrs(x_next), _addr(acc), _addr(eta))
         self._check(self._lib.qoda_step(self._h, _ptrs(msgs), C.byref(st), _stream(stream)))
+
+    def step_rates(self, msgs: Sequence, x1: Sequence, y: Sequence, x_half: Sequence, rates,
+                   x_next: Optional[Sequence] = None, stream=None):
+        """The fused step with the caller's two rates (device float[2]: eta_{t+1}, gamma_{t+1})."""
+        assert len(msgs) == self.K
+        st = _State(_ptrs(x1), _ptrs(y), _ptrs(x_half), None if x_next is None else _ptrs(x_next), None, None)
+        self._check(self._lib.qoda_step_rates(self._h, _ptrs(msgs), C.byref(st), _addr(rates), _stream(stream)))
 
     def step_alt(self, msgs: Sequence, x1: Sequence, y: Sequence, x_half: Sequence, sums, eta, q_hat: float,
                  x_next: Optional[Sequence] = None, stream=None):

@@ -410,3 +410,33 @@ def test_extreme_magnitudes(oracle, scope):
     got = m.layers(m.mean)
     for l in range(L):
         assert np.array_equal(got[l], mean[l]), l
+
+
+def test_step_with_the_callers_own_rates(oracle):
+    """Alg. 1 takes the two learning-rate sequences as inputs (any non-increasing pair with gamma_t >= eta_t > 0):
+    three rounds with a schedule of the caller's, the two rates different, iterates against the oracle's eq. (ODA)."""
+    sizes = [5000, 300, 0, 16384 + 77]
+    L, K, S = len(sizes), 3, 8
+    rng = np.random.default_rng(8)
+    x1 = [rng.standard_normal(s).astype(np.float32) for s in sizes]
+    m = gm(sizes, [0] * L, [S], K, seed=6)
+    m.set_layers(m.x1, x1)
+    lev = helpers.uniform_levels(S)
+    y = [np.zeros(s, np.float32) for s in sizes]
+    rates = torch.zeros(2, dtype=torch.float32, device="cuda:0")
+    for t in range(1, 4):
+        eta, gamma = np.float32(0.5 / t), np.float32(0.8 / np.sqrt(t))
+        rates.copy_(torch.tensor([eta, gamma], dtype=torch.float32))
+        grads = [[rng.standard_normal(s).astype(np.float32) for s in sizes] for _ in range(K)]
+        m.set_grads(grads)
+        m.quantize_all(t)
+        want = [oracle.quantize(sizes, [S] * L, [lev] * L, grads[k], 6, t, k)[0] for k in range(K)]
+        mean = oracle.dequant_aggregate(sizes, [S] * L, want)
+        m.ctx.step_rates(m.msg[m.cur], m.layer_ptrs(m.x1), m.layer_ptrs(m.y), m.layer_ptrs(m.x_half), rates,
+                         m.layer_ptrs(m.x_next))
+        gy, gxh, gxn = m.layers(m.y), m.layers(m.x_half), m.layers(m.x_next)
+        for l in range(L):
+            xn, xh = oracle.oda_update(mean[l], x1[l], y[l], eta, gamma)
+            assert np.array_equal(gy[l], y[l]) and np.array_equal(gxh[l], xh) and np.array_equal(gxn[l], xn), (t, l)
+    with pytest.raises(qoda.QodaError):
+        m.ctx.step_rates(m.msg[m.cur], m.layer_ptrs(m.x1), m.layer_ptrs(m.y), m.layer_ptrs(m.x_half), None)
