@@ -36,7 +36,7 @@ def _short(name: str) -> str:
     raw = [a.strip() for a in (m.group(2) or "<>")[1:-1].split(",") if a.strip()]
     if base == "k_decode" and len(raw) >= 2:
         return "k_decode<" + {"0": "false", "1": "true", "2": "alt", "3": "extrapolate"}.get(raw[1], raw[1]) + ">"
-    if base == "k_quantize_b":
+    if base in ("k_quantize", "k_quantize_b"):   # whatever the code width, with or without a previous message
         return "k_quantize"
     if base == "k_index_hist":
         return base
@@ -82,7 +82,10 @@ def main():
     for r in csv.DictReader(open(_one(os.path.join(a.stats, "**", "*_kernel_stats.csv")))):
         if "qoda::" not in r["Name"]:
             continue
-        lines.append(f"{_short(r['Name']):<22}{r['Calls']:>7}{float(r['AverageNs']) / 1e3:>12.1f}"
+        label = _short(r["Name"])
+        if label == "k_quantize" and re.search(r"k_quantize(_b)?<\d+, false", r["Name"]):
+            label = "k_quantize (no prev)"   # the round-1 variant that reads no previous message
+        lines.append(f"{label:<22}{r['Calls']:>7}{float(r['AverageNs']) / 1e3:>12.1f}"
                      f"{float(r['MinNs']) / 1e3:>12.1f}{float(r['MaxNs']) / 1e3:>12.1f}{float(r['Percentage']):>8.2f}")
     traffic = {}
     if a.fetch and a.write:
