@@ -20,10 +20,10 @@ import re
 
 
 def _one(pattern: str) -> str:
-    hits = sorted(glob.glob(pattern, recursive=True))
+    hits = glob.glob(pattern, recursive=True)
     if not hits:
         raise SystemExit(f"no file matches {pattern}")
-    return hits[-1]
+    return max(hits, key=os.path.getmtime)   # a directory reused by several runs: the latest one
 
 
 def _short(name: str) -> str:
