@@ -929,7 +929,7 @@ int qoda_profile_read(qoda_ctx *c, double *ms, int64_t *launches, void *stream) 
 
 const char *qoda_kernel_name(int32_t id) {
   static const char *names[kNumKernelIds] = {"k_zero_u32", "k_sumsq<false>", "k_sumsq<true>", "k_norm_finalize",
-                                             "k_write_header", "k_quantize", "k_delta_finalize", "k_step_scalars",
+                                             "(unused)", "k_quantize", "k_delta_finalize", "k_step_scalars",
                                              "k_decode<false>", "k_decode<true>", "k_fit_typemax", "k_fit_pool",
                                              "k_fit_dp", "k_build_tables", "k_copy_f4", "k_alt_scalars",
                                              "k_decode<alt>", "k_alt_finalize", "k_norm_vector", "k_bucket_max",

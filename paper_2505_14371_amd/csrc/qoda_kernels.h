@@ -95,7 +95,7 @@ enum DecodeMode { kDecodeMean = 0, kDecodeUpdate = 1, kDecodeUpdateAlt = 2, kDec
 
 // Kernel classes, for the optional per-kernel event timing of the host API.
 enum KernelId {
-  kIdZero = 0, kIdSumsq, kIdSumsqHist, kIdNormFinalize, kIdWriteHeader, kIdQuantize, kIdDeltaFinalize, kIdStepScalars,
+  kIdZero = 0, kIdSumsq, kIdSumsqHist, kIdNormFinalize, kIdReserved4 /* no kernel: keeps the class numbers of the others stable */, kIdQuantize, kIdDeltaFinalize, kIdStepScalars,
   kIdDecodeMean, kIdDecodeUpdate, kIdFitTypemax, kIdFitPool, kIdFitDp, kIdBuildTables, kIdCopy, kIdAltScalars,
   kIdDecodeAlt, kIdAltFinalize, kIdNormVector, kIdBucketMax, kIdBucketHist, kIdDecodeExtrapolate, kIdIndexHist, kNumKernelIds
 };
