@@ -440,3 +440,55 @@ def test_step_with_the_callers_own_rates(oracle):
             assert np.array_equal(gy[l], y[l]) and np.array_equal(gxh[l], xh) and np.array_equal(gxn[l], xn), (t, l)
     with pytest.raises(qoda.QodaError):
         m.ctx.step_rates(m.msg[m.cur], m.layer_ptrs(m.x1), m.layer_ptrs(m.y), m.layer_ptrs(m.x_half), None)
+
+
+@pytest.mark.parametrize("scope", [qoda.SCOPE_LAYER, qoda.SCOPE_BUCKET])
+def test_adversarial_level_sequences(oracle, scope):
+    """Levels one unit in the last place apart, subnormal levels, a level next to 1: the search table, the walk past a
+    bin's lower edge, reciprocal gaps at the top of the fp32 range and the rounding threshold must all agree."""
+    f = np.float32
+    tiny = np.nextafter(f(0), f(1))
+    seqs = [
+        np.array([0, tiny, 2 * tiny, f(2.0 ** -126), np.nextafter(f(2.0 ** -126), f(1)), f(0.5), np.nextafter(f(0.5), f(1)), 1], f),
+        np.array([0, f(1e-30), f(0.25), np.nextafter(f(0.25), f(1)), np.nextafter(np.nextafter(f(0.25), f(1)), f(1)),
+                  f(0.75), np.nextafter(f(1), f(0)), 1], f),
+        np.array([0, np.nextafter(f(1), f(0)), 1], f),
+        np.array([0, tiny, 1], f),
+    ]
+    rng = np.random.default_rng(17)
+    for lev in seqs:
+        S = lev.size
+        assert np.all(np.diff(lev.astype(np.float64)) > 0)
+        sizes = [4096 + 300, 700]
+        K = 2
+        grads = []
+        for k in range(K):
+            g = []
+            for s in sizes:
+                v = rng.standard_normal(s).astype(np.float32)
+                v[: s // 4] *= f(1e-6)
+                v[s // 4: s // 2] = rng.choice(lev, s // 2 - s // 4) * f(3.0) * rng.choice([-1.0, 1.0], s // 2 - s // 4)
+                v[5] = 0.0
+                v[6] = -0.0
+                g.append(v.astype(np.float32))
+            grads.append(g)
+        m = gm(sizes, [0, 0], [S], K, seed=23, norm_scope=scope)
+        m.ctx.set_levels(0, lev)
+        for t in (1, 2):
+            m.set_grads(grads)
+            m.quantize_all(t)
+            msgs = m.messages()
+            delta = m.ctx.read_buffer(qoda.BUF_DELTA)
+            for k in range(K):
+                prev = None if t == 1 else prev_msgs[k]
+                wm, _, dl, st = oracle.quantize(sizes, [S, S], [lev, lev], grads[k], 23, t, k, msg_prev=prev, scope=scope)
+                assert st == 0
+                assert np.array_equal(msgs[k], wm), (S, t, k)
+                assert delta[k] == dl, (S, t, k)
+            prev_msgs = msgs
+            m.aggregate()
+            mean = m.layers(m.mean)
+            want = oracle.dequant_aggregate(sizes, [S, S], msgs, scope=scope)
+            assert all(np.array_equal(a, b) for a, b in zip(mean, want))
+            m.step()
+        assert m.ctx.status() == qoda.OK
