@@ -35,7 +35,7 @@ def _library():
     return qoda
 
 
-def _cpu_baseline(w, model, K, scope=0, kind=2, sample_target=2.5e7):
+def _cpu_baseline(w, model, K, scope=0, kind=2, sample_target=6e7):
     """The oracle, as it stands, single-threaded, on a bounded sample of the same data: a run of consecutive
     tensors (skipping a leading embedding-sized one) for up to 4 nodes, one full round."""
     import oracle
