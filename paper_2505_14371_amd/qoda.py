@@ -107,11 +107,19 @@ def _addr(x) -> Optional[int]:
     return int(x.data_ptr())
 
 
-def _ptrs(xs: Sequence) -> C.Array:
+def _ptrs(xs) -> C.Array:
+    if isinstance(xs, C.Array):          # built once by the caller with pointer_array(): passed through
+        return xs
     arr = (C.c_void_p * len(xs))()
     for i, x in enumerate(xs):
         arr[i] = _addr(x)
     return arr
+
+
+def pointer_array(xs: Sequence) -> C.Array:
+    """A host array of device pointers in the form the library takes, for callers that pass the same set every
+    round and do not want it rebuilt on every call (tensors or integer addresses; None -> NULL)."""
+    return _ptrs(list(xs))
 
 
 def _stream(stream) -> Optional[int]:

@@ -61,6 +61,12 @@ class QODA:
         self._acc = torch.zeros(1, dtype=torch.float64, device=dev)            # eq. (general_stepsize)
         self._sums = torch.zeros(2, dtype=torch.float64, device=dev)           # eq. (Alt): lambda, mu
         self.rates = torch.ones(2, dtype=torch.float32, device=dev)            # eta_{t+1}, gamma_{t+1} after a step
+        # pointer sets that never change: marshalled once
+        self._p_msg = [qoda.pointer_array(m) for m in self._msg]
+        self._p_xh = qoda.pointer_array(self.params)
+        self._p_x1 = qoda.pointer_array(self._x1)
+        self._p_y = qoda.pointer_array(self._y)
+        self._p_xn = None if self._xn is None else qoda.pointer_array(self._xn)
         self.t = 0
 
     def _check_grads(self, node_grads) -> List[int]:
@@ -78,23 +84,21 @@ class QODA:
 
     def step(self, node_grads: Sequence[Sequence[torch.Tensor]], stream=None) -> None:
         """One round of Alg. 1 given the K nodes' dual vectors at the current query point (the parameters)."""
-        gp = self._check_grads(node_grads)
+        gp = qoda.pointer_array(self._check_grads(node_grads))
         self.t += 1
         t, cur = self.t, self.t & 1
         if self.fit_every > 0 and (t - 1) % self.fit_every == 0:
             # bucket scope after the first fit: from the statistics the previous quantize pass gathered
             self.ctx.fit_levels(None if (self.norm_scope == qoda.SCOPE_BUCKET and t > 1) else gp, t, stream=stream)
         alt = self.q_hat is not None
-        prev = self._msg[1 - cur] if (t > 1 and not alt) else None
-        self.ctx.quantize_all(gp, t, self._msg[cur], prev, stream=stream)
-        xh = [p.data_ptr() for p in self.params]
-        x1 = [x.data_ptr() for x in self._x1]
-        y = [x.data_ptr() for x in self._y]
-        xn = None if self._xn is None else [x.data_ptr() for x in self._xn]
+        prev = self._p_msg[1 - cur] if (t > 1 and not alt) else None
+        self.ctx.quantize_all(gp, t, self._p_msg[cur], prev, stream=stream)
         if alt:
-            self.ctx.step_alt(self._msg[cur], x1, y, xh, self._sums, self.rates, self.q_hat, xn, stream=stream)
+            self.ctx.step_alt(self._p_msg[cur], self._p_x1, self._p_y, self._p_xh, self._sums, self.rates, self.q_hat,
+                              self._p_xn, stream=stream)
         else:
-            self.ctx.step(self._msg[cur], x1, y, xh, self._acc, xn, self.rates, stream=stream)
+            self.ctx.step(self._p_msg[cur], self._p_x1, self._p_y, self._p_xh, self._acc, self._p_xn, self.rates,
+                          stream=stream)
 
     def state_point(self) -> List[torch.Tensor]:
         """X_{t+1} (the dual-averaging iterate; the parameters hold X_{t+3/2}); needs keep_next=True."""
