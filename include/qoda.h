@@ -144,6 +144,19 @@ int qoda_quantize(qoda_ctx *ctx, int32_t node, const float *const *grad_dev, uin
 int qoda_quantize_all(qoda_ctx *ctx, const float *const *grad_dev, uint32_t round, void *const *msg_dev,
                       const void *const *msg_prev_dev, void *stream);
 
+/* qoda_quantize for callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same message bytes and the same delta_k left in the context as qoda_quantize,
+ * but nothing is allocated, uploaded or waited for: the kernels' scratch (one node's per-tile partial sums, per-layer
+ * statistics, norms, reciprocals and pointer tables) lives in a static device array of about 2.1 MiB that every GPU
+ * the library runs on holds until the process ends, and the pointers travel as kernel arguments.  The norms are always
+ * computed from grad_dev (no reuse of a fit's norms), launches are never timed by qoda_profile_enable, and under
+ * bucket scope the node's fit statistics still go to the context.  Limits: L <= 4096 layers and at most 131072 tiles
+ * of 16384 coordinates per node (2^31 coordinates), else QODA_EINVAL.  All calls on one GPU share the one array, which
+ * keeps the last call's contents (every entry a call reads it has written first, so nothing needs clearing): calls
+ * whose work overlaps on one GPU -- two streams, two contexts, two threads -- race; order them on one stream. */
+int qoda_quantize_noalloc(qoda_ctx *ctx, int32_t node, const float *const *grad_dev, uint32_t round, void *msg_dev,
+                          const void *msg_prev_dev, void *stream);
+
 /* DECODE + mean, Alg. 1 lines 15-17 without the update: mean_out[l][e] = (Vhat_0 + ... + Vhat_{K-1}) / K with
  * Vhat_k = +-norm_k * l_h, summed in fp32 in increasing k.  msgs_dev: host [K]; mean_out_dev: host [L]. */
 int qoda_dequant_aggregate(qoda_ctx *ctx, const void *const *msgs_dev, float *const *mean_out_dev, void *stream);

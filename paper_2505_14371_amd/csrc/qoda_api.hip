@@ -8,6 +8,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -85,7 +86,42 @@ struct qoda_ctx {
   std::string err;
 };
 
+// ---- scratch of qoda_quantize_noalloc: one node's per-tile partial sums, per-layer statistics and pointer tables in a
+// file-scope device array instead of the context's allocations.  Every GPU the library runs on holds its own copy
+// (about 2.1 MiB) until the process ends.
 namespace {
+constexpr size_t kNoallocMaxTiles = 1u << 17;     // tiles of 16384 coordinates of one node: 2^31 coordinates
+constexpr size_t kNoallocMaxLayers = 4096;
+constexpr size_t kOffPartial = 0;                                          // double[tiles]   per-tile statistics
+constexpr size_t kOffDpartial = kOffPartial + 8 * kNoallocMaxTiles;        // double[tiles]   per-tile squared distances
+constexpr size_t kOffSumsq = kOffDpartial + 8 * kNoallocMaxTiles;          // double[layers]
+constexpr size_t kOffNorm = kOffSumsq + 8 * kNoallocMaxLayers;             // float[layers]
+constexpr size_t kOffInv = kOffNorm + 4 * kNoallocMaxLayers;               // float[layers]
+constexpr size_t kOffGrad = kOffInv + 4 * kNoallocMaxLayers;               // pointer[layers] the node's layers
+constexpr size_t kOffMsg = kOffGrad + 8 * kNoallocMaxLayers;               // pointer[1]      the message
+constexpr size_t kOffPrev = kOffMsg + 256;                                 // pointer[1]      the previous message
+constexpr size_t kScratchBytes = kOffPrev + 256;
+constexpr int kMaxDevices = 64;
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+namespace {
+// In host code `scratch` is only a handle for the symbol; the array's address on each device is looked up once, with
+// that device current, and only these addresses are ever handed to kernels.
+unsigned char *g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+hipError_t scratch_setup(int device) {
+  if (device < 0 || device >= kMaxDevices) return hipSuccess;   // such a device has no entry: the entry point says so
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[device]) return hipSuccess;
+  void *ptr = nullptr;
+  const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+  if (e != hipSuccess) return e;
+  g_scratch_ptr[device] = static_cast<unsigned char *>(ptr);
+  return hipSuccess;
+}
 
 int fail(qoda_ctx *c, int code, const char *fmt, ...) {
   if (c) {
@@ -437,6 +473,7 @@ int qoda_create(const qoda_config *cfg, qoda_ctx **out) {
   qoda_ctx *c = new (std::nothrow) qoda_ctx;
   if (!c) return QODA_ENOMEM;
   int rc = (hipGetDevice(&c->device) == hipSuccess) ? QODA_OK : QODA_EHIP;
+  if (rc == QODA_OK && scratch_setup(c->device) != hipSuccess) rc = QODA_EHIP;
   if (rc == QODA_OK) rc = guarded(c, [&]() -> int { return create_impl(cfg, c); });
   if (rc != QODA_OK) {
     free_all(c);
@@ -618,6 +655,65 @@ int qoda_quantize(qoda_ctx *c, int32_t node, const float *const *grad_dev, uint3
     rc = sync_table(c, c->t_prev, p.data(), c->K, s);
     if (rc) return rc;
     return quantize_impl(c, node, 1, reinterpret_cast<const float *const *>(c->t_grad.host().data()), round, s, true);
+  });
+}
+
+int qoda_quantize_noalloc(qoda_ctx *c, int32_t node, const float *const *grad_dev, uint32_t round, void *msg_dev,
+                          const void *msg_prev_dev, void *stream) {
+  if (!c) return QODA_EINVAL;
+  return guarded(c, [&]() -> int {
+    if (const int rc_ = check_device(c)) return rc_;
+    if (node < 0 || node >= c->K) return fail(c, QODA_EINVAL, "qoda_quantize_noalloc: node %d out of range", node);
+    int rc = check_layer_ptrs(c, reinterpret_cast<const void *const *>(grad_dev), c->L, "qoda_quantize_noalloc: grad_dev", true);
+    if (rc) return rc;
+    const void *mp[1] = {msg_dev};
+    rc = check_msg_ptrs(c, mp, 1, "qoda_quantize_noalloc: msg_dev", false);
+    if (rc) return rc;
+    const void *pp[1] = {msg_prev_dev};
+    rc = check_msg_ptrs(c, pp, 1, "qoda_quantize_noalloc: msg_prev_dev", true);
+    if (rc) return rc;
+    if (msg_prev_dev == msg_dev) return fail(c, QODA_EINVAL, "qoda_quantize_noalloc: msg_prev_dev aliases msg_dev");
+    if ((size_t)c->L > kNoallocMaxLayers || (size_t)c->G > kNoallocMaxTiles)
+      return fail(c, QODA_EINVAL,
+                  "qoda_quantize_noalloc: %d layers and %d tiles of 16384 coordinates exceed the static scratch "
+                  "(at most %zu layers and %zu tiles per node)", c->L, c->G, kNoallocMaxLayers, kNoallocMaxTiles);
+    unsigned char *sp = (c->device >= 0 && c->device < kMaxDevices) ? g_scratch_ptr[c->device] : nullptr;
+    if (!sp) return fail(c, QODA_EHIP, "qoda_quantize_noalloc: no static scratch on device %d", c->device);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // the node's pointers reach the device as kernel arguments: no staging buffer, no copy
+    void **t_grad = reinterpret_cast<void **>(sp + kOffGrad);
+    void **t_msg = reinterpret_cast<void **>(sp + kOffMsg);
+    void **t_prev = reinterpret_cast<void **>(sp + kOffPrev);
+    HIP_TRY(c, launch_stage_pointers(t_grad, reinterpret_cast<const void *const *>(grad_dev), (size_t)c->L, s));
+    HIP_TRY(c, launch_stage_pointers(t_msg, mp, 1, s));
+    HIP_TRY(c, launch_stage_pointers(t_prev, pp, 1, s));
+    Dev a = base_args(c);
+    a.partial = reinterpret_cast<double *>(sp + kOffPartial);
+    a.dpartial = reinterpret_cast<double *>(sp + kOffDpartial);
+    a.grad = reinterpret_cast<const float *const *>(t_grad);
+    a.msg = reinterpret_cast<unsigned char *const *>(t_msg);
+    a.prev = msg_prev_dev ? reinterpret_cast<const unsigned char *const *>(t_prev) : nullptr;
+    a.round = round;
+    a.node0 = node;
+    a.nnodes = 1;
+    a.row0 = node;   // the tables above hold this node's rows only
+    if (c->scope == kScopeBucket) {
+      // the bucket norms are computed by the quantize kernel, which also gathers this node's fit statistics into the
+      // context (they are state of the next fit, not scratch): they start from zero
+      const size_t n0 = (size_t)node * c->L, nn = (size_t)c->L;
+      HIP_TRY(c, launch_zero_u32(c->d_hist + n0 * kHistBins, nn * kHistBins, s));
+      HIP_TRY(c, launch_zero_u32(reinterpret_cast<unsigned int *>(c->d_sumsq + n0), 2 * nn, s));
+    } else {
+      a.sumsq = reinterpret_cast<double *>(sp + kOffSumsq);
+      a.norm = reinterpret_cast<float *>(sp + kOffNorm);
+      a.inv = reinterpret_cast<float *>(sp + kOffInv);
+      HIP_TRY(c, launch_sumsq(a, false, s));
+      HIP_TRY(c, launch_norm_finalize(a, s));
+      if (c->scope == kScopeVector) HIP_TRY(c, launch_norm_vector(a, s));
+    }
+    HIP_TRY(c, launch_quantize(a, c->planes_mask, s));
+    HIP_TRY(c, launch_delta_finalize(a, s));
+    return QODA_OK;
   });
 }
 

@@ -84,6 +84,9 @@ struct Dev {
   unsigned int round;
   int node0;    // first node handled by this launch
   int nnodes;   // nodes handled by this launch (grid.y)
+  int row0;     // the node whose rows come first in grad, msg, prev, partial, dpartial, sumsq, norm and inv (0 when
+                // these hold all K nodes; the node itself when they hold one node's rows only).  delta and the fit
+                // statistics of bucket scope (hist, sumsq) are always indexed by the node.
   float invK;
   double invK2;
 };
@@ -120,5 +123,7 @@ hipError_t launch_fit_pool(const Dev &a, hipStream_t s);
 hipError_t launch_fit_dp(const Dev &a, hipStream_t s);
 hipError_t launch_copy(const void *src, void *dst, size_t bytes, hipStream_t s);
 hipError_t launch_build_tables(const Dev &a, int type, hipStream_t s);
+// Copy n pointers from a host array into device memory through kernel arguments (no staging buffer, no copy engine).
+hipError_t launch_stage_pointers(void **dst_dev, const void *const *src_host, size_t n, hipStream_t s);
 
 }  // namespace qoda

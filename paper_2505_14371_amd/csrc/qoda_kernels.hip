@@ -279,8 +279,9 @@ __global__ void __launch_bounds__(kThreads) k_sumsq(Dev a) {
   const int4 st = a.stiles[blockIdx.x];   // (layer, first chunk inside the layer, chunks)
   const int l = st.x;
   const int k = a.node0 + blockIdx.y;
+  const int kr = k - a.row0;   // row of this node in the per-node scratch and pointer tables
   const LayerMeta m = a.meta[l];
-  const float *__restrict__ v = a.grad[(size_t)k * a.L + l];
+  const float *__restrict__ v = a.grad[(size_t)kr * a.L + l];
   const int t = threadIdx.x;
   const int w = t >> 6, i = t & 63;
   if (HIST) {
@@ -327,7 +328,7 @@ __global__ void __launch_bounds__(kThreads) k_sumsq(Dev a) {
       }
     }
     const double total = (KIND == kNormLinf) ? block_max((double)magnitude_from_bits(mb), red) : block_tree(acc, red);
-    if (t == 0) a.partial[(size_t)k * a.G + m.first_chunk + chunk] = total;
+    if (t == 0) a.partial[(size_t)kr * a.G + m.first_chunk + chunk] = total;
   }
   if (HIST) {
     __syncthreads();
@@ -344,7 +345,7 @@ __global__ void __launch_bounds__(kThreads) k_sumsq(Dev a) {
 __global__ void __launch_bounds__(kThreads) k_norm_finalize(Dev a) {
   __shared__ double red[kThreads];
   const int l = blockIdx.x;
-  const int k = a.node0 + blockIdx.y;
+  const int k = a.node0 + blockIdx.y - a.row0;   // row in the per-node scratch tables
   const LayerMeta m = a.meta[l];
   const double *p = a.partial + (size_t)k * a.G + m.first_chunk;
   double acc = 0.0;
@@ -373,7 +374,7 @@ __global__ void __launch_bounds__(kThreads) k_norm_finalize(Dev a) {
 __global__ void __launch_bounds__(kThreads) k_norm_vector(Dev a) {
   __shared__ double red[kThreads];
   __shared__ double tot[1];
-  const int k = a.node0 + blockIdx.x;
+  const int k = a.node0 + blockIdx.x - a.row0;   // row in the per-node scratch tables
   double acc = 0.0;
   double s;
   if (a.kind == kNormLinf) {
@@ -514,11 +515,12 @@ __device__ __forceinline__ void quantize_tile(const Dev &a, const LayerMeta &m, 
   const int t = threadIdx.x;
   const int w = __builtin_amdgcn_readfirstlane(t >> 6);
   const int i = t & 63;
-  const float *__restrict__ v = a.grad[(size_t)k * a.L + l];
-  unsigned char *body = a.msg[k] + m.body_off;
-  const unsigned char *prevbody = (a.prev != nullptr && a.prev[k] != nullptr) ? a.prev[k] + m.body_off : nullptr;
-  const float inv = a.inv[(size_t)k * a.L + l];
-  const float norm = a.norm[(size_t)k * a.L + l];
+  const int kr = k - a.row0;   // row of this node in the per-node scratch and pointer tables
+  const float *__restrict__ v = a.grad[(size_t)kr * a.L + l];
+  unsigned char *body = a.msg[kr] + m.body_off;
+  const unsigned char *prevbody = (a.prev != nullptr && a.prev[kr] != nullptr) ? a.prev[kr] + m.body_off : nullptr;
+  const float inv = a.inv[(size_t)kr * a.L + l];
+  const float norm = a.norm[(size_t)kr * a.L + l];
   const long long noct = (m.nblk + 7) >> 3;
   float acc = 0.0f;   // this slot's squared differences: an fp32 fused multiply-add chain in increasing coordinate
   for (int oo = 0; oo < 2; ++oo) {
@@ -530,7 +532,7 @@ __device__ __forceinline__ void quantize_tile(const Dev &a, const LayerMeta &m, 
       quantize_octet<C1, false, PREV>(a, m, l, k, O, v, body, prevbody, inv, norm, lut, tab, tprev, i, acc);
   }
   const double total = block_tree((double)acc, red);
-  if (t == 0) a.dpartial[(size_t)k * a.G + blockIdx.x] = total;
+  if (t == 0) a.dpartial[(size_t)kr * a.G + blockIdx.x] = total;
 }
 
 template <int C1, bool PREV>
@@ -548,15 +550,16 @@ __global__ void __launch_bounds__(kThreads) k_quantize(Dev a) {
   const float *lev = a.lev + (size_t)m.type * kMaxPoints;
   const float *rg = a.rgap + (size_t)m.type * kMaxPoints;
   reinterpret_cast<unsigned int *>(lut)[t] = reinterpret_cast<const unsigned int *>(a.lut + (size_t)m.type * kLutSize)[t];
-  const float norm = a.norm[(size_t)k * a.L + l];
-  const unsigned char *prevmsg = (a.prev != nullptr) ? a.prev[k] : nullptr;
+  const int kr = k - a.row0;
+  const float norm = a.norm[(size_t)kr * a.L + l];
+  const unsigned char *prevmsg = (a.prev != nullptr) ? a.prev[kr] : nullptr;
   if (t < m.S) {
     const float lj = lev[t];
     const float ln = (t + 1 < m.S) ? lev[t + 1] : __builtin_inff();   // the last entry stops every walk
     tab[t] = make_float4(lj, (t + 1 < m.S) ? rg[t] : 0.0f, ln, 0.0f);
   }
   if (tile.y == 0) {   // message header of this layer: {norm, levels[S]} (Sec. 3.2: the norm in C_q = 32 bits)
-    float *h = reinterpret_cast<float *>(a.msg[k] + m.hdr_off);
+    float *h = reinterpret_cast<float *>(a.msg[kr] + m.hdr_off);
     for (int j = t; j <= m.S; j += kThreads) h[j] = (j == 0) ? norm : lev[j - 1];
   }
   for (int c = t; c < (1 << m.planes); c += kThreads) {   // codes past S-1 decode as the last level
@@ -800,7 +803,8 @@ __global__ void __launch_bounds__(kThreads) k_quantize_b(Dev a) {
   const float *lev = a.lev + (size_t)m.type * kMaxPoints;
   const float *rg = a.rgap + (size_t)m.type * kMaxPoints;
   reinterpret_cast<unsigned int *>(lut)[t] = reinterpret_cast<const unsigned int *>(a.lut + (size_t)m.type * kLutSize)[t];
-  const unsigned char *prevmsg = (a.prev != nullptr) ? a.prev[k] : nullptr;
+  const int kr = k - a.row0;   // row in the pointer tables and in the per-tile scratch; the fit statistics use k
+  const unsigned char *prevmsg = (a.prev != nullptr) ? a.prev[kr] : nullptr;
   const int ex = a.type_exp[m.type];
   if (t < m.S) {
     const float lj = lev[t];
@@ -808,7 +812,7 @@ __global__ void __launch_bounds__(kThreads) k_quantize_b(Dev a) {
     tab[t] = make_float4(lj, (t + 1 < m.S) ? rg[t] : 0.0f, ln, 0.0f);
   }
   if (st.y == 0) {   // header of this layer: the norm entry is unused under bucket scope
-    float *h = reinterpret_cast<float *>(a.msg[k] + m.hdr_off);
+    float *h = reinterpret_cast<float *>(a.msg[kr] + m.hdr_off);
     for (int j = t; j <= m.S; j += kThreads) h[j] = (j == 0) ? 0.0f : lev[j - 1];
   }
   for (int c = t; c < (1 << m.planes); c += kThreads) {
@@ -824,8 +828,8 @@ __global__ void __launch_bounds__(kThreads) k_quantize_b(Dev a) {
   __syncthreads();
   const int w = __builtin_amdgcn_readfirstlane(t >> 6);
   const int i = t & 63;
-  const float *__restrict__ v = a.grad[(size_t)k * a.L + l];
-  unsigned char *body = a.msg[k] + m.body_off;
+  const float *__restrict__ v = a.grad[(size_t)kr * a.L + l];
+  unsigned char *body = a.msg[kr] + m.body_off;
   const unsigned char *prevbody = prevmsg ? prevmsg + m.body_off : nullptr;
   const long long noct = (m.nblk + 7) >> 3;
   unsigned long long best = 0ull;
@@ -841,7 +845,7 @@ __global__ void __launch_bounds__(kThreads) k_quantize_b(Dev a) {
         quantize_octet_b<C1, false, PREV, KIND>(a, m, l, k, O, v, body, prevbody, lut, tab, tprev, bws[w], i, acc, ex, best, lh);
     }
     const double total = block_tree((double)acc, red);
-    if (t == 0) a.dpartial[(size_t)k * a.G + m.first_chunk + chunk] = total;
+    if (t == 0) a.dpartial[(size_t)kr * a.G + m.first_chunk + chunk] = total;
   }
   // statistics of the run: largest sampled bucket sum (bit pattern of a non-negative double) and the histogram
 #pragma unroll
@@ -869,7 +873,8 @@ __global__ void __launch_bounds__(kThreads) k_quantize_b(Dev a) {
 __global__ void __launch_bounds__(kThreads) k_delta_finalize(Dev a) {
   __shared__ double red[kThreads];
   const int k = a.node0 + blockIdx.x;
-  const double *p = a.dpartial + (size_t)k * a.G;
+  const int kr = k - a.row0;   // row in the per-node scratch and pointer tables
+  const double *p = a.dpartial + (size_t)kr * a.G;
   double acc = 0.0;
   for (int g = threadIdx.x; g < a.G; g += kThreads) acc = acc + p[g];
   const double s = block_tree(acc, red);
@@ -877,9 +882,9 @@ __global__ void __launch_bounds__(kThreads) k_delta_finalize(Dev a) {
   // layers without coordinates have no tile: their header entries (norm 0, levels) are written here
   for (int q = 0; q < a.n_empty; ++q) {
     const LayerMeta m = a.meta[a.empty_layers[q]];
-    float *h = reinterpret_cast<float *>(a.msg[k] + m.hdr_off);
+    float *h = reinterpret_cast<float *>(a.msg[kr] + m.hdr_off);
     const float *lev = a.lev + (size_t)m.type * kMaxPoints;
-    const float n0 = (a.scope == kScopeBucket) ? 0.0f : a.norm[(size_t)k * a.L + a.empty_layers[q]];
+    const float n0 = (a.scope == kScopeBucket) ? 0.0f : a.norm[(size_t)kr * a.L + a.empty_layers[q]];
     for (int j = threadIdx.x; j <= m.S; j += kThreads) h[j] = (j == 0) ? n0 : lev[j - 1];
   }
 }
@@ -1459,7 +1464,27 @@ __global__ void __launch_bounds__(kThreads) k_copy_f4(const float4 *__restrict__
   for (; i < n; i += stride) dst[i] = src[i];
 }
 
+// ------------------------------------------------------------------------------------------------ pointer staging
+// Up to kPackPointers pointers travel as kernel arguments and are written to a device table by the kernel itself.
+constexpr int kPackPointers = 128;
+struct PointerPack { void *p[kPackPointers]; };
+
+__global__ void __launch_bounds__(kPackPointers) k_stage_pointers(void **dst, PointerPack pack, int n) {
+  const int t = threadIdx.x;
+  if (t < n) dst[t] = pack.p[t];
+}
+
 // ------------------------------------------------------------------------------------------------ launchers
+hipError_t launch_stage_pointers(void **dst_dev, const void *const *src_host, size_t n, hipStream_t s) {
+  for (size_t q = 0; q < n; q += kPackPointers) {
+    PointerPack pack;
+    const int m = (int)(n - q < (size_t)kPackPointers ? n - q : (size_t)kPackPointers);
+    for (int j = 0; j < kPackPointers; ++j) pack.p[j] = j < m ? const_cast<void *>(src_host[q + j]) : nullptr;
+    hipLaunchKernelGGL(k_stage_pointers, dim3(1), dim3(kPackPointers), 0, s, dst_dev + q, pack, m);
+  }
+  return hipGetLastError();
+}
+
 hipError_t launch_copy(const void *src, void *dst, size_t bytes, hipStream_t s) {
   const size_t n = bytes / 16;
   if (n == 0) return hipSuccess;

@@ -73,6 +73,7 @@ def load():
     L.qoda_get_levels.argtypes = [vp, C.c_int32, C.POINTER(C.c_float), vp]
     L.qoda_fit_levels.argtypes = [vp, pp, C.c_uint32, vp]
     L.qoda_quantize.argtypes = [vp, C.c_int32, pp, C.c_uint32, vp, vp, vp]
+    L.qoda_quantize_noalloc.argtypes = [vp, C.c_int32, pp, C.c_uint32, vp, vp, vp]
     L.qoda_quantize_all.argtypes = [vp, pp, C.c_uint32, pp, pp, vp]
     L.qoda_dequant_aggregate.argtypes = [vp, pp, pp, vp]
     L.qoda_step.argtypes = [vp, pp, C.POINTER(_State), vp]
@@ -91,7 +92,7 @@ def load():
     L.qoda_last_error.argtypes = [vp]
     L.qoda_last_error.restype = C.c_char_p
     for name in ("qoda_create", "qoda_destroy", "qoda_message_layout", "qoda_set_levels", "qoda_get_levels",
-                 "qoda_fit_levels", "qoda_quantize", "qoda_quantize_all", "qoda_dequant_aggregate", "qoda_step", "qoda_step_alt",
+                 "qoda_fit_levels", "qoda_quantize", "qoda_quantize_noalloc", "qoda_quantize_all", "qoda_dequant_aggregate", "qoda_step", "qoda_step_alt",
                  "qoda_step_rates", "qoda_extrapolate", "qoda_index_counts", "qoda_code_length",
                  "qoda_read_buffer", "qoda_status", "qoda_profile_enable", "qoda_profile_read", "qoda_copy_calibration"):
         getattr(L, name).restype = C.c_int
@@ -202,6 +203,12 @@ class Context:
         assert len(grads) == self.L
         self._check(self._lib.qoda_quantize(self._h, node, _ptrs(grads), round_, _addr(msg), _addr(msg_prev),
                                             _stream(stream)))
+
+    def quantize_noalloc(self, node: int, grads: Sequence, round_: int, msg, msg_prev=None, stream=None):
+        """quantize() for callers that cannot allocate: the kernels' scratch is the library's static device array."""
+        assert len(grads) == self.L
+        self._check(self._lib.qoda_quantize_noalloc(self._h, node, _ptrs(grads), round_, _addr(msg), _addr(msg_prev),
+                                                    _stream(stream)))
 
     def quantize_all(self, grads: Sequence, round_: int, msgs: Sequence, msgs_prev: Optional[Sequence] = None,
                      stream=None):
