@@ -20,9 +20,12 @@
  *     been used, the calls of a round enqueue kernels (and, for the statistics-based fit, one device-to-device copy)
  *     only: no upload, no wait.  Such a steady-state round can be captured into a HIP graph; pointers and the round
  *     number are then fixed in the captured launches.  The calls that wait (see above) cannot be captured.
- *   - Non-finite input (a layer whose sum of squares is not a finite number or whose norm exceeds FLT_MAX) sets
- *     a sticky device-side flag reported by qoda_status(); that layer's output is then unspecified (but in
- *     bounds).
+ *   - Non-finite input (a vector -- layer, whole dual vector or bucket, by scope -- whose sum of squares is not a
+ *     finite number or whose norm exceeds FLT_MAX) sets a sticky device-side flag reported by qoda_status(); that
+ *     vector's output is then unspecified (but in bounds).  A second flag marks a vector whose norm is positive but
+ *     below 2^-126 (the smallest normal float): 1/norm is then not a float, the normalised magnitudes fall short of
+ *     |v| / norm and the quantizer of that vector is biased -- the one case in which E[Q(v)] = v (Thm 5.1) does not
+ *     hold to rounding.
  *
  * Level sequences (Sec. 3.1): type m has S_m grid points 0 = l_0 < l_1 < ... < l_{S_m-1} = 1, i.e. the paper's
  * alpha_m = S_m - 2 interior levels.  A coordinate's code is one sign bit plus a ceil(log2 S_m)-bit level index.
@@ -50,7 +53,8 @@ extern "C" {
 #define QODA_EINVAL (-1)    /* bad argument (null, misaligned, out of range, levels not increasing, ...) */
 #define QODA_ENOMEM (-2)    /* device or host allocation failed */
 #define QODA_EHIP (-3)      /* a HIP runtime call failed; see qoda_last_error() */
-#define QODA_ENONFINITE (-4) /* returned by qoda_status() when the device flag is set */
+#define QODA_ENONFINITE (-4) /* returned by qoda_status(): some vector's norm statistic was not a finite number */
+#define QODA_ETINYNORM (-5)  /* returned by qoda_status(): some vector's norm was positive but below 2^-126 */
 
 #define QODA_MAX_POINTS 256 /* S_m <= 256: level index fits 8 bits */
 
@@ -63,9 +67,9 @@ extern "C" {
  *           gradient is read once).  The 256*(1+b) code bytes of every octet are followed by the octet's 16 bucket
  *           norms (fp32; the bucket of block bb = 0..7, half hf = 0..1 of the octet at position 8*hf + bb), so an
  *           octet takes 256*(1+b) + 64 bytes; the header's norm entry is 0 and unused.  A bucket's sum of squares is
- *           accumulated in single precision: entries below about 4e-23 in magnitude add nothing to it (a bucket made
- *           of such entries only has norm 0 and decodes to zeros), and a bucket with an entry above about 1.8e19 is
- *           "not finite" (flagged as in the conventions above). */
+ *           accumulated in single precision inside a lane (relative error below 3e-7); when that result is below 2^-100
+ *           or not finite -- squares may have vanished or overflowed -- the bucket is summed again with exact fp64
+ *           squares, so buckets of very small or very large entries are normalised as exactly as layers are. */
 #define QODA_SCOPE_LAYER 0
 #define QODA_SCOPE_VECTOR 1
 #define QODA_SCOPE_BUCKET 2
@@ -115,19 +119,17 @@ int qoda_get_levels(qoda_ctx *ctx, int32_t type, float *levels_host, void *strea
 
 /* Level fit, Alg. 1 lines 2-7 / eq. (Qada2) with the weights lambda_z: the K nodes' current vectors are the Z
  * samples; every coordinate of (node, layer) weighs ||v_{k,l}||^2; layers of one type pool.  The distribution is
- * estimated by a histogram on the top 11 magnitude bits of a fixed quarter of the entries (256-coordinate blocks
- * 0, 4, 8, ... of each layer) and the objective is minimised exactly
+ * estimated by a histogram of every entry on its top 11 magnitude bits and the objective is minimised exactly
  * over level positions on a 257-point grid (3 mantissa bits per octave down to 2^-32).  A type whose vectors are
  * all zero keeps its levels.  grad_dev: host array [K*L], entry k*L+l.
  * Side effect: the per-(node, layer) norms of these vectors stay in the context tagged with `round`; a following
  * qoda_quantize / qoda_quantize_all with the same `round` and the same pointers reuses them instead of reading
  * the vectors a second time.  The caller must not change the vectors in between.
  * Bucket scope: every bucket is a vector of its own (weight = its sum of squares, normalisation = its norm); with
- * grad_dev the fit takes two passes over the sampled quarter of these vectors (scale of the weights, then the weighted
- * grid histogram).  With grad_dev == NULL (bucket scope only) it reads nothing: it uses the statistics that the last
+ * grad_dev the fit takes two passes over these vectors (scale of the weights, then the weighted grid histogram).  With grad_dev == NULL (bucket scope only) it reads nothing: it uses the statistics that the last
  * quantize pass of every node gathered while it quantized -- Alg. 1 runs lines 3-5 before the round's vectors exist,
  * so the estimate comes from the previous round's vectors -- and hands the next pass its weight scale (exponent of the
- * largest sampled bucket sum per type; weights are floor(sum * 2^(23 - exponent)) capped at 2^30).  A pass gathers a
+ * largest bucket sum per type; weights are floor(sum * 2^(23 - exponent)) capped at 2^30).  A pass gathers a
  * histogram only once some fit has produced a scale: call the fit with vectors once (or with NULL twice, the first of
  * which only sets the scale), then with NULL at every later update step. */
 int qoda_fit_levels(qoda_ctx *ctx, const float *const *grad_dev, uint32_t round, void *stream);
@@ -244,7 +246,7 @@ int qoda_code_length(qoda_ctx *ctx, const uint64_t *counts, uint32_t num_message
 
 /* Read an internal device buffer into host memory (waits for `stream`); for tests and diagnostics. */
 #define QODA_BUF_SUMSQ 0  /* double[K*L]  per-layer statistic of the last norm pass (sum of squares; L1: sum of
-                              magnitudes; LINF: largest magnitude); bucket scope: largest sampled bucket's */
+                              magnitudes; LINF: largest magnitude); bucket scope: largest bucket's */
 #define QODA_BUF_NORM 1   /* float [K*L]  norms                                                            */
 #define QODA_BUF_INV 2    /* float [K*L]  reciprocal norms                                                 */
 #define QODA_BUF_DELTA 3  /* double[K]    delta_k of the last quantize of each node                        */
@@ -252,8 +254,8 @@ int qoda_code_length(qoda_ctx *ctx, const uint64_t *counts, uint32_t num_message
 #define QODA_BUF_POOLED 5 /* uint64[M*257] pooled grid weights of the last fit                             */
 int qoda_read_buffer(qoda_ctx *ctx, int32_t which, void *dst_host, size_t bytes, void *stream);
 
-/* Waits for `stream`; returns QODA_OK, or QODA_ENONFINITE if a non-finite layer was seen since the last call
- * (the flag is cleared). */
+/* Waits for `stream`; returns QODA_OK, or QODA_ENONFINITE if a non-finite vector was seen since the last call, or
+ * QODA_ETINYNORM if only vectors with a norm below 2^-126 were (both flags are cleared). */
 int qoda_status(qoda_ctx *ctx, void *stream);
 
 /* Measurement aids (no part of the method).

@@ -112,6 +112,14 @@ def lib():
         L.oracle_fit_levels.restype = C.c_int32
         L.oracle_fit_from_stats.argtypes = [C.c_int32, i32p, C.c_int32, i32p, C.c_int32, u64p, dp, i32p, pp, u64p, C.c_int32]
         L.oracle_fit_from_stats.restype = C.c_int32
+        L.oracle_delta_plain.argtypes = [C.c_int32, i64p, i32p, C.c_int32, u8p, u8p]
+        L.oracle_delta_plain.restype = C.c_double
+        L.oracle_sumsq_plain.argtypes = [fp, C.c_int64]
+        L.oracle_sumsq_plain.restype = C.c_double
+        L.oracle_variance_plain.argtypes = [fp, C.c_int64, fp, C.c_int32, C.c_int32]
+        L.oracle_variance_plain.restype = C.c_double
+        L.oracle_mqv_objective_plain.argtypes = [C.c_int32, i64p, i32p, i32p, C.c_int32, C.c_int32, pp, pp, C.c_int32]
+        L.oracle_mqv_objective_plain.restype = C.c_double
         L.oracle_norm_stat.argtypes = [fp, C.c_int64, C.c_int32]
         L.oracle_norm_stat.restype = C.c_double
         L.oracle_bucket_stat.argtypes = [fp, C.c_int64, C.c_int32]
@@ -487,6 +495,40 @@ def fit_from_stats(layer_type, type_points, K: int, hist, bmax, exps, levels: Se
     st = lib().oracle_fit_from_stats(L, _p(lt, C.c_int32), M, _p(tp, C.c_int32), K, _p(h, C.c_uint64), _p(b, C.c_double),
                                      _p(ex, C.c_int32), _ptr_array(lev), _p(pooled, C.c_uint64), norm_kind)
     return lev, pooled.reshape(M, GRID_POINTS), ex, int(st)
+
+
+# ------------------------------------------------------------------ plain definitions (references, no contract)
+def delta_plain(sizes, points, msg, msg_prev=None, scope: int = SCOPE_LAYER) -> float:
+    """sum_i (Vhat_i - Vhat_prev_i)^2 of two stored messages in fp64, plain order (eq. (general_stepsize))."""
+    d, S = _dims(sizes, points)
+    m = np.ascontiguousarray(msg, dtype=np.uint8)
+    p = None if msg_prev is None else np.ascontiguousarray(msg_prev, dtype=np.uint8)
+    return float(lib().oracle_delta_plain(d.size, _p(d, C.c_int64), _p(S, C.c_int32), scope, _p(m, C.c_uint8),
+                                          None if p is None else _p(p, C.c_uint8)))
+
+
+def sumsq_plain(v) -> float:
+    v = _f32(v)
+    return float(lib().oracle_sumsq_plain(_p(v, C.c_float), v.size))
+
+
+def variance_plain(v, levels, norm_kind: int = NORM_L2) -> float:
+    """eq. (Var) for one vector and one level sequence, from the definition in fp64."""
+    v, lev = _f32(v), _f32(levels)
+    return float(lib().oracle_variance_plain(_p(v, C.c_float), v.size, _p(lev, C.c_float), lev.size, norm_kind))
+
+
+def mqv_objective_plain(sizes, layer_type, type_points, K: int, grads: Sequence[np.ndarray],
+                        levels: Sequence[np.ndarray], scope: int = SCOPE_LAYER, norm_kind: int = NORM_L2) -> float:
+    """eq. (MQV): total quantization variance of the K nodes' vectors (grads: K*L arrays) under per-type levels."""
+    d = np.ascontiguousarray(sizes, dtype=np.int64)
+    lt = np.ascontiguousarray(layer_type, dtype=np.int32)
+    tp = np.ascontiguousarray(type_points, dtype=np.int32)
+    g = [_f32(a) for a in grads]
+    lev = [_f32(a) for a in levels]
+    assert len(g) == K * d.size and len(lev) == tp.size
+    return float(lib().oracle_mqv_objective_plain(d.size, _p(d, C.c_int64), _p(lt, C.c_int32), _p(tp, C.c_int32), K, scope,
+                                                  _ptr_array(g), _ptr_array(lev), norm_kind))
 
 
 def grid_values() -> np.ndarray:

@@ -30,6 +30,9 @@
 // optimiser itself to third-party code it does not describe, so optimality relative to that code is
 // "parity unpinned".
 //
+// Where the contract below is narrower than the textbook definition (step-size term, bucket sums, the histogram of
+// the fit) the plain definition is at the end of this file, and the tests bound one against the other.
+//
 // Arithmetic contract (the GPU library follows the same written contract independently):
 //   fp32 operations are single IEEE operations, never fused; sums that feed integer decisions are
 //   taken in fp64 in a fixed "slot + halving tree" order; square roots and reciprocals that feed
@@ -339,25 +342,37 @@ inline float *bucket_norm_slot(uint8_t *layer_base, int planes, int64_t ostride,
 }
 
 // Sum of squares of one bucket (n <= 128 coordinates, missing ones count as 0): "lane" i = (e mod 128)/4 adds the
-// squares of its four consecutive coordinates in order with an fp32 fused chain (acc = fma(x, x, acc) from 0), the 32
-// lane sums are widened to fp64 and combined by the in-order binary tree (lanes 0+1, 2+3, ...; then pairs of those; ...).
-// Single precision inside a lane is what a bucket norm needs (relative error about 1e-7) and what keeps the pass that
-// computes it cheap; squares below the fp32 range vanish and squares above it overflow (then the bucket is reported
-// as not finite), unlike the per-layer sums, which are exact in fp64.
-double bucket_sumsq(const float *v, int64_t n) {
+// squares of its four consecutive coordinates in order, the 32 lane sums are combined in fp64 by the in-order binary
+// tree (lanes 0+1, 2+3, ...; then pairs of those; ...).  A lane first works in single precision (fused chain
+// acc = fma(x, x, acc) from 0, then widened): relative error about 1e-7, which is all a bucket norm needs.  Single
+// precision loses squares below 2^-149 and overflows above 2^128, and a norm that is too small makes u = |v|/norm
+// exceed 1, which the clamp would turn into a bias (Thm 5.1 needs u <= 1 unclamped).  So whenever the single-precision
+// result is below 2^-100 (zero included) or not a finite number, the lanes redo their chains in fp64, where every
+// square is exact: acc = fma((double)x, (double)x, acc); same tree.
+double bucket_sumsq_lanes(const float *v, int64_t n, bool exact) {
   double p[32];
   for (int i = 0; i < 32; ++i) {
-    float acc = 0.0f;
+    float acc32 = 0.0f;
+    double acc64 = 0.0;
     for (int j = 0; j < 4; ++j) {
       const int64_t e = 4 * i + j;
       const float x = (e < n) ? v[e] : 0.0f;
-      acc = std::fmaf(x, x, acc);
+      if (exact) acc64 = std::fma((double)x, (double)x, acc64);
+      else acc32 = std::fmaf(x, x, acc32);
     }
-    p[i] = (double)acc;
+    p[i] = exact ? acc64 : (double)acc32;
   }
   for (int w = 1; w < 32; w *= 2)
     for (int i = 0; i < 32; i += 2 * w) p[i] = p[i] + p[i + w];
   return p[0];
+}
+
+constexpr double kBucketRescueBelow = 7.888609052210118e-31;   // 2^-100
+
+double bucket_sumsq(const float *v, int64_t n) {
+  const double s = bucket_sumsq_lanes(v, n, false);
+  const bool trusted = (s >= kBucketRescueBelow) && (s <= std::numeric_limits<double>::max());
+  return trusted ? s : bucket_sumsq_lanes(v, n, true);
 }
 
 // The other kinds over a bucket, lane by lane as above: a lane adds its four magnitudes in order in fp32 from 0 (the
@@ -486,6 +501,11 @@ double oracle_weight_of(double s, int32_t kind) { return weight_of(s, kind); }
 namespace {
 constexpr int32_t kTypeSkip = 0x7fffffff;   // "this type has no weight scale": nothing is gathered / fitted for it
 
+// Status bits returned by the routines below.
+constexpr int32_t kStatusNonFinite = 1;   // a statistic is not a finite number in range: its vector's output is unspecified
+constexpr int32_t kStatusTinyNorm = 2;    // 0 < norm < 2^-126: 1/norm is not a float, so u = |v| * inv falls short of
+                                          // |v| / norm and E[Q(v)] = v (Thm 5.1) no longer holds for that vector
+
 // integer weight of a bucket with sum of squares s under the scale 2^ex: floor(s * 2^(23 - ex)), capped at 2^30 (a
 // scale taken from the previous round can be exceeded; the cap keeps every 64-bit total far from overflow)
 inline uint64_t stat_weight(double s, int ex) {
@@ -493,141 +513,45 @@ inline uint64_t stat_weight(double s, int ex) {
   return (uint64_t)std::fmin(w, 1073741824.0);
 }
 
-
 // the norm DECODE uses for coordinate e of layer l: the header's (layer and vector scope) or the bucket's
 inline float stored_norm(const uint8_t *msg, const Layout &lay, int l, int64_t e) {
   if (lay.scope != kScopeBucket) return header_of(msg, lay, l).norm;
   return *bucket_norm_slot(const_cast<uint8_t *>(msg) + lay.msg_off[l], lay.planes[l], lay.ostride[l], e);
 }
-}  // namespace
 
-// ---------------------------------------------------------------- ENCODE(Q(V_k)) for one node: Alg. 1 line 12
-// grads[l]  : layer l of the node's dual vector.      levels[l] : the S[l] levels of layer l's type.
-// msg       : message_bytes output.                    msg_prev  : previous-round message of this node or NULL.
-// scope     : what one norm covers.  Layer: the layer's canonical sum of squares.  Vector: the canonical
-//             combination of the L layer sums (slot j takes layers j, j+256, ...; then the tree), used by every
-//             layer.  Bucket: every 128 consecutive coordinates of a layer (bucket_sumsq); the norms travel in the body.
-// sumsq_out : L sums of squares (may be NULL): the layer's; under vector scope the whole vector's in every entry;
-//             under bucket scope the largest bucket sum of the layer.
-// delta_out : || Vhat_{k,t+1/2} - Vhat_{k,t-1/2} ||^2 (the step-size term of eq. (general_stepsize)); prev = 0 if NULL.
-// returns 0, or 1 if a sum of squares is not finite or a norm exceeds the largest float.
-// Bucket scope can also gather the level fit's statistics while it quantizes (Alg. 1 runs lines 3-5 before the round's
-// vectors exist, so the estimate can only come from earlier vectors: those of the previous round, seen by the pass
-// that quantized them).  layer_exp[l] (NULL: gather nothing) is the weight scale of layer l's type, kTypeSkip for
-// "no scale yet"; stats_hist (L*257, added to) receives floor(sumsq_b * 2^(23 - exp)), capped at 2^30, at the grid
-// bin of every sampled coordinate as in oracle_fit_levels; stats_max (L, maximised) the largest sampled bucket sum,
-// +infinity if one is not finite.
-int32_t oracle_quantize(int32_t L, const int64_t *d, const int32_t *S, const float *const *levels,
-                        const float *const *grads, uint64_t seed, uint32_t round, uint32_t node, int32_t scope,
-                        uint8_t *msg, const uint8_t *msg_prev, double *sumsq_out, double *delta_out,
-                        const int32_t *layer_exp, uint64_t *stats_hist, double *stats_max, int32_t norm_kind) {
-  const Layout lay = make_layout(L, d, S, scope);
-  std::memset(msg, 0, (size_t)lay.message_bytes);
-  int32_t status = 0;
-  std::vector<double> layer_sums(L, 0.0);
-  if (scope != kScopeBucket) {
-    for (int l = 0; l < L; ++l) layer_sums[l] = layer_stat(grads[l], d[l], norm_kind);
-    if (scope == kScopeVector) {
-      const double total = combine_stats(layer_sums, norm_kind);
-      for (int l = 0; l < L; ++l) layer_sums[l] = total;
-    }
-  }
-  std::vector<double> delta_chunks;
-  for (int l = 0; l < L; ++l) {
-    float norm = 0.0f, inv = 0.0f;
-    if (scope != kScopeBucket) {
-      const double s = layer_sums[l];
-      if (sumsq_out) sumsq_out[l] = s;
-      const bool finite = stat_finite(s, norm_kind);
-      if (!finite) status = 1;
-      norm = finite ? norm_of(s, norm_kind) : 0.0f;
-      inv = rcp_floor(norm);
-    } else if (sumsq_out) {
-      sumsq_out[l] = 0.0;
-    }
-    float *hdr = reinterpret_cast<float *>(msg + lay.hdr_off[l]);
-    hdr[0] = norm;   // bucket scope: unused, 0
-    for (int j = 0; j < S[l]; ++j) hdr[1 + j] = levels[l][j];
-    uint8_t *region = msg + lay.msg_off[l];
-    const int64_t nchunks = (d[l] + kChunk - 1) / kChunk;
-    for (int64_t c = 0; c < nchunks; ++c) {
-      // a slot's (at most 64) squared differences are accumulated in fp32 with a fused multiply-add, in
-      // increasing coordinate; the 256 slot sums are then combined in fp64
-      float p32[kSlots];
-      for (int j = 0; j < kSlots; ++j) p32[j] = 0.0f;
-      const int64_t e1 = std::min(d[l], (c + 1) * kChunk);   // padding coordinates carry code 0 and add nothing
-      for (int64_t e = c * kChunk; e < e1; ++e) {
-        if (scope == kScopeBucket && e % kBucket == 0) {
-          const double s = bucket_stat(grads[l] + e, std::min<int64_t>(kBucket, d[l] - e), norm_kind);
-          const bool finite = stat_finite(s, norm_kind);
-          if (!finite) status = 1;
-          norm = finite ? norm_of(s, norm_kind) : 0.0f;
-          inv = rcp_floor(norm);
-          *bucket_norm_slot(region, lay.planes[l], lay.ostride[l], e) = norm;
-          if (sumsq_out && finite && s > sumsq_out[l]) sumsq_out[l] = s;
-          if (layer_exp && ((e / kBlock) % 4) == 0) {
-            const double sm = finite ? s : std::numeric_limits<double>::infinity();
-            if (sm > stats_max[l]) stats_max[l] = sm;
-            const uint64_t wfix =
-                (layer_exp[l] == kTypeSkip || !finite) ? 0 : stat_weight(weight_of(s, norm_kind), layer_exp[l]);
-            if (wfix != 0 && inv != 0.0f) {
-              const int64_t n = std::min<int64_t>(kBucket, d[l] - e);
-              for (int64_t q = e; q < e + n; ++q) {
-                if (((f2u(grads[l][q]) & 0x7FFFFFFFu) >> 20) == 0) continue;
-                const float uc = std::fmin(std::fabs(grads[l][q]) * inv, 1.0f);
-                int j = (int)(f2u(uc) >> 20) - kGridBase;
-                if (j < 0) j = 0;
-                if (j > kGridPoints - 1) j = kGridPoints - 1;
-                stats_hist[(size_t)l * kGridPoints + j] += wfix;
-              }
-            }
-          }
-        }
-        const Code code =
-            quantize_coord(grads[l][e], inv, levels[l], S[l], draw16(seed, round, node, (uint32_t)l, (uint64_t)e));
-        put_code(region, lay.planes[l], lay.ostride[l], e, code);
-        const float cur = decode_value(code.sign, code.h, norm, levels[l], S[l]);
-        float prev = 0.0f;
-        if (msg_prev) {
-          const HeaderView hp = header_of(msg_prev, lay, l);
-          const Code pc = get_code(msg_prev + lay.msg_off[l], lay.planes[l], lay.ostride[l], e);
-          prev = decode_value(pc.sign, pc.h, stored_norm(msg_prev, lay, l, e), hp.lev, S[l]);
-        }
-        const float diff = cur - prev;
-        p32[slot_of(e)] = std::fmaf(diff, diff, p32[slot_of(e)]);
-      }
-      double p[kSlots];
-      for (int j = 0; j < kSlots; ++j) p[j] = (double)p32[j];
-      delta_chunks.push_back(halving_tree(p));
-    }
-  }
-  if (delta_out) *delta_out = combine_chunks(delta_chunks);
-  return status;
+// DECODE of coordinate e of layer l of a stored message (Sec. 3.2): +-norm * level, with the message's own levels
+inline float decoded_value(const uint8_t *msg, const Layout &lay, int l, int64_t e) {
+  const HeaderView h = header_of(msg, lay, l);
+  const Code c = get_code(msg + lay.msg_off[l], lay.planes[l], lay.ostride[l], e);
+  return decode_value(c.sign, c.h, stored_norm(msg, lay, l, e), h.lev, lay.S[l]);
 }
 
-// ---------------------------------------------------------------- step-size term from two stored messages
-// || DECODE(msg) - DECODE(msg_prev) ||^2 in the same order as oracle_quantize accumulates it (msg_prev NULL: zeros).
-// Lets a test check delta_k of a full-size model without quantizing it on the CPU.
-double oracle_delta_from_messages(int32_t L, const int64_t *d, const int32_t *S, int32_t scope, const uint8_t *msg,
-                                  const uint8_t *msg_prev) {
-  const Layout lay = make_layout(L, d, S, scope);
+// Norm and reciprocal from a statistic (Sec. 2.2); raises the status bits above.
+struct NormPair { float norm, inv; };
+inline NormPair norm_pair(double stat, int kind, int32_t *status) {
+  const bool finite = stat_finite(stat, kind);
+  if (!finite) *status |= kStatusNonFinite;
+  NormPair n;
+  n.norm = finite ? norm_of(stat, kind) : 0.0f;
+  n.inv = rcp_floor(n.norm);
+  if (n.norm > 0.0f && n.norm < std::numeric_limits<float>::min()) *status |= kStatusTinyNorm;
+  return n;
+}
+
+// || DECODE(msg) - DECODE(msg_prev) ||^2 (eq. (general_stepsize); msg_prev NULL: zeros) in the contract's order: per
+// slot an fp32 fused chain over its coordinates of a chunk in increasing order, the 256 slots widened to fp64 and
+// reduced by the tree, chunks numbered through all layers and combined like chunk sums.
+double delta_between(const Layout &lay, const uint8_t *msg, const uint8_t *msg_prev) {
   std::vector<double> delta_chunks;
-  for (int l = 0; l < L; ++l) {
-    const HeaderView hc = header_of(msg, lay, l);
-    const int64_t nchunks = (d[l] + kChunk - 1) / kChunk;
+  for (int l = 0; l < lay.L; ++l) {
+    const int64_t nchunks = (lay.d[l] + kChunk - 1) / kChunk;
     for (int64_t c = 0; c < nchunks; ++c) {
       float p32[kSlots];
       for (int j = 0; j < kSlots; ++j) p32[j] = 0.0f;
-      const int64_t e1 = std::min(d[l], (c + 1) * kChunk);
+      const int64_t e1 = std::min(lay.d[l], (c + 1) * kChunk);   // padding coordinates carry code 0 and add nothing
       for (int64_t e = c * kChunk; e < e1; ++e) {
-        const Code cc = get_code(msg + lay.msg_off[l], lay.planes[l], lay.ostride[l], e);
-        const float cur = decode_value(cc.sign, cc.h, stored_norm(msg, lay, l, e), hc.lev, S[l]);
-        float prev = 0.0f;
-        if (msg_prev) {
-          const HeaderView hp = header_of(msg_prev, lay, l);
-          const Code pc = get_code(msg_prev + lay.msg_off[l], lay.planes[l], lay.ostride[l], e);
-          prev = decode_value(pc.sign, pc.h, stored_norm(msg_prev, lay, l, e), hp.lev, S[l]);
-        }
+        const float cur = decoded_value(msg, lay, l, e);
+        const float prev = msg_prev ? decoded_value(msg_prev, lay, l, e) : 0.0f;
         const float diff = cur - prev;
         p32[slot_of(e)] = std::fmaf(diff, diff, p32[slot_of(e)]);
       }
@@ -637,6 +561,94 @@ double oracle_delta_from_messages(int32_t L, const int64_t *d, const int32_t *S,
     }
   }
   return combine_chunks(delta_chunks);
+}
+
+// Bucket scope: the level fit's statistics of one layer, gathered from the vectors a quantize pass sees (Alg. 1 runs
+// lines 3-5 before the round's vectors exist, so the estimate can only come from earlier vectors).  hist (257, added
+// to) receives the weight floor(sumsq_b * 2^(23 - ex)), capped at 2^30, at the grid bin of u for every coordinate whose
+// raw magnitude bin is not 0; *bmax (maximised) the largest bucket statistic, +infinity if one is not finite.
+void gather_bucket_stats(const float *v, int64_t d, int32_t ex, int norm_kind, uint64_t *hist, double *bmax) {
+  for (int64_t e0 = 0; e0 < d; e0 += kBucket) {
+    const int64_t n = std::min<int64_t>(kBucket, d - e0);
+    const double s = bucket_stat(v + e0, n, norm_kind);
+    const bool finite = stat_finite(s, norm_kind);
+    const double sm = finite ? s : std::numeric_limits<double>::infinity();
+    if (sm > *bmax) *bmax = sm;
+    if (ex == kTypeSkip || !finite) continue;
+    const uint64_t wfix = stat_weight(weight_of(s, norm_kind), ex);
+    const float inv = rcp_floor(norm_of(s, norm_kind));
+    if (wfix == 0 || inv == 0.0f) continue;
+    for (int64_t q = e0; q < e0 + n; ++q) {
+      if (((f2u(v[q]) & 0x7FFFFFFFu) >> 20) == 0) continue;
+      const float uc = std::fmin(std::fabs(v[q]) * inv, 1.0f);
+      int j = (int)(f2u(uc) >> 20) - kGridBase;
+      if (j < 0) j = 0;
+      if (j > kGridPoints - 1) j = kGridPoints - 1;
+      hist[j] += wfix;
+    }
+  }
+}
+}  // namespace
+
+// ---------------------------------------------------------------- ENCODE(Q(V_k)) for one node: Alg. 1 line 12
+// grads[l]  : layer l of the node's dual vector.      levels[l] : the S[l] levels of layer l's type.
+// msg       : message_bytes output.                    msg_prev  : previous-round message of this node or NULL.
+// scope     : what one norm covers.  Layer: the layer's canonical statistic.  Vector: the canonical combination of
+//             the L layer statistics (slot j takes layers j, j+256, ...; then the tree), used by every layer.
+//             Bucket: every 128 consecutive coordinates of a layer (bucket_stat); the norms travel in the body.
+// sumsq_out : L statistics (may be NULL): the layer's; under vector scope the whole vector's in every entry; under
+//             bucket scope the largest bucket statistic of the layer.
+// delta_out : || Vhat_{k,t+1/2} - Vhat_{k,t-1/2} ||^2 (the step-size term of eq. (general_stepsize)); prev = 0 if NULL.
+// layer_exp : NULL, or (bucket scope) the weight scale of every layer's type: then stats_hist (L*257, added to) and
+//             stats_max (L, maximised) receive the fit statistics of these vectors (gather_bucket_stats).
+// returns the status bits (0: fine).
+int32_t oracle_quantize(int32_t L, const int64_t *d, const int32_t *S, const float *const *levels,
+                        const float *const *grads, uint64_t seed, uint32_t round, uint32_t node, int32_t scope,
+                        uint8_t *msg, const uint8_t *msg_prev, double *sumsq_out, double *delta_out,
+                        const int32_t *layer_exp, uint64_t *stats_hist, double *stats_max, int32_t norm_kind) {
+  const Layout lay = make_layout(L, d, S, scope);
+  std::memset(msg, 0, (size_t)lay.message_bytes);
+  int32_t status = 0;
+  // 1. the statistic every norm is derived from (Sec. 2.2)
+  std::vector<double> stat(L, 0.0);
+  if (scope != kScopeBucket) {
+    for (int l = 0; l < L; ++l) stat[l] = layer_stat(grads[l], d[l], norm_kind);
+    if (scope == kScopeVector) stat.assign(L, combine_stats(stat, norm_kind));
+  }
+  for (int l = 0; l < L; ++l) {
+    // 2. header: the norm in 32 bits (Sec. 3.2; unused and 0 under bucket scope), then the levels in force
+    NormPair n = {0.0f, 0.0f};
+    if (scope != kScopeBucket) n = norm_pair(stat[l], norm_kind, &status);
+    float *hdr = reinterpret_cast<float *>(msg + lay.hdr_off[l]);
+    hdr[0] = n.norm;
+    for (int j = 0; j < S[l]; ++j) hdr[1 + j] = levels[l][j];
+    // 3. every coordinate: Q (Sec. 3.1) with its vector's norm, then its code into the body
+    uint8_t *region = msg + lay.msg_off[l];
+    for (int64_t e = 0; e < d[l]; ++e) {
+      if (scope == kScopeBucket && e % kBucket == 0) {   // a new bucket: its own norm, stored after the octet's codes
+        const double s = bucket_stat(grads[l] + e, std::min<int64_t>(kBucket, d[l] - e), norm_kind);
+        n = norm_pair(s, norm_kind, &status);
+        *bucket_norm_slot(region, lay.planes[l], lay.ostride[l], e) = n.norm;
+        if (stat_finite(s, norm_kind) && s > stat[l]) stat[l] = s;
+      }
+      const Code code = quantize_coord(grads[l][e], n.inv, levels[l], S[l], draw16(seed, round, node, (uint32_t)l, (uint64_t)e));
+      put_code(region, lay.planes[l], lay.ostride[l], e, code);
+    }
+    if (sumsq_out) sumsq_out[l] = stat[l];
+    if (scope == kScopeBucket && layer_exp)
+      gather_bucket_stats(grads[l], d[l], layer_exp[l], norm_kind, stats_hist + (size_t)l * kGridPoints, &stats_max[l]);
+  }
+  // 4. the step-size term, from the two messages as stored
+  if (delta_out) *delta_out = delta_between(lay, msg, msg_prev);
+  return status;
+}
+
+// ---------------------------------------------------------------- step-size term from two stored messages
+// || DECODE(msg) - DECODE(msg_prev) ||^2 in the contract's order (msg_prev NULL: zeros): what oracle_quantize returns
+// as delta, for a test that holds the messages of a full-size model but cannot quantize it on the CPU.
+double oracle_delta_from_messages(int32_t L, const int64_t *d, const int32_t *S, int32_t scope, const uint8_t *msg,
+                                  const uint8_t *msg_prev) {
+  return delta_between(make_layout(L, d, S, scope), msg, msg_prev);
 }
 
 // ---------------------------------------------------------------- DECODE + mean over the K nodes: Alg. 1 lines 15-17
@@ -831,18 +843,16 @@ double oracle_oda_update_alt(int32_t L, const int64_t *d, const float *const *me
 // The K nodes' current vectors are the Z samples.  Every coordinate of (node k, layer l) carries weight
 // ||v_{k,l}||^2 (the factor that multiplies its normalised variance in eq. (MQV)/(Qada2)); layers of the
 // same type pool.  The distribution is estimated by a histogram:
-//   1. bin |v| on its top 11 magnitude bits (8 exponent + 3 mantissa bits): counts[k][l][2048]; the estimate
-//      uses a fixed quarter of the coordinates: those in 256-coordinate blocks number 0, 4, 8, ... of the layer;
+//   1. bin |v| of every coordinate on its top 11 magnitude bits (8 exponent + 3 mantissa bits): counts[k][l][2048];
 //   2. map each bin's midpoint c to u = min(c * inv_norm, 1), re-bin u the same way onto the 257-point
 //      grid g_j (g_0 = 2^-32, ..., g_256 = 1), adding weight wfix(k,l) * count, where
 //      wfix = floor(sumsq(k,l) * 2^(23 - e)) and e is the binary exponent of the largest sumsq of the type;
 //   3. minimise sum_i sum_{bins in [l_i, l_{i+1})} W_j (l_{i+1} - mid_j)(mid_j - l_i) exactly over interior
 //      levels restricted to grid points, by dynamic programming (first level 0 and last level 1 are fixed).
 // hist_out (optional): K*L*2048 uint32 counts.  pooled_out (optional): M*257 uint64 weights.
-// levels_io: M pointers to S_m floats; a type whose sampled vectors are all zero keeps its levels.
+// levels_io: M pointers to S_m floats; a type whose vectors are all zero keeps its levels.
 void oracle_histogram(const float *v, int64_t d, uint32_t *counts /* 2048, accumulated into */) {
-  for (int64_t e = 0; e < d; ++e)
-    if (((e / kBlock) % 4) == 0) counts[(f2u(v[e]) & 0x7FFFFFFFu) >> 20] += 1;
+  for (int64_t e = 0; e < d; ++e) counts[(f2u(v[e]) & 0x7FFFFFFFu) >> 20] += 1;
 }
 
 // objective of eq. (Qada2) for given levels on pooled grid weights W[257] (used by the fit and by its pins)
@@ -917,10 +927,10 @@ int32_t oracle_fit_levels(int32_t L, const int64_t *d, const int32_t *layer_type
                           float *const *levels_io, uint32_t *hist_out, uint64_t *pooled_out, int32_t norm_kind) {
   int32_t status = 0;
   if (scope == kScopeBucket) {
-    // Every bucket is a vector of its own: weight = its sum of squares, normalisation = its norm.  Sampled
-    // coordinates (blocks 0, 4, 8, ... as above, minus those whose raw magnitude bin is 0) go straight onto the
-    // normalised grid: W[bin(min(|v| * inv_b, 1))] += floor(sumsq_b * 2^(23 - e)), e = binary exponent of the type's
-    // largest sampled bucket sum.  There is no per-layer raw histogram in this scope (hist_out is left untouched).
+    // Every bucket is a vector of its own: weight = its sum of squares, normalisation = its norm.  Every coordinate
+    // whose raw magnitude bin is not 0 goes straight onto the normalised grid:
+    // W[bin(min(|v| * inv_b, 1))] += floor(sumsq_b * 2^(23 - e)), e = binary exponent of the type's largest bucket
+    // sum.  There is no per-layer raw histogram in this scope (hist_out is left untouched).
     for (int m = 0; m < M; ++m) {
       std::vector<uint64_t> W(kGridPoints, 0);
       double smax = 0.0;
@@ -929,7 +939,6 @@ int32_t oracle_fit_levels(int32_t L, const int64_t *d, const int32_t *layer_type
         if (layer_type[l] != m) continue;
         for (int k = 0; k < K; ++k)
           for (int64_t e = 0; e < d[l]; e += kBucket) {
-            if (((e / kBlock) % 4) != 0) continue;   // only sampled buckets carry weight, so only they set the scale
             const double st = bucket_stat(grads[(size_t)k * L + l] + e, std::min<int64_t>(kBucket, d[l] - e), norm_kind);
             const double v = weight_of(st, norm_kind);
             if (!stat_finite(st, norm_kind)) finite = false;
@@ -944,7 +953,6 @@ int32_t oracle_fit_levels(int32_t L, const int64_t *d, const int32_t *layer_type
           for (int k = 0; k < K; ++k) {
             const float *g = grads[(size_t)k * L + l];
             for (int64_t e0 = 0; e0 < d[l]; e0 += kBucket) {
-              if (((e0 / kBlock) % 4) != 0) continue;
               const int64_t n = std::min<int64_t>(kBucket, d[l] - e0);
               const double sv = bucket_stat(g + e0, n, norm_kind);
               const uint64_t wfix = stat_weight(weight_of(sv, norm_kind), ex);
@@ -961,7 +969,7 @@ int32_t oracle_fit_levels(int32_t L, const int64_t *d, const int32_t *layer_type
             }
           }
         }
-        if (any_weight(W)) oracle_fit_dp(W.data(), type_points[m], levels_io[m]);   // no sampled mass: keep the levels
+        if (any_weight(W)) oracle_fit_dp(W.data(), type_points[m], levels_io[m]);   // no mass on the grid: keep the levels
       }
       if (pooled_out) std::memcpy(pooled_out + (size_t)m * kGridPoints, W.data(), kGridPoints * sizeof(uint64_t));
     }
@@ -1015,7 +1023,7 @@ int32_t oracle_fit_levels(int32_t L, const int64_t *d, const int32_t *layer_type
           }
         }
       }
-      if (any_weight(W)) oracle_fit_dp(W.data(), type_points[m], levels_io[m]);   // no sampled mass: keep the levels
+      if (any_weight(W)) oracle_fit_dp(W.data(), type_points[m], levels_io[m]);   // no mass on the grid: keep the levels
     }
     if (pooled_out) std::memcpy(pooled_out + (size_t)m * kGridPoints, W.data(), kGridPoints * sizeof(uint64_t));
   }
@@ -1023,8 +1031,8 @@ int32_t oracle_fit_levels(int32_t L, const int64_t *d, const int32_t *layer_type
 }
 
 // The level fit from statistics gathered by oracle_quantize (bucket scope) over the K nodes of the previous round:
-// pool the grid histograms of every type, fit (a type without a scale, or without any sampled mass, keeps its levels),
-// then derive the scale of the next gathering pass from the largest sampled bucket sum of the type.
+// pool the grid histograms of every type, fit (a type without a scale, or without any mass on the grid, keeps its levels),
+// then derive the scale of the next gathering pass from the largest bucket sum of the type.
 // hist: K*L*257 (entry (k*L + l)*257 + j), bmax: K*L, exp_io: M (in: the scale the histograms were gathered with).
 int32_t oracle_fit_from_stats(int32_t L, const int32_t *layer_type, int32_t M, const int32_t *type_points, int32_t K,
                               const uint64_t *hist, const double *bmax, int32_t *exp_io, float *const *levels_io,
@@ -1050,6 +1058,107 @@ int32_t oracle_fit_from_stats(int32_t L, const int32_t *layer_type, int32_t M, c
     exp_io[m] = (finite && smax > 0.0) ? std::ilogb(smax) : kTypeSkip;
   }
   return status;
+}
+
+// ================================================================ plain definitions (references, no contract)
+// The routines above fix precision and order of every operation so that two implementations can agree to the bit.
+// Two of their quantities are narrower than the textbook definition, for the sake of a cheap GPU pass: the step-size
+// term (single-precision chains inside a reduction slot) and the bucket sum of squares (single-precision chains inside
+// a lane, where the result is in a safe range); the level fit works on a histogram instead of the samples themselves.
+// What follows are the definitions themselves -- fp64 arithmetic, long double accumulators, plain coordinate order --
+// for the tests that bound the contract's values against them.  Nothing here is called by the routines above.
+
+// eq. (general_stepsize), one node's term: sum_i (Vhat_i - Vhat_prev_i)^2 over the decoded messages (prev NULL: 0).
+double oracle_delta_plain(int32_t L, const int64_t *d, const int32_t *S, int32_t scope, const uint8_t *msg,
+                          const uint8_t *msg_prev) {
+  const Layout lay = make_layout(L, d, S, scope);
+  long double total = 0.0L;
+  for (int l = 0; l < L; ++l)
+    for (int64_t e = 0; e < d[l]; ++e) {
+      const double cur = (double)decoded_value(msg, lay, l, e);
+      const double prev = msg_prev ? (double)decoded_value(msg_prev, lay, l, e) : 0.0;
+      total += (long double)((cur - prev) * (cur - prev));
+    }
+  return (double)total;
+}
+
+// sum of squares of n coordinates (Sec. 2.2: the square of the L2 norm)
+double oracle_sumsq_plain(const float *v, int64_t n) {
+  long double total = 0.0L;
+  for (int64_t e = 0; e < n; ++e) total += (long double)((double)v[e] * (double)v[e]);
+  return (double)total;
+}
+
+namespace {
+// ||v||_q for q = 2, 1, infinity, straight from the definition
+double norm_plain(const float *v, int64_t n, int kind) {
+  if (kind == kNormL2) return std::sqrt(oracle_sumsq_plain(v, n));
+  long double total = 0.0L;
+  double mx = 0.0;
+  for (int64_t e = 0; e < n; ++e) {
+    total += (long double)std::fabs((double)v[e]);
+    mx = std::fmax(mx, std::fabs((double)v[e]));
+  }
+  return kind == kNormL1 ? (double)total : mx;
+}
+
+// sum_i (l_{tau+1} - u_i)(u_i - l_tau) with u_i = |v_i| / norm  (the normalised variance of eq. (Var))
+long double normalised_variance(const float *v, int64_t n, double norm, const float *lev, int S) {
+  long double total = 0.0L;
+  if (!(norm > 0.0)) return total;
+  for (int64_t e = 0; e < n; ++e) {
+    const double u = std::fmin(std::fabs((double)v[e]) / norm, 1.0);
+    int tau = 0;
+    for (int j = 1; j <= S - 2; ++j)
+      if ((double)lev[j] <= u) tau = j;
+    total += (long double)(((double)lev[tau + 1] - u) * (u - (double)lev[tau]));
+  }
+  return total;
+}
+}  // namespace
+
+// eq. (Var) for one vector with one level sequence: ||v||_q^2 * sum_i (l_{tau+1} - u_i)(u_i - l_tau).
+double oracle_variance_plain(const float *v, int64_t n, const float *lev, int32_t S, int32_t norm_kind) {
+  const double norm = norm_plain(v, n, norm_kind);
+  return (double)((long double)(norm * norm) * normalised_variance(v, n, norm, lev, S));
+}
+
+// eq. (MQV): the total quantization variance of the K nodes' vectors under the given per-type levels -- what the level
+// fit is meant to minimise.  A "vector" is what one norm covers: a layer, the node's whole dual vector, or a bucket.
+double oracle_mqv_objective_plain(int32_t L, const int64_t *d, const int32_t *layer_type, const int32_t *type_points,
+                                  int32_t K, int32_t scope, const float *const *grads /* K*L */,
+                                  const float *const *levels /* M */, int32_t norm_kind) {
+  long double total = 0.0L;
+  for (int k = 0; k < K; ++k) {
+    double vnorm = 0.0;
+    if (scope == kScopeVector) {   // the norm of the concatenation of the node's layers
+      long double acc = 0.0L;
+      double mx = 0.0;
+      for (int l = 0; l < L; ++l) {
+        const double nl = norm_plain(grads[(size_t)k * L + l], d[l], norm_kind);
+        if (norm_kind == kNormL2) acc += (long double)(nl * nl);
+        else if (norm_kind == kNormL1) acc += (long double)nl;
+        else mx = std::fmax(mx, nl);
+      }
+      vnorm = norm_kind == kNormL2 ? std::sqrt((double)acc) : (norm_kind == kNormL1 ? (double)acc : mx);
+    }
+    for (int l = 0; l < L; ++l) {
+      const float *g = grads[(size_t)k * L + l];
+      const float *lev = levels[layer_type[l]];
+      const int S = type_points[layer_type[l]];
+      if (scope == kScopeBucket) {
+        for (int64_t e0 = 0; e0 < d[l]; e0 += kBucket) {
+          const int64_t n = std::min<int64_t>(kBucket, d[l] - e0);
+          const double nb = norm_plain(g + e0, n, norm_kind);
+          total += (long double)(nb * nb) * normalised_variance(g + e0, n, nb, lev, S);
+        }
+      } else {
+        const double nl = scope == kScopeVector ? vnorm : norm_plain(g, d[l], norm_kind);
+        total += (long double)(nl * nl) * normalised_variance(g, d[l], nl, lev, S);
+      }
+    }
+  }
+  return (double)total;
 }
 
 }  // extern "C"

@@ -572,7 +572,7 @@ int qoda_fit_levels(qoda_ctx *c, const float *const *grad_dev, uint32_t round, v
     a.round = round;
     LAUNCH(c, kIdZero, s, launch_zero_u32(c->d_hist, KL * kHistBins, s));
     if (c->scope == kScopeBucket) {
-      // two passes over the sampled quarter of the gradient: the scale of the weights, then the weighted histogram
+      // two passes over the gradient: the scale of the weights, then the weighted histogram
       LAUNCH(c, kIdZero, s, launch_zero_u32(reinterpret_cast<unsigned int *>(c->d_sumsq), 2 * KL, s));
       LAUNCH(c, kIdBucketMax, s, launch_bucket_max(a, s));
       LAUNCH(c, kIdFitTypemax, s, launch_fit_typemax(a, s));
@@ -985,7 +985,8 @@ int qoda_status(qoda_ctx *c, void *stream) {
     HIP_TRY(c, hipStreamSynchronize(s));
     if (flag) {
       HIP_TRY(c, launch_zero_u32(c->d_status, 1, s));
-      return fail(c, QODA_ENONFINITE, "a layer's sum of squares was not a finite number");
+      if (flag & 1u) return fail(c, QODA_ENONFINITE, "a vector's norm statistic was not a finite number in range");
+      return fail(c, QODA_ETINYNORM, "a vector's norm was positive but below 2^-126: its reciprocal is not a float");
     }
     return QODA_OK;
   });

@@ -54,7 +54,7 @@ struct Dev {
   const unsigned char *const *msgs_in;  // [K] messages to decode
   double *partial;    // [K*G] per-tile statistics (sums of squares, sums of magnitudes or largest magnitudes)
   double *dpartial;   // [K*G] per-tile squared differences
-  double *sumsq;      // [K*L] the statistic of (node, layer); bucket scope: its largest sampled bucket statistic
+  double *sumsq;      // [K*L] the statistic of (node, layer); bucket scope: its largest bucket statistic
   float *norm;        // [K*L]
   float *inv;         // [K*L]
   double *delta;      // [K]

@@ -23,6 +23,12 @@ __device__ __forceinline__ unsigned int f2u(float f) { return __float_as_uint(f)
 __device__ __forceinline__ float u2f(unsigned int u) { return __uint_as_float(u); }
 
 constexpr float kFltMax = 3.402823466e+38f;
+constexpr float kFltMin = 1.17549435e-38f;   // 2^-126, the smallest normal float
+
+// Bits of the sticky device status word.
+constexpr unsigned int kStatusNonFinite = 1u;   // a statistic is not a finite number in range
+constexpr unsigned int kStatusTinyNorm = 2u;    // 0 < norm < 2^-126: 1/norm is not a float (the one case where the
+                                                // quantizer of that vector is biased, Thm 5.1)
 
 // largest float n >= 0 with n*n <= s (n*n is exact in fp64); 0 when s is not a finite number in range.
 __device__ float sqrt_floor(double s) {
@@ -268,8 +274,7 @@ __global__ void k_zero_u32(unsigned int *p, size_t n) {
 
 // ------------------------------------------------------------------------------------------------ pass 1
 // Sum of squares of one tile in fp64 (Sec. 2.2, L2 norm before the root), optionally with the histogram of the
-// top 11 magnitude bits (the distribution estimate of Alg. 1 line 4), taken over a fixed quarter of the
-// coordinates (every fourth 256-coordinate block) to keep the shared-memory atomics off the critical path.
+// top 11 magnitude bits of every coordinate (the distribution estimate of Alg. 1 line 4).
 template <bool HIST, int KIND>
 __global__ void __launch_bounds__(kThreads) k_sumsq(Dev a) {
   __shared__ double red[kThreads];
@@ -308,7 +313,7 @@ __global__ void __launch_bounds__(kThreads) k_sumsq(Dev a) {
           if (KIND == kNormL2) acc = __builtin_fma(xd, xd, acc);   // the product is exact in fp64, so this equals acc + xd*xd
           else if (KIND == kNormL1) acc = acc + fabs(xd);
           else mb = max(mb, f2u(x[j]) & 0x7FFFFFFFu);
-          if (HIST && (s & 3) == 0) atomicAdd(&lh[(f2u(x[j]) & 0x7FFFFFFFu) >> 20], 1u);   // blocks 0, 4, 8, ... only
+          if (HIST) atomicAdd(&lh[(f2u(x[j]) & 0x7FFFFFFFu) >> 20], 1u);
         }
       }
     } else {
@@ -323,7 +328,7 @@ __global__ void __launch_bounds__(kThreads) k_sumsq(Dev a) {
           if (KIND == kNormL2) acc = __builtin_fma(xd, xd, acc);
           else if (KIND == kNormL1) acc = acc + fabs(xd);
           else mb = max(mb, f2u(x[j]) & 0x7FFFFFFFu);
-          if (HIST && (s & 3) == 0 && e + j < m.d) atomicAdd(&lh[(f2u(x[j]) & 0x7FFFFFFFu) >> 20], 1u);
+          if (HIST && e + j < m.d) atomicAdd(&lh[(f2u(x[j]) & 0x7FFFFFFFu) >> 20], 1u);
         }
       }
     }
@@ -364,7 +369,8 @@ __global__ void __launch_bounds__(kThreads) k_norm_finalize(Dev a) {
     a.sumsq[idx] = s;
     a.norm[idx] = n;
     a.inv[idx] = rcp_floor(n);
-    if (!finite) atomicOr(a.status, 1u);
+    if (!finite) atomicOr(a.status, kStatusNonFinite);
+    if (n > 0.0f && n < kFltMin) atomicOr(a.status, kStatusTinyNorm);
   }
 }
 
@@ -396,7 +402,8 @@ __global__ void __launch_bounds__(kThreads) k_norm_vector(Dev a) {
     a.norm[idx] = n;
     a.inv[idx] = r;
   }
-  if (threadIdx.x == 0 && !finite) atomicOr(a.status, 1u);
+  if (threadIdx.x == 0 && !finite) atomicOr(a.status, kStatusNonFinite);
+  if (threadIdx.x == 0 && n > 0.0f && n < kFltMin) atomicOr(a.status, kStatusTinyNorm);
 }
 
 // ------------------------------------------------------------------------------------------------ pass 2
@@ -581,7 +588,9 @@ __global__ void __launch_bounds__(kThreads) k_quantize(Dev a) {
 // the first, is served by the cache).
 //
 // Per-wave shared memory of the bucket-scope quantizer.
-struct BucketWave {
+constexpr double kBucketRescueBelow = 7.888609052210118e-31;   // 2^-100
+
+struct __attribute__((aligned(8))) BucketWave {
   // the lane's sum of its 4 squares (fp32 fused chain in coordinate order) for block bb, lane i, at index
   // 72*bb + i + i/8: one word of padding after every 8, so that the transposed read below (lane L reads the 8
   // consecutive entries 8L .. 8L+7, i.e. a stride of 9 words between lanes) spreads over all banks
@@ -592,12 +601,52 @@ struct BucketWave {
   unsigned int wfix[16];   // fit statistics: integer weight of the bucket (0: gathers nothing)
 };
 
+// The sums of squares of the 16 buckets of one octet once more with exact fp64 squares (a lane's chain
+// acc = fma((double)x, (double)x, acc), then the same tree): the path taken when a single-precision result is below
+// 2^-100 or not finite.  The 8 x 64 lane sums go through the wave's shared memory four blocks at a time (as doubles they
+// fill the area the single-precision pass used).  Every lane of the wave must call this; the result is the sum of
+// the lane's own bucket.
+template <bool FAST>
+__device__ __forceinline__ double bucket_sums_exact(const LayerMeta &m, long long O, const float *__restrict__ v,
+                                                 float *psum, int i) {
+  double *dsum = reinterpret_cast<double *>(psum);
+  const int q = i >> 2, r = i & 3;
+  const int bb = q >> 1, hf = q & 1;
+  double s = 0.0;
+  for (int half = 0; half < 2; ++half) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    for (int b4 = 0; b4 < 4; ++b4) {
+      const long long e = (O * 8 + 4 * half + b4) * kBlockCoords + 4 * i;
+      float x[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+      if (FAST || e < m.d) load4(v, e, FAST ? e + 4 : m.d, x);
+      double acc = 0.0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc = __builtin_fma((double)x[j], (double)x[j], acc);
+      dsum[72 * b4 + i + (i >> 3)] = acc;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    if ((bb >> 2) == half) {
+      const double *p = &dsum[72 * (bb & 3) + 36 * hf + 9 * r];
+      s = ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+    }
+  }
+  s = s + __shfl_xor(s, 1, 64);
+  s = s + __shfl_xor(s, 2, 64);
+  return s;
+}
+
 // Sums of squares of the 16 buckets of one octet -> norm, inv (shared memory) and the octet's norm trailer.
 // A lane's four squares are an fp32 fused chain; lane L then finishes bucket q = L/4 (block q/2, half q%2): it adds 8
 // consecutive lane sums, widened to fp64, by the in-order binary tree, then the four lanes of the quad combine
 // (neighbour, then pair), which continues the same tree.
+// A single-precision result below 2^-100 (squares may have vanished) or not finite (squares may have overflowed) is
+// replaced by the exact one (bucket_sums_exact).
 // ex: weight scale of the layer's type for the fit statistics (kTypeSkip: none); best: running maximum of the bit
-// patterns of the lane's sampled bucket sums (blocks 0 and 4 of the octet, i.e. every fourth block of the layer).
+// patterns of the lane's bucket sums.
 template <bool FAST, int KIND>
 __device__ __forceinline__ void bucket_norms(const Dev &a, const LayerMeta &m, long long O, const float *__restrict__ v,
                                              float *trailer, const float *prev_trailer, BucketWave &bw, int i, int ex,
@@ -645,6 +694,13 @@ __device__ __forceinline__ void bucket_norms(const Dev &a, const LayerMeta &m, l
     s = s + __shfl_xor(s, 1, 64);
     s = s + __shfl_xor(s, 2, 64);
   }
+  if (KIND == kNormL2) {
+    const bool redo = !(s >= kBucketRescueBelow) || !(s <= 1.7976931348623157e308);
+    if (__ballot(redo) != 0ull) {   // rare: all lanes of the wave take the exact path together
+      const double exact = bucket_sums_exact<FAST>(m, O, v, bw.psum, i);
+      if (redo) s = exact;
+    }
+  }
   const bool finite = stat_finite(s, KIND);
   float n = 0.0f, rinv = 0.0f;
   if (finite) {
@@ -655,8 +711,9 @@ __device__ __forceinline__ void bucket_norms(const Dev &a, const LayerMeta &m, l
       rinv = inverse_of(n);
     }
   }
-  if (!finite) atomicOr(a.status, 1u);
-  if ((bb & 3) == 0) {
+  if (!finite) atomicOr(a.status, kStatusNonFinite);
+  if (n > 0.0f && n < kFltMin) atomicOr(a.status, kStatusTinyNorm);
+  {
     const unsigned long long bits = finite ? (unsigned long long)__double_as_longlong(s) : 0x7FF0000000000000ull;
     best = bits > best ? bits : best;
   }
@@ -690,7 +747,7 @@ __device__ __forceinline__ void quantize_block_b(const float (&x)[4], const unsi
     u[j] = __builtin_amdgcn_fmed3f(fabsf(x[j]) * inv, 0.0f, 1.0f);
     tau[j] = lut[f2u(u[j]) >> 20];
   }
-  if (wfix != 0u) {   // a sampled block of a bucket with weight: the fit's grid histogram (integer adds)
+  if (wfix != 0u) {   // a bucket with weight: the fit's grid histogram (integer adds)
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       if ((f2u(x[j]) & 0x7FF00000u) == 0u) continue;   // raw magnitude bin 0; also the +0 padding past the layer's end
@@ -773,10 +830,9 @@ __device__ __forceinline__ void quantize_octet_b(const Dev &a, const LayerMeta &
       const float2 pn = *reinterpret_cast<const float2 *>(&bw.pnorm[hf8 + 2 * pp]);
       unsigned int o[4];
       philox4x32_10((unsigned int)((B0 >> 1) * 64 + i), (unsigned int)l, a.round, (unsigned int)k, k0, k1, o);
-      // blocks 0 and 4 of the octet (first block of pairs 0 and 2) are the sampled ones
-      const unsigned int wf = ((pp & 1) == 0) ? bw.wfix[hf8 + 2 * pp] : 0u;
-      quantize_block_b<C1, PREV>(x0, o, 0, ii.x, nn.x, pn.x, lut, tab, tprev, D, Dp, acc, wf, lh);
-      quantize_block_b<C1, PREV>(x1, o, 1, ii.y, nn.y, pn.y, lut, tab, tprev, D, Dp, acc, 0u, lh);
+      const uint2 wf = *reinterpret_cast<const uint2 *>(&bw.wfix[hf8 + 2 * pp]);   // fit statistics: the buckets' weights
+      quantize_block_b<C1, PREV>(x0, o, 0, ii.x, nn.x, pn.x, lut, tab, tprev, D, Dp, acc, wf.x, lh);
+      quantize_block_b<C1, PREV>(x1, o, 1, ii.y, nn.y, pn.y, lut, tab, tprev, D, Dp, acc, wf.y, lh);
     }
     if (PREV) shift_out_pair<C1>(Dp);
   }
@@ -847,7 +903,7 @@ __global__ void __launch_bounds__(kThreads) k_quantize_b(Dev a) {
     const double total = block_tree((double)acc, red);
     if (t == 0) a.dpartial[(size_t)kr * a.G + m.first_chunk + chunk] = total;
   }
-  // statistics of the run: largest sampled bucket sum (bit pattern of a non-negative double) and the histogram
+  // statistics of the run: largest bucket sum (bit pattern of a non-negative double) and the histogram
 #pragma unroll
   for (int sh = 1; sh < 64; sh *= 2) {
     const unsigned long long other = __shfl_xor(best, sh, 64);
@@ -1167,11 +1223,11 @@ __global__ void __launch_bounds__(kThreads) k_fit_pool(Dev a) {
   }
 }
 
-// ---- level fit under bucket scope.  Only the sampled blocks (0, 4, 8, ... of a layer, i.e. blocks 0 and 4 of every
-// octet) are read: a quarter of the gradient per pass.
-// Sum of squares of the lane's bucket (half of block B) by the in-order binary tree, valid in all its 32 lanes.
-__device__ __forceinline__ double sampled_bucket_sum(const LayerMeta &m, const float *__restrict__ v, long long B, int i,
-                                                     float (&x)[4], int kind) {
+// ---- level fit under bucket scope from given vectors: two passes over them (scale of the weights, then histogram).
+// Statistic of the lane's bucket (half of block B) by the in-order binary tree, valid in all its 32 lanes.  Every lane
+// of the wave must call this.
+__device__ __forceinline__ double half_block_stat(const LayerMeta &m, const float *__restrict__ v, long long B, int i,
+                                                  float (&x)[4], int kind) {
   const long long e = B * kBlockCoords + 4 * i;
 #pragma unroll
   for (int j = 0; j < 4; ++j) x[j] = 0.0f;
@@ -1196,10 +1252,22 @@ __device__ __forceinline__ double sampled_bucket_sum(const LayerMeta &m, const f
   double s = (double)acc;
 #pragma unroll
   for (int w = 1; w < 32; w *= 2) s = s + __shfl_xor(s, w, 64);
+  if (kind == kNormL2) {
+    // below 2^-100 (squares may have vanished) or not finite (they may have overflowed): exact fp64 squares instead
+    const bool redo = !(s >= kBucketRescueBelow) || !(s <= 1.7976931348623157e308);
+    if (__ballot(redo) != 0ull) {
+      double acc64 = 0.0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc64 = __builtin_fma((double)x[j], (double)x[j], acc64);
+#pragma unroll
+      for (int w = 1; w < 32; w *= 2) acc64 = acc64 + __shfl_xor(acc64, w, 64);
+      if (redo) s = acc64;
+    }
+  }
   return s;
 }
 
-// Largest sampled bucket statistic of every (node, layer), as the bit pattern of a non-negative double (ordered like
+// Largest bucket statistic of every (node, layer), as the bit pattern of a non-negative double (ordered like
 // an integer); one that is not a finite number in range leaves +infinity.  a.sumsq must be zero on entry.
 __global__ void __launch_bounds__(kThreads) k_bucket_max(Dev a) {
   __shared__ unsigned long long wmax[kThreads / 64];
@@ -1212,12 +1280,11 @@ __global__ void __launch_bounds__(kThreads) k_bucket_max(Dev a) {
   for (int cc = 0; cc < st.z; ++cc)
     for (int oo = 0; oo < 2; ++oo) {
       const long long O = (long long)(st.y + cc) * 8 + w * 2 + oo;
-#pragma unroll
-      for (int bb = 0; bb < 8; bb += 4) {
+      for (int bb = 0; bb < 8; ++bb) {
         const long long B = O * 8 + bb;
-        if (B >= m.nblk) continue;
+        if (B >= m.nblk) break;   // the same for every lane of the wave
         float x[4];
-        const double s = sampled_bucket_sum(m, v, B, i, x, a.kind);
+        const double s = half_block_stat(m, v, B, i, x, a.kind);
         const bool finite = stat_finite(s, a.kind);
         const unsigned long long bits = finite ? (unsigned long long)__double_as_longlong(s) : 0x7FF0000000000000ull;
         best = bits > best ? bits : best;
@@ -1234,7 +1301,7 @@ __global__ void __launch_bounds__(kThreads) k_bucket_max(Dev a) {
   }
 }
 
-// Weighted histogram of the normalised magnitudes of the sampled coordinates of every (node, layer) on the 257-point
+// Weighted histogram of the normalised magnitudes of the coordinates of every (node, layer) on the 257-point
 // grid: weight floor(bucket sum * 2^(23 - exponent of the type)), integer adds, kept per (node, layer) in the first
 // 257 64-bit words of its histogram area.
 __global__ void __launch_bounds__(kThreads) k_bucket_hist(Dev a) {
@@ -1251,12 +1318,11 @@ __global__ void __launch_bounds__(kThreads) k_bucket_hist(Dev a) {
   for (int cc = 0; cc < st.z; ++cc)
     for (int oo = 0; oo < 2; ++oo) {
       const long long O = (long long)(st.y + cc) * 8 + w * 2 + oo;
-#pragma unroll
-      for (int bb = 0; bb < 8; bb += 4) {
+      for (int bb = 0; bb < 8; ++bb) {
         const long long B = O * 8 + bb;
-        if (B >= m.nblk) continue;
+        if (B >= m.nblk) break;   // the same for every lane of the wave
         float x[4];
-        const double s = sampled_bucket_sum(m, v, B, i, x, a.kind);
+        const double s = half_block_stat(m, v, B, i, x, a.kind);
         const unsigned long long wfix = (unsigned long long)floor(ldexp(weight_of(s, a.kind), 23 - ex));
         const float inv = rcp_floor(norm_of(s, a.kind));
         if (wfix == 0ull || inv == 0.0f) continue;
@@ -1372,7 +1438,7 @@ __global__ void __launch_bounds__(kFitThreads) k_fit_dp(Dev a) {
     if (f == 0) row[kGridPoints].g = 0.0;
   }
   __syncthreads();
-  if (row[kGridPoints].p0 == 0.0) return;   // no sampled mass at all: the type keeps its levels
+  if (row[kGridPoints].p0 == 0.0) return;   // no mass on the grid at all: the type keeps its levels
   const double inf = __longlong_as_double(0x7FF0000000000000ll);
   short *arg = a.dp_arg + a.dp_arg_off[mtype];
   const bool lds_arg = S <= kFitLdsPoints;   // candidates a are at most 254: a byte each, 255 for "none"
@@ -1502,19 +1568,18 @@ hipError_t launch_zero_u32(unsigned int *p, size_t n, hipStream_t s) {
   return hipGetLastError();
 }
 
+template <int KIND>
+static void launch_sumsq_kind(const Dev &a, bool with_hist, hipStream_t s) {
+  const dim3 grid(a.GS, a.nnodes), block(kThreads);
+  if (with_hist) hipLaunchKernelGGL((k_sumsq<true, KIND>), grid, block, 0, s, a);
+  else hipLaunchKernelGGL((k_sumsq<false, KIND>), grid, block, 0, s, a);
+}
+
 hipError_t launch_sumsq(const Dev &a, bool with_hist, hipStream_t s) {
   if (a.GS == 0 || a.nnodes == 0) return hipSuccess;
-  const dim3 grid(a.GS, a.nnodes), block(kThreads);
-  if (a.kind == kNormL2) {
-    if (with_hist) hipLaunchKernelGGL((k_sumsq<true, kNormL2>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((k_sumsq<false, kNormL2>), grid, block, 0, s, a);
-  } else if (a.kind == kNormL1) {
-    if (with_hist) hipLaunchKernelGGL((k_sumsq<true, kNormL1>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((k_sumsq<false, kNormL1>), grid, block, 0, s, a);
-  } else {
-    if (with_hist) hipLaunchKernelGGL((k_sumsq<true, kNormLinf>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((k_sumsq<false, kNormLinf>), grid, block, 0, s, a);
-  }
+  if (a.kind == kNormL2) launch_sumsq_kind<kNormL2>(a, with_hist, s);
+  else if (a.kind == kNormL1) launch_sumsq_kind<kNormL1>(a, with_hist, s);
+  else launch_sumsq_kind<kNormLinf>(a, with_hist, s);
   return hipGetLastError();
 }
 

@@ -15,7 +15,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libqoda.so")
 
-OK, EINVAL, ENOMEM, EHIP, ENONFINITE = 0, -1, -2, -3, -4
+OK, EINVAL, ENOMEM, EHIP, ENONFINITE, ETINYNORM = 0, -1, -2, -3, -4, -5
 BUF_SUMSQ, BUF_NORM, BUF_INV, BUF_DELTA, BUF_HIST, BUF_POOLED = range(6)
 NUM_KERNELS = 23
 SCOPE_LAYER, SCOPE_VECTOR, SCOPE_BUCKET = 0, 1, 2

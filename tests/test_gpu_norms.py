@@ -39,7 +39,7 @@ def test_statistics_and_norms_are_bit_exact(oracle, kind):
     ss = m.ctx.read_buffer(qoda.BUF_SUMSQ)
     nr = m.ctx.read_buffer(qoda.BUF_NORM)
     iv = m.ctx.read_buffer(qoda.BUF_INV)
-    assert m.ctx.status() == qoda.OK
+    assert m.ctx.status() == qoda.ETINYNORM                              # the subnormal layer: its norm is below 2^-126
     for k in range(K):
         for l, s in enumerate(RAGGED):
             want = oracle.norm_stat(grads[k][l], kind)

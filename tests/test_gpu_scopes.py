@@ -211,3 +211,64 @@ def test_fit_from_statistics_gathered_by_the_quantize_pass(oracle):
         prev = want
         m.step()
     assert not np.array_equal(levels[0], helpers.uniform_levels(S))
+
+
+def test_buckets_outside_the_single_precision_range(oracle):
+    """Buckets whose squares vanish or overflow in single precision are summed again with exact fp64 squares: their norms,
+    codes and decoded values match the oracle bit for bit, next to ordinary buckets in the same octet."""
+    S, K = 8, 1
+    sizes = [2048 * 2 + 128 * 3 + 7, 300]
+    L = len(sizes)
+    rng = np.random.default_rng(31)
+    g0 = (rng.standard_normal(sizes[0]) * 1e-3).astype(np.float32)
+    for b, scale in ((1, 1e-25), (2, 1e19), (5, 3e-30), (17, 1e-36), (18, 2e18), (33, 1e-27)):
+        g0[128 * b: 128 * (b + 1)] = (rng.standard_normal(128) * scale).astype(np.float32)[: max(0, min(128, sizes[0] - 128 * b))]
+    g0[128 * 7: 128 * 8] = np.float32(1e-30)
+    g0[128 * 7 + 5] = np.float32(1e-21)                          # one entry carries the bucket, the others vanish
+    g1 = (rng.standard_normal(sizes[1]) * 1e-24).astype(np.float32)
+    grads = [[g0, g1]]
+    m = gm(sizes, [0] * L, [S], K, seed=5, norm_scope=BUCKET)
+    lev = irregular_levels(S, 3)
+    m.ctx.set_levels(0, lev)
+    m.set_grads(grads)
+    m.quantize_all(1)
+    msgs = m.messages()
+    delta = m.ctx.read_buffer(qoda.BUF_DELTA)
+    assert m.ctx.status() == qoda.OK
+    want, _, dl, st = oracle.quantize(sizes, [S] * L, [lev] * L, grads[0], 5, 1, 0, scope=BUCKET)
+    assert st == 0
+    assert np.array_equal(msgs[0], want), int(np.argmax(msgs[0] != want))
+    assert delta[0] == dl
+    _, _, norms = oracle.unpack_layer(want[oracle.header_bytes(sizes, [S] * L, BUCKET):], sizes[0], S, BUCKET)
+    assert np.all(norms > 0)                                     # no bucket was lost
+    m.aggregate()
+    mean = m.layers(m.mean)
+    ref = oracle.dequant_aggregate(sizes, [S] * L, msgs, scope=BUCKET)
+    for l in range(L):
+        assert np.array_equal(mean[l], ref[l]), l
+    # the explicit fit sees the same statistics
+    m.fit(1)
+    levs, _, pooled, st = oracle.fit_levels(sizes, [0] * L, [S], K, [g0, g1], [lev], scope=BUCKET)
+    assert st == 0 and np.array_equal(m.ctx.read_buffer(qoda.BUF_POOLED), pooled)
+    assert np.array_equal(m.ctx.get_levels(0), levs[0])
+
+
+@pytest.mark.parametrize("scope", [qoda.SCOPE_LAYER, VECTOR, BUCKET])
+def test_a_norm_below_the_normal_range_raises_its_own_flag(oracle, scope):
+    S, K = 4, 1
+    sizes = [300, 128]
+    v = np.zeros(300, np.float32)
+    v[:128] = np.float32(1e-41)
+    grads = [[v, np.zeros(128, np.float32)]]
+    m = gm(sizes, [0, 0], [S], K, seed=6, norm_scope=scope)
+    m.set_grads(grads)
+    m.quantize_all(1)
+    msgs = m.messages()
+    want, _, _, st = oracle.quantize(sizes, [S] * 2, [helpers.uniform_levels(S)] * 2, grads[0], 6, 1, 0, scope=scope)
+    assert st == 2 and np.array_equal(msgs[0], want)
+    assert m.ctx.status() == qoda.ETINYNORM
+    assert m.ctx.status() == qoda.OK                             # cleared by reading it
+    v[:128] = np.float32(1e-37)
+    m.set_grads(grads)
+    m.quantize_all(2)
+    assert m.ctx.status() == qoda.OK

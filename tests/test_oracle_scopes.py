@@ -17,7 +17,8 @@ def uniform_levels(S):
 
 
 def test_bucket_sum_of_squares(oracle):
-    """Lane sums are fp32 fused chains over 4 coordinates, widened and combined by the in-order binary tree in fp64."""
+    """Lane sums are fp32 fused chains over 4 coordinates, widened and combined by the in-order binary tree in fp64;
+    a result below 2^-100 or not finite is redone with exact fp64 squares."""
     rng = np.random.default_rng(0)
     ints = rng.integers(-2000, 2000, 128).astype(np.float32)           # squares and lane sums below 2^24: all exact
     assert oracle.bucket_sumsq(ints) == float(np.sum(ints.astype(np.int64) ** 2))
@@ -28,8 +29,15 @@ def test_bucket_sum_of_squares(oracle):
         padded = np.concatenate([v, np.zeros(128 - n, np.float32)])
         assert oracle.bucket_sumsq(padded) == oracle.bucket_sumsq(v)   # missing coordinates count as zeros
     assert oracle.bucket_sumsq(np.array([4097.0], np.float32)) == 16785408.0   # 4097^2 = 2^24 + 8193 rounded in fp32
-    assert oracle.bucket_sumsq(np.full(128, 1e-30, np.float32)) == 0.0         # squares below the fp32 range vanish
-    assert oracle.bucket_sumsq(np.array([3e19], np.float32)) == np.inf         # ... and above it overflow
+    # squares outside the fp32 range: the bucket is redone with exact fp64 squares (same lanes, same tree)
+    tiny = np.full(128, 1e-30, np.float32)
+    assert oracle.bucket_sumsq(tiny) == pytest.approx(128 * float(tiny[0]) ** 2, rel=1e-15)
+    assert oracle.bucket_sumsq(np.array([3e19], np.float32)) == float(np.float32(3e19)) ** 2
+    assert oracle.bucket_sumsq(np.array([2.0 ** -149], np.float32)) == 2.0 ** -298
+    assert oracle.bucket_sumsq(np.array([np.inf, 1.0], np.float32)) == np.inf and np.isnan(oracle.bucket_sumsq(np.array([np.nan], np.float32)))
+    edge = np.zeros(128, np.float32)
+    edge[5] = 2.0 ** -50                                               # exactly 2^-100: single precision is kept
+    assert oracle.bucket_sumsq(edge) == 2.0 ** -100
     # the combination order is the in-order binary tree in fp64: a case where another order rounds differently
     v = np.zeros(128, np.float32)
     v[0], v[4], v[8], v[12] = 2.0 ** 27, 1.0, 1.0, 2.0 ** 27           # lane sums 2^54, 1, 1, 2^54
@@ -206,7 +214,7 @@ def test_previous_message_distance_in_bucket_scope(oracle):
 
 
 def test_fit_pooled_weights_from_the_definition(oracle):
-    """Bucket scope: W[bin(u)] += floor(sumsq_b * 2^(23 - e)) over the sampled coordinates, recomputed with numpy;
+    """Bucket scope: W[bin(u)] += floor(sumsq_b * 2^(23 - e)) over every coordinate, recomputed with numpy;
     vector scope with one layer equals the per-layer fit."""
     S, K = 8, 2
     sizes = [5000, 1300]
@@ -222,13 +230,10 @@ def test_fit_pooled_weights_from_the_definition(oracle):
         for l, s in enumerate(sizes):
             for b in range(0, s, 128):
                 sums[(k, l, b)] = oracle.bucket_sumsq(g[k][l][b: b + 128])
-                if (b // 256) % 4 == 0:                      # the scale comes from the sampled buckets
-                    smax = max(smax, sums[(k, l, b)])
+                smax = max(smax, sums[(k, l, b)])            # the scale comes from the heaviest bucket
     ex = int(np.floor(np.log2(smax)))
     W = np.zeros(257, dtype=np.uint64)
     for (k, l, b), sv in sums.items():
-        if (b // 256) % 4 != 0:
-            continue
         wfix = int(np.floor(np.ldexp(sv, 23 - ex)))
         inv = oracle.rcp_floor(oracle.sqrt_floor(sv))
         if wfix == 0 or inv == 0:
@@ -277,7 +282,7 @@ def test_statistics_gathered_while_quantizing_equal_the_explicit_fit(oracle):
     """Alg. 1 updates the levels before the round's vectors exist, so the estimate comes from the previous round:
     the pass that quantizes (bucket scope) gathers the same pooled weights as the explicit fit on those vectors when it
     is given the same scale, and the fit from the gathered statistics gives the same levels; the scale it hands on is
-    the exponent of the largest sampled bucket sum; without a scale nothing is gathered and the levels stay."""
+    the exponent of the largest bucket sum; without a scale nothing is gathered and the levels stay."""
     S, K = 8, 2
     sizes, types = [5000, 1300, 0, 70000], [0, 0, 1, 1]
     L = len(sizes)
@@ -286,7 +291,7 @@ def test_statistics_gathered_while_quantizing_equal_the_explicit_fit(oracle):
     flat = [g[k][l] for k in range(K) for l in range(L)]
     lev0 = [uniform_levels(S), uniform_levels(S)]
     want_lev, _, want_pooled, _ = oracle.fit_levels(sizes, types, [S, S], K, flat, lev0, scope=BUCKET)
-    # the explicit fit's scale: exponent of the largest sampled bucket sum of the type
+    # the explicit fit's scale: exponent of the largest bucket sum of the type
     exps = []
     for m in range(2):
         smax = 0.0
@@ -295,8 +300,7 @@ def test_statistics_gathered_while_quantizing_equal_the_explicit_fit(oracle):
                 if types[l] != m:
                     continue
                 for b in range(0, sizes[l], 128):
-                    if (b // 256) % 4 == 0:
-                        smax = max(smax, oracle.bucket_sumsq(g[k][l][b: b + 128]))
+                    smax = max(smax, oracle.bucket_sumsq(g[k][l][b: b + 128]))
         exps.append(int(np.floor(np.log2(smax))))
     lev_l = [lev0[types[l]] for l in range(L)]
     hist = np.zeros((K, L, 257), np.uint64)
@@ -318,5 +322,4 @@ def test_statistics_gathered_while_quantizing_equal_the_explicit_fit(oracle):
     assert all(np.array_equal(a, b) for a, b in zip(lev, lev0)) and list(e2) == exps
     # a scale from an earlier, much smaller round: weights hit the cap 2^30 instead of overflowing
     out = oracle.quantize(sizes, [S] * L, lev_l, g[0], 5, 1, 0, scope=BUCKET, stats_exp=[e - 40 for e in [exps[t] for t in types]])
-    sampled = sum(int(np.sum((np.arange(s) // 256) % 4 == 0)) for s in sizes)
-    assert (1 << 30) <= int(out[4].max()) and int(out[4].sum()) <= sampled * (1 << 30)
+    assert (1 << 30) <= int(out[4].max()) and int(out[4].sum()) <= sum(sizes) * (1 << 30)
