@@ -144,7 +144,12 @@ def main() -> int:
         if w.adaptive:
             # bucket scope: after the first round the fit uses the statistics gathered by the previous quantize pass
             # (the order of Alg. 1: the levels are updated before the round's vectors exist) and reads no gradient
-            ctx.fit_levels(gptrs if (not bucket or t == 1) else None, t)
+            # layer / vector scope: the fit runs on the round's own vectors (they exist by now on this device) and keeps
+            # their norms for the quantize call below
+            if bucket and t > 1:
+                ctx.fit_levels(None, t)
+            else:
+                ctx.fit_levels_keep_norms(gptrs, t)
         ctx.quantize_all(gptrs, t, msg_arr[cur], msg_arr[1 - cur] if (t > 1 and not alt) else None)
         if alt:
             ctx.step_alt(msg_arr[cur], x1p, yp, xhp, alt_sums, eta, args.q_hat, xnp)

@@ -16,10 +16,12 @@
  *     throws across this boundary.  Bad arguments are rejected before anything is launched.
  *   - A context is not thread-safe: use it from one host thread at a time, on one stream at a time.  It belongs to
  *     the device that was current in qoda_create; a call made with another device current returns QODA_EINVAL.
- *   - The library keeps a few device copies of every pointer array it is given; once each distinct set of arrays has
- *     been used, the calls of a round enqueue kernels (and, for the statistics-based fit, one device-to-device copy)
- *     only: no upload, no wait.  Such a steady-state round can be captured into a HIP graph; pointers and the round
- *     number are then fixed in the captured launches.  The calls that wait (see above) cannot be captured.
+ *   - Host arrays (pointer tables, levels) are consumed before a call returns: they reach the device as kernel
+ *     arguments, so no call copies from host memory later or waits for an earlier upload.  The library keeps a few
+ *     device copies of every K-wide pointer array it is given and recognises a set it has seen; the calls of a round
+ *     enqueue kernels (and, for the statistics-based fit, one device-to-device copy) only.  Such a round can be
+ *     captured into a HIP graph; pointers and the round number are then fixed in the captured launches.  The calls
+ *     that wait (see above) cannot be captured.
  *   - Non-finite input (a vector -- layer, whole dual vector or bucket, by scope -- whose sum of squares is not a
  *     finite number or whose norm exceeds FLT_MAX) sets a sticky device-side flag reported by qoda_status(); that
  *     vector's output is then unspecified (but in bounds).  A second flag marks a vector whose norm is positive but
@@ -94,7 +96,8 @@ typedef struct {
   int32_t num_types;          /* M >= 1 */
   const int32_t *type_points; /* S_m in [2, 256], host array [M], copied */
   int32_t num_nodes;          /* K >= 1, K <= 65535, and K * 2^(1+b_max) <= 16384 with b_max = ceil(log2 max_m S_m)
-                                 (the decode tables of all K nodes are kept in shared memory), else QODA_EINVAL */
+                                 (the decode tables of all K nodes are kept in shared memory), else QODA_EINVAL;
+                                 qoda_step_alt needs K * 2^(1+b_max) <= 15872 */
   int32_t norm_kind;          /* QODA_NORM_*: the q of the L^q normalisation */
   uint64_t seed;              /* key of the counter-based generator */
   int32_t norm_scope;         /* QODA_SCOPE_*: what one norm covers */
@@ -121,10 +124,9 @@ int qoda_get_levels(qoda_ctx *ctx, int32_t type, float *levels_host, void *strea
  * samples; every coordinate of (node, layer) weighs ||v_{k,l}||^2; layers of one type pool.  The distribution is
  * estimated by a histogram of every entry on its top 11 magnitude bits and the objective is minimised exactly
  * over level positions on a 257-point grid (3 mantissa bits per octave down to 2^-32).  A type whose vectors are
- * all zero keeps its levels.  grad_dev: host array [K*L], entry k*L+l.
- * Side effect: the per-(node, layer) norms of these vectors stay in the context tagged with `round`; a following
- * qoda_quantize / qoda_quantize_all with the same `round` and the same pointers reuses them instead of reading
- * the vectors a second time.  The caller must not change the vectors in between.
+ * all zero keeps its levels.  grad_dev: host array [K*L], entry k*L+l.  Alg. 1 places the update before the round's
+ * vectors exist, so the vectors given here are normally the previous round's; the quantize calls that follow compute
+ * their own norms from whatever they are given (see qoda_fit_levels_keep_norms for the other case).
  * Bucket scope: every bucket is a vector of its own (weight = its sum of squares, normalisation = its norm); with
  * grad_dev the fit takes two passes over these vectors (scale of the weights, then the weighted grid histogram).  With grad_dev == NULL (bucket scope only) it reads nothing: it uses the statistics that the last
  * quantize pass of every node gathered while it quantized -- Alg. 1 runs lines 3-5 before the round's vectors exist,
@@ -133,6 +135,15 @@ int qoda_get_levels(qoda_ctx *ctx, int32_t type, float *levels_host, void *strea
  * histogram only once some fit has produced a scale: call the fit with vectors once (or with NULL twice, the first of
  * which only sets the scale), then with NULL at every later update step. */
 int qoda_fit_levels(qoda_ctx *ctx, const float *const *grad_dev, uint32_t round, void *stream);
+
+/* The same fit for a caller who fits on the round's own vectors (layer and vector scope; under bucket scope identical
+ * to qoda_fit_levels).  Calling it DECLARES that grad_dev holds exactly what the qoda_quantize / qoda_quantize_all
+ * calls of the same `round` will be given, unchanged: the norms computed here on the way stay in the context, and such
+ * a call with the same `round` and the same pointers skips its norm pass (one read of the vectors less per round).
+ * A caller who rewrites the buffers in between gets messages scaled by stale norms; the library cannot see that.
+ * Anything else -- another round number, other pointers, any other fit call -- drops the kept norms.
+ * grad_dev must not be NULL. */
+int qoda_fit_levels_keep_norms(qoda_ctx *ctx, const float *const *grad_dev, uint32_t round, void *stream);
 
 /* ENCODE(Q(V_{k,t+1/2})), Alg. 1 line 12 (Sec. 2.2, 3.1, 3.2): per-layer L2 norm, u = min(|v| / ||v||, 1), level
  * search, stochastic rounding with one 16-bit counter-based draw per coordinate (counter = coordinate, layer,
@@ -212,7 +223,8 @@ typedef struct {
  * q_hat is used to 32 binary digits; the power is built from square roots (no library pow), so the rates are
  * reproducible bit for bit.  Of the two forms the paper prints for lambda (sum of the K squared norms in the main
  * text and in the appendix's choice of rates; squared norm of the sum in the appendix's lemma notation) the first is
- * taken.  Errors: QODA_EINVAL for q_hat outside (0, 1/4] or below 2^-32, null sums_dev or eta_dev. */
+ * taken.  Errors: QODA_EINVAL for q_hat outside (0, 1/4] or below 2^-32, null sums_dev or eta_dev, or
+ * K * 2^(1+b_max) > 15872 (this pass keeps a reduction buffer in shared memory beside the decode tables). */
 int qoda_step_alt(qoda_ctx *ctx, const void *const *msgs_dev, const qoda_alt_state *state, double q_hat, void *stream);
 
 /* DECODE + mean + one plain step: out[l][e] = x[l][e] - gamma * mean[l][e] (two fp32 operations), mean as in

@@ -84,7 +84,7 @@ def main() -> int:
 
     def qoda_round(t=1):
         cur = state["cur"]
-        ctx.fit_levels(gptrs, t)
+        ctx.fit_levels_keep_norms(gptrs, t)
         ctx.quantize_all(gptrs, t, msg[cur], msg[1 - cur] if t > 1 else None)
         ctx.step(msg[cur], ptrs(x), ptrs(y), ptrs(xh), acc, None, eta)
         state["cur"] = 1 - cur
@@ -100,7 +100,7 @@ def main() -> int:
     msg1 = [torch.zeros(mb, dtype=torch.uint8, device=dev) for _ in range(K)]
 
     def eg_round(t=1):
-        ctx.fit_levels(gptrs, 2 * t)
+        ctx.fit_levels_keep_norms(gptrs, 2 * t)
         for leg in (0, 1):                                # the same synthetic vectors stand in for both operator calls
             ctx.quantize_all(gptrs, 2 * t + leg, msg1, None)
             ctx.extrapolate(msg1, ptrs(x), ptrs(xh if leg == 0 else x), gamma)

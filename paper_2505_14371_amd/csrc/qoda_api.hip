@@ -69,13 +69,11 @@ struct qoda_ctx {
     bool valid() const { return slots[cur].valid; }
   };
   Table t_grad, t_msg, t_prev, t_in, t_x1, t_y, t_xh, t_xn, t_mean;
-  hipEvent_t upload_done = nullptr;
-  bool upload_pending = false;
-  // norm cache left by qoda_fit_levels
+  void **d_node_tab = nullptr;   // per-node calls: L layer pointers, then the message and the previous message
+  // norms kept by qoda_fit_levels_keep_norms for the quantize calls of the same round on the same vectors
   bool norms_valid = false;
   uint32_t norms_round = 0;
   std::vector<const float *> norms_grad;
-  std::vector<float> h_lev;   // host shadow of the level tables (source of asynchronous uploads)
   // optional per-kernel event timing
   struct ProfRec { int id; hipEvent_t a, b; };
   unsigned int prof_mask = 0;   // bit i: time kernel class i
@@ -97,10 +95,9 @@ constexpr size_t kOffDpartial = kOffPartial + 8 * kNoallocMaxTiles;        // do
 constexpr size_t kOffSumsq = kOffDpartial + 8 * kNoallocMaxTiles;          // double[layers]
 constexpr size_t kOffNorm = kOffSumsq + 8 * kNoallocMaxLayers;             // float[layers]
 constexpr size_t kOffInv = kOffNorm + 4 * kNoallocMaxLayers;               // float[layers]
-constexpr size_t kOffGrad = kOffInv + 4 * kNoallocMaxLayers;               // pointer[layers] the node's layers
-constexpr size_t kOffMsg = kOffGrad + 8 * kNoallocMaxLayers;               // pointer[1]      the message
-constexpr size_t kOffPrev = kOffMsg + 256;                                 // pointer[1]      the previous message
-constexpr size_t kScratchBytes = kOffPrev + 256;
+constexpr size_t kOffTab = kOffInv + 4 * kNoallocMaxLayers;                // pointer[layers + 2] the node's layers, its
+                                                                           // message, its previous message
+constexpr size_t kScratchBytes = kOffTab + 8 * (kNoallocMaxLayers + 2) + 240;
 constexpr int kMaxDevices = 64;
 }  // namespace
 
@@ -141,10 +138,13 @@ int guarded(qoda_ctx *c, F &&body) {
   try {
     return body();
   } catch (const std::bad_alloc &) {
-    if (c) c->err.clear();   // no allocation on this path
+    if (c) c->err.clear();   // no allocation on this path: the code alone says what happened
     return QODA_ENOMEM;
   } catch (...) {
-    if (c) c->err.clear();
+    // nothing in the library throws anything else on purpose; say so rather than leaving the last message standing
+    if (c) {
+      try { c->err = "internal exception"; } catch (...) { c->err.clear(); }
+    }
     return QODA_EHIP;
   }
 }
@@ -171,10 +171,12 @@ hipError_t prof_event(qoda_ctx *c, hipEvent_t *e) {
 }
 
 // Enqueue one kernel class; with profiling on, bracket it with two events on the same stream.
-#define LAUNCH(c, id, s, call)                                                   \
+#define LAUNCH(c, id, s, call) LAUNCH_IF(c, true, id, s, call)
+// The same; with may_time false the launch is never timed (the calls that must not create events).
+#define LAUNCH_IF(c, may_time, id, s, call)                                      \
   do {                                                                           \
     qoda_ctx::ProfRec r_{(id), nullptr, nullptr};                                \
-    const bool timed_ = (((c)->prof_mask >> (id)) & 1u) != 0u;                  \
+    const bool timed_ = (may_time) && (((c)->prof_mask >> (id)) & 1u) != 0u;    \
     if (timed_) {                                                                \
       HIP_TRY((c), prof_event((c), &r_.a));                                      \
       HIP_TRY((c), prof_event((c), &r_.b));                                      \
@@ -200,7 +202,7 @@ hipError_t dev_alloc(T **p, size_t n) {
   return hipMalloc(reinterpret_cast<void **>(p), (n ? n : 1) * sizeof(T));
 }
 
-// Upload a table of device pointers if it differs from what the device copy holds.
+// Make a table of device pointers current on the device if none of its cached copies holds this set already.
 int sync_table(qoda_ctx *c, qoda_ctx::Table &t, const void *const *src, size_t n, hipStream_t s) {
   int victim = 0;
   for (int q = 0; q < qoda_ctx::Table::kSlots; ++q) {
@@ -213,17 +215,12 @@ int sync_table(qoda_ctx *c, qoda_ctx::Table &t, const void *const *src, size_t n
     if (!sl.valid) victim = q;
     else if (t.slots[victim].valid && sl.stamp < t.slots[victim].stamp) victim = q;
   }
-  if (c->upload_pending) {   // an earlier asynchronous upload may still be reading a host shadow
-    HIP_TRY(c, hipEventSynchronize(c->upload_done));
-    c->upload_pending = false;
-  }
   qoda_ctx::Table::Slot &sl = t.slots[victim];
   sl.host.resize(n);
-  std::memcpy(sl.host.data(), src, n * sizeof(void *));
+  std::memcpy(sl.host.data(), src, n * sizeof(void *));   // kept only to recognise the same set next time
   sl.n = n;
-  HIP_TRY(c, hipMemcpyAsync(sl.dev, sl.host.data(), n * sizeof(void *), hipMemcpyHostToDevice, s));
-  HIP_TRY(c, hipEventRecord(c->upload_done, s));
-  c->upload_pending = true;
+  sl.valid = false;
+  HIP_TRY(c, launch_stage_pointers(sl.dev, src, n, s));   // through kernel arguments: nothing to wait for
   sl.valid = true;
   sl.stamp = ++t.clock;
   t.cur = victim;
@@ -284,14 +281,13 @@ int check_msg_ptrs(qoda_ctx *c, const void *const *p, size_t n, const char *what
 void free_all(qoda_ctx *c) {
   void *ptrs[] = {c->d_meta, c->d_tiles, c->d_stiles, c->d_empty, c->d_type_points, c->d_partial, c->d_dpartial, c->d_sumsq, c->d_delta,
                   c->d_norm, c->d_inv, c->d_lev, c->d_rgap, c->d_eta, c->d_lut, c->d_hist, c->d_status, c->d_pooled, c->d_index_counts, c->d_type_exp_next,
-                  c->d_type_exp, c->d_dp_arg, c->d_dp_arg_off};
+                  c->d_type_exp, c->d_dp_arg, c->d_dp_arg_off, c->d_node_tab};
   for (void *p : ptrs)
     if (p) (void)hipFree(p);
   qoda_ctx::Table *tabs[] = {&c->t_grad, &c->t_msg, &c->t_prev, &c->t_in, &c->t_x1, &c->t_y, &c->t_xh, &c->t_xn, &c->t_mean};
   for (qoda_ctx::Table *t : tabs)
     for (auto &sl : t->slots)
       if (sl.dev) (void)hipFree(sl.dev);
-  if (c->upload_done) (void)hipEventDestroy(c->upload_done);
   for (auto &r : c->prof_recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
   for (hipEvent_t e : c->prof_pool) (void)hipEventDestroy(e);
 }
@@ -304,7 +300,8 @@ int run_norm_pass(qoda_ctx *c, Dev a, bool with_hist, hipStream_t s) {
   return QODA_OK;
 }
 
-int quantize_impl(qoda_ctx *c, int node0, int nnodes, const float *const *grad_full /* K*L shadow */, uint32_t round,
+// All nodes in one set of launches, from the K-wide tables already on the device.
+int quantize_impl(qoda_ctx *c, int node0, int nnodes, const float *const *grad_full /* K*L */, uint32_t round,
                   hipStream_t s, bool have_prev) {
   Dev a = base_args(c);
   a.grad = reinterpret_cast<const float *const *>(c->t_grad.dev());
@@ -381,7 +378,6 @@ static int create_impl(const qoda_config *cfg, qoda_ctx *c) {
   }
   c->message_bytes = round_up(off, 256);
   c->G = (int)chunks;
-  c->h_lev.assign((size_t)c->M * kMaxPoints, 0.0f);
 
   std::vector<int2> tiles((size_t)c->G);
   for (int l = 0; l < c->L; ++l)
@@ -430,7 +426,7 @@ static int create_impl(const qoda_config *cfg, qoda_ctx *c) {
   const size_t tab_n[] = {KL, (size_t)c->K, (size_t)c->K, (size_t)c->K, (size_t)c->L, (size_t)c->L, (size_t)c->L, (size_t)c->L, (size_t)c->L};
   for (int i = 0; i < 9; ++i)
     for (auto &sl : tabs[i]->slots) A(dev_alloc(&sl.dev, tab_n[i]));
-  A(hipEventCreateWithFlags(&c->upload_done, hipEventDisableTiming));
+  A(dev_alloc(&c->d_node_tab, (size_t)c->L + 64));
   if (e == hipSuccess) A(hipMemcpy(c->d_meta, c->meta.data(), c->L * sizeof(LayerMeta), hipMemcpyHostToDevice));
   if (e == hipSuccess && c->G) A(hipMemcpy(c->d_tiles, tiles.data(), c->G * sizeof(int2), hipMemcpyHostToDevice));
   if (e == hipSuccess && c->GS) A(hipMemcpy(c->d_stiles, stiles.data(), c->GS * sizeof(int4), hipMemcpyHostToDevice));
@@ -513,15 +509,7 @@ int qoda_set_levels(qoda_ctx *c, int32_t type, const float *lev, void *stream) {
     for (int j = 0; j + 1 < S; ++j)
       if (!(lev[j] < lev[j + 1])) return fail(c, QODA_EINVAL, "qoda_set_levels: levels must be strictly increasing");
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (c->upload_pending) {   // an earlier asynchronous upload may still be reading a host shadow
-      HIP_TRY(c, hipEventSynchronize(c->upload_done));
-      c->upload_pending = false;
-    }
-    float *shadow = c->h_lev.data() + (size_t)type * kMaxPoints;
-    std::memcpy(shadow, lev, S * sizeof(float));
-    HIP_TRY(c, hipMemcpyAsync(c->d_lev + (size_t)type * kMaxPoints, shadow, S * sizeof(float), hipMemcpyHostToDevice, s));
-    HIP_TRY(c, hipEventRecord(c->upload_done, s));
-    c->upload_pending = true;
+    HIP_TRY(c, launch_stage_words(c->d_lev + (size_t)type * kMaxPoints, lev, (size_t)S, s));
     Dev a = base_args(c);
     LAUNCH(c, kIdBuildTables, s, launch_build_tables(a, type, s));
     return QODA_OK;
@@ -541,8 +529,7 @@ int qoda_get_levels(qoda_ctx *c, int32_t type, float *lev, void *stream) {
   });
 }
 
-int qoda_fit_levels(qoda_ctx *c, const float *const *grad_dev, uint32_t round, void *stream) {
-  if (!c) return QODA_EINVAL;
+static int fit_levels_impl(qoda_ctx *c, const float *const *grad_dev, uint32_t round, void *stream, bool keep_norms) {
   return guarded(c, [&]() -> int {
     if (const int rc_ = check_device(c)) return rc_;
     const size_t KL = (size_t)c->K * c->L;
@@ -585,11 +572,24 @@ int qoda_fit_levels(qoda_ctx *c, const float *const *grad_dev, uint32_t round, v
     LAUNCH(c, kIdFitTypemax, s, launch_fit_typemax(a, s));
     LAUNCH(c, kIdFitPool, s, launch_fit_pool(a, s));
     LAUNCH(c, kIdFitDp, s, launch_fit_dp(a, s));
-    c->norms_grad.assign(grad_dev, grad_dev + KL);
-    c->norms_round = round;
-    c->norms_valid = true;
+    if (keep_norms) {   // the caller has declared that these are the vectors the round's quantize calls will be given
+      c->norms_grad.assign(grad_dev, grad_dev + KL);
+      c->norms_round = round;
+      c->norms_valid = true;
+    }
     return QODA_OK;
   });
+}
+
+int qoda_fit_levels(qoda_ctx *c, const float *const *grad_dev, uint32_t round, void *stream) {
+  if (!c) return QODA_EINVAL;
+  return fit_levels_impl(c, grad_dev, round, stream, false);
+}
+
+int qoda_fit_levels_keep_norms(qoda_ctx *c, const float *const *grad_dev, uint32_t round, void *stream) {
+  if (!c) return QODA_EINVAL;
+  if (!grad_dev) return fail(c, QODA_EINVAL, "qoda_fit_levels_keep_norms: needs the round's vectors");
+  return fit_levels_impl(c, grad_dev, round, stream, true);
 }
 
 int qoda_quantize_all(qoda_ctx *c, const float *const *grad_dev, uint32_t round, void *const *msg_dev,
@@ -621,40 +621,80 @@ int qoda_quantize_all(qoda_ctx *c, const float *const *grad_dev, uint32_t round,
   });
 }
 
+// One node through tables and scratch rows of its own (row0 = node): shared by qoda_quantize (rows of the context's
+// buffers, norms may be reused, launches may be timed) and qoda_quantize_noalloc (the static array, neither).
+struct NodeBuffers {
+  void **tab;   // L layer pointers, then the message pointer, then the previous message pointer
+  double *partial, *dpartial, *sumsq;
+  float *norm, *inv;
+};
+
+static int quantize_node(qoda_ctx *c, int32_t node, const float *const *grad_dev, uint32_t round, void *msg_dev,
+                         const void *msg_prev_dev, hipStream_t s, const NodeBuffers &nb, bool of_context,
+                         const char *who) {
+  char what[96];   // names for the error messages, built on the stack: this path must not allocate
+  if (node < 0 || node >= c->K) return fail(c, QODA_EINVAL, "%s: node %d out of range", who, node);
+  snprintf(what, sizeof what, "%s: grad_dev", who);
+  int rc = check_layer_ptrs(c, reinterpret_cast<const void *const *>(grad_dev), c->L, what, true);
+  if (rc) return rc;
+  const void *mp[1] = {msg_dev};
+  snprintf(what, sizeof what, "%s: msg_dev", who);
+  rc = check_msg_ptrs(c, mp, 1, what, false);
+  if (rc) return rc;
+  const void *pp[1] = {msg_prev_dev};
+  snprintf(what, sizeof what, "%s: msg_prev_dev", who);
+  rc = check_msg_ptrs(c, pp, 1, what, true);
+  if (rc) return rc;
+  if (msg_prev_dev == msg_dev) return fail(c, QODA_EINVAL, "%s: msg_prev_dev aliases msg_dev", who);
+  // the node's pointers reach the device as kernel arguments: no staging buffer, no copy, nothing to wait for
+  HIP_TRY(c, launch_stage_pointers(nb.tab, reinterpret_cast<const void *const *>(grad_dev), (size_t)c->L, s));
+  HIP_TRY(c, launch_stage_pointers(nb.tab + c->L, mp, 1, s));
+  HIP_TRY(c, launch_stage_pointers(nb.tab + c->L + 1, pp, 1, s));
+  Dev a = base_args(c);
+  a.grad = reinterpret_cast<const float *const *>(nb.tab);
+  a.msg = reinterpret_cast<unsigned char *const *>(nb.tab + c->L);
+  a.prev = msg_prev_dev ? reinterpret_cast<const unsigned char *const *>(nb.tab + c->L + 1) : nullptr;
+  a.partial = nb.partial;
+  a.dpartial = nb.dpartial;
+  a.round = round;
+  a.node0 = node;
+  a.nnodes = 1;
+  a.row0 = node;   // the tables and scratch rows above are this node's only
+  if (c->scope == kScopeBucket) {
+    // the bucket norms are computed by the quantize kernel, which also gathers this node's fit statistics into the
+    // context (state of the next fit, not scratch): their histograms and running maxima start from zero
+    const size_t n0 = (size_t)node * c->L, nn = (size_t)c->L;
+    LAUNCH_IF(c, of_context, kIdZero, s, launch_zero_u32(c->d_hist + n0 * kHistBins, nn * kHistBins, s));
+    LAUNCH_IF(c, of_context, kIdZero, s, launch_zero_u32(reinterpret_cast<unsigned int *>(c->d_sumsq + n0), 2 * nn, s));
+  } else {
+    a.sumsq = nb.sumsq;
+    a.norm = nb.norm;
+    a.inv = nb.inv;
+    bool kept = of_context && c->norms_valid && c->norms_round == round;
+    for (int l = 0; l < c->L && kept; ++l) kept = c->norms_grad[(size_t)node * c->L + l] == grad_dev[l];
+    if (!kept) {
+      if (of_context) c->norms_valid = false;   // this node's kept norms are about to be overwritten
+      LAUNCH_IF(c, of_context, kIdSumsq, s, launch_sumsq(a, false, s));
+      LAUNCH_IF(c, of_context, kIdNormFinalize, s, launch_norm_finalize(a, s));
+      if (c->scope == kScopeVector) LAUNCH_IF(c, of_context, kIdNormVector, s, launch_norm_vector(a, s));
+    }
+  }
+  LAUNCH_IF(c, of_context, kIdQuantize, s, launch_quantize(a, c->planes_mask, s));
+  LAUNCH_IF(c, of_context, kIdDeltaFinalize, s, launch_delta_finalize(a, s));
+  return QODA_OK;
+}
+
 int qoda_quantize(qoda_ctx *c, int32_t node, const float *const *grad_dev, uint32_t round, void *msg_dev,
                   const void *msg_prev_dev, void *stream) {
   if (!c) return QODA_EINVAL;
   return guarded(c, [&]() -> int {
     if (const int rc_ = check_device(c)) return rc_;
     if (node < 0 || node >= c->K) return fail(c, QODA_EINVAL, "qoda_quantize: node %d out of range", node);
-    int rc = check_layer_ptrs(c, reinterpret_cast<const void *const *>(grad_dev), c->L, "qoda_quantize: grad_dev", true);
-    if (rc) return rc;
-    const void *mp[1] = {msg_dev};
-    rc = check_msg_ptrs(c, mp, 1, "qoda_quantize: msg_dev", false);
-    if (rc) return rc;
-    const void *pp[1] = {msg_prev_dev};
-    rc = check_msg_ptrs(c, pp, 1, "qoda_quantize: msg_prev_dev", true);
-    if (rc) return rc;
-    if (msg_prev_dev == msg_dev) return fail(c, QODA_EINVAL, "qoda_quantize: msg_prev_dev aliases msg_dev");
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    // splice this node's pointers into full-size shadows of the K*L / K tables
-    const size_t KL = (size_t)c->K * c->L;
-    std::vector<void *> g(c->t_grad.valid() ? c->t_grad.host() : std::vector<void *>(KL, nullptr));
-    g.resize(KL, nullptr);
-    for (int l = 0; l < c->L; ++l) g[(size_t)node * c->L + l] = const_cast<float *>(grad_dev[l]);
-    std::vector<void *> m(c->t_msg.valid() ? c->t_msg.host() : std::vector<void *>(c->K, nullptr));
-    m.resize(c->K, nullptr);
-    m[node] = msg_dev;
-    std::vector<void *> p(c->t_prev.valid() ? c->t_prev.host() : std::vector<void *>(c->K, nullptr));
-    p.resize(c->K, nullptr);
-    p[node] = const_cast<void *>(msg_prev_dev);
-    rc = sync_table(c, c->t_grad, g.data(), KL, s);
-    if (rc) return rc;
-    rc = sync_table(c, c->t_msg, m.data(), c->K, s);
-    if (rc) return rc;
-    rc = sync_table(c, c->t_prev, p.data(), c->K, s);
-    if (rc) return rc;
-    return quantize_impl(c, node, 1, reinterpret_cast<const float *const *>(c->t_grad.host().data()), round, s, true);
+    const size_t rowL = (size_t)node * c->L, rowG = (size_t)node * c->G;
+    const NodeBuffers nb = {c->d_node_tab, c->d_partial + rowG, c->d_dpartial + rowG, c->d_sumsq + rowL,
+                            c->d_norm + rowL, c->d_inv + rowL};
+    return quantize_node(c, node, grad_dev, round, msg_dev, msg_prev_dev, static_cast<hipStream_t>(stream), nb, true,
+                         "qoda_quantize");
   });
 }
 
@@ -663,57 +703,17 @@ int qoda_quantize_noalloc(qoda_ctx *c, int32_t node, const float *const *grad_de
   if (!c) return QODA_EINVAL;
   return guarded(c, [&]() -> int {
     if (const int rc_ = check_device(c)) return rc_;
-    if (node < 0 || node >= c->K) return fail(c, QODA_EINVAL, "qoda_quantize_noalloc: node %d out of range", node);
-    int rc = check_layer_ptrs(c, reinterpret_cast<const void *const *>(grad_dev), c->L, "qoda_quantize_noalloc: grad_dev", true);
-    if (rc) return rc;
-    const void *mp[1] = {msg_dev};
-    rc = check_msg_ptrs(c, mp, 1, "qoda_quantize_noalloc: msg_dev", false);
-    if (rc) return rc;
-    const void *pp[1] = {msg_prev_dev};
-    rc = check_msg_ptrs(c, pp, 1, "qoda_quantize_noalloc: msg_prev_dev", true);
-    if (rc) return rc;
-    if (msg_prev_dev == msg_dev) return fail(c, QODA_EINVAL, "qoda_quantize_noalloc: msg_prev_dev aliases msg_dev");
     if ((size_t)c->L > kNoallocMaxLayers || (size_t)c->G > kNoallocMaxTiles)
       return fail(c, QODA_EINVAL,
                   "qoda_quantize_noalloc: %d layers and %d tiles of 16384 coordinates exceed the static scratch "
                   "(at most %zu layers and %zu tiles per node)", c->L, c->G, kNoallocMaxLayers, kNoallocMaxTiles);
     unsigned char *sp = (c->device >= 0 && c->device < kMaxDevices) ? g_scratch_ptr[c->device] : nullptr;
     if (!sp) return fail(c, QODA_EHIP, "qoda_quantize_noalloc: no static scratch on device %d", c->device);
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    // the node's pointers reach the device as kernel arguments: no staging buffer, no copy
-    void **t_grad = reinterpret_cast<void **>(sp + kOffGrad);
-    void **t_msg = reinterpret_cast<void **>(sp + kOffMsg);
-    void **t_prev = reinterpret_cast<void **>(sp + kOffPrev);
-    HIP_TRY(c, launch_stage_pointers(t_grad, reinterpret_cast<const void *const *>(grad_dev), (size_t)c->L, s));
-    HIP_TRY(c, launch_stage_pointers(t_msg, mp, 1, s));
-    HIP_TRY(c, launch_stage_pointers(t_prev, pp, 1, s));
-    Dev a = base_args(c);
-    a.partial = reinterpret_cast<double *>(sp + kOffPartial);
-    a.dpartial = reinterpret_cast<double *>(sp + kOffDpartial);
-    a.grad = reinterpret_cast<const float *const *>(t_grad);
-    a.msg = reinterpret_cast<unsigned char *const *>(t_msg);
-    a.prev = msg_prev_dev ? reinterpret_cast<const unsigned char *const *>(t_prev) : nullptr;
-    a.round = round;
-    a.node0 = node;
-    a.nnodes = 1;
-    a.row0 = node;   // the tables above hold this node's rows only
-    if (c->scope == kScopeBucket) {
-      // the bucket norms are computed by the quantize kernel, which also gathers this node's fit statistics into the
-      // context (they are state of the next fit, not scratch): they start from zero
-      const size_t n0 = (size_t)node * c->L, nn = (size_t)c->L;
-      HIP_TRY(c, launch_zero_u32(c->d_hist + n0 * kHistBins, nn * kHistBins, s));
-      HIP_TRY(c, launch_zero_u32(reinterpret_cast<unsigned int *>(c->d_sumsq + n0), 2 * nn, s));
-    } else {
-      a.sumsq = reinterpret_cast<double *>(sp + kOffSumsq);
-      a.norm = reinterpret_cast<float *>(sp + kOffNorm);
-      a.inv = reinterpret_cast<float *>(sp + kOffInv);
-      HIP_TRY(c, launch_sumsq(a, false, s));
-      HIP_TRY(c, launch_norm_finalize(a, s));
-      if (c->scope == kScopeVector) HIP_TRY(c, launch_norm_vector(a, s));
-    }
-    HIP_TRY(c, launch_quantize(a, c->planes_mask, s));
-    HIP_TRY(c, launch_delta_finalize(a, s));
-    return QODA_OK;
+    const NodeBuffers nb = {reinterpret_cast<void **>(sp + kOffTab), reinterpret_cast<double *>(sp + kOffPartial),
+                            reinterpret_cast<double *>(sp + kOffDpartial), reinterpret_cast<double *>(sp + kOffSumsq),
+                            reinterpret_cast<float *>(sp + kOffNorm), reinterpret_cast<float *>(sp + kOffInv)};
+    return quantize_node(c, node, grad_dev, round, msg_dev, msg_prev_dev, static_cast<hipStream_t>(stream), nb, false,
+                         "qoda_quantize_noalloc");
   });
 }
 
@@ -936,6 +936,10 @@ int qoda_step_alt(qoda_ctx *c, const void *const *msgs_dev, const qoda_alt_state
     if (!(q_hat > 0.0) || !(q_hat <= 0.25)) return fail(c, QODA_EINVAL, "qoda_step_alt: the exponent must lie in (0, 1/4]");
     const double digits = std::floor(std::ldexp(q_hat, 32));
     if (digits < 1.0) return fail(c, QODA_EINVAL, "qoda_step_alt: the exponent is below 2^-32");
+    // this pass keeps a 2 KiB reduction buffer in shared memory beside the K decode tables
+    if ((size_t)c->K * c->maxSP * sizeof(float) + kThreads * sizeof(double) > 64 * 1024)
+      return fail(c, QODA_EINVAL, "qoda_step_alt: K * 2^(1+b) = %zu exceeds 15872 (decode tables plus the reduction "
+                                  "buffer of this pass must fit 64 KiB of shared memory)", (size_t)c->K * c->maxSP);
     hipStream_t s = static_cast<hipStream_t>(stream);
     Dev a = base_args(c);
     const int rc = step_common(c, msgs_dev, st->x1_dev, st->y_dev, st->x_half_dev, st->x_next_dev, a, s, "qoda_step_alt");

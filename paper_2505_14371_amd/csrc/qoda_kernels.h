@@ -123,7 +123,9 @@ hipError_t launch_fit_pool(const Dev &a, hipStream_t s);
 hipError_t launch_fit_dp(const Dev &a, hipStream_t s);
 hipError_t launch_copy(const void *src, void *dst, size_t bytes, hipStream_t s);
 hipError_t launch_build_tables(const Dev &a, int type, hipStream_t s);
-// Copy n pointers from a host array into device memory through kernel arguments (no staging buffer, no copy engine).
+// Copy a small host array (32-bit words; pointers) into device memory through kernel arguments: no staging buffer, no
+// copy engine, and the host array may be reused as soon as the call returns.
+hipError_t launch_stage_words(void *dst_dev, const void *src_host, size_t nwords, hipStream_t s);
 hipError_t launch_stage_pointers(void **dst_dev, const void *const *src_host, size_t n, hipStream_t s);
 
 }  // namespace qoda

@@ -1530,25 +1530,33 @@ __global__ void __launch_bounds__(kThreads) k_copy_f4(const float4 *__restrict__
   for (; i < n; i += stride) dst[i] = src[i];
 }
 
-// ------------------------------------------------------------------------------------------------ pointer staging
-// Up to kPackPointers pointers travel as kernel arguments and are written to a device table by the kernel itself.
-constexpr int kPackPointers = 128;
-struct PointerPack { void *p[kPackPointers]; };
+// ------------------------------------------------------------------------------------------------ staging
+// Small host arrays (pointer tables, level values) reach the device as kernel arguments and are written to their device
+// table by the kernel itself: no staging buffer, no copy engine, no host memory that must outlive the call.
+constexpr int kPackWords = 256;
+struct WordPack { unsigned int w[kPackWords]; };
 
-__global__ void __launch_bounds__(kPackPointers) k_stage_pointers(void **dst, PointerPack pack, int n) {
+__global__ void __launch_bounds__(kPackWords) k_stage_words(unsigned int *dst, WordPack pack, int n) {
   const int t = threadIdx.x;
-  if (t < n) dst[t] = pack.p[t];
+  if (t < n) dst[t] = pack.w[t];
 }
 
 // ------------------------------------------------------------------------------------------------ launchers
-hipError_t launch_stage_pointers(void **dst_dev, const void *const *src_host, size_t n, hipStream_t s) {
-  for (size_t q = 0; q < n; q += kPackPointers) {
-    PointerPack pack;
-    const int m = (int)(n - q < (size_t)kPackPointers ? n - q : (size_t)kPackPointers);
-    for (int j = 0; j < kPackPointers; ++j) pack.p[j] = j < m ? const_cast<void *>(src_host[q + j]) : nullptr;
-    hipLaunchKernelGGL(k_stage_pointers, dim3(1), dim3(kPackPointers), 0, s, dst_dev + q, pack, m);
+hipError_t launch_stage_words(void *dst_dev, const void *src_host, size_t nwords, hipStream_t s) {
+  const unsigned int *src = static_cast<const unsigned int *>(src_host);
+  unsigned int *dst = static_cast<unsigned int *>(dst_dev);
+  for (size_t q = 0; q < nwords; q += kPackWords) {
+    WordPack pack;
+    const int m = (int)(nwords - q < (size_t)kPackWords ? nwords - q : (size_t)kPackWords);
+    for (int j = 0; j < kPackWords; ++j) pack.w[j] = j < m ? src[q + j] : 0u;
+    hipLaunchKernelGGL(k_stage_words, dim3(1), dim3(kPackWords), 0, s, dst + q, pack, m);
   }
   return hipGetLastError();
+}
+
+hipError_t launch_stage_pointers(void **dst_dev, const void *const *src_host, size_t n, hipStream_t s) {
+  static_assert(sizeof(void *) == 2 * sizeof(unsigned int), "a pointer is two words");
+  return launch_stage_words(dst_dev, src_host, 2 * n, s);
 }
 
 hipError_t launch_copy(const void *src, void *dst, size_t bytes, hipStream_t s) {

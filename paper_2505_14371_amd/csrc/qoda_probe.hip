@@ -123,7 +123,10 @@ int main(int argc, char **argv) {
       CK(hipEventRecord(e0, 0));
     }
     // bucket scope: after the first round the fit uses the statistics gathered by the previous quantize pass
-    if (adaptive) QK(qoda_fit_levels(ctx, (scope == QODA_SCOPE_BUCKET && t > 1) ? nullptr : gp.data(), (uint32_t)t, nullptr));
+    if (adaptive) {
+      if (scope == QODA_SCOPE_BUCKET && t > 1) QK(qoda_fit_levels(ctx, nullptr, (uint32_t)t, nullptr));
+      else QK(qoda_fit_levels_keep_norms(ctx, gp.data(), (uint32_t)t, nullptr));   // the round's own vectors
+    }
     QK(qoda_quantize_all(ctx, gp.data(), (uint32_t)t, msg.data() + cur * K,
                          (t > 1 && q_hat <= 0.0) ? (const void *const *)(msg.data() + (1 - cur) * K) : nullptr, nullptr));
     if (q_hat > 0.0) QK(qoda_step_alt(ctx, (const void *const *)(msg.data() + cur * K), &ast, q_hat, nullptr));

@@ -89,7 +89,10 @@ class QODA:
         t, cur = self.t, self.t & 1
         if self.fit_every > 0 and (t - 1) % self.fit_every == 0:
             # bucket scope after the first fit: from the statistics the previous quantize pass gathered
-            self.ctx.fit_levels(None if (self.norm_scope == qoda.SCOPE_BUCKET and t > 1) else gp, t, stream=stream)
+            if self.norm_scope == qoda.SCOPE_BUCKET and t > 1:
+                self.ctx.fit_levels(None, t, stream=stream)
+            else:                                    # the round's own vectors, quantized unchanged right below
+                self.ctx.fit_levels_keep_norms(gp, t, stream=stream)
         alt = self.q_hat is not None
         prev = self._p_msg[1 - cur] if (t > 1 and not alt) else None
         self.ctx.quantize_all(gp, t, self._p_msg[cur], prev, stream=stream)

@@ -139,3 +139,46 @@ def test_argument_errors_of_the_added_entry_points():
     with pytest.raises(qoda.QodaError):
         m.ctx.index_counts([m.msg[0][0], None])
     assert m.ctx.status() == qoda.OK
+
+
+def test_largest_node_count_under_the_alternative_rule(oracle):
+    """eq. (Alt)'s fused pass keeps a 2 KiB reduction buffer beside the decode tables: its limit is K * 2^(1+b) = 15872
+    (K = 3968 nodes of two grid points), exercised here; at 16384, which the main rule admits, it is refused with a
+    message instead of failing to launch."""
+    sizes, S, K, q = [2100, 16384 + 77], 2, 3968, 0.25
+    L = len(sizes)
+    rng = np.random.default_rng(1)
+    x1 = [rng.standard_normal(s).astype(np.float32) for s in sizes]
+    m = gm(sizes, [0] * L, [S], K, seed=23)
+    m.set_layers(m.x1, x1)
+    lev = helpers.uniform_levels(S)
+    base = [(rng.standard_t(4, s) * 0.1).astype(np.float32) for s in sizes]
+    grads = [[(b * np.float32(1.0 + 0.001 * k)).astype(np.float32) for b in base] for k in range(K)]
+    m.set_grads(grads)
+    m.quantize_all_alt(1)
+    deltas = m.ctx.read_buffer(qoda.BUF_DELTA)
+    m.step_alt(q)
+    msgs = m.messages(0)
+    for k in (0, 1, K // 2, K - 1):
+        out = oracle.quantize(sizes, [S] * L, [lev] * L, grads[k], 23, 1, k)
+        assert np.array_equal(msgs[k], out[0]) and deltas[k] == out[2], k
+    mean = oracle.dequant_aggregate(sizes, [S] * L, msgs)
+    eta, gamma = oracle.alt_step_size(0.0, 0.0, q)
+    y = [np.zeros(s, np.float32) for s in sizes]
+    xn, xh, dx2 = oracle.oda_update_alt(sizes, mean, x1, y, np.float32(1.0), eta, gamma)
+    lam, mu = oracle.alt_advance(deltas, dx2, 0.0, 0.0)
+    sums = m.alt_sums.cpu().numpy()
+    assert sums[0] == lam and sums[1] == mu
+    gy, gxh = m.layers(m.y), m.layers(m.x_half)
+    for l in range(L):
+        assert np.array_equal(gy[l], y[l]) and np.array_equal(gxh[l], xh[l]), l
+    assert m.ctx.status() == qoda.OK
+    big = gm([300], [0], [2], 4096, seed=1)                      # admitted by the main rule ...
+    big.set_grads([[np.ones(300, np.float32)]] * 4096)
+    big.quantize_all_alt(1)
+    with pytest.raises(qoda.QodaError) as e:                      # ... refused by this one, before anything is launched
+        big.step_alt(q)
+    assert e.value.code == qoda.EINVAL and "15872" in str(e.value)
+    big.step()
+    big.sync()
+    assert big.ctx.status() == qoda.OK

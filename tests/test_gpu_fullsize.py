@@ -61,7 +61,7 @@ class Full:
     def round_(self, t):
         cur = (t - 1) & 1
         if self.w.adaptive:
-            self.ctx.fit_levels(self.gptrs(), t)
+            self.ctx.fit_levels_keep_norms(self.gptrs(), t)        # as bench.py does: the round's own vectors
         self.ctx.quantize_all(self.gptrs(), t, self.msg[cur], self.msg[1 - cur] if t > 1 else None)
         deltas = self.ctx.read_buffer(qoda.BUF_DELTA)
         acc_before = float(self.acc.cpu()[0])

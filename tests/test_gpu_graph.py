@@ -38,7 +38,10 @@ def test_two_rounds_replayed_from_a_graph(scope):
 
     def two_rounds(stream):
         for cur, t in ((0, 2), (1, 3)):
-            ctx.fit_levels(None if bucket else gp, t, stream=stream)
+            if bucket:
+                ctx.fit_levels(None, t, stream=stream)
+            else:
+                ctx.fit_levels_keep_norms(gp, t, stream=stream)
             ctx.quantize_all(gp, t, msg[cur], msg[1 - cur], stream=stream)
             ctx.step(msg[cur], ptrs(x1), ptrs(y), ptrs(xh), acc, None, eta, stream=stream)
 
