@@ -279,12 +279,19 @@ int qoda_status(qoda_ctx *ctx, void *stream);
  * qoda_kernel_name: the kernel's name for a class index (as it appears in a profiler's kernel trace), "" if out
  *   of range.
  * qoda_copy_calibration: a plain 128-bit copy kernel of `bytes` bytes (multiple of 16; 16-byte aligned device
- *   pointers): the known-traffic kernel that hardware byte counters are scaled by. */
-#define QODA_NUM_KERNELS 23
+ *   pointers): the known-traffic kernel that hardware byte counters are scaled by.
+ * qoda_stream_calibration: streaming with the access type of the big kernels (nontemporal 128-bit loads and stores,
+ *   64 KiB tiles): reads `bytes` (multiple of 65536) from src_dev and writes bytes * stores_per_16_loads / 16 to the
+ *   head of each tile of dst_dev.  0 stores: the read-only ceiling; 16: a copy; 2 and 8: about the read/write mix of
+ *   the quantize pass and of the decode + update pass.  The measured ceilings that bench.py prints beside the nominal
+ *   HBM peak come from this kernel. */
+#define QODA_NUM_KERNELS 24
 int qoda_profile_enable(qoda_ctx *ctx, uint32_t class_mask);
 int qoda_profile_read(qoda_ctx *ctx, double *ms, int64_t *launches, void *stream);
 const char *qoda_kernel_name(int32_t id);
 int qoda_copy_calibration(qoda_ctx *ctx, const void *src_dev, void *dst_dev, size_t bytes, void *stream);
+int qoda_stream_calibration(qoda_ctx *ctx, const void *src_dev, void *dst_dev, size_t bytes, int32_t stores_per_16_loads,
+                            void *stream);
 
 const char *qoda_last_error(const qoda_ctx *ctx);
 

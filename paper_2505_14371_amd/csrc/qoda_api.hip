@@ -413,7 +413,7 @@ static int create_impl(const qoda_config *cfg, qoda_ctx *c) {
   A(dev_alloc(&c->d_rgap, (size_t)c->M * kMaxPoints));
   A(dev_alloc(&c->d_eta, 3));
   A(dev_alloc(&c->d_lut, (size_t)c->M * kLutSize));
-  A(dev_alloc(&c->d_status, 1));
+  A(dev_alloc(&c->d_status, 2));   // the status word, and a word no kernel result depends on
   A(dev_alloc(&c->d_pooled, (size_t)c->M * kGridPoints));
   A(dev_alloc(&c->d_type_exp, (size_t)c->M));
   if (c->scope == kScopeBucket) {   // the quantize pass gathers the fit's statistics itself
@@ -1034,7 +1034,7 @@ const char *qoda_kernel_name(int32_t id) {
                                              "k_decode<false>", "k_decode<true>", "k_fit_typemax", "k_fit_pool",
                                              "k_fit_dp", "k_build_tables", "k_copy_f4", "k_alt_scalars",
                                              "k_decode<alt>", "k_alt_finalize", "k_norm_vector", "k_bucket_max",
-                                             "k_bucket_hist", "k_decode<extrapolate>", "k_index_hist"};
+                                             "k_bucket_hist", "k_decode<extrapolate>", "k_index_hist", "k_stream"};
   return (id >= 0 && id < kNumKernelIds) ? names[id] : "";
 }
 
@@ -1047,6 +1047,22 @@ int qoda_copy_calibration(qoda_ctx *c, const void *src_dev, void *dst_dev, size_
       return fail(c, QODA_EINVAL, "qoda_copy_calibration: pointers and size must be multiples of 16 bytes");
     hipStream_t s = static_cast<hipStream_t>(stream);
     LAUNCH(c, kIdCopy, s, launch_copy(src_dev, dst_dev, bytes, s));
+    return QODA_OK;
+  });
+}
+
+int qoda_stream_calibration(qoda_ctx *c, const void *src_dev, void *dst_dev, size_t bytes, int32_t stores_per_16_loads,
+                            void *stream) {
+  if (!c) return QODA_EINVAL;
+  return guarded(c, [&]() -> int {
+    if (const int rc_ = check_device(c)) return rc_;
+    const int w = stores_per_16_loads;
+    if (!src_dev || !dst_dev || bytes % 65536 != 0 || reinterpret_cast<uintptr_t>(src_dev) % 16 != 0 ||
+        reinterpret_cast<uintptr_t>(dst_dev) % 16 != 0 || !(w == 0 || w == 1 || w == 2 || w == 4 || w == 8 || w == 16))
+      return fail(c, QODA_EINVAL, "qoda_stream_calibration: 16-byte aligned pointers, a multiple of 65536 bytes and "
+                                  "0, 1, 2, 4, 8 or 16 stores per 16 loads");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    LAUNCH(c, kIdStream, s, launch_stream(src_dev, dst_dev, bytes, w, c->d_status + 1, s));
     return QODA_OK;
   });
 }

@@ -100,7 +100,7 @@ enum DecodeMode { kDecodeMean = 0, kDecodeUpdate = 1, kDecodeUpdateAlt = 2, kDec
 enum KernelId {
   kIdZero = 0, kIdSumsq, kIdSumsqHist, kIdNormFinalize, kIdReserved4 /* no kernel: keeps the class numbers of the others stable */, kIdQuantize, kIdDeltaFinalize, kIdStepScalars,
   kIdDecodeMean, kIdDecodeUpdate, kIdFitTypemax, kIdFitPool, kIdFitDp, kIdBuildTables, kIdCopy, kIdAltScalars,
-  kIdDecodeAlt, kIdAltFinalize, kIdNormVector, kIdBucketMax, kIdBucketHist, kIdDecodeExtrapolate, kIdIndexHist, kNumKernelIds
+  kIdDecodeAlt, kIdAltFinalize, kIdNormVector, kIdBucketMax, kIdBucketHist, kIdDecodeExtrapolate, kIdIndexHist, kIdStream, kNumKernelIds
 };
 
 // Launch wrappers (each checks nothing: the host API validates shapes before calling).
@@ -122,6 +122,8 @@ hipError_t launch_fit_typemax(const Dev &a, hipStream_t s);
 hipError_t launch_fit_pool(const Dev &a, hipStream_t s);
 hipError_t launch_fit_dp(const Dev &a, hipStream_t s);
 hipError_t launch_copy(const void *src, void *dst, size_t bytes, hipStream_t s);
+// nontemporal streaming over whole 64 KiB tiles of `bytes`: 16 loads and `stores` (0, 1, 2, 4, 8 or 16) stores per thread
+hipError_t launch_stream(const void *src, void *dst, size_t bytes, int stores, void *sink, hipStream_t s);
 hipError_t launch_build_tables(const Dev &a, int type, hipStream_t s);
 // Copy a small host array (32-bit words; pointers) into device memory through kernel arguments: no staging buffer, no
 // copy engine, and the host array may be reused as soon as the call returns.

@@ -1530,6 +1530,36 @@ __global__ void __launch_bounds__(kThreads) k_copy_f4(const float4 *__restrict__
   for (; i < n; i += stride) dst[i] = src[i];
 }
 
+// Streaming with the access type of the three big kernels: a workgroup takes tiles of 64 KiB; every thread issues 16
+// nontemporal 128-bit loads per tile (1 KiB contiguous per wave and load) and STORES nontemporal 128-bit stores of
+// values derived from them.  STORES = 0 measures the read-only ceiling (the norm pass), 16 a copy, values between
+// the read/write mixes of the quantize pass (about 2) and of the decode + update pass (about 9).
+template <int STORES>
+__global__ void __launch_bounds__(kThreads) k_stream(const float *__restrict__ src, float *__restrict__ dst, size_t tiles,
+                                                     float *sink) {
+  const int t = threadIdx.x;
+  float keep = 0.0f;
+  for (size_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    const size_t base = tile * kChunkCoords + (size_t)(t >> 6) * 16 * kBlockCoords + 4 * (t & 63);
+    v4f q[16];
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {
+      const auto *lp = reinterpret_cast<const __attribute__((address_space(1))) v4f *>(as_global(src) + base + (size_t)s * kBlockCoords);
+      q[s] = __builtin_nontemporal_load(lp);
+    }
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {
+      if (s < STORES) {
+        auto *sp = reinterpret_cast<__attribute__((address_space(1))) v4f *>((__attribute__((address_space(1))) float *)dst + base + (size_t)s * kBlockCoords);
+        __builtin_nontemporal_store(q[s], sp);
+      } else {
+        keep += (q[s].x + q[s].y) + (q[s].z + q[s].w);
+      }
+    }
+  }
+  if (keep == 12345.678f) sink[0] = keep;   // keeps the loads alive; practically never true
+}
+
 // ------------------------------------------------------------------------------------------------ staging
 // Small host arrays (pointer tables, level values) reach the device as kernel arguments and are written to their device
 // table by the kernel itself: no staging buffer, no copy engine, no host memory that must outlive the call.
@@ -1566,6 +1596,24 @@ hipError_t launch_copy(const void *src, void *dst, size_t bytes, hipStream_t s) 
   const unsigned int blocks = (unsigned int)(want < 1048576 ? want : 1048576);
   hipLaunchKernelGGL(k_copy_f4, dim3(blocks), dim3(kThreads), 0, s, reinterpret_cast<const float4 *>(src),
                      reinterpret_cast<float4 *>(dst), n);
+  return hipGetLastError();
+}
+
+hipError_t launch_stream(const void *src, void *dst, size_t bytes, int stores, void *sink, hipStream_t s) {
+  const size_t tiles = bytes / (4 * (size_t)kChunkCoords);
+  if (tiles == 0) return hipSuccess;
+  const dim3 grid((unsigned int)(tiles < 65536 ? tiles : 65536)), block(kThreads);
+  const float *a = static_cast<const float *>(src);
+  float *b = static_cast<float *>(dst), *k = static_cast<float *>(sink);
+  switch (stores) {
+    case 0: hipLaunchKernelGGL((k_stream<0>), grid, block, 0, s, a, b, tiles, k); break;
+    case 1: hipLaunchKernelGGL((k_stream<1>), grid, block, 0, s, a, b, tiles, k); break;
+    case 2: hipLaunchKernelGGL((k_stream<2>), grid, block, 0, s, a, b, tiles, k); break;
+    case 4: hipLaunchKernelGGL((k_stream<4>), grid, block, 0, s, a, b, tiles, k); break;
+    case 8: hipLaunchKernelGGL((k_stream<8>), grid, block, 0, s, a, b, tiles, k); break;
+    case 16: hipLaunchKernelGGL((k_stream<16>), grid, block, 0, s, a, b, tiles, k); break;
+    default: return hipErrorInvalidValue;
+  }
   return hipGetLastError();
 }
 

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libqoda.so")
 
 OK, EINVAL, ENOMEM, EHIP, ENONFINITE, ETINYNORM = 0, -1, -2, -3, -4, -5
 BUF_SUMSQ, BUF_NORM, BUF_INV, BUF_DELTA, BUF_HIST, BUF_POOLED = range(6)
-NUM_KERNELS = 23
+NUM_KERNELS = 24
 SCOPE_LAYER, SCOPE_VECTOR, SCOPE_BUCKET = 0, 1, 2
 NORM_LINF, NORM_L1, NORM_L2 = 0, 1, 2
 HIST_BINS, GRID_POINTS = 2048, 257
@@ -90,12 +90,14 @@ def load():
     L.qoda_kernel_name.argtypes = [C.c_int32]
     L.qoda_kernel_name.restype = C.c_char_p
     L.qoda_copy_calibration.argtypes = [vp, vp, vp, C.c_size_t, vp]
+    L.qoda_stream_calibration.argtypes = [vp, vp, vp, C.c_size_t, C.c_int32, vp]
     L.qoda_last_error.argtypes = [vp]
     L.qoda_last_error.restype = C.c_char_p
     for name in ("qoda_create", "qoda_destroy", "qoda_message_layout", "qoda_set_levels", "qoda_get_levels",
                  "qoda_fit_levels", "qoda_fit_levels_keep_norms", "qoda_quantize", "qoda_quantize_noalloc", "qoda_quantize_all", "qoda_dequant_aggregate", "qoda_step", "qoda_step_alt",
                  "qoda_step_rates", "qoda_extrapolate", "qoda_index_counts", "qoda_code_length",
-                 "qoda_read_buffer", "qoda_status", "qoda_profile_enable", "qoda_profile_read", "qoda_copy_calibration"):
+                 "qoda_read_buffer", "qoda_status", "qoda_profile_enable", "qoda_profile_read", "qoda_copy_calibration",
+                 "qoda_stream_calibration"):
         getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -305,6 +307,10 @@ class Context:
 
     def copy_calibration(self, src, dst, nbytes: int, stream=None):
         self._check(self._lib.qoda_copy_calibration(self._h, _addr(src), _addr(dst), nbytes, _stream(stream)))
+
+    def stream_calibration(self, src, dst, nbytes: int, stores_per_16_loads: int, stream=None):
+        self._check(self._lib.qoda_stream_calibration(self._h, _addr(src), _addr(dst), nbytes, stores_per_16_loads,
+                                                      _stream(stream)))
 
 
 def kernel_name(i: int) -> str:

@@ -1,11 +1,11 @@
 """Full-size GPU parity, in the launch configuration bench.py times (all K nodes, every tensor of the workload,
-fit -> quantize_all -> step, two rounds so that the previous-message path is exercised).
+fit -> quantize_all -> step, the second round against the first round's messages).
 
-The oracle cannot redo 10^9..2*10^10 (node, coordinate) pairs in test time, so the big workloads are checked on
-pieces it can compute one by one: whole small tensors, and octet-aligned slices (first, middle, ragged tail) of
-the big ones -- norms, histograms, fitted levels, packed codes, the per-node step-size term (recomputed by the
-oracle from the two stored messages of a node), and the updated iterates on those pieces.  The DCGAN-shaped
-workload is small enough to be compared in full."""
+The oracle does about 25 million node-coordinates per second and thread; spread over the box's threads that is enough
+to redo whole messages: every tensor of every node, byte for byte, for all three layer-shaped workloads (the DCGAN- and
+Transformer-XL-shaped ones for two rounds with every iterate; the 1.3e9-coordinate one for all 16 nodes in round 1,
+then two nodes and pieces).  A second test runs the workloads' own round counts with device-side checks every round and
+the oracle on pieces of the last one."""
 import numpy as np
 import pytest
 
@@ -97,85 +97,228 @@ def pieces_for(w, whole_limit=3_000_000):
     return out
 
 
-@pytest.mark.timeout(1200)
-@pytest.mark.parametrize("name", ["dcgan", "txl", "gpt1p3b"])
-def test_full_size_two_rounds(oracle, name):
-    f = Full(name)
+def _pool(n=None):
+    """Threads for the oracle's per-(layer, node) work: its C routines release the interpreter lock.  Sized to the GPU
+    box's CPU share."""
+    import concurrent.futures
+    import os
+
+    return concurrent.futures.ThreadPoolExecutor(max_workers=n or min(16, os.cpu_count() or 1))
+
+
+def _whole_round(oracle, f, t, prev_levels, prev_msgs, check_iterates):
+    """One round in bench.py's configuration, then EVERYTHING against the oracle: per (node, layer) statistic, norm and
+    reciprocal; per layer histogram, pooled weights and fitted levels; every node's whole message byte for byte
+    (header, every code of every tensor, padding); every node's step-size term recomputed from its stored messages;
+    the step size; and (check_iterates) Y and X_{t+3/2} on every coordinate.  Gradients come back from the device
+    layer by layer; the oracle's work is spread over threads."""
     w, K, L, S = f.w, f.K, f.L, f.S
-    pieces = [(l, 0, w.sizes[l]) for l in range(L)] if name == "dcgan" else pieces_for(w)
-    layers = sorted({p[0] for p in pieces})
-    check_nodes = list(range(K)) if name == "dcgan" else [0, K - 1]
-    prev_levels = {l: uniform_levels(S) for l in layers}
-    prev_msgs_host = None
-    for t in (1, 2):
-        f.fill(t)
-        y_old = {p: f.layer(f.y, p[0], p[1], p[2]) for p in pieces}
-        cur, deltas, acc_before = f.round_(t)
-        assert f.ctx.status() == qoda.OK
-        ss = f.ctx.read_buffer(qoda.BUF_SUMSQ)
-        nr = f.ctx.read_buffer(qoda.BUF_NORM)
-        iv = f.ctx.read_buffer(qoda.BUF_INV)
-        hist = f.ctx.read_buffer(qoda.BUF_HIST) if w.adaptive else None
-        pooled = f.ctx.read_buffer(qoda.BUF_POOLED) if w.adaptive else None
-        # ---- per layer: norms of every node, histogram + pooled weights + fitted levels
-        levels = {}
-        for l in layers:
-            host = [f.layer(f.grad[k], l) for k in range(K)]
-            for k in range(K):
-                s = oracle.sumsq(host[k])
-                assert ss[k, l] == s, (t, k, l)
-                n = oracle.sqrt_floor(s)
-                assert nr[k, l] == n and iv[k, l] == oracle.rcp_floor(n)
+    f.fill(t)
+    y_old = f.y.clone() if check_iterates else None
+    cur, deltas, acc_before = f.round_(t)
+    assert f.ctx.status() == qoda.OK
+    ss = f.ctx.read_buffer(qoda.BUF_SUMSQ)
+    nr = f.ctx.read_buffer(qoda.BUF_NORM)
+    iv = f.ctx.read_buffer(qoda.BUF_INV)
+    hist = f.ctx.read_buffer(qoda.BUF_HIST) if w.adaptive else None
+    pooled = f.ctx.read_buffer(qoda.BUF_POOLED) if w.adaptive else None
+    got_levels = [f.ctx.get_levels(l) for l in range(L)]
+    msgs = [f.msg[cur][k].cpu().numpy() for k in range(K)]
+    hb = int(f.body_off[0])
+    want_hdr = oracle.header_bytes(w.sizes, [S] * L)
+    assert hb == want_hdr and f.mbytes == oracle.message_bytes(w.sizes, [S] * L)
+    levels = [None] * L
+    order = sorted(range(L), key=lambda l: -w.sizes[l])           # big tensors first: better balance over the threads
+
+    def node_task(l, k, host, lev):
+        s = oracle.sumsq(host)
+        assert ss[k, l] == s, (t, k, l)
+        n = oracle.sqrt_floor(s)
+        assert nr[k, l] == n and iv[k, l] == oracle.rcp_floor(n), (t, k, l)
+        mh_norm, mh_lev = f.header(msgs[k][:hb], l)
+        assert mh_norm == n and np.array_equal(mh_lev, lev), (t, k, l)
+        sign, idx = oracle.quantize_range(host, 0, w.sizes[l], iv[k, l], lev, w.seed, t, k, l)
+        want = oracle.pack_layer(sign, idx, S)
+        b0 = int(f.body_off[l])
+        assert np.array_equal(msgs[k][b0: b0 + want.size], want), (t, k, l)
+        return want.size
+
+    with _pool() as pool:
+        pending = []
+        for l in order:
+            host = [f.layer(f.grad[k], l) for k in range(K)]     # D2H of this layer, all nodes
             if w.adaptive:
                 levs, oh, op, st = oracle.fit_levels([w.sizes[l]], [0], [S], K, host, [prev_levels[l]])
                 assert st == 0
                 assert np.array_equal(hist[:, l, :], oh[:, 0, :]), (t, l)
                 assert np.array_equal(pooled[l], op[0]), (t, l)
                 levels[l] = levs[0]
-                assert np.array_equal(f.ctx.get_levels(l), levs[0]), (t, l)
             else:
                 levels[l] = prev_levels[l]
-            # ---- packed codes of the checked nodes on this layer's pieces
-            for k in check_nodes:
-                mh_norm, mh_lev = f.header(f.msg[cur][k][: int(f.body_off[0])].cpu().numpy(), l)
-                assert mh_norm == nr[k, l] and np.array_equal(mh_lev, levels[l])
-                for (pl, e0, e1) in pieces:
-                    if pl != l:
-                        continue
-                    sign, idx = oracle.quantize_range(host[k], e0, e1, iv[k, l], levels[l], w.seed, t, k, l)
-                    gs, gi = oracle.unpack_layer(f.body_slice(f.msg[cur][k], l, e0, e1), e1 - e0, S)
-                    assert np.array_equal(gs, sign) and np.array_equal(gi, idx), (t, k, l, e0)
+            assert np.array_equal(got_levels[l], levels[l]), (t, l)
+            pending += [pool.submit(node_task, l, k, host[k], levels[l]) for k in range(K)]
+            while len(pending) > 64:                             # bound the host copies kept alive
+                pending.pop(0).result()
             del host
-        prev_levels = levels
-        # ---- step-size term of one node, recomputed by the oracle from the node's two stored messages
-        k = check_nodes[-1]
-        cur_host = f.msg[cur][k].cpu().numpy()
-        prev_host = f.msg[1 - cur][k].cpu().numpy() if t > 1 else None
-        if name != "gpt1p3b" or t == 2:          # 1.3e9 coordinates take the oracle about a minute: once is enough
-            want = oracle.delta_from_messages(w.sizes, [S] * L, cur_host, prev_host)
-            assert deltas[k] == want, (t, k)
-        del cur_host, prev_host
+        body = [0] * K
+        for fu in pending:
+            fu.result()
+        # nothing but zeros between the last body byte and the end of the message
+        end = int(f.body_off[L - 1]) + ((w.sizes[L - 1] + OCT - 1) // OCT) * 256 * f.c1
+        for k in range(K):
+            assert not msgs[k][end:].any() and not msgs[k][4 * sum(1 + S for _ in range(L)): hb].any(), k
+        del body
+        # step-size terms of every node from its stored messages, then the step size
+        fut = [pool.submit(oracle.delta_from_messages, w.sizes, [S] * L, msgs[k], None if prev_msgs is None else prev_msgs[k])
+               for k in range(K)]
+        for k in range(K):
+            assert deltas[k] == fut[k].result(), (t, k)
         acc, eta = oracle.step_size(deltas, acc_before)
         assert float(f.acc.cpu()[0]) == acc and float(f.eta.cpu()[0]) == float(eta)
-        # ---- decode + mean + update on the pieces: sub-messages (header entry + octets of the piece) per node
-        for (l, e0, e1) in pieces:
-            sub = []
-            for kk in range(K):
-                hdr = f.msg[cur][kk][int(f.hdr_off[l]): int(f.hdr_off[l]) + 4 * (1 + S)].cpu().numpy()
-                body = f.body_slice(f.msg[cur][kk], l, e0, e1)
-                hb = oracle.header_bytes([e1 - e0], [S])
-                m = np.zeros(oracle.message_bytes([e1 - e0], [S]), np.uint8)
-                m[: hdr.size] = hdr
-                m[hb: hb + body.size] = body
-                sub.append(m)
-            mean = oracle.dequant_aggregate([e1 - e0], [S], sub)[0]
-            yv = y_old[(l, e0, e1)].copy()
-            x1 = f.layer(f.x1, l, e0, e1)
-            _, xh = oracle.oda_update(mean, x1, yv, eta, eta, want_next=False)
-            gy, gxh = f.layer(f.y, l, e0, e1), f.layer(f.xh, l, e0, e1)
-            for a, b in ((gy, yv), (gxh, xh)):
-                tol = 1e-6 * np.abs(b) + 1e-9 * np.abs(b).max()
-                assert np.all(np.abs(a.astype(np.float64) - b) <= tol), (t, l, e0)
+        if check_iterates:                                       # decode + mean + update of every coordinate
+            def layer_task(l):
+                d = w.sizes[l]
+                nb = ((d + OCT - 1) // OCT) * 256 * f.c1
+                sub = []
+                for kk in range(K):
+                    m = np.zeros(oracle.message_bytes([d], [S]), np.uint8)
+                    h0 = int(f.hdr_off[l])
+                    m[: 4 * (1 + S)] = msgs[kk][h0: h0 + 4 * (1 + S)]
+                    o0 = oracle.header_bytes([d], [S])
+                    m[o0: o0 + nb] = msgs[kk][int(f.body_off[l]): int(f.body_off[l]) + nb]
+                    sub.append(m)
+                mean = oracle.dequant_aggregate([d], [S], sub)[0]
+                yv = f.layer(y_old, l)
+                _, xh = oracle.oda_update(mean, f.layer(f.x1, l), yv, eta, eta, want_next=False)
+                assert np.array_equal(f.layer(f.y, l), yv), (t, l)
+                assert np.array_equal(f.layer(f.xh, l), xh), (t, l)
+            for fu in [pool.submit(layer_task, l) for l in order]:
+                fu.result()
+    return levels, msgs
+
+
+@pytest.mark.timeout(1500)
+@pytest.mark.parametrize("name", ["dcgan", "txl", "gpt1p3b"])
+def test_full_size_whole_messages(oracle, name):
+    """Every workload at its full size, two rounds (the second against the first round's messages): every tensor of
+    every node, whole messages byte for byte, and every node's step-size term.  Iterates: every coordinate for the two
+    smaller workloads; for the 1.3e9-coordinate one a third round checked on pieces (decoding 2e10 node-coordinates a
+    second time on the CPU would double the test's time)."""
+    f = Full(name)
+    levels = {l: uniform_levels(f.S) for l in range(f.L)}
+    levels = [levels[l] for l in range(f.L)]
+    if name != "gpt1p3b":
+        prev = None
+        for t in (1, 2):
+            levels, prev = _whole_round(oracle, f, t, levels, prev, check_iterates=True)
+        return
+    prev = None
+    for t in (1, 2):
+        levels, prev = _whole_round(oracle, f, t, levels, prev, check_iterates=False)
+    del prev
+    _pieces_round(oracle, f, 3, levels, [0, f.K - 1], pieces_for(f.w))
+
+
+def _pieces_round(oracle, f, t, prev_levels_list, check_nodes, pieces):
+    """A round checked on pieces the oracle can do one by one: whole small tensors, and octet-aligned slices (first,
+    middle, ragged tail) of the big ones, for the given nodes; the step-size term of one node from its two stored
+    messages; iterates on the pieces."""
+    w, K, L, S = f.w, f.K, f.L, f.S
+    layers = sorted({p[0] for p in pieces})
+    prev_levels = {l: prev_levels_list[l] for l in layers}
+    prev_host = {k: f.msg[(t - 2) & 1][k].cpu().numpy() for k in check_nodes[-1:]} if t > 1 else {}
+    f.fill(t)
+    y_old = {p: f.layer(f.y, p[0], p[1], p[2]) for p in pieces}
+    cur, deltas, acc_before = f.round_(t)
+    assert f.ctx.status() == qoda.OK
+    ss = f.ctx.read_buffer(qoda.BUF_SUMSQ)
+    nr = f.ctx.read_buffer(qoda.BUF_NORM)
+    iv = f.ctx.read_buffer(qoda.BUF_INV)
+    hist = f.ctx.read_buffer(qoda.BUF_HIST) if w.adaptive else None
+    pooled = f.ctx.read_buffer(qoda.BUF_POOLED) if w.adaptive else None
+    levels = {}
+    for l in layers:
+        host = [f.layer(f.grad[k], l) for k in range(K)]
+        for k in range(K):
+            s = oracle.sumsq(host[k])
+            assert ss[k, l] == s, (t, k, l)
+            n = oracle.sqrt_floor(s)
+            assert nr[k, l] == n and iv[k, l] == oracle.rcp_floor(n)
+        if w.adaptive:
+            levs, oh, op, st = oracle.fit_levels([w.sizes[l]], [0], [S], K, host, [prev_levels[l]])
+            assert st == 0
+            assert np.array_equal(hist[:, l, :], oh[:, 0, :]), (t, l)
+            assert np.array_equal(pooled[l], op[0]), (t, l)
+            levels[l] = levs[0]
+            assert np.array_equal(f.ctx.get_levels(l), levs[0]), (t, l)
+        else:
+            levels[l] = prev_levels[l]
+        for k in check_nodes:
+            mh_norm, mh_lev = f.header(f.msg[cur][k][: int(f.body_off[0])].cpu().numpy(), l)
+            assert mh_norm == nr[k, l] and np.array_equal(mh_lev, levels[l])
+            for (pl, e0, e1) in pieces:
+                if pl != l:
+                    continue
+                sign, idx = oracle.quantize_range(host[k], e0, e1, iv[k, l], levels[l], w.seed, t, k, l)
+                gs, gi = oracle.unpack_layer(f.body_slice(f.msg[cur][k], l, e0, e1), e1 - e0, S)
+                assert np.array_equal(gs, sign) and np.array_equal(gi, idx), (t, k, l, e0)
+        del host
+    k = check_nodes[-1]
+    want = oracle.delta_from_messages(w.sizes, [S] * L, f.msg[cur][k].cpu().numpy(), prev_host.get(k))
+    assert deltas[k] == want, (t, k)
+    acc, eta = oracle.step_size(deltas, acc_before)
+    assert float(f.acc.cpu()[0]) == acc and float(f.eta.cpu()[0]) == float(eta)
+    for (l, e0, e1) in pieces:
+        sub = []
+        for kk in range(K):
+            hdr = f.msg[cur][kk][int(f.hdr_off[l]): int(f.hdr_off[l]) + 4 * (1 + S)].cpu().numpy()
+            body = f.body_slice(f.msg[cur][kk], l, e0, e1)
+            hb = oracle.header_bytes([e1 - e0], [S])
+            m = np.zeros(oracle.message_bytes([e1 - e0], [S]), np.uint8)
+            m[: hdr.size] = hdr
+            m[hb: hb + body.size] = body
+            sub.append(m)
+        mean = oracle.dequant_aggregate([e1 - e0], [S], sub)[0]
+        yv = y_old[(l, e0, e1)].copy()
+        _, xh = oracle.oda_update(mean, f.layer(f.x1, l, e0, e1), yv, eta, eta, want_next=False)
+        assert np.array_equal(f.layer(f.y, l, e0, e1), yv), (t, l, e0)
+        assert np.array_equal(f.layer(f.xh, l, e0, e1), xh), (t, l, e0)
+    return levels
+
+
+@pytest.mark.timeout(1200)
+@pytest.mark.parametrize("name", ["dcgan", "txl", "gpt1p3b"])
+def test_full_size_named_round_counts(oracle, name):
+    """The workloads' own round counts at full size (100, 20, 10 rounds; fit every round), so that the state that
+    accumulates -- Y, the step-size sum, levels that move, double-buffered messages -- is carried as far as the
+    workload says.  Every round is checked on the device with operations that hold bit for bit: Y_{t+1} = Y_t - mean_t
+    and X_{t+3/2} = (X_1 + eta Y_{t+1}) - gamma mean_t with the mean from qoda_dequant_aggregate and the same fp32
+    operations in torch; eta never grows; the status stays clean.  The last round is checked against the oracle on
+    pieces, with the levels fitted by then."""
+    f = Full(name)
+    w, K, L = f.w, f.K, f.L
+    mean = torch.zeros_like(f.x1)
+    y_ref = torch.zeros_like(f.x1)
+    last_eta = 1.0
+    pieces = pieces_for(w, whole_limit=300_000)[:10]
+    for t in range(1, w.rounds):
+        f.fill(t)
+        cur, deltas, _ = f.round_(t)
+        f.ctx.dequant_aggregate(f.msg[cur], f.ptrs(mean))
+        torch.cuda.synchronize()
+        eta = float(f.eta.cpu()[0])
+        assert f.ctx.status() == qoda.OK and 0.0 < eta <= last_eta, t
+        last_eta = eta
+        y_ref -= mean                                            # the kernel's own operation: one fp32 subtraction
+        assert torch.equal(f.y, y_ref), t
+        want_xh = (f.x1 + f.eta[0] * f.y) - f.eta[1] * mean      # two fp32 operations each, as in the kernel
+        for l in range(L):                                       # (the gaps between layers are not state)
+            o, d = int(f.off[l]), w.sizes[l]
+            assert torch.equal(f.xh[o: o + d], want_xh[o: o + d]), (t, l)
+        del want_xh
+    lev = [f.ctx.get_levels(l) for l in range(L)]
+    _pieces_round(oracle, f, w.rounds, lev, [0, K - 1], pieces)
+    assert float(f.eta.cpu()[0]) <= last_eta
 
 
 @pytest.mark.timeout(900)
