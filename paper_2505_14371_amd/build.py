@@ -7,8 +7,8 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 SOURCES = [os.path.join(_HERE, "csrc", f) for f in ("qoda_kernels.hip", "qoda_api.hip")]
 LIB = os.path.join(_HERE, "libqoda.so")
-PROBE_SRC = os.path.join(_HERE, "csrc", "qoda_probe.hip")
-PROBE = os.path.join(_HERE, "qoda_probe")
+PROBE_SRC = os.path.join(_HERE, "harness", "qoda_probe.hip")
+PROBE = os.path.join(_HERE, "harness", "qoda_probe")
 
 # -ffp-contract=off: every fp32/fp64 operation that feeds a packed bit stays a single IEEE operation.
 # packed-fp32 instructions are switched off for the whole library.
@@ -24,7 +24,7 @@ def build(verbose: bool = False) -> str:
     subprocess.check_call(cmd)
     # the torch-free measurement driver (links the library through its C ABI only)
     cmd = [hipcc, "--offload-arch=gfx950", "-O2", "-std=c++17", PROBE_SRC, "-o", PROBE, "-L" + _HERE, "-lqoda",
-           "-Wl,-rpath,$ORIGIN"]
+           "-Wl,-rpath,$ORIGIN/.."]
     if verbose:
         print(" ".join(cmd))
     subprocess.check_call(cmd)

@@ -1,12 +1,21 @@
 """Turn rocprofv3 CSV output of the qoda_probe driver into the short text summaries kept under profiles/.
 
-    python -m paper_2505_14371_amd.profile_summary --name txl --stats DIR --fetch DIR --write DIR \\
+    python -m paper_2505_14371_amd.harness.profile_summary --name txl --stats DIR --fetch DIR --write DIR \\
         --probe-log FILE --command "..." --out profiles/
 
 Reads <DIR>/**/*_kernel_stats.csv (from --kernel-trace --stats) and <DIR>/**/*_counter_collection.csv (from
 --pmc FETCH_SIZE / --pmc WRITE_SIZE, values in KiB per dispatch).  The byte counters are scaled by what the same
 counter reads for the plain copy kernel k_copy_f4, whose true size the probe log states.  Writes
 <out>/<name>_kernels.txt and merges the per-kernel traffic into <out>/traffic.json (read by bench.py).
+
+    python -m paper_2505_14371_amd.harness.profile_summary --name txl --sq DIR [DIR ...] --probe-log FILE \
+        --command "..." --out profiles/
+
+Reads the counter CSVs of one or more --pmc passes over SQ_* / GRBM_* counters, averages every counter per kernel
+class over its dispatches (the warm-up round's left out), and writes <out>/<name>_sq_counters.txt: the raw averages
+and, from them and the workload size in the probe log, vector / scalar / LDS instructions per node-coordinate, the
+share of cycles the vector ALU and the LDS were busy, and LDS bank-conflict cycles.  The vector instructions per
+node-coordinate are merged into <out>/sq_counters.json, from which bench.py derives each kernel's model time.
 """
 from __future__ import annotations
 
@@ -52,12 +61,76 @@ def _counters(directory: str):
     return agg
 
 
+def _sq_summary(a):
+    log = open(a.probe_log).read()
+    m = re.search(r"d=(\d+) K=(\d+)", log)
+    node_coords = float(m.group(1)) * float(m.group(2))
+    agg = collections.defaultdict(lambda: collections.defaultdict(list))
+    for d in a.sq:
+        for f in glob.glob(os.path.join(d, "**", "*_counter_collection.csv"), recursive=True):
+            for r in csv.DictReader(open(f)):
+                name = r["Kernel_Name"]
+                if "qoda::" not in name:
+                    continue
+                label = _short(name)
+                if label == "k_quantize" and re.search(r"k_quantize(_b)?<\d+, false", name):
+                    label = "k_quantize (no prev)"
+                agg[label][r["Counter_Name"]].append(float(r["Counter_Value"]))
+    lines = [f"# rocprofv3 --pmc summary (SQ / GRBM counters): {a.name}", "# command:", "#   " + a.command, "#",
+             "# probe output:"] + ["#   " + l for l in log.strip().splitlines()]
+    lines += ["#", "# Counters are sums over the device (32 shader engines, 256 CUs, 1024 SIMDs); GRBM_GUI_ACTIVE sums the",
+              "# 8 XCDs.  One vector instruction occupies its SIMD for 4 cycles (64 lanes over 16), a 64-bit integer",
+              "# multiply-add (the generator's 32x32->64 products) for 8.  Derived columns:",
+              "#   valu/nc, salu/nc, lds/nc   instructions x 64 lanes / node-coordinates of one launch",
+              "#   valu_busy                  (4 x SQ_INSTS_VALU + 4 x SQ_INSTS_VALU_INT64) / 1024 SIMDs / (GRBM_GUI_ACTIVE / 8)",
+              "#   lds_busy                   SQ_LDS_IDX_ACTIVE / 256 CUs / (GRBM_GUI_ACTIVE / 8);  conflict = SQ_LDS_BANK_CONFLICT share of it", ""]
+    big = {"k_sumsq<true>", "k_sumsq<false>", "k_quantize", "k_quantize (no prev)", "k_decode<true>", "k_decode<alt>"}
+    valu_per = {}
+    for k in sorted(agg):
+        c = {n: (sum(v[1:]) / len(v[1:]) if len(v) > 1 else v[0]) for n, v in agg[k].items()}
+        if k not in big:
+            continue
+        lines.append(k)
+        for n in sorted(c):
+            lines.append(f"    {n:<28}{c[n]:>18.0f}")
+        if "SQ_INSTS_VALU" in c:
+            per = 64.0 / node_coords
+            cyc = c.get("GRBM_GUI_ACTIVE", 0.0) / 8.0
+            d = [f"valu/nc={c['SQ_INSTS_VALU'] * per:.2f}"]
+            valu_per[k] = c["SQ_INSTS_VALU"] * per
+            if "SQ_INSTS_VALU_INT64" in c:
+                d.append(f"int64/nc={c['SQ_INSTS_VALU_INT64'] * per:.2f}")
+            if "SQ_INSTS_SALU" in c:
+                d.append(f"salu/nc={c['SQ_INSTS_SALU'] * per:.2f}")
+            if "SQ_INSTS_LDS" in c:
+                d.append(f"lds/nc={c['SQ_INSTS_LDS'] * per:.2f}")
+            if cyc:
+                busy = (4.0 * c["SQ_INSTS_VALU"] + 4.0 * c.get("SQ_INSTS_VALU_INT64", 0.0)) / 1024.0 / cyc
+                d.append(f"valu_busy={busy:.2f}")
+                if "SQ_LDS_IDX_ACTIVE" in c:
+                    d.append(f"lds_busy={c['SQ_LDS_IDX_ACTIVE'] / 256.0 / cyc:.2f}")
+                    d.append(f"conflict={c.get('SQ_LDS_BANK_CONFLICT', 0.0) / max(c['SQ_LDS_IDX_ACTIVE'], 1.0):.2f}")
+                d.append(f"cycles_per_xcd={cyc:.0f}")
+            lines.append("    derived: " + "  ".join(d))
+        lines.append("")
+    os.makedirs(a.out, exist_ok=True)
+    with open(os.path.join(a.out, f"{a.name}_sq_counters.txt"), "w") as f:
+        f.write("\n".join(lines) + "\n")
+    jpath = os.path.join(a.out, "sq_counters.json")
+    allc = json.load(open(jpath)) if os.path.exists(jpath) else {}
+    allc.setdefault("valu_instructions_per_node_coordinate", {})[a.key or a.name] = {
+        k: round(v, 3) for k, v in valu_per.items() if "(" not in k}
+    json.dump(allc, open(jpath, "w"), indent=1, sort_keys=True)
+    print("\n".join(lines))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--name", required=True)
     ap.add_argument("--key", help="entry of traffic.json to write (default: --name); bench.py looks up "
                                   "<workload>[+alt][+vector|+bucket]")
-    ap.add_argument("--stats", required=True)
+    ap.add_argument("--stats")
+    ap.add_argument("--sq", nargs="+", help="directories of --pmc passes over SQ_* / GRBM_* counters")
     ap.add_argument("--fetch")
     ap.add_argument("--write")
     ap.add_argument("--probe-log", help="stdout of qoda_probe (states the copy kernel's true size); needed with --fetch/--write")
@@ -65,6 +138,10 @@ def main():
     ap.add_argument("--command", required=True)
     ap.add_argument("--out", default="profiles")
     a = ap.parse_args()
+    if a.sq:
+        return _sq_summary(a)
+    if not a.stats:
+        raise SystemExit("--stats or --sq is needed")
     lines = [f"# rocprofv3 summary: {a.name}", "# command:", "#   " + a.command, "#"]
     copy_bytes = None
     if a.probe_log:
