@@ -79,11 +79,13 @@ def _sq_summary(a):
     lines = [f"# rocprofv3 --pmc summary (SQ / GRBM counters): {a.name}", "# command:", "#   " + a.command, "#",
              "# probe output:"] + ["#   " + l for l in log.strip().splitlines()]
     lines += ["#", "# Counters are sums over the device (32 shader engines, 256 CUs, 1024 SIMDs); GRBM_GUI_ACTIVE sums the",
-              "# 8 XCDs.  One vector instruction occupies its SIMD for 4 cycles (64 lanes over 16), a 64-bit integer",
-              "# multiply-add (the generator's 32x32->64 products) for 8.  Derived columns:",
-              "#   valu/nc, salu/nc, lds/nc   instructions x 64 lanes / node-coordinates of one launch",
-              "#   valu_busy                  (4 x SQ_INSTS_VALU + 4 x SQ_INSTS_VALU_INT64) / 1024 SIMDs / (GRBM_GUI_ACTIVE / 8)",
-              "#   lds_busy                   SQ_LDS_IDX_ACTIVE / 256 CUs / (GRBM_GUI_ACTIVE / 8);  conflict = SQ_LDS_BANK_CONFLICT share of it", ""]
+              "# 8 XCDs.  One vector instruction occupies its SIMD for 4 cycles (64 lanes over 16).  Derived columns:",
+              "#   valu/nc, int64/nc, salu/nc, lds/nc   instructions x 64 lanes / node-coordinates of one launch",
+              "#   valu_cycles   4 x SQ_INSTS_VALU / 1024 SIMDs: cycles a SIMD spends issuing vector instructions",
+              "#   kernel_cycles GRBM_GUI_ACTIVE / 8: the launch's duration in the counter's clock",
+              "#   valu_share    valu_cycles / kernel_cycles: near 1 = the vector ALUs are saturated (the two counters tick in",
+              "#                 different clock domains, so the share can pass 1); valu_ms_2.4GHz = valu_cycles / 2.4e9",
+              "#   lds_share     SQ_LDS_IDX_ACTIVE / 256 CUs / kernel_cycles;  conflict = SQ_LDS_BANK_CONFLICT / SQ_LDS_IDX_ACTIVE", ""]
     big = {"k_sumsq<true>", "k_sumsq<false>", "k_quantize", "k_quantize (no prev)", "k_decode<true>", "k_decode<alt>"}
     valu_per = {}
     for k in sorted(agg):
@@ -105,12 +107,13 @@ def _sq_summary(a):
             if "SQ_INSTS_LDS" in c:
                 d.append(f"lds/nc={c['SQ_INSTS_LDS'] * per:.2f}")
             if cyc:
-                busy = (4.0 * c["SQ_INSTS_VALU"] + 4.0 * c.get("SQ_INSTS_VALU_INT64", 0.0)) / 1024.0 / cyc
-                d.append(f"valu_busy={busy:.2f}")
+                vc = 4.0 * c["SQ_INSTS_VALU"] / 1024.0
+                d.append(f"valu_cycles={vc:.0f}  kernel_cycles={cyc:.0f}  valu_share={vc / cyc:.2f}  valu_ms_2.4GHz={vc / 2.4e6:.3f}")
                 if "SQ_LDS_IDX_ACTIVE" in c:
-                    d.append(f"lds_busy={c['SQ_LDS_IDX_ACTIVE'] / 256.0 / cyc:.2f}")
+                    d.append(f"lds_share={c['SQ_LDS_IDX_ACTIVE'] / 256.0 / cyc:.2f}")
                     d.append(f"conflict={c.get('SQ_LDS_BANK_CONFLICT', 0.0) / max(c['SQ_LDS_IDX_ACTIVE'], 1.0):.2f}")
-                d.append(f"cycles_per_xcd={cyc:.0f}")
+            if "TCC_REQ_sum" in c and c["TCC_REQ_sum"]:
+                d.append(f"l2_hit_rate={c.get('TCC_HIT_sum', 0.0) / c['TCC_REQ_sum']:.2f}")
             lines.append("    derived: " + "  ".join(d))
         lines.append("")
     os.makedirs(a.out, exist_ok=True)
@@ -155,14 +158,17 @@ def main():
                   f"#   workload={b['config']['workload']} ms_per_step={b['ms_per_step']:.4f} value={b['value']:.1f} {b['unit']} "
                   f"hbm_peak_fraction_algorithmic={b['hbm_peak_fraction_algorithmic']:.4f}",
                   f"#   roofline: kernel={r['kernel']} avg_ms={r['avg_ms']:.4f} achieved={r['achieved']:.1f} GB/s frac={r['frac']:.4f}"]
-    lines += ["", "kernel-trace --stats (ours only):", f"{'kernel':<22}{'calls':>7}{'avg_us':>12}{'min_us':>12}{'max_us':>12}{'pct':>8}"]
+    lines += ["", "kernel-trace --stats (ours only):", f"{'kernel':<36}{'calls':>7}{'avg_us':>12}{'min_us':>12}{'max_us':>12}{'pct':>8}"]
     for r in csv.DictReader(open(_one(os.path.join(a.stats, "**", "*_kernel_stats.csv")))):
         if "qoda::" not in r["Name"]:
             continue
         label = _short(r["Name"])
         if label == "k_quantize" and re.search(r"k_quantize(_b)?<\d+, false", r["Name"]):
             label = "k_quantize (no prev)"   # the round-1 variant that reads no previous message
-        lines.append(f"{label:<22}{r['Calls']:>7}{float(r['AverageNs']) / 1e3:>12.1f}"
+        width = re.search(r"k_(quantize|quantize_b|decode)<(\d+)", r["Name"])
+        if width and a.bench_json:             # a run with two workloads: tell their code widths apart
+            label += f" [{width.group(2)}-bit codes]"
+        lines.append(f"{label:<36}{r['Calls']:>7}{float(r['AverageNs']) / 1e3:>12.1f}"
                      f"{float(r['MinNs']) / 1e3:>12.1f}{float(r['MaxNs']) / 1e3:>12.1f}{float(r['Percentage']):>8.2f}")
     traffic = {}
     if a.fetch and a.write:
