@@ -150,7 +150,10 @@ def run_workload(args, name, steps, warmup, with_ceilings):
         state["t"] += 1
         t, cur = state["t"], state["cur"]
         g = gptrs[t % nsets]
-        if w.adaptive:
+        every = max(args.fit_every, 1)
+        if bucket and every > 1:
+            ctx.gather_statistics(t % every == 0)        # only the round before an update step gathers
+        if w.adaptive and (every == 1 or t % every == 1):
             if bucket and t > 1:
                 # bucket scope: the fit uses the statistics gathered by the previous quantize pass (the order of
                 # Alg. 1: the levels are updated before the round's vectors exist) and reads no gradient
@@ -246,7 +249,8 @@ def run_workload(args, name, steps, warmup, with_ceilings):
     if bucket:   # norms and fit statistics are computed inside the quantize pass
         alg_round = alg["k_quantize"] + alg[dec]
     else:
-        alg_round = sum(alg[n] for n in (("k_sumsq<true>" if w.adaptive else "k_sumsq<false>"), "k_quantize", dec))
+        alg_round = sum(alg[n] for n in (("k_sumsq<true>" if (w.adaptive and args.fit_every <= 1) else "k_sumsq<false>"),
+                                         "k_quantize", dec))
     med = statistics.median(per_group)
     out = {
         "value": grad_bytes / (ms_per_step * 1e-3) / 1e9,
@@ -258,7 +262,8 @@ def run_workload(args, name, steps, warmup, with_ceilings):
         "config": {"workload": name, "num_nodes": K, "coordinates": d, "tensors": L, "level_points": S,
                    "adaptive_levels": w.adaptive, "message_bytes_per_node": mbytes, "x_next": xn is not None,
                    "step_sizes": f"eq. (Alt), q_hat={args.q_hat}" if alt else "eq. (general_stepsize)",
-                   "norm_scope": args.norm_scope, "norm_kind": args.norm_kind, "gradient_sets_alternated": nsets},
+                   "norm_scope": args.norm_scope, "norm_kind": args.norm_kind, "gradient_sets_alternated": nsets,
+                   "levels_fitted_every": max(args.fit_every, 1) if w.adaptive else None},
         "hbm_peak_fraction_algorithmic": alg_round / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "algorithmic_bytes_per_step": alg_round,
         "host_wall_ms_per_step": t_host / steps * 1e3,
@@ -286,6 +291,9 @@ def main() -> int:
                     help="what one norm covers: a layer (default), the node's whole vector, or buckets of 128 entries")
     ap.add_argument("--norm-kind", default="l2", choices=["l2", "l1", "linf"],
                     help="the q of the L^q normalisation (Sec. 2.2); the workloads' default is L2")
+    ap.add_argument("--fit-every", type=int, default=1,
+                    help="update the levels every N rounds (the workloads say every round, the default; the paper's "
+                         "experiments every few thousand steps)")
     ap.add_argument("--q-hat", type=float, default=0.0,
                     help="> 0: the step sizes of eq. (Alt) with this exponent instead of eq. (general_stepsize)")
     args = ap.parse_args()

@@ -136,6 +136,13 @@ int qoda_get_levels(qoda_ctx *ctx, int32_t type, float *levels_host, void *strea
  * which only sets the scale), then with NULL at every later update step. */
 int qoda_fit_levels(qoda_ctx *ctx, const float *const *grad_dev, uint32_t round, void *stream);
 
+/* Bucket scope only (no effect otherwise): whether the quantize passes that follow gather the histogram for the next
+ * statistics-based fit (default: yes).  Gathering costs the quantize pass 11-13 %; a caller who updates the levels
+ * every few thousand rounds, as the paper's experiments do, switches it on for the round before an update step only.
+ * A pass that does not gather still records the largest bucket sum per (node, layer), from which the next
+ * qoda_fit_levels(NULL) derives the weight scale; its pooled histogram is empty then and the levels stay. */
+int qoda_gather_statistics(qoda_ctx *ctx, int32_t enable);
+
 /* The same fit for a caller who fits on the round's own vectors (layer and vector scope; under bucket scope identical
  * to qoda_fit_levels).  Calling it DECLARES that grad_dev holds exactly what the qoda_quantize / qoda_quantize_all
  * calls of the same `round` will be given, unchanged: the norms computed here on the way stay in the context, and such

@@ -47,6 +47,8 @@ struct qoda_ctx {
   short *d_dp_arg = nullptr;
   long long *d_dp_arg_off = nullptr;
   int *d_type_exp_next = nullptr;   // bucket scope: the weight scales the next gathering pass will use
+  int *d_type_skip = nullptr;       // bucket scope: "no scale" for every type (passes that gather no histogram)
+  bool gather = true;               // bucket scope: quantize passes gather the fit's histogram
   unsigned long long *d_index_counts = nullptr;   // [M*256], allocated by the first qoda_index_counts
   // device pointer tables (uploaded when their host shadow changes)
   // A few device copies per table, each remembering the host array it was filled from: a caller that alternates
@@ -281,7 +283,7 @@ int check_msg_ptrs(qoda_ctx *c, const void *const *p, size_t n, const char *what
 void free_all(qoda_ctx *c) {
   void *ptrs[] = {c->d_meta, c->d_tiles, c->d_stiles, c->d_empty, c->d_type_points, c->d_partial, c->d_dpartial, c->d_sumsq, c->d_delta,
                   c->d_norm, c->d_inv, c->d_lev, c->d_rgap, c->d_eta, c->d_lut, c->d_hist, c->d_status, c->d_pooled, c->d_index_counts, c->d_type_exp_next,
-                  c->d_type_exp, c->d_dp_arg, c->d_dp_arg_off, c->d_node_tab};
+                  c->d_type_exp, c->d_dp_arg, c->d_dp_arg_off, c->d_node_tab, c->d_type_skip};
   for (void *p : ptrs)
     if (p) (void)hipFree(p);
   qoda_ctx::Table *tabs[] = {&c->t_grad, &c->t_msg, &c->t_prev, &c->t_in, &c->t_x1, &c->t_y, &c->t_xh, &c->t_xn, &c->t_mean};
@@ -315,6 +317,7 @@ int quantize_impl(qoda_ctx *c, int node0, int nnodes, const float *const *grad_f
     for (int k = node0; k < node0 + nnodes && cached; ++k)
       for (int l = 0; l < c->L; ++l)
         if (c->norms_grad[(size_t)k * c->L + l] != grad_full[(size_t)k * c->L + l]) { cached = false; break; }
+  if (c->scope == kScopeBucket && !c->gather) a.type_exp = c->d_type_skip;   // running maxima only, no histogram
   if (c->scope == kScopeBucket) {
     cached = true;   // the bucket norms are computed by the quantize kernel itself, which also gathers the fit's
                      // statistics of these nodes: their histograms and running maxima start from zero
@@ -418,6 +421,7 @@ static int create_impl(const qoda_config *cfg, qoda_ctx *c) {
   A(dev_alloc(&c->d_type_exp, (size_t)c->M));
   if (c->scope == kScopeBucket) {   // the quantize pass gathers the fit's statistics itself
     A(dev_alloc(&c->d_type_exp_next, (size_t)c->M));
+    A(dev_alloc(&c->d_type_skip, (size_t)c->M));
     A(dev_alloc(&c->d_hist, KL * kHistBins));
   }
   A(dev_alloc(&c->d_dp_arg, (size_t)arg_total));
@@ -436,6 +440,7 @@ static int create_impl(const qoda_config *cfg, qoda_ctx *c) {
   if (e == hipSuccess) {   // no weight scale yet: nothing is gathered until a fit has produced one
     const std::vector<int> skip((size_t)c->M, kTypeSkip);
     A(hipMemcpy(c->d_type_exp, skip.data(), c->M * sizeof(int), hipMemcpyHostToDevice));
+    if (c->d_type_skip) A(hipMemcpy(c->d_type_skip, skip.data(), c->M * sizeof(int), hipMemcpyHostToDevice));
   }
   if (e == hipSuccess) A(hipMemset(c->d_status, 0, sizeof(unsigned int)));
   if (e == hipSuccess) A(hipMemset(c->d_delta, 0, c->K * sizeof(double)));
@@ -660,6 +665,7 @@ static int quantize_node(qoda_ctx *c, int32_t node, const float *const *grad_dev
   a.node0 = node;
   a.nnodes = 1;
   a.row0 = node;   // the tables and scratch rows above are this node's only
+  if (c->scope == kScopeBucket && !c->gather) a.type_exp = c->d_type_skip;   // running maxima only, no histogram
   if (c->scope == kScopeBucket) {
     // the bucket norms are computed by the quantize kernel, which also gathers this node's fit statistics into the
     // context (state of the next fit, not scratch): their histograms and running maxima start from zero
@@ -994,6 +1000,12 @@ int qoda_status(qoda_ctx *c, void *stream) {
     }
     return QODA_OK;
   });
+}
+
+int qoda_gather_statistics(qoda_ctx *c, int32_t enable) {
+  if (!c) return QODA_EINVAL;
+  c->gather = enable != 0;
+  return QODA_OK;
 }
 
 int qoda_profile_enable(qoda_ctx *c, uint32_t class_mask) {

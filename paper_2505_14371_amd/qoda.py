@@ -73,6 +73,7 @@ def load():
     L.qoda_get_levels.argtypes = [vp, C.c_int32, C.POINTER(C.c_float), vp]
     L.qoda_fit_levels.argtypes = [vp, pp, C.c_uint32, vp]
     L.qoda_fit_levels_keep_norms.argtypes = [vp, pp, C.c_uint32, vp]
+    L.qoda_gather_statistics.argtypes = [vp, C.c_int32]
     L.qoda_quantize.argtypes = [vp, C.c_int32, pp, C.c_uint32, vp, vp, vp]
     L.qoda_quantize_noalloc.argtypes = [vp, C.c_int32, pp, C.c_uint32, vp, vp, vp]
     L.qoda_quantize_all.argtypes = [vp, pp, C.c_uint32, pp, pp, vp]
@@ -94,7 +95,7 @@ def load():
     L.qoda_last_error.argtypes = [vp]
     L.qoda_last_error.restype = C.c_char_p
     for name in ("qoda_create", "qoda_destroy", "qoda_message_layout", "qoda_set_levels", "qoda_get_levels",
-                 "qoda_fit_levels", "qoda_fit_levels_keep_norms", "qoda_quantize", "qoda_quantize_noalloc", "qoda_quantize_all", "qoda_dequant_aggregate", "qoda_step", "qoda_step_alt",
+                 "qoda_fit_levels", "qoda_fit_levels_keep_norms", "qoda_gather_statistics", "qoda_quantize", "qoda_quantize_noalloc", "qoda_quantize_all", "qoda_dequant_aggregate", "qoda_step", "qoda_step_alt",
                  "qoda_step_rates", "qoda_extrapolate", "qoda_index_counts", "qoda_code_length",
                  "qoda_read_buffer", "qoda_status", "qoda_profile_enable", "qoda_profile_read", "qoda_copy_calibration",
                  "qoda_stream_calibration"):
@@ -206,6 +207,10 @@ class Context:
         unchanged, so that they reuse the norms computed here."""
         assert len(grads) == self.K * self.L
         self._check(self._lib.qoda_fit_levels_keep_norms(self._h, _ptrs(grads), round_, _stream(stream)))
+
+    def gather_statistics(self, enable: bool):
+        """Bucket scope: whether quantize passes gather the histogram for the next statistics-based fit."""
+        self._check(self._lib.qoda_gather_statistics(self._h, 1 if enable else 0))
 
     # -- hot path
     def quantize(self, node: int, grads: Sequence, round_: int, msg, msg_prev=None, stream=None):

@@ -272,3 +272,58 @@ def test_a_norm_below_the_normal_range_raises_its_own_flag(oracle, scope):
     m.set_grads(grads)
     m.quantize_all(2)
     assert m.ctx.status() == qoda.OK
+
+
+def test_gathering_can_be_switched_off_between_update_steps(oracle):
+    """qoda_gather_statistics(0): the quantize passes write the same messages and still record the largest bucket sums
+    (the next weight scale), but no histogram; a fit from such a round keeps the levels and refreshes the scale, and the
+    round after gathers with it -- the schedule of a caller who updates the levels every few thousand rounds."""
+    sizes, types = [5000, 16384 * 3 + 77, 300], [0, 1, 1]
+    L, K, S, M = len(sizes), 2, 8, 2
+    m = gm(sizes, types, [S] * M, K, seed=14, norm_scope=BUCKET)
+    rng = np.random.default_rng(7)
+    draw = lambda: [[(rng.standard_t(3, s) * 10.0 ** rng.uniform(-3, 0)).astype(np.float32) for s in sizes] for _ in range(K)]
+    lev = [helpers.uniform_levels(S) for _ in range(M)]
+    lev_l = [lev[ty] for ty in types]
+    # round 1, gathering off: no scale, no histogram; the maxima are recorded
+    g1 = draw()
+    m.set_grads(g1)
+    m.ctx.gather_statistics(False)
+    m.quantize_all(1)
+    msgs = m.messages()
+    got_max = m.ctx.read_buffer(qoda.BUF_SUMSQ)
+    assert not m.ctx.read_buffer(qoda.BUF_HIST).any()
+    bmax = np.zeros((K, L))
+    for k in range(K):
+        out = oracle.quantize(sizes, [S] * L, lev_l, g1[k], 14, 1, k, scope=BUCKET, stats_exp=[oracle.TYPE_SKIP] * L)
+        assert np.array_equal(msgs[k], out[0]), k
+        assert out[4].sum() == 0
+        bmax[k] = out[5]
+    assert np.array_equal(got_max, bmax)
+    m.step()
+    # the fit before round 2 finds no histogram: levels stay, the scale is set from the maxima
+    m.ctx.fit_levels(None, 2)
+    lev2, pooled, exps, st = oracle.fit_from_stats(types, [S] * M, K, np.zeros((K, L, 257), np.uint64), bmax,
+                                                  [oracle.TYPE_SKIP] * M, lev)
+    assert st == 0 and pooled.sum() == 0
+    for ty in range(M):
+        assert np.array_equal(m.ctx.get_levels(ty), lev[ty]) and np.array_equal(lev2[ty], lev[ty])
+    # round 2, gathering on with that scale; the fit before round 3 moves the levels
+    g2 = draw()
+    m.set_grads(g2)
+    m.ctx.gather_statistics(True)
+    m.quantize_all(2)
+    hist = np.zeros((K, L, 257), np.uint64)
+    for k in range(K):
+        out = oracle.quantize(sizes, [S] * L, lev_l, g2[k], 14, 2, k, msg_prev=msgs[k], scope=BUCKET,
+                              stats_exp=[int(exps[ty]) for ty in types])
+        assert np.array_equal(m.messages()[k], out[0]), k
+        hist[k], bmax[k] = out[4], out[5]
+    m.step()
+    m.ctx.fit_levels(None, 3)
+    lev3, pooled3, _, st = oracle.fit_from_stats(types, [S] * M, K, hist, bmax, exps, lev)
+    assert np.array_equal(m.ctx.read_buffer(qoda.BUF_POOLED), pooled3) and pooled3.sum() > 0
+    for ty in range(M):
+        assert np.array_equal(m.ctx.get_levels(ty), lev3[ty])
+    assert not np.array_equal(lev3[0], lev[0])
+    assert m.ctx.status() == qoda.OK
