@@ -213,6 +213,48 @@ def test_microbenchmark_full_size(oracle):
     assert abs(err - var) < 0.01 * var
 
 
+def test_unbiasedness_over_1000_draws_on_the_gpu():
+    """Config 2's statistical check run on the device itself, with no oracle in the loop: the 4096-entry prefix of the
+    microbenchmark vector quantized as its own vector under 1000 independent draws (900 round numbers under one seed,
+    then 100 seeds), decoded by the library.  E[Q(v)] = v (Thm 5.1): every coordinate's sample mean lies within 5
+    standard errors of v, the standard error from the exact variance eq. (Var); the pooled chi-square of the
+    standardised means is what 4096 degrees of freedom allow; and the total squared error averages to eq. (Var)."""
+    wl = workloads.get("microbench")
+    d, S, n_draws = 4096, wl.points, 1000
+    v = workloads.layer_numpy(wl, 0, 0, 1)[:d].copy()
+    dev = torch.device("cuda:0")
+    total = torch.zeros(64 * ((d + 63) // 64), dtype=torch.float64, device=dev)
+    sq_err = 0.0
+    vd = torch.from_numpy(v.astype(np.float64)).to(dev)
+    draws = [(wl.seed, r) for r in range(1, 901)] + [(1000 + s, 1) for s in range(100)]
+    models = {}
+    for seed, r in draws:
+        if seed not in models:
+            m = gm([d], [0], [S], 1, seed=seed)
+            m.set_grads([[v]])
+            models[seed] = m
+        m = models[seed]
+        m.quantize_all(r)
+        m.aggregate()
+        dec = m.mean[:d].double()
+        total[:d] += dec
+        sq_err += float(torch.sum((dec - vd) ** 2))
+    mean = (total[:d] / n_draws).cpu().numpy()
+    norm = float(np.sqrt(np.sum(v.astype(np.float64) ** 2)))
+    u = np.minimum(np.abs(v.astype(np.float64)) / norm, 1.0)
+    tau = np.minimum((u * (S - 1)).astype(np.int64), S - 2)
+    var = norm ** 2 * ((tau + 1) / (S - 1) - u) * (u - tau / (S - 1))      # eq. (Var), per coordinate
+    se = np.sqrt(var / n_draws)
+    z = (mean - v) / np.maximum(se, 1e-300)
+    live = var > 0
+    assert np.all(np.abs(z[live]) < 5.0), float(np.abs(z[live]).max())
+    assert np.all(mean[~live] == v[~live])                                 # on-grid values are reproduced exactly
+    chi2 = float(np.sum(z[live] ** 2))
+    dof = int(live.sum())
+    assert abs(chi2 - dof) < 5.0 * np.sqrt(2.0 * dof), (chi2, dof)
+    assert sq_err / n_draws == pytest.approx(float(var.sum()), rel=0.02)
+
+
 def test_fit_levels_matches_and_feeds_the_quantizer(oracle):
     """Config 3 shapes shrunk: histogram, pooled grid weights and fitted levels identical; the quantize that
     follows (reusing the norms of the fit pass) writes the oracle's bytes; so does a quantize that recomputes them."""
