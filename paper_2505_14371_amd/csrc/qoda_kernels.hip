@@ -733,6 +733,8 @@ __device__ __forceinline__ void bucket_norms(const Dev &a, const LayerMeta &m, l
 }
 
 // quantize_block with the block's own (bucket) norm, reciprocal and previous norm; the tables hold plain levels.
+constexpr int kBucketHistCopies = 4;   // power of two
+
 template <int C1, bool PREV>
 __device__ __forceinline__ void quantize_block_b(const float (&x)[4], const unsigned int (&o)[4], int half, float inv,
                                                  float norm, float pnorm, const unsigned char *lut, const float4 *tab,
@@ -753,7 +755,7 @@ __device__ __forceinline__ void quantize_block_b(const float (&x)[4], const unsi
       if ((f2u(x[j]) & 0x7FF00000u) == 0u) continue;   // raw magnitude bin 0; also the +0 padding past the layer's end
       // u <= 1, so its bin never exceeds the last grid index: only the lower clamp is needed (saturating subtract)
       const unsigned int g = __builtin_elementwise_sub_sat(f2u(u[j]) >> 20, (unsigned int)kGridBase);
-      atomicAdd(&lh[g], (unsigned long long)wfix);
+      atomicAdd(&lh[g * kBucketHistCopies], (unsigned long long)wfix);
     }
   }
 #pragma unroll
@@ -846,7 +848,9 @@ __global__ void __launch_bounds__(kThreads) k_quantize_b(Dev a) {
   __shared__ float tprev[2 * kMaxPoints];   // +-level of the previous message, indexed by code = sign | h << 1
   __shared__ double red[kThreads];
   __shared__ BucketWave bws[kThreads / 64];
-  __shared__ unsigned long long lh[kGridPoints];        // fit statistics of this run: weighted grid histogram
+  // fit statistics of this run: weighted grid histogram, one copy per lane residue (a wave's lanes that meet in a
+  // bin then collide a quarter as often), copies of a bin side by side
+  __shared__ unsigned long long lh[kGridPoints * kBucketHistCopies];
   __shared__ unsigned long long wmax[kThreads / 64];
   // a workgroup takes a run of up to kSuperTile consecutive tiles of one layer: the tables are set up and the
   // statistics flushed once per run
@@ -880,10 +884,11 @@ __global__ void __launch_bounds__(kThreads) k_quantize_b(Dev a) {
     }
     tprev[c] = pl;
   }
-  for (int j = t; j < kGridPoints; j += kThreads) lh[j] = 0ull;
+  for (int j = t; j < kGridPoints * kBucketHistCopies; j += kThreads) lh[j] = 0ull;
   __syncthreads();
   const int w = __builtin_amdgcn_readfirstlane(t >> 6);
   const int i = t & 63;
+  unsigned long long *lhc = lh + (i & (kBucketHistCopies - 1));   // this lane's copy
   const float *__restrict__ v = a.grad[(size_t)kr * a.L + l];
   unsigned char *body = a.msg[kr] + m.body_off;
   const unsigned char *prevbody = prevmsg ? prevmsg + m.body_off : nullptr;
@@ -896,9 +901,9 @@ __global__ void __launch_bounds__(kThreads) k_quantize_b(Dev a) {
       const long long O = (long long)chunk * 8 + w * 2 + oo;
       if (O >= noct) break;
       if ((O + 1) * 2048 <= m.d)
-        quantize_octet_b<C1, true, PREV, KIND>(a, m, l, k, O, v, body, prevbody, lut, tab, tprev, bws[w], i, acc, ex, best, lh);
+        quantize_octet_b<C1, true, PREV, KIND>(a, m, l, k, O, v, body, prevbody, lut, tab, tprev, bws[w], i, acc, ex, best, lhc);
       else
-        quantize_octet_b<C1, false, PREV, KIND>(a, m, l, k, O, v, body, prevbody, lut, tab, tprev, bws[w], i, acc, ex, best, lh);
+        quantize_octet_b<C1, false, PREV, KIND>(a, m, l, k, O, v, body, prevbody, lut, tab, tprev, bws[w], i, acc, ex, best, lhc);
     }
     const double total = block_tree((double)acc, red);
     if (t == 0) a.dpartial[(size_t)kr * a.G + m.first_chunk + chunk] = total;
@@ -919,7 +924,9 @@ __global__ void __launch_bounds__(kThreads) k_quantize_b(Dev a) {
   if (ex != kTypeSkip) {
     unsigned long long *gh = reinterpret_cast<unsigned long long *>(a.hist + idx * kHistBins);
     for (int j = t; j < kGridPoints; j += kThreads) {
-      const unsigned long long c = lh[j];
+      unsigned long long c = 0ull;
+#pragma unroll
+      for (int q = 0; q < kBucketHistCopies; ++q) c += lh[j * kBucketHistCopies + q];
       if (c) atomicAdd(&gh[j], c);
     }
   }
