@@ -91,7 +91,8 @@ typedef struct qoda_ctx qoda_ctx;
 
 typedef struct {
   int32_t num_layers;         /* L >= 1 */
-  const int64_t *layer_size;  /* d_l >= 0 elements, host array [L], copied; d_l < 2^34 */
+  const int64_t *layer_size;  /* d_l >= 0 elements, host array [L], copied; d_l < 2^34, and at most 2^28 tiles of
+                                 16384 elements over all layers (each layer rounded up to whole tiles) */
   const int32_t *layer_type;  /* m(l) in [0, M), host array [L], copied */
   int32_t num_types;          /* M >= 1 */
   const int32_t *type_points; /* S_m in [2, 256], host array [M], copied */

@@ -369,7 +369,8 @@ static int create_impl(const qoda_config *cfg, qoda_ctx *c) {
     if (m.S > c->maxS) c->maxS = m.S;
     if ((1 << m.planes) > c->maxSP) c->maxSP = 1 << m.planes;
     c->planes_mask |= 1u << m.planes;
-    if (hdr > (1u << 30) || chunks > (1ll << 30)) return QODA_EINVAL;
+    // tiles per node: the decode pass launches up to 8 workgroups per tile in one grid dimension
+    if (hdr > (1u << 30) || chunks > (1ll << 28)) return QODA_EINVAL;
   }
   if ((size_t)c->K * c->maxSP * sizeof(float) > 64 * 1024) return QODA_EINVAL;   // decode tables must fit LDS
   c->header_bytes = round_up(hdr, 256);

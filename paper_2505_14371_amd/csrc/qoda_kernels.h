@@ -10,6 +10,7 @@ constexpr int kBlockCoords = 256;    // coordinates per packed block (one wave64
 constexpr int kChunkCoords = 16384;  // coordinates per workgroup tile (64 blocks) = one reduction chunk
 constexpr int kSuperTile = 8;        // tiles per workgroup in the norm pass
 constexpr int kTaperWorkgroups = 2048;   // workgroups of 256 threads the device holds at once (256 CUs x 8)
+constexpr int kDecodeWaves = 2;       // waves (= octets) per workgroup in the decode pass: 1, 2 or 4
 constexpr int kThreads = 256;        // workgroup size everywhere: 4 waves, 256 reduction slots
 constexpr int kHistBins = 2048;      // top 11 magnitude bits of an fp32 value
 constexpr int kGridBase = 760;       // (127 - 32) << 3

@@ -1095,9 +1095,32 @@ __device__ __forceinline__ void decode_octet(const Dev &a, const LayerMeta &m, i
   }
 }
 
+// The decode pass runs best in short workgroups of one octet per wave (measured against one tile per workgroup of
+// four waves with two octets each: 6 % faster at K = 8, 4 % at K = 16): a workgroup has blockDim / 64 waves (1, 2 or 4)
+// and takes that many consecutive octets of a tile.  Only the (Alt) variant keeps one workgroup of four waves per
+// tile, two octets per wave: its squared-distance term is defined per slot and tile (a slot's chain runs through both
+// octets of its wave).
 template <int C1, int MODE, bool BUCKET>
-__device__ __forceinline__ void decode_tile(const Dev &a, const LayerMeta &m, int l, int chunk, const float *T,
-                                            double *red) {
+__global__ void __launch_bounds__(kThreads) k_decode(Dev a) {
+  extern __shared__ float T[];   // [K][2^C1]: +-norm_k * level_h (bucket scope: +-level_h) from the K message headers
+  __shared__ double red[MODE == kDecodeUpdateAlt ? kThreads : 1];
+  constexpr bool WHOLE = MODE == kDecodeUpdateAlt;
+  const int nw = blockDim.x >> 6;
+  const int PARTS = WHOLE ? 1 : 8 / nw;   // workgroups per tile
+  const int g = blockIdx.x / PARTS, part = blockIdx.x - g * PARTS;
+  const int2 tile = a.tiles[g];
+  const int l = tile.x;
+  const LayerMeta m = a.meta[l];
+  if (m.planes != C1) return;
+  const int TS = 1 << C1;
+  for (int idx = threadIdx.x; idx < a.K * TS; idx += blockDim.x) {
+    const int k = idx / TS, c = idx - k * TS;
+    const float *hp = reinterpret_cast<const float *>(a.msgs_in[k] + m.hdr_off);
+    const float lvl = hp[1 + min(c >> 1, m.S - 1)];
+    const float mag = BUCKET ? lvl : hp[0] * lvl;
+    T[idx] = (c & 1) ? -mag : mag;
+  }
+  __syncthreads();
   const int t = threadIdx.x;
   const int w = __builtin_amdgcn_readfirstlane(t >> 6);
   const int i = t & 63;
@@ -1106,36 +1129,16 @@ __device__ __forceinline__ void decode_tile(const Dev &a, const LayerMeta &m, in
   if (MODE == kDecodeUpdateAlt) eta_prev = a.eta[2];
   if (MODE == kDecodeExtrapolate) gamma = a.gamma_in[0];
   const long long noct = (m.nblk + 7) >> 3;
-  for (int oo = 0; oo < 2; ++oo) {
-    const long long O = (long long)chunk * 8 + w * 2 + oo;
+  for (int oo = 0; oo < (WHOLE ? 2 : 1); ++oo) {
+    const long long O = (long long)tile.y * 8 + (WHOLE ? w * 2 + oo : part * nw + w);
     if (O >= noct) break;
     if ((O + 1) * 2048 <= m.d) decode_octet<C1, MODE, true, BUCKET>(a, m, l, O, T, i, eta, gamma, eta_prev, accx);
     else decode_octet<C1, MODE, false, BUCKET>(a, m, l, O, T, i, eta, gamma, eta_prev, accx);
   }
   if (MODE == kDecodeUpdateAlt) {
     const double total = block_tree((double)accx, red);
-    if (t == 0) a.dpartial[blockIdx.x] = total;
+    if (t == 0) a.dpartial[g] = total;
   }
-}
-
-template <int C1, int MODE, bool BUCKET>
-__global__ void __launch_bounds__(kThreads) k_decode(Dev a) {
-  extern __shared__ float T[];   // [K][2^C1]: +-norm_k * level_h (bucket scope: +-level_h) from the K message headers
-  __shared__ double red[MODE == kDecodeUpdateAlt ? kThreads : 1];
-  const int2 tile = a.tiles[blockIdx.x];
-  const int l = tile.x;
-  const LayerMeta m = a.meta[l];
-  if (m.planes != C1) return;
-  const int TS = 1 << C1;
-  for (int idx = threadIdx.x; idx < a.K * TS; idx += kThreads) {
-    const int k = idx / TS, c = idx - k * TS;
-    const float *hp = reinterpret_cast<const float *>(a.msgs_in[k] + m.hdr_off);
-    const float lvl = hp[1 + min(c >> 1, m.S - 1)];
-    const float mag = BUCKET ? lvl : hp[0] * lvl;
-    T[idx] = (c & 1) ? -mag : mag;
-  }
-  __syncthreads();
-  decode_tile<C1, MODE, BUCKET>(a, m, l, tile.y, T, red);
 }
 
 // ------------------------------------------------------------------------------------------------ code lengths
@@ -1705,11 +1708,14 @@ hipError_t launch_step_scalars(const Dev &a, hipStream_t s) {
 
 template <int C1, bool BUCKET>
 static void launch_decode_scope(const Dev &a, int mode, size_t lds_bytes, hipStream_t s) {
-  const dim3 grid(a.G), block(kThreads);
-  if (mode == kDecodeExtrapolate) hipLaunchKernelGGL((k_decode<C1, kDecodeExtrapolate, BUCKET>), grid, block, lds_bytes, s, a);
-  else if (mode == kDecodeUpdateAlt) hipLaunchKernelGGL((k_decode<C1, kDecodeUpdateAlt, BUCKET>), grid, block, lds_bytes, s, a);
-  else if (mode == kDecodeUpdate) hipLaunchKernelGGL((k_decode<C1, kDecodeUpdate, BUCKET>), grid, block, lds_bytes, s, a);
-  else hipLaunchKernelGGL((k_decode<C1, kDecodeMean, BUCKET>), grid, block, lds_bytes, s, a);
+  const dim3 whole(a.G), block(kThreads);                                           // one workgroup per tile
+  // short workgroups: two waves, four where the K decode tables are large enough to limit the workgroups per CU
+  const int nw = lds_bytes > 8192 ? 4 : kDecodeWaves;
+  const dim3 parts((unsigned int)a.G * (8 / nw)), small(64 * nw);
+  if (mode == kDecodeExtrapolate) hipLaunchKernelGGL((k_decode<C1, kDecodeExtrapolate, BUCKET>), parts, small, lds_bytes, s, a);
+  else if (mode == kDecodeUpdateAlt) hipLaunchKernelGGL((k_decode<C1, kDecodeUpdateAlt, BUCKET>), whole, block, lds_bytes, s, a);
+  else if (mode == kDecodeUpdate) hipLaunchKernelGGL((k_decode<C1, kDecodeUpdate, BUCKET>), parts, small, lds_bytes, s, a);
+  else hipLaunchKernelGGL((k_decode<C1, kDecodeMean, BUCKET>), parts, small, lds_bytes, s, a);
 }
 
 template <int C1>
