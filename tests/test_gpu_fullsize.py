@@ -495,6 +495,58 @@ def test_full_size_bucket_scope(oracle):
 
 
 @pytest.mark.timeout(900)
+@pytest.mark.parametrize("scope,kind", [(qoda.SCOPE_LAYER, qoda.NORM_L1), (qoda.SCOPE_LAYER, qoda.NORM_LINF),
+                                        (qoda.SCOPE_VECTOR, qoda.NORM_L2)])
+def test_full_size_other_norms_whole_messages(oracle, scope, kind):
+    """The Transformer-XL-shaped workload under L1 / L-infinity normalisation and under one norm per node vector:
+    two rounds (the second against the first round's messages) at uniform levels, every node's whole message byte for
+    byte and every node's step-size term against the oracle's whole-node routine, the mean on every coordinate of
+    round 2."""
+    w = workloads.get("txl")
+    L, K, S = len(w.sizes), w.num_nodes, w.points
+    dev = torch.device("cuda:0")
+    ctx = qoda.Context(w.sizes, list(range(L)), [S] * L, K, w.seed, norm_scope=scope, norm_kind=kind)
+    off, n = workloads.padded_offsets(w.sizes)
+    grad = [torch.zeros(n, dtype=torch.float32, device=dev) for _ in range(K)]
+    mb = ctx.message_bytes()
+    assert mb == oracle.message_bytes(w.sizes, [S] * L, scope)
+    msg = [[torch.zeros(mb, dtype=torch.uint8, device=dev) for _ in range(K)] for _ in range(2)]
+    mean = torch.zeros(n, dtype=torch.float32, device=dev)
+    ptrs = lambda t: [t.data_ptr() + 4 * int(o) for o in off]
+    lev = [uniform_levels(S)] * L
+    prev = [None] * K
+    for t in (1, 2):
+        for k in range(K):
+            workloads.node_torch(w, k, t, dev, out=grad[k])
+        cur = (t - 1) & 1
+        ctx.quantize_all([p for k in range(K) for p in ptrs(grad[k])], t, msg[cur], msg[1 - cur] if t > 1 else None)
+        deltas = ctx.read_buffer(qoda.BUF_DELTA)
+        torch.cuda.synchronize()
+        assert ctx.status() == qoda.OK
+        got = [msg[cur][k].cpu().numpy() for k in range(K)]
+
+        def node_task(k):
+            flat = grad[k].cpu().numpy()
+            layers = [flat[int(o): int(o) + d] for o, d in zip(off, w.sizes)]
+            wm, _, dl, st = oracle.quantize(w.sizes, [S] * L, lev, layers, w.seed, t, k, msg_prev=prev[k], scope=scope,
+                                            norm_kind=kind)
+            assert st == 0, (t, k)
+            assert np.array_equal(got[k], wm), (t, k)
+            assert deltas[k] == dl, (t, k)
+
+        with _pool(8) as pool:
+            for fu in [pool.submit(node_task, k) for k in range(K)]:
+                fu.result()
+        prev = got
+    ctx.dequant_aggregate(msg[cur], ptrs(mean))
+    torch.cuda.synchronize()
+    want = oracle.dequant_aggregate(w.sizes, [S] * L, prev, scope=scope)
+    host = mean.cpu().numpy()
+    for l in range(L):
+        assert np.array_equal(host[int(off[l]): int(off[l]) + w.sizes[l]], want[l]), l
+
+
+@pytest.mark.timeout(900)
 def test_layer_beyond_32_bit_indices(oracle):
     """One tensor of 2^32 + 10317 entries (coordinate indices beyond both int32 and uint32; the second tensor's
     body sits beyond 2^31 bytes inside the message), one node, fit -> quantize -> step: the sum of squares, the
