@@ -1,10 +1,11 @@
 // gfx950 kernels of the QODA hot path (arXiv 2505.14371): per-layer norms, stochastic quantization + code
 // packing, fused decode + K-way mean + optimistic dual averaging update, and the histogram level fit.
 //
-// Execution shape used throughout: one workgroup = 256 threads = 4 wave64 = one tile of 16384 coordinates of
-// one (node, layer).  Wave w owns the 16 consecutive 256-coordinate blocks 16w..16w+15 of the tile; in a block,
-// lane i owns coordinates 4i..4i+3 (one 128-bit load, 1 KB contiguous per wave).  Thread t = 64w+i is reduction
-// slot t of the fixed-order fp64 sums.  The packed message is lane-local: the codes of the 32 coordinates a lane
+// Execution shape of the norm and quantize passes: one workgroup = 256 threads = 4 wave64 = one tile of 16384
+// coordinates of one (node, layer).  Wave w owns the 16 consecutive 256-coordinate blocks 16w..16w+15 of the tile; in a
+// block, lane i owns coordinates 4i..4i+3 (one 128-bit load, 1 KB contiguous per wave).  Thread t = 64w+i is reduction
+// slot t of the fixed-order fp64 sums.  The decode pass keeps the lane <-> coordinate mapping but runs in shorter
+// workgroups (one octet per wave, see k_decode).  The packed message is lane-local: the codes of the 32 coordinates a lane
 // owns in 8 consecutive blocks (an octet) are shifted into C1 = 1 + b 32-bit words per lane, and word r of the
 // 64 lanes is one contiguous 256-byte store.
 //
