@@ -1407,23 +1407,34 @@ __device__ __forceinline__ double fit_cost(const FitRow &ra, const FitRow &rb) {
   return ((ra.g + rb.g) * (rb.p1 - ra.p1) - (rb.p2 - ra.p2)) - (ra.g * rb.g) * (rb.p0 - ra.p0);
 }
 
-constexpr int kFitThreads = 1024;   // 4 threads per grid index b: each scans a quarter of the candidates a
+constexpr int kFitThreads = 1024;
 constexpr int kFitLdsPoints = 128;  // up to this many level points the back-pointers stay in shared memory
+// The cost of a pair (a, b) does not depend on the stage, so every thread computes the costs of its pairs once and
+// keeps them in registers: grid index b (1..255, the only places an interior level can sit) has its b candidates
+// a = 0..b-1 cut into segments of kFitSeg, one thread per segment -- 945 threads, at most kFitSeg costs each.  A stage
+// is then one shared-memory read, one addition and one comparison per pair, and a second step in which the first
+// thread of every b combines its segments in increasing a.
+constexpr int kFitSeg = 40;
+constexpr int kFitPad = 320;        // D rows are padded with +infinity: a segment may reach index 240 + 39
 
 __global__ void __launch_bounds__(kFitThreads) k_fit_dp(Dev a) {
   __shared__ FitRow row[kGridPoints + 1];
-  __shared__ double D[2][kGridPoints];
-  __shared__ double wd[3][kGridPoints];   // W, W*mid, (W*mid)*mid per bin
-  __shared__ double rv[kThreads];
-  __shared__ int ri[kThreads];
+  __shared__ double D[2][kFitPad];
+  __shared__ double pbest[kFitThreads];   // first the per-bin terms of the prefix sums, then the segments' minima
+  __shared__ int pa[kFitThreads];         // ... and where they are taken
   __shared__ float slev[kMaxPoints];
   __shared__ unsigned char sarg[kFitLdsPoints * 256];   // back-pointers of the stages, when S is small enough
+  static_assert(3 * kGridPoints <= kFitThreads, "the per-bin terms share the segments' array");
+  double (*wd)[kGridPoints] = reinterpret_cast<double (*)[kGridPoints]>(pbest);   // W, W*mid, (W*mid)*mid per bin
+  double *rv = pbest;   // the last stage's candidates: after the stage loop
+  int *ri = pa;
   const int mtype = blockIdx.x;
   if (a.type_exp[mtype] == kTypeSkip) return;   // all-zero or non-finite vectors: the type keeps its levels
   const int S = a.type_points[mtype];
   const int t = threadIdx.x;
   const unsigned long long *W = a.pooled + (size_t)mtype * kGridPoints;
   const int last = kGridPoints - 1;
+  const double inf = __longlong_as_double(0x7FF0000000000000ll);
   for (int j = t; j < kGridPoints; j += kFitThreads) {
     const double wj = (double)W[j];
     const double mid = (j == last) ? 1.0 : (double)u2f(((unsigned int)(j + kGridBase) << 20) | (1u << 19));
@@ -1433,6 +1444,7 @@ __global__ void __launch_bounds__(kFitThreads) k_fit_dp(Dev a) {
     wd[2][j] = wm * mid;
     row[j].g = (double)grid_value(j);
   }
+  for (int j = t; j < 2 * kFitPad; j += kFitThreads) D[0][j] = inf;   // both rows: index 0, index `last`, the padding
   __syncthreads();
   // the three running sums, each by one thread of its own wave, bin after bin
   if ((t & 63) == 0 && t < 3 * 64) {
@@ -1450,47 +1462,68 @@ __global__ void __launch_bounds__(kFitThreads) k_fit_dp(Dev a) {
   }
   __syncthreads();
   if (row[kGridPoints].p0 == 0.0) return;   // no mass on the grid at all: the type keeps its levels
-  const double inf = __longlong_as_double(0x7FF0000000000000ll);
   short *arg = a.dp_arg + a.dp_arg_off[mtype];
   const bool lds_arg = S <= kFitLdsPoints;   // candidates a are at most 254: a byte each, 255 for "none"
   if (S > 2) {
     // level 1 at grid index b: cost of the bins below g_b against the levels 0 and g_b
     for (int b = t; b < kGridPoints; b += kFitThreads)
       D[1][b] = (b >= 1 && b <= last - (S - 2)) ? (row[b].g * row[b].p1 - row[b].p2) : inf;
+    // this thread's grid index b, segment and number of segments of b (b = 0: no work): the indices
+    // 40(g-1)+1 .. 40g have g segments each
+    int b = 0, seg = 0, nseg = 0;
+    {
+      int base = 0;
+      for (int g = 1; (g - 1) * kFitSeg + 1 <= last - 1; ++g) {
+        const int r0 = (g - 1) * kFitSeg + 1, r1 = min(g * kFitSeg, last - 1);
+        const int cnt = (r1 - r0 + 1) * g;
+        if (t >= base && t < base + cnt) {
+          const int o = t - base;
+          b = r0 + o / g;
+          seg = o - (o / g) * g;
+          nseg = g;
+        }
+        base += cnt;
+      }
+    }
+    const int a0 = seg * kFitSeg;
+    double cost[kFitSeg];
+    {
+      const FitRow rb = row[b];
+#pragma unroll
+      for (int j = 0; j < kFitSeg; ++j) {
+        const int aa = a0 + j;
+        const FitRow ra = row[min(aa, last)];
+        cost[j] = (aa <= b - 1) ? fit_cost(ra, rb) : inf;   // +infinity never wins a comparison below
+        __builtin_amdgcn_sched_barrier(0);   // one pair at a time: 40 rows in flight would not fit the registers
+      }
+    }
     __syncthreads();
-    // Four threads per grid index b (interior levels only ever sit at b <= 255), each scanning a quarter of the
-    // candidates a.  A wave covers 16 consecutive b and its work grows with b; the waves take the blocks of 16 in
-    // serpentine order so that the four waves sharing a SIMD (every fourth wave) carry equal work in total.
-    const int wv = t >> 6;
-    const int blk = (wv & 4) ? (wv ^ 3) : wv;
-    const int b = blk * 16 + ((t >> 2) & 15), q = t & 3;
     for (int s = 2; s <= S - 2; ++s) {
-      const double *Dp = D[(s - 1) & 1];
+      // D of the previous stage is +infinity wherever level s-1 cannot sit (in particular below index s-1), so the
+      // candidates need no range test: min over a of D[a] + cost(a, b), the smallest a on equal cost
+      const double *Dp = D[(s - 1) & 1] + a0;
       double *Dc = D[s & 1];
       double best = inf;
-      int besta = 0x7FFFFFFF;
-      if (b >= s && b <= last - (S - 1 - s)) {
-        const FitRow rb = row[b];
-#pragma unroll 2
-        for (int aa = s - 1 + q; aa <= b - 1; aa += 4) {
-          const FitRow ra = row[aa];
-          const double c = Dp[aa] + fit_cost(ra, rb);
-          if (c < best) { best = c; besta = aa; }
-        }
-      }
-      // smallest cost over the four strided scans; on equal cost the smallest a, as one scan in increasing a gives
+      int bj = 0;
 #pragma unroll
-      for (int x = 1; x <= 2; x <<= 1) {
-        const double ov = __shfl_xor(best, x, 64);
-        const int oa = __shfl_xor(besta, x, 64);
-        if (ov < best || (ov == best && oa < besta)) { best = ov; besta = oa; }
+      for (int j = 0; j < kFitSeg; ++j) {
+        const double c = Dp[j] + cost[j];
+        if (c < best) { best = c; bj = j; }
       }
-      if (q == 0) {
+      pbest[t] = best;
+      pa[t] = a0 + bj;
+      __syncthreads();
+      if (b != 0 && seg == 0) {
+        int besta = pa[t];
+        for (int q = 1; q < nseg; ++q) {   // later segments hold larger a: they win only with a smaller cost
+          const double ov = pbest[t + q];
+          if (ov < best) { best = ov; besta = pa[t + q]; }
+        }
+        if (!(b >= s && b <= last - (S - 1 - s))) best = inf;   // level s cannot sit here
         Dc[b] = best;
         if (lds_arg) sarg[s * 256 + b] = (unsigned char)(best < inf ? besta : 255);
         else arg[(size_t)s * kGridPoints + b] = (short)(best < inf ? besta : -1);
       }
-      if (t == 0) Dc[last] = inf;
       __syncthreads();
     }
     // last level (1.0) at grid index `last`: one candidate per thread, then the smallest cost (ties: smallest index)
