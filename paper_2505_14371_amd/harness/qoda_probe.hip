@@ -115,13 +115,8 @@ int main(int argc, char **argv) {
   CK(hipEventCreate(&e0));
   CK(hipEventCreate(&e1));
   float ms_total = 0.0f;
-  for (int t = 1; t <= rounds + 1; ++t) {            // round 1 is a warm-up and is not reported
+  auto one_round = [&](int t) -> int {
     const int cur = t & 1;
-    if (t == 2) {
-      double ms[QODA_NUM_KERNELS]; int64_t n[QODA_NUM_KERNELS];
-      QK(qoda_profile_read(ctx, ms, n, nullptr));
-      CK(hipEventRecord(e0, 0));
-    }
     // bucket scope: after the first round the fit uses the statistics gathered by the previous quantize pass
     if (adaptive) {
       if (scope == QODA_SCOPE_BUCKET && t > 1) QK(qoda_fit_levels(ctx, nullptr, (uint32_t)t, nullptr));
@@ -131,6 +126,15 @@ int main(int argc, char **argv) {
                          (t > 1 && q_hat <= 0.0) ? (const void *const *)(msg.data() + (1 - cur) * K) : nullptr, nullptr));
     if (q_hat > 0.0) QK(qoda_step_alt(ctx, (const void *const *)(msg.data() + cur * K), &ast, q_hat, nullptr));
     else QK(qoda_step(ctx, (const void *const *)(msg.data() + cur * K), &st, nullptr));
+    return 0;
+  };
+  for (int t = 1; t <= rounds + 1; ++t) {            // round 1 is a warm-up and is not reported
+    if (t == 2) {
+      double ms[QODA_NUM_KERNELS]; int64_t n[QODA_NUM_KERNELS];
+      QK(qoda_profile_read(ctx, ms, n, nullptr));
+      CK(hipEventRecord(e0, 0));
+    }
+    if (one_round(t)) return 1;
   }
   CK(hipEventRecord(e1, 0));
   CK(hipEventSynchronize(e1));
@@ -143,6 +147,18 @@ int main(int argc, char **argv) {
          4.0 * K * (double)d / (ms_total / rounds * 1e-3) / 1e9);
   for (int i = 0; i < QODA_NUM_KERNELS; ++i)
     if (n[i]) printf("  %-18s launches=%lld avg_ms=%.4f\n", qoda_kernel_name(i), (long long)n[i], ms[i] / n[i]);
+  if (time_classes != 0u) {   // the same rounds once more with no launch bracketed by events
+    float ms_plain = 0.0f;
+    QK(qoda_profile_enable(ctx, 0u));
+    CK(hipEventRecord(e0, 0));
+    for (int t = rounds + 2; t <= 2 * rounds + 1; ++t)
+      if (one_round(t)) return 1;
+    CK(hipEventRecord(e1, 0));
+    CK(hipEventSynchronize(e1));
+    CK(hipEventElapsedTime(&ms_plain, e0, e1));
+    printf("rounds=%d ms_per_round_without_kernel_events=%.4f fp32_gradient_GBps=%.1f\n", rounds, ms_plain / rounds,
+           4.0 * K * (double)d / (ms_plain / rounds * 1e-3) / 1e9);
+  }
   const int status = qoda_status(ctx, nullptr);
   printf("status=%d\n", status);
 
