@@ -940,7 +940,16 @@ __global__ void __launch_bounds__(kThreads) k_delta_finalize(Dev a) {
   const int kr = k - a.row0;   // row in the per-node scratch and pointer tables
   const double *p = a.dpartial + (size_t)kr * a.G;
   double acc = 0.0;
-  for (int g = threadIdx.x; g < a.G; g += kThreads) acc = acc + p[g];
+  // the loads of a slot are independent of its running sum: requested 16 at a time, added in the slot's order
+  int g = threadIdx.x;
+  for (; g + 15 * kThreads < a.G; g += 16 * kThreads) {
+    double v[16];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) v[q] = p[g + q * kThreads];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) acc = acc + v[q];
+  }
+  for (; g < a.G; g += kThreads) acc = acc + p[g];
   const double s = block_tree(acc, red);
   if (threadIdx.x == 0) a.delta[k] = s;
   // layers without coordinates have no tile: their header entries (norm 0, levels) are written here
@@ -999,7 +1008,15 @@ __global__ void k_alt_scalars(Dev a) {
 __global__ void __launch_bounds__(kThreads) k_alt_finalize(Dev a) {
   __shared__ double red[kThreads];
   double acc = 0.0;
-  for (int g = threadIdx.x; g < a.G; g += kThreads) acc = acc + a.dpartial[g];
+  int g = threadIdx.x;
+  for (; g + 15 * kThreads < a.G; g += 16 * kThreads) {   // loads 16 at a time, sums in the slot's order
+    double v[16];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) v[q] = a.dpartial[g + q * kThreads];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) acc = acc + v[q];
+  }
+  for (; g < a.G; g += kThreads) acc = acc + a.dpartial[g];
   const double s = block_tree(acc, red);
   if (threadIdx.x == 0) a.alt_sums[1] = a.alt_sums[1] + s;
 }
