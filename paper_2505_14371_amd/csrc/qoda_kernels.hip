@@ -1524,8 +1524,9 @@ __global__ void __launch_bounds__(kFitThreads) k_fit_dp(Dev a) {
       int bj = 0;
 #pragma unroll
       for (int j = 0; j < kFitSeg; ++j) {
-        const double c = Dp[j] + cost[j];
-        if (c < best) { best = c; bj = j; }
+        const double c = Dp[j] + cost[j];   // never a NaN: costs and D are finite or +infinity
+        bj = (c < best) ? j : bj;
+        best = fmin(best, c);
       }
       pbest[t] = best;
       pa[t] = a0 + bj;
