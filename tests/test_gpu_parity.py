@@ -291,6 +291,34 @@ def test_fit_levels_matches_and_feeds_the_quantizer(oracle):
     del S
 
 
+@pytest.mark.parametrize("scope", [qoda.SCOPE_LAYER, qoda.SCOPE_BUCKET])
+def test_fit_for_every_number_of_levels(oracle, scope):
+    """The level fit from 2 to 256 points per type (few, the widths around the code-size steps, the largest that keeps
+    its back-pointers in shared memory and the first that does not, the maximum): pooled weights and levels bit for
+    bit, two rounds so that the second fit starts from fitted levels."""
+    points = [2, 3, 4, 5, 9, 33, 64, 128, 129, 200, 256]
+    M = len(points)
+    sizes = [3000 + 700 * t for t in range(M)] + [40001, 257]
+    types = list(range(M)) + [M - 1, 3]
+    L, K = len(sizes), 3
+    rng = np.random.default_rng(77)
+    m = gm(sizes, types, points, K, seed=9, norm_scope=scope)
+    levels = [helpers.uniform_levels(s) for s in points]
+    for t in (1, 2):
+        grads = [[(rng.standard_t(3, s) * 10.0 ** rng.uniform(-4, 0)).astype(np.float32) for s in sizes] for _ in range(K)]
+        m.set_grads(grads)
+        m.fit(t)
+        flat = [grads[k][l] for k in range(K) for l in range(L)]
+        levels, _, pooled, st = oracle.fit_levels(sizes, types, points, K, flat, levels, scope=scope)
+        assert st == 0
+        assert np.array_equal(m.ctx.read_buffer(qoda.BUF_POOLED), pooled), t
+        for ty in range(M):
+            got = m.ctx.get_levels(ty)
+            assert np.array_equal(got, levels[ty]), (t, ty, points[ty])
+            assert got[0] == 0.0 and got[-1] == 1.0 and np.all(np.diff(got) > 0), (t, ty)
+    assert m.ctx.status() == qoda.OK
+
+
 @pytest.mark.parametrize("name,rounds", [("dcgan", 3), ("txl", 2), ("gpt1p3b", 2)])
 def test_adaptive_rounds_on_shrunken_workloads(oracle, name, rounds):
     """Configs 3-5 shrunk (same distributions, node counts and level counts, ragged layer sizes): fit every
