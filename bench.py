@@ -86,16 +86,27 @@ def _cpu_baseline(w, model, K, scope=0, kind=2, sample_target=6e7):
 
 def _ceilings(qoda, ctx, a, b, nbytes):
     """Bandwidth this device sustains for the kernels' own access type (nontemporal 128-bit loads and stores over
-    64 KiB tiles) at several read/write mixes, and for a plain copy kernel: GB/s of total traffic."""
-    nb = nbytes // 65536 * 65536
+    64 KiB tiles) at several read/write mixes, and for a plain copy kernel: GB/s of total traffic.  Where a tile's
+    stores fall relative to its loads matters by several per cent, so every mix is measured with the destination
+    shifted by a few distances against the source: the figure is the best of them, the others are kept beside it."""
+    if nbytes < (1 << 28):   # a streaming ceiling needs a buffer well beyond the caches: only the large workloads give one
+        return None
+    shifts = (0, 1024, 4352, 69888)
+    nb = (nbytes - (1 << 20)) // 65536 * 65536
+    src, dst = a.data_ptr(), b.data_ptr()
     out = {}
     for name, stores in (("read_nt_GBps", 0), ("mix_1_store_per_8_loads_nt_GBps", 2), ("mix_1_store_per_2_loads_nt_GBps", 8),
                          ("copy_nt_GBps", 16)):
-        ctx.profile_enable(["k_stream"])
-        for _ in range(5):
-            ctx.stream_calibration(a, b, nb, stores)
-        ms, n = ctx.profile_read()["k_stream"]
-        out[name] = nb * (1.0 + stores / 16.0) / (ms / n * 1e-3) / 1e9
+        rates = []
+        for sh in (shifts if stores else shifts[:1]):
+            ctx.profile_enable(["k_stream"])
+            for _ in range(5):
+                ctx.stream_calibration(src, dst + sh, nb, stores)
+            ms, n = ctx.profile_read()["k_stream"]
+            rates.append(nb * (1.0 + stores / 16.0) / (ms / n * 1e-3) / 1e9)
+        out[name] = max(rates)
+        if stores:
+            out[name.replace("_GBps", "_by_shift_GBps")] = dict(zip((str(x) for x in shifts), rates))
     ctx.profile_enable(["k_copy_f4"])
     for _ in range(5):
         ctx.copy_calibration(a, b, nb)
